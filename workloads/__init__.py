@@ -1,0 +1,55 @@
+"""Neutral description of the benchmark workloads: op lists and seeded inputs.
+
+Imported by the tests and the bench only; neither the oracle nor the HIP library
+depends on it.
+"""
+from __future__ import annotations
+
+from . import graphs, inputs
+
+ITEMSIZE = {"f32": 4, "f16": 2, "bf16": 2}
+# comparison bar |gpu - ref| <= atol + rtol*|ref| for a group by its storage dtype
+TOLERANCE = {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2}
+
+
+def algorithmic_bytes(ops):
+    """Bytes a group must move: every parameter read once, every output written once."""
+    total = 0
+    for op in ops:
+        if op.kind in ("parameter", "output"):
+            n = 1
+            for e in op.shape:
+                n *= e
+            total += n * ITEMSIZE[op.dtype]
+    return total
+
+
+class Config:
+    def __init__(self, index, name, graph_fn, input_fn, full, small, dtype):
+        self.index, self.name = index, name
+        self.graph_fn, self.input_fn = graph_fn, input_fn
+        self.full, self.small, self.dtype = full, small, dtype
+
+    def build(self, size="full", **override):
+        kw = dict(self.full if size == "full" else self.small)
+        kw.update(override)
+        ops = self.graph_fn(**kw)
+        ins = self.input_fn(**kw)
+        return ops, ins
+
+
+CONFIGS = [
+    Config(1, "layernorm_fwd", graphs.layernorm_fwd, inputs.layernorm_fwd,
+           dict(rows=256, cols=768), dict(rows=37, cols=768), "f32"),
+    Config(2, "scaled_masked_softmax", graphs.scaled_masked_softmax,
+           inputs.scaled_masked_softmax,
+           dict(shape=(131072, 128), mask="full"), dict(shape=(1030, 128), mask="full"), "f32"),
+    Config(3, "causal_attention", graphs.causal_attention, inputs.causal_attention,
+           dict(batch=512, seq=64, dim=64), dict(batch=5, seq=64, dim=64), "f16"),
+    Config(4, "bias_gelu_residual_layernorm", graphs.bias_gelu_residual_layernorm,
+           inputs.bias_gelu_residual_layernorm,
+           dict(rows=16384, cols=1024), dict(rows=203, cols=1024), "bf16"),
+    Config(5, "layernorm_bwd", graphs.layernorm_bwd, inputs.layernorm_bwd,
+           dict(rows=32768, cols=1024), dict(rows=517, cols=1024), "f32"),
+]
+BY_NAME = {c.name: c for c in CONFIGS}

@@ -1,0 +1,283 @@
+"""Fusion-group op lists (the paper's "fusion pattern": a sub-DAG of XLA-semantics
+ops with one or more outputs, Section 3.1 and Section 4.1).
+
+This module only *describes* computations: it builds topologically ordered lists
+of `Op` records.  It evaluates nothing and holds none of the method's
+arithmetic.  Both the CPU oracle and the HIP library are handed the same lists
+by the tests and the bench; neither imports this module.
+
+Op semantics (shared vocabulary, defined here once):
+
+  parameter            group input, dense row-major
+  constant             rank-0 scalar with value `attr`; may be used directly as an
+                       operand of a binary op (implicit scalar broadcast)
+  add subtract multiply divide maximum          elementwise binary, equal shapes
+  negate exp log tanh rsqrt sqrt                elementwise unary
+  convert              change of storage dtype (value-preserving up to rounding)
+  broadcast            operand dims map to result dims [axis, axis+rank(operand));
+                       operand dims of extent 1 are expanded
+  reduce_sum reduce_max   reduce over `axis`; that dim is removed from the shape
+  dot                  batched matrix product a[B,M,K] x b[B,K,N];  axis=1 means b is
+                       stored [B,N,K] (contraction over the last dim of both)
+  causal_mask          x[..., i, j] kept where j <= i, else replaced by `attr`
+  output               marks operand 0 as a group output (one element of the
+                       paper's terminal `tuple`)
+"""
+from __future__ import annotations
+
+from collections import namedtuple
+
+Op = namedtuple("Op", "kind dtype shape operands axis attr name")
+
+KINDS = (
+    "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum",
+    "negate", "exp", "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast",
+    "reduce_sum", "reduce_max", "dot", "causal_mask", "output",
+)
+DTYPES = ("f32", "f16", "bf16")
+
+
+class Graph:
+    """Builder for one fusion group.  Methods return the index of the new op."""
+
+    def __init__(self):
+        self.ops = []
+
+    def _new(self, kind, dtype, shape, operands=(), axis=-1, attr=0.0, name=""):
+        assert kind in KINDS and dtype in DTYPES
+        self.ops.append(Op(kind, dtype, tuple(int(s) for s in shape),
+                           tuple(int(o) for o in operands), int(axis), float(attr), name))
+        return len(self.ops) - 1
+
+    def dtype(self, i):
+        return self.ops[i].dtype
+
+    def shape(self, i):
+        return self.ops[i].shape
+
+    # leaves
+    def parameter(self, name, dtype, shape):
+        return self._new("parameter", dtype, shape, name=name)
+
+    def constant(self, value, dtype="f32"):
+        return self._new("constant", dtype, (), attr=value)
+
+    # elementwise
+    def _binary(self, kind, a, b):
+        sa, sb = self.shape(a), self.shape(b)
+        shape = sa if sa != () else sb
+        assert sa == () or sb == () or sa == sb, (kind, sa, sb)
+        dt = self.dtype(a) if sa != () else self.dtype(b)
+        return self._new(kind, dt, shape, (a, b))
+
+    def add(self, a, b): return self._binary("add", a, b)
+    def subtract(self, a, b): return self._binary("subtract", a, b)
+    def multiply(self, a, b): return self._binary("multiply", a, b)
+    def divide(self, a, b): return self._binary("divide", a, b)
+    def maximum(self, a, b): return self._binary("maximum", a, b)
+
+    def _unary(self, kind, a):
+        return self._new(kind, self.dtype(a), self.shape(a), (a,))
+
+    def negate(self, a): return self._unary("negate", a)
+    def exp(self, a): return self._unary("exp", a)
+    def log(self, a): return self._unary("log", a)
+    def tanh(self, a): return self._unary("tanh", a)
+    def rsqrt(self, a): return self._unary("rsqrt", a)
+    def sqrt(self, a): return self._unary("sqrt", a)
+
+    def convert(self, a, dtype):
+        return self._new("convert", dtype, self.shape(a), (a,))
+
+    # shape ops
+    def broadcast(self, a, shape, axis):
+        sa = self.shape(a)
+        assert axis + len(sa) <= len(shape)
+        for d, e in enumerate(sa):
+            assert e == 1 or e == shape[axis + d], (sa, shape, axis)
+        return self._new("broadcast", self.dtype(a), shape, (a,), axis=axis)
+
+    def _reduce(self, kind, a, axis):
+        sa = self.shape(a)
+        axis = axis % len(sa)
+        return self._new(kind, self.dtype(a), sa[:axis] + sa[axis + 1:], (a,), axis=axis)
+
+    def reduce_sum(self, a, axis): return self._reduce("reduce_sum", a, axis)
+    def reduce_max(self, a, axis): return self._reduce("reduce_max", a, axis)
+
+    def dot(self, a, b, transpose_b=False, dtype="f32"):
+        sa, sb = self.shape(a), self.shape(b)
+        assert len(sa) == 3 and len(sb) == 3 and sa[0] == sb[0]
+        if transpose_b:
+            assert sa[2] == sb[2]
+            shape = (sa[0], sa[1], sb[1])
+        else:
+            assert sa[2] == sb[1]
+            shape = (sa[0], sa[1], sb[2])
+        return self._new("dot", dtype, shape, (a, b), axis=1 if transpose_b else 0)
+
+    def causal_mask(self, a, fill):
+        return self._new("causal_mask", self.dtype(a), self.shape(a), (a,), attr=fill)
+
+    def output(self, a, name=""):
+        return self._new("output", self.dtype(a), self.shape(a), (a,), name=name)
+
+    # helper spellings used by several groups
+    def row_broadcast(self, a, like):
+        """[R...] per-row values -> shape of `like` (expanded along the last dim)."""
+        return self.broadcast(a, self.shape(like), 0)
+
+    def col_broadcast(self, a, like):
+        """[C] per-column values -> shape of `like` (expanded along leading dims)."""
+        return self.broadcast(a, self.shape(like), len(self.shape(like)) - 1)
+
+
+# ----------------------------------------------------------------------------------
+# The five groups of the benchmark.  Each returns a list[Op].
+# ----------------------------------------------------------------------------------
+
+def _layernorm_tail(g, r, gamma, beta, eps):
+    """r -> layernorm(r) * gamma + beta over the last dim (biased variance, eps
+    inside the root): row mean, subtract, square, row mean, rsqrt, scale, shift."""
+    n = g.shape(r)[-1]
+    mean = g.divide(g.reduce_sum(r, -1), g.constant(n))
+    c = g.subtract(r, g.row_broadcast(mean, r))
+    sq = g.multiply(c, c)
+    var = g.divide(g.reduce_sum(sq, -1), g.constant(n))
+    rstd = g.rsqrt(g.add(var, g.constant(eps)))
+    xhat = g.multiply(c, g.row_broadcast(rstd, r))
+    scaled = g.multiply(xhat, g.col_broadcast(gamma, r))
+    return g.add(scaled, g.col_broadcast(beta, r))
+
+
+def layernorm_fwd(rows, cols, dtype="f32", eps=1e-5):
+    """Config 1: y = (x - mean) * rsqrt(var + eps) * gamma + beta."""
+    g = Graph()
+    x = g.parameter("x", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    beta = g.parameter("beta", dtype, (cols,))
+    if dtype != "f32":
+        x, gamma, beta = (g.convert(t, "f32") for t in (x, gamma, beta))
+    y = _layernorm_tail(g, x, gamma, beta, eps)
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
+
+
+def scaled_masked_softmax(shape, scale=0.125, mask="full", dtype="f32"):
+    """Config 2: softmax over the last dim of (scores * scale + mask).
+
+    mask="full": the mask has the shape of the scores.
+    mask="key_padding": scores are [B,H,S,S] and the mask is [B,1,1,S].
+    mask="none": no mask operand.
+    """
+    g = Graph()
+    s = g.parameter("scores", dtype, shape)
+    m = None
+    if mask == "full":
+        m = g.parameter("mask", dtype, shape)
+    elif mask == "key_padding":
+        assert len(shape) == 4
+        m = g.parameter("mask", dtype, (shape[0], 1, 1, shape[3]))
+    else:
+        assert mask == "none"
+    if dtype != "f32":
+        s = g.convert(s, "f32")
+        if m is not None:
+            m = g.convert(m, "f32")
+    z = g.multiply(s, g.constant(scale))
+    if mask == "full":
+        z = g.add(z, m)
+    elif mask == "key_padding":
+        z = g.add(z, g.broadcast(m, shape, 0))
+    zmax = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
+    denom = g.reduce_sum(e, -1)
+    p = g.divide(e, g.row_broadcast(denom, e))
+    if dtype != "f32":
+        p = g.convert(p, dtype)
+    g.output(p, "p")
+    return g.ops
+
+
+def causal_attention(batch, seq, dim, dtype="f16", scale=None):
+    """Config 3: O = softmax_rows(causal(Q K^T * scale)) V with fp32 accumulation."""
+    if scale is None:
+        scale = dim ** -0.5
+    g = Graph()
+    q = g.parameter("q", dtype, (batch, seq, dim))
+    k = g.parameter("k", dtype, (batch, seq, dim))
+    v = g.parameter("v", dtype, (batch, seq, dim))
+    s = g.dot(q, k, transpose_b=True, dtype="f32")
+    z = g.multiply(s, g.constant(scale))
+    z = g.causal_mask(z, float("-inf"))
+    zmax = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
+    denom = g.reduce_sum(e, -1)
+    p = g.divide(e, g.row_broadcast(denom, e))
+    p = g.convert(p, dtype)
+    o = g.dot(p, v, transpose_b=False, dtype="f32")
+    g.output(g.convert(o, dtype), "o")
+    return g.ops
+
+
+GELU_K0 = 0.7978845608028654   # sqrt(2/pi)
+GELU_K1 = 0.044715
+
+
+def bias_gelu_residual_layernorm(rows, cols, dtype="bf16", eps=1e-5):
+    """Config 4: y = LayerNorm(gelu_tanh(x + bias) + residual) * gamma + beta,
+    storage in `dtype`, all arithmetic in fp32."""
+    g = Graph()
+    x = g.parameter("x", dtype, (rows, cols))
+    bias = g.parameter("bias", dtype, (cols,))
+    res = g.parameter("residual", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    beta = g.parameter("beta", dtype, (cols,))
+    if dtype != "f32":
+        x, bias, res, gamma, beta = (g.convert(t, "f32") for t in (x, bias, res, gamma, beta))
+    h = g.add(x, g.col_broadcast(bias, x))
+    h3 = g.multiply(g.multiply(h, h), h)
+    inner = g.multiply(g.add(h, g.multiply(h3, g.constant(GELU_K1))), g.constant(GELU_K0))
+    t = g.tanh(inner)
+    gelu = g.multiply(g.multiply(h, g.constant(0.5)), g.add(t, g.constant(1.0)))
+    r = g.add(gelu, res)
+    y = _layernorm_tail(g, r, gamma, beta, eps)
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
+
+
+def layernorm_bwd(rows, cols, dtype="f32"):
+    """Config 5: (dx, dgamma, dbeta) of LayerNorm from dy, x, gamma and the saved
+    per-row mean and rstd.  Row reductions for dx, column reductions for the
+    parameter gradients, 15 arithmetic ops."""
+    assert dtype == "f32"
+    g = Graph()
+    dy = g.parameter("dy", dtype, (rows, cols))
+    x = g.parameter("x", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    mean = g.parameter("mean", dtype, (rows,))
+    rstd = g.parameter("rstd", dtype, (rows,))
+    n = g.constant(cols)
+    rstd_b = g.row_broadcast(rstd, x)
+    xhat = g.multiply(g.subtract(x, g.row_broadcast(mean, x)), rstd_b)      # 2 ops
+    gg = g.multiply(dy, g.col_broadcast(gamma, dy))                          # g = dy*gamma
+    dbeta = g.reduce_sum(dy, 0)
+    t = g.multiply(dy, xhat)
+    dgamma = g.reduce_sum(t, 0)
+    s1 = g.reduce_sum(gg, 1)
+    gx = g.multiply(gg, xhat)
+    s2 = g.reduce_sum(gx, 1)
+    c1 = g.divide(s1, n)
+    c2 = g.divide(s2, n)
+    u = g.multiply(xhat, g.row_broadcast(c2, x))
+    v = g.subtract(gg, g.row_broadcast(c1, x))
+    w = g.subtract(v, u)
+    dx = g.multiply(w, rstd_b)
+    g.output(dx, "dx")
+    g.output(dgamma, "dgamma")
+    g.output(dbeta, "dbeta")
+    return g.ops

@@ -1,0 +1,88 @@
+"""Seeded synthetic inputs for the five benchmark groups.
+
+Every tensor is drawn from numpy's PCG64 with seed `BASE_SEED + config index`,
+in fp64, in parameter order, and then rounded once to its storage dtype.  What is
+returned is the rounded value held in a float64 array (so the oracle reads it
+exactly) together with the storage dtype name (so the GPU side can allocate the
+tensor in that dtype without a second rounding).
+
+Distributions follow the benchmark configs; the second argument of N(.,.) is
+read as a standard deviation.  Nothing here evaluates any op of a fusion group;
+the only statistics computed are the saved per-row mean and reciprocal standard
+deviation that a LayerNorm forward pass would hand to its backward pass, taken
+with numpy's own `mean` / `var`.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+BASE_SEED = 1911_11576
+
+_TORCH = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def round_to(a, dtype):
+    """Round an fp64 array to `dtype` storage (nearest even) and widen back."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if dtype == "f32":
+        return a.astype(np.float32).astype(np.float64)
+    if dtype == "f16":
+        return a.astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        t = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16)
+        return t.to(torch.float64).numpy()
+    raise ValueError(dtype)
+
+
+def to_torch(a, dtype, device="cpu"):
+    """Exact conversion of an already-rounded fp64 array to a storage tensor."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(_TORCH[dtype]).to(device)
+
+
+def _rng(config):
+    return np.random.Generator(np.random.PCG64(BASE_SEED + config))
+
+
+def layernorm_fwd(rows=256, cols=768, dtype="f32", seed_offset=1):
+    r = _rng(seed_offset)
+    x = r.normal(0.0, 1.0, (rows, cols))
+    gamma = r.uniform(0.5, 1.5, (cols,))
+    beta = r.normal(0.0, 0.1, (cols,))
+    return [round_to(t, dtype) for t in (x, gamma, beta)]
+
+
+def scaled_masked_softmax(shape=(131072, 128), mask="full", dtype="f32",
+                          p_pad=0.1, mask_value=-1e4, seed_offset=2):
+    r = _rng(seed_offset)
+    s = round_to(r.normal(0.0, 2.0, shape), dtype)
+    if mask == "none":
+        return [s]
+    mshape = shape if mask == "full" else (shape[0], 1, 1, shape[3])
+    m = np.where(r.random(mshape) < p_pad, mask_value, 0.0)
+    return [s, round_to(m, dtype)]
+
+
+def causal_attention(batch=512, seq=64, dim=64, dtype="f16", seed_offset=3):
+    r = _rng(seed_offset)
+    return [round_to(r.normal(0.0, 1.0, (batch, seq, dim)), dtype) for _ in range(3)]
+
+
+def bias_gelu_residual_layernorm(rows=16384, cols=1024, dtype="bf16", seed_offset=4):
+    r = _rng(seed_offset)
+    x = r.normal(0.0, 1.0, (rows, cols))
+    bias = r.normal(0.0, 0.02, (cols,))
+    res = r.normal(0.0, 1.0, (rows, cols))
+    gamma = 1.0 + r.normal(0.0, 0.02, (cols,))
+    beta = r.normal(0.0, 0.02, (cols,))
+    return [round_to(t, dtype) for t in (x, bias, res, gamma, beta)]
+
+
+def layernorm_bwd(rows=32768, cols=1024, dtype="f32", eps=1e-5, seed_offset=5):
+    r = _rng(seed_offset)
+    dy = round_to(r.normal(0.0, 1.0, (rows, cols)), dtype)
+    x = round_to(r.normal(0.0, 1.0, (rows, cols)), dtype)
+    gamma = round_to(1.0 + r.normal(0.0, 0.02, (cols,)), dtype)
+    mean = round_to(np.mean(x, axis=1), dtype)
+    rstd = round_to(1.0 / np.sqrt(np.var(x, axis=1) + eps), dtype)
+    return [dy, x, gamma, mean, rstd]
