@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the stitched fusion-group kernels on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME] [--no-groups] [--no-cpu]
+
+Prints ONE JSON line.  The headline workload is the scaled-masked-softmax group (fp32
+scores [131072,128] with a full additive mask): one step = one launch of the stitched
+plan over one batch of synthetic input already resident in HBM.  `value` is algorithmic
+bytes (every group input read once, every output written once) per second of wall time
+over the timed steps.  Input buffers rotate over enough distinct sets that the bytes
+touched between two uses of a set exceed the 256 MB last-level cache.
+
+`roofline` is the same kernel against the 8 TB/s HBM peak, from HIP events recorded on
+the launch stream around the timed launches.  `groups` lists all five benchmark groups
+(stitched, per-op baseline, speedup, plain-copy ceiling); `cpu_baseline` is the CPU
+oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ROTATE_BYTES = 640 * 2**20     # bytes touched between reuses of one buffer set
+
+TORCH_DT = None
+
+
+def _torch_dt():
+    global TORCH_DT
+    import torch
+    if TORCH_DT is None:
+        TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    return TORCH_DT
+
+
+def make_sets(ops, ins, algo_bytes, max_sets=8):
+    """Device copies of the inputs and outputs, rotated so consecutive launches touch
+    different memory.  Set 0 holds the seeded inputs; the others hold the same tensors
+    with their leading dim rolled (same distribution, different addresses)."""
+    import torch
+    from workloads import inputs as wl_inputs
+    dts = [op.dtype for op in ops if op.kind == "parameter"]
+    outs = [(op.shape, op.dtype) for op in ops if op.kind == "output"]
+    n_sets = max(1, min(max_sets, -(-ROTATE_BYTES // max(1, algo_bytes))))
+    base = [wl_inputs.to_torch(a, dt, "cuda:0") for a, dt in zip(ins, dts)]
+    sets = []
+    for j in range(n_sets):
+        lead = base[0].shape[0]
+        tin = base if j == 0 else [torch.roll(t, 997 * j, 0).contiguous() if t.shape[0] == lead else t.clone()
+                                   for t in base]
+        tout = [torch.empty(shape, dtype=_torch_dt()[dt], device="cuda:0") for shape, dt in outs]
+        sets.append((tin, tout))
+    return sets
+
+
+def time_plan(plan, sets, steps, warmup):
+    """-> (wall ms per step, event ms per step)."""
+    import torch
+    n = len(sets)
+    for i in range(warmup):
+        plan.launch(*sets[i % n])
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        plan.launch(*sets[i % n])
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def time_copy(nbytes, steps, warmup):
+    """Plain copy kernel moving `nbytes` in total (half read, half written)."""
+    import torch
+    from paper_1911_11576_amd import fs_stream_copy
+    half = max(16, (nbytes // 2) // 16 * 16)
+    n = max(1, min(8, -(-ROTATE_BYTES // (2 * half))))
+    src = [torch.empty(half, dtype=torch.uint8, device="cuda:0").random_(0, 255) for _ in range(n)]
+    dst = [torch.empty(half, dtype=torch.uint8, device="cuda:0") for _ in range(n)]
+    for i in range(warmup):
+        fs_stream_copy(dst[i % n], src[i % n], half)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fs_stream_copy(dst[i % n], src[i % n], half)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps, 2 * half
+
+
+def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
+    import torch
+    from paper_1911_11576_amd import Plan
+    from workloads import algorithmic_bytes
+    ops, ins = cfg.build("full", **(build_kw or {}))
+    algo = algorithmic_bytes(ops)
+    sets = make_sets(ops, ins, algo)
+    res = {"algorithmic_bytes": algo, "buffer_sets": len(sets)}
+    with Plan(ops) as plan:
+        info = plan.info()
+        wall_ms, ev_ms = time_plan(plan, sets, steps, warmup)
+    res.update(schedule=info["schedule"], template=None, stitched_us=ev_ms * 1e3, stitched_wall_us=wall_ms * 1e3,
+               stitched_gbs=algo / (ev_ms * 1e-3) / 1e9, stitched_frac_of_peak=algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               lds_bytes=info["lds_bytes"], workspace_bytes=info["workspace_bytes"])
+    if with_per_op:
+        psteps = max(5, steps // 10)
+        with Plan(ops, "per_op") as plan:
+            pinfo = plan.info()
+            pwall, pev = time_plan(plan, sets, psteps, max(2, warmup // 10))
+        res.update(per_op_us=pev * 1e3, per_op_kernels=pinfo["n_kernels"], per_op_moved_bytes=pinfo["moved_bytes"],
+                   speedup_vs_per_op=pev / ev_ms)
+    cms, cbytes = time_copy(algo, steps, warmup)
+    res.update(copy_us=cms * 1e3, copy_gbs=cbytes / (cms * 1e-3) / 1e9,
+               stitched_frac_of_copy=(algo / ev_ms) / (cbytes / cms))
+    del sets
+    torch.cuda.empty_cache()
+    return res, ev_ms, wall_ms
+
+
+def cpu_baseline(cfg):
+    """The oracle as it stands on the host cores, on a bounded row sample of the headline
+    workload (numpy runs its elementwise loops on one thread)."""
+    from oracle import interp
+    from workloads import algorithmic_bytes, graphs, inputs
+    rows = 32768           # a quarter of the 131072 rows: a few seconds of CPU work
+    ops = graphs.scaled_masked_softmax((rows, 128), 0.125, "full")
+    ins = inputs.scaled_masked_softmax((rows, 128), "full")
+    reps, t_total = 0, 0.0
+    while t_total < 10.0 and reps < 50:
+        t0 = time.perf_counter()
+        interp.run(ops, ins)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    sec = t_total / reps
+    return {"value": algorithmic_bytes(ops) / sec / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rows} of 131072 rows of the same workload, {reps} repetitions, mean",
+            "ms_per_sample": sec * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--only", default=None, help="time just this group as the headline (a config name)")
+    ap.add_argument("--no-groups", action="store_true", help="skip the per-group table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (one stitched kernel per fusion group; "
+              "rows / batch elements would shard across GPUs without communication, see DESIGN.md). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from workloads import BY_NAME, CONFIGS
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    head = BY_NAME[args.only or "scaled_masked_softmax"]
+    res, ev_ms, wall_ms = bench_group(head, args.steps, args.warmup, with_per_op=True)
+    algo = res["algorithmic_bytes"]
+    out = {
+        "metric": "achieved HBM GB/s of the stitched fusion group (algorithmic bytes / time); fraction of 8 TB/s in roofline.frac",
+        "value": algo / (wall_ms * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head.dtype, "data": "synthetic",
+        "config": {"workload": f"{head.name} {head.full}", "algorithmic_bytes": algo,
+                   "buffer_sets": res["buffer_sets"], "speedup_vs_per_op": res.get("speedup_vs_per_op"),
+                   "per_op_kernels": res.get("per_op_kernels")},
+        "roofline": {"bound": "hbm", "achieved": algo / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_us": ev_ms * 1e3, "frac_of_copy_kernel": res["stitched_frac_of_copy"]},
+    }
+    if not args.no_groups:
+        groups = {head.name: res}
+        for cfg in CONFIGS:
+            if cfg.name == head.name:
+                continue
+            steps = args.steps if cfg.index != 5 else max(20, args.steps // 4)
+            groups[cfg.name] = bench_group(cfg, steps, max(5, args.warmup // 2))[0]
+        kp = dict(shape=(64, 16, 128, 128), mask="key_padding")
+        groups["scaled_masked_softmax_key_padding"] = bench_group(BY_NAME["scaled_masked_softmax"], args.steps,
+                                                                  args.warmup, build_kw=kp)[0]
+        out["groups"] = groups
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(head)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

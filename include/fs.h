@@ -1,0 +1,164 @@
+/*
+ * fs.h -- C ABI of the stitched-kernel library for MI355X (gfx950).
+ *
+ * One fs_plan runs ONE fusion group -- a small DAG of memory-intensive tensor ops
+ * with one or more outputs (the paper's "fusion pattern", Section 4.1; its ops and
+ * its terminal tuple, Section 3.1) -- as a single stitched GPU kernel whose
+ * intermediates stay in registers or LDS instead of going through HBM
+ * (Section 5.1: thread, warp and block composition, kernel packing).
+ *
+ * All pointers named "device" are HIP device pointers; everything else is host
+ * memory.  No function throws, aborts or synchronises the device; every failure
+ * is a status code plus a message readable through fs_last_error().
+ */
+#ifndef FS_H_
+#define FS_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_MAX_RANK 4
+
+typedef struct fs_plan fs_plan; /* opaque, owned by the library */
+
+typedef enum { FS_F32 = 0, FS_F16 = 1, FS_BF16 = 2 } fs_dtype;
+
+typedef enum {
+  FS_OK = 0,
+  FS_ERR_INVALID = 1,     /* malformed op list or bad argument */
+  FS_ERR_UNSUPPORTED = 2, /* well-formed group that no stitched schedule covers: the
+                             paper's "negative score", Section 4.3 -- the caller keeps
+                             the group unfused (FS_MODE_PER_OP always works) */
+  FS_ERR_LDS = 3,         /* shared-memory volume constraint violated (Section 5.3,
+                             SharedPlanning) */
+  FS_ERR_HIP = 4,         /* a HIP runtime call failed */
+  FS_ERR_NOMEM = 5
+} fs_status;
+
+/* Op vocabulary: XLA-style tensor ops, the semantics the paper adopts (Section 3.1).
+ * Tensors are dense, row-major, rank <= FS_MAX_RANK.
+ *
+ *  FS_PARAMETER   group input; the i-th parameter of the list is inputs[i] of fs_launch
+ *  FS_CONSTANT    rank-0 scalar of value `attr`; allowed directly as an operand of a
+ *                 binary op (implicit scalar broadcast)
+ *  FS_ADD .. FS_MAXIMUM   elementwise binary; operands have the result's shape and dtype
+ *  FS_NEGATE .. FS_SQRT   elementwise unary
+ *  FS_CONVERT     changes the storage dtype
+ *  FS_BROADCAST   operand dim d maps to result dim axis+d; operand dims of extent 1
+ *                 are expanded; every other result dim is new
+ *  FS_REDUCE_SUM / FS_REDUCE_MAX   reduce over `axis`, which is removed from the shape
+ *  FS_DOT         batched matrix product a[B,M,K] . b[B,K,N]; axis==1: b is stored
+ *                 [B,N,K] and the contraction runs over the last dim of both
+ *  FS_CAUSAL_MASK x[..., i, j] is kept where j <= i and replaced by `attr` elsewhere
+ *  FS_OUTPUT      marks operand 0 as a group output; the i-th output op is outputs[i]
+ */
+typedef enum {
+  FS_PARAMETER = 0, FS_CONSTANT = 1,
+  FS_ADD = 2, FS_SUBTRACT = 3, FS_MULTIPLY = 4, FS_DIVIDE = 5, FS_MAXIMUM = 6,
+  FS_NEGATE = 7, FS_EXP = 8, FS_LOG = 9, FS_TANH = 10, FS_RSQRT = 11, FS_SQRT = 12,
+  FS_CONVERT = 13, FS_BROADCAST = 14,
+  FS_REDUCE_SUM = 15, FS_REDUCE_MAX = 16,
+  FS_DOT = 17, FS_CAUSAL_MASK = 18, FS_OUTPUT = 19,
+  FS_NUM_OPKINDS = 20
+} fs_opkind;
+
+/* One op.  Plain data, caller-owned, copied by fs_plan_create.  `operand` holds
+ * indices of EARLIER ops in the list (topological order), -1 where unused. */
+typedef struct {
+  int32_t kind;                 /* fs_opkind */
+  int32_t dtype;                /* fs_dtype of the result */
+  int32_t rank;                 /* 0..FS_MAX_RANK */
+  int32_t axis;                 /* broadcast / reduce / dot attribute, else ignored */
+  int64_t shape[FS_MAX_RANK];   /* result extents, first `rank` entries used */
+  int32_t operand[3];
+  int32_t reserved;             /* must be 0 */
+  double attr;                  /* constant value / mask fill value */
+} fs_op_desc;
+
+typedef enum {
+  FS_MODE_STITCHED = 0, /* the whole group as one stitched kernel */
+  FS_MODE_PER_OP = 1    /* baseline: one kernel per op, intermediates in a plan-owned HBM
+                           workspace (the sum of K(Op_j) side of the execution-based
+                           score, Section 4.3) */
+} fs_mode;
+
+/* Launch parameters a template would carry (cta_size, cta_num and the per-warp tile,
+ * Section 5.2).  0 = let the plan choose. */
+typedef struct {
+  int32_t mode;          /* fs_mode */
+  int32_t wg_size;       /* threads per workgroup: 64..1024, multiple of 64 */
+  int32_t rows_per_wave; /* independent row groups a wavefront keeps in flight: 1..8 */
+  int32_t grid;          /* number of workgroups */
+} fs_plan_options;
+
+/* Schedule chosen for a stitched plan (fs_plan_info). */
+typedef enum {
+  FS_SCHED_PER_OP = 0,
+  FS_SCHED_ROW = 1,      /* elementwise -> row reduce -> broadcast, wavefront reductions */
+  FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials */
+  FS_SCHED_BDOT_SOFTMAX = 3 /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
+} fs_schedule;
+
+/* Build a plan from a fusion group.
+ *   ops, n_ops  host array of ops in topological order (borrowed for the call only)
+ *   opt         host, may be NULL (stitched mode, automatic launch parameters)
+ *   out         host, receives the plan on FS_OK, NULL otherwise
+ * Pure host work: validates shapes and dtypes, recognises the group as one of the
+ * stitched schedules (Algorithm 3 reduced to a recogniser over hand-written kernels),
+ * checks the LDS budget and fixes the launch geometry.  Touches no GPU, so it also
+ * works on a machine without one.
+ * Errors: FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_NOMEM. */
+fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
+                         const fs_plan_options* opt, fs_plan** out);
+
+/* Enqueue the group on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without waiting.
+ *   inputs[n_in]    host array of DEVICE pointers, one per FS_PARAMETER in list order
+ *   outputs[n_out]  host array of DEVICE pointers, one per FS_OUTPUT in list order
+ * Tensors are dense row-major in their op's dtype, 16-byte aligned, and borrowed until
+ * the work enqueued by this call has finished.  Inputs are never written; outputs must
+ * not overlap inputs or each other.  A plan that owns a workspace (fs_plan_info) must
+ * not have two launches in flight at once; the workspace is allocated on the first
+ * launch on the then-current device and the plan stays bound to that device.
+ * Errors: FS_ERR_INVALID (NULL or misaligned pointer, wrong counts), FS_ERR_HIP,
+ * FS_ERR_NOMEM.  Extents of 0 are legal: nothing is launched. */
+fs_status fs_launch(fs_plan* plan, const void* const* inputs, int32_t n_in,
+                    void* const* outputs, int32_t n_out, void* hip_stream);
+
+/* Release the plan and its workspace.  NULL is a no-op.  The caller makes sure no
+ * launch of the plan is still running. */
+fs_status fs_destroy(fs_plan* plan);
+
+/* Message of the last failing call on this thread.  Library-owned, valid until the
+ * next failing call on the same thread.  Never NULL. */
+const char* fs_last_error(void);
+
+/* Introspection (host only).  Any out-pointer may be NULL.
+ *   schedule           fs_schedule
+ *   n_kernels          kernel launches per fs_launch (the paper's N for the per-op mode)
+ *   lds_bytes          LDS per workgroup of the stitched kernel
+ *   workspace_bytes    plan-owned HBM scratch
+ *   algorithmic_bytes  bytes of all parameters read once plus all outputs written once
+ *   moved_bytes        bytes the plan's kernels read and write in HBM by construction
+ *                      (per-op mode: every intermediate written and re-read) */
+fs_status fs_plan_info(const fs_plan* plan, int32_t* schedule, int32_t* n_kernels,
+                       int64_t* lds_bytes, int64_t* workspace_bytes,
+                       int64_t* algorithmic_bytes, int64_t* moved_bytes);
+
+/* The plan's schedule written in the paper's template notation (Section 5.2), e.g.
+ * "reduce_1[GRID-WARP_2,WARP]; ... cta_num=..., cta_size=...".  Host string owned by
+ * the plan, valid until fs_destroy.  For logs and tests; nothing parses it. */
+const char* fs_plan_describe(const fs_plan* plan);
+
+/* Measurement aid: plain streaming copy of `bytes` (multiple of 16) from src to dst,
+ * both DEVICE pointers, 16-byte aligned, on `hip_stream`.  Gives the achievable HBM
+ * ceiling beside the 8 TB/s peak and the calibration factor for byte counters. */
+fs_status fs_stream_copy(void* dst, const void* src, int64_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FS_H_ */

@@ -1,0 +1,187 @@
+"""ctypes binding of include/fs.h: same entry points, argument marshalling only.
+
+Every step of the path runs in the HIP library.  PyTorch appears here only as the
+owner of device memory and streams (`tensor.data_ptr()`, the current stream's
+handle).  If the built library is missing, loading fails loudly: there is no CPU
+or eager fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+FS_MAX_RANK = 4
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfusionstitch.so")
+
+FS_OK, FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_HIP, FS_ERR_NOMEM = range(6)
+STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID", "FS_ERR_UNSUPPORTED", "FS_ERR_LDS", "FS_ERR_HIP", "FS_ERR_NOMEM"]
+FS_MODE_STITCHED, FS_MODE_PER_OP = 0, 1
+SCHEDULE_NAMES = ["per_op", "row", "row_col", "bdot_softmax"]
+
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+OPKINDS = {name: i for i, name in enumerate((
+    "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum", "negate",
+    "exp", "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast", "reduce_sum", "reduce_max",
+    "dot", "causal_mask", "output"))}
+
+
+class fs_op_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("rank", C.c_int32), ("axis", C.c_int32),
+                ("shape", C.c_int64 * FS_MAX_RANK), ("operand", C.c_int32 * 3),
+                ("reserved", C.c_int32), ("attr", C.c_double)]
+
+
+class fs_plan_options(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("wg_size", C.c_int32), ("rows_per_wave", C.c_int32),
+                ("grid", C.c_int32)]
+
+
+class FsError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (loaded on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is not built: run `python -m paper_1911_11576_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        L.fs_plan_create.argtypes = [C.POINTER(fs_op_desc), i32, C.POINTER(fs_plan_options), C.POINTER(vp)]
+        L.fs_plan_create.restype = i32
+        L.fs_launch.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), i32, vp]
+        L.fs_launch.restype = i32
+        L.fs_destroy.argtypes = [vp]
+        L.fs_destroy.restype = i32
+        L.fs_last_error.argtypes = []
+        L.fs_last_error.restype = C.c_char_p
+        L.fs_plan_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64),
+                                   C.POINTER(i64), C.POINTER(i64)]
+        L.fs_plan_info.restype = i32
+        L.fs_plan_describe.argtypes = [vp]
+        L.fs_plan_describe.restype = C.c_char_p
+        L.fs_stream_copy.argtypes = [vp, vp, i64, vp]
+        L.fs_stream_copy.restype = i32
+        _lib = L
+    return _lib
+
+
+def fs_last_error():
+    return lib().fs_last_error().decode()
+
+
+def _check(status):
+    if status != FS_OK:
+        raise FsError(status, fs_last_error())
+
+
+def marshal_ops(ops):
+    """Sequence of records with fields kind, dtype, shape, operands, axis, attr ->
+    a C array of fs_op_desc."""
+    arr = (fs_op_desc * len(ops))()
+    for d, op in zip(arr, ops):
+        d.kind = OPKINDS[op.kind]
+        d.dtype = DTYPES[op.dtype]
+        d.rank = len(op.shape)
+        d.axis = op.axis if op.axis >= 0 else 0
+        for k in range(FS_MAX_RANK):
+            d.shape[k] = op.shape[k] if k < len(op.shape) else 0
+        for k in range(3):
+            d.operand[k] = op.operands[k] if k < len(op.operands) else -1
+        d.reserved = 0
+        d.attr = op.attr
+    return arr
+
+
+def fs_plan_create(ops, mode=FS_MODE_STITCHED, wg_size=0, rows_per_wave=0, grid=0):
+    """-> opaque plan handle (int).  `ops` may be a marshalled array or op records."""
+    arr = ops if isinstance(ops, C.Array) else marshal_ops(ops)
+    opt = fs_plan_options(mode, wg_size, rows_per_wave, grid)
+    out = C.c_void_p()
+    _check(lib().fs_plan_create(arr, len(arr), C.byref(opt), C.byref(out)))
+    return out.value
+
+
+def _pointers(tensors):
+    arr = (C.c_void_p * max(1, len(tensors)))()
+    for i, t in enumerate(tensors):
+        arr[i] = t if isinstance(t, int) else t.data_ptr()
+    return arr
+
+
+def fs_launch(plan, inputs, outputs, stream=None):
+    """inputs/outputs: device tensors (anything with .data_ptr()) or raw addresses.
+    stream: a hipStream_t address; None = torch's current stream."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().fs_launch(plan, _pointers(inputs), len(inputs), _pointers(outputs), len(outputs), stream))
+
+
+def fs_destroy(plan):
+    _check(lib().fs_destroy(plan))
+
+
+def fs_plan_info(plan):
+    sched, nk = C.c_int32(), C.c_int32()
+    lds, ws, algo, moved = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib().fs_plan_info(plan, C.byref(sched), C.byref(nk), C.byref(lds), C.byref(ws),
+                              C.byref(algo), C.byref(moved)))
+    return {"schedule": SCHEDULE_NAMES[sched.value], "n_kernels": nk.value, "lds_bytes": lds.value,
+            "workspace_bytes": ws.value, "algorithmic_bytes": algo.value, "moved_bytes": moved.value}
+
+
+def fs_plan_describe(plan):
+    return lib().fs_plan_describe(plan).decode()
+
+
+def fs_stream_copy(dst, src, nbytes, stream=None):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().fs_stream_copy(dst if isinstance(dst, int) else dst.data_ptr(),
+                                src if isinstance(src, int) else src.data_ptr(), nbytes, stream))
+
+
+class Plan:
+    """Owner of one fs_plan handle."""
+
+    def __init__(self, ops, mode="stitched", wg_size=0, rows_per_wave=0, grid=0):
+        self._h = None
+        m = {"stitched": FS_MODE_STITCHED, "per_op": FS_MODE_PER_OP}[mode]
+        self._h = fs_plan_create(ops, m, wg_size, rows_per_wave, grid)
+
+    def launch(self, inputs, outputs, stream=None):
+        fs_launch(self._h, inputs, outputs, stream)
+
+    def info(self):
+        return fs_plan_info(self._h)
+
+    def describe(self):
+        return fs_plan_describe(self._h)
+
+    def close(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            fs_destroy(h)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -1,0 +1,203 @@
+// The C ABI of fs.h: plan construction (validate -> recognise -> size), launch, destroy.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/fs.h"
+#include "graph.h"
+#include "launchers.h"
+#include "match.h"
+#include "per_op.h"
+
+struct fs_plan {
+  fs::Graph graph;
+  int mode = FS_MODE_STITCHED;
+  int schedule = FS_SCHED_PER_OP;
+  fs::Match match;
+  fs::RowLaunch row;
+  fs::LnBwdLaunch lnbwd;
+  fs::AttnLaunch attn;
+  fs::PerOpPlan per_op;
+  int n_kernels = 1;
+  int64_t lds_bytes = 0, workspace_bytes = 0, moved_bytes = 0;
+  void* workspace = nullptr;
+  int device = -1;
+  std::string description;
+};
+
+namespace {
+
+thread_local std::string g_error = "";
+
+fs_status set_error(fs_status st, const std::string& msg) {
+  g_error = msg;
+  return st;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fs_last_error(void) { return g_error.c_str(); }
+
+fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_options* opt, fs_plan** out) {
+  if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
+  *out = nullptr;
+  fs_plan* p = new (std::nothrow) fs_plan;
+  if (!p) return set_error(FS_ERR_NOMEM, "out of host memory");
+  std::string err;
+  try {
+    if (!fs::build_graph(ops, n_ops, &p->graph, &err)) { delete p; return set_error(FS_ERR_INVALID, err); }
+    fs::LaunchOpts lo;
+    if (opt) {
+      if (opt->mode != FS_MODE_STITCHED && opt->mode != FS_MODE_PER_OP) { delete p; return set_error(FS_ERR_INVALID, "unknown mode"); }
+      if (opt->wg_size < 0 || opt->rows_per_wave < 0 || opt->grid < 0) { delete p; return set_error(FS_ERR_INVALID, "negative launch option"); }
+      p->mode = opt->mode;
+      lo.wg_size = opt->wg_size; lo.rows_per_wave = opt->rows_per_wave; lo.grid = opt->grid;
+    }
+    const int64_t algo = p->graph.algorithmic_bytes();
+    if (p->mode == FS_MODE_PER_OP) {
+      if (!fs::per_op_plan(p->graph, &p->per_op, &err)) { delete p; return set_error(FS_ERR_UNSUPPORTED, err); }
+      p->schedule = FS_SCHED_PER_OP;
+      p->n_kernels = p->per_op.n_kernels;
+      p->workspace_bytes = p->per_op.workspace_bytes;
+      p->moved_bytes = p->per_op.moved_bytes;
+      p->description = fs::per_op_describe(p->per_op);
+    } else {
+      if (!fs::recognise(p->graph, &p->match)) {
+        const std::string why = p->match.why;
+        delete p;
+        return set_error(FS_ERR_UNSUPPORTED, why);
+      }
+      p->moved_bytes = algo;
+      switch (p->match.kind) {
+        case fs::MATCH_ROW:
+          if (!fs::row_stitch_plan(p->match.row, lo, &p->row, &err)) {
+            const bool bad_opt = err.find("wg_size") != std::string::npos || err.find("rows_per_wave") != std::string::npos;
+            delete p;
+            return set_error(bad_opt ? FS_ERR_INVALID : FS_ERR_UNSUPPORTED, err);
+          }
+          p->schedule = FS_SCHED_ROW;
+          p->description = fs::row_stitch_describe(p->match.row, p->row);
+          break;
+        case fs::MATCH_LNBWD:
+          if (!fs::lnbwd_stitch_plan(p->match.lnbwd, lo, &p->lnbwd, &err)) {
+            const bool bad_opt = err.find("wg_size") != std::string::npos;
+            delete p;
+            return set_error(bad_opt ? FS_ERR_INVALID : FS_ERR_UNSUPPORTED, err);
+          }
+          p->schedule = FS_SCHED_ROW_COL;
+          p->lds_bytes = p->lnbwd.lds_bytes;
+          p->workspace_bytes = p->lnbwd.workspace_bytes;
+          p->moved_bytes = algo + 2 * (p->lnbwd.workspace_bytes);
+          p->description = fs::lnbwd_stitch_describe(p->match.lnbwd, p->lnbwd);
+          break;
+        case fs::MATCH_ATTN: {
+          int st = FS_OK;
+          if (!fs::attn_stitch_plan(p->match.attn, lo, &p->attn, &st, &err)) { delete p; return set_error((fs_status)st, err); }
+          p->schedule = FS_SCHED_BDOT_SOFTMAX;
+          p->lds_bytes = p->attn.lds_bytes;
+          p->description = fs::attn_stitch_describe(p->match.attn, p->attn);
+          break;
+        }
+        default:
+          delete p;
+          return set_error(FS_ERR_UNSUPPORTED, "no stitched schedule matches this group");
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  } catch (...) {
+    delete p;
+    return set_error(FS_ERR_INVALID, "internal error while planning");
+  }
+  *out = p;
+  return FS_OK;
+}
+
+fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* const* outputs, int32_t n_out,
+                    void* hip_stream) {
+  if (!p) return set_error(FS_ERR_INVALID, "plan is NULL");
+  const fs::Graph& g = p->graph;
+  if (n_in != (int32_t)g.params.size()) return set_error(FS_ERR_INVALID, "n_in differs from the number of parameters");
+  if (n_out != (int32_t)g.outputs.size()) return set_error(FS_ERR_INVALID, "n_out differs from the number of outputs");
+  if (!inputs || !outputs) return set_error(FS_ERR_INVALID, "inputs/outputs is NULL");
+  for (int i = 0; i < n_in; ++i) {
+    if (g[g.params[i]].numel() == 0) continue;
+    if (!inputs[i] || (reinterpret_cast<uintptr_t>(inputs[i]) & 15)) return set_error(FS_ERR_INVALID, "input pointer is NULL or not 16-byte aligned");
+  }
+  for (int i = 0; i < n_out; ++i) {
+    if (g[g.outputs[i]].numel() == 0) continue;
+    if (!outputs[i] || (reinterpret_cast<uintptr_t>(outputs[i]) & 15)) return set_error(FS_ERR_INVALID, "output pointer is NULL or not 16-byte aligned");
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  std::string err;
+  try {
+    if (p->workspace_bytes > 0) {
+      int dev = -1;
+      if (hipGetDevice(&dev) != hipSuccess) return set_error(FS_ERR_HIP, "hipGetDevice failed");
+      if (!p->workspace) {
+        hipError_t e = hipMalloc(&p->workspace, (size_t)p->workspace_bytes);
+        if (e != hipSuccess) { p->workspace = nullptr; return set_error(FS_ERR_NOMEM, std::string("workspace hipMalloc: ") + hipGetErrorString(e)); }
+        p->device = dev;
+        // tickets start at zero; every launch leaves them at zero again
+        e = hipMemsetAsync(p->workspace, 0, (size_t)(p->workspace_bytes < 65536 ? p->workspace_bytes : 65536), stream);
+        if (e != hipSuccess) return set_error(FS_ERR_HIP, std::string("workspace memset: ") + hipGetErrorString(e));
+      } else if (dev != p->device) {
+        return set_error(FS_ERR_INVALID, "plan is bound to the device of its first launch");
+      }
+    }
+    int rc = 0;
+    switch (p->schedule) {
+      case FS_SCHED_ROW: rc = fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err); break;
+      case FS_SCHED_ROW_COL: rc = fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err); break;
+      case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
+      default: rc = fs::per_op_launch(g, p->per_op, inputs, outputs, p->workspace, hip_stream, &err); break;
+    }
+    if (rc != 0) return set_error(FS_ERR_HIP, err);
+  } catch (...) {
+    return set_error(FS_ERR_HIP, "internal error while launching");
+  }
+  return FS_OK;
+}
+
+fs_status fs_destroy(fs_plan* p) {
+  if (!p) return FS_OK;
+  fs_status st = FS_OK;
+  if (p->workspace) {
+    const hipError_t e = hipFree(p->workspace);
+    if (e != hipSuccess) st = set_error(FS_ERR_HIP, std::string("hipFree: ") + hipGetErrorString(e));
+  }
+  delete p;
+  return st;
+}
+
+fs_status fs_plan_info(const fs_plan* p, int32_t* schedule, int32_t* n_kernels, int64_t* lds_bytes,
+                       int64_t* workspace_bytes, int64_t* algorithmic_bytes, int64_t* moved_bytes) {
+  if (!p) return set_error(FS_ERR_INVALID, "plan is NULL");
+  if (schedule) *schedule = p->schedule;
+  if (n_kernels) *n_kernels = p->n_kernels;
+  if (lds_bytes) *lds_bytes = p->lds_bytes;
+  if (workspace_bytes) *workspace_bytes = p->workspace_bytes;
+  if (algorithmic_bytes) *algorithmic_bytes = p->graph.algorithmic_bytes();
+  if (moved_bytes) *moved_bytes = p->moved_bytes;
+  return FS_OK;
+}
+
+const char* fs_plan_describe(const fs_plan* p) { return p ? p->description.c_str() : ""; }
+
+fs_status fs_stream_copy(void* dst, const void* src, int64_t bytes, void* hip_stream) {
+  if (bytes < 0 || (bytes & 15)) return set_error(FS_ERR_INVALID, "bytes must be a non-negative multiple of 16");
+  if (bytes == 0) return FS_OK;
+  if (!dst || !src || (reinterpret_cast<uintptr_t>(dst) & 15) || (reinterpret_cast<uintptr_t>(src) & 15))
+    return set_error(FS_ERR_INVALID, "pointer is NULL or not 16-byte aligned");
+  std::string err;
+  if (fs::stream_copy_launch(dst, src, bytes, hip_stream, &err) != 0) return set_error(FS_ERR_HIP, err);
+  return FS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Device-side building blocks shared by the stitched kernels: 16-byte vector access
+// for the three storage dtypes and wave64 all-reduce over lane groups.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct bf16_t { uint16_t bits; };   // storage-only tags: all arithmetic is fp32
+struct f16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);   // round to nearest even
+}
+__device__ __forceinline__ float f16_to_f32(uint32_t b) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+}
+__device__ __forceinline__ uint32_t f32_to_f16(float f) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// One 16-byte vector of T <-> V fp32 values.
+template <typename T> struct Vec;
+
+template <> struct Vec<float> {
+  static constexpr int V = 4;
+  static __device__ __forceinline__ u32x4 load_raw(const float* p) {
+    return *reinterpret_cast<const u32x4*>(p);
+  }
+  static __device__ __forceinline__ void unpack(u32x4 t, float (&o)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = __builtin_bit_cast(float, t[i]);
+  }
+  static __device__ __forceinline__ void load(const float* p, float (&o)[4]) { unpack(load_raw(p), o); }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+    f32x4 t = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(p) = t;
+  }
+  static __device__ __forceinline__ float load1(const float* p) { return *p; }
+  static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+};
+
+template <> struct Vec<bf16_t> {
+  static constexpr int V = 8;
+  static __device__ __forceinline__ u32x4 load_raw(const bf16_t* p) {
+    return *reinterpret_cast<const u32x4*>(p);
+  }
+  static __device__ __forceinline__ void unpack(u32x4 t, float (&o)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = __builtin_bit_cast(float, t[i] << 16);
+      o[2 * i + 1] = __builtin_bit_cast(float, t[i] & 0xFFFF0000u);
+    }
+  }
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&o)[8]) { unpack(load_raw(p), o); }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    u32x4 t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = f32_to_bf16(v[2 * i]) | (f32_to_bf16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<u32x4*>(p) = t;
+  }
+  static __device__ __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(p->bits); }
+  static __device__ __forceinline__ void store1(bf16_t* p, float v) { p->bits = (uint16_t)f32_to_bf16(v); }
+};
+
+template <> struct Vec<f16_t> {
+  static constexpr int V = 8;
+  static __device__ __forceinline__ u32x4 load_raw(const f16_t* p) {
+    return *reinterpret_cast<const u32x4*>(p);
+  }
+  static __device__ __forceinline__ void unpack(u32x4 t, float (&o)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = f16_to_f32(t[i] & 0xFFFFu);
+      o[2 * i + 1] = f16_to_f32(t[i] >> 16);
+    }
+  }
+  static __device__ __forceinline__ void load(const f16_t* p, float (&o)[8]) { unpack(load_raw(p), o); }
+  static __device__ __forceinline__ void store(f16_t* p, const float (&v)[8]) {
+    u32x4 t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = f32_to_f16(v[2 * i]) | (f32_to_f16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<u32x4*>(p) = t;
+  }
+  static __device__ __forceinline__ float load1(const f16_t* p) { return f16_to_f32(p->bits); }
+  static __device__ __forceinline__ void store1(f16_t* p, float v) { p->bits = (uint16_t)f32_to_f16(v); }
+};
+
+// ---- wave64 all-reduce over aligned groups of L lanes (L a power of two) -----------
+// Steps inside a 16-lane DPP row are DPP permutes (quad swaps, half mirror, mirror);
+// the two cross-row steps use the gfx950 permlane16/32 swaps, so no step goes through
+// LDS.  Every lane of the wave must be active.
+struct SumOp { static __device__ __forceinline__ float apply(float a, float b) { return a + b; } };
+struct MaxOp { static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); } };
+
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
+template <class Op, int L> __device__ __forceinline__ float group_allreduce(float v) {
+  static_assert(L == 1 || L == 2 || L == 4 || L == 8 || L == 16 || L == 32 || L == 64, "L");
+  if (L >= 2) v = Op::apply(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
+  if (L >= 4) v = Op::apply(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
+  if (L >= 8) v = Op::apply(v, dpp_move<0x141>(v));   // row_half_mirror
+  if (L >= 16) v = Op::apply(v, dpp_move<0x140>(v));  // row_mirror
+  if (L >= 32) {
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = Op::apply(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+  }
+  if (L >= 64) {
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    v = Op::apply(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+  }
+  return v;
+}
+
+}  // namespace fs

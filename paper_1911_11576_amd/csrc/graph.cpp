@@ -1,0 +1,151 @@
+// Validation of a fusion group: topological order, operand counts, shapes and dtypes of
+// every op of the vocabulary in fs.h.  Pure host code.
+#include "graph.h"
+
+#include <cstdio>
+
+namespace fs {
+
+const char* kind_name(int k) {
+  static const char* names[FS_NUM_OPKINDS] = {
+      "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum", "negate", "exp",
+      "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast", "reduce_sum", "reduce_max", "dot",
+      "causal_mask", "output"};
+  return (k >= 0 && k < FS_NUM_OPKINDS) ? names[k] : "?";
+}
+
+int64_t Graph::algorithmic_bytes() const {
+  int64_t total = 0;
+  for (int i : params) total += nodes[i].numel() * (nodes[i].dtype == FS_F32 ? 4 : 2);
+  for (int i : outputs) total += nodes[i].numel() * (nodes[i].dtype == FS_F32 ? 4 : 2);
+  return total;
+}
+
+namespace {
+
+struct Fail {
+  std::string* err;
+  int index;
+  bool operator()(const char* what) const {
+    char buf[256];
+    snprintf(buf, sizeof buf, "op %d: %s", index, what);
+    *err = buf;
+    return false;
+  }
+};
+
+int operand_count(int kind) {
+  if (kind == FS_PARAMETER || kind == FS_CONSTANT) return 0;
+  if (is_binary(kind) || kind == FS_DOT) return 2;
+  return 1;
+}
+
+}  // namespace
+
+bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* err) {
+  if (!ops) { *err = "ops is NULL"; return false; }
+  if (n_ops < 1 || n_ops > 4096) { *err = "n_ops out of range [1,4096]"; return false; }
+  g->nodes.clear(); g->params.clear(); g->outputs.clear();
+  g->nodes.reserve(n_ops);
+  std::vector<char> consumed_output(n_ops, 0);
+  for (int i = 0; i < n_ops; ++i) {
+    const fs_op_desc& d = ops[i];
+    Fail fail{err, i};
+    if (d.kind < 0 || d.kind >= FS_NUM_OPKINDS) return fail("unknown op kind");
+    if (d.dtype < FS_F32 || d.dtype > FS_BF16) return fail("unknown dtype");
+    if (d.rank < 0 || d.rank > FS_MAX_RANK) return fail("rank out of range");
+    if (d.reserved != 0) return fail("reserved field must be 0");
+    Node n;
+    n.kind = d.kind; n.dtype = d.dtype; n.rank = d.rank; n.axis = d.axis; n.attr = d.attr;
+    for (int k = 0; k < d.rank; ++k) {
+      if (d.shape[k] < 0) return fail("negative extent");
+      n.shape[k] = d.shape[k];
+    }
+    if (n.numel() >= ((int64_t)1 << 40)) return fail("tensor too large");
+    const int nop = operand_count(d.kind);
+    for (int k = 0; k < 3; ++k) {
+      if (k < nop) {
+        if (d.operand[k] < 0 || d.operand[k] >= i) return fail("operand must refer to an earlier op");
+        if (g->nodes[d.operand[k]].kind == FS_OUTPUT) return fail("an output op cannot be consumed");
+        n.operand[k] = d.operand[k];
+      } else if (d.operand[k] != -1) {
+        return fail("unused operand slot must be -1");
+      }
+    }
+    const Node* a = nop > 0 ? &g->nodes[n.operand[0]] : nullptr;
+    const Node* b = nop > 1 ? &g->nodes[n.operand[1]] : nullptr;
+    switch (d.kind) {
+      case FS_PARAMETER:
+        if (n.rank < 1) return fail("parameter must have rank >= 1");
+        n.ordinal = (int)g->params.size();
+        g->params.push_back(i);
+        break;
+      case FS_CONSTANT:
+        if (n.rank != 0) return fail("constant must have rank 0");
+        break;
+      case FS_ADD: case FS_SUBTRACT: case FS_MULTIPLY: case FS_DIVIDE: case FS_MAXIMUM: {
+        const bool ca = a->kind == FS_CONSTANT, cb = b->kind == FS_CONSTANT;
+        if (ca && cb) return fail("binary op of two constants");
+        if (!ca && !(a->same_shape(n) && a->dtype == n.dtype)) return fail("operand 0 shape/dtype differs from result");
+        if (!cb && !(b->same_shape(n) && b->dtype == n.dtype)) return fail("operand 1 shape/dtype differs from result");
+        break;
+      }
+      case FS_NEGATE: case FS_EXP: case FS_LOG: case FS_TANH: case FS_RSQRT: case FS_SQRT:
+        if (!(a->same_shape(n) && a->dtype == n.dtype)) return fail("operand shape/dtype differs from result");
+        break;
+      case FS_CONVERT:
+        if (!a->same_shape(n)) return fail("convert changes the shape");
+        break;
+      case FS_BROADCAST: {
+        if (a->dtype != n.dtype) return fail("broadcast changes the dtype");
+        if (a->kind == FS_CONSTANT) return fail("broadcast of a rank-0 constant: use the constant directly");
+        if (n.axis < 0 || n.axis + a->rank > n.rank) return fail("broadcast axis out of range");
+        for (int k = 0; k < a->rank; ++k)
+          if (a->shape[k] != 1 && a->shape[k] != n.shape[n.axis + k]) return fail("broadcast extent mismatch");
+        break;
+      }
+      case FS_REDUCE_SUM: case FS_REDUCE_MAX: {
+        if (a->dtype != n.dtype) return fail("reduce changes the dtype");
+        if (a->rank < 1 || n.axis < 0 || n.axis >= a->rank) return fail("reduce axis out of range");
+        if (n.rank != a->rank - 1) return fail("reduce result must drop the reduced dim");
+        for (int k = 0, j = 0; k < a->rank; ++k) {
+          if (k == n.axis) continue;
+          if (n.shape[j++] != a->shape[k]) return fail("reduce result extent mismatch");
+        }
+        if (d.kind == FS_REDUCE_MAX && a->shape[n.axis] == 0) return fail("reduce_max over an empty dim");
+        break;
+      }
+      case FS_DOT: {
+        if (a->rank != 3 || b->rank != 3 || n.rank != 3) return fail("dot operands and result must have rank 3");
+        if (a->dtype != b->dtype) return fail("dot operands differ in dtype");
+        if (n.axis != 0 && n.axis != 1) return fail("dot axis must be 0 or 1");
+        const int64_t kb = n.axis ? b->shape[2] : b->shape[1], nb = n.axis ? b->shape[1] : b->shape[2];
+        if (a->shape[0] != b->shape[0] || a->shape[2] != kb) return fail("dot operand extents mismatch");
+        if (n.shape[0] != a->shape[0] || n.shape[1] != a->shape[1] || n.shape[2] != nb)
+          return fail("dot result extents mismatch");
+        break;
+      }
+      case FS_CAUSAL_MASK:
+        if (n.rank < 2) return fail("causal_mask needs rank >= 2");
+        if (!(a->same_shape(n) && a->dtype == n.dtype)) return fail("operand shape/dtype differs from result");
+        break;
+      case FS_OUTPUT:
+        if (!(a->same_shape(n) && a->dtype == n.dtype)) return fail("output shape/dtype differs from its operand");
+        if (a->kind == FS_CONSTANT) return fail("output of a constant");
+        if (consumed_output[n.operand[0]]) return fail("value is already an output");
+        consumed_output[n.operand[0]] = 1;
+        n.ordinal = (int)g->outputs.size();
+        g->outputs.push_back(i);
+        break;
+      default:
+        return fail("unknown op kind");
+    }
+    g->nodes.push_back(n);
+  }
+  if (g->params.empty()) { *err = "group has no parameter"; return false; }
+  if (g->outputs.empty()) { *err = "group has no output"; return false; }
+  if (g->params.size() > 64 || g->outputs.size() > 16) { *err = "too many parameters or outputs"; return false; }
+  return true;
+}
+
+}  // namespace fs

@@ -1,0 +1,45 @@
+// Validated host copy of a fusion group (the op list handed to fs_plan_create).
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "../../include/fs.h"
+
+namespace fs {
+
+struct Node {
+  int kind = 0, dtype = 0, rank = 0, axis = 0;
+  int64_t shape[FS_MAX_RANK] = {0, 0, 0, 0};
+  int operand[3] = {-1, -1, -1};
+  double attr = 0.0;
+  int ordinal = -1;   // parameter ordinal or output ordinal
+
+  int64_t numel() const {
+    int64_t n = 1;
+    for (int d = 0; d < rank; ++d) n *= shape[d];
+    return n;
+  }
+  bool same_shape(const Node& o) const {
+    if (rank != o.rank) return false;
+    for (int d = 0; d < rank; ++d) if (shape[d] != o.shape[d]) return false;
+    return true;
+  }
+};
+
+struct Graph {
+  std::vector<Node> nodes;
+  std::vector<int> params;    // node index of each parameter, in order
+  std::vector<int> outputs;   // node index of each FS_OUTPUT op, in order
+  const Node& operator[](int i) const { return nodes[i]; }
+  int size() const { return (int)nodes.size(); }
+  int64_t algorithmic_bytes() const;
+};
+
+// Copies and checks the list.  On failure returns false and sets *err.
+bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* err);
+
+inline bool is_binary(int k) { return k >= FS_ADD && k <= FS_MAXIMUM; }
+inline bool is_unary(int k) { return k >= FS_NEGATE && k <= FS_SQRT; }
+const char* kind_name(int k);
+
+}  // namespace fs

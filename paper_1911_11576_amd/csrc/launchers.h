@@ -1,0 +1,31 @@
+// Host entry points of the stitched schedules: each schedule has a `plan` step (pure
+// host: geometry, LDS budget; no GPU call), a `describe` step and a `launch` step.
+#pragma once
+#include <string>
+#include "specs.h"
+
+namespace fs {
+
+struct RowLaunch { int variant = 0, K = 1, L = 64, U = 1, wg = 256, grid = 1; };
+bool row_stitch_plan(const RowSpec&, const LaunchOpts&, RowLaunch*, std::string* err);
+std::string row_stitch_describe(const RowSpec&, const RowLaunch&);
+int row_stitch_launch(const RowSpec&, const RowLaunch&, const void* const* in, void* const* out,
+                      void* stream, std::string* err);
+
+// LayerNorm backward: row path for dx packed with the column path for dgamma/dbeta.
+struct LnBwdLaunch { int K = 1, wg = 512, grid = 1, group = 1; int64_t lds_bytes = 0, workspace_bytes = 0; };
+bool lnbwd_stitch_plan(const LnBwdSpec&, const LaunchOpts&, LnBwdLaunch*, std::string* err);
+std::string lnbwd_stitch_describe(const LnBwdSpec&, const LnBwdLaunch&);
+int lnbwd_stitch_launch(const LnBwdSpec&, const LnBwdLaunch&, const void* const* in, void* const* out,
+                        void* workspace, void* stream, std::string* err);
+
+// Batched dot -> softmax -> batched dot on MFMA.
+struct AttnLaunch { int wg = 256, grid = 1, tiles = 4; int64_t lds_bytes = 0; };
+bool attn_stitch_plan(const AttnSpec&, const LaunchOpts&, AttnLaunch*, int* status, std::string* err);
+std::string attn_stitch_describe(const AttnSpec&, const AttnLaunch&);
+int attn_stitch_launch(const AttnSpec&, const AttnLaunch&, const void* const* in, void* const* out,
+                       void* stream, std::string* err);
+
+int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, std::string* err);
+
+}  // namespace fs

@@ -1,0 +1,148 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports what
+include/fs.h declares, plans are recognised and sized, and malformed or unsupported
+groups come back as status codes (the paper's "negative score", Section 4.3)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1911_11576_amd import FsError, Plan, binding
+from workloads import BY_NAME, CONFIGS, graphs
+from workloads.graphs import Graph, Op
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fs.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fs_[a-z_]+)\s*\(", header))
+    assert {"fs_plan_create", "fs_launch", "fs_destroy", "fs_last_error", "fs_plan_info",
+            "fs_plan_describe", "fs_stream_copy"} <= names
+    lib = binding.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches_the_header():
+    # int32 x4, int64 x4, int32 x3, int32, double
+    assert ctypes.sizeof(binding.fs_op_desc) == 16 + 32 + 12 + 4 + 8
+    assert binding.fs_op_desc.shape.offset == 16
+    assert binding.fs_op_desc.operand.offset == 48
+    assert binding.fs_op_desc.attr.offset == 64
+    assert ctypes.sizeof(binding.fs_plan_options) == 16
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_configs_are_recognised(cfg):
+    want = {"layernorm_fwd": "row", "scaled_masked_softmax": "row", "causal_attention": "bdot_softmax",
+            "bias_gelu_residual_layernorm": "row", "layernorm_bwd": "row_col"}[cfg.name]
+    ops = cfg.graph_fn(**cfg.full)
+    with Plan(ops) as p:
+        info = p.info()
+        assert info["schedule"] == want
+        assert info["n_kernels"] == 1
+        assert "cta_num=" in p.describe() and "cta_size=" in p.describe()
+    with Plan(ops, "per_op") as p:
+        info = p.info()
+        assert info["schedule"] == "per_op" and info["n_kernels"] >= 7
+        assert info["moved_bytes"] > 3 * info["algorithmic_bytes"]
+        assert info["workspace_bytes"] > 0
+
+
+def test_plan_info_sizes():
+    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full)) as p:
+        info = p.info()
+        assert info["algorithmic_bytes"] == 402_927_616
+        assert info["lds_bytes"] == 16 * 1024
+        assert 0 < info["workspace_bytes"] < 16 * 2**20
+    with Plan(BY_NAME["causal_attention"].graph_fn(**BY_NAME["causal_attention"].full)) as p:
+        assert 0 < p.info()["lds_bytes"] <= 64 * 1024
+
+
+def test_commuted_and_reassociated_spellings_are_recognised():
+    # LayerNorm with mean spelled as multiply by 1/N, operands swapped, beta added first
+    g = Graph()
+    x = g.parameter("x", "f32", (16, 256))
+    gamma = g.parameter("gamma", "f32", (256,))
+    beta = g.parameter("beta", "f32", (256,))
+    mean = g.multiply(g.constant(1.0 / 256), g.reduce_sum(x, 1))
+    c = g.subtract(x, g.row_broadcast(mean, x))
+    var = g.multiply(g.reduce_sum(g.multiply(c, c), 1), g.constant(1.0 / 256))
+    rstd = g.rsqrt(g.add(g.constant(1e-6), var))
+    y = g.add(g.col_broadcast(beta, x), g.multiply(g.col_broadcast(gamma, x), g.multiply(g.row_broadcast(rstd, x), c)))
+    g.output(y)
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "row"
+    # softmax without scale or mask
+    with Plan(graphs.scaled_masked_softmax((8, 64), 1.0, "none")) as p:
+        assert p.info()["schedule"] == "row"
+
+
+def _expect(status, ops, **kw):
+    with pytest.raises(FsError) as e:
+        Plan(ops, **kw)
+    assert e.value.status == status, e.value
+    assert e.value.message
+    return e.value.message
+
+
+def test_unsupported_groups_return_unsupported_not_crash():
+    g = Graph()
+    x = g.parameter("x", "f32", (8, 64))
+    g.output(g.exp(g.tanh(x)))                     # plain elementwise chain: no stitched schedule yet
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    with Plan(g.ops, "per_op") as p:               # the per-op plan always exists
+        assert p.info()["n_kernels"] == 2
+    # row too long for one wavefront's registers
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 4096))
+    # cols not a multiple of the vector width
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 770))
+    # fp32 attention has no MFMA path
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 64, 64, "f32"))
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 256, 64))
+
+
+def test_lds_volume_constraint():
+    msg = _expect(binding.FS_ERR_LDS, graphs.causal_attention(2, 128, 128))
+    assert "LDS" in msg
+
+
+def test_invalid_op_lists():
+    ok = graphs.layernorm_fwd(4, 64)
+
+    def mutate(i, **kw):
+        ops = list(ok)
+        ops[i] = ops[i]._replace(**kw)
+        return ops
+    _expect(binding.FS_ERR_INVALID, [])                                            # empty
+    _expect(binding.FS_ERR_INVALID, mutate(4, operands=(7,)))                       # forward reference
+    _expect(binding.FS_ERR_INVALID, mutate(3, axis=5))                              # reduce axis
+    _expect(binding.FS_ERR_INVALID, mutate(0, shape=(4, 65)))                       # shape mismatch downstream
+    _expect(binding.FS_ERR_INVALID, mutate(0, shape=(4, -64)))                      # negative extent
+    _expect(binding.FS_ERR_INVALID, [op for op in ok if op.kind != "output"])       # no output
+    _expect(binding.FS_ERR_INVALID, [Op("constant", "f32", (), (), -1, 1.0, ""),
+                                     Op("output", "f32", (), (0,), -1, 0.0, "")])    # no parameter / const output
+    _expect(binding.FS_ERR_INVALID, ok, wg_size=100)                                # bad launch option
+    _expect(binding.FS_ERR_INVALID, ok, wg_size=-64)
+    # raw ABI misuse: NULL out pointer, unknown kind/dtype, non-zero reserved field
+    lib = binding.lib()
+    arr = binding.marshal_ops(ok)
+    assert lib.fs_plan_create(arr, len(arr), None, None) == binding.FS_ERR_INVALID
+    out = ctypes.c_void_p()
+    assert lib.fs_plan_create(None, 3, None, ctypes.byref(out)) == binding.FS_ERR_INVALID
+    for field, val in (("kind", 99), ("dtype", 7), ("reserved", 1), ("rank", 9)):
+        arr = binding.marshal_ops(ok)
+        setattr(arr[2], field, val)
+        assert lib.fs_plan_create(arr, len(arr), None, ctypes.byref(out)) == binding.FS_ERR_INVALID
+        assert out.value is None
+        assert binding.fs_last_error()
+    assert lib.fs_destroy(None) == binding.FS_OK
+
+
+def test_launch_without_plan_is_an_error_not_a_crash():
+    lib = binding.lib()
+    assert lib.fs_launch(None, None, 0, None, 0, None) == binding.FS_ERR_INVALID
+    assert lib.fs_plan_info(None, None, None, None, None, None, None) == binding.FS_ERR_INVALID
+    assert lib.fs_stream_copy(None, None, 24, None) == binding.FS_ERR_INVALID

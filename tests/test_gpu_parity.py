@@ -1,0 +1,339 @@
+"""GPU parity: the stitched kernels (and the per-op baseline), called through the C ABI,
+against the CPU oracle, element by element on the same seeded inputs.
+
+Bar: |gpu - oracle| <= tol + tol*|oracle| with tol = 1e-5 for fp32 groups and 2e-2 for
+fp16/bf16 groups (the oracle is fp64 and unrounded)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import interp
+from paper_1911_11576_amd import FsError, Plan
+from paper_1911_11576_amd import binding
+from workloads import BY_NAME, CONFIGS, TOLERANCE, graphs, inputs
+
+from gpu_util import (alloc_outputs, assert_close, check_against_oracle, group_dtype, run_gpu,
+                      to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    # names the case on the real stderr before any GPU work, so that it survives a dead box
+    sys.__stderr__.write(f"[gpu-case] {msg}\n")
+    sys.__stderr__.flush()
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu(device):
+    yield
+
+
+# ---------------------------------------------------------------- the five configs, small
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_config_small_stitched(cfg):
+    announce(f"small stitched {cfg.name}")
+    ops, ins = cfg.build("small")
+    check_against_oracle(ops, ins, "stitched", what=cfg.name)
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_config_small_per_op_baseline(cfg):
+    """The unfused baseline rounds every intermediate to its declared dtype, as the oracle's
+    storage-rounding mode does; it is held to the group tolerance except for the fp32
+    column sums over many rows, whose per-op rounding alone exceeds 1e-5 absolute."""
+    announce(f"small per_op {cfg.name}")
+    ops, ins = cfg.build("small")
+    want = interp.run(ops, ins)
+    got = run_gpu(ops, ins, "per_op")
+    tol = TOLERANCE[cfg.dtype]
+    for i, (a, b) in enumerate(zip(got, want)):
+        t = 1e-3 if (cfg.name == "layernorm_bwd" and b.ndim == 1) else tol
+        assert_close(a, b, t, f"{cfg.name} per_op output {i}")
+
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_stitched_equals_per_op_on_gpu(cfg):
+    announce(f"stitched vs per_op {cfg.name}")
+    ops, ins = cfg.build("small")
+    a = run_gpu(ops, ins, "stitched")
+    b = run_gpu(ops, ins, "per_op")
+    tol = TOLERANCE[cfg.dtype]
+    for i, (x, y) in enumerate(zip(a, b)):
+        t = 1e-3 if (cfg.name == "layernorm_bwd" and x.ndim == 1) else 2 * tol
+        assert_close(x, y, t, f"{cfg.name} stitched vs per_op output {i}")
+
+
+# ---------------------------------------------------------------- row schedule: shapes
+
+@pytest.mark.parametrize("rows,cols", [(1, 4), (3, 8), (5, 24), (37, 100), (9, 256), (64, 768), (37, 1000),
+                                       (11, 1536), (6, 2048), (130, 32)])
+def test_layernorm_shapes_f32(rows, cols):
+    announce(f"layernorm f32 {rows}x{cols}")
+    check_against_oracle(graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols), what=f"ln {rows}x{cols}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 40), (33, 512), (19, 1024), (5, 2048)])
+def test_layernorm_shapes_16bit(rows, cols, dtype):
+    announce(f"layernorm {dtype} {rows}x{cols}")
+    check_against_oracle(graphs.layernorm_fwd(rows, cols, dtype), inputs.layernorm_fwd(rows, cols, dtype),
+                         what=f"ln {dtype} {rows}x{cols}")
+
+
+@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 203, 1024), ("f16", 33, 768), ("f32", 65, 1024),
+                                             ("bf16", 4, 2048), ("f32", 3, 8)])
+def test_bias_gelu_residual_layernorm_shapes(dtype, rows, cols):
+    announce(f"bias+gelu+res+ln {dtype} {rows}x{cols}")
+    check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 {dtype} {rows}x{cols}")
+
+
+@pytest.mark.parametrize("shape", [(1, 4), (3, 12), (1030, 128), (77, 64), (5, 1000), (9, 2048), (130, 32), (33, 16)])
+@pytest.mark.parametrize("mask", ["full", "none"])
+def test_softmax_shapes_f32(shape, mask):
+    announce(f"softmax f32 {shape} mask={mask}")
+    check_against_oracle(graphs.scaled_masked_softmax(shape, 0.125, mask),
+                         inputs.scaled_masked_softmax(shape, mask), what=f"softmax {shape} {mask}")
+
+
+@pytest.mark.parametrize("shape", [(3, 4, 16, 16), (2, 3, 5, 128), (4, 2, 7, 64)])
+def test_softmax_key_padding_mask(shape):
+    announce(f"softmax key_padding {shape}")
+    check_against_oracle(graphs.scaled_masked_softmax(shape, 0.125, "key_padding"),
+                         inputs.scaled_masked_softmax(shape, "key_padding"), what=f"softmax kp {shape}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_softmax_16bit(dtype):
+    announce(f"softmax {dtype}")
+    shape = (67, 128)
+    # a mask of -1e4 is not representable in f16/bf16 exactly; the generator rounds it
+    check_against_oracle(graphs.scaled_masked_softmax(shape, 0.125, "full", dtype),
+                         inputs.scaled_masked_softmax(shape, "full", dtype), what=f"softmax {dtype}")
+
+
+def test_softmax_fully_masked_rows_and_large_values():
+    announce("softmax degenerate rows")
+    shape = (8, 128)
+    ops = graphs.scaled_masked_softmax(shape, 0.125, "full")
+    s, m = inputs.scaled_masked_softmax(shape, "full")
+    m[0, :] = -1e4          # fully padded row: still a softmax of the shifted row
+    s[1, :] = 3.0           # constant row
+    s[2, :] = 600.0         # exp would overflow without the max subtraction
+    s[3, 5] = -700.0
+    check_against_oracle(ops, [s, m], what="softmax degenerate")
+
+
+# ---------------------------------------------------------------- launch parameters
+
+@pytest.mark.parametrize("opts", [dict(wg_size=64), dict(wg_size=512), dict(rows_per_wave=1), dict(rows_per_wave=2),
+                                  dict(grid=7), dict(wg_size=128, rows_per_wave=4, grid=3)])
+def test_row_schedule_launch_options_do_not_change_results(opts):
+    announce(f"row options {opts}")
+    shape = (1030, 128)
+    ops, ins = graphs.scaled_masked_softmax(shape, 0.125, "full"), inputs.scaled_masked_softmax(shape, "full")
+    ref = run_gpu(ops, ins)
+    got = run_gpu(ops, ins, **opts)
+    assert np.array_equal(ref[0], got[0])
+    ops, ins = graphs.layernorm_fwd(517, 768), inputs.layernorm_fwd(517, 768)
+    ref = run_gpu(ops, ins)
+    got = run_gpu(ops, ins, **opts)
+    assert np.array_equal(ref[0], got[0])
+
+
+# ---------------------------------------------------------------- LayerNorm backward
+
+@pytest.mark.parametrize("rows,cols", [(1, 4), (5, 64), (517, 1024), (4099, 1000), (33, 2048), (700, 256)])
+def test_layernorm_bwd_shapes(rows, cols):
+    announce(f"layernorm_bwd {rows}x{cols}")
+    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), what=f"lnbwd {rows}x{cols}")
+
+
+@pytest.mark.parametrize("opts", [dict(grid=1), dict(grid=3, wg_size=64), dict(grid=100, wg_size=256), dict(grid=1024)])
+def test_layernorm_bwd_launch_options(opts):
+    announce(f"layernorm_bwd options {opts}")
+    rows, cols = 2100, 1024
+    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), what=f"lnbwd {opts}", **opts)
+
+
+def test_layernorm_bwd_is_bit_reproducible_and_reusable():
+    announce("layernorm_bwd determinism")
+    rows, cols = 3000, 1024
+    ops, ins = graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols)
+    dev_in = to_device(ops, ins)
+    runs = []
+    with Plan(ops) as plan:
+        for _ in range(5):
+            out = alloc_outputs(ops)
+            plan.launch(dev_in, out)
+            torch.cuda.synchronize()
+            runs.append([t.cpu().numpy() for t in out])
+    for r in runs[1:]:
+        for a, b in zip(runs[0], r):
+            assert np.array_equal(a, b)
+
+
+def test_layernorm_bwd_output_subsets():
+    announce("layernorm_bwd subsets")
+    rows, cols = 300, 512
+    full = graphs.layernorm_bwd(rows, cols)
+    ins = inputs.layernorm_bwd(rows, cols)
+    outs = [i for i, op in enumerate(full) if op.kind == "output"]
+    for keep in ([0], [1, 2], [2], [0, 2]):
+        ops = [op for i, op in enumerate(full) if op.kind != "output" or outs.index(i) in keep]
+        check_against_oracle(ops, ins, what=f"lnbwd outputs {keep}")
+
+
+# ---------------------------------------------------------------- attention
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("seq,dim", [(64, 64), (1, 32), (7, 64), (16, 32), (33, 64), (94, 64), (128, 32), (48, 128), (128, 64)])
+def test_attention_shapes(seq, dim, dtype):
+    announce(f"attention {dtype} seq={seq} dim={dim}")
+    B = 5
+    check_against_oracle(graphs.causal_attention(B, seq, dim, dtype), inputs.causal_attention(B, seq, dim, dtype),
+                         what=f"attn {dtype} {seq}x{dim}")
+
+
+def _attention_variant(B, S, d, causal, fill, dtype="f16"):
+    g = graphs.Graph()
+    q = g.parameter("q", dtype, (B, S, d))
+    k = g.parameter("k", dtype, (B, S, d))
+    v = g.parameter("v", dtype, (B, S, d))
+    z = g.multiply(g.dot(q, k, transpose_b=True), g.constant(d ** -0.5))
+    if causal:
+        z = g.causal_mask(z, fill)
+    zmax = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
+    p = g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), e))
+    o = g.dot(g.convert(p, dtype), v)
+    g.output(g.convert(o, dtype))
+    return g.ops
+
+
+@pytest.mark.parametrize("causal,fill", [(False, 0.0), (True, -1e4), (True, -3.0)])
+def test_attention_mask_variants(causal, fill):
+    announce(f"attention causal={causal} fill={fill}")
+    B, S, d = 3, 40, 64
+    ops = _attention_variant(B, S, d, causal, fill)
+    check_against_oracle(ops, inputs.causal_attention(B, S, d), what=f"attn causal={causal} fill={fill}")
+
+
+# ---------------------------------------------------------------- full-size configs, bench launch shape
+
+def _sample_rows(n, k=64, seed=0):
+    r = np.random.default_rng(seed)
+    idx = np.unique(np.concatenate([[0, 1, n // 2, n - 2, n - 1], r.integers(0, n, k)]))
+    return idx
+
+
+def test_full_size_layernorm_fwd():
+    announce("full cfg1")
+    ops, ins = BY_NAME["layernorm_fwd"].build("full")
+    check_against_oracle(ops, ins, what="cfg1 full")
+
+
+def test_full_size_softmax_sampled_rows():
+    announce("full cfg2")
+    cfg = BY_NAME["scaled_masked_softmax"]
+    ops, ins = cfg.build("full")
+    (got,) = run_gpu(ops, ins)
+    idx = _sample_rows(ins[0].shape[0], 256)
+    sub_ops = graphs.scaled_masked_softmax((len(idx), 128), 0.125, "full")
+    (want,) = interp.run(sub_ops, [ins[0][idx], ins[1][idx]])
+    assert_close(got[idx], want, 1e-5, "cfg2 full sampled rows")
+    # properties that hold for every row
+    assert np.abs(got.sum(axis=1) - 1).max() < 1e-5
+    assert got.min() >= 0 and not np.isnan(got).any()
+
+
+def test_full_size_attention_sampled_batches():
+    announce("full cfg3")
+    cfg = BY_NAME["causal_attention"]
+    ops, ins = cfg.build("full")
+    (got,) = run_gpu(ops, ins)
+    idx = _sample_rows(512, 24)
+    (want,) = interp.run(graphs.causal_attention(len(idx), 64, 64), [a[idx] for a in ins])
+    assert_close(got[idx], want, 2e-2, "cfg3 full sampled batches")
+    assert np.allclose(got[:, 0, :], ins[2][:, 0, :], atol=1e-3)   # first query row sees only V[0]
+    assert not np.isnan(got).any()
+
+
+def test_full_size_bias_gelu_ln_sampled_rows():
+    announce("full cfg4")
+    cfg = BY_NAME["bias_gelu_residual_layernorm"]
+    ops, ins = cfg.build("full")
+    (got,) = run_gpu(ops, ins)
+    idx = _sample_rows(ins[0].shape[0], 128)
+    sub = graphs.bias_gelu_residual_layernorm(len(idx), 1024)
+    (want,) = interp.run(sub, [ins[0][idx], ins[1], ins[2][idx], ins[3], ins[4]])
+    assert_close(got[idx], want, 2e-2, "cfg4 full sampled rows")
+    assert not np.isnan(got).any()
+
+
+def test_full_size_layernorm_bwd():
+    announce("full cfg5")
+    cfg = BY_NAME["layernorm_bwd"]
+    ops, ins = cfg.build("full")
+    dx, dgamma, dbeta = run_gpu(ops, ins)
+    want_dx, want_dgamma, want_dbeta = interp.run(ops, ins)
+    assert_close(dgamma, want_dgamma, 1e-5, "cfg5 full dgamma")
+    assert_close(dbeta, want_dbeta, 1e-5, "cfg5 full dbeta")
+    assert_close(dx, want_dx, 1e-5, "cfg5 full dx")
+
+
+# ---------------------------------------------------------------- edge cases and error paths
+
+def test_empty_inputs_launch_nothing_and_succeed():
+    announce("empty inputs")
+    for ops, ins in [(graphs.layernorm_fwd(0, 768), inputs.layernorm_fwd(0, 768)),
+                     (graphs.causal_attention(0, 64, 64), inputs.causal_attention(0, 64, 64))]:
+        for mode in ("stitched", "per_op"):
+            out = run_gpu(ops, ins, mode)
+            assert out[0].size == 0
+
+
+def test_launch_rejects_bad_pointers_and_counts():
+    announce("launch argument errors")
+    ops, ins = graphs.layernorm_fwd(4, 768), inputs.layernorm_fwd(4, 768)
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    with Plan(ops) as plan:
+        with pytest.raises(FsError) as e:
+            plan.launch(dev_in[:2], dev_out)
+        assert e.value.status == binding.FS_ERR_INVALID
+        with pytest.raises(FsError) as e:
+            plan.launch([dev_in[0].data_ptr() + 4, dev_in[1], dev_in[2]], dev_out)
+        assert e.value.status == binding.FS_ERR_INVALID
+        with pytest.raises(FsError) as e:
+            plan.launch([0, dev_in[1], dev_in[2]], dev_out)
+        assert e.value.status == binding.FS_ERR_INVALID
+        plan.launch(dev_in, dev_out)      # the plan still works afterwards
+        torch.cuda.synchronize()
+    (want,) = interp.run(ops, ins)
+    assert_close(dev_out[0].double().cpu().numpy(), want, 1e-5, "after errors")
+
+
+def test_stream_copy_matches_source():
+    announce("stream copy")
+    src = torch.randint(0, 255, (3 * 1024 * 1024 + 16,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    binding.fs_stream_copy(dst, src, src.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+
+
+def test_launch_on_a_side_stream():
+    announce("side stream")
+    ops, ins = graphs.layernorm_fwd(64, 768), inputs.layernorm_fwd(64, 768)
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with Plan(ops) as plan:
+        plan.launch(dev_in, dev_out, stream=s.cuda_stream)
+        s.synchronize()
+    (want,) = interp.run(ops, ins)
+    assert_close(dev_out[0].double().cpu().numpy(), want, 1e-5, "side stream")
