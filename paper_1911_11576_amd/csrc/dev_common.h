@@ -12,10 +12,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// Bit reinterpretation through a by-value parameter.  (Applying __builtin_bit_cast
+// directly to a vector element expression such as t[i] reads element 0 for every i.)
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
 struct bf16_t { uint16_t bits; };   // storage-only tags: all arithmetic is fp32
 struct f16_t { uint16_t bits; };
 
-__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return as_f32(b << 16); }
 __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);   // round to nearest even
 }
@@ -36,7 +41,7 @@ template <> struct Vec<float> {
   }
   static __device__ __forceinline__ void unpack(u32x4 t, float (&o)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = __builtin_bit_cast(float, t[i]);
+    for (int i = 0; i < 4; ++i) o[i] = as_f32(t[i]);
   }
   static __device__ __forceinline__ void load(const float* p, float (&o)[4]) { unpack(load_raw(p), o); }
   static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
@@ -55,8 +60,8 @@ template <> struct Vec<bf16_t> {
   static __device__ __forceinline__ void unpack(u32x4 t, float (&o)[8]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      o[2 * i] = __builtin_bit_cast(float, t[i] << 16);
-      o[2 * i + 1] = __builtin_bit_cast(float, t[i] & 0xFFFF0000u);
+      o[2 * i] = as_f32(t[i] << 16);
+      o[2 * i + 1] = as_f32(t[i] & 0xFFFF0000u);
     }
   }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&o)[8]) { unpack(load_raw(p), o); }
@@ -114,12 +119,12 @@ template <class Op, int L> __device__ __forceinline__ float group_allreduce(floa
   if (L >= 32) {
     uint32_t u = __builtin_bit_cast(uint32_t, v);
     auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    v = Op::apply(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    v = Op::apply(as_f32(r[0]), as_f32(r[1]));
   }
   if (L >= 64) {
     uint32_t u = __builtin_bit_cast(uint32_t, v);
     auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    v = Op::apply(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+    v = Op::apply(as_f32(r[0]), as_f32(r[1]));
   }
   return v;
 }
