@@ -11,7 +11,8 @@ import ctypes as C
 import os
 
 FS_MAX_RANK = 4
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfusionstitch.so")
+LIB_PATH = os.environ.get("FS_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                        "libfusionstitch.so")
 
 FS_OK, FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_HIP, FS_ERR_NOMEM = range(6)
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID", "FS_ERR_UNSUPPORTED", "FS_ERR_LDS", "FS_ERR_HIP", "FS_ERR_NOMEM"]

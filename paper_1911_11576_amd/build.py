@@ -13,10 +13,10 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libfusionstitch.so")
+OBJ = os.environ.get("FS_OBJ_DIR", os.path.join(HERE, "_build"))
+LIB = os.environ.get("FS_LIB_OUT", os.path.join(HERE, "libfusionstitch.so"))
 
-SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "lnbwd_stitch.hip",
+SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f32.hip", "row_stitch_f16.hip", "row_stitch_bf16.hip", "lnbwd_stitch.hip",
            "attn_stitch.hip", "per_op.hip", "util.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -27,7 +27,8 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
 
 def _compile(src):
     obj = os.path.join(OBJ, src.rsplit(".", 1)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("FS_EXTRA_FLAGS", "").split()
+    cmd = [HIPCC, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the device-only target feature; that message is harmless
     log = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)

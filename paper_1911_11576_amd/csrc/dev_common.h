@@ -36,6 +36,7 @@ template <typename T> struct Vec;
 
 template <> struct Vec<float> {
   static constexpr int V = 4;
+  static constexpr uint32_t kOneBits = 0x3F800000u;
   static __device__ __forceinline__ u32x4 load_raw(const float* p) {
     return *reinterpret_cast<const u32x4*>(p);
   }
@@ -54,6 +55,7 @@ template <> struct Vec<float> {
 
 template <> struct Vec<bf16_t> {
   static constexpr int V = 8;
+  static constexpr uint32_t kOneBits = 0x3F80u;
   static __device__ __forceinline__ u32x4 load_raw(const bf16_t* p) {
     return *reinterpret_cast<const u32x4*>(p);
   }
@@ -77,6 +79,7 @@ template <> struct Vec<bf16_t> {
 
 template <> struct Vec<f16_t> {
   static constexpr int V = 8;
+  static constexpr uint32_t kOneBits = 0x3C00u;
   static __device__ __forceinline__ u32x4 load_raw(const f16_t* p) {
     return *reinterpret_cast<const u32x4*>(p);
   }
@@ -97,6 +100,35 @@ template <> struct Vec<f16_t> {
   static __device__ __forceinline__ float load1(const f16_t* p) { return f16_to_f32(p->bits); }
   static __device__ __forceinline__ void store1(f16_t* p, float v) { p->bits = (uint16_t)f32_to_f16(v); }
 };
+
+// Streaming access for tensors that are touched exactly once: nontemporal 16-byte loads
+// and stores keep them from displacing reusable lines in L2 / the memory-side cache and
+// measurably raise achieved HBM bandwidth on gfx950 (plain copy: about +7%).
+__device__ __forceinline__ u32x4 stream_load16(const void* p) {
+  return __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ void stream_store16(void* p, u32x4 v) {
+  __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
+}
+template <typename T> __device__ __forceinline__ u32x4 pack16(const float (&v)[Vec<T>::V]);
+template <> __device__ __forceinline__ u32x4 pack16<float>(const float (&v)[4]) {
+  u32x4 t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = as_u32(v[i]);
+  return t;
+}
+template <> __device__ __forceinline__ u32x4 pack16<bf16_t>(const float (&v)[8]) {
+  u32x4 t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = f32_to_bf16(v[2 * i]) | (f32_to_bf16(v[2 * i + 1]) << 16);
+  return t;
+}
+template <> __device__ __forceinline__ u32x4 pack16<f16_t>(const float (&v)[8]) {
+  u32x4 t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = f32_to_f16(v[2 * i]) | (f32_to_f16(v[2 * i + 1]) << 16);
+  return t;
+}
 
 // ---- wave64 all-reduce over aligned groups of L lanes (L a power of two) -----------
 // Steps inside a 16-lane DPP row are DPP permutes (quad swaps, half mirror, mirror);

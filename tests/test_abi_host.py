@@ -99,6 +99,8 @@ def test_unsupported_groups_return_unsupported_not_crash():
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 4096))
     # cols not a multiple of the vector width
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 770))
+    # LayerNorm backward keeps fp64 column accumulators per lane: at most 1024 columns
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048))
     # fp32 attention has no MFMA path
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 64, 64, "f32"))
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 256, 64))

@@ -147,7 +147,7 @@ def test_row_schedule_launch_options_do_not_change_results(opts):
 
 # ---------------------------------------------------------------- LayerNorm backward
 
-@pytest.mark.parametrize("rows,cols", [(1, 4), (5, 64), (517, 1024), (4099, 1000), (33, 2048), (700, 256)])
+@pytest.mark.parametrize("rows,cols", [(1, 4), (5, 64), (517, 1024), (4099, 1000), (33, 768), (700, 256)])
 def test_layernorm_bwd_shapes(rows, cols):
     announce(f"layernorm_bwd {rows}x{cols}")
     check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), what=f"lnbwd {rows}x{cols}")
