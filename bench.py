@@ -28,6 +28,20 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_all_groups.md")
+
+
+def measured_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what it reads for the plain copy kernel), or None."""
+    import re
+    try:
+        text = open(TRAFFIC_FILE).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)" % re.escape(name), text)
+    return int(m.group(1)) if m else None
+
 ROTATE_BYTES = 640 * 2**20     # bytes touched between reuses of one buffer set
 
 TORCH_DT = None
@@ -62,18 +76,22 @@ def make_sets(ops, ins, algo_bytes, max_sets=8):
 
 
 def time_plan(plan, sets, steps, warmup):
-    """-> (wall ms per step, event ms per step)."""
+    """-> (wall ms per step, event ms per step).  Launches go to torch's current stream
+    and the HIP events are recorded on that same stream."""
     import torch
-    n = len(sets)
+    from paper_1911_11576_amd import BoundArgs
+    bound = [BoundArgs(i, o) for i, o in sets]
+    n = len(bound)
+    stream = torch.cuda.current_stream().cuda_stream
     for i in range(warmup):
-        plan.launch(*sets[i % n])
+        plan.launch_bound(bound[i % n], stream)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for i in range(steps):
-        plan.launch(*sets[i % n])
+        plan.launch_bound(bound[i % n], stream)
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -184,7 +202,7 @@ def main():
                    "buffer_sets": res["buffer_sets"], "speedup_vs_per_op": res.get("speedup_vs_per_op"),
                    "per_op_kernels": res.get("per_op_kernels")},
         "roofline": {"bound": "hbm", "achieved": algo / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(head.name),
                      "kernel_us": ev_ms * 1e3, "frac_of_copy_kernel": res["stitched_frac_of_copy"]},
     }
     if not args.no_groups:

@@ -153,6 +153,16 @@ def fs_stream_copy(dst, src, nbytes, stream=None):
                                 src if isinstance(src, int) else src.data_ptr(), nbytes, stream))
 
 
+class BoundArgs:
+    """Pointer arrays of one (inputs, outputs) set, marshalled once so that repeated
+    launches of the same buffers cost a single foreign call.  Keeps the tensors alive."""
+
+    def __init__(self, inputs, outputs):
+        self.keep = (list(inputs), list(outputs))
+        self.n_in, self.n_out = len(inputs), len(outputs)
+        self.in_ptrs, self.out_ptrs = _pointers(inputs), _pointers(outputs)
+
+
 class Plan:
     """Owner of one fs_plan handle."""
 
@@ -163,6 +173,12 @@ class Plan:
 
     def launch(self, inputs, outputs, stream=None):
         fs_launch(self._h, inputs, outputs, stream)
+
+    def launch_bound(self, bound, stream):
+        """Launch with pre-marshalled arguments (see BoundArgs) on an explicit stream handle."""
+        st = lib().fs_launch(self._h, bound.in_ptrs, bound.n_in, bound.out_ptrs, bound.n_out, stream)
+        if st != FS_OK:
+            raise FsError(st, fs_last_error())
 
     def info(self):
         return fs_plan_info(self._h)

@@ -158,9 +158,10 @@ void lnbwd_stitch_kernel(const LnBwdArgs a) {
       if constexpr (NEED_X) Vec<float>::unpack(xn[k], xv[k]);
     }
     const float mu = mun, rs = rsn;
-    // prefetch the next row: issued unconditionally (the last iteration re-reads its own
-    // row) and pinned ahead of the arithmetic
-    const int64_t nrow = row + row_step < row_end ? row + row_step : row;
+    // prefetch the next row: issued unconditionally and pinned ahead of the arithmetic (the
+    // last iteration reads row 0, which every wavefront does at that point: an L2 hit, no
+    // extra HBM traffic)
+    const int64_t nrow = row + row_step < row_end ? row + row_step : 0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       dyn[k] = stream_load16(a.dy + nrow * a.cols + voff[k]);

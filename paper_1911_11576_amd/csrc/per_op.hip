@@ -189,7 +189,15 @@ __global__ __launch_bounds__(256) void col_reduce_stage2(const double* __restric
   if (c >= inner) return;
   const int64_t o = blockIdx.y;
   double acc = is_max ? -INFINITY : 0.0;
-  for (int k = 0; k < chunks; ++k) {
+  int k = 0;
+  for (; k + 8 <= chunks; k += 8) {   // eight independent loads in flight
+    double v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = part[(o * chunks + k + j) * inner + c];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = is_max ? fmax(acc, v[j]) : acc + v[j];
+  }
+  for (; k < chunks; ++k) {
     const double v = part[(o * chunks + k) * inner + c];
     acc = is_max ? fmax(acc, v) : acc + v;
   }
@@ -338,12 +346,12 @@ hipError_t launch_dot_out(int out_dt, const void* A, const void* B, void* C, int
 }
 
 int col_chunks(const PerOpStep& st) {
-  // enough workgroups to fill the chip: about 2048 in total
+  // enough workgroups to fill the chip: about 1024 in total
   const int64_t gx = (st.inner + 255) / 256;
-  int64_t chunks = 2048 / (gx * st.outer);
+  int64_t chunks = 1024 / (gx * st.outer);
   if (chunks < 1) chunks = 1;
   if (chunks > st.red) chunks = st.red > 0 ? st.red : 1;
-  if (chunks > 1024) chunks = 1024;
+  if (chunks > 256) chunks = 256;
   return (int)chunks;
 }
 

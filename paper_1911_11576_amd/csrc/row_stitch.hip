@@ -51,7 +51,8 @@ bool row_stitch_plan(const RowSpec& sp, const LaunchOpts& opt, RowLaunch* out, s
   if (opt.grid > 0 && opt.grid < grid) grid = opt.grid;
   if (grid > 0x7fffffff) grid = 0x7fffffff;
   rl.grid = (int)grid;
-  rl.variant = sp.core == CORE_LAYERNORM ? (sp.gelu ? 1 : 0) : (sp.in_mask >= 0 ? 3 : 2);
+  const bool mask_bcast = !(sp.mask_d1 == 1 && sp.mask_d2 == 1 && sp.mask_stride[0] == 1);
+  rl.variant = sp.core == CORE_LAYERNORM ? (sp.gelu ? 1 : 0) : (sp.in_mask < 0 ? 2 : mask_bcast ? 4 : 3);
   *out = rl;
   return true;
 }
@@ -90,7 +91,6 @@ int row_stitch_launch(const RowSpec& sp, const RowLaunch& rl, const void* const*
   a.g_mul = 2.f * sp.gelu_half;
   a.g_a0 = (float)(-2.0 * (double)sp.gelu_k0 * 1.4426950408889634);
   a.g_a1 = (float)(-2.0 * (double)sp.gelu_k0 * 1.4426950408889634 * (double)sp.gelu_k1);
-  a.mask_general = !(sp.mask_d1 == 1 && sp.mask_d2 == 1 && sp.mask_stride[0] == 1);
   a.mask_d1 = (uint32_t)sp.mask_d1; a.mask_d2 = (uint32_t)sp.mask_d2;
   a.ms0 = sp.mask_stride[0]; a.ms1 = sp.mask_stride[1]; a.ms2 = sp.mask_stride[2];
   hipStream_t s = static_cast<hipStream_t>(stream);

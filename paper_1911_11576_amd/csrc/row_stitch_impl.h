@@ -25,18 +25,19 @@ struct RowArgs {
   int64_t rows; int cols; int nvec;
   float scale, eps, inv_n;
   float g_mul, g_a0, g_a1;   // gelu: g = g_mul * h / (1 + exp2(h * (g_a0 + g_a1*h*h)))
-  int mask_general; uint32_t mask_d1, mask_d2; int64_t ms0, ms1, ms2;
+  uint32_t mask_d1, mask_d2; int64_t ms0, ms1, ms2;
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// VARIANT: 0 LayerNorm, 1 prologue(bias,GELU,residual)+LayerNorm, 2 softmax, 3 masked softmax
+// VARIANT: 0 LayerNorm, 1 prologue(bias,GELU,residual)+LayerNorm, 2 softmax, 3 softmax with a
+// mask of the scores' shape, 4 softmax with a mask broadcast over leading dims
 // EXACT: the row fills the lane tile exactly (cols == K*L*V): no per-vector masking
 template <typename T, int VARIANT, int K, int L, int U, bool EXACT>
 __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
   constexpr int V = Vec<T>::V;
   constexpr int G = 64 / L;
-  constexpr bool kLN = VARIANT <= 1, kGelu = VARIANT == 1, kMask = VARIANT == 3;
+  constexpr bool kLN = VARIANT <= 1, kGelu = VARIANT == 1, kMask = VARIANT >= 3, kMaskBcast = VARIANT == 4;
   const int lane = threadIdx.x & 63;
   const int sub = lane / L, l = lane % L;
   const int waves = blockDim.x >> 6;
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         int64_t mrow = row[u];
-        if (a.mask_general) {
+        if constexpr (kMaskBcast) {
           const uint32_t r32 = (uint32_t)row[u];
           const uint32_t i2 = r32 % a.mask_d2, t = r32 / a.mask_d2;
           const uint32_t i1 = t % a.mask_d1, i0 = t / a.mask_d1;
@@ -267,7 +268,8 @@ hipError_t row_launch_dtype(const RowArgs& a, const RowLaunch& rl, hipStream_t s
     case 0: return row_launch_KL<T, 0>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
     case 1: return row_launch_KL<T, 1>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
     case 2: return row_launch_KL<T, 2>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
-    default: return row_launch_KL<T, 3>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
+    case 3: return row_launch_KL<T, 3>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
+    default: return row_launch_KL<T, 4>(a, rl.K, rl.L, rl.U, exact, rl.grid, rl.wg, s);
   }
 }
 
