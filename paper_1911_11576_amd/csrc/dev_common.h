@@ -11,6 +11,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 // Bit reinterpretation through a by-value parameter.  (Applying __builtin_bit_cast
 // directly to a vector element expression such as t[i] reads element 0 for every i.)
@@ -29,6 +32,16 @@ __device__ __forceinline__ float f16_to_f32(uint32_t b) {
 }
 __device__ __forceinline__ uint32_t f32_to_f16(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+// two fp32 -> one packed 32-bit word (lo in bits 0..15), round to nearest even: a single
+// v_cvt_pk_{bf16,f16}_f32
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ uint32_t pack2_f16(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
 // One 16-byte vector of T <-> V fp32 values.
@@ -70,7 +83,7 @@ template <> struct Vec<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
     u32x4 t;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t[i] = f32_to_bf16(v[2 * i]) | (f32_to_bf16(v[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) t[i] = pack2_bf16(v[2 * i], v[2 * i + 1]);
     *reinterpret_cast<u32x4*>(p) = t;
   }
   static __device__ __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(p->bits); }
@@ -94,7 +107,7 @@ template <> struct Vec<f16_t> {
   static __device__ __forceinline__ void store(f16_t* p, const float (&v)[8]) {
     u32x4 t;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t[i] = f32_to_f16(v[2 * i]) | (f32_to_f16(v[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) t[i] = pack2_f16(v[2 * i], v[2 * i + 1]);
     *reinterpret_cast<u32x4*>(p) = t;
   }
   static __device__ __forceinline__ float load1(const f16_t* p) { return f16_to_f32(p->bits); }
@@ -120,13 +133,13 @@ template <> __device__ __forceinline__ u32x4 pack16<float>(const float (&v)[4]) 
 template <> __device__ __forceinline__ u32x4 pack16<bf16_t>(const float (&v)[8]) {
   u32x4 t;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) t[i] = f32_to_bf16(v[2 * i]) | (f32_to_bf16(v[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) t[i] = pack2_bf16(v[2 * i], v[2 * i + 1]);
   return t;
 }
 template <> __device__ __forceinline__ u32x4 pack16<f16_t>(const float (&v)[8]) {
   u32x4 t;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) t[i] = f32_to_f16(v[2 * i]) | (f32_to_f16(v[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) t[i] = pack2_f16(v[2 * i], v[2 * i + 1]);
   return t;
 }
 

@@ -36,10 +36,10 @@ bool row_stitch_plan(const RowSpec& sp, const LaunchOpts& opt, RowLaunch* out, s
   rl.L = pick_L((int)nvec);
   rl.wg = opt.wg_size ? opt.wg_size : 256;
   if (rl.wg < 64 || rl.wg > 512 || rl.wg % 64) { *err = "row schedule: wg_size must be a multiple of 64 in [64,512]"; return false; }
-  // default rows in flight per wavefront: about 64 bytes per lane per tensor (measured: more
-  // only costs registers once a row group already spans a whole wavefront)
+  // default row groups in flight per wavefront: two while a lane holds at most 32 bytes of
+  // a row, else one (measured: more only costs registers)
   const int kv = rl.K * V;
-  int U = opt.rows_per_wave ? opt.rows_per_wave : (kv <= 4 ? 4 : kv <= 8 ? 2 : 1);
+  int U = opt.rows_per_wave ? opt.rows_per_wave : (kv <= 8 ? 2 : 1);
   if (U < 1 || U > 8) { *err = "rows_per_wave out of range [1,8]"; return false; }
   const int mu = max_U(rl.K, V);
   rl.U = U >= 4 && mu >= 4 ? 4 : U >= 2 && mu >= 2 ? 2 : 1;
@@ -91,7 +91,7 @@ int row_stitch_launch(const RowSpec& sp, const RowLaunch& rl, const void* const*
   a.g_mul = 2.f * sp.gelu_half;
   a.g_a0 = (float)(-2.0 * (double)sp.gelu_k0 * 1.4426950408889634);
   a.g_a1 = (float)(-2.0 * (double)sp.gelu_k0 * 1.4426950408889634 * (double)sp.gelu_k1);
-  a.mask_d1 = (uint32_t)sp.mask_d1; a.mask_d2 = (uint32_t)sp.mask_d2;
+  a.mask_d1 = FastDiv::make((uint32_t)sp.mask_d1); a.mask_d2 = FastDiv::make((uint32_t)sp.mask_d2);
   a.ms0 = sp.mask_stride[0]; a.ms1 = sp.mask_stride[1]; a.ms2 = sp.mask_stride[2];
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;

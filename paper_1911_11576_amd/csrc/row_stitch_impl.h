@@ -19,13 +19,34 @@
 
 namespace fs {
 
+// Unsigned 32-bit division by a launch-time constant as multiply-high, subtract, shifts
+// (Granlund & Montgomery's round-up method): q = (t + ((n - t) >> sh1)) >> sh2 with
+// t = mulhi(m, n).  Exact for every n < 2^32.
+struct FastDiv {
+  uint32_t d = 1, m = 1, sh1 = 0, sh2 = 0;
+  static FastDiv make(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while (l < 32 && ((uint64_t)1 << l) < d) ++l;            // ceil(log2 d)
+    f.m = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l > 0 ? l - 1 : 0;
+    return f;
+  }
+  __device__ __forceinline__ uint32_t div(uint32_t n) const {
+    const uint32_t t = __umulhi(m, n);
+    return (t + ((n - t) >> sh1)) >> sh2;
+  }
+};
+
 struct RowArgs {
   const void* x; const void* res; const void* bias; const void* gamma; const void* beta;
   const void* mask; void* y;
   int64_t rows; int cols; int nvec;
   float scale, eps, inv_n;
   float g_mul, g_a0, g_a1;   // gelu: g = g_mul * h / (1 + exp2(h * (g_a0 + g_a1*h*h)))
-  uint32_t mask_d1, mask_d2; int64_t ms0, ms1, ms2;
+  FastDiv mask_d1, mask_d2; int64_t ms0, ms1, ms2;
 };
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -53,54 +74,81 @@ __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
     voff[k] = (vld[k] ? vi : 0) * V;   // masked-off lanes re-read vector 0: always in bounds
   }
 
-  // per-column operands: read once per wavefront (cached loads) and kept, still packed in
-  // their storage dtype, in registers for all its rows; an absent operand becomes its
-  // neutral element so the per-element code has no conditionals
-  u32x4 gam[K], bet[K], bia[K];
-  if constexpr (kLN) {
-    constexpr uint32_t one = sizeof(T) == 4 ? 0x3F800000u : (Vec<T>::kOneBits | (Vec<T>::kOneBits << 16));
+  // per-column operands (cached loads, kept packed in their storage dtype); an absent
+  // operand becomes its neutral element so the per-element code has no conditionals.
+  // The bias is needed first and is read up front; gamma and beta are read inside the
+  // loop right where the epilogue needs them, which keeps them out of the register budget
+  // while the row is being reduced (a one-shot grid visits one row group per wavefront, so
+  // nothing is read twice; a persistent grid re-reads them from L1).
+  constexpr uint32_t kOne = sizeof(T) == 4 ? 0x3F800000u : (Vec<T>::kOneBits | (Vec<T>::kOneBits << 16));
+  u32x4 bia[K];
+  if constexpr (kGelu) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      gam[k] = u32x4{one, one, one, one};
-      bet[k] = u32x4{0u, 0u, 0u, 0u};
       bia[k] = u32x4{0u, 0u, 0u, 0u};
-      if (a.gamma) gam[k] = Vec<T>::load_raw(static_cast<const T*>(a.gamma) + voff[k]);
-      if (a.beta) bet[k] = Vec<T>::load_raw(static_cast<const T*>(a.beta) + voff[k]);
-      if constexpr (kGelu) if (a.bias) bia[k] = Vec<T>::load_raw(static_cast<const T*>(a.bias) + voff[k]);
+      if (a.bias) bia[k] = Vec<T>::load_raw(static_cast<const T*>(a.bias) + voff[k]);
     }
   }
 
   const int64_t n_groups = (a.rows + G - 1) / G;
   const int64_t n_iters = (n_groups + U - 1) / U;
-  for (int64_t it = (int64_t)blockIdx.x * waves + (threadIdx.x >> 6); it < n_iters;
-       it += (int64_t)gridDim.x * waves) {
-    float v[U][K][V];
-    int64_t row[U];
-    bool rok[U];
-    u32x4 raw[U][K];
+  const int64_t first = (int64_t)blockIdx.x * waves + (threadIdx.x >> 6);
+  const int64_t stride = (int64_t)gridDim.x * waves;
+
+  // all HBM reads of one iteration: the row groups of x and of the second streamed operand
+  // (`aux`: the residual, or the mask)
+  auto load_groups = [&](int64_t it, u32x4 (&raw)[U][K], u32x4 (&aux)[U][K], int64_t (&row)[U], bool (&rok)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = (it * U + u) * G + sub;
       rok[u] = r < a.rows;
       row[u] = rok[u] ? r : a.rows - 1;
 #pragma unroll
-      for (int k = 0; k < K; ++k) raw[u][k] = stream_load16(x + row[u] * a.cols + voff[k]);
+      for (int k = 0; k < K; ++k) {
+        raw[u][k] = stream_load16(x + row[u] * a.cols + voff[k]);
+        aux[u][k] = u32x4{0u, 0u, 0u, 0u};
+      }
     }
-
-    // ---- thread-composed prologue ---------------------------------------------------
     if constexpr (kGelu) {
-      u32x4 rs[U][K];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int k = 0; k < K; ++k) rs[u][k] = u32x4{0u, 0u, 0u, 0u};
       if (a.res) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
           for (int k = 0; k < K; ++k)
-            rs[u][k] = stream_load16(static_cast<const T*>(a.res) + row[u] * a.cols + voff[k]);
+            aux[u][k] = stream_load16(static_cast<const T*>(a.res) + row[u] * a.cols + voff[k]);
       }
+    }
+    if constexpr (kMask) {
+      const T* __restrict__ mk = static_cast<const T*>(a.mask);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int64_t mrow = row[u];
+        if constexpr (kMaskBcast) {
+          const uint32_t r32 = (uint32_t)row[u];
+          const uint32_t t = a.mask_d2.div(r32), i2 = r32 - t * a.mask_d2.d;
+          const uint32_t i0 = a.mask_d1.div(t), i1 = t - i0 * a.mask_d1.d;
+          mrow = i0 * a.ms0 + i1 * a.ms1 + i2 * a.ms2;
+        }
+        // a broadcast mask row is shared by many score rows: cached load; a full mask is
+        // touched once: streaming load
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+          aux[u][k] = kMaskBcast ? Vec<T>::load_raw(mk + mrow * a.cols + voff[k]) : stream_load16(mk + mrow * a.cols + voff[k]);
+      }
+    }
+  };
+
+  // (Register double buffering of the next iteration's loads on a persistent grid was tried
+  // and measured 10-30% slower than this one-shot form on MI355X.)
+  for (int64_t it = first; it < n_iters; it += stride) {
+    float v[U][K][V];
+    int64_t row[U];
+    bool rok[U];
+    u32x4 raw[U][K], aux[U][K];
+    load_groups(it, raw, aux, row, rok);
+
+    // ---- thread-composed prologue ---------------------------------------------------
+    if constexpr (kGelu) {
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         float b[V];
@@ -109,7 +157,7 @@ __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
         for (int u = 0; u < U; ++u) {
           float r[V];
           Vec<T>::unpack(raw[u][k], v[u][k]);
-          Vec<T>::unpack(rs[u][k], r);
+          Vec<T>::unpack(aux[u][k], r);
 #pragma unroll
           for (int j = 0; j < V; ++j) {
             const float h = v[u][k][j] + b[j];
@@ -121,27 +169,13 @@ __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
         }
       }
     } else if constexpr (kMask) {
-      u32x4 m[U][K];
-      const T* __restrict__ mk = static_cast<const T*>(a.mask);
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int64_t mrow = row[u];
-        if constexpr (kMaskBcast) {
-          const uint32_t r32 = (uint32_t)row[u];
-          const uint32_t i2 = r32 % a.mask_d2, t = r32 / a.mask_d2;
-          const uint32_t i1 = t % a.mask_d1, i0 = t / a.mask_d1;
-          mrow = i0 * a.ms0 + i1 * a.ms1 + i2 * a.ms2;
-        }
-#pragma unroll
-        for (int k = 0; k < K; ++k) m[u][k] = stream_load16(mk + mrow * a.cols + voff[k]);
-      }
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int k = 0; k < K; ++k) {
           float mm[V];
           Vec<T>::unpack(raw[u][k], v[u][k]);
-          Vec<T>::unpack(m[u][k], mm);
+          Vec<T>::unpack(aux[u][k], mm);
 #pragma unroll
           for (int j = 0; j < V; ++j) v[u][k][j] = v[u][k][j] * a.scale + mm[j];
         }
@@ -176,6 +210,14 @@ __global__ __launch_bounds__(512) void row_stitch_kernel(const RowArgs a) {
             v[u][k][j] -= mean;
             q += vld[k] ? v[u][k][j] * v[u][k][j] : 0.f;
           }
+        u32x4 gam[K], bet[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          gam[k] = u32x4{kOne, kOne, kOne, kOne};
+          bet[k] = u32x4{0u, 0u, 0u, 0u};
+          if (a.gamma) gam[k] = Vec<T>::load_raw(static_cast<const T*>(a.gamma) + voff[k]);
+          if (a.beta) bet[k] = Vec<T>::load_raw(static_cast<const T*>(a.beta) + voff[k]);
+        }
         const float var = group_allreduce<SumOp, L>(q) * a.inv_n;
         const float rstd = 1.f / sqrtf(var + a.eps);
 #pragma unroll
