@@ -18,6 +18,8 @@ struct fs_plan {
   int schedule = FS_SCHED_PER_OP;
   fs::Match match;
   fs::RowLaunch row;
+  fs::RowBlockLaunch row_block;
+  bool use_row_block = false;
   fs::LnBwdLaunch lnbwd;
   fs::AttnLaunch attn;
   fs::PerOpPlan per_op;
@@ -75,13 +77,20 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
       p->moved_bytes = algo;
       switch (p->match.kind) {
         case fs::MATCH_ROW:
-          if (!fs::row_stitch_plan(p->match.row, lo, &p->row, &err)) {
-            const bool bad_opt = err.find("wg_size") != std::string::npos || err.find("rows_per_wave") != std::string::npos;
-            delete p;
-            return set_error(bad_opt ? FS_ERR_INVALID : FS_ERR_UNSUPPORTED, err);
-          }
           p->schedule = FS_SCHED_ROW;
-          p->description = fs::row_stitch_describe(p->match.row, p->row);
+          if (fs::row_stitch_plan(p->match.row, lo, &p->row, &err)) {
+            p->description = fs::row_stitch_describe(p->match.row, p->row);
+          } else if (err.find("wg_size") != std::string::npos || err.find("rows_per_wave") != std::string::npos) {
+            delete p;
+            return set_error(FS_ERR_INVALID, err);
+          } else {
+            // the row does not fit the register-resident form: block-composed form, row in LDS
+            int st = FS_OK;
+            if (!fs::row_block_plan(p->match.row, lo, &p->row_block, &st, &err)) { delete p; return set_error((fs_status)st, err); }
+            p->use_row_block = true;
+            p->lds_bytes = p->row_block.lds_bytes;
+            p->description = fs::row_block_describe(p->match.row, p->row_block);
+          }
           break;
         case fs::MATCH_LNBWD:
           if (!fs::lnbwd_stitch_plan(p->match.lnbwd, lo, &p->lnbwd, &err)) {
@@ -153,7 +162,10 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
     }
     int rc = 0;
     switch (p->schedule) {
-      case FS_SCHED_ROW: rc = fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err); break;
+      case FS_SCHED_ROW:
+        rc = p->use_row_block ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
+                              : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
+        break;
       case FS_SCHED_ROW_COL: rc = fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err); break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
       default: rc = fs::per_op_launch(g, p->per_op, inputs, outputs, p->workspace, hip_stream, &err); break;

@@ -12,6 +12,13 @@ std::string row_stitch_describe(const RowSpec&, const RowLaunch&);
 int row_stitch_launch(const RowSpec&, const RowLaunch&, const void* const* in, void* const* out,
                       void* stream, std::string* err);
 
+// Block-composed form of the row schedule for long or unaligned rows (row cached in LDS).
+struct RowBlockLaunch { int variant = 0, wg = 256, grid = 1; bool vector = true; int64_t lds_bytes = 0; };
+bool row_block_plan(const RowSpec&, const LaunchOpts&, RowBlockLaunch*, int* status, std::string* err);
+std::string row_block_describe(const RowSpec&, const RowBlockLaunch&);
+int row_block_launch(const RowSpec&, const RowBlockLaunch&, const void* const* in, void* const* out,
+                     void* stream, std::string* err);
+
 // LayerNorm backward: row path for dx packed with the column path for dgamma/dbeta.
 struct LnBwdLaunch { int K = 1, wg = 512, grid = 1, group = 1; int64_t lds_bytes = 0, workspace_bytes = 0; };
 bool lnbwd_stitch_plan(const LnBwdSpec&, const LaunchOpts&, LnBwdLaunch*, std::string* err);

@@ -72,10 +72,8 @@ std::string row_stitch_describe(const RowSpec& sp, const RowLaunch& rl) {
   return buf;
 }
 
-int row_stitch_launch(const RowSpec& sp, const RowLaunch& rl, const void* const* in, void* const* out,
-                      void* stream, std::string* err) {
-  if (sp.rows == 0 || sp.cols == 0) return 0;
-  RowArgs a{};
+void row_fill_args(const RowSpec& sp, const void* const* in, void* const* out, RowArgs* pa) {
+  RowArgs& a = *pa;
   a.x = in[sp.in_x];
   a.res = sp.in_res >= 0 ? in[sp.in_res] : nullptr;
   a.bias = sp.in_bias >= 0 ? in[sp.in_bias] : nullptr;
@@ -93,6 +91,13 @@ int row_stitch_launch(const RowSpec& sp, const RowLaunch& rl, const void* const*
   a.g_a1 = (float)(-2.0 * (double)sp.gelu_k0 * 1.4426950408889634 * (double)sp.gelu_k1);
   a.mask_d1 = FastDiv::make((uint32_t)sp.mask_d1); a.mask_d2 = FastDiv::make((uint32_t)sp.mask_d2);
   a.ms0 = sp.mask_stride[0]; a.ms1 = sp.mask_stride[1]; a.ms2 = sp.mask_stride[2];
+}
+
+int row_stitch_launch(const RowSpec& sp, const RowLaunch& rl, const void* const* in, void* const* out,
+                      void* stream, std::string* err) {
+  if (sp.rows == 0 || sp.cols == 0) return 0;
+  RowArgs a{};
+  row_fill_args(sp, in, out, &a);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   switch (sp.dtype) {

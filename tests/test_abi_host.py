@@ -96,10 +96,6 @@ def test_unsupported_groups_return_unsupported_not_crash():
     _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
     with Plan(g.ops, "per_op") as p:               # the per-op plan always exists
         assert p.info()["n_kernels"] == 2
-    # row too long for one wavefront's registers
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 4096))
-    # cols not a multiple of the vector width
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_fwd(4, 770))
     # LayerNorm backward keeps fp64 column accumulators per lane: at most 1024 columns
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048))
     # fp32 attention has no MFMA path
@@ -110,6 +106,22 @@ def test_unsupported_groups_return_unsupported_not_crash():
 def test_lds_volume_constraint():
     msg = _expect(binding.FS_ERR_LDS, graphs.causal_attention(2, 128, 128))
     assert "LDS" in msg
+    # a row longer than the LDS row cache of the block-composed row form
+    msg = _expect(binding.FS_ERR_LDS, graphs.layernorm_fwd(4, 50000))
+    assert "LDS" in msg
+
+
+def test_long_and_unaligned_rows_take_the_block_composed_form():
+    for ops in (graphs.layernorm_fwd(4, 4096), graphs.layernorm_fwd(4, 770),
+                graphs.scaled_masked_softmax((3, 94), 0.125, "full"),
+                graphs.bias_gelu_residual_layernorm(5, 8192, "bf16")):
+        with Plan(ops) as p:
+            info = p.info()
+            assert info["schedule"] == "row" and info["n_kernels"] == 1
+            assert info["lds_bytes"] > 0 and "CTA" in p.describe()
+    # rows that fit a wavefront's registers keep the register-resident form (no LDS)
+    with Plan(graphs.layernorm_fwd(4, 2048)) as p:
+        assert p.info()["lds_bytes"] == 0
 
 
 def test_invalid_op_lists():

@@ -128,6 +128,38 @@ def test_softmax_fully_masked_rows_and_large_values():
     check_against_oracle(ops, [s, m], what="softmax degenerate")
 
 
+# ---------------------------------------------------------------- row schedule, block-composed form
+
+@pytest.mark.parametrize("rows,cols", [(3, 770), (5, 4096), (2, 3001), (7, 10007), (2, 16384), (1, 40000), (9, 1), (4, 3)])
+def test_layernorm_long_or_unaligned_rows_f32(rows, cols):
+    announce(f"layernorm block form f32 {rows}x{cols}")
+    check_against_oracle(graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols), what=f"ln block {rows}x{cols}")
+
+
+@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 5, 4096), ("f16", 3, 3001), ("bf16", 2, 12), ("f16", 6, 8200)])
+def test_gelu_layernorm_long_or_unaligned_rows_16bit(dtype, rows, cols):
+    announce(f"bias+gelu+res+ln block form {dtype} {rows}x{cols}")
+    check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 block {dtype} {rows}x{cols}")
+
+
+@pytest.mark.parametrize("shape,mask", [((5, 94), "full"), ((3, 4100), "full"), ((6, 2049), "none"), ((2, 3, 94, 94), "key_padding"),
+                                        ((2, 2, 5, 4096), "key_padding"), ((4, 1), "full")])
+def test_softmax_long_or_unaligned_rows(shape, mask):
+    announce(f"softmax block form {shape} {mask}")
+    check_against_oracle(graphs.scaled_masked_softmax(shape, 0.125, mask),
+                         inputs.scaled_masked_softmax(shape, mask), what=f"softmax block {shape} {mask}")
+
+
+def test_block_form_launch_options():
+    announce("row block form options")
+    ops, ins = graphs.layernorm_fwd(300, 4096), inputs.layernorm_fwd(300, 4096)
+    ref = run_gpu(ops, ins)
+    for opts in (dict(wg_size=64), dict(wg_size=1024), dict(grid=7)):
+        got = run_gpu(ops, ins, **opts)
+        assert_close(got[0], ref[0], 1e-6, f"block form {opts}")
+
+
 # ---------------------------------------------------------------- launch parameters
 
 @pytest.mark.parametrize("opts", [dict(wg_size=64), dict(wg_size=512), dict(rows_per_wave=1), dict(rows_per_wave=2),
