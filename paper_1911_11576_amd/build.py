@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.environ.get("FS_OBJ_DIR", os.path.join(HERE, "_build"))
 LIB = os.environ.get("FS_LIB_OUT", os.path.join(HERE, "libfusionstitch.so"))
 
-SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f32.hip", "row_stitch_f16.hip", "row_stitch_bf16.hip", "row_block.hip", "lnbwd_stitch.hip",
+SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f32.hip", "row_stitch_f16.hip", "row_stitch_bf16.hip", "row_team.hip", "row_block.hip", "lnbwd_stitch.hip",
            "attn_stitch.hip", "per_op.hip", "util.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

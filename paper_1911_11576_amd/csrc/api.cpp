@@ -18,8 +18,9 @@ struct fs_plan {
   int schedule = FS_SCHED_PER_OP;
   fs::Match match;
   fs::RowLaunch row;
+  fs::RowTeamLaunch row_team;
   fs::RowBlockLaunch row_block;
-  bool use_row_block = false;
+  int row_form = 0;   // 0 one wavefront per row group, 1 wavefront team, 2 row cached in LDS
   fs::LnBwdLaunch lnbwd;
   fs::AttnLaunch attn;
   fs::PerOpPlan per_op;
@@ -83,11 +84,17 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           } else if (err.find("wg_size") != std::string::npos || err.find("rows_per_wave") != std::string::npos) {
             delete p;
             return set_error(FS_ERR_INVALID, err);
+          } else if (fs::row_team_plan(p->match.row, lo, &p->row_team, &err)) {
+            // the row does not fit one wavefront: a team of wavefronts holds it in registers
+            p->row_form = 1;
+            p->lds_bytes = 2 * 16 * 4;
+            p->description = fs::row_team_describe(p->match.row, p->row_team);
           } else {
-            // the row does not fit the register-resident form: block-composed form, row in LDS
+            // unaligned or very long row: block-composed form, row cached in LDS
             int st = FS_OK;
-            if (!fs::row_block_plan(p->match.row, lo, &p->row_block, &st, &err)) { delete p; return set_error((fs_status)st, err); }
-            p->use_row_block = true;
+            fs::LaunchOpts lb = lo;
+            if (!fs::row_block_plan(p->match.row, lb, &p->row_block, &st, &err)) { delete p; return set_error((fs_status)st, err); }
+            p->row_form = 2;
             p->lds_bytes = p->row_block.lds_bytes;
             p->description = fs::row_block_describe(p->match.row, p->row_block);
           }
@@ -163,8 +170,9 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
     int rc = 0;
     switch (p->schedule) {
       case FS_SCHED_ROW:
-        rc = p->use_row_block ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
-                              : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
+        rc = p->row_form == 2   ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
+             : p->row_form == 1 ? fs::row_team_launch(p->match.row, p->row_team, inputs, outputs, hip_stream, &err)
+                                : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
         break;
       case FS_SCHED_ROW_COL: rc = fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err); break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;

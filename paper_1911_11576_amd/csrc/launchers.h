@@ -12,6 +12,14 @@ std::string row_stitch_describe(const RowSpec&, const RowLaunch&);
 int row_stitch_launch(const RowSpec&, const RowLaunch&, const void* const* in, void* const* out,
                       void* stream, std::string* err);
 
+// Wavefront-team form of the row schedule: a register-resident row spread over the
+// wavefronts of one workgroup (2049..32768 elements).
+struct RowTeamLaunch { int variant = 0, K = 1, wg = 128, grid = 1; };
+bool row_team_plan(const RowSpec&, const LaunchOpts&, RowTeamLaunch*, std::string* err);
+std::string row_team_describe(const RowSpec&, const RowTeamLaunch&);
+int row_team_launch(const RowSpec&, const RowTeamLaunch&, const void* const* in, void* const* out,
+                    void* stream, std::string* err);
+
 // Block-composed form of the row schedule for long or unaligned rows (row cached in LDS).
 struct RowBlockLaunch { int variant = 0, wg = 256, grid = 1; bool vector = true; int64_t lds_bytes = 0; };
 bool row_block_plan(const RowSpec&, const LaunchOpts&, RowBlockLaunch*, int* status, std::string* err);

@@ -151,6 +151,35 @@ def test_softmax_long_or_unaligned_rows(shape, mask):
                          inputs.scaled_masked_softmax(shape, mask), what=f"softmax block {shape} {mask}")
 
 
+@pytest.mark.parametrize("rows,cols", [(3, 2052), (5, 5000), (4, 8192), (2, 32768), (3, 20480)])
+def test_layernorm_team_form_f32(rows, cols):
+    announce(f"layernorm team form f32 {rows}x{cols}")
+    check_against_oracle(graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols), what=f"ln team {rows}x{cols}")
+
+
+@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 3, 2056), ("f16", 5, 4096), ("bf16", 2, 32768), ("f16", 3, 12288)])
+def test_gelu_layernorm_team_form_16bit(dtype, rows, cols):
+    announce(f"bias+gelu+res+ln team form {dtype} {rows}x{cols}")
+    check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 team {dtype} {rows}x{cols}")
+
+
+@pytest.mark.parametrize("shape,mask", [((5, 4096), "full"), ((2, 2, 3, 8192), "key_padding"), ((3, 16000), "none")])
+def test_softmax_team_form(shape, mask):
+    announce(f"softmax team form {shape} {mask}")
+    check_against_oracle(graphs.scaled_masked_softmax(shape, 0.125, mask),
+                         inputs.scaled_masked_softmax(shape, mask), what=f"softmax team {shape} {mask}")
+
+
+def test_team_form_launch_options():
+    announce("row team form options")
+    ops, ins = graphs.layernorm_fwd(77, 8192), inputs.layernorm_fwd(77, 8192)
+    ref = run_gpu(ops, ins)
+    for opts in (dict(wg_size=256), dict(wg_size=1024), dict(grid=5), dict(wg_size=512, grid=3)):
+        got = run_gpu(ops, ins, **opts)
+        assert_close(got[0], ref[0], 1e-6, f"team form {opts}")
+
+
 def test_block_form_launch_options():
     announce("row block form options")
     ops, ins = graphs.layernorm_fwd(300, 4096), inputs.layernorm_fwd(300, 4096)
