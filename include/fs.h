@@ -8,8 +8,9 @@
  * (Section 5.1: thread, warp and block composition, kernel packing).
  *
  * All pointers named "device" are HIP device pointers; everything else is host
- * memory.  No function throws, aborts or synchronises the device; every failure
- * is a status code plus a message readable through fs_last_error().
+ * memory.  No function throws or aborts, and none but fs_plan_tune synchronises the
+ * device; every failure is a status code plus a message readable through
+ * fs_last_error().
  */
 #ifndef FS_H_
 #define FS_H_
@@ -89,7 +90,9 @@ typedef enum {
  * Section 5.2).  0 = let the plan choose. */
 typedef struct {
   int32_t mode;          /* fs_mode */
-  int32_t wg_size;       /* threads per workgroup: 64..1024, multiple of 64 */
+  int32_t wg_size;       /* threads per workgroup: multiple of 64; each schedule states its
+                            own range in its error message (64..512 for one-wavefront rows,
+                            a power of two 128..1024 for wavefront teams, ...) */
   int32_t rows_per_wave; /* independent row groups a wavefront keeps in flight: 1..8 */
   int32_t grid;          /* number of workgroups */
 } fs_plan_options;
@@ -127,6 +130,25 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
  * FS_ERR_NOMEM.  Extents of 0 are legal: nothing is launched. */
 fs_status fs_launch(fs_plan* plan, const void* const* inputs, int32_t n_in,
                     void* const* outputs, int32_t n_out, void* hip_stream);
+
+/* Kernel tuning (Algorithm 3's outer loop, Section 5.3: generate templates, evaluate each
+ * kernel, keep the best; "optimize once, reuse").  Builds the stitched plan of the group
+ * under every launch template the group's schedule offers (workgroup size, row groups in
+ * flight, grid), runs each `trials` times on `hip_stream` with the caller's buffers, and
+ * returns the fastest plan.
+ *   inputs / outputs   as for fs_launch (DEVICE pointers); the outputs end up holding the
+ *                      group's result
+ *   trials             timed launches per template, 1..1000 (2 untimed ones come first)
+ *   out                receives the best plan
+ *   best               host, may be NULL: receives the winning options
+ *   best_us            host, may be NULL: its average time per launch in microseconds
+ * Unlike fs_launch this call SYNCHRONISES: it waits on HIP events it records on the
+ * stream, and it must not be used while the stream is being captured.
+ * Errors: those of fs_plan_create and fs_launch. */
+fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops,
+                       const void* const* inputs, int32_t n_in,
+                       void* const* outputs, int32_t n_out, void* hip_stream,
+                       int32_t trials, fs_plan** out, fs_plan_options* best, double* best_us);
 
 /* Release the plan and its workspace.  NULL is a no-op.  The caller makes sure no
  * launch of the plan is still running. */

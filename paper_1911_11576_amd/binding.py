@@ -70,6 +70,9 @@ def lib():
         L.fs_plan_info.restype = i32
         L.fs_plan_describe.argtypes = [vp]
         L.fs_plan_describe.restype = C.c_char_p
+        L.fs_plan_tune.argtypes = [C.POINTER(fs_op_desc), i32, C.POINTER(vp), i32, C.POINTER(vp), i32, vp, i32,
+                                   C.POINTER(vp), C.POINTER(fs_plan_options), C.POINTER(C.c_double)]
+        L.fs_plan_tune.restype = i32
         L.fs_stream_copy.argtypes = [vp, vp, i64, vp]
         L.fs_stream_copy.restype = i32
         _lib = L
@@ -128,6 +131,18 @@ def fs_launch(plan, inputs, outputs, stream=None):
     _check(lib().fs_launch(plan, _pointers(inputs), len(inputs), _pointers(outputs), len(outputs), stream))
 
 
+def fs_plan_tune(ops, inputs, outputs, stream=None, trials=20):
+    """-> (plan handle, winning options as a dict, microseconds per launch)."""
+    arr = ops if isinstance(ops, C.Array) else marshal_ops(ops)
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    out, opt, us = C.c_void_p(), fs_plan_options(), C.c_double()
+    _check(lib().fs_plan_tune(arr, len(arr), _pointers(inputs), len(inputs), _pointers(outputs), len(outputs),
+                              stream, trials, C.byref(out), C.byref(opt), C.byref(us)))
+    return out.value, {"wg_size": opt.wg_size, "rows_per_wave": opt.rows_per_wave, "grid": opt.grid}, us.value
+
+
 def fs_destroy(plan):
     _check(lib().fs_destroy(plan))
 
@@ -166,10 +181,20 @@ class BoundArgs:
 class Plan:
     """Owner of one fs_plan handle."""
 
-    def __init__(self, ops, mode="stitched", wg_size=0, rows_per_wave=0, grid=0):
-        self._h = None
-        m = {"stitched": FS_MODE_STITCHED, "per_op": FS_MODE_PER_OP}[mode]
-        self._h = fs_plan_create(ops, m, wg_size, rows_per_wave, grid)
+    def __init__(self, ops, mode="stitched", wg_size=0, rows_per_wave=0, grid=0, _handle=None):
+        self._h = _handle
+        if _handle is None:
+            m = {"stitched": FS_MODE_STITCHED, "per_op": FS_MODE_PER_OP}[mode]
+            self._h = fs_plan_create(ops, m, wg_size, rows_per_wave, grid)
+        self.tuned = None
+
+    @classmethod
+    def tune(cls, ops, inputs, outputs, stream=None, trials=20):
+        """The fastest of the schedule's launch templates for these buffers (fs_plan_tune)."""
+        h, opts, us = fs_plan_tune(ops, inputs, outputs, stream, trials)
+        plan = cls(ops, _handle=h)
+        plan.tuned = dict(opts, us=us)
+        return plan
 
     def launch(self, inputs, outputs, stream=None):
         fs_launch(self._h, inputs, outputs, stream)

@@ -4,7 +4,9 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <set>
 #include <string>
+#include <vector>
 
 #include "../../include/fs.h"
 #include "graph.h"
@@ -182,6 +184,87 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
   } catch (...) {
     return set_error(FS_ERR_HIP, "internal error while launching");
   }
+  return FS_OK;
+}
+
+fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* inputs, int32_t n_in,
+                       void* const* outputs, int32_t n_out, void* hip_stream, int32_t trials, fs_plan** out,
+                       fs_plan_options* best, double* best_us) {
+  if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
+  *out = nullptr;
+  if (trials < 1 || trials > 1000) return set_error(FS_ERR_INVALID, "trials out of range [1,1000]");
+  // the default template first: it decides the schedule, and it is the fallback
+  fs_plan* base = nullptr;
+  fs_status st = fs_plan_create(ops, n_ops, nullptr, &base);
+  if (st != FS_OK) return st;
+  // launch templates worth trying for each schedule (TemplatesGeneration, pruned by hand as
+  // the paper does for JIT use)
+  std::vector<fs_plan_options> cands;
+  cands.push_back(fs_plan_options{FS_MODE_STITCHED, 0, 0, 0});
+  if (base->schedule == FS_SCHED_ROW && base->row_form == 0) {
+    for (int wg : {128, 256, 512})
+      for (int u : {1, 2, 4}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, u, 0});
+  } else if (base->schedule == FS_SCHED_ROW && base->row_form == 1) {
+    for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+  } else if (base->schedule == FS_SCHED_ROW) {
+    for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+  } else if (base->schedule == FS_SCHED_ROW_COL) {
+    for (int wg : {256, 384, 512})
+      for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (e0) (void)hipEventDestroy(e0);
+    fs_destroy(base);
+    return set_error(FS_ERR_HIP, "hipEventCreate failed");
+  }
+  std::set<std::string> seen;
+  fs_plan* best_plan = nullptr;
+  fs_plan_options best_opt = cands[0];
+  double best_t = 0.0;
+  std::string first_launch_error;
+  fs_status launch_status = FS_OK;
+  for (size_t i = 0; i < cands.size(); ++i) {
+    fs_plan* p = nullptr;
+    if (i == 0) p = base;
+    else if (fs_plan_create(ops, n_ops, &cands[i], &p) != FS_OK) continue;   // template not generable: skip
+    // identical geometry to a template already timed: skip
+    if (!seen.insert(p->description).second) { fs_destroy(p); continue; }
+    fs_status ls = FS_OK;
+    for (int w = 0; w < 2 && ls == FS_OK; ++w) ls = fs_launch(p, inputs, n_in, outputs, n_out, hip_stream);
+    bool ok = ls == FS_OK && hipEventRecord(e0, stream) == hipSuccess;
+    for (int t = 0; t < trials && ok; ++t) ok = (ls = fs_launch(p, inputs, n_in, outputs, n_out, hip_stream)) == FS_OK;
+    if (ok) ok = hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+    float ms = 0.f;
+    if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    if (!ok) {
+      if (launch_status == FS_OK) {
+        launch_status = ls != FS_OK ? ls : FS_ERR_HIP;
+        first_launch_error = ls != FS_OK ? g_error : std::string("HIP event call failed while timing");
+      }
+      fs_destroy(p);
+      if (i == 0) break;   // the default template itself fails: argument error, report it
+      continue;
+    }
+    const double us = 1e3 * ms / trials;
+    if (!best_plan || us < best_t) {
+      if (best_plan) fs_destroy(best_plan);
+      best_plan = p; best_t = us; best_opt = cands[i];
+    } else {
+      fs_destroy(p);
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!best_plan) return set_error(launch_status == FS_OK ? FS_ERR_HIP : launch_status,
+                                   first_launch_error.empty() ? "no template could be launched" : first_launch_error);
+  // leave the outputs written by the returned plan
+  st = fs_launch(best_plan, inputs, n_in, outputs, n_out, hip_stream);
+  if (st != FS_OK) { fs_destroy(best_plan); return st; }
+  *out = best_plan;
+  if (best) *best = best_opt;
+  if (best_us) *best_us = best_t;
   return FS_OK;
 }
 

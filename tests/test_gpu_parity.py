@@ -347,6 +347,52 @@ def test_full_size_layernorm_bwd():
     assert_close(dx, want_dx, 1e-5, "cfg5 full dx")
 
 
+# ---------------------------------------------------------------- tuning (Algorithm 3's outer loop)
+
+@pytest.mark.parametrize("cfg", CONFIGS, ids=lambda c: c.name)
+def test_plan_tune_returns_a_correct_plan(cfg):
+    announce(f"tune {cfg.name}")
+    ops, ins = cfg.build("small")
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    plan = Plan.tune(ops, dev_in, dev_out, trials=3)
+    try:
+        assert plan.tuned["us"] > 0
+        want = interp.run(ops, ins)
+        tol = TOLERANCE[cfg.dtype]
+        # the outputs already hold the winner's result
+        torch.cuda.synchronize()
+        for got, ref in zip(dev_out, want):
+            assert_close(got.double().cpu().numpy(), ref, tol, f"tuned {cfg.name}")
+        # and the returned plan is an ordinary plan
+        fresh = alloc_outputs(ops)
+        plan.launch(dev_in, fresh)
+        torch.cuda.synchronize()
+        for got, ref in zip(fresh, want):
+            assert_close(got.double().cpu().numpy(), ref, tol, f"tuned relaunch {cfg.name}")
+        assert plan.info()["n_kernels"] == 1
+    finally:
+        plan.close()
+
+
+def test_plan_tune_rejects_unsupported_groups_and_bad_arguments():
+    announce("tune errors")
+    g = graphs.Graph()
+    x = g.parameter("x", "f32", (8, 64))
+    g.output(g.exp(x))
+    t = torch.zeros(8, 64, device="cuda:0")
+    with pytest.raises(FsError) as e:
+        Plan.tune(g.ops, [t], [torch.empty_like(t)])
+    assert e.value.status == binding.FS_ERR_UNSUPPORTED
+    ops, ins = graphs.layernorm_fwd(4, 768), inputs.layernorm_fwd(4, 768)
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    with pytest.raises(FsError) as e:
+        Plan.tune(ops, dev_in[:2], dev_out)
+    assert e.value.status == binding.FS_ERR_INVALID
+    with pytest.raises(FsError) as e:
+        Plan.tune(ops, dev_in, dev_out, trials=0)
+    assert e.value.status == binding.FS_ERR_INVALID
+
+
 # ---------------------------------------------------------------- edge cases and error paths
 
 def test_empty_inputs_launch_nothing_and_succeed():
