@@ -102,7 +102,8 @@ typedef enum {
   FS_SCHED_PER_OP = 0,
   FS_SCHED_ROW = 1,      /* elementwise -> row reduce -> broadcast, wavefront reductions */
   FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials */
-  FS_SCHED_BDOT_SOFTMAX = 3 /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
+  FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
+  FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing */
 } fs_schedule;
 
 /* Build a plan from a fusion group.

@@ -25,6 +25,7 @@ struct fs_plan {
   int row_form = 0;   // 0 one wavefront per row group, 1 wavefront team, 2 row cached in LDS
   fs::LnBwdLaunch lnbwd;
   fs::AttnLaunch attn;
+  fs::EwLaunch ew;
   fs::PerOpPlan per_op;
   int n_kernels = 1;
   int64_t lds_bytes = 0, workspace_bytes = 0, moved_bytes = 0;
@@ -72,13 +73,23 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
       p->moved_bytes = p->per_op.moved_bytes;
       p->description = fs::per_op_describe(p->per_op);
     } else {
-      if (!fs::recognise(p->graph, &p->match)) {
-        const std::string why = p->match.why;
-        delete p;
-        return set_error(FS_ERR_UNSUPPORTED, why);
-      }
       p->moved_bytes = algo;
+      if (!fs::recognise(p->graph, &p->match)) {
+        // not one of the reduce / dot patterns: an all-elementwise group still stitches
+        std::string why = p->match.why;
+        int st = FS_OK;
+        if (!fs::ew_stitch_plan(p->graph, lo, &p->ew, &st, &err)) {
+          if (st == FS_ERR_UNSUPPORTED && why != "no stitched schedule matches this group") err = why;
+          delete p;
+          return set_error((fs_status)st, err);
+        }
+        p->match.kind = fs::MATCH_NONE;
+        p->schedule = FS_SCHED_ELEMENTWISE;
+        p->lds_bytes = p->ew.lds_bytes;
+        p->description = fs::ew_stitch_describe(p->ew);
+      }
       switch (p->match.kind) {
+        case fs::MATCH_NONE: break;   // elementwise schedule, set up above
         case fs::MATCH_ROW:
           p->schedule = FS_SCHED_ROW;
           if (fs::row_stitch_plan(p->match.row, lo, &p->row, &err)) {
@@ -178,6 +189,7 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
         break;
       case FS_SCHED_ROW_COL: rc = fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err); break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
+      case FS_SCHED_ELEMENTWISE: rc = fs::ew_stitch_launch(p->ew, inputs, outputs, n_out, hip_stream, &err); break;
       default: rc = fs::per_op_launch(g, p->per_op, inputs, outputs, p->workspace, hip_stream, &err); break;
     }
     if (rc != 0) return set_error(FS_ERR_HIP, err);
@@ -211,6 +223,8 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
   } else if (base->schedule == FS_SCHED_ROW_COL) {
     for (int wg : {256, 384, 512})
       for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
+  } else if (base->schedule == FS_SCHED_ELEMENTWISE) {
+    for (int wg : {64, 128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipEvent_t e0 = nullptr, e1 = nullptr;

@@ -2,6 +2,7 @@
 // host: geometry, LDS budget; no GPU call), a `describe` step and a `launch` step.
 #pragma once
 #include <string>
+#include <vector>
 #include "specs.h"
 
 namespace fs {
@@ -40,6 +41,19 @@ bool attn_stitch_plan(const AttnSpec&, const LaunchOpts&, AttnLaunch*, int* stat
 std::string attn_stitch_describe(const AttnSpec&, const AttnLaunch&);
 int attn_stitch_launch(const AttnSpec&, const AttnLaunch&, const void* const* in, void* const* out,
                        void* stream, std::string* err);
+
+// Generic elementwise stitching: the group compiled to a register program (ew_stitch.hip).
+struct Graph;
+struct EwLaunch {
+  int wg = 256, grid = 1, U = 1, n_slots = 0, n_ins = 0;   // U: chunks a thread carries in lock step
+  bool vector = true;
+  int64_t lds_bytes = 0;
+  std::vector<char> blob;   // the compiled program (plain data)
+};
+bool ew_stitch_plan(const Graph&, const LaunchOpts&, EwLaunch*, int* status, std::string* err);
+std::string ew_stitch_describe(const EwLaunch&);
+int ew_stitch_launch(const EwLaunch&, const void* const* in, void* const* out, int n_out, void* stream,
+                     std::string* err);
 
 int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, std::string* err);
 

@@ -19,6 +19,10 @@ struct PerOpView {          // how a consumer reads one operand
   int64_t stride[FS_MAX_RANK] = {0, 0, 0, 0};   // element strides along the consumer's dims
 };
 
+// how node `n` (a value of its consumer's shape) maps onto memory: broadcasts and outputs
+// are looked through down to the parameter or materialised op that owns the bytes
+PerOpView view_of(const Graph& g, int n);
+
 struct PerOpStep {
   int node = -1;
   int kind = 0;             // fs_opkind of the node (FS_OUTPUT: plain copy)

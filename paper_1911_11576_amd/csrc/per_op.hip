@@ -7,6 +7,26 @@
 #include "per_op.h"
 
 namespace fs {
+
+// how `n` (a value of the consumer's shape) maps onto memory
+PerOpView view_of(const Graph& g, int n) {
+  const Node& x = g[n];
+  PerOpView v;
+  if (x.kind == FS_CONSTANT) { v.base = -1; v.cval = (float)x.attr; v.full = false; return v; }
+  if (x.kind == FS_BROADCAST) {
+    const PerOpView o = view_of(g, x.operand[0]);
+    const Node& a = g[x.operand[0]];
+    v.base = o.base; v.full = false;
+    for (int d = 0; d < a.rank; ++d) v.stride[x.axis + d] = a.shape[d] == 1 ? 0 : o.stride[d];
+    return v;
+  }
+  if (x.kind == FS_OUTPUT) return view_of(g, x.operand[0]);
+  v.base = n; v.full = true;
+  int64_t s = 1;
+  for (int d = x.rank - 1; d >= 0; --d) { v.stride[d] = s; s *= x.shape[d]; }
+  return v;
+}
+
 namespace {
 
 // ------------------------------------------------------------------------------------
@@ -253,25 +273,6 @@ int64_t bytes_of(const Node& n) { return n.numel() * (n.dtype == FS_F32 ? 4 : 2)
 
 bool materialised(const Node& n) {
   return n.kind != FS_PARAMETER && n.kind != FS_CONSTANT && n.kind != FS_BROADCAST && n.kind != FS_OUTPUT;
-}
-
-// how `n` (a value of the consumer's shape) maps onto memory
-PerOpView view_of(const Graph& g, int n) {
-  const Node& x = g[n];
-  PerOpView v;
-  if (x.kind == FS_CONSTANT) { v.base = -1; v.cval = (float)x.attr; v.full = false; return v; }
-  if (x.kind == FS_BROADCAST) {
-    const PerOpView o = view_of(g, x.operand[0]);
-    const Node& a = g[x.operand[0]];
-    v.base = o.base; v.full = false;
-    for (int d = 0; d < a.rank; ++d) v.stride[x.axis + d] = a.shape[d] == 1 ? 0 : o.stride[d];
-    return v;
-  }
-  if (x.kind == FS_OUTPUT) return view_of(g, x.operand[0]);
-  v.base = n; v.full = true;
-  int64_t s = 1;
-  for (int d = x.rank - 1; d >= 0; --d) { v.stride[d] = s; s *= x.shape[d]; }
-  return v;
 }
 
 bool view_vector_ok(const PerOpView& v, const Node& res) {

@@ -92,10 +92,15 @@ def _expect(status, ops, **kw):
 def test_unsupported_groups_return_unsupported_not_crash():
     g = Graph()
     x = g.parameter("x", "f32", (8, 64))
-    g.output(g.exp(g.tanh(x)))                     # plain elementwise chain: no stitched schedule yet
+    g.output(g.reduce_sum(g.exp(x), 0))            # a lone column reduction: no stitched schedule
     _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
     with Plan(g.ops, "per_op") as p:               # the per-op plan always exists
-        assert p.info()["n_kernels"] == 2
+        assert p.info()["n_kernels"] == 3
+    g = Graph()
+    x = g.parameter("x", "f32", (8, 64))
+    g.output(g.exp(g.tanh(x)))                     # any all-elementwise group stitches
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "elementwise"
     # LayerNorm backward keeps fp64 column accumulators per lane: at most 1024 columns
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048))
     # fp32 attention has no MFMA path
@@ -161,3 +166,46 @@ def test_launch_without_plan_is_an_error_not_a_crash():
     assert lib.fs_launch(None, None, 0, None, 0, None) == binding.FS_ERR_INVALID
     assert lib.fs_plan_info(None, None, None, None, None, None, None) == binding.FS_ERR_INVALID
     assert lib.fs_stream_copy(None, None, 24, None) == binding.FS_ERR_INVALID
+
+
+# ---------------------------------------------------------------- elementwise schedule (host side)
+
+def test_elementwise_groups_compile_to_one_kernel():
+    ops = graphs.adam_update((64, 1024))
+    with Plan(ops) as p:
+        info = p.info()
+        assert info["schedule"] == "elementwise" and info["n_kernels"] == 1
+        assert info["workspace_bytes"] == 0
+        # four parameters read once, three outputs written once
+        assert info["algorithmic_bytes"] == 7 * 64 * 1024 * 4 == info["moved_bytes"]
+        assert "THREAD_4" in p.describe() and "cta_size=256" in p.describe()
+    with Plan(ops, "per_op") as q:
+        assert q.info()["n_kernels"] > 8 and q.info()["moved_bytes"] > 3 * 7 * 64 * 1024 * 4
+    # a last extent that is not a multiple of 4: one element per thread
+    with Plan(graphs.adam_update((7, 5))) as p:
+        assert "THREAD_4" not in p.describe()
+    # widening converts are free: 16-bit storage, fp32 arithmetic
+    with Plan(graphs.bias_gelu_residual(32, 1024, "bf16")) as p:
+        assert p.info()["schedule"] == "elementwise"
+        assert p.info()["algorithmic_bytes"] == (3 * 32 * 1024 + 1024) * 2
+
+
+def test_elementwise_limits_are_reported():
+    g = Graph()
+    x = g.parameter("x", "f32", (8, 64))
+    y = x
+    for _ in range(70):                      # longer than the register program may be
+        y = g.tanh(y)
+    g.output(y)
+    e = _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    assert "64 instructions" in str(e)
+    g = Graph()
+    x = g.parameter("x", "f32", (8, 64))
+    g.output(g.exp(x))
+    e = _expect(binding.FS_ERR_INVALID, g.ops, wg_size=512)
+    assert "wg_size" in str(e)
+    g = Graph()                               # a broadcast of a computed value is not elementwise
+    x = g.parameter("x", "f32", (8, 64))
+    v = g.parameter("v", "f32", (64,))
+    g.output(g.add(x, g.col_broadcast(g.exp(v), x)))
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)

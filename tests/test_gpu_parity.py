@@ -378,10 +378,10 @@ def test_plan_tune_rejects_unsupported_groups_and_bad_arguments():
     announce("tune errors")
     g = graphs.Graph()
     x = g.parameter("x", "f32", (8, 64))
-    g.output(g.exp(x))
+    g.output(g.reduce_sum(g.exp(x), 0))       # a lone column reduction has no stitched schedule
     t = torch.zeros(8, 64, device="cuda:0")
     with pytest.raises(FsError) as e:
-        Plan.tune(g.ops, [t], [torch.empty_like(t)])
+        Plan.tune(g.ops, [t], [torch.empty(64, device="cuda:0")])
     assert e.value.status == binding.FS_ERR_UNSUPPORTED
     ops, ins = graphs.layernorm_fwd(4, 768), inputs.layernorm_fwd(4, 768)
     dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)

@@ -281,3 +281,63 @@ def layernorm_bwd(rows, cols, dtype="f32"):
     g.output(dgamma, "dgamma")
     g.output(dbeta, "dbeta")
     return g.ops
+
+
+# ----------------------------------------------------------------------------------
+# All-elementwise groups (thread composition and kernel packing, Section 5.1).
+# ----------------------------------------------------------------------------------
+
+def bias_gelu_residual(rows, cols, dtype="bf16"):
+    """y = gelu_tanh(x + bias) + residual: the prologue of config 4 as a group of its own."""
+    g = Graph()
+    x = g.parameter("x", dtype, (rows, cols))
+    bias = g.parameter("bias", dtype, (cols,))
+    res = g.parameter("residual", dtype, (rows, cols))
+    if dtype != "f32":
+        x, bias, res = (g.convert(t, "f32") for t in (x, bias, res))
+    h = g.add(x, g.col_broadcast(bias, x))
+    h3 = g.multiply(g.multiply(h, h), h)
+    inner = g.multiply(g.add(h, g.multiply(h3, g.constant(GELU_K1))), g.constant(GELU_K0))
+    gelu = g.multiply(g.multiply(h, g.constant(0.5)), g.add(g.tanh(inner), g.constant(1.0)))
+    y = g.add(gelu, res)
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
+
+
+def adam_update(shape, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, dtype="f32"):
+    """Three packed outputs over one shape (the backward-phase gradient-accumulation
+    pattern the paper packs): m' = b1*m + (1-b1)*g, v' = b2*v + (1-b2)*g*g,
+    p' = p - lr * m' / (sqrt(v') + eps)."""
+    g = Graph()
+    p = g.parameter("p", dtype, shape)
+    grad = g.parameter("grad", dtype, shape)
+    m = g.parameter("m", dtype, shape)
+    v = g.parameter("v", dtype, shape)
+    m2 = g.add(g.multiply(m, g.constant(beta1)), g.multiply(grad, g.constant(1.0 - beta1)))
+    v2 = g.add(g.multiply(v, g.constant(beta2)), g.multiply(g.multiply(grad, grad), g.constant(1.0 - beta2)))
+    step = g.divide(g.multiply(m2, g.constant(lr)), g.add(g.sqrt(v2), g.constant(eps)))
+    p2 = g.subtract(p, step)
+    g.output(p2, "p")
+    g.output(m2, "m")
+    g.output(v2, "v")
+    return g.ops
+
+
+def scale_shift_rows_cols(shape, dtype="f32"):
+    """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
+    broadcasts along either side folded into one elementwise group."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    rowv = g.parameter("rowv", dtype, shape[:-1])
+    colv = g.parameter("colv", dtype, (shape[-1],))
+    if dtype != "f32":
+        x, rowv, colv = (g.convert(t, "f32") for t in (x, rowv, colv))
+    a = g.multiply(g.subtract(x, g.row_broadcast(rowv, x)), g.col_broadcast(colv, x))
+    sig = g.divide(g.constant(1.0), g.add(g.exp(g.negate(x)), g.constant(1.0)))
+    y = g.multiply(a, sig)
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops

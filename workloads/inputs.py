@@ -86,3 +86,28 @@ def layernorm_bwd(rows=32768, cols=1024, dtype="f32", eps=1e-5, seed_offset=5):
     mean = round_to(np.mean(x, axis=1), dtype)
     rstd = round_to(1.0 / np.sqrt(np.var(x, axis=1) + eps), dtype)
     return [dy, x, gamma, mean, rstd]
+
+
+def bias_gelu_residual(rows, cols, dtype="bf16", seed_offset=11):
+    r = _rng(seed_offset)
+    x = r.normal(0.0, 1.0, (rows, cols))
+    bias = r.normal(0.0, 0.02, (cols,))
+    res = r.normal(0.0, 1.0, (rows, cols))
+    return [round_to(t, dtype) for t in (x, bias, res)]
+
+
+def adam_update(shape, dtype="f32", seed_offset=12):
+    r = _rng(seed_offset)
+    p = r.normal(0.0, 1.0, shape)
+    grad = r.normal(0.0, 0.1, shape)
+    m = r.normal(0.0, 0.05, shape)
+    v = r.uniform(1e-4, 1e-2, shape)
+    return [round_to(t, dtype) for t in (p, grad, m, v)]
+
+
+def scale_shift_rows_cols(shape, dtype="f32", seed_offset=13):
+    r = _rng(seed_offset)
+    x = r.normal(0.0, 1.5, shape)
+    rowv = r.normal(0.0, 1.0, shape[:-1])
+    colv = r.uniform(0.5, 1.5, (shape[-1],))
+    return [round_to(t, dtype) for t in (x, rowv, colv)]
