@@ -81,9 +81,14 @@ typedef struct {
 
 typedef enum {
   FS_MODE_STITCHED = 0, /* the whole group as one stitched kernel */
-  FS_MODE_PER_OP = 1    /* baseline: one kernel per op, intermediates in a plan-owned HBM
+  FS_MODE_PER_OP = 1,   /* baseline: one kernel per op, intermediates in a plan-owned HBM
                            workspace (the sum of K(Op_j) side of the execution-based
                            score, Section 4.3) */
+  FS_MODE_STITCHED_PREBUILT = 2 /* stitched, but only with kernels compiled into the library:
+                           no kernel generation (Section 5.3) and so no compiler run inside
+                           fs_plan_create.  Differs from FS_MODE_STITCHED only for
+                           FS_SCHED_ELEMENTWISE groups, which then run through the
+                           library's register-program interpreter kernel */
 } fs_mode;
 
 /* Launch parameters a template would carry (cta_size, cta_num and the per-warp tile,
@@ -103,7 +108,9 @@ typedef enum {
   FS_SCHED_ROW = 1,      /* elementwise -> row reduce -> broadcast, wavefront reductions */
   FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials */
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
-  FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing */
+  FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as
+                                a kernel generated for the group (or interpreted, see
+                                FS_MODE_STITCHED_PREBUILT) */
 } fs_schedule;
 
 /* Build a plan from a fusion group.
@@ -112,8 +119,11 @@ typedef enum {
  *   out         host, receives the plan on FS_OK, NULL otherwise
  * Pure host work: validates shapes and dtypes, recognises the group as one of the
  * stitched schedules (Algorithm 3 reduced to a recogniser over hand-written kernels),
- * checks the LDS budget and fixes the launch geometry.  Touches no GPU, so it also
- * works on a machine without one.
+ * checks the LDS budget and fixes the launch geometry.  An all-elementwise group that
+ * matches none of them gets a kernel generated for it and compiled for gfx950 with the
+ * HIP run-time compiler (a few hundred milliseconds the first time a given group is
+ * seen in a process, cached afterwards).  Touches no GPU, so it also works on a
+ * machine without one.
  * Errors: FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_NOMEM. */
 fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
                          const fs_plan_options* opt, fs_plan** out);

@@ -1,8 +1,8 @@
 """Builds the HIP library for gfx950:  python -m paper_1911_11576_amd.build
 
-Every source under csrc/ is compiled with hipcc (device code for gfx950 only, no JIT
-at run time) and linked into libfusionstitch.so next to this file.  hipcc
-cross-compiles without a GPU.
+Every source under csrc/ is compiled with hipcc (device code for gfx950 only) and linked
+into libfusionstitch.so next to this file, together with the HIP run-time compiler that
+the kernel generator of the elementwise schedule uses.  hipcc cross-compiles without a GPU.
 """
 from __future__ import annotations
 
@@ -17,7 +17,7 @@ OBJ = os.environ.get("FS_OBJ_DIR", os.path.join(HERE, "_build"))
 LIB = os.environ.get("FS_LIB_OUT", os.path.join(HERE, "libfusionstitch.so"))
 
 SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f32.hip", "row_stitch_f16.hip", "row_stitch_bf16.hip", "row_team.hip", "row_block.hip", "lnbwd_stitch.hip",
-           "attn_stitch.hip", "per_op.hip", "ew_stitch.hip", "util.hip"]
+           "attn_stitch.hip", "per_op.hip", "ew_stitch.hip", "ew_codegen.cpp", "util.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -45,7 +45,7 @@ def build(verbose=False, jobs=None):
     for (obj, log), src in zip(results, SOURCES):
         if verbose and log.strip():
             print(f"--- {src}\n{log}")
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *[o for o, _ in results]]
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *[o for o, _ in results], "-lhiprtc"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout + r.stderr)

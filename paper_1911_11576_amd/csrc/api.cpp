@@ -59,9 +59,13 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
     if (!fs::build_graph(ops, n_ops, &p->graph, &err)) { delete p; return set_error(FS_ERR_INVALID, err); }
     fs::LaunchOpts lo;
     if (opt) {
-      if (opt->mode != FS_MODE_STITCHED && opt->mode != FS_MODE_PER_OP) { delete p; return set_error(FS_ERR_INVALID, "unknown mode"); }
+      if (opt->mode != FS_MODE_STITCHED && opt->mode != FS_MODE_PER_OP && opt->mode != FS_MODE_STITCHED_PREBUILT) {
+        delete p;
+        return set_error(FS_ERR_INVALID, "unknown mode");
+      }
       if (opt->wg_size < 0 || opt->rows_per_wave < 0 || opt->grid < 0) { delete p; return set_error(FS_ERR_INVALID, "negative launch option"); }
-      p->mode = opt->mode;
+      p->mode = opt->mode == FS_MODE_PER_OP ? FS_MODE_PER_OP : FS_MODE_STITCHED;
+      lo.codegen = opt->mode != FS_MODE_STITCHED_PREBUILT;
       lo.wg_size = opt->wg_size; lo.rows_per_wave = opt->rows_per_wave; lo.grid = opt->grid;
     }
     const int64_t algo = p->graph.algorithmic_bytes();
@@ -224,7 +228,9 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
     for (int wg : {256, 384, 512})
       for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
   } else if (base->schedule == FS_SCHED_ELEMENTWISE) {
-    for (int wg : {64, 128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    // the generated kernel under two workgroup sizes, and the interpreted form
+    for (int wg : {128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    cands.push_back(fs_plan_options{FS_MODE_STITCHED_PREBUILT, 0, 0, 0});
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -289,6 +295,7 @@ fs_status fs_destroy(fs_plan* p) {
     const hipError_t e = hipFree(p->workspace);
     if (e != hipSuccess) st = set_error(FS_ERR_HIP, std::string("hipFree: ") + hipGetErrorString(e));
   }
+  fs::ew_stitch_release(p->ew);
   delete p;
   return st;
 }

@@ -1,0 +1,284 @@
+// Kernel generation for all-elementwise fusion groups (paper Section 5.1: thread composition
+// and kernel packing; Section 5.3: the stitched op is emitted as code).  The group's ops
+// become one straight-line loop body over a chunk of consecutive elements: every parameter
+// is loaded once, every intermediate is a register value, every output is stored once.
+// Shapes, strides and constants are literals in the source, so index arithmetic for
+// broadcast operands compiles to multiplications by constants.
+//
+// The source is compiled by the HIP run-time compiler for gfx950 (no GPU needed for that)
+// and cached per process; loading the code object onto a device happens at the first launch.
+#include "ew_ir.h"
+
+#include <hip/hip_runtime.h>
+#include <hip/hiprtc.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+
+namespace fs {
+
+namespace {
+
+struct Emitter {
+  std::string s;
+  void line(const char* fmt, ...) __attribute__((format(printf, 2, 3))) {
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    s += buf;
+    s += '\n';
+  }
+};
+
+const char* kPreamble = R"SRC(
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+struct Args { const void* in[12]; void* out[8]; };
+#define UNROLL _Pragma("unroll")
+static __device__ __forceinline__ float bits_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+static __device__ __forceinline__ unsigned f32_bits(float f) { return __builtin_bit_cast(unsigned, f); }
+static __device__ __forceinline__ float bf16_lo(unsigned w) { return bits_f32(w << 16); }
+static __device__ __forceinline__ float bf16_hi(unsigned w) { return bits_f32(w & 0xffff0000u); }
+static __device__ __forceinline__ float f16_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
+static __device__ __forceinline__ float f16_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
+// round to nearest even; NaN stays NaN
+static __device__ __forceinline__ unsigned to_bf16(float f) {
+  const unsigned u = f32_bits(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+static __device__ __forceinline__ unsigned to_f16(float f) { return __builtin_bit_cast(unsigned short, (_Float16)f); }
+static __device__ __forceinline__ float round_bf16(float f) { return bits_f32(to_bf16(f) << 16); }
+static __device__ __forceinline__ float round_f16(float f) { return (float)(_Float16)f; }
+)SRC";
+
+int dtype_bytes(int dt) { return dt == FS_F32 ? 4 : 2; }
+
+std::string operand_text(const EwIrOperand& o) {
+  char buf[64];
+  if (o.kind == EW_FROM_NODE) snprintf(buf, sizeof buf, "t%d[j]", o.index);
+  else if (o.kind == EW_FROM_VIEW) snprintf(buf, sizeof buf, "v%d[j]", o.index);
+  else {
+    uint32_t u;
+    memcpy(&u, &o.cval, 4);
+    snprintf(buf, sizeof buf, "bits_f32(0x%08xu)", u);
+  }
+  return buf;
+}
+
+std::string op_text(const EwIrNode& n) {
+  const std::string a = operand_text(n.opnd[0]);
+  const std::string b = n.n_operands == 2 ? operand_text(n.opnd[1]) : std::string();
+  switch (n.op) {
+    case FS_ADD: return a + " + " + b;
+    case FS_SUBTRACT: return a + " - " + b;
+    case FS_MULTIPLY: return a + " * " + b;
+    case FS_DIVIDE: return a + " / " + b;
+    case FS_MAXIMUM: return "fmaxf(" + a + ", " + b + ")";
+    case FS_NEGATE: return "-" + a;
+    case FS_EXP: return "expf(" + a + ")";
+    case FS_LOG: return "logf(" + a + ")";
+    case FS_TANH: return "tanhf(" + a + ")";
+    case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
+    case FS_SQRT: return "sqrtf(" + a + ")";
+    case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
+    case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
+    default: return a;
+  }
+}
+
+}  // namespace
+
+std::string ew_emit_source(const EwIr& ir, int* width, int* unroll) {
+  // Chunk width: as many consecutive elements as one 16-byte access of the narrowest tensor
+  // holds, provided every row start stays aligned; otherwise one element.
+  const int64_t last = ir.shape[FS_MAX_RANK - 1];
+  bool any32 = false;
+  for (const EwIrView& v : ir.views) if (v.full && v.dtype == FS_F32) any32 = true;
+  for (const EwIrNode& n : ir.nodes) if (n.out_ordinal >= 0 && n.out_dtype == FS_F32) any32 = true;
+  auto fits = [&](int w) {
+    if (last % w) return false;
+    for (const EwIrView& v : ir.views) {
+      if (v.full) continue;
+      const int64_t ls = v.stride[FS_MAX_RANK - 1];
+      if (ls != 0 && ls != 1) return false;
+      if (ls == 1) for (int d = 0; d + 1 < FS_MAX_RANK; ++d) if (v.stride[d] % w) return false;
+    }
+    return true;
+  };
+  int W = 1;
+  if (!any32 && fits(8)) W = 8;
+  else if (fits(4)) W = 4;
+  *width = W;
+  *unroll = 1;
+  bool need_idx = false;
+  for (const EwIrView& v : ir.views) if (!v.full) need_idx = true;
+
+  Emitter e;
+  e.s = kPreamble;
+  e.line("extern \"C\" __global__ __launch_bounds__(256) void fs_ew(const Args a) {");
+  e.line("  constexpr int W = %d;", W);
+  e.line("  const long long nchunk = %lldll;", (long long)(ir.n / W));
+  e.line("  for (long long ci = (long long)blockIdx.x * blockDim.x + threadIdx.x; ci < nchunk; ci += (long long)gridDim.x * blockDim.x) {");
+  e.line("    const long long e0 = ci * W;");
+  if (need_idx) {
+    // coordinates of the chunk's first element (the chunk never crosses a row: W divides the last extent)
+    const bool small = ir.n <= 0x7fffffffLL;
+    e.line("    %s r = (%s)e0;", small ? "unsigned" : "unsigned long long", small ? "unsigned" : "unsigned long long");
+    for (int d = FS_MAX_RANK - 1; d >= 0; --d) {
+      if (ir.shape[d] == 1) { e.line("    const long long i%d = 0;", d); continue; }
+      const char* sfx = small ? "u" : "ull";
+      e.line("    const long long i%d = r %% %lld%s; r /= %lld%s;", d, (long long)ir.shape[d], sfx, (long long)ir.shape[d], sfx);
+    }
+  }
+  // ---- loads: every view once
+  for (size_t k = 0; k < ir.views.size(); ++k) {
+    const EwIrView& v = ir.views[k];
+    const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+    e.line("    float v%zu[W];", k);
+    std::string off = "e0";
+    bool splat = false;
+    if (!v.full) {
+      off.clear();
+      for (int d = 0; d < FS_MAX_RANK; ++d) {
+        if (v.stride[d] == 0) continue;
+        char buf[64];
+        snprintf(buf, sizeof buf, "%si%d * %lldll", off.empty() ? "" : " + ", d, (long long)v.stride[d]);
+        off += buf;
+      }
+      if (off.empty()) off = "0";
+      splat = v.stride[FS_MAX_RANK - 1] == 0;
+    }
+    e.line("    {");
+    e.line("      const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s);", ty, ty, k, off.c_str());
+    // operands of the group's own shape stream through once; broadcast operands are re-read by
+    // many threads and stay cached
+    const char* ld = v.full ? "__builtin_nontemporal_load" : "*";
+    if (splat || W == 1) {
+      const char* conv = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
+      e.line("      const float x = %s;", conv);
+      e.line("      UNROLL for (int j = 0; j < W; ++j) v%zu[j] = x;", k);
+    } else if (v.dtype == FS_F32) {
+      for (int q = 0; q < W / 4; ++q) {
+        e.line("      { const f32x4 x = %s(reinterpret_cast<const f32x4*>(p) + %d);", ld, q);
+        e.line("        UNROLL for (int j = 0; j < 4; ++j) v%zu[%d + j] = x[j]; }", k, 4 * q);
+      }
+    } else {
+      const char* lo = v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
+      const char* hi = v.dtype == FS_F16 ? "f16_hi" : "bf16_hi";
+      if (W == 8) e.line("      const u32x4 x = %s(reinterpret_cast<const u32x4*>(p));", ld);
+      else e.line("      const u32x2 x = %s(reinterpret_cast<const u32x2*>(p));", ld);
+      e.line("      UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[2 * j] = %s(x[j]); v%zu[2 * j + 1] = %s(x[j]); }", k, lo, k, hi);
+    }
+    e.line("    }");
+  }
+  // ---- the ops, in order; outputs stored as soon as they exist
+  for (const EwIrNode& n : ir.nodes) {
+    e.line("    float t%d[W];", n.id);
+    e.line("    UNROLL for (int j = 0; j < W; ++j) t%d[j] = %s;", n.id, op_text(n).c_str());
+    if (n.out_ordinal < 0) continue;
+    e.line("    {");
+    if (n.out_dtype == FS_F32) {
+      e.line("      float* p = static_cast<float*>(a.out[%d]) + e0;", n.out_ordinal);
+      if (W == 1) e.line("      p[0] = t%d[0];", n.id);
+      else for (int q = 0; q < W / 4; ++q)
+        e.line("      __builtin_nontemporal_store(f32x4{t%d[%d], t%d[%d], t%d[%d], t%d[%d]}, reinterpret_cast<f32x4*>(p) + %d);",
+               n.id, 4 * q, n.id, 4 * q + 1, n.id, 4 * q + 2, n.id, 4 * q + 3, q);
+    } else {
+      const char* cv = n.out_dtype == FS_F16 ? "to_f16" : "to_bf16";
+      e.line("      unsigned short* p = static_cast<unsigned short*>(a.out[%d]) + e0;", n.out_ordinal);
+      if (W == 1) e.line("      p[0] = (unsigned short)%s(t%d[0]);", cv, n.id);
+      else {
+        e.line("      unsigned w[W / 2];");
+        e.line("      UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[2 * j]) | (%s(t%d[2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+        if (W == 8) e.line("      __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
+        else e.line("      __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
+      }
+    }
+    e.line("    }");
+  }
+  e.line("  }");
+  e.line("}");
+  return e.s;
+}
+
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+std::mutex g_cache_mutex;
+std::map<std::string, std::shared_ptr<std::vector<char>>> g_cache;
+}  // namespace
+
+bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err) {
+  {
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    auto it = g_cache.find(source);
+    if (it != g_cache.end()) { *code_object = *it->second; return true; }
+  }
+  hiprtcProgram prog = nullptr;
+  hiprtcResult r = hiprtcCreateProgram(&prog, source.c_str(), "fs_ew.hip", 0, nullptr, nullptr);
+  if (r != HIPRTC_SUCCESS) { *err = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r); return false; }
+  // same code generation rules as the library's own kernels: gfx950 only, packed fp32 math off
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+  r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    std::string log;
+    if (hiprtcGetProgramLogSize(prog, &n) == HIPRTC_SUCCESS && n > 1) {
+      log.resize(n);
+      (void)hiprtcGetProgramLog(prog, &log[0]);
+    }
+    *err = std::string("hiprtcCompileProgram: ") + hiprtcGetErrorString(r) + "\n" + log.substr(0, 2000);
+    (void)hiprtcDestroyProgram(&prog);
+    return false;
+  }
+  size_t bytes = 0;
+  r = hiprtcGetCodeSize(prog, &bytes);
+  if (r == HIPRTC_SUCCESS) {
+    code_object->resize(bytes);
+    r = hiprtcGetCode(prog, code_object->data());
+  }
+  (void)hiprtcDestroyProgram(&prog);
+  if (r != HIPRTC_SUCCESS) { *err = std::string("hiprtcGetCode: ") + hiprtcGetErrorString(r); return false; }
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  g_cache[source] = std::make_shared<std::vector<char>>(*code_object);
+  return true;
+}
+
+int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const void* args, size_t args_bytes,
+                     int grid, int block, void* stream, std::string* err) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { *err = "hipGetDevice failed"; return -1; }
+  if (!m->function) {
+    hipModule_t mod = nullptr;
+    hipError_t e = hipModuleLoadData(&mod, code_object.data());
+    if (e != hipSuccess) { *err = std::string("hipModuleLoadData: ") + hipGetErrorString(e); return -1; }
+    hipFunction_t fn = nullptr;
+    e = hipModuleGetFunction(&fn, mod, "fs_ew");
+    if (e != hipSuccess) { (void)hipModuleUnload(mod); *err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e); return -1; }
+    m->module = mod; m->function = fn; m->device = dev;
+  } else if (dev != m->device) {
+    *err = "plan is bound to the device of its first launch";
+    return -1;
+  }
+  size_t sz = args_bytes;
+  void* config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, const_cast<void*>(args), HIP_LAUNCH_PARAM_BUFFER_SIZE, &sz, HIP_LAUNCH_PARAM_END};
+  const hipError_t e = hipModuleLaunchKernel(static_cast<hipFunction_t>(m->function), (unsigned)grid, 1, 1, (unsigned)block, 1, 1, 0,
+                                             static_cast<hipStream_t>(stream), nullptr, config);
+  if (e != hipSuccess) { *err = std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e); return -1; }
+  return 0;
+}
+
+void ew_module_release(EwModule* m) {
+  if (m->module) (void)hipModuleUnload(static_cast<hipModule_t>(m->module));
+  m->module = nullptr; m->function = nullptr; m->device = -1;
+}
+
+}  // namespace fs

@@ -1,0 +1,69 @@
+// An all-elementwise fusion group after analysis: the ops that compute something, in list
+// order, with their operands resolved to earlier ops, parameter views (broadcasts folded
+// into strides) or constants.  Written by the analysis in ew_stitch.hip; read by the
+// register-program compiler there and by the kernel generator (ew_codegen.cpp).
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "../../include/fs.h"
+
+namespace fs {
+
+enum EwOperandKind : int { EW_FROM_NODE = 0, EW_FROM_VIEW = 1, EW_FROM_CONST = 2 };
+enum EwExtraOp : int { EW_OP_ROUND_F16 = 100, EW_OP_ROUND_BF16 = 101 };   // beside the fs_opkind values
+
+struct EwIrOperand {
+  int kind = EW_FROM_NODE;
+  int index = -1;          // EW_FROM_NODE: id of the producing node; EW_FROM_VIEW: view number
+  float cval = 0.f;        // EW_FROM_CONST
+};
+struct EwIrNode {
+  int id = -1;             // op index in the group (names the value)
+  int op = 0;              // fs_opkind of an elementwise op, or an EwExtraOp
+  int n_operands = 1;
+  EwIrOperand opnd[2];
+  int out_ordinal = -1;    // >= 0: the value is this group output ...
+  int out_dtype = FS_F32;  // ... stored in this dtype
+};
+struct EwIrView {
+  int param = -1;          // parameter ordinal
+  int dtype = FS_F32;      // its storage dtype
+  bool full = true;        // same dense layout as the group's shape
+  int64_t stride[FS_MAX_RANK] = {0, 0, 0, 0};   // element strides along the (right-aligned) dims
+};
+struct EwIr {
+  std::vector<EwIrNode> nodes;
+  std::vector<EwIrView> views;
+  int64_t shape[FS_MAX_RANK] = {1, 1, 1, 1};    // right-aligned: leading extents 1
+  int rank = 0;
+  int64_t n = 0;
+  int n_outputs = 0;
+};
+
+// ---- kernel generation (Section 5: the stitched op is emitted as code, compiled, cached) ----
+
+struct EwGenerated {
+  int width = 4;                      // consecutive elements per thread and load
+  int unroll = 1;                     // independent chunks a thread handles
+  std::string source;
+  std::vector<char> code_object;      // compiled for gfx950
+};
+
+// HIP source of one kernel computing the whole group; pure text, no GPU or compiler involved.
+std::string ew_emit_source(const EwIr& ir, int* width, int* unroll);
+// Compile with the run-time compiler (works on a machine without a GPU).  Results are cached
+// per process by source text.  False + message if the compiler is unavailable or fails.
+bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err);
+
+// A loaded kernel (module handle and function), bound to the device current at load time.
+struct EwModule {
+  void* module = nullptr;
+  void* function = nullptr;
+  int device = -1;
+};
+int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const void* args, size_t args_bytes,
+                     int grid, int block, void* stream, std::string* err);
+void ew_module_release(EwModule* m);
+
+}  // namespace fs

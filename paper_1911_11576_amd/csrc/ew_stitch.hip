@@ -13,10 +13,13 @@
 // a wavefront's access is conflict-free).  Slots are reused by liveness.  RegisterPlanning
 // in the paper's sense falls out: an op with several consumers is computed once.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
 #include "dev_common.h"
+#include "ew_ir.h"
 #include "launchers.h"
 #include "per_op.h"
 #include "../../include/fs.h"
@@ -322,6 +325,7 @@ namespace {
 struct EwCompiler {
   const Graph& g;
   EwCompiled c;
+  EwIr ir;
   std::string err;
   int S = -1;                       // node that fixes the iteration shape
   bool vec = true;
@@ -403,11 +407,18 @@ struct EwCompiler {
       for (int d = 0; d + 1 < shape.rank; ++d) if (last == 1 && pv.stride[d] % 4 != 0) vec = false;
     }
     c.view_param[c.n_views] = g[pv.base].ordinal;
+    EwIrView iv;
+    iv.param = g[pv.base].ordinal;
+    iv.dtype = g[pv.base].dtype;
+    iv.full = pv.full;
+    for (int d = 0; d < FS_MAX_RANK; ++d) iv.stride[d] = ev.s[d];
+    ir.views.push_back(iv);
     *view = c.n_views++;
     return true;
   }
 
-  bool run() {
+  // shape checks, outputs, and the group as a list of resolved ops
+  bool analyse() {
     const int n = g.size();
     for (int i = 0; i < n; ++i) {
       const Node& x = g[i];
@@ -450,6 +461,35 @@ struct EwCompiler {
       out_dtype[src] = g[o].dtype;
     }
 
+    ir.rank = g[S].rank;
+    ir.n = P.n;
+    ir.n_outputs = (int)g.outputs.size();
+    for (int d = 0; d < FS_MAX_RANK; ++d) ir.shape[d] = P.shape[d];
+    for (int node : order) {
+      const Node& x = g[node];
+      EwIrNode in;
+      in.id = node;
+      in.op = x.kind == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : x.kind;
+      in.n_operands = n_operands(node);
+      for (int j = 0; j < in.n_operands; ++j) {
+        const int a = canon(x.operand[j]);
+        if (is_compute(a)) { in.opnd[j].kind = EW_FROM_NODE; in.opnd[j].index = a; continue; }
+        bool is_const = false;
+        if (!leaf(a, &in.opnd[j].index, &is_const, &in.opnd[j].cval)) return false;
+        in.opnd[j].kind = is_const ? EW_FROM_CONST : EW_FROM_VIEW;
+      }
+      if (in.n_operands == 2 && in.opnd[0].kind == EW_FROM_CONST && in.opnd[1].kind == EW_FROM_CONST)
+        return fail("elementwise schedule: op of two constants");
+      in.out_ordinal = out_ord[node];
+      in.out_dtype = out_dtype[node];
+      ir.nodes.push_back(in);
+    }
+    return true;
+  }
+
+  // the register program for the interpreter kernel; false (with the reason in err) if the
+  // group is too long or keeps too many values alive for it
+  bool program() {
     for (size_t k = 0; k < order.size(); ++k) {
       const int node = order[k];
       const Node& x = g[node];
@@ -538,13 +578,15 @@ struct EwCompiler {
 
 }  // namespace
 
+// The generated kernel's arguments: one pointer per operand view, one per output.
+struct EwGenArgs { const void* in[12]; void* out[8]; };
+static_assert(kEwMaxViews == 12 && kEwMaxOuts == 8, "EwGenArgs mirrors the Args struct of the generated source");
+
 bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* status, std::string* err) {
   *status = FS_ERR_UNSUPPORTED;
   EwCompiler cc(g);
-  if (!cc.run()) { *err = cc.err; return false; }
+  if (!cc.analyse()) { *err = cc.err; return false; }
   EwLaunch l;
-  l.vector = cc.vec;
-  l.n_slots = cc.n_slots;
   *status = FS_ERR_INVALID;
   if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
     *err = "elementwise schedule: wg_size must be 64, 128, 192 or 256";
@@ -554,6 +596,44 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
     *err = "elementwise schedule: rows_per_wave (chunks a thread carries in lock step) must be 1, 2 or 4";
     return false;
   }
+  l.n_ops = (int)cc.ir.nodes.size();
+  l.view_param.assign(cc.c.view_param, cc.c.view_param + cc.c.n_views);
+
+  // First choice: generate the kernel (the paper's way).  The interpreter below is the form
+  // that needs no compiler at run time; it also takes over if generation fails.
+  std::string gen_err;
+  if (opt.codegen) {
+    int width = 1, unroll = 1;
+    const std::string src = ew_emit_source(cc.ir, &width, &unroll);
+    if (const char* dump = getenv("FS_DUMP_SOURCE")) {        // debugging aid: append what was generated
+      if (FILE* f = fopen(dump, "a")) { fputs(src.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
+    }
+    if (ew_compile_source(src, &l.code_object, &gen_err)) {
+      l.generated = true;
+      l.width = width;
+      l.wg = opt.wg_size ? opt.wg_size : 256;
+      l.n = cc.ir.n;
+      const int64_t chunks = cc.ir.n / width;
+      int64_t grid = (chunks + l.wg - 1) / l.wg;
+      if (grid > (1 << 22)) grid = 1 << 22;
+      if (opt.grid > 0 && opt.grid < grid) grid = opt.grid;
+      l.grid = (int)(grid < 1 ? 1 : grid);
+      l.lds_bytes = 0;
+      *out = l;
+      *status = FS_OK;
+      return true;
+    }
+  }
+
+  *status = FS_ERR_UNSUPPORTED;
+  if (!cc.program()) {
+    *err = cc.err + (gen_err.empty() ? "" : " (and kernel generation failed: " + gen_err + ")");
+    return false;
+  }
+  l.note = gen_err;
+  l.vector = cc.vec;
+  l.n_slots = cc.n_slots;
+  *status = FS_ERR_INVALID;
   // Geometry under the LDS volume constraint: slots * chunks * threads * 16 bytes + the
   // program <= 64 KB.
   // More chunks per thread amortise the decode of a program step; small problems keep one
@@ -627,9 +707,13 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
 }
 
 std::string ew_stitch_describe(const EwLaunch& l) {
-  char buf[256];
-  snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (%d program steps, %d LDS slots); cta_num=%d, cta_size=%d, lds=%lld",
-           (l.vector ? 4 : 1) * l.U, l.n_ins, l.n_ins, l.n_slots, l.grid, l.wg, (long long)l.lds_bytes);
+  char buf[320];
+  if (l.generated)
+    snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (generated kernel, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
+             l.width, l.n_ops, l.code_object.size(), l.grid, l.wg);
+  else
+    snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (interpreted: %d program steps, %d LDS slots); cta_num=%d, cta_size=%d, lds=%lld",
+             (l.vector ? 4 : 1) * l.U, l.n_ops, l.n_ins, l.n_slots, l.grid, l.wg, (long long)l.lds_bytes);
   return buf;
 }
 
@@ -642,7 +726,16 @@ static void ew_launch_u(const EwLaunch& l, hipStream_t s, const EwProgram& prog)
   else hipLaunchKernelGGL((ew_stitch_kernel<VEC, 1>), grid, block, lds, s, prog);
 }
 
-int ew_stitch_launch(const EwLaunch& l, const void* const* in, void* const* out, int n_out, void* stream, std::string* err) {
+void ew_stitch_release(EwLaunch& l) { ew_module_release(&l.loaded); }
+
+int ew_stitch_launch(EwLaunch& l, const void* const* in, void* const* out, int n_out, void* stream, std::string* err) {
+  if (l.generated) {
+    if (l.n == 0) return 0;
+    EwGenArgs args{};
+    for (size_t k = 0; k < l.view_param.size(); ++k) args.in[k] = in[l.view_param[k]];
+    for (int k = 0; k < n_out; ++k) args.out[k] = out[k];
+    return ew_module_launch(&l.loaded, l.code_object, &args, sizeof args, l.grid, l.wg, stream, err);
+  }
   EwCompiled c;
   memcpy(&c, l.blob.data(), sizeof(EwCompiled));
   if (c.prog.n == 0) return 0;

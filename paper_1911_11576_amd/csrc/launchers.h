@@ -3,6 +3,7 @@
 #pragma once
 #include <string>
 #include <vector>
+#include "ew_ir.h"
 #include "specs.h"
 
 namespace fs {
@@ -42,18 +43,30 @@ std::string attn_stitch_describe(const AttnSpec&, const AttnLaunch&);
 int attn_stitch_launch(const AttnSpec&, const AttnLaunch&, const void* const* in, void* const* out,
                        void* stream, std::string* err);
 
-// Generic elementwise stitching: the group compiled to a register program (ew_stitch.hip).
+// Generic elementwise stitching (ew_stitch.hip, ew_codegen.cpp): the group either as a
+// generated kernel or as a register program for the interpreter kernel.
 struct Graph;
 struct EwLaunch {
-  int wg = 256, grid = 1, U = 1, n_slots = 0, n_ins = 0;   // U: chunks a thread carries in lock step
+  int wg = 256, grid = 1, n_ops = 0;
+  std::vector<int> view_param;        // parameter ordinal behind each operand view
+  // generated form
+  bool generated = false;
+  int width = 4;                      // elements per thread
+  int64_t n = 0;
+  std::vector<char> code_object;
+  EwModule loaded;                    // run-time state: the module once it is on a device
+  std::string note;                   // why generation was not used, if it was tried
+  // interpreted form
+  int U = 1, n_slots = 0, n_ins = 0;  // U: chunks a thread carries in lock step
   bool vector = true;
   int64_t lds_bytes = 0;
-  std::vector<char> blob;   // the compiled program (plain data)
+  std::vector<char> blob;             // the compiled program (plain data)
 };
 bool ew_stitch_plan(const Graph&, const LaunchOpts&, EwLaunch*, int* status, std::string* err);
 std::string ew_stitch_describe(const EwLaunch&);
-int ew_stitch_launch(const EwLaunch&, const void* const* in, void* const* out, int n_out, void* stream,
+int ew_stitch_launch(EwLaunch&, const void* const* in, void* const* out, int n_out, void* stream,
                      std::string* err);
+void ew_stitch_release(EwLaunch&);
 
 int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, std::string* err);
 

@@ -15,6 +15,7 @@ struct LaunchOpts {
   int wg_size = 0;
   int rows_per_wave = 0;
   int grid = 0;
+  bool codegen = true;     // schedules that generate their kernel at run time may do so
 };
 
 // ---- schedule 1: elementwise prologue -> row reduce(s) -> broadcast -> epilogue ------

@@ -178,7 +178,10 @@ def test_elementwise_groups_compile_to_one_kernel():
         assert info["workspace_bytes"] == 0
         # four parameters read once, three outputs written once
         assert info["algorithmic_bytes"] == 7 * 64 * 1024 * 4 == info["moved_bytes"]
-        assert "THREAD_4" in p.describe() and "cta_size=256" in p.describe()
+        assert "THREAD_4" in p.describe() and "cta_size=256" in p.describe() and "generated kernel" in p.describe()
+    with Plan(ops, "prebuilt") as p:         # the same group without run-time compilation
+        assert p.info()["schedule"] == "elementwise" and "interpreted" in p.describe()
+        assert p.info()["lds_bytes"] > 0
     with Plan(ops, "per_op") as q:
         assert q.info()["n_kernels"] > 8 and q.info()["moved_bytes"] > 3 * 7 * 64 * 1024 * 4
     # a last extent that is not a multiple of 4: one element per thread
@@ -186,7 +189,7 @@ def test_elementwise_groups_compile_to_one_kernel():
         assert "THREAD_4" not in p.describe()
     # widening converts are free: 16-bit storage, fp32 arithmetic
     with Plan(graphs.bias_gelu_residual(32, 1024, "bf16")) as p:
-        assert p.info()["schedule"] == "elementwise"
+        assert p.info()["schedule"] == "elementwise" and "THREAD_8" in p.describe()   # 16-byte accesses
         assert p.info()["algorithmic_bytes"] == (3 * 32 * 1024 + 1024) * 2
 
 
@@ -197,7 +200,9 @@ def test_elementwise_limits_are_reported():
     for _ in range(70):                      # longer than the register program may be
         y = g.tanh(y)
     g.output(y)
-    e = _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    with Plan(g.ops) as p:                   # the generated kernel has no such limit
+        assert "generated kernel" in p.describe()
+    e = _expect(binding.FS_ERR_UNSUPPORTED, g.ops, mode="prebuilt")
     assert "64 instructions" in str(e)
     g = Graph()
     x = g.parameter("x", "f32", (8, 64))

@@ -1,5 +1,6 @@
-"""GPU parity of the generic elementwise schedule (thread composition + kernel packing
-through the register-program interpreter) against the CPU oracle."""
+"""GPU parity of the generic elementwise schedule (thread composition + kernel packing)
+against the CPU oracle, in both of its forms: the kernel generated for the group
+(mode "stitched") and the register-program interpreter (mode "prebuilt")."""
 import sys
 
 import numpy as np
@@ -25,47 +26,58 @@ def _need_gpu(device):
     yield
 
 
+MODES = ["stitched", "prebuilt"]
+
+
 def _rand(shape, seed, lo=-2.0, hi=2.0):
     return inputs.round_to(np.random.default_rng(seed).uniform(lo, hi, shape), "f32")
 
 
-def test_unary_chain_and_schedule_name():
-    announce("elementwise unary chain")
+@pytest.mark.parametrize("mode", MODES)
+def test_unary_chain_and_schedule_name(mode):
+    announce(f"elementwise unary chain {mode}")
     g = graphs.Graph()
     x = g.parameter("x", "f32", (37, 64))
     g.output(g.exp(g.tanh(x)))
-    with Plan(g.ops) as p:
+    with Plan(g.ops, mode) as p:
         info = p.info()
         assert info["schedule"] == "elementwise" and info["n_kernels"] == 1
-        assert info["lds_bytes"] == 2048        # a pure chain lives in the accumulator: only the program is in LDS
-    check_against_oracle(g.ops, [_rand((37, 64), 1)], what="exp(tanh(x))")
+        # interpreted, a pure chain lives in the accumulator: only the program is in LDS
+        assert info["lds_bytes"] == (0 if mode == "stitched" else 2048)
+    check_against_oracle(g.ops, [_rand((37, 64), 1)], mode, what="exp(tanh(x))")
 
 
-@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 203, 1024), ("f16", 33, 768), ("f32", 65, 1000), ("bf16", 7, 30), ("f32", 5, 3)])
-def test_bias_gelu_residual(dtype, rows, cols):
-    announce(f"elementwise bias+gelu+residual {dtype} {rows}x{cols}")
-    check_against_oracle(graphs.bias_gelu_residual(rows, cols, dtype), inputs.bias_gelu_residual(rows, cols, dtype),
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("dtype,rows,cols", [("bf16", 203, 1024), ("f16", 33, 768), ("f32", 65, 1000), ("bf16", 7, 30), ("f32", 5, 3),
+                                             ("bf16", 19, 1028), ("f16", 3, 8)])
+def test_bias_gelu_residual(dtype, rows, cols, mode):
+    announce(f"elementwise bias+gelu+residual {dtype} {rows}x{cols} {mode}")
+    check_against_oracle(graphs.bias_gelu_residual(rows, cols, dtype), inputs.bias_gelu_residual(rows, cols, dtype), mode,
                          what=f"bias_gelu_residual {dtype} {rows}x{cols}")
 
 
-@pytest.mark.parametrize("shape", [(1000,), (64, 1024), (3, 5, 7), (2, 3, 4, 8), (4099,)])
-def test_adam_update_three_packed_outputs(shape):
-    announce(f"elementwise adam {shape}")
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape", [(1000,), (64, 1024), (3, 5, 7), (2, 3, 4, 8), (4099,), (300, 1024)])
+def test_adam_update_three_packed_outputs(shape, mode):
+    announce(f"elementwise adam {shape} {mode}")
     ops, ins = graphs.adam_update(shape), inputs.adam_update(shape)
-    with Plan(ops) as p:
+    with Plan(ops, mode) as p:
         assert p.info()["schedule"] == "elementwise"
-    check_against_oracle(ops, ins, what=f"adam {shape}")
+    check_against_oracle(ops, ins, mode, what=f"adam {shape}")
 
 
-@pytest.mark.parametrize("dtype,shape", [("f32", (33, 128)), ("f32", (4, 6, 100)), ("bf16", (17, 256)), ("f32", (9, 7)), ("f16", (2, 3, 5, 64))])
-def test_row_and_column_broadcast_operands(dtype, shape):
-    announce(f"elementwise row/col broadcast {dtype} {shape}")
-    check_against_oracle(graphs.scale_shift_rows_cols(shape, dtype), inputs.scale_shift_rows_cols(shape, dtype),
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("dtype,shape", [("f32", (33, 128)), ("f32", (4, 6, 100)), ("bf16", (17, 256)), ("f32", (9, 7)), ("f16", (2, 3, 5, 64)),
+                                         ("bf16", (5, 12)), ("f32", (700, 1024))])
+def test_row_and_column_broadcast_operands(dtype, shape, mode):
+    announce(f"elementwise row/col broadcast {dtype} {shape} {mode}")
+    check_against_oracle(graphs.scale_shift_rows_cols(shape, dtype), inputs.scale_shift_rows_cols(shape, dtype), mode,
                          what=f"rows_cols {dtype} {shape}")
 
 
-def test_diamond_reuse_many_live_values_and_constant_first_operand():
-    announce("elementwise diamond")
+@pytest.mark.parametrize("mode", MODES)
+def test_diamond_reuse_many_live_values_and_constant_first_operand(mode):
+    announce(f"elementwise diamond {mode}")
     g = graphs.Graph()
     a = g.parameter("a", "f32", (40, 96))
     b = g.parameter("b", "f32", (40, 96))
@@ -79,48 +91,76 @@ def test_diamond_reuse_many_live_values_and_constant_first_operand():
     g.output(u)
     g.output(r)
     ops = g.ops
-    with Plan(ops) as plan:
+    with Plan(ops, "prebuilt") as plan:
         assert plan.info()["lds_bytes"] > 2048
-    check_against_oracle(ops, [_rand((40, 96), 2), _rand((40, 96), 3)], what="diamond")
+    check_against_oracle(ops, [_rand((40, 96), 2), _rand((40, 96), 3)], mode, what="diamond")
 
 
-def test_mid_graph_rounding_is_applied():
-    announce("elementwise mid-graph convert")
+@pytest.mark.parametrize("mode", MODES)
+def test_mid_graph_rounding_is_applied(mode):
+    announce(f"elementwise mid-graph convert {mode}")
     g = graphs.Graph()
     x = g.parameter("x", "f32", (16, 64))
     y = g.convert(g.multiply(x, g.constant(1.0009765625)), "bf16")     # rounds here
     z = g.multiply(g.convert(y, "f32"), g.constant(3.0))
     g.output(z)
     xs = _rand((16, 64), 4)
-    (got,) = run_gpu(g.ops, [xs])
+    (got,) = run_gpu(g.ops, [xs], mode)
     (want,) = interp.run(g.ops, [xs], storage_rounding=True)
     assert_close(got, want, 1e-6, "mid-graph bf16 rounding")
 
 
-def test_key_padding_style_broadcast_rank4():
-    announce("elementwise rank-4 broadcast")
+@pytest.mark.parametrize("mode", MODES)
+def test_key_padding_style_broadcast_rank4(mode):
+    announce(f"elementwise rank-4 broadcast {mode}")
     g = graphs.Graph()
     s = g.parameter("s", "f32", (2, 3, 5, 64))
     m = g.parameter("m", "f32", (2, 1, 1, 64))
     g.output(g.add(g.multiply(s, g.constant(0.125)), g.broadcast(m, (2, 3, 5, 64), 0)))
-    check_against_oracle(g.ops, [_rand((2, 3, 5, 64), 5), _rand((2, 1, 1, 64), 6)], what="rank-4 broadcast")
+    check_against_oracle(g.ops, [_rand((2, 3, 5, 64), 5), _rand((2, 1, 1, 64), 6)], mode, what="rank-4 broadcast")
 
 
 def test_elementwise_matches_per_op_and_options():
     announce("elementwise vs per_op")
     ops, ins = graphs.adam_update((129, 512)), inputs.adam_update((129, 512))
-    a = run_gpu(ops, ins, "stitched")
     b = run_gpu(ops, ins, "per_op")
-    for x, y in zip(a, b):
-        assert_close(x, y, 1e-6, "stitched vs per_op")
-    for opts in (dict(wg_size=64), dict(wg_size=128), dict(grid=3)):
-        c = run_gpu(ops, ins, **opts)
-        for x, y in zip(a, c):
-            assert np.array_equal(x, y)
+    for mode in MODES:
+        a = run_gpu(ops, ins, mode)
+        for x, y in zip(a, b):
+            assert_close(x, y, 1e-6, f"{mode} vs per_op")
+        for opts in (dict(wg_size=64), dict(wg_size=128), dict(grid=3), dict(rows_per_wave=2), dict(rows_per_wave=4)):
+            c = run_gpu(ops, ins, mode, **opts)
+            for x, y in zip(a, c):
+                assert np.array_equal(x, y)
+
+
+def test_long_chain_only_the_generated_kernel_takes():
+    announce("elementwise 100-op chain")
+    g = graphs.Graph()
+    x = g.parameter("x", "f32", (33, 64))
+    y = x
+    for i in range(100):
+        y = g.add(g.multiply(y, g.constant(0.99)), g.constant(0.01)) if i % 2 else g.tanh(y)
+    g.output(y)
+    check_against_oracle(g.ops, [_rand((33, 64), 9)], what="100-op chain")
+
+
+def test_tuner_picks_among_generated_and_interpreted_forms():
+    announce("elementwise tune")
+    from gpu_util import to_device, alloc_outputs
+    ops, ins = graphs.adam_update((256, 1024)), inputs.adam_update((256, 1024))
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    with Plan.tune(ops, dev_in, dev_out, trials=5) as plan:
+        assert plan.info()["schedule"] == "elementwise" and plan.tuned["us"] > 0
+    torch.cuda.synchronize()
+    want = interp.run(ops, ins)
+    for t, w in zip(dev_out, want):
+        assert_close(t.to(torch.float64).cpu().numpy(), w, 1e-5, "tuned elementwise")
 
 
 def test_empty_elementwise_group():
     announce("elementwise empty")
     ops = graphs.adam_update((0, 16))
-    out = run_gpu(ops, inputs.adam_update((0, 16)))
-    assert all(o.size == 0 for o in out)
+    for mode in MODES:
+        out = run_gpu(ops, inputs.adam_update((0, 16)), mode)
+        assert all(o.size == 0 for o in out)
