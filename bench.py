@@ -183,7 +183,7 @@ def main():
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
-    from workloads import BY_NAME, CONFIGS
+    from workloads import BY_NAME, CONFIGS, EXTRA_GROUPS
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
@@ -215,6 +215,8 @@ def main():
         kp = dict(shape=(64, 16, 128, 128), mask="key_padding")
         groups["scaled_masked_softmax_key_padding"] = bench_group(BY_NAME["scaled_masked_softmax"], args.steps,
                                                                   args.warmup, build_kw=kp)[0]
+        for cfg in EXTRA_GROUPS:
+            groups[cfg.name] = bench_group(cfg, max(20, args.steps // 4), max(5, args.warmup // 2))[0]
         out["groups"] = groups
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(head)

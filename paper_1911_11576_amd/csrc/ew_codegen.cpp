@@ -55,6 +55,12 @@ static __device__ __forceinline__ unsigned to_bf16(float f) {
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 static __device__ __forceinline__ unsigned to_f16(float f) { return __builtin_bit_cast(unsigned short, (_Float16)f); }
+// tanh(x) = 1 - 2 / (1 + e^(2x)) on the hardware exp2 and reciprocal: absolute error of a
+// few 1e-7; exp2 overflow gives rcp(inf) = 0 -> 1, underflow gives 1 - 2 = -1
+static __device__ __forceinline__ float tanh_fast(float x) {
+  const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+}
 static __device__ __forceinline__ float round_bf16(float f) { return bits_f32(to_bf16(f) << 16); }
 static __device__ __forceinline__ float round_f16(float f) { return (float)(_Float16)f; }
 )SRC";
@@ -73,7 +79,7 @@ std::string operand_text(const EwIrOperand& o) {
   return buf;
 }
 
-std::string op_text(const EwIrNode& n) {
+std::string op_text(const EwIrNode& n, bool fast) {
   const std::string a = operand_text(n.opnd[0]);
   const std::string b = n.n_operands == 2 ? operand_text(n.opnd[1]) : std::string();
   switch (n.op) {
@@ -85,7 +91,7 @@ std::string op_text(const EwIrNode& n) {
     case FS_NEGATE: return "-" + a;
     case FS_EXP: return "expf(" + a + ")";
     case FS_LOG: return "logf(" + a + ")";
-    case FS_TANH: return "tanhf(" + a + ")";
+    case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
     case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
@@ -96,7 +102,7 @@ std::string op_text(const EwIrNode& n) {
 
 }  // namespace
 
-std::string ew_emit_source(const EwIr& ir, int* width, int* unroll) {
+std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name) {
   // Chunk width: as many consecutive elements as one 16-byte access of the narrowest tensor
   // holds, provided every row start stays aligned; otherwise one element.
   const int64_t last = ir.shape[FS_MAX_RANK - 1];
@@ -120,10 +126,15 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll) {
   *unroll = 1;
   bool need_idx = false;
   for (const EwIrView& v : ir.views) if (!v.full) need_idx = true;
+  // A group that stores 16-bit values is compared at 16-bit accuracy: its tanh may take the
+  // short hardware form.  fp32 groups keep the library function.
+  bool fast = false;
+  for (const EwIrView& v : ir.views) if (v.dtype != FS_F32) fast = true;
+  for (const EwIrNode& n : ir.nodes) if (n.out_ordinal >= 0 && n.out_dtype != FS_F32) fast = true;
 
   Emitter e;
   e.s = kPreamble;
-  e.line("extern \"C\" __global__ __launch_bounds__(256) void fs_ew(const Args a) {");
+  e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_EW_NAME(const Args a) {");
   e.line("  constexpr int W = %d;", W);
   e.line("  const long long nchunk = %lldll;", (long long)(ir.n / W));
   e.line("  for (long long ci = (long long)blockIdx.x * blockDim.x + threadIdx.x; ci < nchunk; ci += (long long)gridDim.x * blockDim.x) {");
@@ -182,7 +193,7 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll) {
   // ---- the ops, in order; outputs stored as soon as they exist
   for (const EwIrNode& n : ir.nodes) {
     e.line("    float t%d[W];", n.id);
-    e.line("    UNROLL for (int j = 0; j < W; ++j) t%d[j] = %s;", n.id, op_text(n).c_str());
+    e.line("    UNROLL for (int j = 0; j < W; ++j) t%d[j] = %s;", n.id, op_text(n, fast).c_str());
     if (n.out_ordinal < 0) continue;
     e.line("    {");
     if (n.out_dtype == FS_F32) {
@@ -206,6 +217,15 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll) {
   }
   e.line("  }");
   e.line("}");
+  // the kernel is named after its own text, so that traces tell generated kernels apart
+  uint64_t h = 1469598103934665603ull;
+  for (unsigned char c : e.s) { h ^= c; h *= 1099511628211ull; }
+  char name[32];
+  snprintf(name, sizeof name, "fs_ew_%08x", (unsigned)(h ^ (h >> 32)));
+  *kernel_name = name;
+  const std::string tag = "FS_EW_NAME";
+  const size_t at = e.s.find(tag);
+  e.s.replace(at, tag.size(), name);
   return e.s;
 }
 
@@ -252,8 +272,8 @@ bool ew_compile_source(const std::string& source, std::vector<char>* code_object
   return true;
 }
 
-int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const void* args, size_t args_bytes,
-                     int grid, int block, void* stream, std::string* err) {
+int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const std::string& kernel_name,
+                     const void* args, size_t args_bytes, int grid, int block, void* stream, std::string* err) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) { *err = "hipGetDevice failed"; return -1; }
   if (!m->function) {
@@ -261,7 +281,7 @@ int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const vo
     hipError_t e = hipModuleLoadData(&mod, code_object.data());
     if (e != hipSuccess) { *err = std::string("hipModuleLoadData: ") + hipGetErrorString(e); return -1; }
     hipFunction_t fn = nullptr;
-    e = hipModuleGetFunction(&fn, mod, "fs_ew");
+    e = hipModuleGetFunction(&fn, mod, kernel_name.c_str());
     if (e != hipSuccess) { (void)hipModuleUnload(mod); *err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e); return -1; }
     m->module = mod; m->function = fn; m->device = dev;
   } else if (dev != m->device) {

@@ -43,15 +43,8 @@ struct EwIr {
 
 // ---- kernel generation (Section 5: the stitched op is emitted as code, compiled, cached) ----
 
-struct EwGenerated {
-  int width = 4;                      // consecutive elements per thread and load
-  int unroll = 1;                     // independent chunks a thread handles
-  std::string source;
-  std::vector<char> code_object;      // compiled for gfx950
-};
-
 // HIP source of one kernel computing the whole group; pure text, no GPU or compiler involved.
-std::string ew_emit_source(const EwIr& ir, int* width, int* unroll);
+std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name);
 // Compile with the run-time compiler (works on a machine without a GPU).  Results are cached
 // per process by source text.  False + message if the compiler is unavailable or fails.
 bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err);
@@ -62,8 +55,8 @@ struct EwModule {
   void* function = nullptr;
   int device = -1;
 };
-int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const void* args, size_t args_bytes,
-                     int grid, int block, void* stream, std::string* err);
+int ew_module_launch(EwModule* m, const std::vector<char>& code_object, const std::string& kernel_name,
+                     const void* args, size_t args_bytes, int grid, int block, void* stream, std::string* err);
 void ew_module_release(EwModule* m);
 
 }  // namespace fs

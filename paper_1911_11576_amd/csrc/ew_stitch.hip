@@ -604,7 +604,7 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
   std::string gen_err;
   if (opt.codegen) {
     int width = 1, unroll = 1;
-    const std::string src = ew_emit_source(cc.ir, &width, &unroll);
+    const std::string src = ew_emit_source(cc.ir, &width, &unroll, &l.kernel_name);
     if (const char* dump = getenv("FS_DUMP_SOURCE")) {        // debugging aid: append what was generated
       if (FILE* f = fopen(dump, "a")) { fputs(src.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
     }
@@ -709,8 +709,8 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
 std::string ew_stitch_describe(const EwLaunch& l) {
   char buf[320];
   if (l.generated)
-    snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (generated kernel, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
-             l.width, l.n_ops, l.code_object.size(), l.grid, l.wg);
+    snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
+             l.width, l.n_ops, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg);
   else
     snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (interpreted: %d program steps, %d LDS slots); cta_num=%d, cta_size=%d, lds=%lld",
              (l.vector ? 4 : 1) * l.U, l.n_ops, l.n_ins, l.n_slots, l.grid, l.wg, (long long)l.lds_bytes);
@@ -734,7 +734,7 @@ int ew_stitch_launch(EwLaunch& l, const void* const* in, void* const* out, int n
     EwGenArgs args{};
     for (size_t k = 0; k < l.view_param.size(); ++k) args.in[k] = in[l.view_param[k]];
     for (int k = 0; k < n_out; ++k) args.out[k] = out[k];
-    return ew_module_launch(&l.loaded, l.code_object, &args, sizeof args, l.grid, l.wg, stream, err);
+    return ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
   }
   EwCompiled c;
   memcpy(&c, l.blob.data(), sizeof(EwCompiled));

@@ -54,6 +54,7 @@ struct EwLaunch {
   int width = 4;                      // elements per thread
   int64_t n = 0;
   std::vector<char> code_object;
+  std::string kernel_name;
   EwModule loaded;                    // run-time state: the module once it is on a device
   std::string note;                   // why generation was not used, if it was tried
   // interpreted form

@@ -52,4 +52,12 @@ CONFIGS = [
     Config(5, "layernorm_bwd", graphs.layernorm_bwd, inputs.layernorm_bwd,
            dict(rows=32768, cols=1024), dict(rows=517, cols=1024), "f32"),
 ]
-BY_NAME = {c.name: c for c in CONFIGS}
+# All-elementwise groups measured beside the five (the packing pattern of the backward
+# phase, Section 5.1): not benchmark configs, so not in CONFIGS.
+EXTRA_GROUPS = [
+    Config(6, "adam_update_packed", graphs.adam_update, inputs.adam_update,
+           dict(shape=(16384, 1024)), dict(shape=(129, 512)), "f32"),
+    Config(7, "bias_gelu_residual", graphs.bias_gelu_residual, inputs.bias_gelu_residual,
+           dict(rows=16384, cols=1024, dtype="bf16"), dict(rows=203, cols=1024, dtype="bf16"), "bf16"),
+]
+BY_NAME = {c.name: c for c in CONFIGS + EXTRA_GROUPS}
