@@ -84,11 +84,16 @@ typedef enum {
   FS_MODE_PER_OP = 1,   /* baseline: one kernel per op, intermediates in a plan-owned HBM
                            workspace (the sum of K(Op_j) side of the execution-based
                            score, Section 4.3) */
-  FS_MODE_STITCHED_PREBUILT = 2 /* stitched, but only with kernels compiled into the library:
+  FS_MODE_STITCHED_PREBUILT = 2, /* stitched, but only with kernels compiled into the library:
                            no kernel generation (Section 5.3) and so no compiler run inside
                            fs_plan_create.  Differs from FS_MODE_STITCHED only for
                            FS_SCHED_ELEMENTWISE groups, which then run through the
                            library's register-program interpreter kernel */
+  FS_MODE_STITCHED_GENERATED = 3 /* stitched, preferring a kernel generated for the group
+                           wherever the generators cover it (all-elementwise groups; groups
+                           of elementwise ops and reductions over the last dim), even where
+                           a hand-written kernel matches.  fs_plan_tune times this form
+                           against the hand-written one */
 } fs_mode;
 
 /* Launch parameters a template would carry (cta_size, cta_num and the per-warp tile,
@@ -105,7 +110,10 @@ typedef struct {
 /* Schedule chosen for a stitched plan (fs_plan_info). */
 typedef enum {
   FS_SCHED_PER_OP = 0,
-  FS_SCHED_ROW = 1,      /* elementwise -> row reduce -> broadcast, wavefront reductions */
+  FS_SCHED_ROW = 1,      /* elementwise -> row reduce -> broadcast, wavefront reductions:
+                            hand-written kernels for the recognised patterns (LayerNorm,
+                            softmax, ...), a generated kernel for any other mix of
+                            elementwise ops and reductions over the last dim */
   FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials */
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
   FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as

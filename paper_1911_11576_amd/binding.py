@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("FS_LIB_PATH") or os.path.join(os.path.dirname(os.path
 
 FS_OK, FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_HIP, FS_ERR_NOMEM = range(6)
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID", "FS_ERR_UNSUPPORTED", "FS_ERR_LDS", "FS_ERR_HIP", "FS_ERR_NOMEM"]
-FS_MODE_STITCHED, FS_MODE_PER_OP, FS_MODE_STITCHED_PREBUILT = 0, 1, 2
+FS_MODE_STITCHED, FS_MODE_PER_OP, FS_MODE_STITCHED_PREBUILT, FS_MODE_STITCHED_GENERATED = 0, 1, 2, 3
 SCHEDULE_NAMES = ["per_op", "row", "row_col", "bdot_softmax", "elementwise"]
 
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
@@ -184,7 +184,8 @@ class Plan:
     def __init__(self, ops, mode="stitched", wg_size=0, rows_per_wave=0, grid=0, _handle=None):
         self._h = _handle
         if _handle is None:
-            m = {"stitched": FS_MODE_STITCHED, "per_op": FS_MODE_PER_OP, "prebuilt": FS_MODE_STITCHED_PREBUILT}[mode]
+            m = {"stitched": FS_MODE_STITCHED, "per_op": FS_MODE_PER_OP, "prebuilt": FS_MODE_STITCHED_PREBUILT,
+                 "generated": FS_MODE_STITCHED_GENERATED}[mode]
             self._h = fs_plan_create(ops, m, wg_size, rows_per_wave, grid)
         self.tuned = None
 

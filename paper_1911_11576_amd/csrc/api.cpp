@@ -13,6 +13,7 @@
 #include "launchers.h"
 #include "match.h"
 #include "per_op.h"
+#include "row_codegen.h"
 
 struct fs_plan {
   fs::Graph graph;
@@ -22,7 +23,8 @@ struct fs_plan {
   fs::RowLaunch row;
   fs::RowTeamLaunch row_team;
   fs::RowBlockLaunch row_block;
-  int row_form = 0;   // 0 one wavefront per row group, 1 wavefront team, 2 row cached in LDS
+  fs::RowGenLaunch row_gen;
+  int row_form = 0;   // 0 one wavefront per row group, 1 wavefront team, 2 row cached in LDS, 3 generated kernel
   fs::LnBwdLaunch lnbwd;
   fs::AttnLaunch attn;
   fs::EwLaunch ew;
@@ -58,14 +60,17 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
   try {
     if (!fs::build_graph(ops, n_ops, &p->graph, &err)) { delete p; return set_error(FS_ERR_INVALID, err); }
     fs::LaunchOpts lo;
+    bool want_generated = false;
     if (opt) {
-      if (opt->mode != FS_MODE_STITCHED && opt->mode != FS_MODE_PER_OP && opt->mode != FS_MODE_STITCHED_PREBUILT) {
+      if (opt->mode != FS_MODE_STITCHED && opt->mode != FS_MODE_PER_OP && opt->mode != FS_MODE_STITCHED_PREBUILT &&
+          opt->mode != FS_MODE_STITCHED_GENERATED) {
         delete p;
         return set_error(FS_ERR_INVALID, "unknown mode");
       }
       if (opt->wg_size < 0 || opt->rows_per_wave < 0 || opt->grid < 0) { delete p; return set_error(FS_ERR_INVALID, "negative launch option"); }
       p->mode = opt->mode == FS_MODE_PER_OP ? FS_MODE_PER_OP : FS_MODE_STITCHED;
       lo.codegen = opt->mode != FS_MODE_STITCHED_PREBUILT;
+      want_generated = opt->mode == FS_MODE_STITCHED_GENERATED;
       lo.wg_size = opt->wg_size; lo.rows_per_wave = opt->rows_per_wave; lo.grid = opt->grid;
     }
     const int64_t algo = p->graph.algorithmic_bytes();
@@ -78,19 +83,35 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
       p->description = fs::per_op_describe(p->per_op);
     } else {
       p->moved_bytes = algo;
-      if (!fs::recognise(p->graph, &p->match)) {
-        // not one of the reduce / dot patterns: an all-elementwise group still stitches
-        std::string why = p->match.why;
-        int st = FS_OK;
-        if (!fs::ew_stitch_plan(p->graph, lo, &p->ew, &st, &err)) {
-          if (st == FS_ERR_UNSUPPORTED && why != "no stitched schedule matches this group") err = why;
+      const bool recognised = fs::recognise(p->graph, &p->match);
+      if (!recognised || want_generated) {
+        // Not one of the hand-written reduce / dot patterns (or the caller prefers generated
+        // kernels): an all-elementwise group stitches as schedule 0, a group of elementwise
+        // ops and row reductions as a generated row kernel.
+        const std::string why = p->match.why;
+        bool has_reduce = false;
+        for (const fs::Node& x : p->graph.nodes) if (x.kind == FS_REDUCE_SUM || x.kind == FS_REDUCE_MAX) has_reduce = true;
+        int st = FS_OK, st2 = FS_ERR_UNSUPPORTED;
+        std::string err2;
+        if (fs::ew_stitch_plan(p->graph, lo, &p->ew, &st, &err)) {
+          p->match.kind = fs::MATCH_NONE;
+          p->schedule = FS_SCHED_ELEMENTWISE;
+          p->lds_bytes = p->ew.lds_bytes;
+          p->description = fs::ew_stitch_describe(p->ew);
+        } else if (lo.codegen && has_reduce && fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) {
+          p->match.kind = fs::MATCH_NONE;
+          p->schedule = FS_SCHED_ROW;
+          p->row_form = 3;
+          p->description = fs::row_gen_describe(p->row_gen);
+        } else if (!recognised) {
+          if (has_reduce && lo.codegen) { st = st2; err = err2; }
+          if (st == FS_ERR_UNSUPPORTED && why != "no stitched schedule matches this group") err = why + " (" + err + ")";
           delete p;
           return set_error((fs_status)st, err);
+        } else if (st2 == FS_ERR_INVALID) {
+          delete p;
+          return set_error(FS_ERR_INVALID, err2);
         }
-        p->match.kind = fs::MATCH_NONE;
-        p->schedule = FS_SCHED_ELEMENTWISE;
-        p->lds_bytes = p->ew.lds_bytes;
-        p->description = fs::ew_stitch_describe(p->ew);
       }
       switch (p->match.kind) {
         case fs::MATCH_NONE: break;   // elementwise schedule, set up above
@@ -187,7 +208,8 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
     int rc = 0;
     switch (p->schedule) {
       case FS_SCHED_ROW:
-        rc = p->row_form == 2   ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
+        rc = p->row_form == 3   ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, hip_stream, &err)
+             : p->row_form == 2 ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
              : p->row_form == 1 ? fs::row_team_launch(p->match.row, p->row_team, inputs, outputs, hip_stream, &err)
                                 : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
         break;
@@ -220,10 +242,12 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
   if (base->schedule == FS_SCHED_ROW && base->row_form == 0) {
     for (int wg : {128, 256, 512})
       for (int u : {1, 2, 4}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, u, 0});
-  } else if (base->schedule == FS_SCHED_ROW && base->row_form == 1) {
-    for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});   // hand-written against generated
+  } else if (base->schedule == FS_SCHED_ROW && base->row_form == 3) {
+    for (int wg : {64, 128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
   } else if (base->schedule == FS_SCHED_ROW) {
     for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});
   } else if (base->schedule == FS_SCHED_ROW_COL) {
     for (int wg : {256, 384, 512})
       for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
@@ -296,6 +320,7 @@ fs_status fs_destroy(fs_plan* p) {
     if (e != hipSuccess) st = set_error(FS_ERR_HIP, std::string("hipFree: ") + hipGetErrorString(e));
   }
   fs::ew_stitch_release(p->ew);
+  fs::row_gen_release(p->row_gen);
   delete p;
   return st;
 }

@@ -65,7 +65,6 @@ static __device__ __forceinline__ float round_bf16(float f) { return bits_f32(to
 static __device__ __forceinline__ float round_f16(float f) { return (float)(_Float16)f; }
 )SRC";
 
-int dtype_bytes(int dt) { return dt == FS_F32 ? 4 : 2; }
 
 std::string operand_text(const EwIrOperand& o) {
   char buf[64];
@@ -101,6 +100,8 @@ std::string op_text(const EwIrNode& n, bool fast) {
 }
 
 }  // namespace
+
+const char* ew_preamble() { return kPreamble; }
 
 std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name) {
   // Chunk width: as many consecutive elements as one 16-byte access of the narrowest tensor

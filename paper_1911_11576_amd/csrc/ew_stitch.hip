@@ -1,17 +1,18 @@
 // Schedule 0, generic elementwise stitching (paper Section 5.1: thread composition of
 // data-dependent elementwise ops, and kernel packing of independent ones, merged into one
 // loop): ANY group made only of elementwise ops, converts, broadcasts and constants, with
-// any number of outputs, runs as one kernel that reads every parameter once and writes
-// every output once.
+// up to 8 outputs, runs as one kernel that reads every parameter once and writes every
+// output once.
 //
-// There is no code generation at run time, so the fused loop body is not emitted but
-// interpreted: the plan compiles the group into a short register program (load, ALU op,
-// store; at most 64 instructions) that every thread executes on its own 4 elements.  The
-// program counter is uniform across the chip, so each step is a scalar branch.  Values
-// that are used by the next instruction stay in a VGPR accumulator; values with a later
-// use live in a per-thread LDS slot (a register file of float4 slots, slot-major so that
-// a wavefront's access is conflict-free).  Slots are reused by liveness.  RegisterPlanning
-// in the paper's sense falls out: an op with several consumers is computed once.
+// This file holds the analysis of such a group (resolved ops, operand views), the plan and
+// launch steps, and the form that needs no compiler at run time: the group compiled into a
+// short register program (load, ALU op, store; at most 64 steps) that an interpreter kernel
+// executes.  The program counter is uniform across the chip, so each step is a scalar
+// branch tree.  Values used by the next step stay in a VGPR accumulator; values with a later
+// use live in a per-thread LDS slot (a register file of float4 slots, slot-major so that a
+// wavefront's access is conflict-free), reused by liveness.  RegisterPlanning in the
+// paper's sense falls out: an op with several consumers is computed once.
+// The default form, a kernel generated for the group, is in ew_codegen.cpp.
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>

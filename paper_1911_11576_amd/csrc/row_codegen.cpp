@@ -1,0 +1,539 @@
+// Kernel generation for row groups (paper Section 5.1, warp composition: a reduction and the
+// ops that consume its result run in one kernel, the reduced value handed over in
+// registers; Section 5.3: the stitched op is emitted as code).
+//
+// A row group has one "full" shape [R..., C]; its values are either full (one per element) or
+// per-row (shape [R...]: results of reductions over the last dim and arithmetic on them).
+// Any DAG of elementwise ops on full values, reductions full -> per-row, elementwise ops on
+// per-row values, and per-row values broadcast back into full ops is accepted, with full
+// and per-row outputs in any number up to 8.  The generated kernel gives each row to L
+// lanes (L = 1: the THREAD template of Section 5.2 for tiny rows, sequential reduction in
+// one thread; L = 2..64: the WARP template, lanes combine with DPP / permlane steps); a
+// lane keeps its K chunks of W consecutive elements of every live full value in registers
+// from the row's one read to its one write.
+#include "row_codegen.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+namespace fs {
+
+const char* ew_preamble();   // ew_codegen.cpp: typedefs, Args, dtype conversion helpers
+
+namespace {
+
+enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2 };
+enum OpndKind : int { OP_NODE = 0, OP_ROWB = 1, OP_VIEW = 2, OP_CONST = 3 };
+
+struct Opnd { int kind = OP_NODE; int index = -1; float cval = 0.f; };
+struct RNode {
+  int id = -1, op = 0, cls = CLS_NONE, nop = 1;
+  Opnd o[2];
+  int out_ord = -1, out_dtype = FS_F32;
+};
+struct RView {
+  int param = -1, dtype = FS_F32, cls = CLS_FULL;
+  int64_t stride[FS_MAX_RANK] = {0, 0, 0, 0};   // over the dims of the full shape (row views: last unused)
+};
+
+struct Analysis {
+  const Graph& g;
+  std::string err;
+  int rank = 0;
+  int64_t S[FS_MAX_RANK] = {1, 1, 1, 1};
+  int64_t rows = 1, cols = 1;
+  std::vector<int> cls;
+  std::vector<RNode> nodes;
+  std::vector<RView> views;
+  int n_reduce = 0;
+
+  explicit Analysis(const Graph& gr) : g(gr) {}
+  bool fail(const std::string& m) { err = m; return false; }
+
+  static bool is_reduce(int k) { return k == FS_REDUCE_SUM || k == FS_REDUCE_MAX; }
+  int canon(int n) const {
+    while (g[n].kind == FS_CONVERT && g[n].dtype == FS_F32) n = g[n].operand[0];
+    return n;
+  }
+  bool is_compute(int n) const {
+    const int k = g[n].kind;
+    return (is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k)) && canon(n) == n;
+  }
+  bool shape_is_full(const Node& x) const {
+    if (x.rank != rank) return false;
+    for (int d = 0; d < rank; ++d) if (x.shape[d] != S[d]) return false;
+    return true;
+  }
+  bool shape_is_row(const Node& x) const {
+    if (x.rank != rank - 1) return false;
+    for (int d = 0; d < rank - 1; ++d) if (x.shape[d] != S[d]) return false;
+    return true;
+  }
+
+  // Leaf (parameter seen through broadcasts and widening converts, or constant) -> strides
+  // over the dims of node n's own shape.  False if a computed value sits below a broadcast.
+  bool leaf_strides(int n, int* base, int64_t* stride, bool* is_const, float* cval) {
+    n = canon(n);
+    const Node& x = g[n];
+    *is_const = false;
+    if (x.kind == FS_CONSTANT) { *is_const = true; *cval = (float)x.attr; return true; }
+    if (x.kind == FS_BROADCAST) {
+      int64_t inner[FS_MAX_RANK] = {0, 0, 0, 0};
+      if (!leaf_strides(x.operand[0], base, inner, is_const, cval)) return false;
+      if (*is_const) return true;
+      const Node& a = g[x.operand[0]];
+      for (int d = 0; d < x.rank; ++d) stride[d] = 0;
+      for (int d = 0; d < a.rank; ++d) stride[x.axis + d] = a.shape[d] == 1 ? 0 : inner[d];
+      return true;
+    }
+    if (x.kind != FS_PARAMETER) return fail("generated row schedule: a computed value is broadcast in a way other than per-row");
+    *base = n;
+    int64_t st = 1;
+    for (int d = x.rank - 1; d >= 0; --d) { stride[d] = st; st *= x.shape[d]; }
+    return true;
+  }
+
+  int view_index(int base, const int64_t* stride, int c) {
+    for (size_t k = 0; k < views.size(); ++k) {
+      bool same = views[k].param == g[base].ordinal && views[k].cls == c;
+      for (int d = 0; d < FS_MAX_RANK && same; ++d) same = views[k].stride[d] == stride[d];
+      if (same) return (int)k;
+    }
+    RView v;
+    v.param = g[base].ordinal; v.dtype = g[base].dtype; v.cls = c;
+    for (int d = 0; d < FS_MAX_RANK; ++d) v.stride[d] = stride[d];
+    views.push_back(v);
+    return (int)views.size() - 1;
+  }
+
+  bool operand(int n, int consumer_cls, Opnd* o) {
+    const int c = canon(n);
+    if (is_compute(c)) {
+      if (cls[c] != consumer_cls) return fail("generated row schedule: operand of the wrong shape class");
+      o->kind = OP_NODE; o->index = c;
+      return true;
+    }
+    // a per-row value broadcast along the last dim into a full op
+    if (g[c].kind == FS_BROADCAST && consumer_cls == CLS_FULL) {
+      const int src = canon(g[c].operand[0]);
+      if (is_compute(src)) {
+        if (cls[src] != CLS_ROW || !shape_is_full(g[c]) || (g[src].rank > 0 && g[c].axis != 0))
+          return fail("generated row schedule: only per-row values may be broadcast back");
+        o->kind = OP_ROWB; o->index = src;
+        return true;
+      }
+    }
+    int base = -1;
+    int64_t st[FS_MAX_RANK] = {0, 0, 0, 0};
+    bool is_const = false;
+    float cv = 0.f;
+    if (!leaf_strides(c, &base, st, &is_const, &cv)) return false;
+    if (is_const) { o->kind = OP_CONST; o->cval = cv; return true; }
+    const Node& shp = g[c];
+    if (consumer_cls == CLS_FULL ? !shape_is_full(shp) : !shape_is_row(shp))
+      return fail("generated row schedule: operand shape differs from its consumer's");
+    o->kind = OP_VIEW;
+    o->index = view_index(base, st, consumer_cls);
+    return true;
+  }
+
+  bool run() {
+    const int n = g.size();
+    // the full shape is the operand shape of the first reduction
+    int first = -1;
+    for (int i = 0; i < n && first < 0; ++i) if (is_reduce(g[i].kind)) first = i;
+    if (first < 0) return fail("generated row schedule: no reduction in the group");
+    const Node& src = g[g[first].operand[0]];
+    rank = src.rank;
+    if (rank < 1) return fail("generated row schedule: rank-0 reduction");
+    for (int d = 0; d < rank; ++d) S[d] = src.shape[d];
+    cols = S[rank - 1];
+    rows = 1;
+    for (int d = 0; d + 1 < rank; ++d) rows *= S[d];
+    cls.assign(n, CLS_NONE);
+    std::vector<int> out_ord(n, -1), out_dtype(n, 0);
+    for (int o : g.outputs) {
+      const int s = canon(g[o].operand[0]);
+      if (!is_compute(s)) return fail("generated row schedule: an output that is a plain copy of an input");
+      if (out_ord[s] >= 0) return fail("generated row schedule: one value feeds two outputs");
+      out_ord[s] = g[o].ordinal;
+      out_dtype[s] = g[o].dtype;
+    }
+    if (g.outputs.size() > 8) return fail("generated row schedule: more than 8 outputs");
+    for (int i = 0; i < n; ++i) {
+      const Node& x = g[i];
+      const int k = x.kind;
+      if (k == FS_PARAMETER || k == FS_CONSTANT || k == FS_BROADCAST || k == FS_OUTPUT) continue;
+      if (!(is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k)))
+        return fail(std::string("generated row schedule: op ") + kind_name(k) + " is not elementwise or a reduction");
+      if (!is_compute(i)) continue;       // widening convert: alias
+      RNode r;
+      r.id = i;
+      if (is_reduce(k)) {
+        if (x.axis != rank - 1 || !shape_is_row(x)) return fail("generated row schedule: reduction not over the last dim of the group's shape");
+        r.cls = CLS_ROW; r.op = k; r.nop = 1;
+        cls[i] = CLS_ROW;
+        if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
+        ++n_reduce;
+      } else {
+        r.cls = shape_is_full(x) ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
+        if (r.cls == CLS_NONE) return fail("generated row schedule: an op whose shape is neither the group's nor its row shape");
+        cls[i] = r.cls;
+        r.op = k == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : k;
+        r.nop = is_binary(k) ? 2 : 1;
+        for (int j = 0; j < r.nop; ++j) if (!operand(x.operand[j], r.cls, &r.o[j])) return false;
+        if (r.nop == 2 && r.o[0].kind == OP_CONST && r.o[1].kind == OP_CONST) return fail("generated row schedule: op of two constants");
+      }
+      r.out_ord = out_ord[i];
+      r.out_dtype = out_dtype[i];
+      nodes.push_back(r);
+    }
+    if (views.size() > 12) return fail("generated row schedule: more than 12 distinct operand views");
+    return true;
+  }
+};
+
+struct Emitter {
+  std::string s;
+  void line(const char* fmt, ...) __attribute__((format(printf, 2, 3))) {
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    s += buf;
+    s += '\n';
+  }
+};
+
+// wave64 all-reduce over aligned groups of L lanes: DPP inside a 16-lane row, the gfx950
+// permlane swaps across rows; every lane of the wavefront must be active
+const char* kReducePreamble = R"SRC(
+template <int CTRL> static __device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+struct SumOp { static __device__ __forceinline__ float apply(float a, float b) { return a + b; } };
+struct MaxOp { static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); } };
+template <class Op, int L> static __device__ __forceinline__ float lanes_allreduce(float v) {
+  if (L >= 2) v = Op::apply(v, dpp_move<0xB1>(v));
+  if (L >= 4) v = Op::apply(v, dpp_move<0x4E>(v));
+  if (L >= 8) v = Op::apply(v, dpp_move<0x141>(v));
+  if (L >= 16) v = Op::apply(v, dpp_move<0x140>(v));
+  if (L >= 32) {
+    const unsigned u = f32_bits(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned lo = r[0], hi = r[1];
+    v = Op::apply(bits_f32(lo), bits_f32(hi));
+  }
+  if (L >= 64) {
+    const unsigned u = f32_bits(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned lo = r[0], hi = r[1];
+    v = Op::apply(bits_f32(lo), bits_f32(hi));
+  }
+  return v;
+}
+)SRC";
+
+std::string const_text(float c) {
+  uint32_t u;
+  memcpy(&u, &c, 4);
+  char buf[40];
+  snprintf(buf, sizeof buf, "bits_f32(0x%08xu)", u);
+  return buf;
+}
+
+struct Gen {
+  const Analysis& A;
+  int L = 64, K = 1, W = 4;
+  bool exact = true;          // K*L chunks cover the row exactly
+  bool fast = false;          // 16-bit group: short tanh
+  std::vector<int> splat;     // per view: 1 if one scalar per row (last stride 0 or row view)
+  Emitter e;
+
+  explicit Gen(const Analysis& a) : A(a) {}
+
+  std::string opnd(const Opnd& o, int consumer_cls) const {
+    char buf[64];
+    switch (o.kind) {
+      case OP_NODE: snprintf(buf, sizeof buf, consumer_cls == CLS_FULL ? "t%d[k][j]" : "r%d", o.index); return buf;
+      case OP_ROWB: snprintf(buf, sizeof buf, "r%d", o.index); return buf;
+      case OP_VIEW: snprintf(buf, sizeof buf, splat[o.index] ? "s%d" : "v%d[k][j]", o.index); return buf;
+      default: return const_text(o.cval);
+    }
+  }
+  std::string expr(const RNode& n) const {
+    const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
+    switch (n.op) {
+      case FS_ADD: return a + " + " + b;
+      case FS_SUBTRACT: return a + " - " + b;
+      case FS_MULTIPLY: return a + " * " + b;
+      case FS_DIVIDE:
+        // a full value divided by a per-row value: one reciprocal per row, then multiplies
+        if (n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) { char buf[32]; snprintf(buf, sizeof buf, "inv%d", n.o[1].index); return a + " * " + buf; }
+        return a + " / " + b;
+      case FS_MAXIMUM: return "fmaxf(" + a + ", " + b + ")";
+      case FS_NEGATE: return "-" + a;
+      case FS_EXP: return "expf(" + a + ")";
+      case FS_LOG: return "logf(" + a + ")";
+      case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
+      case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
+      case FS_SQRT: return "sqrtf(" + a + ")";
+      case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
+      case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
+      default: return a;
+    }
+  }
+
+  // offset of the row's first element in a view: "row * c" if the row strides are those of
+  // a dense tensor scaled by a constant, else from the row's coordinates
+  std::string row_offset(const RView& v, bool* needs_coords) const {
+    const int nrow = A.rank - 1;
+    char buf[160];
+    if (nrow == 0) return "0";
+    const int64_t unit = v.stride[nrow - 1];
+    bool linear = true;
+    int64_t mul = 1;
+    for (int d = nrow - 1; d >= 0; --d) {
+      if (A.S[d] != 1 && v.stride[d] != unit * mul) linear = false;
+      mul *= A.S[d];
+    }
+    if (linear) {
+      if (unit == 0) return "0";
+      snprintf(buf, sizeof buf, "row * %lldll", (long long)unit);
+      return buf;
+    }
+    *needs_coords = true;
+    std::string off;
+    for (int d = 0; d < nrow; ++d) {
+      if (v.stride[d] == 0 || A.S[d] == 1) continue;
+      snprintf(buf, sizeof buf, "%si%d * %lldll", off.empty() ? "" : " + ", d, (long long)v.stride[d]);
+      off += buf;
+    }
+    return off.empty() ? "0" : off;
+  }
+
+  bool geometry(std::string* err) {
+    bool any32 = false, any16 = false;
+    for (const RView& v : A.views) {
+      if (v.dtype != FS_F32) any16 = true;
+      if (v.cls == CLS_FULL && v.stride[A.rank - 1] == 1 && v.dtype == FS_F32) any32 = true;
+    }
+    for (const RNode& n : A.nodes) if (n.out_ord >= 0) {
+      if (n.out_dtype != FS_F32) any16 = true;
+      if (n.cls == CLS_FULL && n.out_dtype == FS_F32) any32 = true;
+    }
+    fast = any16;
+    auto fits = [&](int w) {
+      if (A.cols % w) return false;
+      for (const RView& v : A.views) {
+        if (v.cls != CLS_FULL) continue;
+        const int64_t ls = v.stride[A.rank - 1];
+        if (ls != 0 && ls != 1) return false;
+        if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
+      }
+      return true;
+    };
+    if (!any32 && fits(8)) W = 8;
+    else if (fits(4)) W = 4;
+    else if (fits(1)) W = 1;
+    else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
+    const int64_t nvec = A.cols / W;
+    // tiny rows: one thread per row (sequential reduction); otherwise the fewest lanes that
+    // keep at most 8 chunks per lane
+    if (W == 1 ? nvec <= 32 : nvec <= 4) { L = 1; K = (int)nvec; }
+    else {
+      L = 2;
+      while (L < 64 && (nvec + L - 1) / L > (W == 8 ? 2 : 4)) L *= 2;
+      K = (int)((nvec + L - 1) / L);
+    }
+    if ((int64_t)K * W > 32) { *err = "generated row schedule: row too long for one wavefront's registers"; return false; }
+    exact = (int64_t)K * L == nvec;
+    return true;
+  }
+
+  void emit(std::string* kernel_name) {
+    const int rank = A.rank, nrow = rank - 1;
+    e.s = ew_preamble();
+    e.s += kReducePreamble;
+    e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_ROW_NAME(const Args a) {");
+    e.line("  constexpr int L = %d, K = %d, W = %d;", L, K, W);
+    e.line("  const int lane = threadIdx.x & (L - 1);");
+    e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
+    e.line("  const bool row_ok = row < %lldll;", (long long)A.rows);
+    e.line("  if (!row_ok) row = %lldll;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", (long long)A.rows - 1);
+    // which views need the row's coordinates
+    splat.assign(A.views.size(), 0);
+    std::vector<std::string> roff(A.views.size());
+    bool coords = false;
+    for (size_t q = 0; q < A.views.size(); ++q) {
+      const RView& v = A.views[q];
+      roff[q] = row_offset(v, &coords);
+      splat[q] = v.cls == CLS_ROW || v.stride[rank - 1] == 0;
+    }
+    if (coords) {
+      const bool small = A.rows <= 0x7fffffffLL;
+      const char* ty = small ? "unsigned" : "unsigned long long";
+      const char* sfx = small ? "u" : "ull";
+      e.line("  %s rr = (%s)row;", ty, ty);
+      for (int d = nrow - 1; d >= 0; --d) {
+        if (A.S[d] == 1) { e.line("  const long long i%d = 0;", d); continue; }
+        e.line("  const long long i%d = rr %% %lld%s; rr /= %lld%s;", d, (long long)A.S[d], sfx, (long long)A.S[d], sfx);
+      }
+    }
+    e.line("  int col[K]; bool ok[K];");
+    e.line("  UNROLL for (int k = 0; k < K; ++k) { const int c = k * L + lane; ok[k] = c < %lld; col[k] = (ok[k] ? c : 0) * W; }",
+           (long long)(A.cols / W));
+    // ---- loads
+    for (size_t q = 0; q < A.views.size(); ++q) {
+      const RView& v = A.views[q];
+      const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+      const char* one = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
+      if (splat[q]) {
+        e.line("  float s%zu;", q);
+        e.line("  { const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s); s%zu = %s; }", ty, ty, q, roff[q].c_str(), q, one);
+        continue;
+      }
+      // tensors of the group's own shape stream through once; per-column operands are shared by all rows
+      bool dense = true;
+      for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] == 0) dense = false;
+      const char* ld = dense ? "__builtin_nontemporal_load" : "*";
+      e.line("  float v%zu[K][W];", q);
+      e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+      e.line("    const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s) + col[k];", ty, ty, q, roff[q].c_str());
+      if (W == 1) {
+        e.line("    v%zu[k][0] = %s;", q, one);
+      } else if (v.dtype == FS_F32) {
+        for (int h = 0; h < W / 4; ++h) {
+          e.line("    { const f32x4 x = %s(reinterpret_cast<const f32x4*>(p) + %d);", ld, h);
+          e.line("      UNROLL for (int j = 0; j < 4; ++j) v%zu[k][%d + j] = x[j]; }", q, 4 * h);
+        }
+      } else {
+        const char* lo = v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
+        const char* hi = v.dtype == FS_F16 ? "f16_hi" : "bf16_hi";
+        e.line("    const %s x = %s(reinterpret_cast<const %s*>(p));", W == 8 ? "u32x4" : "u32x2", ld, W == 8 ? "u32x4" : "u32x2");
+        e.line("    UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[k][2 * j] = %s(x[j]); v%zu[k][2 * j + 1] = %s(x[j]); }", q, lo, q, hi);
+      }
+      e.line("  }");
+    }
+    // ---- ops in order
+    std::vector<char> inv_done(A.g.size(), 0);
+    for (const RNode& n : A.nodes) {
+      const bool reduce = n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX;
+      if (reduce) {
+        const bool sum = n.op == FS_REDUCE_SUM;
+        const std::string x = opnd(n.o[0], CLS_FULL);
+        e.line("  float r%d = %s;", n.id, sum ? "0.0f" : "-__builtin_inff()");
+        e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+        if (!exact) e.line("    if (!ok[k]) continue;");
+        e.line("    UNROLL for (int j = 0; j < W; ++j) r%d = %s;", n.id,
+               sum ? ("r" + std::to_string(n.id) + " + " + x).c_str() : ("fmaxf(r" + std::to_string(n.id) + ", " + x + ")").c_str());
+        e.line("  }");
+        if (L > 1) e.line("  r%d = lanes_allreduce<%s, L>(r%d);", n.id, sum ? "SumOp" : "MaxOp", n.id);
+      } else if (n.cls == CLS_ROW) {
+        e.line("  const float r%d = %s;", n.id, expr(n).c_str());
+      } else {
+        if (n.op == FS_DIVIDE && n.o[1].kind == OP_ROWB && !inv_done[n.o[1].index]) {
+          e.line("  const float inv%d = 1.0f / r%d;", n.o[1].index, n.o[1].index);
+          inv_done[n.o[1].index] = 1;
+        }
+        e.line("  float t%d[K][W];", n.id);
+        e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) t%d[k][j] = %s;", n.id, expr(n).c_str());
+      }
+      if (n.out_ord < 0) continue;
+      if (n.cls == CLS_ROW) {
+        if (n.out_dtype == FS_F32) e.line("  if (lane == 0 && row_ok) static_cast<float*>(a.out[%d])[row] = r%d;", n.out_ord, n.id);
+        else e.line("  if (lane == 0 && row_ok) static_cast<unsigned short*>(a.out[%d])[row] = (unsigned short)%s(r%d);", n.out_ord,
+                    n.out_dtype == FS_F16 ? "to_f16" : "to_bf16", n.id);
+        continue;
+      }
+      e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+      e.line("    if (!(row_ok && ok[k])) continue;");
+      if (n.out_dtype == FS_F32) {
+        e.line("    float* p = static_cast<float*>(a.out[%d]) + row * %lldll + col[k];", n.out_ord, (long long)A.cols);
+        if (W == 1) e.line("    p[0] = t%d[k][0];", n.id);
+        else for (int h = 0; h < W / 4; ++h)
+          e.line("    __builtin_nontemporal_store(f32x4{t%d[k][%d], t%d[k][%d], t%d[k][%d], t%d[k][%d]}, reinterpret_cast<f32x4*>(p) + %d);",
+                 n.id, 4 * h, n.id, 4 * h + 1, n.id, 4 * h + 2, n.id, 4 * h + 3, h);
+      } else {
+        const char* cv = n.out_dtype == FS_F16 ? "to_f16" : "to_bf16";
+        e.line("    unsigned short* p = static_cast<unsigned short*>(a.out[%d]) + row * %lldll + col[k];", n.out_ord, (long long)A.cols);
+        if (W == 1) e.line("    p[0] = (unsigned short)%s(t%d[k][0]);", cv, n.id);
+        else {
+          e.line("    unsigned w[W / 2];");
+          e.line("    UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[k][2 * j]) | (%s(t%d[k][2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+          if (W == 8) e.line("    __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
+          else e.line("    __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
+        }
+      }
+      e.line("  }");
+    }
+    e.line("}");
+    uint64_t h = 1469598103934665603ull;
+    for (unsigned char c : e.s) { h ^= c; h *= 1099511628211ull; }
+    char name[32];
+    snprintf(name, sizeof name, "fs_row_%08x", (unsigned)(h ^ (h >> 32)));
+    *kernel_name = name;
+    const std::string tag = "FS_ROW_NAME";
+    e.s.replace(e.s.find(tag), tag.size(), name);
+  }
+};
+
+struct GenArgs { const void* in[12]; void* out[8]; };
+
+}  // namespace
+
+bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int* status, std::string* err) {
+  *status = FS_ERR_UNSUPPORTED;
+  Analysis A(g);
+  if (!A.run()) { *err = A.err; return false; }
+  Gen gen(A);
+  if (!gen.geometry(err)) return false;
+  RowGenLaunch l;
+  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
+    *status = FS_ERR_INVALID;
+    *err = "generated row schedule: wg_size must be 64, 128, 192 or 256";
+    return false;
+  }
+  gen.emit(&l.kernel_name);
+  if (const char* dump = getenv("FS_DUMP_SOURCE")) {
+    if (FILE* f = fopen(dump, "a")) { fputs(gen.e.s.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
+  }
+  std::string cerr;
+  if (!ew_compile_source(gen.e.s, &l.code_object, &cerr)) { *err = "generated row schedule: " + cerr; return false; }
+  l.L = gen.L; l.K = gen.K; l.W = gen.W;
+  l.rows = A.rows; l.cols = A.cols;
+  l.n_ops = (int)A.nodes.size();
+  l.n_reduce = A.n_reduce;
+  for (const RView& v : A.views) l.view_param.push_back(v.param);
+  l.wg = opt.wg_size ? opt.wg_size : 256;
+  const int64_t rows_per_wg = l.wg / l.L;
+  int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
+  if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
+  l.grid = (int)(grid < 1 ? 1 : grid);
+  *out = l;
+  *status = FS_OK;
+  return true;
+}
+
+std::string row_gen_describe(const RowGenLaunch& l) {
+  char buf[320];
+  snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
+           l.n_reduce, l.L == 1 ? "THREAD" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : "WARP", l.K * l.W,
+           l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg);
+  return buf;
+}
+
+int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int n_out, void* stream, std::string* err) {
+  if (l.rows == 0 || l.cols == 0) return 0;
+  GenArgs args{};
+  for (size_t k = 0; k < l.view_param.size(); ++k) args.in[k] = in[l.view_param[k]];
+  for (int k = 0; k < n_out && k < 8; ++k) args.out[k] = out[k];
+  return ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
+}
+
+void row_gen_release(RowGenLaunch& l) { ew_module_release(&l.loaded); }
+
+}  // namespace fs

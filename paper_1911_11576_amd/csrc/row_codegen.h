@@ -1,0 +1,30 @@
+// Generated form of the row schedule (warp composition, paper Section 5.1, emitted as code,
+// Section 5.3): any group of elementwise ops and reductions over the last dim, in any
+// order and depth, whose row fits the registers of up to 64 lanes.  See row_codegen.cpp.
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "ew_ir.h"
+#include "graph.h"
+#include "specs.h"
+
+namespace fs {
+
+struct RowGenLaunch {
+  int wg = 256, grid = 1;
+  int L = 64, K = 1, W = 4;           // lanes per row, chunks per lane, elements per chunk
+  int n_ops = 0, n_reduce = 0;
+  int64_t rows = 0, cols = 0;
+  std::vector<int> view_param;        // parameter ordinal behind each operand view
+  std::vector<char> code_object;
+  std::string kernel_name;
+  EwModule loaded;                    // run-time state: the module once it is on a device
+};
+bool row_gen_plan(const Graph&, const LaunchOpts&, RowGenLaunch*, int* status, std::string* err);
+std::string row_gen_describe(const RowGenLaunch&);
+int row_gen_launch(RowGenLaunch&, const void* const* in, void* const* out, int n_out, void* stream,
+                   std::string* err);
+void row_gen_release(RowGenLaunch&);
+
+}  // namespace fs

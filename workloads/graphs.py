@@ -341,3 +341,104 @@ def scale_shift_rows_cols(shape, dtype="f32"):
         y = g.convert(y, dtype)
     g.output(y, "y")
     return g.ops
+
+
+# ----------------------------------------------------------------------------------
+# Row groups outside the five configs (warp composition on other op mixes, Section 5.1).
+# ----------------------------------------------------------------------------------
+
+def _f32_in(g, dtype, *ts):
+    return ts if dtype == "f32" else tuple(g.convert(t, "f32") for t in ts)
+
+
+def log_softmax(shape, dtype="f32"):
+    """y = x - max - log(sum(exp(x - max))) over the last dim."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    (xf,) = _f32_in(g, dtype, x)
+    m = g.reduce_max(xf, -1)
+    c = g.subtract(xf, g.row_broadcast(m, xf))
+    lse = g.log(g.reduce_sum(g.exp(c), -1))
+    y = g.subtract(c, g.row_broadcast(lse, xf))
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
+
+
+def rmsnorm(shape, dtype="f32", eps=1e-6):
+    """y = x * rsqrt(mean(x^2) + eps) * gamma."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    gamma = g.parameter("gamma", dtype, (shape[-1],))
+    xf, gf = _f32_in(g, dtype, x, gamma)
+    ms = g.divide(g.reduce_sum(g.multiply(xf, xf), -1), g.constant(shape[-1]))
+    r = g.rsqrt(g.add(ms, g.constant(eps)))
+    y = g.multiply(g.multiply(xf, g.row_broadcast(r, xf)), g.col_broadcast(gf, xf))
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
+
+
+def l2_normalize_scaled(shape, dtype="f32"):
+    """y = x * s / sqrt(sum(x^2)) with one scale s per row; also returns the norms."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    s = g.parameter("s", dtype, shape[:-1])
+    xf, sf = _f32_in(g, dtype, x, s)
+    norm = g.sqrt(g.reduce_sum(g.multiply(xf, xf), -1))
+    y = g.divide(g.multiply(xf, g.row_broadcast(sf, xf)), g.row_broadcast(norm, xf))
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    g.output(norm, "norm")
+    return g.ops
+
+
+def layernorm_fwd_with_stats(rows, cols, dtype="f32", eps=1e-5):
+    """LayerNorm forward that also returns the per-row mean and reciprocal standard deviation
+    (what a training forward pass saves for the backward pass): a 3-tuple."""
+    g = Graph()
+    x = g.parameter("x", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    beta = g.parameter("beta", dtype, (cols,))
+    xf, gf, bf = _f32_in(g, dtype, x, gamma, beta)
+    mean = g.divide(g.reduce_sum(xf, -1), g.constant(cols))
+    c = g.subtract(xf, g.row_broadcast(mean, xf))
+    var = g.divide(g.reduce_sum(g.multiply(c, c), -1), g.constant(cols))
+    rstd = g.rsqrt(g.add(var, g.constant(eps)))
+    y = g.add(g.multiply(g.multiply(c, g.row_broadcast(rstd, xf)), g.col_broadcast(gf, xf)), g.col_broadcast(bf, xf))
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    g.output(mean, "mean")
+    g.output(rstd, "rstd")
+    return g.ops
+
+
+def softmax_with_lse(shape, temperature=0.7, dtype="f32"):
+    """p = softmax(x / T) over the last dim, plus the log-sum-exp of x / T per row."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    (xf,) = _f32_in(g, dtype, x)
+    z = g.divide(xf, g.constant(temperature))
+    m = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(m, z)))
+    ssum = g.reduce_sum(e, -1)
+    p = g.divide(e, g.row_broadcast(ssum, z))
+    lse = g.add(g.log(ssum), m)
+    if dtype != "f32":
+        p = g.convert(p, dtype)
+    g.output(p, "p")
+    g.output(lse, "lse")
+    return g.ops
+
+
+def row_sum_of_squares(shape, dtype="f32"):
+    """One per-row output only: sum(x^2) over the last dim."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    (xf,) = _f32_in(g, dtype, x)
+    g.output(g.reduce_sum(g.multiply(xf, xf), -1), "ss")
+    return g.ops

@@ -111,3 +111,9 @@ def scale_shift_rows_cols(shape, dtype="f32", seed_offset=13):
     rowv = r.normal(0.0, 1.0, shape[:-1])
     colv = r.uniform(0.5, 1.5, (shape[-1],))
     return [round_to(t, dtype) for t in (x, rowv, colv)]
+
+
+def normal_tensors(shapes, dtype="f32", seed_offset=20, scale=1.0):
+    """One N(0, scale) tensor per shape, for the groups outside the five configs."""
+    r = _rng(seed_offset)
+    return [round_to(r.normal(0.0, scale, s), dtype) for s in shapes]
