@@ -103,7 +103,11 @@ typedef struct {
   int32_t wg_size;       /* threads per workgroup: multiple of 64; each schedule states its
                             own range in its error message (64..512 for one-wavefront rows,
                             a power of two 128..1024 for wavefront teams, ...) */
-  int32_t rows_per_wave; /* independent row groups a wavefront keeps in flight: 1..8 */
+  int32_t rows_per_wave; /* hand-written row kernels: independent row groups a wavefront keeps
+                            in flight, 1..8.  Generated row kernels: rows a wavefront covers
+                            at a time, a power of two 1..64 (lanes per row = 64 / this; 64 is
+                            the one-thread-per-row template).  Elementwise interpreter:
+                            chunks a thread carries, 1, 2 or 4 */
   int32_t grid;          /* number of workgroups */
 } fs_plan_options;
 

@@ -315,6 +315,8 @@ struct Gen {
     return off.empty() ? "0" : off;
   }
 
+  int lanes_per_row = 0;      // 0: choose
+
   bool geometry(std::string* err) {
     bool any32 = false, any16 = false;
     for (const RView& v : A.views) {
@@ -341,15 +343,29 @@ struct Gen {
     else if (fits(1)) W = 1;
     else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
     const int64_t nvec = A.cols / W;
-    // tiny rows: one thread per row (sequential reduction); otherwise the fewest lanes that
-    // keep at most 8 chunks per lane
-    if (W == 1 ? nvec <= 32 : nvec <= 4) { L = 1; K = (int)nvec; }
-    else {
+    auto pow2_at_least = [](int64_t v) { int p = 1; while (p < v && p < 64) p *= 2; return p; };
+    if (lanes_per_row > 0) {
+      // the caller's template
+      L = lanes_per_row;
+    } else if (W == 1 && nvec <= 32) {
+      // a short row that cannot be read in vectors: one thread per row, sequential reduction
+      // (the THREAD template)
+      L = 1;
+    } else if (nvec <= 16) {
+      // short rows: one chunk per lane, so that consecutive lanes read consecutive memory
+      // across row boundaries
+      L = pow2_at_least(nvec);
+    } else {
+      // the fewest lanes that keep at most 16 elements of a value per lane
       L = 2;
       while (L < 64 && (nvec + L - 1) / L > (W == 8 ? 2 : 4)) L *= 2;
-      K = (int)((nvec + L - 1) / L);
     }
-    if ((int64_t)K * W > 32) { *err = "generated row schedule: row too long for one wavefront's registers"; return false; }
+    K = (int)((nvec + L - 1) / L);
+    if ((int64_t)K * W > 32) {
+      *err = lanes_per_row > 0 ? "generated row schedule: too few lanes per row for this row length"
+                               : "generated row schedule: row too long for one wavefront's registers";
+      return false;
+    }
     exact = (int64_t)K * L == nvec;
     return true;
   }
@@ -490,13 +506,23 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   Analysis A(g);
   if (!A.run()) { *err = A.err; return false; }
   Gen gen(A);
-  if (!gen.geometry(err)) return false;
   RowGenLaunch l;
   if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
     *status = FS_ERR_INVALID;
     *err = "generated row schedule: wg_size must be 64, 128, 192 or 256";
     return false;
   }
+  if (opt.rows_per_wave) {
+    // rows one wavefront covers at a time = 64 / lanes per row
+    const int r = opt.rows_per_wave;
+    if (r < 1 || r > 64 || (r & (r - 1))) {
+      *status = FS_ERR_INVALID;
+      *err = "generated row schedule: rows_per_wave must be a power of two in 1..64 (lanes per row = 64 / rows_per_wave)";
+      return false;
+    }
+    gen.lanes_per_row = 64 / r;
+  }
+  if (!gen.geometry(err)) return false;
   gen.emit(&l.kernel_name);
   if (const char* dump = getenv("FS_DUMP_SOURCE")) {
     if (FILE* f = fopen(dump, "a")) { fputs(gen.e.s.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
