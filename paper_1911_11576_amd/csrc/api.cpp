@@ -102,6 +102,7 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           p->match.kind = fs::MATCH_NONE;
           p->schedule = FS_SCHED_ROW;
           p->row_form = 3;
+          p->lds_bytes = p->row_gen.lds_bytes;
           p->description = fs::row_gen_describe(p->row_gen);
         } else if (!recognised) {
           if (has_reduce && lo.codegen) { st = st2; err = err2; }

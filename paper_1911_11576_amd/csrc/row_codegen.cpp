@@ -8,9 +8,10 @@
 // per-row values, and per-row values broadcast back into full ops is accepted, with full
 // and per-row outputs in any number up to 8.  The generated kernel gives each row to L
 // lanes (L = 1: the THREAD template of Section 5.2 for tiny rows, sequential reduction in
-// one thread; L = 2..64: the WARP template, lanes combine with DPP / permlane steps); a
-// lane keeps its K chunks of W consecutive elements of every live full value in registers
-// from the row's one read to its one write.
+// one thread; L = 2..64: the WARP template, lanes combine with DPP / permlane steps;
+// L = 128..1024: the block-composed template, one workgroup per row, wavefronts combine
+// through one float each in LDS and a barrier); a lane keeps its K chunks of W consecutive
+// elements of every live full value in registers from the row's one read to its one write.
 #include "row_codegen.h"
 
 #include <cstdarg>
@@ -361,9 +362,12 @@ struct Gen {
       while (L < 64 && (nvec + L - 1) / L > (W == 8 ? 2 : 4)) L *= 2;
     }
     K = (int)((nvec + L - 1) / L);
+    // a row too long for one wavefront's registers goes to a team of wavefronts (one
+    // workgroup per row)
+    while (lanes_per_row == 0 && (int64_t)K * W > 32 && L < 1024) { L *= 2; K = (int)((nvec + L - 1) / L); }
     if ((int64_t)K * W > 32) {
       *err = lanes_per_row > 0 ? "generated row schedule: too few lanes per row for this row length"
-                               : "generated row schedule: row too long for one wavefront's registers";
+                               : "generated row schedule: row longer than 32768 elements";
       return false;
     }
     exact = (int64_t)K * L == nvec;
@@ -374,10 +378,20 @@ struct Gen {
     const int rank = A.rank, nrow = rank - 1;
     e.s = ew_preamble();
     e.s += kReducePreamble;
-    e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_ROW_NAME(const Args a) {");
+    const int T = L > 64 ? L / 64 : 1;      // wavefronts per row
+    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", L > 256 ? L : 256);
     e.line("  constexpr int L = %d, K = %d, W = %d;", L, K, W);
-    e.line("  const int lane = threadIdx.x & (L - 1);");
-    e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
+    if (T > 1) {
+      // one workgroup of T wavefronts per row; every reduction has its own exchange slots, so one
+      // barrier per reduction is enough
+      e.line("  constexpr int T = %d;", T);
+      e.line("  __shared__ float exch[%d][T];", A.n_reduce);
+      e.line("  const int lane = threadIdx.x;");
+      e.line("  long long row = blockIdx.x;");
+    } else {
+      e.line("  const int lane = threadIdx.x & (L - 1);");
+      e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
+    }
     e.line("  const bool row_ok = row < %lldll;", (long long)A.rows);
     e.line("  if (!row_ok) row = %lldll;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", (long long)A.rows - 1);
     // which views need the row's coordinates
@@ -436,6 +450,7 @@ struct Gen {
     }
     // ---- ops in order
     std::vector<char> inv_done(A.g.size(), 0);
+    int red_index = 0;
     for (const RNode& n : A.nodes) {
       const bool reduce = n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX;
       if (reduce) {
@@ -447,7 +462,17 @@ struct Gen {
         e.line("    UNROLL for (int j = 0; j < W; ++j) r%d = %s;", n.id,
                sum ? ("r" + std::to_string(n.id) + " + " + x).c_str() : ("fmaxf(r" + std::to_string(n.id) + ", " + x + ")").c_str());
         e.line("  }");
-        if (L > 1) e.line("  r%d = lanes_allreduce<%s, L>(r%d);", n.id, sum ? "SumOp" : "MaxOp", n.id);
+        if (T > 1) {
+          const char* op = sum ? "SumOp" : "MaxOp";
+          e.line("  r%d = lanes_allreduce<%s, 64>(r%d);", n.id, op, n.id);
+          e.line("  if ((threadIdx.x & 63) == 0) exch[%d][threadIdx.x >> 6] = r%d;", red_index, n.id);
+          e.line("  __syncthreads();");
+          e.line("  r%d = exch[%d][0];", n.id, red_index);
+          e.line("  UNROLL for (int w = 1; w < T; ++w) r%d = %s::apply(r%d, exch[%d][w]);", n.id, op, n.id, red_index);
+          ++red_index;
+        } else if (L > 1) {
+          e.line("  r%d = lanes_allreduce<%s, L>(r%d);", n.id, sum ? "SumOp" : "MaxOp", n.id);
+        }
       } else if (n.cls == CLS_ROW) {
         e.line("  const float r%d = %s;", n.id, expr(n).c_str());
       } else {
@@ -533,9 +558,10 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   l.rows = A.rows; l.cols = A.cols;
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
+  l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : 0;
   for (const RView& v : A.views) l.view_param.push_back(v.param);
-  l.wg = opt.wg_size ? opt.wg_size : 256;
-  const int64_t rows_per_wg = l.wg / l.L;
+  l.wg = l.L > 64 ? l.L : opt.wg_size ? opt.wg_size : 256;     // a team is one workgroup per row
+  const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;
   int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
   if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
   l.grid = (int)(grid < 1 ? 1 : grid);
@@ -546,9 +572,9 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
 
 std::string row_gen_describe(const RowGenLaunch& l) {
   char buf[320];
-  snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
-           l.n_reduce, l.L == 1 ? "THREAD" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : "WARP", l.K * l.W,
-           l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg);
+  snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
+           l.n_reduce, l.L == 1 ? "THREAD" : l.L > 64 ? "CTA-S" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : l.L > 64 ? "CTA" : "WARP", l.K * l.W,
+           l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
   return buf;
 }
 

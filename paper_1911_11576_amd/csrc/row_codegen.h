@@ -15,7 +15,7 @@ struct RowGenLaunch {
   int wg = 256, grid = 1;
   int L = 64, K = 1, W = 4;           // lanes per row, chunks per lane, elements per chunk
   int n_ops = 0, n_reduce = 0;
-  int64_t rows = 0, cols = 0;
+  int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view
   std::vector<char> code_object;
   std::string kernel_name;
