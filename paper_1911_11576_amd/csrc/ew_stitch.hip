@@ -580,8 +580,8 @@ struct EwCompiler {
 }  // namespace
 
 // The generated kernel's arguments: one pointer per operand view, one per output.
-struct EwGenArgs { const void* in[12]; void* out[8]; };
-static_assert(kEwMaxViews == 12 && kEwMaxOuts == 8, "EwGenArgs mirrors the Args struct of the generated source");
+struct EwGenArgs { const void* in[24]; void* out[8]; };
+static_assert(kEwMaxViews <= 24 && kEwMaxOuts == 8, "EwGenArgs mirrors the Args struct of the generated source");
 
 bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* status, std::string* err) {
   *status = FS_ERR_UNSUPPORTED;

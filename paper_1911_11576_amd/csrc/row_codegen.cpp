@@ -29,14 +29,21 @@ enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2 };
 enum OpndKind : int { OP_NODE = 0, OP_ROWB = 1, OP_VIEW = 2, OP_CONST = 3 };
 
 struct Opnd { int kind = OP_NODE; int index = -1; float cval = 0.f; };
+// beside the fs_opkind / EwExtraOp values: a batched dot with a tiny contraction that produces
+// the full tile (sum over k of a per-row scalar times a per-column vector), and a batched dot
+// that contracts the full last dim into one value per row
+enum RowExtraOp : int { ROP_DOT_OUTER = 200, ROP_DOT_REDUCE = 201 };
+
 struct RNode {
   int id = -1, op = 0, cls = CLS_NONE, nop = 1;
   Opnd o[2];
+  std::vector<int> dot_row, dot_full;   // ROP_DOT_OUTER: view pairs per k; ROP_DOT_REDUCE: dot_full[0]
   int out_ord = -1, out_dtype = FS_F32;
 };
 struct RView {
   int param = -1, dtype = FS_F32, cls = CLS_FULL;
   int64_t stride[FS_MAX_RANK] = {0, 0, 0, 0};   // over the dims of the full shape (row views: last unused)
+  int64_t offset = 0;                            // constant element offset (a slice of a dot operand)
 };
 
 struct Analysis {
@@ -60,14 +67,19 @@ struct Analysis {
   }
   bool is_compute(int n) const {
     const int k = g[n].kind;
-    return (is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k)) && canon(n) == n;
+    return (is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k) || k == FS_DOT) && canon(n) == n;
   }
   bool shape_is_full(const Node& x) const {
     if (x.rank != rank) return false;
     for (int d = 0; d < rank; ++d) if (x.shape[d] != S[d]) return false;
     return true;
   }
+  // one value per row: the full shape without its last dim, or with it collapsed to 1
   bool shape_is_row(const Node& x) const {
+    if (x.rank == rank && x.shape[rank - 1] == 1 && S[rank - 1] != 1) {
+      for (int d = 0; d < rank - 1; ++d) if (x.shape[d] != S[d]) return false;
+      return true;
+    }
     if (x.rank != rank - 1) return false;
     for (int d = 0; d < rank - 1; ++d) if (x.shape[d] != S[d]) return false;
     return true;
@@ -96,14 +108,14 @@ struct Analysis {
     return true;
   }
 
-  int view_index(int base, const int64_t* stride, int c) {
+  int view_index(int base, const int64_t* stride, int c, int64_t offset = 0) {
     for (size_t k = 0; k < views.size(); ++k) {
-      bool same = views[k].param == g[base].ordinal && views[k].cls == c;
+      bool same = views[k].param == g[base].ordinal && views[k].cls == c && views[k].offset == offset;
       for (int d = 0; d < FS_MAX_RANK && same; ++d) same = views[k].stride[d] == stride[d];
       if (same) return (int)k;
     }
     RView v;
-    v.param = g[base].ordinal; v.dtype = g[base].dtype; v.cls = c;
+    v.param = g[base].ordinal; v.dtype = g[base].dtype; v.cls = c; v.offset = offset;
     for (int d = 0; d < FS_MAX_RANK; ++d) v.stride[d] = stride[d];
     views.push_back(v);
     return (int)views.size() - 1;
@@ -120,7 +132,7 @@ struct Analysis {
     if (g[c].kind == FS_BROADCAST && consumer_cls == CLS_FULL) {
       const int src = canon(g[c].operand[0]);
       if (is_compute(src)) {
-        if (cls[src] != CLS_ROW || !shape_is_full(g[c]) || (g[src].rank > 0 && g[c].axis != 0))
+        if (cls[src] != CLS_ROW || !shape_is_full(g[c]) || (g[src].rank > 0 && g[c].axis != 0))  // leading dims line up
           return fail("generated row schedule: only per-row values may be broadcast back");
         o->kind = OP_ROWB; o->index = src;
         return true;
@@ -137,6 +149,63 @@ struct Analysis {
       return fail("generated row schedule: operand shape differs from its consumer's");
     o->kind = OP_VIEW;
     o->index = view_index(base, st, consumer_cls);
+    return true;
+  }
+
+  // A parameter behind widening converts, as a dense tensor: its node and dims.
+  bool dense_param(int n, int* base) const {
+    n = canon(n);
+    if (g[n].kind != FS_PARAMETER) return false;
+    *base = n;
+    return true;
+  }
+
+  // Batched dots small enough to be arithmetic on the row's registers (no matrix unit: the
+  // contraction is a handful of terms, or it is the row reduction itself):
+  //   outer:  a[B,M,K] . b -> [B,M,N] = the group's full shape, K <= 8, a and b parameters,
+  //           b contiguous along N (stored [B,K,N], or K == 1)
+  //   reduce: p[B,M,N] . b -> [B,M,1], p a full value of the group, b a parameter contiguous
+  //           along N (stored [B,1,N], or [B,N,1])
+  bool dot_node(int i, RNode* r) {
+    const Node& x = g[i];
+    if (rank != 3 || x.rank != 3) return fail("generated row schedule: dot outside a rank-3 group");
+    const int ia = canon(x.operand[0]), ib = canon(x.operand[1]);
+    const Node& a = g[ia];
+    const Node& b = g[ib];
+    const bool bt = x.axis == 1;                       // b stored [B, N_out, K_contract]
+    const int64_t Kc = a.shape[2], Nout = bt ? b.shape[1] : b.shape[2];
+    r->id = i;
+    int pb = -1;
+    if (!dense_param(ib, &pb)) return fail("generated row schedule: second dot operand must be a group input");
+    if (a.rank != 3 || b.rank != 3 || b.shape[0] != S[0] || (bt ? b.shape[2] : b.shape[1]) != Kc)
+      return fail("generated row schedule: dot operand shapes do not fit the group");
+    if (shape_is_full(x) && !(is_compute(ia) && cls[ia] == CLS_FULL)) {
+      // outer form
+      int pa = -1;
+      if (!dense_param(ia, &pa)) return fail("generated row schedule: first operand of a producing dot must be a group input");
+      if (Kc > 8) return fail("generated row schedule: dot contraction longer than 8 (a matrix-unit schedule is needed)");
+      if (bt && Kc != 1) return fail("generated row schedule: dot operand not contiguous along the row");
+      if (a.shape[0] != S[0] || a.shape[1] != S[1] || Nout != S[2]) return fail("generated row schedule: dot shape differs from the group's");
+      r->op = ROP_DOT_OUTER; r->cls = CLS_FULL; r->nop = 0;
+      cls[i] = CLS_FULL;
+      for (int64_t k = 0; k < Kc; ++k) {
+        const int64_t sa[FS_MAX_RANK] = {S[1] * Kc, Kc, 0, 0};              // a[b, m, k]: one scalar per row
+        const int64_t sb[FS_MAX_RANK] = {Kc * S[2], 0, 1, 0};               // b[b, k, :]: shared by the rows of a batch
+        r->dot_row.push_back(view_index(pa, sa, CLS_ROW, k));
+        r->dot_full.push_back(view_index(pb, sb, CLS_FULL, bt ? 0 : k * S[2]));
+      }
+      return true;
+    }
+    // reduce form
+    if (!(x.shape[0] == S[0] && x.shape[1] == S[1] && x.shape[2] == 1))
+      return fail("generated row schedule: a consuming dot must produce one value per row");
+    if (Kc != S[2]) return fail("generated row schedule: dot contraction differs from the row length");
+    r->op = ROP_DOT_REDUCE; r->cls = CLS_ROW; r->nop = 1;
+    cls[i] = CLS_ROW;
+    if (!operand(x.operand[0], CLS_FULL, &r->o[0])) return false;
+    const int64_t sb[FS_MAX_RANK] = {S[2], 0, 1, 0};                         // b[b, :, 0] or b[b, 0, :]
+    r->dot_full.push_back(view_index(pb, sb, CLS_FULL, 0));
+    ++n_reduce;
     return true;
   }
 
@@ -167,8 +236,16 @@ struct Analysis {
       const Node& x = g[i];
       const int k = x.kind;
       if (k == FS_PARAMETER || k == FS_CONSTANT || k == FS_BROADCAST || k == FS_OUTPUT) continue;
+      if (k == FS_DOT) {
+        RNode r;
+        if (!dot_node(i, &r)) return false;
+        r.out_ord = out_ord[i];
+        r.out_dtype = out_dtype[i];
+        nodes.push_back(r);
+        continue;
+      }
       if (!(is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k)))
-        return fail(std::string("generated row schedule: op ") + kind_name(k) + " is not elementwise or a reduction");
+        return fail(std::string("generated row schedule: op ") + kind_name(k) + " is not elementwise, a reduction or a small dot");
       if (!is_compute(i)) continue;       // widening convert: alias
       RNode r;
       r.id = i;
@@ -191,7 +268,7 @@ struct Analysis {
       r.out_dtype = out_dtype[i];
       nodes.push_back(r);
     }
-    if (views.size() > 12) return fail("generated row schedule: more than 12 distinct operand views");
+    if (views.size() > 24) return fail("generated row schedule: more than 24 distinct operand views");
     return true;
   }
 };
@@ -293,7 +370,7 @@ struct Gen {
   std::string row_offset(const RView& v, bool* needs_coords) const {
     const int nrow = A.rank - 1;
     char buf[160];
-    if (nrow == 0) return "0";
+    if (nrow == 0) { snprintf(buf, sizeof buf, "%lldll", (long long)v.offset); return buf; }
     const int64_t unit = v.stride[nrow - 1];
     bool linear = true;
     int64_t mul = 1;
@@ -302,8 +379,8 @@ struct Gen {
       mul *= A.S[d];
     }
     if (linear) {
-      if (unit == 0) return "0";
-      snprintf(buf, sizeof buf, "row * %lldll", (long long)unit);
+      if (unit == 0) snprintf(buf, sizeof buf, "%lldll", (long long)v.offset);
+      else snprintf(buf, sizeof buf, "row * %lldll + %lldll", (long long)unit, (long long)v.offset);
       return buf;
     }
     *needs_coords = true;
@@ -313,10 +390,14 @@ struct Gen {
       snprintf(buf, sizeof buf, "%si%d * %lldll", off.empty() ? "" : " + ", d, (long long)v.stride[d]);
       off += buf;
     }
-    return off.empty() ? "0" : off;
+    snprintf(buf, sizeof buf, "%s%lldll", off.empty() ? "" : " + ", (long long)v.offset);
+    return off + buf;
   }
 
   int lanes_per_row = 0;      // 0: choose
+  int wg = 256;               // workgroup size the kernel is generated for
+  bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
+  int64_t stage_bytes = 0;
 
   bool geometry(std::string* err) {
     bool any32 = false, any16 = false;
@@ -336,11 +417,13 @@ struct Gen {
         const int64_t ls = v.stride[A.rank - 1];
         if (ls != 0 && ls != 1) return false;
         if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
+        if (ls == 1 && v.offset % w) return false;
       }
       return true;
     };
     if (!any32 && fits(8)) W = 8;
     else if (fits(4)) W = 4;
+    else if (fits(2)) W = 2;
     else if (fits(1)) W = 1;
     else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
     const int64_t nvec = A.cols / W;
@@ -359,7 +442,7 @@ struct Gen {
     } else {
       // the fewest lanes that keep at most 16 elements of a value per lane
       L = 2;
-      while (L < 64 && (nvec + L - 1) / L > (W == 8 ? 2 : 4)) L *= 2;
+      while (L < 64 && (nvec + L - 1) / L > 16 / W) L *= 2;
     }
     K = (int)((nvec + L - 1) / L);
     // a row too long for one wavefront's registers goes to a team of wavefronts (one
@@ -371,6 +454,19 @@ struct Gen {
       return false;
     }
     exact = (int64_t)K * L == nvec;
+    // Short rows that do not fill whole 128-byte lines: a workgroup's rows are contiguous in
+    // memory, so its full outputs are first laid out in LDS and then stored as one dense run
+    // of 16-byte accesses (stores of separate row pieces straddle lines and measured 2x slower).
+    if (L <= 64) {
+      int min_out = 4;
+      bool full_out = false;
+      for (const RNode& n : A.nodes) if (n.out_ord >= 0 && n.cls == CLS_FULL) { full_out = true; if (n.out_dtype != FS_F32) min_out = 2; }
+      const int64_t row_bytes = A.cols * min_out;
+      const int64_t tile = (int64_t)(wg / L) * A.cols * 4;
+      // (the dense run starts 16-byte aligned when a workgroup's element count is a multiple of 4)
+      stage = full_out && row_bytes % 128 != 0 && row_bytes < 2048 && tile <= 32 * 1024 && ((int64_t)(wg / L) * A.cols) % 4 == 0;
+      stage_bytes = stage ? tile : 0;
+    }
     return true;
   }
 
@@ -391,6 +487,14 @@ struct Gen {
     } else {
       e.line("  const int lane = threadIdx.x & (L - 1);");
       e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
+    }
+    if (stage) {
+      e.line("  constexpr int RPW = %d, N = %lld;            // rows per workgroup, row length", wg / L, (long long)A.cols);
+      e.line("  __shared__ float stage[RPW * N];");
+      e.line("  const int row_local = threadIdx.x / L;");
+      e.line("  const long long wg_row0 = (long long)blockIdx.x * RPW;");
+      e.line("  const long long left = %lldll - wg_row0;", (long long)A.rows);
+      e.line("  const int wg_count = (int)(left < RPW ? left : RPW) * N;   // elements this workgroup owns");
     }
     e.line("  const bool row_ok = row < %lldll;", (long long)A.rows);
     e.line("  if (!row_ok) row = %lldll;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", (long long)A.rows - 1);
@@ -435,6 +539,9 @@ struct Gen {
       e.line("    const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s) + col[k];", ty, ty, q, roff[q].c_str());
       if (W == 1) {
         e.line("    v%zu[k][0] = %s;", q, one);
+      } else if (v.dtype == FS_F32 && W == 2) {
+        e.line("    const f32x2 x = %s(reinterpret_cast<const f32x2*>(p));", ld);
+        e.line("    v%zu[k][0] = x[0]; v%zu[k][1] = x[1];", q, q);
       } else if (v.dtype == FS_F32) {
         for (int h = 0; h < W / 4; ++h) {
           e.line("    { const f32x4 x = %s(reinterpret_cast<const f32x4*>(p) + %d);", ld, h);
@@ -443,7 +550,12 @@ struct Gen {
       } else {
         const char* lo = v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
         const char* hi = v.dtype == FS_F16 ? "f16_hi" : "bf16_hi";
-        e.line("    const %s x = %s(reinterpret_cast<const %s*>(p));", W == 8 ? "u32x4" : "u32x2", ld, W == 8 ? "u32x4" : "u32x2");
+        if (W == 2) {
+          e.line("    const unsigned x1 = %s(reinterpret_cast<const unsigned*>(p));", ld);
+          e.line("    const unsigned x[1] = {x1};");
+        } else {
+          e.line("    const %s x = %s(reinterpret_cast<const %s*>(p));", W == 8 ? "u32x4" : "u32x2", ld, W == 8 ? "u32x4" : "u32x2");
+        }
         e.line("    UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[k][2 * j] = %s(x[j]); v%zu[k][2 * j + 1] = %s(x[j]); }", q, lo, q, hi);
       }
       e.line("  }");
@@ -453,6 +565,20 @@ struct Gen {
     int red_index = 0;
     for (const RNode& n : A.nodes) {
       const bool reduce = n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX;
+      // combine the lanes' partial results of reduction r<id> (wavefront steps, then LDS across wavefronts)
+      auto combine = [&](int id, bool sum) {
+        const char* op = sum ? "SumOp" : "MaxOp";
+        if (T > 1) {
+          e.line("  r%d = lanes_allreduce<%s, 64>(r%d);", id, op, id);
+          e.line("  if ((threadIdx.x & 63) == 0) exch[%d][threadIdx.x >> 6] = r%d;", red_index, id);
+          e.line("  __syncthreads();");
+          e.line("  r%d = exch[%d][0];", id, red_index);
+          e.line("  UNROLL for (int w = 1; w < T; ++w) r%d = %s::apply(r%d, exch[%d][w]);", id, op, id, red_index);
+          ++red_index;
+        } else if (L > 1) {
+          e.line("  r%d = lanes_allreduce<%s, L>(r%d);", id, op, id);
+        }
+      };
       if (reduce) {
         const bool sum = n.op == FS_REDUCE_SUM;
         const std::string x = opnd(n.o[0], CLS_FULL);
@@ -462,17 +588,27 @@ struct Gen {
         e.line("    UNROLL for (int j = 0; j < W; ++j) r%d = %s;", n.id,
                sum ? ("r" + std::to_string(n.id) + " + " + x).c_str() : ("fmaxf(r" + std::to_string(n.id) + ", " + x + ")").c_str());
         e.line("  }");
-        if (T > 1) {
-          const char* op = sum ? "SumOp" : "MaxOp";
-          e.line("  r%d = lanes_allreduce<%s, 64>(r%d);", n.id, op, n.id);
-          e.line("  if ((threadIdx.x & 63) == 0) exch[%d][threadIdx.x >> 6] = r%d;", red_index, n.id);
-          e.line("  __syncthreads();");
-          e.line("  r%d = exch[%d][0];", n.id, red_index);
-          e.line("  UNROLL for (int w = 1; w < T; ++w) r%d = %s::apply(r%d, exch[%d][w]);", n.id, op, n.id, red_index);
-          ++red_index;
-        } else if (L > 1) {
-          e.line("  r%d = lanes_allreduce<%s, L>(r%d);", n.id, sum ? "SumOp" : "MaxOp", n.id);
+        combine(n.id, sum);
+      } else if (n.op == ROP_DOT_REDUCE) {
+        // one value per row: sum over the row of p[n] * b[n]
+        const std::string x = opnd(n.o[0], CLS_FULL);
+        e.line("  float r%d = 0.0f;", n.id);
+        e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+        if (!exact) e.line("    if (!ok[k]) continue;");
+        e.line("    UNROLL for (int j = 0; j < W; ++j) r%d = fmaf(%s, v%d[k][j], r%d);", n.id, x.c_str(), n.dot_full[0], n.id);
+        e.line("  }");
+        combine(n.id, true);
+      } else if (n.op == ROP_DOT_OUTER) {
+        // the full tile from a tiny contraction: sum over k of (row scalar) * (column vector)
+        e.line("  float t%d[K][W];", n.id);
+        std::string ex;
+        for (size_t k = 0; k < n.dot_row.size(); ++k) {
+          char buf[96];
+          if (k == 0) snprintf(buf, sizeof buf, "s%d * v%d[k][j]", n.dot_row[k], n.dot_full[k]);
+          else snprintf(buf, sizeof buf, "fmaf(s%d, v%d[k][j], ", n.dot_row[k], n.dot_full[k]);
+          ex = k == 0 ? std::string(buf) : std::string(buf) + ex + ")";
         }
+        e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) t%d[k][j] = %s;", n.id, ex.c_str());
       } else if (n.cls == CLS_ROW) {
         e.line("  const float r%d = %s;", n.id, expr(n).c_str());
       } else {
@@ -490,11 +626,43 @@ struct Gen {
                     n.out_dtype == FS_F16 ? "to_f16" : "to_bf16", n.id);
         continue;
       }
+      if (stage) {
+        e.line("  __syncthreads();                             // the tile's previous use is over");
+        e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+        e.line("    if (!ok[k]) continue;");
+        e.line("    UNROLL for (int j = 0; j < W; ++j) stage[row_local * N + col[k] + j] = t%d[k][j];", n.id);
+        e.line("  }");
+        e.line("  __syncthreads();");
+        if (n.out_dtype == FS_F32) {
+          e.line("  {");
+          e.line("    float* o = static_cast<float*>(a.out[%d]) + wg_row0 * N;", n.out_ord);
+          e.line("    for (int i = threadIdx.x * 4; i + 4 <= wg_count; i += %d * 4)", wg);
+          e.line("      __builtin_nontemporal_store(f32x4{stage[i], stage[i + 1], stage[i + 2], stage[i + 3]}, reinterpret_cast<f32x4*>(o + i));");
+          e.line("    for (int i = (wg_count & ~3) + threadIdx.x; i < wg_count; i += %d) o[i] = stage[i];", wg);
+          e.line("  }");
+        } else {
+          const char* cv = n.out_dtype == FS_F16 ? "to_f16" : "to_bf16";
+          // 8 values per 16-byte store where the workgroup's first element is 16-byte aligned, else 4
+          const int V = ((int64_t)(wg / L) * A.cols) % 8 == 0 ? 8 : 4;
+          e.line("  {");
+          e.line("    unsigned short* o = static_cast<unsigned short*>(a.out[%d]) + wg_row0 * N;", n.out_ord);
+          e.line("    for (int i = threadIdx.x * %d; i + %d <= wg_count; i += %d * %d) {", V, V, wg, V);
+          e.line("      unsigned w[%d];", V / 2);
+          e.line("      UNROLL for (int j = 0; j < %d; ++j) w[j] = %s(stage[i + 2 * j]) | (%s(stage[i + 2 * j + 1]) << 16);", V / 2, cv, cv);
+          if (V == 8) e.line("      __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(o + i));");
+          else e.line("      __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(o + i));");
+          e.line("    }");
+          e.line("    for (int i = wg_count / %d * %d + threadIdx.x; i < wg_count; i += %d) o[i] = (unsigned short)%s(stage[i]);", V, V, wg, cv);
+          e.line("  }");
+        }
+        continue;
+      }
       e.line("  UNROLL for (int k = 0; k < K; ++k) {");
       e.line("    if (!(row_ok && ok[k])) continue;");
       if (n.out_dtype == FS_F32) {
         e.line("    float* p = static_cast<float*>(a.out[%d]) + row * %lldll + col[k];", n.out_ord, (long long)A.cols);
         if (W == 1) e.line("    p[0] = t%d[k][0];", n.id);
+        else if (W == 2) e.line("    __builtin_nontemporal_store(f32x2{t%d[k][0], t%d[k][1]}, reinterpret_cast<f32x2*>(p));", n.id, n.id);
         else for (int h = 0; h < W / 4; ++h)
           e.line("    __builtin_nontemporal_store(f32x4{t%d[k][%d], t%d[k][%d], t%d[k][%d], t%d[k][%d]}, reinterpret_cast<f32x4*>(p) + %d);",
                  n.id, 4 * h, n.id, 4 * h + 1, n.id, 4 * h + 2, n.id, 4 * h + 3, h);
@@ -506,7 +674,8 @@ struct Gen {
           e.line("    unsigned w[W / 2];");
           e.line("    UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[k][2 * j]) | (%s(t%d[k][2 * j + 1]) << 16);", cv, n.id, cv, n.id);
           if (W == 8) e.line("    __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
-          else e.line("    __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
+          else if (W == 4) e.line("    __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
+          else e.line("    __builtin_nontemporal_store(w[0], reinterpret_cast<unsigned*>(p));");
         }
       }
       e.line("  }");
@@ -522,7 +691,7 @@ struct Gen {
   }
 };
 
-struct GenArgs { const void* in[12]; void* out[8]; };
+struct GenArgs { const void* in[24]; void* out[8]; };   // mirrors Args of the generated source
 
 }  // namespace
 
@@ -547,6 +716,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     }
     gen.lanes_per_row = 64 / r;
   }
+  gen.wg = opt.wg_size ? opt.wg_size : 256;
+  if (gen.wg == 192) gen.wg = 128;            // lanes per row divide the workgroup
   if (!gen.geometry(err)) return false;
   gen.emit(&l.kernel_name);
   if (const char* dump = getenv("FS_DUMP_SOURCE")) {
@@ -558,9 +729,9 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   l.rows = A.rows; l.cols = A.cols;
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
-  l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : 0;
+  l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : gen.stage_bytes;
   for (const RView& v : A.views) l.view_param.push_back(v.param);
-  l.wg = l.L > 64 ? l.L : opt.wg_size ? opt.wg_size : 256;     // a team is one workgroup per row
+  l.wg = l.L > 64 ? l.L : gen.wg;     // a team is one workgroup per row
   const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;
   int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
   if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }

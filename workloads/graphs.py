@@ -442,3 +442,51 @@ def row_sum_of_squares(shape, dtype="f32"):
     (xf,) = _f32_in(g, dtype, x)
     g.output(g.reduce_sum(g.multiply(xf, xf), -1), "ss")
     return g.ops
+
+
+def multi_interest_pattern(batch, m=94, n=94, k=1, scale=0.25, gain=0.5):
+    """A stand-in for the paper's motivating example (Section 3.1; its figure is not
+    available): two batched dots around nine elementwise ops and two reductions, with
+    a four-element output tuple (subtract, divide, log_1, multiply_2).  dot_1 expands
+    two small tensors into a [batch, m, n] tile (contraction length k, 1 in the sizes
+    the paper quotes); dot_2 contracts the tile back to one value per row.
+
+      dot_1      = x[B,m,k] . y[B,k,n]
+      multiply   = dot_1 * scale
+      add        = multiply + mask[B,1,n]
+      reduce_max = max_n add
+      subtract   = add - reduce_max            -> output
+      exp        = exp(subtract)
+      reduce_sum = sum_n exp
+      divide     = exp / reduce_sum            -> output
+      log        = log(reduce_sum)
+      log_1      = log + reduce_max            -> output  [B,m]
+      dot_2      = divide . v[B,n,1]           [B,m,1]
+      multiply_1 = dot_2 * gate[B,m,1]
+      multiply_2 = multiply_1 * gain           -> output  [B,m,1]
+    """
+    g = Graph()
+    x = g.parameter("x", "f32", (batch, m, k))
+    y = g.parameter("y", "f32", (batch, k, n))
+    mask = g.parameter("mask", "f32", (batch, 1, n))
+    v = g.parameter("v", "f32", (batch, n, 1))
+    gate = g.parameter("gate", "f32", (batch, m, 1))
+    full = (batch, m, n)
+    dot_1 = g.dot(x, y)
+    multiply = g.multiply(dot_1, g.constant(scale))
+    add = g.add(multiply, g.broadcast(mask, full, 0))
+    reduce_max = g.reduce_max(add, -1)
+    subtract = g.subtract(add, g.row_broadcast(reduce_max, add))
+    exp = g.exp(subtract)
+    reduce_sum = g.reduce_sum(exp, -1)
+    divide = g.divide(exp, g.row_broadcast(reduce_sum, add))
+    log = g.log(reduce_sum)
+    log_1 = g.add(log, reduce_max)
+    dot_2 = g.dot(divide, v)
+    multiply_1 = g.multiply(dot_2, gate)
+    multiply_2 = g.multiply(multiply_1, g.constant(gain))
+    g.output(subtract, "subtract")
+    g.output(divide, "divide")
+    g.output(log_1, "log_1")
+    g.output(multiply_2, "multiply_2")
+    return g.ops

@@ -117,3 +117,13 @@ def normal_tensors(shapes, dtype="f32", seed_offset=20, scale=1.0):
     """One N(0, scale) tensor per shape, for the groups outside the five configs."""
     r = _rng(seed_offset)
     return [round_to(r.normal(0.0, scale, s), dtype) for s in shapes]
+
+
+def multi_interest_pattern(batch, m=94, n=94, k=1, p_pad=0.1, seed_offset=8):
+    r = _rng(seed_offset)
+    x = r.normal(0.0, 1.0, (batch, m, k))
+    y = r.normal(0.0, 1.0, (batch, k, n))
+    mask = np.where(r.random((batch, 1, n)) < p_pad, -1e4, 0.0)
+    v = r.normal(0.0, 1.0, (batch, n, 1))
+    gate = r.uniform(0.0, 1.0, (batch, m, 1))
+    return [round_to(t, "f32") for t in (x, y, mask, v, gate)]
