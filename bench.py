@@ -106,17 +106,33 @@ def time_copy(nbytes, steps, warmup):
     n = max(1, min(8, -(-ROTATE_BYTES // (2 * half))))
     src = [torch.empty(half, dtype=torch.uint8, device="cuda:0").random_(0, 255) for _ in range(n)]
     dst = [torch.empty(half, dtype=torch.uint8, device="cuda:0") for _ in range(n)]
+    # pointers and stream resolved once: small copies would otherwise time the Python wrapper
+    stream = torch.cuda.current_stream().cuda_stream
+    dp, sp = [t.data_ptr() for t in dst], [t.data_ptr() for t in src]
     for i in range(warmup):
-        fs_stream_copy(dst[i % n], src[i % n], half)
+        fs_stream_copy(dp[i % n], sp[i % n], half, stream)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
     for i in range(steps):
-        fs_stream_copy(dst[i % n], src[i % n], half)
+        fs_stream_copy(dp[i % n], sp[i % n], half, stream)
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / steps, 2 * half
+
+
+def bandwidth_model(steps=100, warmup=10):
+    """M(V) of the paper's model-based score (Section 4.3): achieved bandwidth of a plain
+    streaming kernel as a function of the bytes it moves, measured with the copy kernel."""
+    import torch
+    table = []
+    for mb in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
+        nbytes = mb << 20
+        ms, moved = time_copy(nbytes, steps, warmup)
+        table.append({"bytes": moved, "us": ms * 1e3, "gbs": moved / (ms * 1e-3) / 1e9})
+        torch.cuda.empty_cache()
+    return table
 
 
 def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
@@ -129,8 +145,9 @@ def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
     res = {"algorithmic_bytes": algo, "buffer_sets": len(sets)}
     with Plan(ops) as plan:
         info = plan.info()
+        template = plan.describe()
         wall_ms, ev_ms = time_plan(plan, sets, steps, warmup)
-    res.update(schedule=info["schedule"], template=None, stitched_us=ev_ms * 1e3, stitched_wall_us=wall_ms * 1e3,
+    res.update(schedule=info["schedule"], template=template, stitched_us=ev_ms * 1e3, stitched_wall_us=wall_ms * 1e3,
                stitched_gbs=algo / (ev_ms * 1e-3) / 1e9, stitched_frac_of_peak=algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                lds_bytes=info["lds_bytes"], workspace_bytes=info["workspace_bytes"])
     if with_per_op:
@@ -216,8 +233,10 @@ def main():
         groups["scaled_masked_softmax_key_padding"] = bench_group(BY_NAME["scaled_masked_softmax"], args.steps,
                                                                   args.warmup, build_kw=kp)[0]
         for cfg in EXTRA_GROUPS:
-            groups[cfg.name] = bench_group(cfg, max(20, args.steps // 4), max(5, args.warmup // 2))[0]
+            heavy = cfg.name == "multi_interest_pattern"        # 1.2 GB per launch, 11 ms unfused
+            groups[cfg.name] = bench_group(cfg, max(20, args.steps // (25 if heavy else 4)), max(3, args.warmup // (10 if heavy else 2)))[0]
         out["groups"] = groups
+        out["bandwidth_model"] = bandwidth_model()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(head)
     print(json.dumps(out))

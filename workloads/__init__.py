@@ -52,12 +52,34 @@ CONFIGS = [
     Config(5, "layernorm_bwd", graphs.layernorm_bwd, inputs.layernorm_bwd,
            dict(rows=32768, cols=1024), dict(rows=517, cols=1024), "f32"),
 ]
-# All-elementwise groups measured beside the five (the packing pattern of the backward
-# phase, Section 5.1): not benchmark configs, so not in CONFIGS.
+def _log_softmax_inputs(shape, dtype="f32"):
+    return inputs.normal_tensors([shape], dtype, scale=3.0)
+
+
+def _rmsnorm_inputs(shape, dtype="f32"):
+    return inputs.normal_tensors([shape, shape[-1:]], dtype)
+
+
+def _ln_stats_inputs(rows, cols, dtype="f32"):
+    return inputs.layernorm_fwd(rows, cols, dtype)
+
+
+# Groups measured beside the five, all run by generated kernels: all-elementwise groups (the
+# packing pattern of the backward phase, Section 5.1), row groups that no hand-written kernel
+# matches, and the stand-in for the paper's motivating example (Section 3.1) at the sizes it
+# quotes.  Not benchmark configs, so not in CONFIGS.
 EXTRA_GROUPS = [
     Config(6, "adam_update_packed", graphs.adam_update, inputs.adam_update,
            dict(shape=(16384, 1024)), dict(shape=(129, 512)), "f32"),
     Config(7, "bias_gelu_residual", graphs.bias_gelu_residual, inputs.bias_gelu_residual,
            dict(rows=16384, cols=1024, dtype="bf16"), dict(rows=203, cols=1024, dtype="bf16"), "bf16"),
+    Config(8, "log_softmax", graphs.log_softmax, _log_softmax_inputs,
+           dict(shape=(131072, 128)), dict(shape=(1030, 128)), "f32"),
+    Config(9, "rmsnorm", graphs.rmsnorm, _rmsnorm_inputs,
+           dict(shape=(16384, 1024), dtype="bf16"), dict(shape=(203, 1024), dtype="bf16"), "bf16"),
+    Config(10, "layernorm_fwd_with_stats", graphs.layernorm_fwd_with_stats, _ln_stats_inputs,
+           dict(rows=16384, cols=1024), dict(rows=203, cols=1024), "f32"),
+    Config(11, "multi_interest_pattern", graphs.multi_interest_pattern, inputs.multi_interest_pattern,
+           dict(batch=16384, m=94, n=94, k=1), dict(batch=7, m=94, n=94, k=1), "f32"),
 ]
 BY_NAME = {c.name: c for c in CONFIGS + EXTRA_GROUPS}
