@@ -214,3 +214,54 @@ def test_elementwise_limits_are_reported():
     v = g.parameter("v", "f32", (64,))
     g.output(g.add(x, g.col_broadcast(g.exp(v), x)))
     _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+
+
+# ---------------------------------------------------------------- generated row schedule (host side)
+
+def test_row_groups_without_a_hand_written_kernel_get_a_generated_one():
+    with Plan(graphs.log_softmax((300, 768))) as p:
+        info = p.info()
+        assert info["schedule"] == "row" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+        assert "generated kernel fs_row_" in p.describe() and "WARP" in p.describe()
+        assert info["algorithmic_bytes"] == 2 * 300 * 768 * 4
+    with Plan(graphs.log_softmax((300, 5))) as p:            # short unaligned rows: one thread per row
+        assert "THREAD]" in p.describe()
+    with Plan(graphs.log_softmax((3, 8192))) as p:           # long rows: one workgroup per row
+        assert "CTA-S" in p.describe() and p.info()["lds_bytes"] > 0
+    # the same source is compiled once per process: equal groups share a kernel name
+    with Plan(graphs.rmsnorm((64, 256))) as a, Plan(graphs.rmsnorm((64, 256))) as b:
+        assert a.describe() == b.describe()
+    # full and per-row outputs in one tuple
+    with Plan(graphs.layernorm_fwd_with_stats(64, 1024)) as p:
+        assert p.info()["algorithmic_bytes"] == (2 * 64 * 1024 + 2 * 1024 + 2 * 64) * 4
+
+
+def test_generated_mode_and_prebuilt_mode_on_recognised_groups():
+    ops, _ = BY_NAME["layernorm_fwd"].build("small")
+    with Plan(ops) as p:
+        assert "generated" not in p.describe()               # hand-written by default
+    with Plan(ops, "generated") as p:
+        assert p.info()["schedule"] == "row" and "generated kernel" in p.describe()
+    with Plan(ops, "prebuilt") as p:
+        assert "generated" not in p.describe()
+    # without run-time compilation a row group that only the generator covers is unsupported
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.log_softmax((8, 64)), mode="prebuilt")
+    # lanes per row is the launch template of the generated kernels
+    with Plan(graphs.log_softmax((300, 64)), rows_per_wave=16) as p:
+        assert "THREAD_16" in p.describe()                   # 4 lanes per row, 16 elements per lane
+    _expect(binding.FS_ERR_INVALID, graphs.log_softmax((300, 64)), rows_per_wave=3)
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.log_softmax((2, 65536)))
+
+
+def test_motivating_pattern_plans_as_one_kernel():
+    ops = graphs.multi_interest_pattern(16384)
+    with Plan(ops) as p:
+        info = p.info()
+        assert info["schedule"] == "row" and info["n_kernels"] == 1
+        assert "reduce x3" in p.describe()                   # max, sum, and the second dot
+        # two 552 MiB outputs, the inputs are megabytes
+        assert info["algorithmic_bytes"] == 1201274880
+        assert info["lds_bytes"] > 0                         # the staging tile of the dense stores
+    with Plan(ops, "per_op") as q:
+        assert q.info()["n_kernels"] == 13
+        assert q.info()["moved_bytes"] > 6 * info["algorithmic_bytes"]
