@@ -198,6 +198,22 @@ fs_status fs_plan_info(const fs_plan* plan, int32_t* schedule, int32_t* n_kernel
  * the plan, valid until fs_destroy.  For logs and tests; nothing parses it. */
 const char* fs_plan_describe(const fs_plan* plan);
 
+/* Shared-memory optimisation (Algorithm 4, Section 5.4) on a caller-given data-flow graph:
+ * which ops may take over the shared (LDS) space of an earlier op.  Pure host work; the
+ * library's kernel generator uses the same routine to lay out the row buffers of its
+ * streamed template.
+ *   operands      host, n x 3 indices of EARLIER ops (execution order), -1 where unused
+ *   req_bytes     host, n entries: shared space the op's result needs, 0 = none
+ *   is_output     host, n entries (non-zero: the group's root consumes the op), or NULL:
+ *                 then every op without a user is an output
+ *   offset        host, n entries out: byte offset of the op's space, -1 = none
+ *   shares_with   host, n entries out, may be NULL: the op whose space was taken over
+ *                 (it is dominated by the op: all its uses lie below the op), -1 = none
+ *   total_bytes   host out: the footprint
+ * Errors: FS_ERR_INVALID (NULL pointer, operand index not smaller than the op's own). */
+fs_status fs_shared_plan(const int32_t* operands, const int64_t* req_bytes, const uint8_t* is_output,
+                         int32_t n, int64_t* offset, int32_t* shares_with, int64_t* total_bytes);
+
 /* Measurement aid: plain streaming copy of `bytes` (multiple of 16) from src to dst,
  * both DEVICE pointers, 16-byte aligned, on `hip_stream`.  Gives the achievable HBM
  * ceiling beside the 8 TB/s peak and the calibration factor for byte counters. */

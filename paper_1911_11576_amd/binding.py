@@ -75,6 +75,9 @@ def lib():
         L.fs_plan_tune.restype = i32
         L.fs_stream_copy.argtypes = [vp, vp, i64, vp]
         L.fs_stream_copy.restype = i32
+        L.fs_shared_plan.argtypes = [C.POINTER(i32), C.POINTER(i64), C.POINTER(C.c_uint8), i32, C.POINTER(i64),
+                                     C.POINTER(i32), C.POINTER(i64)]
+        L.fs_shared_plan.restype = i32
         _lib = L
     return _lib
 
@@ -158,6 +161,24 @@ def fs_plan_info(plan):
 
 def fs_plan_describe(plan):
     return lib().fs_plan_describe(plan).decode()
+
+
+def fs_shared_plan(operands, req_bytes, is_output=None):
+    """Algorithm 4 on a DAG given as per-op operand lists (indices of earlier ops) and shared-
+    space requests in bytes.  -> (offsets, shares_with, total_bytes)."""
+    n = len(operands)
+    ops = (C.c_int32 * (3 * max(n, 1)))(*([-1] * (3 * max(n, 1))))
+    for i, lst in enumerate(operands):
+        assert len(lst) <= 3
+        for j, o in enumerate(lst):
+            ops[3 * i + j] = o
+    req = (C.c_int64 * max(n, 1))(*req_bytes) if n else (C.c_int64 * 1)()
+    outs = None if is_output is None else (C.c_uint8 * max(n, 1))(*[1 if b else 0 for b in is_output])
+    off = (C.c_int64 * max(n, 1))()
+    shr = (C.c_int32 * max(n, 1))()
+    total = C.c_int64(0)
+    _check(lib().fs_shared_plan(ops, req, outs, n, off, shr, C.byref(total)))
+    return list(off[:n]), list(shr[:n]), total.value
 
 
 def fs_stream_copy(dst, src, nbytes, stream=None):

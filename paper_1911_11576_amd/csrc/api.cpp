@@ -14,6 +14,7 @@
 #include "match.h"
 #include "per_op.h"
 #include "row_codegen.h"
+#include "shared_plan.h"
 
 struct fs_plan {
   fs::Graph graph;
@@ -344,6 +345,34 @@ fs_status fs_plan_info(const fs_plan* p, int32_t* schedule, int32_t* n_kernels, 
 }
 
 const char* fs_plan_describe(const fs_plan* p) { return p ? p->description.c_str() : ""; }
+
+fs_status fs_shared_plan(const int32_t* operands, const int64_t* req_bytes, const uint8_t* is_output, int32_t n,
+                         int64_t* offset, int32_t* shares_with, int64_t* total_bytes) {
+  if (n < 0 || (n > 0 && (!operands || !req_bytes || !offset)) || !total_bytes)
+    return set_error(FS_ERR_INVALID, "fs_shared_plan: NULL argument");
+  try {
+    fs::SharedPlanInput in;
+    in.operands.resize(n);
+    in.req_bytes.assign(req_bytes, req_bytes + n);
+    if (is_output) in.is_output.assign(is_output, is_output + n);
+    for (int i = 0; i < n; ++i)
+      for (int j = 0; j < 3; ++j) {
+        const int o = operands[3 * i + j];
+        if (o < 0) continue;
+        if (o >= i) return set_error(FS_ERR_INVALID, "fs_shared_plan: operand index not smaller than the op's own");
+        in.operands[i].push_back(o);
+      }
+    const fs::SharedPlanResult r = fs::shared_plan(in);
+    for (int i = 0; i < n; ++i) {
+      offset[i] = r.offset[i];
+      if (shares_with) shares_with[i] = r.shares_with[i];
+    }
+    *total_bytes = r.total_bytes;
+  } catch (...) {
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  }
+  return FS_OK;
+}
 
 fs_status fs_stream_copy(void* dst, const void* src, int64_t bytes, void* hip_stream) {
   if (bytes < 0 || (bytes & 15)) return set_error(FS_ERR_INVALID, "bytes must be a non-negative multiple of 16");
