@@ -13,11 +13,15 @@
 // through one float each in LDS and a barrier); a lane keeps its K chunks of W consecutive
 // elements of every live full value in registers from the row's one read to its one write.
 #include "row_codegen.h"
+#include "shared_plan.h"
 
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
+#include <functional>
+#include <map>
 
 namespace fs {
 
@@ -323,6 +327,26 @@ std::string const_text(float c) {
   return buf;
 }
 
+
+std::string op_text(int op, const std::string& a, const std::string& b, bool fast) {
+  switch (op) {
+    case FS_ADD: return a + " + " + b;
+    case FS_SUBTRACT: return a + " - " + b;
+    case FS_MULTIPLY: return a + " * " + b;
+    case FS_DIVIDE: return a + " / " + b;
+    case FS_MAXIMUM: return "fmaxf(" + a + ", " + b + ")";
+    case FS_NEGATE: return "-" + a;
+    case FS_EXP: return "expf(" + a + ")";
+    case FS_LOG: return "logf(" + a + ")";
+    case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
+    case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
+    case FS_SQRT: return "sqrtf(" + a + ")";
+    case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
+    case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
+    default: return a;
+  }
+}
+
 struct Gen {
   const Analysis& A;
   int L = 64, K = 1, W = 4;
@@ -344,25 +368,9 @@ struct Gen {
   }
   std::string expr(const RNode& n) const {
     const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
-    switch (n.op) {
-      case FS_ADD: return a + " + " + b;
-      case FS_SUBTRACT: return a + " - " + b;
-      case FS_MULTIPLY: return a + " * " + b;
-      case FS_DIVIDE:
-        // a full value divided by a per-row value: one reciprocal per row, then multiplies
-        if (n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) { char buf[32]; snprintf(buf, sizeof buf, "inv%d", n.o[1].index); return a + " * " + buf; }
-        return a + " / " + b;
-      case FS_MAXIMUM: return "fmaxf(" + a + ", " + b + ")";
-      case FS_NEGATE: return "-" + a;
-      case FS_EXP: return "expf(" + a + ")";
-      case FS_LOG: return "logf(" + a + ")";
-      case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
-      case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
-      case FS_SQRT: return "sqrtf(" + a + ")";
-      case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
-      case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
-      default: return a;
-    }
+    // a full value divided by a per-row value: one reciprocal per row, then multiplies
+    if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
+    return op_text(n.op, a, b, fast);
   }
 
   // offset of the row's first element in a view: "row * c" if the row strides are those of
@@ -691,9 +699,423 @@ struct Gen {
   }
 };
 
+
+// ---------------------------------------------------------------------------------------------
+// Streamed block template: one workgroup walks a row in passes (block composition with
+// intermediates in shared memory, Section 5.1, for rows that do not fit registers).  The
+// reductions split the group into passes: pass p holds everything that needs the results of
+// p rounds of reductions.  A full value computed in one pass and read in a later one is
+// either kept in an LDS row buffer or recomputed from the group's inputs (re-read from HBM);
+// the row buffers are laid out by the shared-memory optimisation (Algorithm 4), which lets a
+// value take over the buffer of a value it dominates -- softmax of a 40 000-element row
+// needs one buffer, not three.  If even the shared layout exceeds the LDS, nothing is kept
+// and every pass streams from HBM: any row length runs.
+struct Stream {
+  const Analysis& A;
+  int W = 4, wg = 512;
+  bool fast = false, cached = true, cache_views = true;
+  std::vector<int> idx_of;            // node id -> index into A.nodes
+  std::vector<int> ready;             // full value: first pass it can be computed in; per-row value: passes that must be over
+  std::vector<int> phase;             // reductions: the pass that accumulates them
+  int n_loops = 1;
+  std::vector<char> cut_node, cut_view;     // kept in a row buffer
+  std::vector<int> first_use;               // per view: the first pass that reads it
+  std::vector<int64_t> off_node, off_view;  // float offset of the buffer
+  std::vector<int> share_node;              // planner's report: index (planner numbering) taken over, -1
+  int64_t lds_floats = 0;
+  int n_buffers = 0, n_shared = 0;
+  std::vector<char> splat;
+  std::vector<std::string> roff;
+  bool coords = false;
+  Emitter e;
+
+  explicit Stream(const Analysis& a) : A(a) {}
+
+  static bool is_red(const RNode& n) { return n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX || n.op == ROP_DOT_REDUCE; }
+
+  void schedule() {
+    const int n = (int)A.nodes.size();
+    idx_of.assign(A.g.size(), -1);
+    for (int i = 0; i < n; ++i) idx_of[A.nodes[i].id] = i;
+    ready.assign(n, 0);
+    phase.assign(n, -1);
+    int last = 0;
+    for (int i = 0; i < n; ++i) {
+      const RNode& x = A.nodes[i];
+      int r = 0;
+      for (int j = 0; j < x.nop; ++j)
+        if (x.o[j].kind == OP_NODE || x.o[j].kind == OP_ROWB) r = std::max(r, ready[idx_of[x.o[j].index]]);
+      if (is_red(x)) { phase[i] = r; ready[i] = r + 1; last = std::max(last, r); }
+      else {
+        ready[i] = r;
+        if (x.cls == CLS_FULL && x.out_ord >= 0) last = std::max(last, r);
+      }
+    }
+    n_loops = last + 1;
+  }
+
+  // which values cross from one pass to a later one
+  void find_cuts(std::vector<std::vector<int>>* targets) {
+    const int n = (int)A.nodes.size();
+    cut_node.assign(n, 0);
+    cut_view.assign(A.views.size(), 0);
+    targets->assign(n_loops, {});
+    for (int i = 0; i < n; ++i) {
+      const RNode& x = A.nodes[i];
+      if (is_red(x)) (*targets)[phase[i]].push_back(i);
+      else if (x.cls == CLS_FULL && x.out_ord >= 0) (*targets)[ready[i]].push_back(i);
+    }
+    first_use.assign(A.views.size(), -1);
+    if (!cached) return;
+    // An input read in two or more passes is kept after its first read; one read in a single
+    // pass (a per-column operand of the epilogue, say) is not worth a buffer.
+    std::vector<std::vector<char>> view_pass(A.views.size(), std::vector<char>(n_loops, 0));
+    for (int p = n_loops - 1; p >= 0; --p) {
+      std::vector<char> seen(n, 0);
+      std::vector<int> stack;
+      auto use_view = [&](int v) { if (!splat_view(v)) view_pass[v][p] = 1; };
+      auto use_full = [&](const Opnd& o) {
+        if (o.kind == OP_VIEW) { use_view(o.index); return; }
+        if (o.kind != OP_NODE) return;
+        const int k = idx_of[o.index];
+        if (A.nodes[k].cls != CLS_FULL) return;
+        if (ready[k] < p) { cut_node[k] = 1; return; }
+        if (!seen[k]) { seen[k] = 1; stack.push_back(k); }
+      };
+      for (int t : (*targets)[p]) {
+        if (is_red(A.nodes[t])) {
+          use_full(A.nodes[t].o[0]);
+          for (int v : A.nodes[t].dot_full) use_view(v);
+        } else if (!seen[t]) { seen[t] = 1; stack.push_back(t); }
+      }
+      for (int k = 0; k < n; ++k)        // values kept for later passes are produced in their own pass
+        if (cut_node[k] && ready[k] == p && !seen[k]) { seen[k] = 1; stack.push_back(k); (*targets)[p].push_back(k); }
+      while (!stack.empty()) {
+        const int k = stack.back();
+        stack.pop_back();
+        const RNode& x = A.nodes[k];
+        for (int j = 0; j < x.nop; ++j) use_full(x.o[j]);
+        for (int v : x.dot_full) use_view(v);
+      }
+    }
+    for (size_t v = 0; v < A.views.size(); ++v) {
+      int uses = 0;
+      for (int p = 0; p < n_loops; ++p) if (view_pass[v][p]) { if (first_use[v] < 0) first_use[v] = p; ++uses; }
+      cut_view[v] = cache_views && uses >= 2;
+    }
+  }
+  bool splat_view(int v) const { return A.views[v].cls == CLS_ROW || A.views[v].stride[A.rank - 1] == 0; }
+
+  // Algorithm 4 over the kept values: ops = views, then nodes in execution order (pass, then list order)
+  void plan_buffers() {
+    const int n = (int)A.nodes.size(), nv = (int)A.views.size();
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    auto time_of = [&](int i) { return is_red(A.nodes[i]) ? phase[i] : ready[i]; };
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return time_of(a) < time_of(b); });
+    std::vector<int> pos(n);
+    for (int k = 0; k < n; ++k) pos[order[k]] = nv + k;
+    SharedPlanInput in;
+    in.operands.resize(nv + n);
+    in.req_bytes.assign(nv + n, 0);
+    in.is_output.assign(nv + n, 0);
+    const int64_t row_bytes = A.cols * 4;
+    for (int v = 0; v < nv; ++v) if (cut_view[v]) in.req_bytes[v] = row_bytes;
+    for (int i = 0; i < n; ++i) {
+      const RNode& x = A.nodes[i];
+      std::vector<int>& ops = in.operands[pos[i]];
+      for (int j = 0; j < x.nop; ++j) {
+        if (x.o[j].kind == OP_NODE || x.o[j].kind == OP_ROWB) ops.push_back(pos[idx_of[x.o[j].index]]);
+        else if (x.o[j].kind == OP_VIEW) ops.push_back(x.o[j].index);
+      }
+      for (int v : x.dot_row) ops.push_back(v);
+      for (int v : x.dot_full) ops.push_back(v);
+      if (cut_node[i]) in.req_bytes[pos[i]] = row_bytes;
+      if (x.out_ord >= 0) in.is_output[pos[i]] = 1;
+    }
+    const SharedPlanResult r = shared_plan(in);
+    off_view.assign(nv, -1);
+    off_node.assign(n, -1);
+    n_buffers = 0; n_shared = 0;
+    for (int v = 0; v < nv; ++v) if (cut_view[v]) { off_view[v] = r.offset[v] / 4; ++n_buffers; }
+    for (int i = 0; i < n; ++i) if (cut_node[i]) {
+      off_node[i] = r.offset[pos[i]] / 4;
+      ++n_buffers;
+      if (r.shares_with[pos[i]] >= 0) ++n_shared;
+    }
+    lds_floats = r.total_bytes / 4;
+  }
+
+  bool geometry(int want_wg, std::string* err) {
+    bool any32 = false, any16 = false;
+    for (const RView& v : A.views) {
+      if (v.dtype != FS_F32) any16 = true;
+      if (v.cls == CLS_FULL && v.stride[A.rank - 1] == 1 && v.dtype == FS_F32) any32 = true;
+    }
+    for (const RNode& n : A.nodes) if (n.out_ord >= 0) {
+      if (n.out_dtype != FS_F32) any16 = true;
+      if (n.cls == CLS_FULL && n.out_dtype == FS_F32) any32 = true;
+    }
+    fast = any16;
+    auto fits = [&](int w) {
+      if (A.cols % w) return false;
+      for (const RView& v : A.views) {
+        if (v.cls != CLS_FULL) continue;
+        const int64_t ls = v.stride[A.rank - 1];
+        if (ls != 0 && ls != 1) return false;
+        if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
+        if (ls == 1 && v.offset % w) return false;
+      }
+      return true;
+    };
+    if (!any32 && fits(8)) W = 8;
+    else if (fits(4)) W = 4;
+    else if (fits(2)) W = 2;
+    else if (fits(1)) W = 1;
+    else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
+    const int64_t nvec = A.cols / W;
+    wg = want_wg ? want_wg : nvec <= 2048 ? 256 : nvec <= 8192 ? 512 : 1024;
+    return true;
+  }
+
+  // ---- emission helpers
+  std::string opnd(const Opnd& o, int consumer_cls) const {
+    char buf[64];
+    switch (o.kind) {
+      case OP_NODE: snprintf(buf, sizeof buf, consumer_cls == CLS_FULL ? "t%d[j]" : "r%d", o.index); return buf;
+      case OP_ROWB: snprintf(buf, sizeof buf, "r%d", o.index); return buf;
+      case OP_VIEW: snprintf(buf, sizeof buf, splat[o.index] ? "s%d" : "v%d[j]", o.index); return buf;
+      default: return const_text(o.cval);
+    }
+  }
+  std::string expr(const RNode& n) const {
+    const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
+    if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
+    return op_text(n.op, a, b, fast);
+  }
+
+  void load_global(const std::string& name, int q) {
+    const RView& v = A.views[q];
+    const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+    e.line("        float %s[W];", name.c_str());
+    e.line("        {");
+    e.line("          const %s* p = static_cast<const %s*>(a.in[%d]) + (%s) + col;", ty, ty, q, roff[q].c_str());
+    if (W == 1) {
+      e.line("          %s[0] = %s;", name.c_str(), v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])");
+    } else if (v.dtype == FS_F32 && W == 2) {
+      e.line("          const f32x2 x = *reinterpret_cast<const f32x2*>(p); %s[0] = x[0]; %s[1] = x[1];", name.c_str(), name.c_str());
+    } else if (v.dtype == FS_F32) {
+      for (int h = 0; h < W / 4; ++h)
+        e.line("          { const f32x4 x = *(reinterpret_cast<const f32x4*>(p) + %d); UNROLL for (int j = 0; j < 4; ++j) %s[%d + j] = x[j]; }", h, name.c_str(), 4 * h);
+    } else {
+      const char* lo = v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
+      const char* hi = v.dtype == FS_F16 ? "f16_hi" : "bf16_hi";
+      if (W == 2) e.line("          const unsigned x[1] = {*reinterpret_cast<const unsigned*>(p)};");
+      else e.line("          const %s x = *reinterpret_cast<const %s*>(p);", W == 8 ? "u32x4" : "u32x2", W == 8 ? "u32x4" : "u32x2");
+      e.line("          UNROLL for (int j = 0; j < W / 2; ++j) { %s[2 * j] = %s(x[j]); %s[2 * j + 1] = %s(x[j]); }", name.c_str(), lo, name.c_str(), hi);
+    }
+    e.line("        }");
+  }
+  void store_global(const RNode& n) {
+    e.line("        {");
+    if (n.out_dtype == FS_F32) {
+      e.line("          float* p = static_cast<float*>(a.out[%d]) + row * %lldll + col;", n.out_ord, (long long)A.cols);
+      if (W == 1) e.line("          p[0] = t%d[0];", n.id);
+      else if (W == 2) e.line("          __builtin_nontemporal_store(f32x2{t%d[0], t%d[1]}, reinterpret_cast<f32x2*>(p));", n.id, n.id);
+      else for (int h = 0; h < W / 4; ++h)
+        e.line("          __builtin_nontemporal_store(f32x4{t%d[%d], t%d[%d], t%d[%d], t%d[%d]}, reinterpret_cast<f32x4*>(p) + %d);",
+               n.id, 4 * h, n.id, 4 * h + 1, n.id, 4 * h + 2, n.id, 4 * h + 3, h);
+    } else {
+      const char* cv = n.out_dtype == FS_F16 ? "to_f16" : "to_bf16";
+      e.line("          unsigned short* p = static_cast<unsigned short*>(a.out[%d]) + row * %lldll + col;", n.out_ord, (long long)A.cols);
+      if (W == 1) e.line("          p[0] = (unsigned short)%s(t%d[0]);", cv, n.id);
+      else {
+        e.line("          unsigned w[W / 2];");
+        e.line("          UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[2 * j]) | (%s(t%d[2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+        if (W == 8) e.line("          __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
+        else if (W == 4) e.line("          __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
+        else e.line("          __builtin_nontemporal_store(w[0], reinterpret_cast<unsigned*>(p));");
+      }
+    }
+    e.line("        }");
+  }
+
+  void emit(const std::vector<std::vector<int>>& targets, std::string* kernel_name) {
+    const int n = (int)A.nodes.size(), nv = (int)A.views.size(), nrow = A.rank - 1, T = wg / 64;
+    splat.assign(nv, 0);
+    roff.assign(nv, "");
+    // row offsets reuse the register templates' logic
+    Gen helper(A);
+    for (int q = 0; q < nv; ++q) { splat[q] = splat_view(q); roff[q] = helper.row_offset(A.views[q], &coords); }
+    std::vector<char> is_divisor(A.g.size(), 0);
+    for (const RNode& x : A.nodes) if (x.op == FS_DIVIDE && x.cls == CLS_FULL && x.o[1].kind == OP_ROWB) is_divisor[x.o[1].index] = 1;
+    int n_red = 0;
+    std::vector<int> red_slot(n, -1);
+    for (int i = 0; i < n; ++i) if (is_red(A.nodes[i])) red_slot[i] = n_red++;
+
+    e.s = ew_preamble();
+    e.s += kReducePreamble;
+    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", wg);
+    e.line("  constexpr int W = %d, NVEC = %lld, WG = %d, T = %d;", W, (long long)(A.cols / W), wg, T);
+    if (lds_floats > 0) e.line("  __shared__ float rowbuf[%lld];", (long long)lds_floats);
+    if (n_red > 0) e.line("  __shared__ float exch[%d][T];", n_red);
+    e.line("  for (long long row = blockIdx.x; row < %lldll; row += gridDim.x) {", (long long)A.rows);
+    if (coords) {
+      e.line("    unsigned long long rr = (unsigned long long)row;");
+      for (int d = nrow - 1; d >= 0; --d) {
+        if (A.S[d] == 1) { e.line("    const long long i%d = 0;", d); continue; }
+        e.line("    const long long i%d = rr %% %lldull; rr /= %lldull;", d, (long long)A.S[d], (long long)A.S[d]);
+      }
+    }
+    for (int q = 0; q < nv; ++q) if (splat[q]) {
+      const RView& v = A.views[q];
+      const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+      const char* one = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
+      e.line("    float s%d;", q);
+      e.line("    { const %s* p = static_cast<const %s*>(a.in[%d]) + (%s); s%d = %s; }", ty, ty, q, roff[q].c_str(), q, one);
+    }
+    // per-row values that need no pass at all, then pass by pass
+    auto row_ops = [&](int avail) {
+      for (int i = 0; i < n; ++i) {
+        const RNode& x = A.nodes[i];
+        if (x.cls != CLS_ROW || is_red(x) || ready[i] != avail) continue;
+        e.line("    const float r%d = %s;", x.id, expr(x).c_str());
+        if (is_divisor[x.id]) e.line("    const float inv%d = 1.0f / r%d;", x.id, x.id);
+        row_out(x);
+      }
+    };
+    row_ops(0);
+    for (int p = 0; p < n_loops; ++p) {
+      for (int t : targets[p]) if (is_red(A.nodes[t]))
+        e.line("    float r%d = %s;", A.nodes[t].id, A.nodes[t].op == FS_REDUCE_MAX ? "-__builtin_inff()" : "0.0f");
+      e.line("    for (int c = threadIdx.x; c < NVEC; c += WG) {      // pass %d", p);
+      e.line("      const int col = c * W;");
+      e.line("      {");
+      std::vector<char> have_node(n, 0), have_view(nv, 0);
+      std::function<void(int)> need_view = [&](int q) {
+        if (splat[q] || have_view[q]) return;
+        have_view[q] = 1;
+        char name[16];
+        snprintf(name, sizeof name, "v%d", q);
+        if (cached && cut_view[q] && p > first_use[q]) {
+          e.line("        float %s[W];", name);
+          e.line("        UNROLL for (int j = 0; j < W; ++j) %s[j] = rowbuf[%lld + col + j];", name, (long long)off_view[q]);
+        } else {
+          load_global(name, q);
+        }
+      };
+      std::function<void(int)> need_node = [&](int k) {
+        if (have_node[k]) return;
+        have_node[k] = 1;
+        const RNode& x = A.nodes[k];
+        if (cached && cut_node[k] && ready[k] < p) {
+          e.line("        float t%d[W];", x.id);
+          e.line("        UNROLL for (int j = 0; j < W; ++j) t%d[j] = rowbuf[%lld + col + j];", x.id, (long long)off_node[k]);
+          return;
+        }
+        for (int j = 0; j < x.nop; ++j) {
+          if (x.o[j].kind == OP_VIEW) need_view(x.o[j].index);
+          else if (x.o[j].kind == OP_NODE && A.nodes[idx_of[x.o[j].index]].cls == CLS_FULL) need_node(idx_of[x.o[j].index]);
+        }
+        for (int v : x.dot_full) need_view(v);
+        e.line("        float t%d[W];", x.id);
+        if (x.op == ROP_DOT_OUTER) {
+          std::string ex;
+          for (size_t k2 = 0; k2 < x.dot_row.size(); ++k2) {
+            char buf[96];
+            if (k2 == 0) snprintf(buf, sizeof buf, "s%d * v%d[j]", x.dot_row[k2], x.dot_full[k2]);
+            else snprintf(buf, sizeof buf, "fmaf(s%d, v%d[j], ", x.dot_row[k2], x.dot_full[k2]);
+            ex = k2 == 0 ? std::string(buf) : std::string(buf) + ex + ")";
+          }
+          e.line("        UNROLL for (int j = 0; j < W; ++j) t%d[j] = %s;", x.id, ex.c_str());
+        } else {
+          e.line("        UNROLL for (int j = 0; j < W; ++j) t%d[j] = %s;", x.id, expr(x).c_str());
+        }
+      };
+      // everything this pass reads is loaded before anything it writes is stored: a value may
+      // take over the buffer of the value it was computed from
+      for (int t : targets[p]) {
+        const RNode& x = A.nodes[t];
+        if (is_red(x)) {
+          if (x.o[0].kind == OP_VIEW) need_view(x.o[0].index);
+          else if (x.o[0].kind == OP_NODE) need_node(idx_of[x.o[0].index]);
+          for (int v : x.dot_full) need_view(v);
+        } else need_node(t);
+      }
+      if (cached) for (int q = 0; q < nv; ++q) if (cut_view[q] && first_use[q] == p) need_view(q);
+      for (int t : targets[p]) {
+        const RNode& x = A.nodes[t];
+        if (!is_red(x)) continue;
+        const std::string v = opnd(x.o[0], CLS_FULL);
+        if (x.op == FS_REDUCE_SUM) e.line("        UNROLL for (int j = 0; j < W; ++j) r%d = r%d + %s;", x.id, x.id, v.c_str());
+        else if (x.op == FS_REDUCE_MAX) e.line("        UNROLL for (int j = 0; j < W; ++j) r%d = fmaxf(r%d, %s);", x.id, x.id, v.c_str());
+        else e.line("        UNROLL for (int j = 0; j < W; ++j) r%d = fmaf(%s, v%d[j], r%d);", x.id, v.c_str(), x.dot_full[0], x.id);
+      }
+      if (cached) {
+        for (int q = 0; q < nv; ++q) if (cut_view[q] && first_use[q] == p)
+          e.line("        UNROLL for (int j = 0; j < W; ++j) rowbuf[%lld + col + j] = v%d[j];", (long long)off_view[q], q);
+        for (int k = 0; k < n; ++k) if (cut_node[k] && ready[k] == p)
+          e.line("        UNROLL for (int j = 0; j < W; ++j) rowbuf[%lld + col + j] = t%d[j];", (long long)off_node[k], A.nodes[k].id);
+      }
+      for (int t : targets[p]) {
+        const RNode& x = A.nodes[t];
+        if (!is_red(x) && x.out_ord >= 0) store_global(x);
+      }
+      e.line("      }");
+      e.line("    }");
+      // combine this pass's reductions: wavefront steps, one LDS slot per wavefront, one barrier
+      bool any = false;
+      for (int t : targets[p]) if (is_red(A.nodes[t])) {
+        const RNode& x = A.nodes[t];
+        const char* op = x.op == FS_REDUCE_MAX ? "MaxOp" : "SumOp";
+        e.line("    r%d = lanes_allreduce<%s, 64>(r%d);", x.id, op, x.id);
+        if (T > 1) e.line("    if ((threadIdx.x & 63) == 0) exch[%d][threadIdx.x >> 6] = r%d;", red_slot[t], x.id);
+        any = true;
+      }
+      if (any && T > 1) {
+        e.line("    __syncthreads();");
+        for (int t : targets[p]) if (is_red(A.nodes[t])) {
+          const RNode& x = A.nodes[t];
+          const char* op = x.op == FS_REDUCE_MAX ? "MaxOp" : "SumOp";
+          e.line("    r%d = exch[%d][0];", x.id, red_slot[t]);
+          e.line("    UNROLL for (int w = 1; w < T; ++w) r%d = %s::apply(r%d, exch[%d][w]);", x.id, op, x.id, red_slot[t]);
+        }
+      }
+      for (int t : targets[p]) if (is_red(A.nodes[t])) {
+        const RNode& x = A.nodes[t];
+        if (is_divisor[x.id]) e.line("    const float inv%d = 1.0f / r%d;", x.id, x.id);
+        row_out(x);
+      }
+      row_ops(p + 1);
+    }
+    if (n_red > 0 && T > 1) e.line("    __syncthreads();      // the exchange slots are reused by the next row");
+    e.line("  }");
+    e.line("}");
+    uint64_t h = 1469598103934665603ull;
+    for (unsigned char c : e.s) { h ^= c; h *= 1099511628211ull; }
+    char name[32];
+    snprintf(name, sizeof name, "fs_row_%08x", (unsigned)(h ^ (h >> 32)));
+    *kernel_name = name;
+    const std::string tag = "FS_ROW_NAME";
+    e.s.replace(e.s.find(tag), tag.size(), name);
+  }
+  void row_out(const RNode& x) {
+    if (x.out_ord < 0) return;
+    if (x.out_dtype == FS_F32) e.line("    if (threadIdx.x == 0) static_cast<float*>(a.out[%d])[row] = r%d;", x.out_ord, x.id);
+    else e.line("    if (threadIdx.x == 0) static_cast<unsigned short*>(a.out[%d])[row] = (unsigned short)%s(r%d);", x.out_ord,
+                x.out_dtype == FS_F16 ? "to_f16" : "to_bf16", x.id);
+  }
+};
+
 struct GenArgs { const void* in[24]; void* out[8]; };   // mirrors Args of the generated source
 
 }  // namespace
+
+static void dump_source(const std::string& src) {
+  if (const char* dump = getenv("FS_DUMP_SOURCE")) {        // debugging aid: append what was generated
+    if (FILE* f = fopen(dump, "a")) { fputs(src.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
+  }
+}
 
 bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int* status, std::string* err) {
   *status = FS_ERR_UNSUPPORTED;
@@ -701,9 +1123,10 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   if (!A.run()) { *err = A.err; return false; }
   Gen gen(A);
   RowGenLaunch l;
-  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
+  const bool want_stream = opt.grid > 0;        // a fixed number of workgroups: the streamed template
+  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 1024 || opt.wg_size % 64 || (!want_stream && opt.wg_size > 256))) {
     *status = FS_ERR_INVALID;
-    *err = "generated row schedule: wg_size must be 64, 128, 192 or 256";
+    *err = "generated row schedule: wg_size must be 64, 128, 192 or 256 (a multiple of 64 up to 1024 with a fixed grid)";
     return false;
   }
   if (opt.rows_per_wave) {
@@ -716,25 +1139,70 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     }
     gen.lanes_per_row = 64 / r;
   }
-  gen.wg = opt.wg_size ? opt.wg_size : 256;
-  if (gen.wg == 192) gen.wg = 128;            // lanes per row divide the workgroup
-  if (!gen.geometry(err)) return false;
-  gen.emit(&l.kernel_name);
-  if (const char* dump = getenv("FS_DUMP_SOURCE")) {
-    if (FILE* f = fopen(dump, "a")) { fputs(gen.e.s.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
-  }
-  std::string cerr;
-  if (!ew_compile_source(gen.e.s, &l.code_object, &cerr)) { *err = "generated row schedule: " + cerr; return false; }
-  l.L = gen.L; l.K = gen.K; l.W = gen.W;
   l.rows = A.rows; l.cols = A.cols;
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
-  l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : gen.stage_bytes;
   for (const RView& v : A.views) l.view_param.push_back(v.param);
-  l.wg = l.L > 64 ? l.L : gen.wg;     // a team is one workgroup per row
-  const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;
-  int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
-  if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
+  gen.wg = opt.wg_size && opt.wg_size <= 256 ? opt.wg_size : 256;
+  if (gen.wg == 192) gen.wg = 128;            // lanes per row divide the workgroup
+  std::string gerr;
+  if (!want_stream && gen.geometry(&gerr)) {
+    // the row lives in registers
+    gen.emit(&l.kernel_name);
+    dump_source(gen.e.s);
+    std::string cerr;
+    if (!ew_compile_source(gen.e.s, &l.code_object, &cerr)) { *err = "generated row schedule: " + cerr; return false; }
+    l.L = gen.L; l.K = gen.K; l.W = gen.W;
+    l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : gen.stage_bytes;
+    l.wg = l.L > 64 ? l.L : gen.wg;     // a team is one workgroup per row
+    const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;
+    int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
+    if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
+    l.grid = (int)(grid < 1 ? 1 : grid);
+    *out = l;
+    *status = FS_OK;
+    return true;
+  }
+  if (!want_stream && (opt.rows_per_wave || gerr.find("row longer") == std::string::npos)) { *err = gerr; return false; }
+
+  // the row is streamed in passes by one workgroup
+  Stream st(A);
+  if (!st.geometry(opt.wg_size, err)) return false;
+  st.schedule();
+  std::vector<std::vector<int>> targets;
+  const int64_t kLdsLimit = 160 * 1024 - 512;
+  st.cached = true;
+  st.splat.assign(A.views.size(), 0);
+  st.find_cuts(&targets);
+  st.plan_buffers();
+  const int64_t exch_bytes = (int64_t)A.n_reduce * (st.wg / 64) * 4;
+  if (st.lds_floats * 4 + exch_bytes > kLdsLimit) {
+    // the shared layout does not fit: keep computed values only and re-read the inputs ...
+    st.cache_views = false;
+    st.find_cuts(&targets);
+    st.plan_buffers();
+  }
+  if (st.lds_floats * 4 + exch_bytes > kLdsLimit) {
+    // ... or keep nothing: every pass recomputes from the inputs
+    st.cached = false;
+    st.find_cuts(&targets);
+    st.lds_floats = 0; st.n_buffers = 0; st.n_shared = 0;
+  }
+  st.emit(targets, &l.kernel_name);
+  dump_source(st.e.s);
+  std::string cerr;
+  if (!ew_compile_source(st.e.s, &l.code_object, &cerr)) { *err = "generated row schedule: " + cerr; return false; }
+  l.streamed = true;
+  l.passes = st.n_loops;
+  l.row_buffers = st.n_buffers;
+  l.buffers_shared = st.n_shared;
+  l.inputs_cached = st.cached && st.cache_views;
+  l.W = st.W; l.L = st.wg; l.K = 0;
+  l.wg = st.wg;
+  l.lds_bytes = st.lds_floats * 4 + (int64_t)A.n_reduce * (st.wg / 64) * 4;
+  int64_t grid = A.rows;
+  if (opt.grid > 0 && opt.grid < grid) grid = opt.grid;
+  if (grid > (1 << 22)) grid = 1 << 22;
   l.grid = (int)(grid < 1 ? 1 : grid);
   *out = l;
   *status = FS_OK;
@@ -742,7 +1210,14 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
 }
 
 std::string row_gen_describe(const RowGenLaunch& l) {
-  char buf[320];
+  char buf[400];
+  if (l.streamed) {
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d] streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.n_ops - l.n_reduce, l.W, l.passes, l.row_buffers, l.buffers_shared,
+             l.passes > 1 && !l.inputs_cached ? ", inputs re-read per pass" : "",
+             l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
+    return buf;
+  }
   snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
            l.n_reduce, l.L == 1 ? "THREAD" : l.L > 64 ? "CTA-S" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : l.L > 64 ? "CTA" : "WARP", l.K * l.W,
            l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);

@@ -15,6 +15,9 @@ struct RowGenLaunch {
   int wg = 256, grid = 1;
   int L = 64, K = 1, W = 4;           // lanes per row, chunks per lane, elements per chunk
   int n_ops = 0, n_reduce = 0;
+  bool streamed = false;              // one workgroup walks the row in passes
+  int passes = 1, row_buffers = 0, buffers_shared = 0;
+  bool inputs_cached = true;
   int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view
   std::vector<char> code_object;

@@ -250,7 +250,15 @@ def test_generated_mode_and_prebuilt_mode_on_recognised_groups():
     with Plan(graphs.log_softmax((300, 64)), rows_per_wave=16) as p:
         assert "THREAD_16" in p.describe()                   # 4 lanes per row, 16 elements per lane
     _expect(binding.FS_ERR_INVALID, graphs.log_softmax((300, 64)), rows_per_wave=3)
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.log_softmax((2, 65536)))
+    # rows beyond the register templates are streamed in passes; Algorithm 4 lays out the LDS row buffers
+    with Plan(graphs.log_softmax((2, 40000))) as p:
+        assert "streamed in 3 passes" in p.describe() and "1 taken over" in p.describe()
+        assert p.info()["lds_bytes"] <= 160 * 1024
+    with Plan(graphs.log_softmax((2, 262144))) as p:
+        assert "re-read per pass" in p.describe()
+    with Plan(graphs.log_softmax((300, 64)), grid=8, wg_size=512) as p:
+        assert "streamed" in p.describe() and "cta_num=8" in p.describe() and "cta_size=512" in p.describe()
+    _expect(binding.FS_ERR_INVALID, graphs.log_softmax((300, 64)), wg_size=512)    # register templates: up to 256
 
 
 def test_motivating_pattern_plans_as_one_kernel():
