@@ -246,12 +246,20 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
       for (int u : {1, 2, 4}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, u, 0});
     cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});   // hand-written against generated
   } else if (base->schedule == FS_SCHED_ROW && base->row_form == 3) {
-    // generated row kernel: lanes per row around the default (templates that do not fit the
-    // row are skipped when their plan fails), two workgroup sizes
-    const int rpw = 64 / base->row_gen.L;
-    for (int r : {rpw / 2, rpw * 2, rpw * 4, 64})
-      if (r >= 1 && r <= 64 && r != rpw) cands.push_back(fs_plan_options{FS_MODE_STITCHED, 0, r, 0});
-    for (int wg : {64, 128}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    const fs::RowGenLaunch& rg = base->row_gen;
+    const int all_rows = (int)(rg.rows < (1 << 22) ? rg.rows : (1 << 22));
+    if (rg.streamed || rg.L > 64) {
+      // long rows: the streamed template under three workgroup sizes (against the register
+      // team, if that is the default)
+      for (int wg : {256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, all_rows});
+    } else {
+      // lanes per row around the default (templates that do not fit the row are skipped when
+      // their plan fails), two workgroup sizes
+      const int rpw = 64 / rg.L;
+      for (int r : {rpw / 2, rpw * 2, rpw * 4, 64})
+        if (r >= 1 && r <= 64 && r != rpw) cands.push_back(fs_plan_options{FS_MODE_STITCHED, 0, r, 0});
+      for (int wg : {64, 128}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
+    }
   } else if (base->schedule == FS_SCHED_ROW) {
     for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
     cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});
