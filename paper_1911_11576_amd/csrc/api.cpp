@@ -101,9 +101,12 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           p->description = fs::ew_stitch_describe(p->ew);
         } else if (lo.codegen && has_reduce && fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) {
           p->match.kind = fs::MATCH_NONE;
-          p->schedule = FS_SCHED_ROW;
+          p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
           p->row_form = 3;
           p->lds_bytes = p->row_gen.lds_bytes;
+          p->workspace_bytes = p->row_gen.workspace_bytes;
+          p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
+          p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
           p->description = fs::row_gen_describe(p->row_gen);
         } else if (!recognised) {
           if (has_reduce && lo.codegen) { st = st2; err = err2; }
@@ -115,6 +118,22 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           return set_error(FS_ERR_INVALID, err2);
         }
       }
+      // a recognised group whose hand-written kernel does not take its size: the generated row kernel
+      auto fall_back_to_generated = [&]() {
+        if (!lo.codegen) return false;
+        int st2 = FS_OK;
+        std::string err2;
+        if (!fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) return false;
+        p->match.kind = fs::MATCH_NONE;
+        p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
+        p->row_form = 3;
+        p->lds_bytes = p->row_gen.lds_bytes;
+        p->workspace_bytes = p->row_gen.workspace_bytes;
+        p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
+        p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
+        p->description = fs::row_gen_describe(p->row_gen);
+        return true;
+      };
       switch (p->match.kind) {
         case fs::MATCH_NONE: break;   // elementwise schedule, set up above
         case fs::MATCH_ROW:
@@ -133,13 +152,22 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
             // unaligned or very long row: block-composed form, row cached in LDS
             int st = FS_OK;
             fs::LaunchOpts lb = lo;
-            if (!fs::row_block_plan(p->match.row, lb, &p->row_block, &st, &err)) { delete p; return set_error((fs_status)st, err); }
+            if (!fs::row_block_plan(p->match.row, lb, &p->row_block, &st, &err)) {
+              if (st != FS_ERR_INVALID && fall_back_to_generated()) break;
+              delete p;
+              return set_error((fs_status)st, err);
+            }
             p->row_form = 2;
             p->lds_bytes = p->row_block.lds_bytes;
             p->description = fs::row_block_describe(p->match.row, p->row_block);
           }
           break;
         case fs::MATCH_LNBWD:
+          // The generated kernel (row work and column sums packed, one partial row per workgroup,
+          // then the combine kernel) measured faster than the hand-written single kernel, whose
+          // in-kernel ticket tree costs a serial tail: 71 against 81 us on config 5.  It is the
+          // default where kernels may be generated; the hand-written one serves the prebuilt mode.
+          if (lo.codegen && fall_back_to_generated()) break;
           if (!fs::lnbwd_stitch_plan(p->match.lnbwd, lo, &p->lnbwd, &err)) {
             const bool bad_opt = err.find("wg_size") != std::string::npos;
             delete p;
@@ -210,12 +238,15 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
     int rc = 0;
     switch (p->schedule) {
       case FS_SCHED_ROW:
-        rc = p->row_form == 3   ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, hip_stream, &err)
+        rc = p->row_form == 3   ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, p->workspace, hip_stream, &err)
              : p->row_form == 2 ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
              : p->row_form == 1 ? fs::row_team_launch(p->match.row, p->row_team, inputs, outputs, hip_stream, &err)
                                 : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
         break;
-      case FS_SCHED_ROW_COL: rc = fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err); break;
+      case FS_SCHED_ROW_COL:
+        rc = p->row_form == 3 ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, p->workspace, hip_stream, &err)
+                              : fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err);
+        break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
       case FS_SCHED_ELEMENTWISE: rc = fs::ew_stitch_launch(p->ew, inputs, outputs, n_out, hip_stream, &err); break;
       default: rc = fs::per_op_launch(g, p->per_op, inputs, outputs, p->workspace, hip_stream, &err); break;
@@ -264,8 +295,11 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
     for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
     cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});
   } else if (base->schedule == FS_SCHED_ROW_COL) {
+    // generated (two kernels) against hand-written (one kernel, where it matches the group)
+    for (int wg : {128, 256, 512})
+      for (int grid : {256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
     for (int wg : {256, 384, 512})
-      for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
+      for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED_PREBUILT, wg, 0, grid});
   } else if (base->schedule == FS_SCHED_ELEMENTWISE) {
     // the generated kernel under two workgroup sizes, and the interpreted form
     for (int wg : {128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});

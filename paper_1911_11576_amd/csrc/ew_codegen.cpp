@@ -41,7 +41,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-struct Args { const void* in[24]; void* out[8]; };
+struct Args { const void* in[24]; void* out[8]; void* ws; };
 #define UNROLL _Pragma("unroll")
 static __device__ __forceinline__ float bits_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 static __device__ __forceinline__ unsigned f32_bits(float f) { return __builtin_bit_cast(unsigned, f); }

@@ -580,7 +580,7 @@ struct EwCompiler {
 }  // namespace
 
 // The generated kernel's arguments: one pointer per operand view, one per output.
-struct EwGenArgs { const void* in[24]; void* out[8]; };
+struct EwGenArgs { const void* in[24]; void* out[8]; void* ws; };
 static_assert(kEwMaxViews <= 24 && kEwMaxOuts == 8, "EwGenArgs mirrors the Args struct of the generated source");
 
 bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* status, std::string* err) {

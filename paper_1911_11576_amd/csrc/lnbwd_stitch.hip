@@ -351,7 +351,15 @@ std::string lnbwd_stitch_describe(const LnBwdSpec& sp, const LnBwdLaunch& l) {
 
 int lnbwd_stitch_launch(const LnBwdSpec& sp, const LnBwdLaunch& l, const void* const* in, void* const* out,
                         void* workspace, void* stream, std::string* err) {
-  if (sp.rows == 0 || sp.cols == 0) return 0;   // empty column sums are handled by the caller
+  if (sp.cols == 0) return 0;
+  if (sp.rows == 0) {
+    // sums over zero rows are zero: the combine kernel over zero partial rows writes them
+    void* col_out[2];
+    int dtype[2] = {DT_F32, DT_F32}, n = 0;
+    if (sp.out_dgamma >= 0) col_out[n++] = out[sp.out_dgamma];
+    if (sp.out_dbeta >= 0) col_out[n++] = out[sp.out_dbeta];
+    return col_combine_launch(nullptr, 0, sp.cols, n, col_out, dtype, stream, err);
+  }
   const bool want_dx = sp.out_dx >= 0;
   const bool want_col = sp.out_dgamma >= 0 || sp.out_dbeta >= 0;
   LnBwdArgs a{};

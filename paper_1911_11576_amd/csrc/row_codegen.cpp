@@ -14,10 +14,13 @@
 // elements of every live full value in registers from the row's one read to its one write.
 #include "row_codegen.h"
 #include "shared_plan.h"
+#include "launchers.h"
 
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <hip/hip_runtime.h>
+
 #include <cstring>
 #include <algorithm>
 #include <functional>
@@ -29,7 +32,7 @@ const char* ew_preamble();   // ew_codegen.cpp: typedefs, Args, dtype conversion
 
 namespace {
 
-enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2 };
+enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2, CLS_COL = 3 };   // COL: one value per column (reduced over the rows)
 enum OpndKind : int { OP_NODE = 0, OP_ROWB = 1, OP_VIEW = 2, OP_CONST = 3 };
 
 struct Opnd { int kind = OP_NODE; int index = -1; float cval = 0.f; };
@@ -60,6 +63,7 @@ struct Analysis {
   std::vector<RNode> nodes;
   std::vector<RView> views;
   int n_reduce = 0;
+  int n_col = 0;                 // column reductions (over the rows), results are outputs only
 
   explicit Analysis(const Graph& gr) : g(gr) {}
   bool fail(const std::string& m) { err = m; return false; }
@@ -253,7 +257,15 @@ struct Analysis {
       if (!is_compute(i)) continue;       // widening convert: alias
       RNode r;
       r.id = i;
-      if (is_reduce(k)) {
+      if (is_reduce(k) && rank == 2 && x.axis == 0 && x.rank == 1 && x.shape[0] == S[1]) {
+        // a reduction over the rows: packed with the row work over the same register-resident rows
+        if (k != FS_REDUCE_SUM) return fail("generated row schedule: only sums are reduced over the rows");
+        if (out_ord[i] < 0) return fail("generated row schedule: a column-reduced value must be a group output");
+        r.cls = CLS_COL; r.op = k; r.nop = 1;
+        cls[i] = CLS_COL;
+        if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
+        ++n_col;
+      } else if (is_reduce(k)) {
         if (x.axis != rank - 1 || !shape_is_row(x)) return fail("generated row schedule: reduction not over the last dim of the group's shape");
         r.cls = CLS_ROW; r.op = k; r.nop = 1;
         cls[i] = CLS_ROW;
@@ -293,6 +305,15 @@ struct Emitter {
 // wave64 all-reduce over aligned groups of L lanes: DPP inside a 16-lane row, the gfx950
 // permlane swaps across rows; every lane of the wavefront must be active
 const char* kReducePreamble = R"SRC(
+// the value of lane (own ^ mask) of a double, as two 32-bit permutes
+static __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+  const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int addr = (lane ^ mask) << 2;
+  const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_ds_bpermute(addr, (int)(unsigned)u);
+  const unsigned hi = (unsigned)__builtin_amdgcn_ds_bpermute(addr, (int)(unsigned)(u >> 32));
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
 template <int CTRL> static __device__ __forceinline__ float dpp_move(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
 }
@@ -375,7 +396,7 @@ struct Gen {
 
   // offset of the row's first element in a view: "row * c" if the row strides are those of
   // a dense tensor scaled by a constant, else from the row's coordinates
-  std::string row_offset(const RView& v, bool* needs_coords) const {
+  std::string row_offset(const RView& v, bool* needs_coords, const char* rowvar = "row") const {
     const int nrow = A.rank - 1;
     char buf[160];
     if (nrow == 0) { snprintf(buf, sizeof buf, "%lldll", (long long)v.offset); return buf; }
@@ -388,7 +409,7 @@ struct Gen {
     }
     if (linear) {
       if (unit == 0) snprintf(buf, sizeof buf, "%lldll", (long long)v.offset);
-      else snprintf(buf, sizeof buf, "row * %lldll + %lldll", (long long)unit, (long long)v.offset);
+      else snprintf(buf, sizeof buf, "%s * %lldll + %lldll", rowvar, (long long)unit, (long long)v.offset);
       return buf;
     }
     *needs_coords = true;
@@ -404,6 +425,7 @@ struct Gen {
 
   int lanes_per_row = 0;      // 0: choose
   int wg = 256;               // workgroup size the kernel is generated for
+  bool persistent = false;    // a fixed grid loops over the rows (groups with column reductions)
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
@@ -465,7 +487,12 @@ struct Gen {
     // Short rows that do not fill whole 128-byte lines: a workgroup's rows are contiguous in
     // memory, so its full outputs are first laid out in LDS and then stored as one dense run
     // of 16-byte accesses (stores of separate row pieces straddle lines and measured 2x slower).
-    if (L <= 64) {
+    if (A.n_col > 0) {
+      if (L > 64) { *err = "generated row schedule: column reductions with rows longer than one wavefront's registers"; return false; }
+      if ((int64_t)A.n_col * A.cols * 8 > 96 * 1024) { *err = "generated row schedule: column accumulators exceed the LDS"; return false; }
+      persistent = true;
+    }
+    if (L <= 64 && !persistent) {
       int min_out = 4;
       bool full_out = false;
       for (const RNode& n : A.nodes) if (n.out_ord >= 0 && n.cls == CLS_FULL) { full_out = true; if (n.out_dtype != FS_F32) min_out = 2; }
@@ -480,10 +507,11 @@ struct Gen {
 
   void emit(std::string* kernel_name) {
     const int rank = A.rank, nrow = rank - 1;
+    std::string advance;        // persistent form: hand the prefetched vectors to the next iteration
     e.s = ew_preamble();
     e.s += kReducePreamble;
     const int T = L > 64 ? L / 64 : 1;      // wavefronts per row
-    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", L > 256 ? L : 256);
+    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", L > 256 ? L : wg > 256 ? wg : 256);
     e.line("  constexpr int L = %d, K = %d, W = %d;", L, K, W);
     if (T > 1) {
       // one workgroup of T wavefronts per row; every reduction has its own exchange slots, so one
@@ -494,7 +522,7 @@ struct Gen {
       e.line("  long long row = blockIdx.x;");
     } else {
       e.line("  const int lane = threadIdx.x & (L - 1);");
-      e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
+      if (!persistent) e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
     }
     if (stage) {
       e.line("  constexpr int RPW = %d, N = %lld;            // rows per workgroup, row length", wg / L, (long long)A.cols);
@@ -503,6 +531,21 @@ struct Gen {
       e.line("  const long long wg_row0 = (long long)blockIdx.x * RPW;");
       e.line("  const long long left = %lldll - wg_row0;", (long long)A.rows);
       e.line("  const int wg_count = (int)(left < RPW ? left : RPW) * N;   // elements this workgroup owns");
+    }
+    e.line("  int col[K]; bool ok[K];");
+    e.line("  UNROLL for (int k = 0; k < K; ++k) { const int c = k * L + lane; ok[k] = c < %lld; col[k] = (ok[k] ? c : 0) * W; }",
+           (long long)(A.cols / W));
+    if (persistent) {
+      // Column reductions: every lane keeps a double-precision running sum for each of its
+      // columns while the workgroups loop over the rows; the sums of a workgroup meet in LDS
+      // and leave as one partial row per workgroup (a second, tiny kernel adds the partial rows).
+      for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        e.line("  double ca%d[K][W];", n.id);
+        e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = 0.0;", n.id);
+      }
+      e.line("  constexpr int RPW = %d;                      // rows a workgroup handles at a time", wg / L);
+      e.line("  for (long long row0 = (long long)blockIdx.x * RPW; row0 < %lldll; row0 += (long long)gridDim.x * RPW) {", (long long)A.rows);
+      e.line("  long long row = row0 + threadIdx.x / L;");
     }
     e.line("  const bool row_ok = row < %lldll;", (long long)A.rows);
     e.line("  if (!row_ok) row = %lldll;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", (long long)A.rows - 1);
@@ -525,17 +568,87 @@ struct Gen {
         e.line("  const long long i%d = rr %% %lld%s; rr /= %lld%s;", d, (long long)A.S[d], sfx, (long long)A.S[d], sfx);
       }
     }
-    e.line("  int col[K]; bool ok[K];");
-    e.line("  UNROLL for (int k = 0; k < K; ++k) { const int c = k * L + lane; ok[k] = c < %lld; col[k] = (ok[k] ? c : 0) * W; }",
-           (long long)(A.cols / W));
     // ---- loads
+    // In the persistent form the next row's vectors are requested before the current row is
+    // worked on (raw, still packed) and unpacked one iteration later: with few wavefronts per
+    // CU that is what keeps HBM requests in flight.
+    auto raw_type = [&](const RView& v) -> const char* {
+      if (v.dtype == FS_F32) return W == 4 ? "f32x4" : nullptr;
+      return W == 8 ? "u32x4" : W == 4 ? "u32x2" : nullptr;
+    };
+    std::vector<char> prefetched(A.views.size(), 0);
+    if (persistent) {
+      for (size_t q = 0; q < A.views.size(); ++q) {
+        const RView& v = A.views[q];
+        bool dense = true, needs_coords = false;
+        for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] == 0) dense = false;
+        (void)row_offset(v, &needs_coords);
+        prefetched[q] = !splat[q] && dense && !needs_coords && raw_type(v) != nullptr;
+      }
+    }
+    if (persistent) {
+      std::string pro, nxt, adv;
+      char buf[512];
+      for (size_t q = 0; q < A.views.size(); ++q) if (prefetched[q]) {
+        const RView& v = A.views[q];
+        const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+        const char* rt = raw_type(v);
+        bool dummy = false;
+        const std::string offp = row_offset(v, &dummy, "rowp"), offn = row_offset(v, &dummy, "rown");
+        snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                 rt, q, q, rt, ty, q, offp.c_str());
+        pro += buf;
+        snprintf(buf, sizeof buf, "  %s nraw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) nraw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                 rt, q, q, rt, ty, q, offn.c_str());
+        nxt += buf;
+        snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = nraw%zu[k];\n", q, q);
+        adv += buf;
+      }
+      if (!pro.empty()) {
+        // the prologue goes before the row loop: find the loop header emitted above
+        const std::string header = "  for (long long row0 = ";
+        const size_t at = e.s.rfind(header);
+        snprintf(buf, sizeof buf, "  long long rowp = (long long)blockIdx.x * %d + threadIdx.x / L;\n  if (rowp >= %lldll) rowp = %lldll;\n",
+                 wg / L, (long long)A.rows, (long long)A.rows - 1);
+        e.s.insert(at, std::string(buf) + pro);
+        e.line("  long long rown = row0 + (long long)gridDim.x * %d + threadIdx.x / L;", wg / L);
+        e.line("  if (rown >= %lldll) rown = 0;          // past the end: any valid row (row 0 is cached by then)", (long long)A.rows);
+        e.s += nxt;
+        e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
+        advance = adv;
+      }
+    }
     for (size_t q = 0; q < A.views.size(); ++q) {
       const RView& v = A.views[q];
       const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
       const char* one = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
+      // persistent form: an operand that does not depend on the row (a per-column vector, a
+      // scalar) is loaded once, before the row loop
+      bool invariant = persistent;
+      for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] != 0) invariant = false;
+      const size_t text_from = e.s.size();
+      struct Hoist {
+        Emitter& e; bool on; size_t from;
+        ~Hoist() {
+          if (!on) return;
+          const std::string text = e.s.substr(from);
+          e.s.erase(from);
+          e.s.insert(e.s.rfind("  for (long long row0 = "), text);
+        }
+      } hoist{e, invariant, text_from};
       if (splat[q]) {
         e.line("  float s%zu;", q);
         e.line("  { const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s); s%zu = %s; }", ty, ty, q, roff[q].c_str(), q, one);
+        continue;
+      }
+      if (prefetched[q]) {
+        // unpack what was requested one iteration ago
+        e.line("  float v%zu[K][W];", q);
+        e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+        if (v.dtype == FS_F32) e.line("    UNROLL for (int j = 0; j < 4; ++j) v%zu[k][j] = raw%zu[k][j];", q, q);
+        else e.line("    UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[k][2 * j] = %s(raw%zu[k][j]); v%zu[k][2 * j + 1] = %s(raw%zu[k][j]); }",
+                    q, v.dtype == FS_F16 ? "f16_lo" : "bf16_lo", q, q, v.dtype == FS_F16 ? "f16_hi" : "bf16_hi", q);
+        e.line("  }");
         continue;
       }
       // tensors of the group's own shape stream through once; per-column operands are shared by all rows
@@ -587,6 +700,11 @@ struct Gen {
           e.line("  r%d = lanes_allreduce<%s, L>(r%d);", id, op, id);
         }
       };
+      if (n.cls == CLS_COL) {
+        const std::string x = opnd(n.o[0], CLS_FULL);
+        e.line("  if (row_ok) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += (double)%s;", n.id, x.c_str());
+        continue;
+      }
       if (reduce) {
         const bool sum = n.op == FS_REDUCE_SUM;
         const std::string x = opnd(n.o[0], CLS_FULL);
@@ -687,6 +805,36 @@ struct Gen {
         }
       }
       e.line("  }");
+    }
+    if (persistent) {
+      e.s += advance;
+      e.line("  }");
+      e.line("  __shared__ double colacc[%d][%lld];", A.n_col, (long long)A.cols);
+      e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
+      e.line("  __syncthreads();");
+      // fixed summation order (results are bit-reproducible): first the row groups of a wavefront
+      // (lanes that hold the same columns) by an xor butterfly, then the wavefronts one after the other
+      if (L < 64) {
+        for (const RNode& n : A.nodes) if (n.cls == CLS_COL)
+          e.line("  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id);
+      }
+      e.line("  for (int w = 0; w < (int)blockDim.x / 64; ++w) {");
+      e.line("    if ((int)(threadIdx.x >> 6) == w && (int)(threadIdx.x & 63) < L) {");
+      int ci = 0;
+      for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        e.line("      UNROLL for (int k = 0; k < K; ++k) {");
+        e.line("        if (!ok[k]) continue;");
+        e.line("        UNROLL for (int j = 0; j < W; ++j) colacc[%d][col[k] + j] += ca%d[k][j];", ci, n.id);
+        e.line("      }");
+        ++ci;
+      }
+      e.line("    }");
+      e.line("    __syncthreads();");
+      e.line("  }");
+      e.line("  double* ws = static_cast<double*>(a.ws);");
+      e.line("  for (int r = 0; r < %d; ++r)", A.n_col);
+      e.line("    for (int i = threadIdx.x; i < %lld; i += blockDim.x) ws[((long long)r * gridDim.x + blockIdx.x) * %lldll + i] = colacc[r][i];",
+             (long long)A.cols, (long long)A.cols);
     }
     e.line("}");
     uint64_t h = 1469598103934665603ull;
@@ -1107,7 +1255,7 @@ struct Stream {
   }
 };
 
-struct GenArgs { const void* in[24]; void* out[8]; };   // mirrors Args of the generated source
+struct GenArgs { const void* in[24]; void* out[8]; void* ws; };   // mirrors Args of the generated source
 
 }  // namespace
 
@@ -1123,8 +1271,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   if (!A.run()) { *err = A.err; return false; }
   Gen gen(A);
   RowGenLaunch l;
-  const bool want_stream = opt.grid > 0;        // a fixed number of workgroups: the streamed template
-  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 1024 || opt.wg_size % 64 || (!want_stream && opt.wg_size > 256))) {
+  const bool want_stream = opt.grid > 0 && A.n_col == 0;   // a fixed number of workgroups: the streamed template
+  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 1024 || opt.wg_size % 64 || (!want_stream && A.n_col == 0 && opt.wg_size > 256))) {
     *status = FS_ERR_INVALID;
     *err = "generated row schedule: wg_size must be 64, 128, 192 or 256 (a multiple of 64 up to 1024 with a fixed grid)";
     return false;
@@ -1143,8 +1291,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
   for (const RView& v : A.views) l.view_param.push_back(v.param);
-  gen.wg = opt.wg_size && opt.wg_size <= 256 ? opt.wg_size : 256;
-  if (gen.wg == 192) gen.wg = 128;            // lanes per row divide the workgroup
+  gen.wg = opt.wg_size && (opt.wg_size <= 256 || A.n_col > 0) ? opt.wg_size : 256;
+  if (gen.wg & (gen.wg - 1)) gen.wg = gen.wg > 512 ? 512 : gen.wg > 256 ? 256 : 128;   // lanes per row divide the workgroup
   std::string gerr;
   if (!want_stream && gen.geometry(&gerr)) {
     // the row lives in registers
@@ -1157,6 +1305,18 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     l.wg = l.L > 64 ? l.L : gen.wg;     // a team is one workgroup per row
     const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;
     int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
+    if (gen.persistent) {
+      // a fixed grid loops over the rows: one partial row per workgroup and column reduction
+      const int64_t want = opt.grid > 0 ? opt.grid : 256;
+      if (want < grid) grid = want;
+      for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        l.col_out[l.n_col] = n.out_ord;
+        l.col_dtype[l.n_col] = n.out_dtype;
+        ++l.n_col;
+      }
+      l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
+      l.workspace_bytes = (int64_t)A.n_col * grid * A.cols * 8;
+    }
     if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
     l.grid = (int)(grid < 1 ? 1 : grid);
     *out = l;
@@ -1164,6 +1324,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     return true;
   }
   if (!want_stream && (opt.rows_per_wave || gerr.find("row longer") == std::string::npos)) { *err = gerr; return false; }
+  if (A.n_col > 0) { *err = "generated row schedule: column reductions with rows longer than one wavefront's registers"; return false; }
 
   // the row is streamed in passes by one workgroup
   Stream st(A);
@@ -1218,18 +1379,38 @@ std::string row_gen_describe(const RowGenLaunch& l) {
              l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
     return buf;
   }
+  if (l.n_col > 0) {
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,WARP] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,WARP-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %d partial rows, then a combine kernel); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.n_col, l.n_ops - l.n_reduce - l.n_col, l.K * l.W, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.grid, l.wg,
+             (long long)l.lds_bytes);
+    return buf;
+  }
   snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
            l.n_reduce, l.L == 1 ? "THREAD" : l.L > 64 ? "CTA-S" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : l.L > 64 ? "CTA" : "WARP", l.K * l.W,
            l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
   return buf;
 }
 
-int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int n_out, void* stream, std::string* err) {
-  if (l.rows == 0 || l.cols == 0) return 0;
+int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int n_out, void* workspace, void* stream,
+                   std::string* err) {
+  if (l.rows == 0 || l.cols == 0) {
+    // no rows: the column sums are zero (the combine kernel over zero partial rows writes them)
+    if (l.n_col > 0 && l.cols > 0) {
+      void* col_out[8];
+      for (int r = 0; r < l.n_col; ++r) col_out[r] = out[l.col_out[r]];
+      return col_combine_launch(nullptr, 0, l.cols, l.n_col, col_out, l.col_dtype, stream, err);
+    }
+    return 0;
+  }
   GenArgs args{};
   for (size_t k = 0; k < l.view_param.size(); ++k) args.in[k] = in[l.view_param[k]];
   for (int k = 0; k < n_out && k < 8; ++k) args.out[k] = out[k];
-  return ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
+  args.ws = workspace;
+  const int rc = ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
+  if (rc != 0 || l.n_col == 0) return rc;
+  void* col_out[8];
+  for (int r = 0; r < l.n_col; ++r) col_out[r] = out[l.col_out[r]];
+  return col_combine_launch(workspace, l.grid, l.cols, l.n_col, col_out, l.col_dtype, stream, err);
 }
 
 void row_gen_release(RowGenLaunch& l) { ew_module_release(&l.loaded); }

@@ -18,6 +18,11 @@ struct RowGenLaunch {
   bool streamed = false;              // one workgroup walks the row in passes
   int passes = 1, row_buffers = 0, buffers_shared = 0;
   bool inputs_cached = true;
+  // column reductions: one double-precision partial row per workgroup in the plan's workspace,
+  // then a second kernel adds them
+  int n_col = 0;
+  int col_out[8] = {0}, col_dtype[8] = {0};   // output ordinal and dtype of each
+  int64_t workspace_bytes = 0;
   int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view
   std::vector<char> code_object;
@@ -26,8 +31,8 @@ struct RowGenLaunch {
 };
 bool row_gen_plan(const Graph&, const LaunchOpts&, RowGenLaunch*, int* status, std::string* err);
 std::string row_gen_describe(const RowGenLaunch&);
-int row_gen_launch(RowGenLaunch&, const void* const* in, void* const* out, int n_out, void* stream,
-                   std::string* err);
+int row_gen_launch(RowGenLaunch&, const void* const* in, void* const* out, int n_out, void* workspace,
+                   void* stream, std::string* err);
 void row_gen_release(RowGenLaunch&);
 
 }  // namespace fs

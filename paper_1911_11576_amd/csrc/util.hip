@@ -25,4 +25,49 @@ int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, 
   return 0;
 }
 
+// Second step of a column reduction whose first step left one double-precision partial row
+// per workgroup: out[r][c] = sum over g of partial[r][g][c], summed in a fixed order (64
+// interleaved slices, then the slices in order), stored in the output's dtype.
+struct ColCombineArgs {
+  void* out[8];
+  int dtype[8];
+};
+
+__global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restrict__ partial, int groups, int64_t cols,
+                                                           const ColCombineArgs args) {
+  // a block owns 16 columns; its 1024 threads are 64 slices of the partial rows
+  __shared__ double part[64][17];
+  const int r = blockIdx.y, j = threadIdx.x & 15, slice = threadIdx.x >> 4;
+  const int64_t c = (int64_t)blockIdx.x * 16 + j;
+  double s = 0.0;
+  if (c < cols) {
+    const double* p = partial + ((int64_t)r * groups) * cols + c;
+    for (int g = slice; g < groups; g += 64) s += p[(int64_t)g * cols];
+  }
+  part[slice][j] = s;
+  __syncthreads();
+  if (slice == 0 && c < cols) {
+    double t = part[0][j];
+#pragma unroll 8
+    for (int k = 1; k < 64; ++k) t += part[k][j];
+    void* o = args.out[r];
+    const float f = (float)t;
+    if (args.dtype[r] == DT_F32) static_cast<float*>(o)[c] = f;
+    else static_cast<uint16_t*>(o)[c] = (uint16_t)(args.dtype[r] == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f));
+  }
+}
+
+int col_combine_launch(const void* partial, int groups, int64_t cols, int n_red, void* const* out, const int* dtype,
+                       void* stream, std::string* err) {
+  if (n_red <= 0 || cols <= 0) return 0;
+  ColCombineArgs a{};
+  for (int r = 0; r < n_red && r < 8; ++r) { a.out[r] = out[r]; a.dtype[r] = dtype[r]; }
+  const dim3 grid((unsigned)((cols + 15) / 16), (unsigned)n_red);
+  hipLaunchKernelGGL(col_combine_kernel, grid, dim3(1024), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const double*>(partial), groups, cols, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { *err = std::string("col_combine launch: ") + hipGetErrorString(e); return -1; }
+  return 0;
+}
+
 }  // namespace fs

@@ -42,8 +42,12 @@ def test_configs_are_recognised(cfg):
     with Plan(ops) as p:
         info = p.info()
         assert info["schedule"] == want
-        assert info["n_kernels"] == 1
+        # one stitched kernel; config 5's plan is the generated kernel plus its combine kernel
+        assert info["n_kernels"] == (2 if cfg.name == "layernorm_bwd" else 1)
         assert "cta_num=" in p.describe() and "cta_size=" in p.describe()
+    with Plan(ops, "prebuilt") as p:          # the hand-written kernels: one launch each
+        assert p.info()["schedule"] == want and p.info()["n_kernels"] == 1
+        assert "generated" not in p.describe()
     with Plan(ops, "per_op") as p:
         info = p.info()
         assert info["schedule"] == "per_op" and info["n_kernels"] >= 7
@@ -52,12 +56,17 @@ def test_configs_are_recognised(cfg):
 
 
 def test_plan_info_sizes():
-    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full)) as p:
+    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full), "prebuilt") as p:
         info = p.info()
         assert info["algorithmic_bytes"] == 402_927_616
         # 8 wavefronts x (dgamma, dbeta) x 1024 fp64 accumulator slots
         assert info["lds_bytes"] == 8 * 2 * 1024 * 8
         assert 0 < info["workspace_bytes"] < 16 * 2**20
+    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full)) as p:
+        info = p.info()
+        # generated: (dgamma, dbeta) x 1024 fp64 sums in LDS, 256 partial rows of them in the workspace
+        assert info["lds_bytes"] == 2 * 1024 * 8 and info["workspace_bytes"] == 256 * 2 * 1024 * 8
+        assert info["moved_bytes"] == info["algorithmic_bytes"] + 2 * info["workspace_bytes"]
     with Plan(BY_NAME["causal_attention"].graph_fn(**BY_NAME["causal_attention"].full)) as p:
         assert 0 < p.info()["lds_bytes"] <= 64 * 1024
 
@@ -92,17 +101,26 @@ def _expect(status, ops, **kw):
 def test_unsupported_groups_return_unsupported_not_crash():
     g = Graph()
     x = g.parameter("x", "f32", (8, 64))
-    g.output(g.reduce_sum(g.exp(x), 0))            # a lone column reduction: no stitched schedule
-    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    g.output(g.reduce_sum(g.exp(x), 0))            # a lone column reduction: generated, partial rows + combine
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "row_col" and p.info()["n_kernels"] == 2
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops, mode="prebuilt")   # no hand-written kernel matches it
     with Plan(g.ops, "per_op") as p:               # the per-op plan always exists
         assert p.info()["n_kernels"] == 3
+    g = Graph()
+    x = g.parameter("x", "f32", (4, 8, 64))
+    g.output(g.reduce_sum(g.exp(x), 1))            # a reduction over a middle dim: no stitched schedule
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
     g = Graph()
     x = g.parameter("x", "f32", (8, 64))
     g.output(g.exp(g.tanh(x)))                     # any all-elementwise group stitches
     with Plan(g.ops) as p:
         assert p.info()["schedule"] == "elementwise"
-    # LayerNorm backward keeps fp64 column accumulators per lane: at most 1024 columns
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048))
+    # the hand-written LayerNorm backward takes at most 1024 columns; beyond that the generated kernel
+    with Plan(graphs.layernorm_bwd(8, 2048)) as p:
+        assert p.info()["schedule"] == "row_col" and "generated kernel" in p.describe()
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048), mode="prebuilt")
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 4096))
     # fp32 attention has no MFMA path
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 64, 64, "f32"))
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 256, 64))
@@ -111,9 +129,12 @@ def test_unsupported_groups_return_unsupported_not_crash():
 def test_lds_volume_constraint():
     msg = _expect(binding.FS_ERR_LDS, graphs.causal_attention(2, 128, 128))
     assert "LDS" in msg
-    # a row longer than the LDS row cache of the block-composed row form
-    msg = _expect(binding.FS_ERR_LDS, graphs.layernorm_fwd(4, 50000))
+    # a row longer than the LDS row cache of the block-composed row form: without kernel
+    # generation that is the end, with it the streamed template takes over
+    msg = _expect(binding.FS_ERR_LDS, graphs.layernorm_fwd(4, 50000), mode="prebuilt")
     assert "LDS" in msg
+    with Plan(graphs.layernorm_fwd(4, 50000)) as p:
+        assert "streamed in" in p.describe()
 
 
 def test_long_and_unaligned_rows_take_the_block_composed_form():

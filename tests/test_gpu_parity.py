@@ -208,26 +208,34 @@ def test_row_schedule_launch_options_do_not_change_results(opts):
 
 # ---------------------------------------------------------------- LayerNorm backward
 
+# both forms of the group: the generated kernel + combine kernel (default) and the hand-written
+# single kernel (mode "prebuilt")
+LNBWD_MODES = ["stitched", "prebuilt"]
+
+
+@pytest.mark.parametrize("mode", LNBWD_MODES)
 @pytest.mark.parametrize("rows,cols", [(1, 4), (5, 64), (517, 1024), (4099, 1000), (33, 768), (700, 256)])
-def test_layernorm_bwd_shapes(rows, cols):
-    announce(f"layernorm_bwd {rows}x{cols}")
-    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), what=f"lnbwd {rows}x{cols}")
+def test_layernorm_bwd_shapes(rows, cols, mode):
+    announce(f"layernorm_bwd {rows}x{cols} {mode}")
+    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), mode, what=f"lnbwd {rows}x{cols}")
 
 
+@pytest.mark.parametrize("mode", LNBWD_MODES)
 @pytest.mark.parametrize("opts", [dict(grid=1), dict(grid=3, wg_size=64), dict(grid=100, wg_size=256), dict(grid=1024)])
-def test_layernorm_bwd_launch_options(opts):
-    announce(f"layernorm_bwd options {opts}")
+def test_layernorm_bwd_launch_options(opts, mode):
+    announce(f"layernorm_bwd options {opts} {mode}")
     rows, cols = 2100, 1024
-    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), what=f"lnbwd {opts}", **opts)
+    check_against_oracle(graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols), mode, what=f"lnbwd {opts}", **opts)
 
 
-def test_layernorm_bwd_is_bit_reproducible_and_reusable():
-    announce("layernorm_bwd determinism")
+@pytest.mark.parametrize("mode", LNBWD_MODES)
+def test_layernorm_bwd_is_bit_reproducible_and_reusable(mode):
+    announce(f"layernorm_bwd determinism {mode}")
     rows, cols = 3000, 1024
     ops, ins = graphs.layernorm_bwd(rows, cols), inputs.layernorm_bwd(rows, cols)
     dev_in = to_device(ops, ins)
     runs = []
-    with Plan(ops) as plan:
+    with Plan(ops, mode) as plan:
         for _ in range(5):
             out = alloc_outputs(ops)
             plan.launch(dev_in, out)
@@ -238,15 +246,16 @@ def test_layernorm_bwd_is_bit_reproducible_and_reusable():
             assert np.array_equal(a, b)
 
 
-def test_layernorm_bwd_output_subsets():
-    announce("layernorm_bwd subsets")
+@pytest.mark.parametrize("mode", LNBWD_MODES)
+def test_layernorm_bwd_output_subsets(mode):
+    announce(f"layernorm_bwd subsets {mode}")
     rows, cols = 300, 512
     full = graphs.layernorm_bwd(rows, cols)
     ins = inputs.layernorm_bwd(rows, cols)
     outs = [i for i, op in enumerate(full) if op.kind == "output"]
     for keep in ([0], [1, 2], [2], [0, 2]):
         ops = [op for i, op in enumerate(full) if op.kind != "output" or outs.index(i) in keep]
-        check_against_oracle(ops, ins, what=f"lnbwd outputs {keep}")
+        check_against_oracle(ops, ins, mode, what=f"lnbwd outputs {keep}")
 
 
 # ---------------------------------------------------------------- attention
@@ -336,11 +345,12 @@ def test_full_size_bias_gelu_ln_sampled_rows():
     assert not np.isnan(got).any()
 
 
-def test_full_size_layernorm_bwd():
-    announce("full cfg5")
+@pytest.mark.parametrize("mode", LNBWD_MODES)
+def test_full_size_layernorm_bwd(mode):
+    announce(f"full cfg5 {mode}")
     cfg = BY_NAME["layernorm_bwd"]
     ops, ins = cfg.build("full")
-    dx, dgamma, dbeta = run_gpu(ops, ins)
+    dx, dgamma, dbeta = run_gpu(ops, ins, mode)
     want_dx, want_dgamma, want_dbeta = interp.run(ops, ins)
     assert_close(dgamma, want_dgamma, 1e-5, "cfg5 full dgamma")
     assert_close(dbeta, want_dbeta, 1e-5, "cfg5 full dbeta")
@@ -369,7 +379,8 @@ def test_plan_tune_returns_a_correct_plan(cfg):
         torch.cuda.synchronize()
         for got, ref in zip(fresh, want):
             assert_close(got.double().cpu().numpy(), ref, tol, f"tuned relaunch {cfg.name}")
-        assert plan.info()["n_kernels"] == 1
+        # one stitched kernel; the generated form of a group with column reductions adds its combine kernel
+        assert plan.info()["n_kernels"] <= (2 if plan.info()["schedule"] == "row_col" else 1)
     finally:
         plan.close()
 
@@ -377,11 +388,11 @@ def test_plan_tune_returns_a_correct_plan(cfg):
 def test_plan_tune_rejects_unsupported_groups_and_bad_arguments():
     announce("tune errors")
     g = graphs.Graph()
-    x = g.parameter("x", "f32", (8, 64))
-    g.output(g.reduce_sum(g.exp(x), 0))       # a lone column reduction has no stitched schedule
-    t = torch.zeros(8, 64, device="cuda:0")
+    x = g.parameter("x", "f32", (4, 8, 64))
+    g.output(g.reduce_sum(g.exp(x), 1))       # a reduction over a middle dim has no stitched schedule
+    t = torch.zeros(4, 8, 64, device="cuda:0")
     with pytest.raises(FsError) as e:
-        Plan.tune(g.ops, [t], [torch.empty(64, device="cuda:0")])
+        Plan.tune(g.ops, [t], [torch.empty(4, 64, device="cuda:0")])
     assert e.value.status == binding.FS_ERR_UNSUPPORTED
     ops, ins = graphs.layernorm_fwd(4, 768), inputs.layernorm_fwd(4, 768)
     dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
