@@ -425,7 +425,8 @@ struct Gen {
 
   int lanes_per_row = 0;      // 0: choose
   int wg = 256;               // workgroup size the kernel is generated for
-  bool persistent = false;    // a fixed grid loops over the rows (groups with column reductions)
+  bool persistent = false;    // a fixed grid loops over the rows (groups with column reductions, or on request)
+  bool want_persistent = false;
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
@@ -492,6 +493,7 @@ struct Gen {
       if ((int64_t)A.n_col * A.cols * 8 > 96 * 1024) { *err = "generated row schedule: column accumulators exceed the LDS"; return false; }
       persistent = true;
     }
+    if (want_persistent && L <= 64) persistent = true;
     if (L <= 64 && !persistent) {
       int min_out = 4;
       bool full_out = false;
@@ -809,6 +811,8 @@ struct Gen {
     if (persistent) {
       e.s += advance;
       e.line("  }");
+    }
+    if (persistent && A.n_col > 0) {
       e.line("  __shared__ double colacc[%d][%lld];", A.n_col, (long long)A.cols);
       e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
       e.line("  __syncthreads();");
@@ -1271,7 +1275,11 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   if (!A.run()) { *err = A.err; return false; }
   Gen gen(A);
   RowGenLaunch l;
-  const bool want_stream = opt.grid > 0 && A.n_col == 0;   // a fixed number of workgroups: the streamed template
+  // A fixed number of workgroups that loop over the rows: with the lanes per row given too, the
+  // register templates in their persistent form (the next row is requested while the current
+  // one is worked on); without, the streamed template.
+  const bool want_persistent = opt.grid > 0 && opt.rows_per_wave > 0 && A.n_col == 0;
+  const bool want_stream = opt.grid > 0 && A.n_col == 0 && !want_persistent;
   if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 1024 || opt.wg_size % 64 || (!want_stream && A.n_col == 0 && opt.wg_size > 256))) {
     *status = FS_ERR_INVALID;
     *err = "generated row schedule: wg_size must be 64, 128, 192 or 256 (a multiple of 64 up to 1024 with a fixed grid)";
@@ -1291,6 +1299,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
   for (const RView& v : A.views) l.view_param.push_back(v.param);
+  gen.want_persistent = want_persistent;
   gen.wg = opt.wg_size && (opt.wg_size <= 256 || A.n_col > 0) ? opt.wg_size : 256;
   if (gen.wg & (gen.wg - 1)) gen.wg = gen.wg > 512 ? 512 : gen.wg > 256 ? 256 : 128;   // lanes per row divide the workgroup
   std::string gerr;
@@ -1309,6 +1318,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       // a fixed grid loops over the rows: one partial row per workgroup and column reduction
       const int64_t want = opt.grid > 0 ? opt.grid : 256;
       if (want < grid) grid = want;
+      l.persistent = true;
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
         l.col_out[l.n_col] = n.out_ord;
         l.col_dtype[l.n_col] = n.out_dtype;
@@ -1376,6 +1386,12 @@ std::string row_gen_describe(const RowGenLaunch& l) {
     snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d] streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
              l.n_reduce, l.n_ops - l.n_reduce, l.W, l.passes, l.row_buffers, l.buffers_shared,
              l.passes > 1 && !l.inputs_cached ? ", inputs re-read per pass" : "",
+             l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
+    return buf;
+  }
+  if (l.persistent && l.n_col == 0) {
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + elementwise x%d[GRID,%s-THREAD_%d] persistent, next row prefetched (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.L == 1 ? "THREAD" : "WARP", l.n_ops - l.n_reduce, l.L == 1 ? "CTA" : "WARP", l.K * l.W,
              l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
     return buf;
   }

@@ -16,6 +16,7 @@ struct RowGenLaunch {
   int L = 64, K = 1, W = 4;           // lanes per row, chunks per lane, elements per chunk
   int n_ops = 0, n_reduce = 0;
   bool streamed = false;              // one workgroup walks the row in passes
+  bool persistent = false;            // a fixed grid loops over register-resident rows
   int passes = 1, row_buffers = 0, buffers_shared = 0;
   bool inputs_cached = true;
   // column reductions: one double-precision partial row per workgroup in the plan's workspace,
