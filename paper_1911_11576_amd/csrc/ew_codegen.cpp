@@ -96,6 +96,13 @@ std::string op_text(const EwIrNode& n, bool fast) {
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
+    case FS_CAUSAL_MASK: {
+      // kept where the last index does not exceed the second-to-last one
+      EwIrOperand fill;
+      fill.kind = EW_FROM_CONST;
+      fill.cval = n.opnd[1].cval;
+      return "(i3 + j <= i2) ? " + a + " : " + operand_text(fill);
+    }
     default: return a;
   }
 }
@@ -128,6 +135,7 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
   *unroll = 1;
   bool need_idx = false;
   for (const EwIrView& v : ir.views) if (!v.full) need_idx = true;
+  for (const EwIrNode& n : ir.nodes) if (n.op == FS_CAUSAL_MASK) need_idx = true;
   // A group that stores 16-bit values is compared at 16-bit accuracy: its tanh may take the
   // short hardware form.  fp32 groups keep the library function.
   bool fast = false;

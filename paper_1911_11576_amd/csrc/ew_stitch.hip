@@ -318,7 +318,7 @@ struct EwCompiled {
   int n_views = 0;
 };
 
-static bool ew_is_elementwise(int k) { return is_binary(k) || is_unary(k) || k == FS_CONVERT; }
+static bool ew_is_elementwise(int k) { return is_binary(k) || is_unary(k) || k == FS_CONVERT || k == FS_CAUSAL_MASK; }
 
 namespace {
 
@@ -472,6 +472,10 @@ struct EwCompiler {
       in.id = node;
       in.op = x.kind == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : x.kind;
       in.n_operands = n_operands(node);
+      if (x.kind == FS_CAUSAL_MASK) {
+        if (x.rank < 2) return fail("elementwise schedule: causal_mask below rank 2");
+        in.opnd[1].cval = (float)x.attr;       // the fill value rides in the unused second operand
+      }
       for (int j = 0; j < in.n_operands; ++j) {
         const int a = canon(x.operand[j]);
         if (is_compute(a)) { in.opnd[j].kind = EW_FROM_NODE; in.opnd[j].index = a; continue; }
@@ -494,6 +498,7 @@ struct EwCompiler {
     for (size_t k = 0; k < order.size(); ++k) {
       const int node = order[k];
       const Node& x = g[node];
+      if (x.kind == FS_CAUSAL_MASK) return fail("elementwise schedule: the interpreter has no causal_mask step");
       const int nop = n_operands(node);
       EwInstr alu{};
       alu.kind = EW_ALU;

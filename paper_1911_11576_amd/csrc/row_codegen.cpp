@@ -64,6 +64,7 @@ struct Analysis {
   std::vector<RView> views;
   int n_reduce = 0;
   int n_col = 0;                 // column reductions (over the rows), results are outputs only
+  bool has_causal = false;       // a causal_mask op: the row's index in the second-to-last dim is needed
 
   explicit Analysis(const Graph& gr) : g(gr) {}
   bool fail(const std::string& m) { err = m; return false; }
@@ -75,7 +76,7 @@ struct Analysis {
   }
   bool is_compute(int n) const {
     const int k = g[n].kind;
-    return (is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k) || k == FS_DOT) && canon(n) == n;
+    return (is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k) || k == FS_DOT || k == FS_CAUSAL_MASK) && canon(n) == n;
   }
   bool shape_is_full(const Node& x) const {
     if (x.rank != rank) return false;
@@ -252,6 +253,20 @@ struct Analysis {
         nodes.push_back(r);
         continue;
       }
+      if (k == FS_CAUSAL_MASK) {
+        // x[..., i, j] kept where j <= i: elementwise on a full value, with the row's own index
+        if (!shape_is_full(x) || rank < 2) return fail("generated row schedule: causal_mask on something other than the group's full shape");
+        RNode r;
+        r.id = i; r.op = k; r.cls = CLS_FULL; r.nop = 1;
+        cls[i] = CLS_FULL;
+        if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
+        r.o[1].cval = (float)x.attr;
+        r.out_ord = out_ord[i];
+        r.out_dtype = out_dtype[i];
+        has_causal = true;
+        nodes.push_back(r);
+        continue;
+      }
       if (!(is_binary(k) || is_unary(k) || k == FS_CONVERT || is_reduce(k)))
         return fail(std::string("generated row schedule: op ") + kind_name(k) + " is not elementwise, a reduction or a small dot");
       if (!is_compute(i)) continue;       // widening convert: alias
@@ -391,6 +406,7 @@ struct Gen {
     const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
     // a full value divided by a per-row value: one reciprocal per row, then multiplies
     if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
+    if (n.op == FS_CAUSAL_MASK) return "(col[k] + j <= irow) ? " + a + " : " + const_text(n.o[1].cval);
     return op_text(n.op, a, b, fast);
   }
 
@@ -560,6 +576,7 @@ struct Gen {
       roff[q] = row_offset(v, &coords);
       splat[q] = v.cls == CLS_ROW || v.stride[rank - 1] == 0;
     }
+    if (A.has_causal) coords = true;
     if (coords) {
       const bool small = A.rows <= 0x7fffffffLL;
       const char* ty = small ? "unsigned" : "unsigned long long";
@@ -569,6 +586,7 @@ struct Gen {
         if (A.S[d] == 1) { e.line("  const long long i%d = 0;", d); continue; }
         e.line("  const long long i%d = rr %% %lld%s; rr /= %lld%s;", d, (long long)A.S[d], sfx, (long long)A.S[d], sfx);
       }
+      if (A.has_causal) e.line("  const long long irow = i%d;      // the row's index in the second-to-last dim", nrow - 1);
     }
     // ---- loads
     // In the persistent form the next row's vectors are requested before the current row is
@@ -1043,6 +1061,7 @@ struct Stream {
   std::string expr(const RNode& n) const {
     const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
     if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
+    if (n.op == FS_CAUSAL_MASK) return "(col + j <= irow) ? " + a + " : " + const_text(n.o[1].cval);
     return op_text(n.op, a, b, fast);
   }
 
@@ -1099,6 +1118,7 @@ struct Stream {
     // row offsets reuse the register templates' logic
     Gen helper(A);
     for (int q = 0; q < nv; ++q) { splat[q] = splat_view(q); roff[q] = helper.row_offset(A.views[q], &coords); }
+    if (A.has_causal) coords = true;
     std::vector<char> is_divisor(A.g.size(), 0);
     for (const RNode& x : A.nodes) if (x.op == FS_DIVIDE && x.cls == CLS_FULL && x.o[1].kind == OP_ROWB) is_divisor[x.o[1].index] = 1;
     int n_red = 0;
@@ -1118,6 +1138,7 @@ struct Stream {
         if (A.S[d] == 1) { e.line("    const long long i%d = 0;", d); continue; }
         e.line("    const long long i%d = rr %% %lldull; rr /= %lldull;", d, (long long)A.S[d], (long long)A.S[d]);
       }
+      if (A.has_causal) e.line("    const long long irow = i%d;", nrow - 1);
     }
     for (int q = 0; q < nv; ++q) if (splat[q]) {
       const RView& v = A.views[q];

@@ -490,3 +490,31 @@ def multi_interest_pattern(batch, m=94, n=94, k=1, scale=0.25, gain=0.5):
     g.output(log_1, "log_1")
     g.output(multiply_2, "multiply_2")
     return g.ops
+
+
+def causal_softmax(shape, scale=0.125, dtype="f32"):
+    """softmax over the last dim of causally masked scores [..., S, S] (keys right of the diagonal
+    excluded): the middle of an attention block as a group of its own."""
+    g = Graph()
+    s = g.parameter("scores", dtype, shape)
+    (sf,) = _f32_in(g, dtype, s)
+    z = g.causal_mask(g.multiply(sf, g.constant(scale)), float("-inf"))
+    m = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(m, z)))
+    p = g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), z))
+    if dtype != "f32":
+        p = g.convert(p, dtype)
+    g.output(p, "p")
+    return g.ops
+
+
+def causal_fill(shape, fill=-1e4, dtype="f32"):
+    """y = causal_mask(x * 2, fill): an all-elementwise group with an index-dependent op."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    (xf,) = _f32_in(g, dtype, x)
+    y = g.causal_mask(g.multiply(xf, g.constant(2.0)), fill)
+    if dtype != "f32":
+        y = g.convert(y, dtype)
+    g.output(y, "y")
+    return g.ops
