@@ -214,6 +214,55 @@ const char* fs_plan_describe(const fs_plan* plan);
 fs_status fs_shared_plan(const int32_t* operands, const int64_t* req_bytes, const uint8_t* is_output,
                          int32_t n, int64_t* offset, int32_t* shares_with, int64_t* total_bytes);
 
+/* ---- Fusion planning (Section 4) --------------------------------------------------------
+ * From a computation graph -- an op list like a fusion group's, but of any size -- choose
+ * which ops to fuse: fusion patterns are generated by substitution fusion (Algorithm 1, with
+ * its growing set of partition ops) and exploratory fusion (Algorithm 2), scored by the
+ * model-based score f(P) = M(V) + (N-1)*phi (negative when no stitched kernel can be built
+ * for the pattern), and a set of pairwise disjoint patterns of maximal total score is
+ * selected exactly (the ILP of Section 4.1), with the paper's iterative repair when the
+ * selection would make the graph cyclic.  Pure host work.  The result is a list of groups in
+ * an order that respects data flow; each group comes back as an op list of its own, ready
+ * for fs_plan_create, with the ops of the original list that its parameters and outputs
+ * stand for.  Ops that own no kernel (constants, broadcasts) are copied into every group
+ * that reads them. */
+typedef struct fs_fusion fs_fusion; /* opaque, owned by the library */
+
+typedef struct {
+  double launch_us;        /* phi, the launch latency of one kernel; <= 0: 2.5 */
+  int32_t max_patterns;    /* patterns handed to the solver, best scores first; 1..64, 0: 64 */
+  int32_t explore_budget;  /* patterns the exploratory search may visit; 0: 400; < 0: none */
+  int64_t seed_bytes;      /* exploratory seeds: ops whose result has at least this many bytes; 0: 1 MiB */
+  const int64_t* bw_bytes; /* M(V) model: n_bw points (bytes moved, GB/s achieved), increasing */
+  const double* bw_gbs;    /*   bytes; NULL / 0: the table measured on MI355X with fs_stream_copy */
+  int32_t n_bw;
+  int32_t n_extra;         /* caller-supplied patterns, scored and offered to the solver like the */
+  const int32_t* extra_sizes; /* generated ones: n_extra sizes, then the op indices of all of them  */
+  const int32_t* extra_ops;   /* back to back (kernel-owning ops of the list, any order)            */
+} fs_fusion_options;
+
+/* Errors: FS_ERR_INVALID (malformed list or options), FS_ERR_NOMEM. */
+fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion_options* opt, fs_fusion** out);
+fs_status fs_fusion_destroy(fs_fusion* fusion);
+/* Any out-pointer may be NULL.  solver_rounds = 1 + number of cycle repairs. */
+fs_status fs_fusion_info(const fs_fusion* fusion, int32_t* n_groups, int32_t* n_patterns, double* total_score_us,
+                         int32_t* solver_rounds);
+/* Sizes of group g (0 <= g < n_groups, execution order) and its score (0 for an op left alone). */
+fs_status fs_fusion_group_size(const fs_fusion* fusion, int32_t g, int32_t* n_ops, int32_t* n_inputs,
+                               int32_t* n_outputs, int32_t* n_members, double* score_us);
+/* Group g: its op list (n_ops entries), for each of its parameters / outputs the index in the
+ * ORIGINAL list of the op whose value it is (n_inputs / n_outputs entries; an input index may
+ * name an original parameter), and the original indices of the kernel-owning ops it fuses
+ * (n_members entries).  Caller-owned arrays of the sizes fs_fusion_group_size reports; any may be NULL. */
+fs_status fs_fusion_group(const fs_fusion* fusion, int32_t g, fs_op_desc* ops, int32_t* input_of,
+                          int32_t* output_of, int32_t* members);
+/* Candidate pattern k (0 <= k < n_patterns): number of ops, the ops themselves (up to cap),
+ * how it was found (0 substitution, 1 connected part of a substitution segment, 2 exploratory,
+ * 3 supplied by the caller),
+ * V in bytes, f(P) in microseconds (negative: not generable), whether the plan uses it. */
+fs_status fs_fusion_pattern(const fs_fusion* fusion, int32_t k, int32_t* n_ops, int32_t* ops, int32_t cap,
+                            int32_t* origin, int64_t* saved_bytes, double* score_us, int32_t* chosen);
+
 /* Measurement aid: plain streaming copy of `bytes` (multiple of 16) from src to dst,
  * both DEVICE pointers, 16-byte aligned, on `hip_stream`.  Gives the achievable HBM
  * ceiling beside the 8 TB/s peak and the calibration factor for byte counters. */

@@ -37,6 +37,13 @@ class fs_plan_options(C.Structure):
                 ("grid", C.c_int32)]
 
 
+class fs_fusion_options(C.Structure):
+    _fields_ = [("launch_us", C.c_double), ("max_patterns", C.c_int32), ("explore_budget", C.c_int32),
+                ("seed_bytes", C.c_int64), ("bw_bytes", C.POINTER(C.c_int64)), ("bw_gbs", C.POINTER(C.c_double)),
+                ("n_bw", C.c_int32), ("n_extra", C.c_int32), ("extra_sizes", C.POINTER(C.c_int32)),
+                ("extra_ops", C.POINTER(C.c_int32))]
+
+
 class FsError(RuntimeError):
     def __init__(self, status, message):
         super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {message}")
@@ -78,6 +85,20 @@ def lib():
         L.fs_shared_plan.argtypes = [C.POINTER(i32), C.POINTER(i64), C.POINTER(C.c_uint8), i32, C.POINTER(i64),
                                      C.POINTER(i32), C.POINTER(i64)]
         L.fs_shared_plan.restype = i32
+        L.fs_fusion_create.argtypes = [C.POINTER(fs_op_desc), i32, C.POINTER(fs_fusion_options), C.POINTER(vp)]
+        L.fs_fusion_create.restype = i32
+        L.fs_fusion_destroy.argtypes = [vp]
+        L.fs_fusion_destroy.restype = i32
+        L.fs_fusion_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i32)]
+        L.fs_fusion_info.restype = i32
+        L.fs_fusion_group_size.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32),
+                                           C.POINTER(C.c_double)]
+        L.fs_fusion_group_size.restype = i32
+        L.fs_fusion_group.argtypes = [vp, i32, C.POINTER(fs_op_desc), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        L.fs_fusion_group.restype = i32
+        L.fs_fusion_pattern.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i64),
+                                        C.POINTER(C.c_double), C.POINTER(i32)]
+        L.fs_fusion_pattern.restype = i32
         _lib = L
     return _lib
 
@@ -243,6 +264,125 @@ class Plan:
             self.close()
         except Exception:
             pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+# ---------------------------------------------------------------- fusion planning (Section 4)
+
+_KIND_NAMES = {v: k for k, v in OPKINDS.items()}
+_DTYPE_NAMES = {v: k for k, v in DTYPES.items()}
+
+
+class FusionPlan:
+    """fs_fusion_create on a computation graph (op records as for Plan).
+
+    .groups     list of dicts in execution order: ops (marshalled fs_op_desc array, ready for
+                fs_plan_create), input_of / output_of (indices into the original list), members
+                (the original ops it fuses), score_us
+    .patterns   every scored candidate: ops, origin, saved_bytes, score_us, chosen
+    """
+
+    def __init__(self, ops, launch_us=0.0, max_patterns=0, explore_budget=0, seed_bytes=0, bandwidth=None, extra_patterns=None):
+        arr = ops if isinstance(ops, C.Array) else marshal_ops(ops)
+        opt = fs_fusion_options()
+        opt.launch_us, opt.max_patterns, opt.explore_budget, opt.seed_bytes = launch_us, max_patterns, explore_budget, seed_bytes
+        keep = None
+        if bandwidth:
+            bb = (C.c_int64 * len(bandwidth))(*[int(b) for b, _ in bandwidth])
+            gg = (C.c_double * len(bandwidth))(*[float(g) for _, g in bandwidth])
+            opt.bw_bytes, opt.bw_gbs, opt.n_bw = bb, gg, len(bandwidth)
+            keep = (bb, gg)
+        keep2 = None
+        if extra_patterns:
+            sizes = (C.c_int32 * len(extra_patterns))(*[len(p) for p in extra_patterns])
+            flat = [o for p in extra_patterns for o in p]
+            eo = (C.c_int32 * len(flat))(*flat)
+            opt.n_extra, opt.extra_sizes, opt.extra_ops = len(extra_patterns), sizes, eo
+            keep2 = (sizes, eo)
+        h = C.c_void_p()
+        _check(lib().fs_fusion_create(arr, len(arr), C.byref(opt), C.byref(h)))
+        del keep, keep2
+        try:
+            ng, npat, total, rounds = C.c_int32(), C.c_int32(), C.c_double(), C.c_int32()
+            _check(lib().fs_fusion_info(h, C.byref(ng), C.byref(npat), C.byref(total), C.byref(rounds)))
+            self.total_score_us, self.solver_rounds = total.value, rounds.value
+            self.groups, self.patterns = [], []
+            for g in range(ng.value):
+                n_ops, n_in, n_out, n_mem, score = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32(), C.c_double()
+                _check(lib().fs_fusion_group_size(h, g, C.byref(n_ops), C.byref(n_in), C.byref(n_out), C.byref(n_mem), C.byref(score)))
+                gops = (fs_op_desc * max(1, n_ops.value))()
+                gin, gout = (C.c_int32 * max(1, n_in.value))(), (C.c_int32 * max(1, n_out.value))()
+                gmem = (C.c_int32 * max(1, n_mem.value))()
+                _check(lib().fs_fusion_group(h, g, gops, gin, gout, gmem))
+                trimmed = (fs_op_desc * n_ops.value)(*gops[:n_ops.value])
+                self.groups.append(dict(ops=trimmed, input_of=list(gin[:n_in.value]), output_of=list(gout[:n_out.value]),
+                                        members=list(gmem[:n_mem.value]), score_us=score.value))
+            for k in range(npat.value):
+                n_ops, origin, saved, score, chosen = C.c_int32(), C.c_int32(), C.c_int64(), C.c_double(), C.c_int32()
+                buf = (C.c_int32 * 64)()
+                _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), buf, 64, C.byref(origin), C.byref(saved), C.byref(score), C.byref(chosen)))
+                self.patterns.append(dict(ops=list(buf[:min(64, n_ops.value)]), n_ops=n_ops.value, origin=origin.value,
+                                          saved_bytes=saved.value, score_us=score.value, chosen=bool(chosen.value)))
+        finally:
+            lib().fs_fusion_destroy(h)
+
+
+def describe_group_ops(arr):
+    """The ops of a marshalled list as (kind, dtype, shape, operands) tuples, for logs and tests."""
+    out = []
+    for d in arr:
+        nop = 0 if d.kind in (OPKINDS["parameter"], OPKINDS["constant"]) else 2 if (2 <= d.kind <= 6 or d.kind == OPKINDS["dot"]) else 1
+        out.append((_KIND_NAMES[d.kind], _DTYPE_NAMES[d.dtype], tuple(d.shape[:d.rank]), tuple(d.operand[:nop])))
+    return out
+
+
+class FusedProgram:
+    """A whole computation graph run as the groups its fusion plan chose: one Plan per group,
+    intermediates between groups in device tensors.  Inputs: one tensor per parameter op of the
+    original list, in order; outputs: one per output op."""
+
+    def __init__(self, ops, **fusion_options):
+        import torch
+        self._torch = torch
+        self.ops = list(ops)
+        self.fusion = FusionPlan(self.ops, **fusion_options)
+        self.param_ops = [i for i, op in enumerate(self.ops) if op.kind == "parameter"]
+        self.output_ops = [i for i, op in enumerate(self.ops) if op.kind == "output"]
+        self.plans = []
+        for g in self.fusion.groups:
+            try:
+                plan = Plan(g["ops"])
+            except FsError as e:
+                if e.status != FS_ERR_UNSUPPORTED:
+                    raise
+                plan = Plan(g["ops"], "per_op")       # an op left alone that no stitched schedule takes (a lone dot)
+            self.plans.append(plan)
+        self.n_kernels = sum(p.info()["n_kernels"] for p in self.plans)
+
+    def run(self, inputs, stream=None):
+        torch = self._torch
+        dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+        values = {i: t for i, t in zip(self.param_ops, inputs)}
+        for g, plan in zip(self.fusion.groups, self.plans):
+            gin = [values[i] for i in g["input_of"]]
+            gout = []
+            for i in g["output_of"]:
+                op = self.ops[i]
+                t = torch.empty(op.shape, dtype=dt[op.dtype], device=gin[0].device if gin else "cuda:0")
+                values[i] = t
+                gout.append(t)
+            plan.launch(gin, gout, stream)
+        return [values[self.ops[i].operands[0]] for i in self.output_ops]
+
+    def close(self):
+        for p in self.plans:
+            p.close()
+        self.plans = []
 
     def __enter__(self):
         return self

@@ -15,6 +15,7 @@
 #include "per_op.h"
 #include "row_codegen.h"
 #include "shared_plan.h"
+#include "fusion_plan.h"
 
 struct fs_plan {
   fs::Graph graph;
@@ -35,6 +36,10 @@ struct fs_plan {
   void* workspace = nullptr;
   int device = -1;
   std::string description;
+};
+
+struct fs_fusion {
+  fs::FusionResult result;
 };
 
 namespace {
@@ -413,6 +418,98 @@ fs_status fs_shared_plan(const int32_t* operands, const int64_t* req_bytes, cons
   } catch (...) {
     return set_error(FS_ERR_NOMEM, "out of host memory");
   }
+  return FS_OK;
+}
+
+fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion_options* opt, fs_fusion** out) {
+  if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
+  *out = nullptr;
+  if (!ops || n_ops < 1) return set_error(FS_ERR_INVALID, "ops is NULL or empty");
+  try {
+    fs::FusionConfig cfg;
+    if (opt) {
+      if (opt->n_extra < 0 || (opt->n_extra > 0 && (!opt->extra_sizes || !opt->extra_ops))) return set_error(FS_ERR_INVALID, "extra patterns: NULL table");
+      const int32_t* next = opt->extra_ops;
+      for (int k = 0; k < opt->n_extra; ++k) {
+        if (opt->extra_sizes[k] < 1) return set_error(FS_ERR_INVALID, "extra patterns: empty pattern");
+        std::vector<int> pat(next, next + opt->extra_sizes[k]);
+        next += opt->extra_sizes[k];
+        for (int o : pat) if (o < 0 || o >= n_ops) return set_error(FS_ERR_INVALID, "extra patterns: op index out of range");
+        cfg.extra_patterns.push_back(pat);
+      }
+      if (opt->max_patterns < 0 || opt->max_patterns > 64) return set_error(FS_ERR_INVALID, "max_patterns out of range [0,64]");
+      if (opt->n_bw < 0 || (opt->n_bw > 0 && (!opt->bw_bytes || !opt->bw_gbs))) return set_error(FS_ERR_INVALID, "bandwidth model: NULL table");
+      if (opt->launch_us > 0) cfg.launch_us = opt->launch_us;
+      if (opt->max_patterns > 0) cfg.max_patterns = opt->max_patterns;
+      if (opt->explore_budget != 0) cfg.explore_budget = opt->explore_budget < 0 ? 0 : opt->explore_budget;
+      if (opt->seed_bytes > 0) cfg.seed_bytes = opt->seed_bytes;
+      for (int k = 0; k < opt->n_bw; ++k) {
+        if (opt->bw_bytes[k] <= 0 || opt->bw_gbs[k] <= 0 || (k > 0 && opt->bw_bytes[k] <= opt->bw_bytes[k - 1]))
+          return set_error(FS_ERR_INVALID, "bandwidth model: bytes must increase and rates be positive");
+        cfg.bandwidth.push_back({opt->bw_bytes[k], opt->bw_gbs[k]});
+      }
+    }
+    fs_fusion* f = new fs_fusion;
+    std::string err;
+    const std::vector<fs_op_desc> list(ops, ops + n_ops);
+    if (!fs::fusion_plan(list, cfg, &f->result, &err)) { delete f; return set_error(FS_ERR_INVALID, err); }
+    *out = f;
+  } catch (const std::bad_alloc&) {
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  }
+  return FS_OK;
+}
+
+fs_status fs_fusion_destroy(fs_fusion* f) {
+  delete f;
+  return FS_OK;
+}
+
+fs_status fs_fusion_info(const fs_fusion* f, int32_t* n_groups, int32_t* n_patterns, double* total, int32_t* rounds) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (n_groups) *n_groups = (int32_t)f->result.groups.size();
+  if (n_patterns) *n_patterns = (int32_t)f->result.patterns.size();
+  if (total) *total = f->result.total_score;
+  if (rounds) *rounds = f->result.solver_rounds;
+  return FS_OK;
+}
+
+fs_status fs_fusion_group_size(const fs_fusion* f, int32_t g, int32_t* n_ops, int32_t* n_in, int32_t* n_out,
+                               int32_t* n_members, double* score) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (g < 0 || g >= (int32_t)f->result.groups.size()) return set_error(FS_ERR_INVALID, "group index out of range");
+  const fs::FusionGroup& gr = f->result.groups[g];
+  if (n_ops) *n_ops = (int32_t)gr.list.size();
+  if (n_in) *n_in = (int32_t)gr.input_of.size();
+  if (n_out) *n_out = (int32_t)gr.output_of.size();
+  if (n_members) *n_members = (int32_t)gr.ops.size();
+  if (score) *score = gr.score;
+  return FS_OK;
+}
+
+fs_status fs_fusion_group(const fs_fusion* f, int32_t g, fs_op_desc* ops, int32_t* input_of, int32_t* output_of,
+                          int32_t* members) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (g < 0 || g >= (int32_t)f->result.groups.size()) return set_error(FS_ERR_INVALID, "group index out of range");
+  const fs::FusionGroup& gr = f->result.groups[g];
+  if (ops) for (size_t k = 0; k < gr.list.size(); ++k) ops[k] = gr.list[k];
+  if (input_of) for (size_t k = 0; k < gr.input_of.size(); ++k) input_of[k] = gr.input_of[k];
+  if (output_of) for (size_t k = 0; k < gr.output_of.size(); ++k) output_of[k] = gr.output_of[k];
+  if (members) for (size_t k = 0; k < gr.ops.size(); ++k) members[k] = gr.ops[k];
+  return FS_OK;
+}
+
+fs_status fs_fusion_pattern(const fs_fusion* f, int32_t k, int32_t* n_ops, int32_t* ops, int32_t cap, int32_t* origin,
+                            int64_t* saved_bytes, double* score, int32_t* chosen) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (k < 0 || k >= (int32_t)f->result.patterns.size()) return set_error(FS_ERR_INVALID, "pattern index out of range");
+  const fs::FusionPattern& p = f->result.patterns[k];
+  if (n_ops) *n_ops = (int32_t)p.ops.size();
+  if (ops) for (int32_t j = 0; j < cap && j < (int32_t)p.ops.size(); ++j) ops[j] = p.ops[j];
+  if (origin) *origin = p.origin;
+  if (saved_bytes) *saved_bytes = p.saved_bytes;
+  if (score) *score = p.score;
+  if (chosen) *chosen = p.chosen ? 1 : 0;
   return FS_OK;
 }
 

@@ -244,9 +244,13 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
 namespace {
 std::mutex g_cache_mutex;
 std::map<std::string, std::shared_ptr<std::vector<char>>> g_cache;
+thread_local bool g_dry_run = false;
 }  // namespace
 
+void codegen_set_dry_run(bool on) { g_dry_run = on; }
+
 bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err) {
+  if (g_dry_run) { code_object->clear(); return true; }     // planning only: the source exists, that is enough
   {
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     auto it = g_cache.find(source);

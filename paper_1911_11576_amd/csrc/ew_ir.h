@@ -48,6 +48,9 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
 // Compile with the run-time compiler (works on a machine without a GPU).  Results are cached
 // per process by source text.  False + message if the compiler is unavailable or fails.
 bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err);
+// While on (per thread), ew_compile_source succeeds without compiling: plans made then can be
+// inspected but not launched.  Used by the fusion planner to ask "can this group be generated".
+void codegen_set_dry_run(bool on);
 
 // A loaded kernel (module handle and function), bound to the device current at load time.
 struct EwModule {

@@ -1,0 +1,87 @@
+"""End to end: a computation graph larger than one fusion group is planned (Section 4), every
+group becomes a stitched plan, the groups run in order on the GPU, and the program's outputs
+are compared with the oracle's evaluation of the whole graph."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import interp
+from paper_1911_11576_amd import FusedProgram, Plan
+from workloads import TOLERANCE, graphs, inputs
+
+from gpu_util import assert_close, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    sys.__stderr__.write(f"[gpu-case] {msg}\n")
+    sys.__stderr__.flush()
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu(device):
+    yield
+
+
+def _encoder_inputs(rows, cols, batch, seq):
+    s, m = inputs.scaled_masked_softmax((batch, 1, seq, seq), "key_padding")
+    x, bias, res, gamma, beta = inputs.bias_gelu_residual_layernorm(rows, cols, "f32")
+    return [s.reshape(batch, seq, seq), m.reshape(batch, 1, seq), x, bias, res, gamma, beta]
+
+
+def _run(ops, ins, **kw):
+    dev_in = to_device(ops, ins)
+    with FusedProgram(ops, **kw) as prog:
+        outs = prog.run(dev_in)
+        torch.cuda.synchronize()
+        got = [t.to(torch.float64).cpu().numpy() for t in outs]
+        return got, prog.n_kernels, len(prog.fusion.groups)
+
+
+def test_encoder_tail_runs_as_a_few_stitched_groups():
+    announce("fused program encoder tail")
+    rows, cols, batch, seq = 300, 1024, 6, 128
+    ops, ins = graphs.encoder_tail(rows, cols, batch, seq), _encoder_inputs(rows, cols, batch, seq)
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins)
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], "encoder tail")
+    with Plan(ops, "per_op") as p:
+        unfused = p.info()["n_kernels"]
+    assert n_kernels < unfused / 4          # 30-odd kernels become a handful
+    # planning options change the grouping, never the result
+    for kw in (dict(explore_budget=-1), dict(launch_us=10.0), dict(max_patterns=4)):
+        again, _, _ = _run(ops, ins, **kw)
+        for a, b in zip(again, want):
+            assert_close(a, b, TOLERANCE["f32"], f"encoder tail {kw}")
+
+
+def test_crossing_branches_after_cycle_repair():
+    announce("fused program crossing branches")
+    ops = graphs.crossing_branches(257, 512)
+    ins = inputs.normal_tensors([(257, 512), (512,)], scale=0.5)
+    want = interp.run(ops, ins)
+    kinds = [op.kind for op in ops]
+    b_chain = [kinds.index("tanh"), kinds.index("tanh") + 2, len(ops) - 3]
+    for kw in ({}, dict(extra_patterns=[b_chain])):
+        got, _, _ = _run(ops, ins, **kw)
+        for a, b in zip(got, want):
+            assert_close(a, b, TOLERANCE["f32"], f"crossing branches {kw}")
+
+
+@pytest.mark.parametrize("name", ["layernorm_bwd", "multi_interest", "adam"])
+def test_single_group_graphs_through_the_planner(name):
+    announce(f"fused program {name}")
+    if name == "layernorm_bwd":
+        ops, ins = graphs.layernorm_bwd(517, 1024), inputs.layernorm_bwd(517, 1024)
+    elif name == "multi_interest":
+        ops, ins = graphs.multi_interest_pattern(7), inputs.multi_interest_pattern(7)
+    else:
+        ops, ins = graphs.adam_update((129, 512)), inputs.adam_update((129, 512))
+    want = interp.run(ops, ins)
+    got, _, _ = _run(ops, ins)
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], name)

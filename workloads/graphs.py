@@ -518,3 +518,59 @@ def causal_fill(shape, fill=-1e4, dtype="f32"):
         y = g.convert(y, dtype)
     g.output(y, "y")
     return g.ops
+
+
+# ----------------------------------------------------------------------------------
+# Computation graphs larger than one fusion group (input of the fusion planner, Section 4).
+# ----------------------------------------------------------------------------------
+
+def encoder_tail(rows, cols, batch, seq, dtype="f32"):
+    """Two independent branches of a Transformer block, as one graph:
+      scores[batch, seq, seq] -> * scale -> + mask -> softmax                       -> p
+      x[rows, cols] -> + bias -> gelu -> + residual -> layernorm -> * 2 -> tanh     -> y
+                                                     and the row sums of y**2        -> ss
+    The planner should find one stitched group per connected branch."""
+    g = Graph()
+    s = g.parameter("scores", dtype, (batch, seq, seq))
+    m = g.parameter("mask", dtype, (batch, 1, seq))
+    x = g.parameter("x", dtype, (rows, cols))
+    bias = g.parameter("bias", dtype, (cols,))
+    res = g.parameter("residual", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    beta = g.parameter("beta", dtype, (cols,))
+    z = g.add(g.multiply(s, g.constant(0.125)), g.broadcast(m, (batch, seq, seq), 0))
+    mx = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(mx, z)))
+    p = g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), z))
+    g.output(p, "p")
+    h = g.add(x, g.col_broadcast(bias, x))
+    h3 = g.multiply(g.multiply(h, h), h)
+    inner = g.multiply(g.add(h, g.multiply(h3, g.constant(GELU_K1))), g.constant(GELU_K0))
+    gelu = g.multiply(g.multiply(h, g.constant(0.5)), g.add(g.tanh(inner), g.constant(1.0)))
+    r = g.add(gelu, res)
+    ln = _layernorm_tail(g, r, gamma, beta, 1e-5)
+    y = g.tanh(g.multiply(ln, g.constant(2.0)))
+    g.output(y, "y")
+    g.output(g.reduce_sum(g.multiply(y, y), -1), "ss")
+    return g.ops
+
+
+def crossing_branches(rows, cols):
+    """Two chains that feed each other, so that fusing each chain on its own would make the
+    contracted graph cyclic (the situation of the paper's cyclic-dependence figure, Section 4.1):
+      a1 = exp(x); m = a1 * 2; a2 = m + colbc(b1); c = colsum(a1)      (full shape + column sum)
+      b1 = tanh(v); n = b1 * 3; b2 = n + c                               (per-column values)
+    a2 reads b1, b2 reads c: {a1, m, a2, c} and {b1, n, b2} are each convex, together cyclic."""
+    g = Graph()
+    x = g.parameter("x", "f32", (rows, cols))
+    v = g.parameter("v", "f32", (cols,))
+    a1 = g.exp(x)
+    m = g.multiply(a1, g.constant(2.0))
+    b1 = g.tanh(v)
+    n = g.multiply(b1, g.constant(3.0))
+    a2 = g.add(m, g.col_broadcast(b1, m))
+    c = g.reduce_sum(a1, 0)
+    b2 = g.add(n, c)
+    g.output(a2, "a2")
+    g.output(b2, "b2")
+    return g.ops
