@@ -196,7 +196,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one stitched kernel per fusion group; "
-              "rows / batch elements would shard across GPUs without communication, see DESIGN.md). "
+              "rows / batch elements would shard across GPUs without communication). "
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
