@@ -104,7 +104,7 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           p->schedule = FS_SCHED_ELEMENTWISE;
           p->lds_bytes = p->ew.lds_bytes;
           p->description = fs::ew_stitch_describe(p->ew);
-        } else if (lo.codegen && has_reduce && fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) {
+        } else if (lo.codegen && fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) {
           p->match.kind = fs::MATCH_NONE;
           p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
           p->row_form = 3;
@@ -114,7 +114,8 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
           p->description = fs::row_gen_describe(p->row_gen);
         } else if (!recognised) {
-          if (has_reduce && lo.codegen) { st = st2; err = err2; }
+          if (lo.codegen && (has_reduce || st2 == FS_ERR_INVALID)) { st = st2; err = err2; }
+          else if (lo.codegen && st == FS_ERR_UNSUPPORTED && !err2.empty()) err += "; " + err2;
           if (st == FS_ERR_UNSUPPORTED && why != "no stitched schedule matches this group") err = why + " (" + err + ")";
           delete p;
           return set_error((fs_status)st, err);

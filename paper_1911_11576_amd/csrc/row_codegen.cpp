@@ -220,13 +220,23 @@ struct Analysis {
 
   bool run() {
     const int n = g.size();
-    // the full shape is the operand shape of the first reduction
+    // the full shape is the operand shape of the first reduction; without a reduction (full and
+    // per-row arithmetic mixed, a per-row value broadcast into full ops) the largest shape computed
     int first = -1;
     for (int i = 0; i < n && first < 0; ++i) if (is_reduce(g[i].kind)) first = i;
-    if (first < 0) return fail("generated row schedule: no reduction in the group");
-    const Node& src = g[g[first].operand[0]];
+    int shape_of = first >= 0 ? g[first].operand[0] : -1;
+    if (first < 0) {
+      for (int i = 0; i < n; ++i) {
+        const int k = g[i].kind;
+        if (!(is_binary(k) || is_unary(k) || k == FS_CONVERT || k == FS_CAUSAL_MASK)) continue;
+        if (shape_of < 0 || g[i].numel() > g[shape_of].numel() || (g[i].numel() == g[shape_of].numel() && g[i].rank > g[shape_of].rank))
+          shape_of = i;
+      }
+      if (shape_of < 0) return fail("generated row schedule: the group computes nothing");
+    }
+    const Node& src = g[shape_of];
     rank = src.rank;
-    if (rank < 1) return fail("generated row schedule: rank-0 reduction");
+    if (rank < 1) return fail("generated row schedule: rank-0 group");
     for (int d = 0; d < rank; ++d) S[d] = src.shape[d];
     cols = S[rank - 1];
     rows = 1;

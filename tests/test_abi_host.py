@@ -257,6 +257,18 @@ def test_row_groups_without_a_hand_written_kernel_get_a_generated_one():
         assert p.info()["algorithmic_bytes"] == (2 * 64 * 1024 + 2 * 1024 + 2 * 64) * 4
 
 
+def test_per_row_arithmetic_without_a_reduction_is_a_row_group():
+    # ops of the full and of the per-row shape in one group: not an elementwise group (one shape),
+    # the row generator takes it with the largest computed shape as the full shape
+    with Plan(graphs.gated_rows((300, 96))) as p:
+        info = p.info()
+        assert info["schedule"] == "row" and info["n_kernels"] == 1
+        assert info["algorithmic_bytes"] == (2 * 300 * 96 + 2 * 300 + 96) * 4
+    with pytest.raises(FsError) as e:
+        Plan(graphs.gated_rows((300, 96)), mode="prebuilt")
+    assert e.value.status == binding.FS_ERR_UNSUPPORTED
+
+
 def test_generated_mode_and_prebuilt_mode_on_recognised_groups():
     ops, _ = BY_NAME["layernorm_fwd"].build("small")
     with Plan(ops) as p:

@@ -1,0 +1,71 @@
+"""Parity fuzzing of the kernel generators: random groups (elementwise ops on full and per-row
+values, reductions over the last dim, broadcasts back, optional column sums) are planned, run
+on the GPU and compared with the CPU oracle, through every template that takes them."""
+import random
+import sys
+
+import pytest
+
+from paper_1911_11576_amd import FsError, Plan, binding
+from workloads import graphs, inputs
+
+from gpu_util import check_against_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    sys.__stderr__.write(f"[gpu-case] {msg}\n")
+    sys.__stderr__.flush()
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu(device):
+    yield
+
+
+SHAPES = [(37, 128), (5, 768), (3, 7, 64), (2, 3, 5, 32), (300, 8), (33, 100), (65, 30), (7, 770), (4, 4096), (129, 16)]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_row_groups(seed):
+    rng = random.Random(4242 + seed)
+    shape = SHAPES[seed % len(SHAPES)]
+    dtype = ["f32", "f32", "bf16", "f16"][seed % 4]
+    ops, pshapes = graphs.random_row_group(rng, shape, dtype, n_ops=rng.randint(6, 16))
+    ins = inputs.normal_tensors(pshapes, dtype, seed_offset=100 + seed)
+    announce(f"random row group seed {seed} shape {shape} {dtype}: {len(ops)} ops")
+    with Plan(ops) as p:
+        schedule = p.info()["schedule"]
+        assert schedule in ("row", "elementwise")
+        streamed = "streamed" in p.describe()
+    check_against_oracle(ops, ins, what=f"random group {seed}")
+    if schedule == "row":
+        if not streamed:
+            check_against_oracle(ops, ins, what=f"random group {seed} streamed", grid=3)
+        try:
+            check_against_oracle(ops, ins, what=f"random group {seed} persistent", grid=2, rows_per_wave=1)
+        except FsError as e:
+            assert e.status == binding.FS_ERR_UNSUPPORTED      # rows too long for one wavefront's registers
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_groups_with_column_sums(seed):
+    rng = random.Random(777 + seed)
+    shape = [(37, 128), (300, 8), (33, 100), (517, 1024), (65, 30), (5, 2048), (1000, 64), (129, 16)][seed]
+    ops, pshapes = graphs.random_row_group(rng, shape, "f32", n_ops=rng.randint(5, 12), column_sums=True)
+    ins = inputs.normal_tensors(pshapes, "f32", seed_offset=200 + seed)
+    announce(f"random group with column sum seed {seed} shape {shape}: {len(ops)} ops")
+    with Plan(ops) as p:
+        assert p.info()["schedule"] == "row_col" and p.info()["n_kernels"] == 2
+    check_against_oracle(ops, ins, what=f"random column group {seed}")
+    check_against_oracle(ops, ins, what=f"random column group {seed} grid 3", grid=3, wg_size=128)
+
+
+@pytest.mark.parametrize("shape,dtype", [((300, 96), "f32"), ((7, 5, 33), "f32"), ((64, 2048), "bf16"), ((1000, 4), "f16")])
+def test_per_row_arithmetic_without_a_reduction(shape, dtype):
+    ops = graphs.gated_rows(shape, dtype)
+    ins = inputs.normal_tensors([shape, shape[:-1], shape[-1:]], dtype, seed_offset=31)
+    announce(f"gated rows {shape} {dtype}")
+    check_against_oracle(ops, ins, what=f"gated rows {shape}")
+    check_against_oracle(ops, ins, what=f"gated rows {shape} streamed", grid=5)

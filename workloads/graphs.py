@@ -351,6 +351,21 @@ def _f32_in(g, dtype, *ts):
     return ts if dtype == "f32" else tuple(g.convert(t, "f32") for t in ts)
 
 
+def gated_rows(shape, dtype="f32"):
+    """Per-row arithmetic beside full arithmetic with no reduction: gate = tanh(rowv) * rowv + 1
+    (computed once per row), y = x * gate + colv, and the gate itself as a second output."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    rowv = g.parameter("rowv", dtype, shape[:-1])
+    colv = g.parameter("colv", dtype, (shape[-1],))
+    xf, rf, cf = _f32_in(g, dtype, x, rowv, colv)
+    gate = g.add(g.multiply(g.tanh(rf), rf), g.constant(1.0))
+    y = g.add(g.multiply(xf, g.row_broadcast(gate, xf)), g.col_broadcast(cf, xf))
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
+    g.output(gate if dtype == "f32" else g.convert(gate, dtype), "gate")
+    return g.ops
+
+
 def log_softmax(shape, dtype="f32"):
     """y = x - max - log(sum(exp(x - max))) over the last dim."""
     g = Graph()
@@ -574,3 +589,64 @@ def crossing_branches(rows, cols):
     g.output(a2, "a2")
     g.output(b2, "b2")
     return g.ops
+
+
+# ----------------------------------------------------------------------------------
+# Random groups (parity fuzzing of the kernel generators).
+# ----------------------------------------------------------------------------------
+
+def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
+    """A random DAG over one full shape: elementwise ops on full and per-row values, reductions
+    over the last dim, per-row values broadcast back, a per-row and a per-column operand;
+    values are kept tame (tanh before exp, sums divided by the row length) so that every op
+    list is well conditioned.  `rng` is a random.Random.  Returns (ops, parameter shapes)."""
+    g = Graph()
+    rowshape, ncol = tuple(shape[:-1]), shape[-1]
+    x = g.parameter("x", dtype, shape)
+    y = g.parameter("y", dtype, shape)
+    rv = g.parameter("rv", dtype, rowshape) if rowshape else None
+    cv = g.parameter("cv", dtype, (ncol,))
+    conv = (lambda t: t) if dtype == "f32" else (lambda t: g.convert(t, "f32"))
+    full = [conv(x), conv(y)]
+    rows = [conv(rv)] if rv is not None else []
+    cvf = conv(cv)
+    for _ in range(n_ops):
+        kind = rng.choice(["bin", "bin", "un", "reduce", "rowop", "bcast_row", "bcast_col", "const"])
+        if kind == "bin":
+            a, b = rng.choice(full), rng.choice(full)
+            full.append(getattr(g, rng.choice(["add", "subtract", "multiply", "maximum"]))(a, b))
+        elif kind == "un":
+            a = rng.choice(full)
+            op = rng.choice(["tanh", "negate", "exp_tanh", "square_plus"])
+            if op == "exp_tanh":
+                full.append(g.exp(g.tanh(a)))
+            elif op == "square_plus":
+                full.append(g.rsqrt(g.add(g.multiply(a, a), g.constant(1.0))))
+            else:
+                full.append(getattr(g, op)(a))
+        elif kind == "reduce" and rowshape:
+            a = rng.choice(full)
+            if rng.random() < 0.5:
+                rows.append(g.divide(g.reduce_sum(a, -1), g.constant(ncol)))
+            else:
+                rows.append(g.reduce_max(g.tanh(a), -1))
+        elif kind == "rowop" and len(rows) >= 1:
+            a, b = rng.choice(rows), rng.choice(rows)
+            rows.append(getattr(g, rng.choice(["add", "multiply", "maximum"]))(g.tanh(a), b))
+        elif kind == "bcast_row" and rows:
+            full.append(getattr(g, rng.choice(["add", "multiply", "subtract"]))(rng.choice(full), g.row_broadcast(rng.choice(rows), full[0])))
+        elif kind == "bcast_col":
+            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.col_broadcast(cvf, full[0])))
+        elif kind == "const":
+            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.constant(rng.choice([0.5, -1.25, 2.0]))))
+    out = full[-1]
+    if out in (full[0], full[1]):
+        out = g.add(full[0], full[1])
+    g.output(out if dtype == "f32" else g.convert(out, dtype))
+    computed_rows = [r for r in rows if g.ops[r].kind not in ("parameter", "convert")]
+    if computed_rows:
+        g.output(computed_rows[-1])
+    if column_sums and len(shape) == 2:
+        g.output(g.reduce_sum(g.tanh(rng.choice(full)), 0))
+    pshapes = [shape, shape] + ([rowshape] if rowshape else []) + [(ncol,)]
+    return g.ops, pshapes
