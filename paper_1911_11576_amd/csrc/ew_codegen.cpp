@@ -49,20 +49,21 @@ static __device__ __forceinline__ float bf16_lo(unsigned w) { return bits_f32(w 
 static __device__ __forceinline__ float bf16_hi(unsigned w) { return bits_f32(w & 0xffff0000u); }
 static __device__ __forceinline__ float f16_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
 static __device__ __forceinline__ float f16_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
-// round to nearest even; NaN stays NaN
-static __device__ __forceinline__ unsigned to_bf16(float f) {
-  const unsigned u = f32_bits(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+// round to nearest even, NaN stays NaN: the hardware conversion (v_cvt_pk_bf16_f32, two values
+// per instruction where the caller packs a pair)
+static __device__ __forceinline__ unsigned to_bf16(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
 static __device__ __forceinline__ unsigned to_f16(float f) { return __builtin_bit_cast(unsigned short, (_Float16)f); }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ unsigned pack_to_bf16(float lo, float hi) { return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2)); }
+static __device__ __forceinline__ unsigned pack_to_f16(float lo, float hi) { return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, f16x2)); }
 // tanh(x) = 1 - 2 / (1 + e^(2x)) on the hardware exp2 and reciprocal: absolute error of a
 // few 1e-7; exp2 overflow gives rcp(inf) = 0 -> 1, underflow gives 1 - 2 = -1
 static __device__ __forceinline__ float tanh_fast(float x) {
   const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
-static __device__ __forceinline__ float round_bf16(float f) { return bits_f32(to_bf16(f) << 16); }
+static __device__ __forceinline__ float round_bf16(float f) { return (float)(__bf16)f; }
 static __device__ __forceinline__ float round_f16(float f) { return (float)(_Float16)f; }
 )SRC";
 
@@ -92,7 +93,7 @@ std::string op_text(const EwIrNode& n, bool fast) {
     case FS_EXP: return "expf(" + a + ")";
     case FS_LOG: return "logf(" + a + ")";
     case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
-    case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
+    case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
@@ -218,7 +219,7 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
       if (W == 1) e.line("      p[0] = (unsigned short)%s(t%d[0]);", cv, n.id);
       else {
         e.line("      unsigned w[W / 2];");
-        e.line("      UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[2 * j]) | (%s(t%d[2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+        e.line("      UNROLL for (int j = 0; j < W / 2; ++j) w[j] = pack_%s(t%d[2 * j], t%d[2 * j + 1]);", cv, n.id, n.id);
         if (W == 8) e.line("      __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
         else e.line("      __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
       }

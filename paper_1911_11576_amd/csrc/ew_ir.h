@@ -11,7 +11,9 @@
 namespace fs {
 
 enum EwOperandKind : int { EW_FROM_NODE = 0, EW_FROM_VIEW = 1, EW_FROM_CONST = 2 };
-enum EwExtraOp : int { EW_OP_ROUND_F16 = 100, EW_OP_ROUND_BF16 = 101 };   // beside the fs_opkind values
+// beside the fs_opkind values; EW_OP_COPY stands for a rounding whose only reader is the store of
+// the same dtype, which rounds the same way
+enum EwExtraOp : int { EW_OP_ROUND_F16 = 100, EW_OP_ROUND_BF16 = 101, EW_OP_COPY = 102 };
 
 struct EwIrOperand {
   int kind = EW_FROM_NODE;

@@ -489,6 +489,14 @@ struct EwCompiler {
       in.out_dtype = out_dtype[node];
       ir.nodes.push_back(in);
     }
+    // a rounding read by nothing but the store of the same dtype is left to the store
+    std::vector<char> read(g.size(), 0);
+    for (const EwIrNode& r : ir.nodes)
+      for (int j = 0; j < r.n_operands; ++j) if (r.opnd[j].kind == EW_FROM_NODE) read[r.opnd[j].index] = 1;
+    for (EwIrNode& r : ir.nodes) {
+      const bool rounds = (r.op == EW_OP_ROUND_F16 && r.out_dtype == FS_F16) || (r.op == EW_OP_ROUND_BF16 && r.out_dtype == FS_BF16);
+      if (rounds && r.out_ordinal >= 0 && !read[r.id]) r.op = EW_OP_COPY;
+    }
     return true;
   }
 

@@ -310,6 +310,14 @@ struct Analysis {
       nodes.push_back(r);
     }
     if (views.size() > 24) return fail("generated row schedule: more than 24 distinct operand views");
+    // a rounding read by nothing but the store of the same dtype is left to the store
+    std::vector<char> read(n, 0);
+    for (const RNode& r : nodes)
+      for (int j = 0; j < r.nop; ++j) if (r.o[j].kind == OP_NODE || r.o[j].kind == OP_ROWB) read[r.o[j].index] = 1;
+    for (RNode& r : nodes) {
+      const bool rounds = (r.op == EW_OP_ROUND_F16 && r.out_dtype == FS_F16) || (r.op == EW_OP_ROUND_BF16 && r.out_dtype == FS_BF16);
+      if (rounds && r.out_ord >= 0 && !read[r.id]) r.op = EW_OP_COPY;
+    }
     return true;
   }
 };
@@ -385,7 +393,7 @@ std::string op_text(int op, const std::string& a, const std::string& b, bool fas
     case FS_EXP: return "expf(" + a + ")";
     case FS_LOG: return "logf(" + a + ")";
     case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
-    case FS_RSQRT: return "1.0f / sqrtf(" + a + ")";
+    case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
@@ -804,7 +812,7 @@ struct Gen {
           e.line("    unsigned short* o = static_cast<unsigned short*>(a.out[%d]) + wg_row0 * N;", n.out_ord);
           e.line("    for (int i = threadIdx.x * %d; i + %d <= wg_count; i += %d * %d) {", V, V, wg, V);
           e.line("      unsigned w[%d];", V / 2);
-          e.line("      UNROLL for (int j = 0; j < %d; ++j) w[j] = %s(stage[i + 2 * j]) | (%s(stage[i + 2 * j + 1]) << 16);", V / 2, cv, cv);
+          e.line("      UNROLL for (int j = 0; j < %d; ++j) w[j] = pack_%s(stage[i + 2 * j], stage[i + 2 * j + 1]);", V / 2, cv);
           if (V == 8) e.line("      __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(o + i));");
           else e.line("      __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(o + i));");
           e.line("    }");
@@ -828,7 +836,7 @@ struct Gen {
         if (W == 1) e.line("    p[0] = (unsigned short)%s(t%d[k][0]);", cv, n.id);
         else {
           e.line("    unsigned w[W / 2];");
-          e.line("    UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[k][2 * j]) | (%s(t%d[k][2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+          e.line("    UNROLL for (int j = 0; j < W / 2; ++j) w[j] = pack_%s(t%d[k][2 * j], t%d[k][2 * j + 1]);", cv, n.id, n.id);
           if (W == 8) e.line("    __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
           else if (W == 4) e.line("    __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
           else e.line("    __builtin_nontemporal_store(w[0], reinterpret_cast<unsigned*>(p));");
@@ -1112,7 +1120,7 @@ struct Stream {
       if (W == 1) e.line("          p[0] = (unsigned short)%s(t%d[0]);", cv, n.id);
       else {
         e.line("          unsigned w[W / 2];");
-        e.line("          UNROLL for (int j = 0; j < W / 2; ++j) w[j] = %s(t%d[2 * j]) | (%s(t%d[2 * j + 1]) << 16);", cv, n.id, cv, n.id);
+        e.line("          UNROLL for (int j = 0; j < W / 2; ++j) w[j] = pack_%s(t%d[2 * j], t%d[2 * j + 1]);", cv, n.id, n.id);
         if (W == 8) e.line("          __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(p));");
         else if (W == 4) e.line("          __builtin_nontemporal_store(u32x2{w[0], w[1]}, reinterpret_cast<u32x2*>(p));");
         else e.line("          __builtin_nontemporal_store(w[0], reinterpret_cast<unsigned*>(p));");

@@ -84,12 +84,18 @@ def test_layernorm_shapes_16bit(rows, cols, dtype):
                          what=f"ln {dtype} {rows}x{cols}")
 
 
+# The group with the GELU prologue has two stitched forms: the default is the generated kernel
+# (mode "stitched"), the hand-written kernels serve mode "prebuilt"
+GELU_LN_MODES = ["stitched", "prebuilt"]
+
+
+@pytest.mark.parametrize("mode", GELU_LN_MODES)
 @pytest.mark.parametrize("dtype,rows,cols", [("bf16", 203, 1024), ("f16", 33, 768), ("f32", 65, 1024),
                                              ("bf16", 4, 2048), ("f32", 3, 8)])
-def test_bias_gelu_residual_layernorm_shapes(dtype, rows, cols):
-    announce(f"bias+gelu+res+ln {dtype} {rows}x{cols}")
+def test_bias_gelu_residual_layernorm_shapes(dtype, rows, cols, mode):
+    announce(f"bias+gelu+res+ln {dtype} {rows}x{cols} {mode}")
     check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
-                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 {dtype} {rows}x{cols}")
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), mode, what=f"cfg4 {dtype} {rows}x{cols}")
 
 
 @pytest.mark.parametrize("shape", [(1, 4), (3, 12), (1030, 128), (77, 64), (5, 1000), (9, 2048), (130, 32), (33, 16)])
@@ -136,11 +142,12 @@ def test_layernorm_long_or_unaligned_rows_f32(rows, cols):
     check_against_oracle(graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols), what=f"ln block {rows}x{cols}")
 
 
+@pytest.mark.parametrize("mode", GELU_LN_MODES)
 @pytest.mark.parametrize("dtype,rows,cols", [("bf16", 5, 4096), ("f16", 3, 3001), ("bf16", 2, 12), ("f16", 6, 8200)])
-def test_gelu_layernorm_long_or_unaligned_rows_16bit(dtype, rows, cols):
-    announce(f"bias+gelu+res+ln block form {dtype} {rows}x{cols}")
+def test_gelu_layernorm_long_or_unaligned_rows_16bit(dtype, rows, cols, mode):
+    announce(f"bias+gelu+res+ln block form {dtype} {rows}x{cols} {mode}")
     check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
-                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 block {dtype} {rows}x{cols}")
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), mode, what=f"cfg4 block {dtype} {rows}x{cols}")
 
 
 @pytest.mark.parametrize("shape,mask", [((5, 94), "full"), ((3, 4100), "full"), ((6, 2049), "none"), ((2, 3, 94, 94), "key_padding"),
@@ -157,11 +164,12 @@ def test_layernorm_team_form_f32(rows, cols):
     check_against_oracle(graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols), what=f"ln team {rows}x{cols}")
 
 
+@pytest.mark.parametrize("mode", GELU_LN_MODES)
 @pytest.mark.parametrize("dtype,rows,cols", [("bf16", 3, 2056), ("f16", 5, 4096), ("bf16", 2, 32768), ("f16", 3, 12288)])
-def test_gelu_layernorm_team_form_16bit(dtype, rows, cols):
-    announce(f"bias+gelu+res+ln team form {dtype} {rows}x{cols}")
+def test_gelu_layernorm_team_form_16bit(dtype, rows, cols, mode):
+    announce(f"bias+gelu+res+ln team form {dtype} {rows}x{cols} {mode}")
     check_against_oracle(graphs.bias_gelu_residual_layernorm(rows, cols, dtype),
-                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), what=f"cfg4 team {dtype} {rows}x{cols}")
+                         inputs.bias_gelu_residual_layernorm(rows, cols, dtype), mode, what=f"cfg4 team {dtype} {rows}x{cols}")
 
 
 @pytest.mark.parametrize("shape,mask", [((5, 4096), "full"), ((2, 2, 3, 8192), "key_padding"), ((3, 16000), "none")])
@@ -333,11 +341,12 @@ def test_full_size_attention_sampled_batches():
     assert not np.isnan(got).any()
 
 
-def test_full_size_bias_gelu_ln_sampled_rows():
-    announce("full cfg4")
+@pytest.mark.parametrize("mode", GELU_LN_MODES)
+def test_full_size_bias_gelu_ln_sampled_rows(mode):
+    announce(f"full cfg4 {mode}")
     cfg = BY_NAME["bias_gelu_residual_layernorm"]
     ops, ins = cfg.build("full")
-    (got,) = run_gpu(ops, ins)
+    (got,) = run_gpu(ops, ins, mode)
     idx = _sample_rows(ins[0].shape[0], 128)
     sub = graphs.bias_gelu_residual_layernorm(len(idx), 1024)
     (want,) = interp.run(sub, [ins[0][idx], ins[1], ins[2][idx], ins[3], ins[4]])
