@@ -63,6 +63,11 @@ static __device__ __forceinline__ float tanh_fast(float x) {
   const float e = __builtin_amdgcn_exp2f(x * 2.885390081777927f);
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
+// mul*h / (1 + exp2(h*(a0 + a1*h*h))), the tanh-form GELU; exp2 overflow gives rcp(inf) = 0
+static __device__ __forceinline__ float gelu_tanh(float h, float mul, float a0, float a1) {
+  const float e = __builtin_amdgcn_exp2f(h * (a0 + a1 * (h * h)));
+  return (mul == 1.0f ? h : mul * h) * __builtin_amdgcn_rcpf(1.0f + e);
+}
 static __device__ __forceinline__ float round_bf16(float f) { return (float)(__bf16)f; }
 static __device__ __forceinline__ float round_f16(float f) { return (float)(_Float16)f; }
 )SRC";
@@ -97,6 +102,16 @@ std::string op_text(const EwIrNode& n, bool fast) {
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
+    case EW_OP_GELU_TANH: {
+      std::string t = "gelu_tanh(" + a;
+      for (int q = 0; q < 3; ++q) {
+        EwIrOperand c;
+        c.kind = EW_FROM_CONST;
+        c.cval = n.gelu[q];
+        t += ", " + operand_text(c);
+      }
+      return t + ")";
+    }
     case FS_CAUSAL_MASK: {
       // kept where the last index does not exceed the second-to-last one
       EwIrOperand fill;

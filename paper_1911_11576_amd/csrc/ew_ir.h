@@ -13,7 +13,8 @@ namespace fs {
 enum EwOperandKind : int { EW_FROM_NODE = 0, EW_FROM_VIEW = 1, EW_FROM_CONST = 2 };
 // beside the fs_opkind values; EW_OP_COPY stands for a rounding whose only reader is the store of
 // the same dtype, which rounds the same way
-enum EwExtraOp : int { EW_OP_ROUND_F16 = 100, EW_OP_ROUND_BF16 = 101, EW_OP_COPY = 102 };
+// EW_OP_GELU_TANH is the tanh-form GELU found as an idiom (see match.h), one operand and three constants
+enum EwExtraOp : int { EW_OP_ROUND_F16 = 100, EW_OP_ROUND_BF16 = 101, EW_OP_COPY = 102, EW_OP_GELU_TANH = 103 };
 
 struct EwIrOperand {
   int kind = EW_FROM_NODE;
@@ -25,6 +26,7 @@ struct EwIrNode {
   int op = 0;              // fs_opkind of an elementwise op, or an EwExtraOp
   int n_operands = 1;
   EwIrOperand opnd[2];
+  float gelu[3] = {0.f, 0.f, 0.f};   // EW_OP_GELU_TANH: mul, a0, a1 of mul*h / (1 + exp2(h*(a0 + a1*h*h)))
   int out_ordinal = -1;    // >= 0: the value is this group output ...
   int out_dtype = FS_F32;  // ... stored in this dtype
 };

@@ -21,6 +21,7 @@
 
 #include "dev_common.h"
 #include "ew_ir.h"
+#include "match.h"
 #include "launchers.h"
 #include "per_op.h"
 #include "../../include/fs.h"
@@ -466,12 +467,41 @@ struct EwCompiler {
     ir.n = P.n;
     ir.n_outputs = (int)g.outputs.size();
     for (int d = 0; d < FS_MAX_RANK; ++d) ir.shape[d] = P.shape[d];
+    // the tanh-form GELU is generated as one op (the interpreter's program keeps the ops spelled out)
+    std::vector<int> idiom_of(n, -1);
+    std::vector<char> inside_idiom(n, 0);
+    const std::vector<GeluIdiom> idioms = find_gelu_idioms(g);
+    for (size_t q = 0; q < idioms.size(); ++q) {
+      bool plain = true;   // an interior value that is a group output keeps the ops spelled out
+      for (int v : idioms[q].interior) if (out_ord[v] >= 0) plain = false;
+      if (!plain) continue;
+      idiom_of[idioms[q].out] = (int)q;
+      for (int v : idioms[q].interior) inside_idiom[v] = 1;
+    }
     for (int node : order) {
       const Node& x = g[node];
+      if (inside_idiom[node]) continue;
       EwIrNode in;
       in.id = node;
       in.op = x.kind == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : x.kind;
       in.n_operands = n_operands(node);
+      if (idiom_of[node] >= 0) {
+        const GeluIdiom& id = idioms[idiom_of[node]];
+        in.op = EW_OP_GELU_TANH;
+        in.n_operands = 1;
+        gelu_constants(id, in.gelu);
+        const int a = canon(id.h);
+        if (is_compute(a)) { in.opnd[0].kind = EW_FROM_NODE; in.opnd[0].index = a; }
+        else {
+          bool is_const = false;
+          if (!leaf(a, &in.opnd[0].index, &is_const, &in.opnd[0].cval)) return false;
+          in.opnd[0].kind = is_const ? EW_FROM_CONST : EW_FROM_VIEW;
+        }
+        in.out_ordinal = out_ord[node];
+        in.out_dtype = out_dtype[node];
+        ir.nodes.push_back(in);
+        continue;
+      }
       if (x.kind == FS_CAUSAL_MASK) {
         if (x.rank < 2) return fail("elementwise schedule: causal_mask below rank 2");
         in.opnd[1].cval = (float)x.attr;       // the fill value rides in the unused second operand

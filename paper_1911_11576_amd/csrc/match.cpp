@@ -160,22 +160,9 @@ bool match_layernorm_tail(const Rec& r, int y, LnTail* out) {
   return pc == 1.0 && f.size() == 2 && f[0] == cn && f[1] == cn;
 }
 
-// r = c_half*h*(1 + tanh(k0*(h + k1*h^3))) [+ residual], h = x [+ bias]
-bool match_gelu_prologue(const Rec& r, int rn, RowSpec* sp, int* x_node, int* bias_node, int* res_node) {
+// gel = c_half*h*(1 + tanh(k0*(h + k1*h^3))), in any association and operand order
+bool match_gelu_core(const Rec& r, int gel, int* h_out, double* c_half, double* k0_out, double* k1_out) {
   const Graph& g = r.g;
-  std::vector<Term> t; double c = 0;
-  r.sum_terms(rn, +1, t, c);
-  if (c != 0) return false;
-  int gel = -1;
-  *res_node = -1;
-  if (t.size() == 1 && t[0].sign > 0) gel = t[0].node;
-  else if (t.size() == 2 && t[0].sign > 0 && t[1].sign > 0) {
-    for (int k = 0; k < 2; ++k) {
-      const int p = r.in_param(t[k].node);
-      if (p >= 0 && g[p].same_shape(g[rn])) { *res_node = p; gel = t[1 - k].node; break; }
-    }
-  }
-  if (gel < 0) return false;
   std::vector<int> f; double ch = 1;
   r.prod_factors(gel, f, ch);
   if (f.size() != 2) return false;
@@ -197,6 +184,29 @@ bool match_gelu_prologue(const Rec& r, int rn, RowSpec* sp, int* x_node, int* bi
   std::vector<int> qf; double k1 = 1;
   r.prod_factors(wt[1].node, qf, k1);
   if (qf.size() != 3 || qf[0] != h || qf[1] != h || qf[2] != h) return false;
+  *h_out = h; *c_half = ch; *k0_out = k0; *k1_out = k1;
+  return true;
+}
+
+// r = gel [+ residual], h = x [+ bias]
+bool match_gelu_prologue(const Rec& r, int rn, RowSpec* sp, int* x_node, int* bias_node, int* res_node) {
+  const Graph& g = r.g;
+  std::vector<Term> t; double c = 0;
+  r.sum_terms(rn, +1, t, c);
+  if (c != 0) return false;
+  int gel = -1;
+  *res_node = -1;
+  if (t.size() == 1 && t[0].sign > 0) gel = t[0].node;
+  else if (t.size() == 2 && t[0].sign > 0 && t[1].sign > 0) {
+    for (int k = 0; k < 2; ++k) {
+      const int p = r.in_param(t[k].node);
+      if (p >= 0 && g[p].same_shape(g[rn])) { *res_node = p; gel = t[1 - k].node; break; }
+    }
+  }
+  if (gel < 0) return false;
+  int h = -1;
+  double ch = 1, k0 = 1, k1 = 1;
+  if (!match_gelu_core(r, gel, &h, &ch, &k0, &k1)) return false;
   // h = x (+ bias)
   *bias_node = -1;
   int xp = r.in_param(h);
@@ -499,6 +509,57 @@ bool try_attention(const Rec& r, Match* m) {
 }
 
 }  // namespace
+
+std::vector<GeluIdiom> find_gelu_idioms(const Graph& g) {
+  std::vector<GeluIdiom> found;
+  const int n = g.size();
+  Rec r(g);
+  auto n_operands = [&](const Node& x) {
+    switch (x.kind) {
+      case FS_PARAMETER: case FS_CONSTANT: return 0;
+      case FS_ADD: case FS_SUBTRACT: case FS_MULTIPLY: case FS_DIVIDE: case FS_MAXIMUM: case FS_DOT: return 2;
+      default: return 1;
+    }
+  };
+  std::vector<std::vector<int>> users(n);
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < n_operands(g[i]); ++j) users[g[i].operand[j]].push_back(i);
+  std::vector<char> taken(n, 0);
+  for (int i = n - 1; i >= 0; --i) {
+    if (g[i].kind != FS_MULTIPLY || taken[i]) continue;
+    GeluIdiom id;
+    if (!match_gelu_core(r, i, &id.h, &id.half, &id.k0, &id.k1)) continue;
+    // the ops between h and the result (constants aside)
+    std::vector<int> stack{i};
+    std::vector<char> seen(n, 0);
+    bool ok = true;
+    while (!stack.empty() && ok) {
+      const int v = stack.back(); stack.pop_back();
+      for (int j = 0; j < n_operands(g[v]); ++j) {
+        const int o = g[v].operand[j];
+        if (o == id.h || g[o].kind == FS_CONSTANT || seen[o]) continue;
+        const int k = g[o].kind;
+        if (!(k == FS_MULTIPLY || k == FS_ADD || k == FS_SUBTRACT || k == FS_NEGATE || k == FS_TANH || k == FS_DIVIDE)) { ok = false; break; }
+        seen[o] = 1;
+        id.interior.push_back(o);
+        stack.push_back(o);
+      }
+    }
+    if (!ok) continue;
+    // nothing outside the idiom reads an interior value, and none of them is taken already
+    seen[i] = 1;
+    for (int v : id.interior) {
+      if (taken[v]) ok = false;
+      for (int u : users[v]) if (!seen[u]) ok = false;
+    }
+    if (!ok) continue;
+    id.out = i;
+    for (int v : id.interior) taken[v] = 1;
+    taken[i] = 1;
+    found.push_back(id);
+  }
+  return found;
+}
 
 bool recognise(const Graph& g, Match* m) {
   Rec r(g);

@@ -15,6 +15,7 @@
 #include "row_codegen.h"
 #include "shared_plan.h"
 #include "launchers.h"
+#include "match.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -45,6 +46,7 @@ struct RNode {
   int id = -1, op = 0, cls = CLS_NONE, nop = 1;
   Opnd o[2];
   std::vector<int> dot_row, dot_full;   // ROP_DOT_OUTER: view pairs per k; ROP_DOT_REDUCE: dot_full[0]
+  float gelu[3] = {0.f, 0.f, 0.f};      // EW_OP_GELU_TANH: mul, a0, a1 of mul*h / (1 + exp2(h*(a0 + a1*h*h)))
   int out_ord = -1, out_dtype = FS_F32;
 };
 struct RView {
@@ -251,10 +253,36 @@ struct Analysis {
       out_dtype[s] = g[o].dtype;
     }
     if (g.outputs.size() > 8) return fail("generated row schedule: more than 8 outputs");
+    // the tanh-form GELU is computed as one op
+    std::vector<int> idiom_of(n, -1);
+    std::vector<char> inside_idiom(n, 0);
+    const std::vector<GeluIdiom> idioms = find_gelu_idioms(g);
+    for (size_t q = 0; q < idioms.size(); ++q) {
+      bool plain = true;   // an interior value that is a group output keeps the ops spelled out
+      for (int v : idioms[q].interior) if (out_ord[v] >= 0) plain = false;
+      if (!plain) continue;
+      idiom_of[idioms[q].out] = (int)q;
+      for (int v : idioms[q].interior) inside_idiom[v] = 1;
+    }
     for (int i = 0; i < n; ++i) {
       const Node& x = g[i];
       const int k = x.kind;
       if (k == FS_PARAMETER || k == FS_CONSTANT || k == FS_BROADCAST || k == FS_OUTPUT) continue;
+      if (inside_idiom[i]) continue;
+      if (idiom_of[i] >= 0) {
+        const GeluIdiom& id = idioms[idiom_of[i]];
+        RNode r;
+        r.id = i; r.op = EW_OP_GELU_TANH; r.nop = 1;
+        r.cls = shape_is_full(x) ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
+        if (r.cls == CLS_NONE) return fail("generated row schedule: an op whose shape is neither the group's nor its row shape");
+        cls[i] = r.cls;
+        if (!operand(id.h, r.cls, &r.o[0])) return false;
+        gelu_constants(id, r.gelu);
+        r.out_ord = out_ord[i];
+        r.out_dtype = out_dtype[i];
+        nodes.push_back(r);
+        continue;
+      }
       if (k == FS_DOT) {
         RNode r;
         if (!dot_node(i, &r)) return false;
@@ -425,6 +453,7 @@ struct Gen {
     // a full value divided by a per-row value: one reciprocal per row, then multiplies
     if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
     if (n.op == FS_CAUSAL_MASK) return "(col[k] + j <= irow) ? " + a + " : " + const_text(n.o[1].cval);
+    if (n.op == EW_OP_GELU_TANH) return "gelu_tanh(" + a + ", " + const_text(n.gelu[0]) + ", " + const_text(n.gelu[1]) + ", " + const_text(n.gelu[2]) + ")";
     return op_text(n.op, a, b, fast);
   }
 
@@ -1080,6 +1109,7 @@ struct Stream {
     const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
     if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
     if (n.op == FS_CAUSAL_MASK) return "(col + j <= irow) ? " + a + " : " + const_text(n.o[1].cval);
+    if (n.op == EW_OP_GELU_TANH) return "gelu_tanh(" + a + ", " + const_text(n.gelu[0]) + ", " + const_text(n.gelu[1]) + ", " + const_text(n.gelu[2]) + ")";
     return op_text(n.op, a, b, fast);
   }
 
