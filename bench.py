@@ -43,7 +43,7 @@ def measured_traffic(name):
     return int(m.group(1)) if m else None
 
 ROTATE_BYTES = 640 * 2**20     # bytes touched between reuses of one buffer set
-SPIN_UP_S = 0.1                # untimed launches before every timing loop (see time_plan)
+SPIN_UP_S = 0.05               # seconds of untimed launches before every timing loop (see time_plan; --spin-up)
 
 TORCH_DT = None
 
@@ -203,6 +203,7 @@ def cpu_baseline(cfg):
 
 
 def main():
+    global SPIN_UP_S
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
@@ -210,7 +211,10 @@ def main():
     ap.add_argument("--only", default=None, help="time just this group as the headline (a config name)")
     ap.add_argument("--no-groups", action="store_true", help="skip the per-group table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--spin-up", type=float, default=SPIN_UP_S,
+                    help="seconds of untimed launches before each timing loop (0 for counter runs, which only need a few launches)")
     args = ap.parse_args()
+    SPIN_UP_S = max(0.0, args.spin_up)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one stitched kernel per fusion group; "
               "rows / batch elements would shard across GPUs without communication). "

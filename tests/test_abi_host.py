@@ -269,6 +269,30 @@ def test_per_row_arithmetic_without_a_reduction_is_a_row_group():
     assert e.value.status == binding.FS_ERR_UNSUPPORTED
 
 
+def _gelu_group(extra_output):
+    """tanh-form GELU of x + 1 on [64, 256]; optionally the tanh itself is a second output."""
+    from workloads.graphs import GELU_K0, GELU_K1
+    g = Graph()
+    x = g.parameter("x", "f32", (64, 256))
+    h = g.add(x, g.constant(1.0))
+    h3 = g.multiply(g.multiply(h, h), h)
+    t = g.tanh(g.multiply(g.add(h, g.multiply(h3, g.constant(GELU_K1))), g.constant(GELU_K0)))
+    # operands commuted against the usual spelling
+    g.output(g.multiply(g.add(g.constant(1.0), t), g.multiply(g.constant(0.5), h)), "y")
+    if extra_output:
+        g.output(t, "t")
+    return g.ops
+
+
+def test_gelu_idiom_is_generated_as_one_op():
+    with Plan(_gelu_group(False)) as p:
+        assert "x2 merged" in p.describe()          # the add and the GELU
+    with Plan(_gelu_group(True)) as p:              # an interior value leaves the group: ops stay spelled out
+        assert "x10 merged" in p.describe()
+    with Plan(BY_NAME["bias_gelu_residual_layernorm"].build("small")[0]) as p:
+        assert "elementwise x13" in p.describe()    # 21 with the GELU spelled out
+
+
 def test_generated_mode_and_prebuilt_mode_on_recognised_groups():
     ops, _ = BY_NAME["layernorm_fwd"].build("small")
     with Plan(ops) as p:

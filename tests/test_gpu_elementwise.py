@@ -164,3 +164,49 @@ def test_empty_elementwise_group():
     for mode in MODES:
         out = run_gpu(ops, inputs.adam_update((0, 16)), mode)
         assert all(o.size == 0 for o in out)
+
+
+def _gelu_variants(shape, dtype, spelling, constants=(0.5, None, None)):
+    """tanh-form GELU spelled with operands in different orders / associations, optionally with
+    an interior value as a second output or with other constants than the usual ones."""
+    from workloads.graphs import GELU_K0, GELU_K1, Graph
+    half, k0, k1 = constants[0], constants[1] or GELU_K0, constants[2] or GELU_K1
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    h = x if dtype == "f32" else g.convert(x, "f32")
+    if spelling == "usual":
+        h3 = g.multiply(g.multiply(h, h), h)
+        t = g.tanh(g.multiply(g.add(h, g.multiply(h3, g.constant(k1))), g.constant(k0)))
+        y = g.multiply(g.multiply(h, g.constant(half)), g.add(t, g.constant(1.0)))
+    elif spelling == "commuted":
+        h3 = g.multiply(h, g.multiply(h, h))
+        t = g.tanh(g.multiply(g.constant(k0), g.add(g.multiply(g.constant(k1), h3), h)))
+        y = g.multiply(g.add(g.constant(1.0), t), g.multiply(g.constant(half), h))
+    else:                                   # interior value is an output too: no idiom
+        h3 = g.multiply(g.multiply(h, h), h)
+        t = g.tanh(g.multiply(g.add(h, g.multiply(h3, g.constant(k1))), g.constant(k0)))
+        y = g.multiply(g.multiply(h, g.constant(half)), g.add(t, g.constant(1.0)))
+        g.output(t if dtype == "f32" else g.convert(t, dtype), "t")
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
+    return g.ops
+
+
+@pytest.mark.parametrize("spelling", ["usual", "commuted", "interior_output"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gelu_idiom_matches_the_spelled_out_ops(dtype, spelling):
+    shape = (37, 260)
+    ops = _gelu_variants(shape, dtype, spelling)
+    x = np.random.default_rng(5).normal(0.0, 3.0, shape)
+    x.flat[:8] = [0.0, -0.0, 40.0, -40.0, 1e4, -1e4, 1e-30, -3.0]      # saturated tanh on both sides, zero
+    ins = [inputs.round_to(x, dtype)]
+    announce(f"gelu idiom {dtype} {spelling}")
+    got, want = check_against_oracle(ops, ins, what=f"gelu {spelling}")
+    assert not np.isnan(np.asarray(got[-1], dtype=np.float64)).any()
+
+
+def test_gelu_idiom_with_other_constants():
+    shape = (5, 64)
+    ops = _gelu_variants(shape, "f32", "usual", constants=(1.0, 0.5, 0.1))
+    ins = [_rand(shape, 9, -3, 3)]
+    announce("gelu idiom, other constants")
+    check_against_oracle(ops, ins, what="gelu constants")
