@@ -2,14 +2,22 @@
 //   S = Q K^T  ->  scale  ->  (causal mask)  ->  row softmax  ->  P (16-bit)  ->  O = P V
 // as one kernel, one workgroup per batch element.  The two dots are the only dense
 // contractions of the group and run on MFMA (v_mfma_f32_16x16x32 f16/bf16, fp32
-// accumulate); everything between them is thread-composed on the accumulator registers,
-// the row max/sum are 16-lane DPP all-reduces, and P is handed from the first dot's
-// accumulator layout to the second dot's operand layout through LDS (the `S` attribute),
-// as is V (transposed on the way in) and O (so the final store is 16 bytes per lane).
+// accumulate); everything between them is thread-composed on the accumulator registers.
 //
-// Wavefront w owns query rows 16w..16w+15.  Operand fragments of Q and K are read from
-// global memory directly in MFMA layout (lane (c,g) = (l%16, l/16) holds 8 consecutive
-// k-values of row c starting at 8g: one 16-byte load).  With a causal mask of -inf,
+// Wavefront w owns query rows 16w..16w+15 and computes the scores TRANSPOSED: tile kt is
+// K_kt (16 keys x D) . Q^T, so lane (c,g) = (l%16, l/16) holds S[q0+c][16kt+4g+i], i < 4 - every
+// score a lane holds belongs to ONE query row.  The softmax is then a register reduction plus two
+// cross-row steps (lanes c, c+16, c+32, c+48), and the normalised probabilities already sit in the
+// second dot's B-operand layout: O^T = V^T . P^T contracts over keys, and the order of the keys
+// inside a 32-key step is free as long as both operands use the same one, so k-slot 8g+4h+i of
+// step kk is key 32kk+16h+4g+i - the scores of tiles 2kk and 2kk+1 that lane g holds.  P never
+// leaves the registers.  V is the only operand that goes through LDS (the `S` attribute):
+// transposed on the way in, keys stored in that slot order, read back as 16-byte A fragments.
+// O^T leaves the accumulators as four consecutive head-dim values per lane and tile; one row swap
+// between lane pairs makes that eight, so the final store is 16 bytes per lane.
+//
+// Operand fragments of Q and K are read from global memory directly in MFMA layout (8
+// consecutive k-values of row c starting at 8g: one 16-byte load).  With a causal mask of -inf,
 // key tiles right of the diagonal contribute exactly zero and are skipped.
 #include "dev_common.h"
 #include "launchers.h"
@@ -29,26 +37,33 @@ template <> struct Mfma<f16_t> {
   static __device__ __forceinline__ f32x4 run(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   }
-  static __device__ __forceinline__ uint16_t cvt(float f) { return (uint16_t)f32_to_f16(f); }
+  static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return pack2_f16(lo, hi); }
 };
 template <> struct Mfma<bf16_t> {
   static __device__ __forceinline__ f32x4 run(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   }
-  static __device__ __forceinline__ uint16_t cvt(float f) { return (uint16_t)f32_to_bf16(f); }
+  static __device__ __forceinline__ uint32_t pack(float lo, float hi) { return pack2_bf16(lo, hi); }
 };
+
+// the value of lanes c, c+16, c+32, c+48 combined, in all four
+template <class Op> __device__ __forceinline__ float rows_allreduce(float v) {
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  v = Op::apply(as_f32(r[0]), as_f32(r[1]));
+  u = __builtin_bit_cast(uint32_t, v);
+  r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return Op::apply(as_f32(r[0]), as_f32(r[1]));
+}
 
 // NT: 16-row tiles along the sequence (workgroup = NT wavefronts); D: head dim
 template <typename T, int NT, int D>
 __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) {
   constexpr int KS = D / 32;                 // k-steps of the first dot
   constexpr int NTP = NT < 2 ? 2 : NT;       // key tiles padded to whole 32-key steps
-  constexpr int SP = NTP * 16 + 8;           // padded row length of Vt and P (halves)
-  constexpr int DP = D + 8;                  // padded row length of the O staging tile
-  constexpr int WROW = SP > DP ? SP : DP;
+  constexpr int SP = NTP * 16 + 8;           // padded row length of Vt (halves)
   extern __shared__ uint16_t smem[];
-  uint16_t* vt = smem;                                   // [D][SP]   V transposed
-  uint16_t* pw = smem + D * SP + (threadIdx.x >> 6) * 16 * WROW;   // [16][WROW] per wavefront
+  uint16_t* vt = smem;                       // [D][SP]   V transposed, keys in k-slot order
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.x;
@@ -64,74 +79,105 @@ __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) 
   int tiles = (seq + 15) / 16;
   if (a.skip_masked_tiles && w + 1 < tiles) tiles = w + 1;
 
-  // ---- stage V transposed into LDS (all wavefronts), zero-filling keys >= seq ----------
+  // ---- every global load of the wavefront is issued before the first use: Q, all K tiles, then its
+  // share of V (for the LDS transpose).  Loads behind run-time conditions would each wait out a
+  // full memory latency in turn; rows beyond seq are clamped to the last row and masked later.
   constexpr int CH = D / 8;                  // 16-byte chunks per row
-  for (int ci = threadIdx.x; ci < NTP * 16 * CH; ci += 64 * NT) {
-    const int key = ci / CH, d0 = (ci % CH) * 8;
-    u32x4 t = {0u, 0u, 0u, 0u};
-    if (key < seq) t = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * D + d0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      vt[(d0 + 2 * j) * SP + key] = (uint16_t)(t[j] & 0xFFFFu);
-      vt[(d0 + 2 * j + 1) * SP + key] = (uint16_t)(t[j] >> 16);
-    }
-  }
-
-  f32x4 acc[NT];
-  if (active) {
-    // ---- first dot: S tile kt = Q(16 x D) . K_kt^T ---------------------------------------
-    u32x4 qf[KS];
+  constexpr int NV = NTP * 16 * CH / (64 * NT);
+  static_assert(NV * 64 * NT == NTP * 16 * CH, "V chunks divide evenly over the workgroup");
+  u32x4 qf[KS], kf[NT][KS], vreg[NV];
+  {
     const int qrow = min(q0 + c, seq - 1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[ks] = *reinterpret_cast<const u32x4*>(qb + (int64_t)qrow * D + ks * 32 + 8 * g);
 #pragma unroll
     for (int kt = 0; kt < NT; ++kt) {
-      acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (kt < tiles) {
-        const int krow = min(kt * 16 + c, seq - 1);
+      const int krow = min(kt * 16 + c, seq - 1);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const u32x4 kf = *reinterpret_cast<const u32x4*>(kb + (int64_t)krow * D + ks * 32 + 8 * g);
-          acc[kt] = Mfma<T>::run(qf[ks], kf, acc[kt]);
-        }
+      for (int ks = 0; ks < KS; ++ks) {
+        if (kt < tiles) kf[kt][ks] = *reinterpret_cast<const u32x4*>(kb + (int64_t)krow * D + ks * 32 + 8 * g);   // same for the whole wavefront
       }
     }
-    // ---- scale, mask, softmax on the accumulators: lane holds S[q0+4g+i][16kt+c] ----------
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int qi = q0 + 4 * g + i;
-      float mx = -INFINITY;
+    for (int i = 0; i < NV; ++i) {
+      const int ci = threadIdx.x + i * 64 * NT;
+      const int key = min(ci / CH, seq - 1), d0 = (ci % CH) * 8;
+      vreg[i] = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * D + d0);
+    }
+  }
+
+  u32x4 pb[NTP / 2];                         // P^T, the second dot's B fragments
+  if (active) {
+    // ---- first dot, transposed: tile kt = K_kt(16 x D) . Q^T -----------------------------
+    f32x4 acc[NT];
 #pragma unroll
-      for (int kt = 0; kt < NT; ++kt) {
-        const int key = kt * 16 + c;
+    for (int kt = 0; kt < NT; ++kt) {
+      acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (kt < tiles) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc[kt] = Mfma<T>::run(kf[kt][ks], qf[ks], acc[kt]);
+      }
+    }
+    // ---- scale, mask, softmax of query row q0+c: the lane holds S[q0+c][16kt+4g+i] ---------
+    const int qi = q0 + c;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NT; ++kt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = kt * 16 + 4 * g + i;
         float z = acc[kt][i] * a.scale;
         if (a.causal && key > qi) z = a.fill;
         if (key >= seq || kt >= tiles) z = -INFINITY;
         acc[kt][i] = z;
         mx = fmaxf(mx, z);
       }
-      mx = group_allreduce<MaxOp, 16>(mx);
-      float s = 0.f;
+    mx = rows_allreduce<MaxOp>(mx);
+    float sum = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < NT; ++kt) {
+    for (int kt = 0; kt < NT; ++kt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
         const float e = __expf(acc[kt][i] - mx);
         acc[kt][i] = e;
-        s += e;
+        sum += e;
       }
-      s = group_allreduce<SumOp, 16>(s);
-      const float inv = 1.f / s;
+    sum = rows_allreduce<SumOp>(sum);
+    const float inv = 1.f / sum;
+    // P rounded to the dot's dtype, packed in k-slot order: slots 4h+i of step kk <- tile 2kk+h
 #pragma unroll
-      for (int kt = 0; kt < NTP; ++kt) {
-        const float p = kt < NT ? acc[kt < NT ? kt : 0][i] * inv : 0.f;
-        pw[(4 * g + i) * WROW + kt * 16 + c] = Mfma<T>::cvt(p);   // P rounded to the dot's dtype
+    for (int kk = 0; kk < NTP / 2; ++kk)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int kt = 2 * kk + h;
+        float p[4] = {0.f, 0.f, 0.f, 0.f};
+        if (kt < NT) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) p[i] = acc[kt < NT ? kt : 0][i] * inv;
+        }
+        pb[kk][2 * h] = Mfma<T>::pack(p[0], p[1]);
+        pb[kk][2 * h + 1] = Mfma<T>::pack(p[2], p[3]);
       }
+  }
+  // ---- V transposed into LDS (all wavefronts), zero-filling keys >= seq; key 32kk+16h+4g+i of
+  // a 32-key step sits at slot 8g+4h+i ---------------------------------------------------
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int ci = threadIdx.x + i * 64 * NT;
+    const int key = ci / CH, d0 = (ci % CH) * 8;
+    const int slot = (key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3);
+    const u32x4 t = key < seq ? vreg[i] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      vt[(d0 + 2 * j) * SP + slot] = (uint16_t)(t[j] & 0xFFFFu);
+      vt[(d0 + 2 * j + 1) * SP + slot] = (uint16_t)(t[j] >> 16);
     }
   }
-  __syncthreads();   // Vt complete; P of this wavefront visible to all its lanes
+  __syncthreads();   // Vt complete
 
   if (active) {
-    // ---- second dot: O(16 x D) = P(16 x keys) . V -----------------------------------------
+    // ---- second dot, transposed: O^T(D x 16) = V^T(D x keys) . P^T ---------------------------
     f32x4 o[D / 16];
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -139,30 +185,25 @@ __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) 
 #pragma unroll
     for (int kk = 0; kk < NTP / 2; ++kk) {
       if (kk < ksteps) {
-        const u32x4 pa = *reinterpret_cast<const u32x4*>(pw + c * WROW + kk * 32 + 8 * g);
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
           const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + c) * SP + kk * 32 + 8 * g);
-          o[dt] = Mfma<T>::run(pa, vf, o[dt]);
+          o[dt] = Mfma<T>::run(vf, pb[kk], o[dt]);
         }
       }
     }
-    // ---- O through the wavefront's LDS tile so that each lane stores 16 bytes ---------------
-    // (every lane's reads of P above are complete before the tile is overwritten: LDS
-    // operations of one wavefront execute in order)
+    // ---- the lane holds O[q0+c][16dt+4g+i], i < 4: 8 bytes per tile.  Lanes g and g^1 trade
+    // one tile of a pair (dt, dt+1) so that each ends up with 8 consecutive values, 16 bytes: after
+    // the row swap lane g holds d = 32(dt/2) + 16(g&1) + 8(g>>1) .. +7 ------------------------
+    uint16_t* orow = ob + (int64_t)min(q0 + c, seq - 1) * D + 16 * (g & 1) + 8 * (g >> 1);
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pw[(4 * g + i) * WROW + dt * 16 + c] = Mfma<T>::cvt(o[dt][i]);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-    for (int ci = lane; ci < 16 * CH; ci += 64) {
-      const int r = ci / CH, d0 = (ci % CH) * 8;
-      if (q0 + r < seq)
-        *reinterpret_cast<u32x4*>(ob + (int64_t)(q0 + r) * D + d0) =
-            *reinterpret_cast<const u32x4*>(pw + r * WROW + d0);
+    for (int dp = 0; dp < D / 32; ++dp) {
+      const uint32_t a0 = Mfma<T>::pack(o[2 * dp][0], o[2 * dp][1]), a1 = Mfma<T>::pack(o[2 * dp][2], o[2 * dp][3]);
+      const uint32_t b0 = Mfma<T>::pack(o[2 * dp + 1][0], o[2 * dp + 1][1]), b1 = Mfma<T>::pack(o[2 * dp + 1][2], o[2 * dp + 1][3]);
+      // odd rows of the first operand trade places with even rows of the second
+      const auto r0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
+      const auto r1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
+      if (q0 + c < seq) *reinterpret_cast<u32x4*>(orow + dp * 32) = u32x4{r0[0], r1[0], r0[1], r1[1]};
     }
   }
 }
@@ -171,8 +212,8 @@ namespace {
 
 int64_t attn_lds_bytes(int NT, int D) {
   const int NTP = NT < 2 ? 2 : NT;
-  const int SP = NTP * 16 + 8, DP = D + 8, WROW = SP > DP ? SP : DP;
-  return 2 * ((int64_t)D * SP + (int64_t)NT * 16 * WROW);
+  const int SP = NTP * 16 + 8;
+  return 2 * (int64_t)D * SP;
 }
 
 template <typename T, int NT, int D>
@@ -235,7 +276,7 @@ bool attn_stitch_plan(const AttnSpec& sp, const LaunchOpts& opt, AttnLaunch* out
 std::string attn_stitch_describe(const AttnSpec& sp, const AttnLaunch& l) {
   char buf[512];
   snprintf(buf, sizeof buf,
-           "dot_1[GRID,WARP_16,CTA]; softmax[GRID,WARP_16,WARP]S; dot_2[GRID,WARP_16,CTA]S; "
+           "dot_1[GRID,WARP_16,CTA]; softmax[GRID,WARP_16,WARP]; dot_2[GRID,WARP_16,CTA]S; "
            "cta_num=%d, cta_size=%d, lds=%lld",
            l.grid, l.wg, (long long)l.lds_bytes);
   (void)sp;

@@ -127,8 +127,9 @@ def test_unsupported_groups_return_unsupported_not_crash():
 
 
 def test_lds_volume_constraint():
-    msg = _expect(binding.FS_ERR_LDS, graphs.causal_attention(2, 128, 128))
-    assert "LDS" in msg
+    # the largest attention group the schedule takes keeps V^T (128 x 136 halves) in LDS, inside the budget
+    with Plan(graphs.causal_attention(2, 128, 128)) as p:
+        assert p.info()["lds_bytes"] == 2 * 128 * 136
     # a row longer than the LDS row cache of the block-composed row form: without kernel
     # generation that is the end, with it the streamed template takes over
     msg = _expect(binding.FS_ERR_LDS, graphs.layernorm_fwd(4, 50000), mode="prebuilt")

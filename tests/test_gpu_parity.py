@@ -269,7 +269,7 @@ def test_layernorm_bwd_output_subsets(mode):
 # ---------------------------------------------------------------- attention
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("seq,dim", [(64, 64), (1, 32), (7, 64), (16, 32), (33, 64), (94, 64), (128, 32), (48, 128), (128, 64)])
+@pytest.mark.parametrize("seq,dim", [(64, 64), (1, 32), (7, 64), (16, 32), (33, 64), (94, 64), (128, 32), (48, 128), (128, 64), (128, 128), (100, 128), (17, 32)])
 def test_attention_shapes(seq, dim, dtype):
     announce(f"attention {dtype} seq={seq} dim={dim}")
     B = 5
