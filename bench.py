@@ -167,6 +167,15 @@ def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
     res.update(schedule=info["schedule"], template=template, stitched_us=ev_ms * 1e3, stitched_wall_us=wall_ms * 1e3,
                stitched_gbs=algo / (ev_ms * 1e-3) / 1e9, stitched_frac_of_peak=algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                lds_bytes=info["lds_bytes"], workspace_bytes=info["workspace_bytes"])
+    # the same group after the tuner (Algorithm 3's loop over templates) has timed the schedule's launch
+    # templates on one buffer set and kept the fastest
+    try:
+        with Plan.tune(ops, sets[0][0], sets[0][1], trials=30) as plan:
+            twall, tev = time_plan(plan, sets, steps, warmup)
+            res.update(tuned_us=tev * 1e3, tuned_frac_of_peak=algo / (tev * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       tuned_options={k: v for k, v in plan.tuned.items() if k != "us"}, tuned_template=plan.describe())
+    except Exception as e:   # the tuner is an extra: report, do not fail the bench
+        res.update(tuned_error=str(e))
     if with_per_op:
         psteps = max(5, steps // 10)
         with Plan(ops, "per_op") as plan:
