@@ -125,11 +125,11 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
         }
       }
       // a recognised group whose hand-written kernel does not take its size: the generated row kernel
+      std::string gen_err;
       auto fall_back_to_generated = [&]() {
         if (!lo.codegen) return false;
         int st2 = FS_OK;
-        std::string err2;
-        if (!fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) return false;
+        if (!fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &gen_err)) return false;
         p->match.kind = fs::MATCH_NONE;
         p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
         p->row_form = 3;
@@ -180,6 +180,7 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
           if (lo.codegen && fall_back_to_generated()) break;
           if (!fs::lnbwd_stitch_plan(p->match.lnbwd, lo, &p->lnbwd, &err)) {
             const bool bad_opt = err.find("wg_size") != std::string::npos;
+            if (!bad_opt && !gen_err.empty()) err += "; " + gen_err;
             delete p;
             return set_error(bad_opt ? FS_ERR_INVALID : FS_ERR_UNSUPPORTED, err);
           }

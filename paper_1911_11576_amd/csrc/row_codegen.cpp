@@ -552,10 +552,19 @@ struct Gen {
     // memory, so its full outputs are first laid out in LDS and then stored as one dense run
     // of 16-byte accesses (stores of separate row pieces straddle lines and measured 2x slower).
     if (A.n_col > 0) {
-      if (L > 64) { *err = "generated row schedule: column reductions with rows longer than one wavefront's registers"; return false; }
-      if ((int64_t)A.n_col * A.cols * 8 > 96 * 1024) { *err = "generated row schedule: column accumulators exceed the LDS"; return false; }
+      if (L > 64) {
+        // a team of wavefronts per row: every lane's columns are its own in the workgroup, so the
+        // running sums (two registers per column and reduction) stay few by spreading the row wider
+        while ((int64_t)K * W * A.n_col > 16 && L < 1024) { L *= 2; K = (int)((nvec + L - 1) / L); }
+        if ((int64_t)K * W * A.n_col > 16) { *err = "generated row schedule: column reductions over rows too long for their running sums to stay in registers"; return false; }
+        exact = (int64_t)K * L == nvec;
+      } else if ((int64_t)A.n_col * A.cols * 8 > 96 * 1024) {
+        *err = "generated row schedule: column accumulators exceed the LDS";
+        return false;
+      }
       persistent = true;
     }
+    if (L > 64) wg = L;                       // a team is one workgroup
     if (want_persistent && L <= 64) persistent = true;
     if (L <= 64 && !persistent) {
       int min_out = 4;
@@ -582,9 +591,9 @@ struct Gen {
       // one workgroup of T wavefronts per row; every reduction has its own exchange slots, so one
       // barrier per reduction is enough
       e.line("  constexpr int T = %d;", T);
-      e.line("  __shared__ float exch[%d][T];", A.n_reduce);
+      if (A.n_reduce > 0) e.line("  __shared__ float exch[%d][T];", A.n_reduce);
       e.line("  const int lane = threadIdx.x;");
-      e.line("  long long row = blockIdx.x;");
+      if (!persistent) e.line("  long long row = blockIdx.x;");
     } else {
       e.line("  const int lane = threadIdx.x & (L - 1);");
       if (!persistent) e.line("  long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / L;");
@@ -875,9 +884,21 @@ struct Gen {
     }
     if (persistent) {
       e.s += advance;
+      if (T > 1 && A.n_reduce > 0) e.line("  __syncthreads();                             // the exchange slots are written again in the next row");
       e.line("  }");
     }
-    if (persistent && A.n_col > 0) {
+    if (persistent && A.n_col > 0 && T > 1) {
+      // one row per workgroup at a time: no two lanes of the workgroup hold the same column
+      e.line("  double* ws = static_cast<double*>(a.ws);");
+      int ci = 0;
+      for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        e.line("  UNROLL for (int k = 0; k < K; ++k) {");
+        e.line("    if (!ok[k]) continue;");
+        e.line("    UNROLL for (int j = 0; j < W; ++j) ws[((long long)%d * gridDim.x + blockIdx.x) * %lldll + col[k] + j] = ca%d[k][j];", ci, (long long)A.cols, n.id);
+        e.line("  }");
+        ++ci;
+      }
+    } else if (persistent && A.n_col > 0) {
       e.line("  __shared__ double colacc[%d][%lld];", A.n_col, (long long)A.cols);
       e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
       e.line("  __syncthreads();");
@@ -1385,7 +1406,10 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     int64_t grid = (A.rows + rows_per_wg - 1) / rows_per_wg;
     if (gen.persistent) {
       // a fixed grid loops over the rows: one partial row per workgroup and column reduction
-      const int64_t want = opt.grid > 0 ? opt.grid : 256;
+      // (teams: as many workgroups as keep 2048 threads on every CU, but at least sixteen rows each, so
+      // that the partial rows stay small beside the rows themselves)
+      int64_t want = opt.grid > 0 ? opt.grid : l.L > 64 ? 256 * (2048 / l.L) / 2 : 256;
+      if (l.L > 64 && opt.grid <= 0 && want > (A.rows + 15) / 16) want = (A.rows + 15) / 16;
       if (want < grid) grid = want;
       l.persistent = true;
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
@@ -1393,7 +1417,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
         l.col_dtype[l.n_col] = n.out_dtype;
         ++l.n_col;
       }
-      l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
+      if (A.n_col > 0 && l.L <= 64) l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
       l.workspace_bytes = (int64_t)A.n_col * grid * A.cols * 8;
     }
     if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
@@ -1403,7 +1427,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     return true;
   }
   if (!want_stream && (opt.rows_per_wave || gerr.find("row longer") == std::string::npos)) { *err = gerr; return false; }
-  if (A.n_col > 0) { *err = "generated row schedule: column reductions with rows longer than one wavefront's registers"; return false; }
+  if (A.n_col > 0) { *err = "generated row schedule: column reductions over rows longer than the register templates hold"; return false; }
 
   // the row is streamed in passes by one workgroup
   Stream st(A);
@@ -1465,8 +1489,8 @@ std::string row_gen_describe(const RowGenLaunch& l) {
     return buf;
   }
   if (l.n_col > 0) {
-    snprintf(buf, sizeof buf, "reduce x%d[GRID,WARP] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,WARP-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %d partial rows, then a combine kernel); cta_num=%d, cta_size=%d, lds=%lld",
-             l.n_reduce, l.n_col, l.n_ops - l.n_reduce - l.n_col, l.K * l.W, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.grid, l.wg,
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,%s-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %d partial rows, then a combine kernel); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.L > 64 ? "CTA-S" : "WARP", l.n_col, l.n_ops - l.n_reduce - l.n_col, l.L > 64 ? "CTA" : "WARP", l.K * l.W, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.grid, l.wg,
              (long long)l.lds_bytes);
     return buf;
   }

@@ -120,7 +120,12 @@ def test_unsupported_groups_return_unsupported_not_crash():
     with Plan(graphs.layernorm_bwd(8, 2048)) as p:
         assert p.info()["schedule"] == "row_col" and "generated kernel" in p.describe()
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 2048), mode="prebuilt")
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 4096))
+    # rows beyond one wavefront's registers: a team of wavefronts per row, column sums still packed
+    with Plan(graphs.layernorm_bwd(64, 8192)) as p:
+        assert p.info()["schedule"] == "row_col" and "CTA-S" in p.describe() and "cta_size=1024" in p.describe()
+        assert p.info()["workspace_bytes"] == 2 * 4 * 8192 * 8          # 16 rows per workgroup: 4 partial rows
+    msg = _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 16384))
+    assert "column reductions" in msg
     # fp32 attention has no MFMA path
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 64, 64, "f32"))
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 256, 64))

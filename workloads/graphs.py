@@ -351,6 +351,29 @@ def _f32_in(g, dtype, *ts):
     return ts if dtype == "f32" else tuple(g.convert(t, "f32") for t in ts)
 
 
+def bias_gelu_bwd(rows, cols, dtype="f32"):
+    """Backward of y = gelu_tanh(x + bias): dx = dy * gelu'(h), dbias = column sums of dx.  An
+    elementwise chain packed with a reduction over the rows and no row reduction at all
+    (backward-phase packing, Section 5.1)."""
+    g = Graph()
+    dy = g.parameter("dy", dtype, (rows, cols))
+    x = g.parameter("x", dtype, (rows, cols))
+    b = g.parameter("bias", dtype, (cols,))
+    dyf, xf, bf = _f32_in(g, dtype, dy, x, b)
+    h = g.add(xf, g.col_broadcast(bf, xf))
+    h2 = g.multiply(h, h)
+    u = g.multiply(g.multiply(h, g.add(g.multiply(h2, g.constant(GELU_K1)), g.constant(1.0))), g.constant(GELU_K0))
+    t = g.tanh(u)
+    # d/dh [0.5 h (1 + t)] = 0.5 (1 + t) + 0.5 h (1 - t^2) k0 (1 + 3 k1 h^2)
+    du = g.multiply(g.add(g.multiply(h2, g.constant(3.0 * GELU_K1)), g.constant(1.0)), g.constant(GELU_K0))
+    dt = g.multiply(g.subtract(g.constant(1.0), g.multiply(t, t)), du)
+    dg = g.add(g.multiply(g.add(t, g.constant(1.0)), g.constant(0.5)), g.multiply(g.multiply(h, g.constant(0.5)), dt))
+    dx = g.multiply(dyf, dg)
+    g.output(dx if dtype == "f32" else g.convert(dx, dtype), "dx")
+    g.output(g.reduce_sum(dx, 0), "dbias")
+    return g.ops
+
+
 def gated_rows(shape, dtype="f32"):
     """Per-row arithmetic beside full arithmetic with no reduction: gate = tanh(rowv) * rowv + 1
     (computed once per row), y = x * gate + colv, and the gate itself as a second output."""
