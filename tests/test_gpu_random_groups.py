@@ -70,3 +70,25 @@ def test_per_row_arithmetic_without_a_reduction(shape, dtype):
     announce(f"gated rows {shape} {dtype}")
     check_against_oracle(ops, ins, what=f"gated rows {shape}")
     check_against_oracle(ops, ins, what=f"gated rows {shape} streamed", grid=5)
+
+
+POOL = [(37, 128), (5, 768), (3, 7, 64), (2, 3, 5, 32), (300, 8), (33, 100), (65, 30), (7, 770), (4, 4096), (129, 16),
+        (6, 40000), (50, 2), (9, 1), (3, 2, 2, 2), (17, 6000)]
+
+
+@pytest.mark.parametrize("seed", range(45))
+def test_random_groups_wide_pool(seed):
+    """More shapes (rows of 1 or 2 elements, rows for the streamed template, rows for wavefront
+    teams), all three dtypes, 3 to 24 ops, a column sum on every fourth rank-2 case."""
+    rng = random.Random(9000 + seed)
+    shape = POOL[seed % len(POOL)]
+    dtype = ["f32", "bf16", "f16"][seed % 3]
+    col = seed % 4 == 3 and len(shape) == 2
+    ops, pshapes = graphs.random_row_group(rng, shape, dtype, n_ops=rng.randint(3, 24), column_sums=col)
+    ins = inputs.normal_tensors(pshapes, dtype, seed_offset=300 + seed)
+    announce(f"random group (wide pool) seed {seed} shape {shape} {dtype} column sum {col}: {len(ops)} ops")
+    try:
+        check_against_oracle(ops, ins, what=f"random group {seed}")
+    except FsError as e:
+        # the one documented limit this pool reaches
+        assert e.status == binding.FS_ERR_UNSUPPORTED and "column reductions over rows longer" in e.message
