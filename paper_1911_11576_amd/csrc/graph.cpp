@@ -34,12 +34,6 @@ struct Fail {
   }
 };
 
-int operand_count(int kind) {
-  if (kind == FS_PARAMETER || kind == FS_CONSTANT) return 0;
-  if (is_binary(kind) || kind == FS_DOT) return 2;
-  return 1;
-}
-
 }  // namespace
 
 bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* err) {

@@ -40,6 +40,8 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
 
 inline bool is_binary(int k) { return k >= FS_ADD && k <= FS_MAXIMUM; }
 inline bool is_unary(int k) { return k >= FS_NEGATE && k <= FS_SQRT; }
+// how many entries of Node::operand an op of this kind reads
+inline int operand_count(int k) { return k == FS_PARAMETER || k == FS_CONSTANT ? 0 : (is_binary(k) || k == FS_DOT) ? 2 : 1; }
 const char* kind_name(int k);
 
 }  // namespace fs

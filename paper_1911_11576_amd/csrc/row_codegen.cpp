@@ -253,6 +253,30 @@ struct Analysis {
       out_dtype[s] = g[o].dtype;
     }
     if (g.outputs.size() > 8) return fail("generated row schedule: more than 8 outputs");
+    // A sum over the rows may be spelled as a chain of sums over the leading dim, one per
+    // leading dim of the group's shape ([B, S, H] -> [S, H] -> [H]): the last one stands for the
+    // whole chain, the ones before it (read by nothing else) compute nothing of their own.
+    std::vector<int> col_base(n, -1);
+    std::vector<char> col_mid(n, 0);
+    {
+      std::vector<int> n_users(n, 0);
+      for (int i = 0; i < n; ++i) for (int j = 0; j < operand_count(g[i].kind); ++j) ++n_users[g[i].operand[j]];
+      for (int i = 0; i < n; ++i) {
+        const Node& x = g[i];
+        if (x.kind != FS_REDUCE_SUM || x.axis != 0 || x.rank != 1 || rank < 2 || x.shape[0] != S[rank - 1]) continue;
+        int cur = x.operand[0], levels = 1;
+        std::vector<int> mids;
+        while (g[cur].kind == FS_REDUCE_SUM && g[cur].axis == 0 && n_users[cur] == 1 && out_ord[cur] < 0) {
+          mids.push_back(cur);
+          cur = g[cur].operand[0];
+          ++levels;
+        }
+        cur = canon(cur);
+        if (levels != rank - 1 || g[cur].rank != rank) continue;
+        col_base[i] = cur;
+        for (int m : mids) col_mid[m] = 1;
+      }
+    }
     // the tanh-form GELU is computed as one op
     std::vector<int> idiom_of(n, -1);
     std::vector<char> inside_idiom(n, 0);
@@ -268,7 +292,7 @@ struct Analysis {
       const Node& x = g[i];
       const int k = x.kind;
       if (k == FS_PARAMETER || k == FS_CONSTANT || k == FS_BROADCAST || k == FS_OUTPUT) continue;
-      if (inside_idiom[i]) continue;
+      if (inside_idiom[i] || col_mid[i]) continue;
       if (idiom_of[i] >= 0) {
         const GeluIdiom& id = idioms[idiom_of[i]];
         RNode r;
@@ -310,13 +334,13 @@ struct Analysis {
       if (!is_compute(i)) continue;       // widening convert: alias
       RNode r;
       r.id = i;
-      if (is_reduce(k) && rank == 2 && x.axis == 0 && x.rank == 1 && x.shape[0] == S[1]) {
+      if (col_base[i] >= 0) {
         // a reduction over the rows: packed with the row work over the same register-resident rows
         if (k != FS_REDUCE_SUM) return fail("generated row schedule: only sums are reduced over the rows");
         if (out_ord[i] < 0) return fail("generated row schedule: a column-reduced value must be a group output");
         r.cls = CLS_COL; r.op = k; r.nop = 1;
         cls[i] = CLS_COL;
-        if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
+        if (!operand(col_base[i], CLS_FULL, &r.o[0])) return false;
         ++n_col;
       } else if (is_reduce(k)) {
         if (x.axis != rank - 1 || !shape_is_row(x)) return fail("generated row schedule: reduction not over the last dim of the group's shape");

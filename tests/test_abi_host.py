@@ -299,6 +299,27 @@ def test_gelu_idiom_is_generated_as_one_op():
         assert "elementwise x13" in p.describe()    # 21 with the GELU spelled out
 
 
+def test_sum_over_all_leading_dims_is_one_column_reduction():
+    def bias_grad(partial_is_output):
+        g = Graph()
+        dy = g.parameter("dy", "f32", (4, 50, 256))
+        x = g.parameter("x", "f32", (4, 50, 256))
+        dx = g.multiply(dy, g.tanh(x))
+        g.output(dx, "dx")
+        part = g.reduce_sum(dx, 0)                   # [50, 256]
+        if partial_is_output:
+            g.output(part, "partial")
+        g.output(g.reduce_sum(part, 0), "dbias")     # [256]
+        return g.ops
+    with Plan(bias_grad(False)) as p:
+        info = p.info()
+        assert info["schedule"] == "row_col" and info["n_kernels"] == 2 and "column reduce x1" in p.describe()
+    # the sum over only the first dim is neither a per-row nor a per-column value
+    _expect(binding.FS_ERR_UNSUPPORTED, bias_grad(True))
+    with Plan(bias_grad(True), mode="per_op") as p:
+        assert p.info()["n_kernels"] >= 4
+
+
 def test_generated_mode_and_prebuilt_mode_on_recognised_groups():
     ops, _ = BY_NAME["layernorm_fwd"].build("small")
     with Plan(ops) as p:

@@ -49,11 +49,12 @@ def test_random_row_groups(seed):
             assert e.status == binding.FS_ERR_UNSUPPORTED      # rows too long for one wavefront's registers
 
 
-@pytest.mark.parametrize("seed", range(11))
+@pytest.mark.parametrize("seed", range(15))
 def test_random_groups_with_column_sums(seed):
     rng = random.Random(777 + seed)
+    # (rank above 2: the sum over the rows is a chain of sums over the leading dim)
     shape = [(37, 128), (300, 8), (33, 100), (517, 1024), (65, 30), (5, 2048), (1000, 64), (129, 16),
-             (40, 4096), (33, 3000), (9, 8192)][seed]
+             (40, 4096), (33, 3000), (9, 8192), (3, 7, 64), (2, 3, 5, 32), (2, 9, 4096), (4, 50, 100)][seed]
     ops, pshapes = graphs.random_row_group(rng, shape, "f32", n_ops=rng.randint(5, 12), column_sums=True)
     ins = inputs.normal_tensors(pshapes, "f32", seed_offset=200 + seed)
     announce(f"random group with column sum seed {seed} shape {shape}: {len(ops)} ops")

@@ -669,7 +669,10 @@ def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
     computed_rows = [r for r in rows if g.ops[r].kind not in ("parameter", "convert")]
     if computed_rows:
         g.output(computed_rows[-1])
-    if column_sums and len(shape) == 2:
-        g.output(g.reduce_sum(g.tanh(rng.choice(full)), 0))
+    if column_sums and len(shape) >= 2:
+        c = g.tanh(rng.choice(full))
+        for _ in range(len(shape) - 1):          # one sum per leading dim: [B, S, H] -> [S, H] -> [H]
+            c = g.reduce_sum(c, 0)
+        g.output(c)
     pshapes = [shape, shape] + ([rowshape] if rowshape else []) + [(ncol,)]
     return g.ops, pshapes
