@@ -72,6 +72,20 @@ def test_crossing_branches_after_cycle_repair():
             assert_close(a, b, TOLERANCE["f32"], f"crossing branches {kw}")
 
 
+@pytest.mark.parametrize("rows,cols", [(300, 1024), (33, 4096), (517, 96)])
+def test_encoder_tail_backward_is_one_group(rows, cols):
+    """LayerNorm backward, GELU backward and the three parameter gradients of a Transformer block's
+    tail: 38 per-op kernels; the planner makes one group of it, which runs as the row kernel
+    with three packed column sums plus the combine kernel."""
+    announce(f"fused program encoder tail backward {rows}x{cols}")
+    ops, ins = graphs.encoder_tail_bwd(rows, cols), inputs.encoder_tail_bwd(rows, cols)
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins)
+    assert n_groups == 1 and n_kernels == 2
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], "encoder tail backward")
+
+
 @pytest.mark.parametrize("name", ["layernorm_bwd", "multi_interest", "adam"])
 def test_single_group_graphs_through_the_planner(name):
     announce(f"fused program {name}")

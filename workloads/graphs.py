@@ -593,6 +593,44 @@ def encoder_tail(rows, cols, batch, seq, dtype="f32"):
     return g.ops
 
 
+def encoder_tail_bwd(rows, cols):
+    """Backward of y = LayerNorm(gelu_tanh(x + bias) + residual) from dy and what the forward pass
+    saved (r = the LayerNorm input, its per-row mean and rstd): dr (= the residual's gradient), dx,
+    and the three parameter gradients dgamma, dbeta, dbias -- two row reductions, three column
+    reductions and two full outputs over the same rows."""
+    g = Graph()
+    dy = g.parameter("dy", "f32", (rows, cols))
+    x = g.parameter("x", "f32", (rows, cols))
+    bias = g.parameter("bias", "f32", (cols,))
+    r = g.parameter("r", "f32", (rows, cols))
+    gamma = g.parameter("gamma", "f32", (cols,))
+    mean = g.parameter("mean", "f32", (rows,))
+    rstd = g.parameter("rstd", "f32", (rows,))
+    n = g.constant(cols)
+    rstd_b = g.row_broadcast(rstd, r)
+    xhat = g.multiply(g.subtract(r, g.row_broadcast(mean, r)), rstd_b)
+    gg = g.multiply(dy, g.col_broadcast(gamma, dy))
+    dbeta = g.reduce_sum(dy, 0)
+    dgamma = g.reduce_sum(g.multiply(dy, xhat), 0)
+    c1 = g.divide(g.reduce_sum(gg, -1), n)
+    c2 = g.divide(g.reduce_sum(g.multiply(gg, xhat), -1), n)
+    dr = g.multiply(g.subtract(g.subtract(gg, g.row_broadcast(c1, gg)), g.multiply(xhat, g.row_broadcast(c2, gg))), rstd_b)
+    h = g.add(x, g.col_broadcast(bias, x))
+    h2 = g.multiply(h, h)
+    u = g.multiply(g.multiply(h, g.add(g.multiply(h2, g.constant(GELU_K1)), g.constant(1.0))), g.constant(GELU_K0))
+    t = g.tanh(u)
+    du = g.multiply(g.add(g.multiply(h2, g.constant(3.0 * GELU_K1)), g.constant(1.0)), g.constant(GELU_K0))
+    dt = g.multiply(g.subtract(g.constant(1.0), g.multiply(t, t)), du)
+    dg = g.add(g.multiply(g.add(t, g.constant(1.0)), g.constant(0.5)), g.multiply(g.multiply(h, g.constant(0.5)), dt))
+    dx = g.multiply(dr, dg)
+    g.output(dr, "dr")
+    g.output(dx, "dx")
+    g.output(dgamma, "dgamma")
+    g.output(dbeta, "dbeta")
+    g.output(g.reduce_sum(dx, 0), "dbias")
+    return g.ops
+
+
 def crossing_branches(rows, cols):
     """Two chains that feed each other, so that fusing each chain on its own would make the
     contracted graph cyclic (the situation of the paper's cyclic-dependence figure, Section 4.1):

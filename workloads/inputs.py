@@ -127,3 +127,18 @@ def multi_interest_pattern(batch, m=94, n=94, k=1, p_pad=0.1, seed_offset=8):
     v = r.normal(0.0, 1.0, (batch, n, 1))
     gate = r.uniform(0.0, 1.0, (batch, m, 1))
     return [round_to(t, "f32") for t in (x, y, mask, v, gate)]
+
+
+def encoder_tail_bwd(rows, cols):
+    """dy, x ~ N(0,1); bias ~ N(0,0.02); r ~ N(0,1) (stands for the saved LayerNorm input);
+    gamma = 1 + N(0,0.02); mean and rstd of r as a forward pass would have saved them."""
+    rng = _rng(40)
+    dy = rng.standard_normal((rows, cols))
+    x = rng.standard_normal((rows, cols))
+    bias = 0.02 * rng.standard_normal(cols)
+    r = round_to(rng.standard_normal((rows, cols)), "f32")
+    gamma = 1.0 + 0.02 * rng.standard_normal(cols)
+    r64 = r
+    mean = r64.mean(axis=-1) if rows else np.zeros(0)
+    rstd = 1.0 / np.sqrt(r64.var(axis=-1) + 1e-5) if rows else np.zeros(0)
+    return [round_to(t, "f32") for t in (dy, x, bias)] + [r] + [round_to(t, "f32") for t in (gamma, mean, rstd)]
