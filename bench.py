@@ -43,6 +43,7 @@ def measured_traffic(name):
     return int(m.group(1)) if m else None
 
 ROTATE_BYTES = 640 * 2**20     # bytes touched between reuses of one buffer set
+TUNE = True                    # also time every group after fs_plan_tune (--no-tune)
 SPIN_UP_S = 0.05               # seconds of untimed launches before every timing loop (see time_plan; --spin-up)
 
 TORCH_DT = None
@@ -170,6 +171,8 @@ def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
     # the same group after the tuner (Algorithm 3's loop over templates) has timed the schedule's launch
     # templates on one buffer set and kept the fastest
     try:
+        if not TUNE:
+            raise RuntimeError("skipped (--no-tune)")
         with Plan.tune(ops, sets[0][0], sets[0][1], trials=30) as plan:
             twall, tev = time_plan(plan, sets, steps, warmup)
             res.update(tuned_us=tev * 1e3, tuned_frac_of_peak=algo / (tev * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -212,7 +215,7 @@ def cpu_baseline(cfg):
 
 
 def main():
-    global SPIN_UP_S
+    global SPIN_UP_S, TUNE
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
@@ -222,8 +225,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--spin-up", type=float, default=SPIN_UP_S,
                     help="seconds of untimed launches before each timing loop (0 for counter runs, which only need a few launches)")
+    ap.add_argument("--no-tune", action="store_true", help="skip the timing of each group after the tuner (counter runs)")
     args = ap.parse_args()
     SPIN_UP_S = max(0.0, args.spin_up)
+    TUNE = not args.no_tune
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one stitched kernel per fusion group; "
               "rows / batch elements would shard across GPUs without communication). "
