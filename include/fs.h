@@ -173,6 +173,26 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops,
                        void* const* outputs, int32_t n_out, void* hip_stream,
                        int32_t trials, fs_plan** out, fs_plan_options* best, double* best_us);
 
+/* Tuning cache ("optimize once, reuse", Section 1): fs_plan_tune records the winning options
+ * under a key of the group (every field of every op: kinds, dtypes, shapes, wiring, constants),
+ * per process.  fs_plan_create with opt == NULL, or with FS_MODE_STITCHED and all launch
+ * parameters 0, uses the recorded options of a group it finds there (and falls back to its own
+ * defaults if they no longer build).  Explicit options, and the other modes, never look.
+ * The cache can be written to and merged from a text file, so that one tuning run serves
+ * later processes: one line per group, "key(hex) mode wg_size rows_per_wave grid microseconds"
+ * after a header line.  All of it is host work and thread-safe.
+ *   fs_group_key         key of a group (host out-pointer); FS_ERR_INVALID on a NULL or empty list
+ *   fs_tune_cache_size   number of recorded groups
+ *   fs_tune_cache_clear  forget them all
+ *   fs_tune_cache_save   write the file (overwrites); FS_ERR_INVALID if it cannot be written
+ *   fs_tune_cache_load   merge a file, later entries winning; FS_ERR_INVALID if it cannot be
+ *                        read or a line is malformed (nothing is merged then) */
+fs_status fs_group_key(const fs_op_desc* ops, int32_t n_ops, uint64_t* key);
+int32_t fs_tune_cache_size(void);
+fs_status fs_tune_cache_clear(void);
+fs_status fs_tune_cache_save(const char* path);
+fs_status fs_tune_cache_load(const char* path);
+
 /* Release the plan and its workspace.  NULL is a no-op.  The caller makes sure no
  * launch of the plan is still running. */
 fs_status fs_destroy(fs_plan* plan);

@@ -82,6 +82,16 @@ def lib():
         L.fs_plan_tune.restype = i32
         L.fs_stream_copy.argtypes = [vp, vp, i64, vp]
         L.fs_stream_copy.restype = i32
+        L.fs_group_key.argtypes = [C.POINTER(fs_op_desc), i32, C.POINTER(C.c_uint64)]
+        L.fs_group_key.restype = i32
+        L.fs_tune_cache_size.argtypes = []
+        L.fs_tune_cache_size.restype = i32
+        L.fs_tune_cache_clear.argtypes = []
+        L.fs_tune_cache_clear.restype = i32
+        L.fs_tune_cache_save.argtypes = [C.c_char_p]
+        L.fs_tune_cache_save.restype = i32
+        L.fs_tune_cache_load.argtypes = [C.c_char_p]
+        L.fs_tune_cache_load.restype = i32
         L.fs_shared_plan.argtypes = [C.POINTER(i32), C.POINTER(i64), C.POINTER(C.c_uint8), i32, C.POINTER(i64),
                                      C.POINTER(i32), C.POINTER(i64)]
         L.fs_shared_plan.restype = i32
@@ -200,6 +210,30 @@ def fs_shared_plan(operands, req_bytes, is_output=None):
     total = C.c_int64(0)
     _check(lib().fs_shared_plan(ops, req, outs, n, off, shr, C.byref(total)))
     return list(off[:n]), list(shr[:n]), total.value
+
+
+def fs_group_key(ops):
+    """Key of a group in the tuning cache (an int)."""
+    arr = ops if isinstance(ops, C.Array) else marshal_ops(ops)
+    key = C.c_uint64()
+    _check(lib().fs_group_key(arr, len(arr), C.byref(key)))
+    return key.value
+
+
+def fs_tune_cache_size():
+    return lib().fs_tune_cache_size()
+
+
+def fs_tune_cache_clear():
+    _check(lib().fs_tune_cache_clear())
+
+
+def fs_tune_cache_save(path):
+    _check(lib().fs_tune_cache_save(str(path).encode()))
+
+
+def fs_tune_cache_load(path):
+    _check(lib().fs_tune_cache_load(str(path).encode()))
 
 
 def fs_stream_copy(dst, src, nbytes, stream=None):

@@ -3,6 +3,8 @@
 
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <set>
 #include <string>
@@ -51,6 +53,31 @@ fs_status set_error(fs_status st, const std::string& msg) {
   return st;
 }
 
+// ---- tuning cache: winning options of fs_plan_tune per group key
+struct TuneEntry { fs_plan_options opt; double us; };
+std::mutex g_tune_mu;
+std::map<uint64_t, TuneEntry> g_tune;
+thread_local bool g_tuning = false;     // the tuner's own plans are built from the options it passes
+
+uint64_t group_key(const fs_op_desc* ops, int32_t n_ops) {
+  uint64_t h = 1469598103934665603ull;
+  auto mix = [&](uint64_t v) { for (int b = 0; b < 8; ++b) { h ^= (v >> (8 * b)) & 0xffu; h *= 1099511628211ull; } };
+  mix((uint64_t)n_ops);
+  for (int i = 0; i < n_ops; ++i) {
+    const fs_op_desc& d = ops[i];
+    mix((uint64_t)(uint32_t)d.kind); mix((uint64_t)(uint32_t)d.dtype); mix((uint64_t)(uint32_t)d.rank); mix((uint64_t)(uint32_t)d.axis);
+    const int r = d.rank < 0 ? 0 : d.rank > FS_MAX_RANK ? FS_MAX_RANK : d.rank;
+    for (int k = 0; k < r; ++k) mix((uint64_t)d.shape[k]);
+    for (int k = 0; k < 3; ++k) mix((uint64_t)(uint32_t)d.operand[k]);
+    uint64_t a;
+    memcpy(&a, &d.attr, 8);
+    mix(a);
+  }
+  return h;
+}
+
+fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_options* opt, fs_plan** out);
+
 }  // namespace
 
 extern "C" {
@@ -58,6 +85,94 @@ extern "C" {
 const char* fs_last_error(void) { return g_error.c_str(); }
 
 fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_options* opt, fs_plan** out) {
+  if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
+  const bool defaults = !opt || (opt->mode == FS_MODE_STITCHED && opt->wg_size == 0 && opt->rows_per_wave == 0 && opt->grid == 0);
+  if (defaults && !g_tuning && ops && n_ops >= 1 && n_ops <= 4096) {
+    TuneEntry e;
+    bool hit = false;
+    {
+      std::lock_guard<std::mutex> lock(g_tune_mu);
+      if (!g_tune.empty()) {
+        const auto it = g_tune.find(group_key(ops, n_ops));
+        if (it != g_tune.end()) { e = it->second; hit = true; }
+      }
+    }
+    // recorded options that no longer build (another library version wrote the file): the defaults
+    if (hit && plan_create_impl(ops, n_ops, &e.opt, out) == FS_OK) return FS_OK;
+  }
+  return plan_create_impl(ops, n_ops, opt, out);
+}
+
+fs_status fs_group_key(const fs_op_desc* ops, int32_t n_ops, uint64_t* key) {
+  if (!ops || !key || n_ops < 1 || n_ops > 4096) return set_error(FS_ERR_INVALID, "fs_group_key: NULL argument or n_ops out of range [1,4096]");
+  *key = group_key(ops, n_ops);
+  return FS_OK;
+}
+
+int32_t fs_tune_cache_size(void) {
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  return (int32_t)g_tune.size();
+}
+
+fs_status fs_tune_cache_clear(void) {
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  g_tune.clear();
+  return FS_OK;
+}
+
+fs_status fs_tune_cache_save(const char* path) {
+  if (!path) return set_error(FS_ERR_INVALID, "fs_tune_cache_save: path is NULL");
+  FILE* f = fopen(path, "w");
+  if (!f) return set_error(FS_ERR_INVALID, std::string("fs_tune_cache_save: cannot write ") + path);
+  fprintf(f, "fs-tune-cache 1\n");
+  {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    for (const auto& kv : g_tune)
+      fprintf(f, "%016llx %d %d %d %d %.3f\n", (unsigned long long)kv.first, kv.second.opt.mode, kv.second.opt.wg_size,
+              kv.second.opt.rows_per_wave, kv.second.opt.grid, kv.second.us);
+  }
+  if (fclose(f) != 0) return set_error(FS_ERR_INVALID, std::string("fs_tune_cache_save: write failed on ") + path);
+  return FS_OK;
+}
+
+fs_status fs_tune_cache_load(const char* path) {
+  if (!path) return set_error(FS_ERR_INVALID, "fs_tune_cache_load: path is NULL");
+  FILE* f = fopen(path, "r");
+  if (!f) return set_error(FS_ERR_INVALID, std::string("fs_tune_cache_load: cannot read ") + path);
+  std::map<uint64_t, TuneEntry> read;
+  char line[256];
+  bool ok = fgets(line, sizeof line, f) && strncmp(line, "fs-tune-cache 1", 15) == 0;
+  int lineno = 1;
+  while (ok && fgets(line, sizeof line, f)) {
+    ++lineno;
+    if (line[0] == '\n' || line[0] == '\0') continue;
+    unsigned long long key = 0;
+    TuneEntry e{};
+    int used = 0;
+    if (sscanf(line, "%llx %d %d %d %d %lf %n", &key, &e.opt.mode, &e.opt.wg_size, &e.opt.rows_per_wave, &e.opt.grid, &e.us, &used) != 6 ||
+        line[used] != '\0' || e.opt.mode < 0 || e.opt.mode > FS_MODE_STITCHED_GENERATED || e.opt.mode == FS_MODE_PER_OP ||
+        e.opt.wg_size < 0 || e.opt.rows_per_wave < 0 || e.opt.grid < 0 || !(e.us >= 0.0)) {
+      ok = false;
+      break;
+    }
+    read[(uint64_t)key] = e;
+  }
+  fclose(f);
+  if (!ok) {
+    char buf[96];
+    snprintf(buf, sizeof buf, ": malformed line %d", lineno);
+    return set_error(FS_ERR_INVALID, std::string("fs_tune_cache_load: ") + path + buf);
+  }
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  for (const auto& kv : read) g_tune[kv.first] = kv.second;
+  return FS_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_options* opt, fs_plan** out) {
   if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
   *out = nullptr;
   fs_plan* p = new (std::nothrow) fs_plan;
@@ -214,6 +329,10 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
   return FS_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
 fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* const* outputs, int32_t n_out,
                     void* hip_stream) {
   if (!p) return set_error(FS_ERR_INVALID, "plan is NULL");
@@ -276,6 +395,7 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
   *out = nullptr;
   if (trials < 1 || trials > 1000) return set_error(FS_ERR_INVALID, "trials out of range [1,1000]");
   // the default template first: it decides the schedule, and it is the fallback
+  struct Tuning { Tuning() { g_tuning = true; } ~Tuning() { g_tuning = false; } } tuning_scope;
   fs_plan* base = nullptr;
   fs_status st = fs_plan_create(ops, n_ops, nullptr, &base);
   if (st != FS_OK) return st;
@@ -369,6 +489,10 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
   *out = best_plan;
   if (best) *best = best_opt;
   if (best_us) *best_us = best_t;
+  {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    g_tune[group_key(ops, n_ops)] = TuneEntry{best_opt, best_t};
+  }
   return FS_OK;
 }
 

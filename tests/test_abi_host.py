@@ -357,3 +357,57 @@ def test_motivating_pattern_plans_as_one_kernel():
     with Plan(ops, "per_op") as q:
         assert q.info()["n_kernels"] == 13
         assert q.info()["moved_bytes"] > 6 * info["algorithmic_bytes"]
+
+
+def test_tuning_cache_on_the_host(tmp_path):
+    """The cache that fs_plan_tune fills: keys, file round trip, and its use by fs_plan_create
+    when the caller leaves the launch parameters open."""
+    from paper_1911_11576_amd import (fs_group_key, fs_tune_cache_clear, fs_tune_cache_load, fs_tune_cache_save,
+                                      fs_tune_cache_size)
+    fs_tune_cache_clear()
+    ops = graphs.log_softmax((300, 768))
+    key = fs_group_key(ops)
+    assert key == fs_group_key(graphs.log_softmax((300, 768)))              # a function of the group alone
+    assert key != fs_group_key(graphs.log_softmax((301, 768))) and key != fs_group_key(graphs.log_softmax((300, 768), "bf16"))
+    with Plan(ops) as p:
+        default = p.describe()
+    with Plan(ops, rows_per_wave=2) as p:
+        wide = p.describe()
+    assert wide != default
+    f = tmp_path / "tune.txt"
+    f.write_text("fs-tune-cache 1\n%016x 0 0 2 0 12.500\n" % key)
+    fs_tune_cache_load(f)
+    assert fs_tune_cache_size() == 1
+    with Plan(ops) as p:                                                    # launch parameters left open: the recorded ones
+        assert p.describe() == wide
+    with Plan(ops, rows_per_wave=1) as p:                                   # explicit options never look
+        assert p.describe() == default
+    with Plan(graphs.log_softmax((301, 768))) as p:                         # another group
+        assert "THREAD_12" in p.describe()
+    # round trip through a file
+    g = tmp_path / "again.txt"
+    fs_tune_cache_save(g)
+    fs_tune_cache_clear()
+    assert fs_tune_cache_size() == 0
+    with Plan(ops) as p:
+        assert p.describe() == default
+    fs_tune_cache_load(g)
+    assert fs_tune_cache_size() == 1 and g.read_text() == f.read_text()
+    # recorded options that do not build (written by something else): the defaults, silently
+    f.write_text("fs-tune-cache 1\n%016x 0 100 0 0 1.000\n" % key)
+    fs_tune_cache_load(f)
+    with Plan(ops) as p:
+        assert p.describe() == default
+    # malformed files merge nothing
+    for text in ("", "something else\n", "fs-tune-cache 1\nzz 0 0 0 0 1\n", "fs-tune-cache 1\n%016x 1 0 0 0 1.0\n" % key,
+                 "fs-tune-cache 1\n%016x 0 0 2 0\n" % key, "fs-tune-cache 1\n%016x 0 -1 2 0 1.0\n" % key):
+        f.write_text(text)
+        with pytest.raises(FsError) as e:
+            fs_tune_cache_load(f)
+        assert e.value.status == binding.FS_ERR_INVALID and "fs_tune_cache_load" in e.value.message
+    with pytest.raises(FsError):
+        fs_tune_cache_load(tmp_path / "missing.txt")
+    with pytest.raises(FsError):
+        fs_tune_cache_save(tmp_path / "no_such_dir" / "x.txt")
+    assert fs_tune_cache_size() == 1
+    fs_tune_cache_clear()

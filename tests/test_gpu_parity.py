@@ -394,6 +394,30 @@ def test_plan_tune_returns_a_correct_plan(cfg):
         plan.close()
 
 
+def test_tuned_options_are_reused_by_later_plans(tmp_path):
+    """'Optimize once, reuse': the winner of fs_plan_tune is what fs_plan_create builds for the same
+    group from then on (launch parameters left open), also after a trip through the cache file."""
+    from paper_1911_11576_amd import fs_tune_cache_clear, fs_tune_cache_load, fs_tune_cache_save, fs_tune_cache_size
+    announce("tuning cache")
+    ops, ins = graphs.rmsnorm((2048, 1024), "bf16"), inputs.normal_tensors([(2048, 1024), (1024,)], "bf16")
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    assert fs_tune_cache_size() == 0
+    with Plan.tune(ops, dev_in, dev_out, trials=5) as tuned:
+        winner = tuned.describe()
+    assert fs_tune_cache_size() == 1
+    with Plan(ops) as p:
+        assert p.describe() == winner
+    check_against_oracle(ops, ins, what="plan from the tuning cache")
+    fs_tune_cache_save(tmp_path / "t.txt")
+    fs_tune_cache_clear()
+    fs_tune_cache_load(tmp_path / "t.txt")
+    with Plan(ops) as p:
+        assert p.describe() == winner
+    # another shape of the same group is another entry
+    with Plan(graphs.rmsnorm((2047, 1024), "bf16")) as p:
+        assert "THREAD_16" in p.describe()
+
+
 def test_plan_tune_rejects_unsupported_groups_and_bad_arguments():
     announce("tune errors")
     g = graphs.Graph()
