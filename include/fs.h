@@ -250,7 +250,7 @@ typedef struct fs_fusion fs_fusion; /* opaque, owned by the library */
 
 typedef struct {
   double launch_us;        /* phi, the launch latency of one kernel; <= 0: 2.5 */
-  int32_t max_patterns;    /* patterns handed to the solver, best scores first; 1..64, 0: 64 */
+  int32_t max_patterns;    /* patterns per conflict component handed to the solver, best scores first; 1..256, 0: 256 */
   int32_t explore_budget;  /* patterns the exploratory search may visit; 0: 400; < 0: none */
   int64_t seed_bytes;      /* exploratory seeds: ops whose result has at least this many bytes; 0: 1 MiB */
   const int64_t* bw_bytes; /* M(V) model: n_bw points (bytes moved, GB/s achieved), increasing */

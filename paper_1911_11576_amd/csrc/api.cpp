@@ -567,7 +567,7 @@ fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion
         for (int o : pat) if (o < 0 || o >= n_ops) return set_error(FS_ERR_INVALID, "extra patterns: op index out of range");
         cfg.extra_patterns.push_back(pat);
       }
-      if (opt->max_patterns < 0 || opt->max_patterns > 64) return set_error(FS_ERR_INVALID, "max_patterns out of range [0,64]");
+      if (opt->max_patterns < 0 || opt->max_patterns > 256) return set_error(FS_ERR_INVALID, "max_patterns out of range [0,256]");
       if (opt->n_bw < 0 || (opt->n_bw > 0 && (!opt->bw_bytes || !opt->bw_gbs))) return set_error(FS_ERR_INVALID, "bandwidth model: NULL table");
       if (opt->launch_us > 0) cfg.launch_us = opt->launch_us;
       if (opt->max_patterns > 0) cfg.max_patterns = opt->max_patterns;

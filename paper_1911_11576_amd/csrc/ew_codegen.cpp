@@ -41,7 +41,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-struct Args { const void* in[24]; void* out[8]; void* ws; };
+struct Args { const void* in[64]; void* out[16]; void* ws; };
 #define UNROLL _Pragma("unroll")
 static __device__ __forceinline__ float bits_f32(unsigned u) { return __builtin_bit_cast(float, u); }
 static __device__ __forceinline__ unsigned f32_bits(float f) { return __builtin_bit_cast(unsigned, f); }
@@ -127,9 +127,9 @@ std::string op_text(const EwIrNode& n, bool fast) {
 
 const char* ew_preamble() { return kPreamble; }
 
-std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name) {
-  // Chunk width: as many consecutive elements as one 16-byte access of the narrowest tensor
-  // holds, provided every row start stays aligned; otherwise one element.
+// Chunk width of a group: as many consecutive elements as one 16-byte access of the narrowest
+// tensor holds, provided every row start stays aligned; otherwise one element.
+static int chunk_width(const EwIr& ir) {
   const int64_t last = ir.shape[FS_MAX_RANK - 1];
   bool any32 = false;
   for (const EwIrView& v : ir.views) if (v.full && v.dtype == FS_F32) any32 = true;
@@ -144,11 +144,15 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
     }
     return true;
   };
-  int W = 1;
-  if (!any32 && fits(8)) W = 8;
-  else if (fits(4)) W = 4;
-  *width = W;
-  *unroll = 1;
+  if (!any32 && fits(8)) return 8;
+  if (fits(4)) return 4;
+  return 1;
+}
+
+// The loop of one group over its chunks.  `blk` / `nblk` are the expressions for this group's
+// workgroup index and workgroup count (the whole grid, or its share of a packed launch);
+// `view_base` is where its operand views start in Args::in.
+static void emit_part(Emitter& e, const EwIr& ir, int W, const std::string& blk, const std::string& nblk, int view_base) {
   bool need_idx = false;
   for (const EwIrView& v : ir.views) if (!v.full) need_idx = true;
   for (const EwIrNode& n : ir.nodes) if (n.op == FS_CAUSAL_MASK) need_idx = true;
@@ -158,12 +162,9 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
   for (const EwIrView& v : ir.views) if (v.dtype != FS_F32) fast = true;
   for (const EwIrNode& n : ir.nodes) if (n.out_ordinal >= 0 && n.out_dtype != FS_F32) fast = true;
 
-  Emitter e;
-  e.s = kPreamble;
-  e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_EW_NAME(const Args a) {");
   e.line("  constexpr int W = %d;", W);
   e.line("  const long long nchunk = %lldll;", (long long)(ir.n / W));
-  e.line("  for (long long ci = (long long)blockIdx.x * blockDim.x + threadIdx.x; ci < nchunk; ci += (long long)gridDim.x * blockDim.x) {");
+  e.line("  for (long long ci = %s * blockDim.x + threadIdx.x; ci < nchunk; ci += %s * blockDim.x) {", blk.c_str(), nblk.c_str());
   e.line("    const long long e0 = ci * W;");
   if (need_idx) {
     // coordinates of the chunk's first element (the chunk never crosses a row: W divides the last extent)
@@ -194,7 +195,7 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
       splat = v.stride[FS_MAX_RANK - 1] == 0;
     }
     e.line("    {");
-    e.line("      const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s);", ty, ty, k, off.c_str());
+    e.line("      const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s);", ty, ty, view_base + k, off.c_str());
     // operands of the group's own shape stream through once; broadcast operands are re-read by
     // many threads and stay cached
     const char* ld = v.full ? "__builtin_nontemporal_load" : "*";
@@ -242,8 +243,10 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
     e.line("    }");
   }
   e.line("  }");
-  e.line("}");
-  // the kernel is named after its own text, so that traces tell generated kernels apart
+}
+
+// the kernel is named after its own text, so that traces tell generated kernels apart
+static std::string name_kernel(Emitter& e, std::string* kernel_name) {
   uint64_t h = 1469598103934665603ull;
   for (unsigned char c : e.s) { h ^= c; h *= 1099511628211ull; }
   char name[32];
@@ -253,6 +256,50 @@ std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string*
   const size_t at = e.s.find(tag);
   e.s.replace(at, tag.size(), name);
   return e.s;
+}
+
+std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name) {
+  const int W = chunk_width(ir);
+  *width = W;
+  *unroll = 1;
+  Emitter e;
+  e.s = kPreamble;
+  e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_EW_NAME(const Args a) {");
+  emit_part(e, ir, W, "(long long)blockIdx.x", "(long long)gridDim.x", 0);
+  e.line("}");
+  return name_kernel(e, kernel_name);
+}
+
+std::string ew_emit_packed(const std::vector<const EwIr*>& parts, int wg, std::vector<int>* widths, std::vector<int>* blocks,
+                           std::string* kernel_name) {
+  Emitter e;
+  e.s = kPreamble;
+  e.line("// %zu independent groups packed into one launch: each owns a run of consecutive workgroups", parts.size());
+  e.line("extern \"C\" __global__ __launch_bounds__(256) void FS_EW_NAME(const Args a) {");
+  int first = 0, view_base = 0;
+  widths->clear();
+  blocks->clear();
+  for (size_t q = 0; q < parts.size(); ++q) {
+    const EwIr& ir = *parts[q];
+    const int W = chunk_width(ir);
+    const int64_t chunks = ir.n / W;
+    int64_t nb = (chunks + wg - 1) / wg;
+    if (nb > (1 << 20)) nb = 1 << 20;         // the loop strides over what is left
+    if (nb < 1) nb = 1;
+    widths->push_back(W);
+    blocks->push_back((int)nb);
+    char blk[64], nblk[32];
+    snprintf(blk, sizeof blk, "(long long)(blockIdx.x - %du)", (unsigned)first);
+    snprintf(nblk, sizeof nblk, "%lldll", (long long)nb);
+    e.line("  if (blockIdx.x < %du) {", (unsigned)(first + nb));
+    emit_part(e, ir, W, blk, nblk, view_base);
+    e.line("    return;");
+    e.line("  }");
+    first += (int)nb;
+    view_base += (int)ir.views.size();
+  }
+  e.line("}");
+  return name_kernel(e, kernel_name);
 }
 
 // ---------------------------------------------------------------------------------------------

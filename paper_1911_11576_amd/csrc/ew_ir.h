@@ -49,6 +49,11 @@ struct EwIr {
 
 // HIP source of one kernel computing the whole group; pure text, no GPU or compiler involved.
 std::string ew_emit_source(const EwIr& ir, int* width, int* unroll, std::string* kernel_name);
+// Several independent groups (each with its own shape) as one kernel: group q owns a run of
+// blocks[q] consecutive workgroups of `wg` threads, its views start after those of the groups
+// before it in Args::in, its outputs keep their ordinals of the whole list.
+std::string ew_emit_packed(const std::vector<const EwIr*>& parts, int wg, std::vector<int>* widths, std::vector<int>* blocks,
+                           std::string* kernel_name);
 // Compile with the run-time compiler (works on a machine without a GPU).  Results are cached
 // per process by source text.  False + message if the compiler is unavailable or fails.
 bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err);

@@ -17,6 +17,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
+#include <memory>
 #include <vector>
 
 #include "dev_common.h"
@@ -338,6 +340,7 @@ struct EwCompiler {
   std::vector<int> free_slots;
   int n_slots = 0;
   int acc_holds = -1;
+  std::vector<char> active;         // if not empty: the compute ops this compiler looks at (one part of a packed group)
 
   explicit EwCompiler(const Graph& gr) : g(gr) {}
 
@@ -426,6 +429,7 @@ struct EwCompiler {
       const Node& x = g[i];
       if (ew_is_elementwise(x.kind)) {
         if (!is_compute(i)) continue;            // a widening convert: an alias of its operand
+        if (!active.empty() && !active[i]) continue;
         if (S < 0) S = i;
         else if (!x.same_shape(g[S])) return fail("elementwise schedule: ops of different shapes in one group");
         order.push_back(i);
@@ -436,7 +440,7 @@ struct EwCompiler {
     }
     if (S < 0 || order.empty()) return fail("elementwise schedule: the group computes nothing");
     if (g[S].rank < 1) return fail("elementwise schedule: rank-0 group");
-    if ((int)g.outputs.size() > kEwMaxOuts) return fail("elementwise schedule: more than 8 outputs");
+    if (active.empty() && (int)g.outputs.size() > kEwMaxOuts) return fail("elementwise schedule: more than 8 outputs");
     EwProgram& P = c.prog;
     P.rank = g[S].rank;
     P.n = g[S].numel();
@@ -455,9 +459,12 @@ struct EwCompiler {
         const int a = canon(g[order[k]].operand[j]);
         if (is_compute(a)) last_use[a] = (int)k;
       }
+    int n_my_outputs = 0;
     for (int o : g.outputs) {
       const int src = canon(g[o].operand[0]);
       if (!is_compute(src)) return fail("elementwise schedule: an output that is a plain copy of an input");
+      if (!active.empty() && !active[src]) continue;
+      ++n_my_outputs;
       if (out_ord[src] >= 0) return fail("elementwise schedule: one value feeds two outputs");
       out_ord[src] = g[o].ordinal;
       out_dtype[src] = g[o].dtype;
@@ -465,7 +472,8 @@ struct EwCompiler {
 
     ir.rank = g[S].rank;
     ir.n = P.n;
-    ir.n_outputs = (int)g.outputs.size();
+    ir.n_outputs = n_my_outputs;
+    if (n_my_outputs == 0) return fail("elementwise schedule: ops that reach no output");
     for (int d = 0; d < FS_MAX_RANK; ++d) ir.shape[d] = P.shape[d];
     // the tanh-form GELU is generated as one op (the interpreter's program keeps the ops spelled out)
     std::vector<int> idiom_of(n, -1);
@@ -623,13 +631,90 @@ struct EwCompiler {
 }  // namespace
 
 // The generated kernel's arguments: one pointer per operand view, one per output.
-struct EwGenArgs { const void* in[24]; void* out[8]; void* ws; };
-static_assert(kEwMaxViews <= 24 && kEwMaxOuts == 8, "EwGenArgs mirrors the Args struct of the generated source");
+struct EwGenArgs { const void* in[64]; void* out[16]; void* ws; };
+static_assert(kEwMaxViews <= 64 && kEwMaxOuts <= 16, "EwGenArgs mirrors the Args struct of the generated source");
+
+// Kernel packing of independent elementwise computations (Section 5.1): the group falls into parts
+// that share no computed value -- typically the same update applied to tensors of different
+// shapes -- and each part is an elementwise group of its own shape.  One generated kernel runs
+// them all, each part on its own run of workgroups.
+static bool ew_plan_packed(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* status, std::string* err) {
+  *status = FS_ERR_UNSUPPORTED;
+  const int n = g.size();
+  EwCompiler probe(g);
+  // parts = connected components of the compute ops under "reads the value of"
+  std::vector<int> part(n, -1);
+  std::function<int(int)> find = [&](int v) { return part[v] == v ? v : part[v] = find(part[v]); };
+  for (int i = 0; i < n; ++i) if (probe.is_compute(i)) part[i] = i;
+  for (int i = 0; i < n; ++i) {
+    if (part[i] < 0) continue;
+    for (int j = 0; j < probe.n_operands(i); ++j) {
+      const int a = probe.canon(g[i].operand[j]);
+      if (probe.is_compute(a)) part[find(i)] = find(a);
+    }
+  }
+  std::vector<int> roots;
+  for (int i = 0; i < n; ++i) if (part[i] >= 0 && find(i) == i) roots.push_back(i);
+  if (roots.size() < 2) { *err = "elementwise schedule: ops of different shapes in one group"; return false; }
+  if (roots.size() > 16) { *err = "elementwise schedule: more than 16 independent parts in one group"; return false; }
+  if (g.outputs.size() > 16) { *err = "elementwise schedule: more than 16 outputs"; return false; }
+  if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
+    *status = FS_ERR_INVALID;
+    *err = "elementwise schedule: wg_size must be 64, 128, 192 or 256";
+    return false;
+  }
+  std::vector<std::unique_ptr<EwCompiler>> cs;
+  std::vector<const EwIr*> irs;
+  EwLaunch l;
+  int n_views = 0;
+  for (int r : roots) {
+    cs.emplace_back(new EwCompiler(g));
+    EwCompiler& cc = *cs.back();
+    cc.active.assign(n, 0);
+    for (int i = 0; i < n; ++i) if (part[i] >= 0 && find(i) == r) cc.active[i] = 1;
+    if (!cc.analyse()) { *err = cc.err; return false; }
+    if (cc.ir.n_outputs > kEwMaxOuts) { *err = "elementwise schedule: more than 8 outputs in one part"; return false; }
+    irs.push_back(&cc.ir);
+    l.n_ops += (int)cc.ir.nodes.size();
+    for (int k = 0; k < cc.c.n_views; ++k) l.view_param.push_back(cc.c.view_param[k]);
+    n_views += cc.c.n_views;
+    l.n += cc.ir.n;
+  }
+  if (n_views > 64) { *err = "elementwise schedule: more than 64 operand views over all parts"; return false; }
+  l.wg = opt.wg_size ? opt.wg_size : 256;
+  std::vector<int> widths, blocks;
+  const std::string src = ew_emit_packed(irs, l.wg, &widths, &blocks, &l.kernel_name);
+  if (const char* dump = getenv("FS_DUMP_SOURCE")) {
+    if (FILE* f = fopen(dump, "a")) { fputs(src.c_str(), f); fputs("\n// ----\n", f); fclose(f); }
+  }
+  std::string gen_err;
+  if (!ew_compile_source(src, &l.code_object, &gen_err)) { *err = "elementwise schedule: " + gen_err; return false; }
+  l.generated = true;
+  l.parts = (int)roots.size();
+  l.width = *std::max_element(widths.begin(), widths.end());
+  int64_t grid = 0;
+  for (int b : blocks) grid += b;
+  l.grid = (int)grid;          // at most 16 * 2^20
+  l.lds_bytes = 0;
+  *out = l;
+  *status = FS_OK;
+  return true;
+}
 
 bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* status, std::string* err) {
   *status = FS_ERR_UNSUPPORTED;
   EwCompiler cc(g);
-  if (!cc.analyse()) { *err = cc.err; return false; }
+  if (!cc.analyse()) {
+    *err = cc.err;
+    // several shapes: perhaps independent parts that can be packed into one kernel
+    if (opt.codegen && cc.err.find("ops of different shapes") != std::string::npos) {
+      std::string perr;
+      int pst = FS_ERR_UNSUPPORTED;
+      if (ew_plan_packed(g, opt, out, &pst, &perr)) { *status = FS_OK; return true; }
+      if (pst == FS_ERR_INVALID) { *status = pst; *err = perr; }
+    }
+    return false;
+  }
   EwLaunch l;
   *status = FS_ERR_INVALID;
   if (opt.wg_size && (opt.wg_size < 64 || opt.wg_size > 256 || opt.wg_size % 64)) {
@@ -752,7 +837,10 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
 
 std::string ew_stitch_describe(const EwLaunch& l) {
   char buf[320];
-  if (l.generated)
+  if (l.generated && l.parts > 1)
+    snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d packed in %d independent parts (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
+             l.width, l.n_ops, l.parts, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg);
+  else if (l.generated)
     snprintf(buf, sizeof buf, "elementwise[GRID,CTA-THREAD_%d] x%d merged (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=0",
              l.width, l.n_ops, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg);
   else
@@ -777,7 +865,7 @@ int ew_stitch_launch(EwLaunch& l, const void* const* in, void* const* out, int n
     if (l.n == 0) return 0;
     EwGenArgs args{};
     for (size_t k = 0; k < l.view_param.size(); ++k) args.in[k] = in[l.view_param[k]];
-    for (int k = 0; k < n_out; ++k) args.out[k] = out[k];
+    for (int k = 0; k < n_out && k < 16; ++k) args.out[k] = out[k];
     return ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
   }
   EwCompiled c;

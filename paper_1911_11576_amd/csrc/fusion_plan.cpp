@@ -311,29 +311,43 @@ struct Planner {
 };
 
 // maximise sum of scores over pairwise disjoint patterns, none of the forbidden sets complete
+// Maximum-weight selection of pairwise compatible patterns by branch and bound over up to 256
+// patterns (heaviest first).  Exact unless the node budget runs out, in which case the best
+// selection found so far stands (the first descent is the greedy one).
+struct Mask {
+  uint64_t w[4] = {0, 0, 0, 0};
+  void set(int i) { w[i >> 6] |= 1ull << (i & 63); }
+  bool test(int i) const { return (w[i >> 6] >> (i & 63)) & 1; }
+  Mask operator|(const Mask& o) const { Mask r; for (int k = 0; k < 4; ++k) r.w[k] = w[k] | o.w[k]; return r; }
+  bool contains(const Mask& o) const { for (int k = 0; k < 4; ++k) if ((w[k] & o.w[k]) != o.w[k]) return false; return true; }
+};
+
 struct Solver {
   std::vector<double> w;
-  std::vector<uint64_t> conflict;
-  std::vector<uint64_t> forbidden;
-  uint64_t best_sel = 0;
+  std::vector<Mask> conflict;
+  std::vector<Mask> forbidden;
+  Mask best_sel;
   double best = -1.0;
-  void rec(int i, uint64_t sel, uint64_t blocked, double val, double rest) {
+  long long nodes = 0;
+  static constexpr long long kNodeBudget = 4000000;
+  void rec(int i, const Mask& sel, const Mask& blocked, double val, double rest) {
     if (val > best) { best = val; best_sel = sel; }
-    if (i == (int)w.size() || val + rest <= best) return;
+    if (i == (int)w.size() || val + rest <= best || ++nodes > kNodeBudget) return;
     const double rest_after = rest - w[i];
-    if (!((blocked >> i) & 1)) {
-      const uint64_t s2 = sel | (1ull << i);
+    if (!blocked.test(i)) {
+      Mask s2 = sel;
+      s2.set(i);
       bool ok = true;
-      for (uint64_t fset : forbidden) if ((s2 & fset) == fset) ok = false;
+      for (const Mask& fset : forbidden) if (s2.contains(fset)) ok = false;
       if (ok) rec(i + 1, s2, blocked | conflict[i], val + w[i], rest_after);
     }
     rec(i + 1, sel, blocked, val, rest_after);
   }
-  uint64_t solve() {
+  Mask solve() {
     double rest = 0;
     for (double x : w) rest += x;
-    best = -1.0; best_sel = 0;
-    rec(0, 0, 0, 0.0, rest);
+    best = -1.0; best_sel = Mask(); nodes = 0;
+    rec(0, Mask(), Mask(), 0.0, rest);
     return best_sel;
   }
 };
@@ -351,11 +365,11 @@ bool fusion_plan(const std::vector<fs_op_desc>& ops, const FusionConfig& cfg, Fu
   // Candidates: the patterns with non-negative scores.  Patterns that share no op with each
   // other never constrain each other, so the selection problem splits along the connected
   // components of the conflict graph; each component is solved exactly over its best
-  // max_patterns (at most 64) patterns.
+  // max_patterns (at most 256) patterns.
   std::vector<int> cand;
   for (size_t k = 0; k < pl.patterns.size(); ++k) if (pl.patterns[k].score >= 0.0) cand.push_back((int)k);
   std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return pl.patterns[a].score > pl.patterns[b].score; });
-  const int cap = std::min(cfg.max_patterns, 64);
+  const int cap = std::min(cfg.max_patterns, 256);
   const int m = (int)cand.size();
   std::vector<std::set<int>> sets(m);
   for (int a = 0; a < m; ++a) sets[a].insert(pl.patterns[cand[a]].ops.begin(), pl.patterns[cand[a]].ops.end());
@@ -380,11 +394,30 @@ bool fusion_plan(const std::vector<fs_op_desc>& ops, const FusionConfig& cfg, Fu
     for (int a = 0; a < m; ++a) by_comp[find(a)].push_back(a);      // candidates are sorted by score already
     for (auto& kv : by_comp) {
       std::vector<int> ids = kv.second;
-      if ((int)ids.size() > cap) ids.resize(cap);
+      if ((int)ids.size() > cap) {
+        // More candidates than the solver takes: first the two heaviest patterns that contain each
+        // op (so that no op loses its best cover to a crowd of variants elsewhere), then the
+        // heaviest of the rest.
+        std::map<int, int> covers;
+        std::vector<char> keep(ids.size(), 0);
+        int kept = 0;
+        for (size_t q = 0; q < ids.size() && kept < cap; ++q) {
+          bool wanted = false;
+          for (int o : sets[ids[q]]) if (covers[o] < 2) wanted = true;
+          if (!wanted) continue;
+          keep[q] = 1;
+          ++kept;
+          for (int o : sets[ids[q]]) ++covers[o];
+        }
+        for (size_t q = 0; q < ids.size() && kept < cap; ++q) if (!keep[q]) { keep[q] = 1; ++kept; }
+        std::vector<int> chosen_ids;
+        for (size_t q = 0; q < ids.size(); ++q) if (keep[q]) chosen_ids.push_back(ids[q]);
+        ids.swap(chosen_ids);
+      }
       Solver sv;
       const int k = (int)ids.size();
       sv.w.resize(k);
-      sv.conflict.assign(k, 0);
+      sv.conflict.assign(k, Mask());
       std::map<int, int> local;
       for (int i = 0; i < k; ++i) { sv.w[i] = pl.patterns[cand[ids[i]]].score; local[ids[i]] = i; }
       for (int i = 0; i < k; ++i)
@@ -392,16 +425,16 @@ bool fusion_plan(const std::vector<fs_op_desc>& ops, const FusionConfig& cfg, Fu
           if (i == j) continue;
           bool meet = false;
           for (int o : sets[ids[i]]) if (sets[ids[j]].count(o)) { meet = true; break; }
-          if (meet) sv.conflict[i] |= 1ull << j;
+          if (meet) sv.conflict[i].set(j);
         }
       for (const std::vector<int>& fs_ : forbidden_sets) {
-        uint64_t mask = 0;
+        Mask mask;
         bool inside = true;
-        for (int a : fs_) { auto it = local.find(a); if (it == local.end()) { inside = false; break; } mask |= 1ull << it->second; }
+        for (int a : fs_) { auto it = local.find(a); if (it == local.end()) { inside = false; break; } mask.set(it->second); }
         if (inside) sv.forbidden.push_back(mask);
       }
-      const uint64_t sel = sv.solve();
-      for (int i = 0; i < k; ++i) if ((sel >> i) & 1) chosen[ids[i]] = 1;
+      const Mask sel = sv.solve();
+      for (int i = 0; i < k; ++i) if (sel.test(i)) chosen[ids[i]] = 1;
     }
     return chosen;
   };

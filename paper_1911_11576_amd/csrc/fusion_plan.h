@@ -11,7 +11,7 @@ namespace fs {
 
 struct FusionConfig {
   double launch_us = 2.5;                 // phi: average launch latency of one kernel
-  int max_patterns = 64;                  // patterns handed to the solver (the best by score)
+  int max_patterns = 256;                 // patterns per conflict component handed to the solver (the best by score)
   int explore_budget = 400;               // patterns the exploratory search may visit
   int max_pattern_ops = 40;
   int64_t seed_bytes = 1 << 20;           // exploratory seeds: ops whose result is at least this large

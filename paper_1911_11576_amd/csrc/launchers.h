@@ -52,6 +52,7 @@ struct EwLaunch {
   // generated form
   bool generated = false;
   int width = 4;                      // elements per thread
+  int parts = 1;                      // independent groups packed into the launch (each on its own run of workgroups)
   int64_t n = 0;
   std::vector<char> code_object;
   std::string kernel_name;

@@ -1373,7 +1373,7 @@ struct Stream {
   }
 };
 
-struct GenArgs { const void* in[24]; void* out[8]; void* ws; };   // mirrors Args of the generated source
+struct GenArgs { const void* in[64]; void* out[16]; void* ws; };   // mirrors Args of the generated source
 
 }  // namespace
 

@@ -215,7 +215,7 @@ def test_random_elementwise_graphs():
 def test_planner_rejects_bad_input():
     ops = graphs.log_softmax((64, 64))
     with pytest.raises(FsError) as e:
-        FusionPlan(ops, max_patterns=100)
+        FusionPlan(ops, max_patterns=300)
     assert e.value.status == binding.FS_ERR_INVALID
     with pytest.raises(FsError) as e:
         FusionPlan(ops, bandwidth=[(100, 5.0), (50, 6.0)])

@@ -210,3 +210,42 @@ def test_gelu_idiom_with_other_constants():
     ins = [_rand(shape, 9, -3, 3)]
     announce("gelu idiom, other constants")
     check_against_oracle(ops, ins, what="gelu constants")
+
+
+# ---------------------------------------------------------------- independent parts of different shapes, one kernel
+
+@pytest.mark.parametrize("shapes,dtypes", [
+    ([(1024, 1024), (1024,), (4096, 1024), (4096,), (3, 5, 7)], ["f32", "f32", "bf16", "f32", "f16"]),
+    ([(7,), (300, 96)], None),
+    ([(64, 64)] + [(k + 1,) for k in range(7)], None),                 # eight parts, 16 outputs
+    ([(0,), (5, 8), (3, 0, 2)], None),                                 # empty tensors among them
+])
+def test_packed_parts_of_different_shapes(shapes, dtypes):
+    ops = graphs.multi_tensor_momentum(shapes, dtypes=dtypes)
+    ins = inputs.multi_tensor_momentum(shapes, dtypes)
+    announce(f"packed elementwise parts {shapes}")
+    with Plan(ops) as p:
+        info = p.info()
+        assert info["schedule"] == "elementwise" and info["n_kernels"] == 1
+        assert f"packed in {len(shapes)} independent parts" in p.describe()
+    check_against_oracle(ops, ins, what="packed parts")
+    check_against_oracle(ops, ins, what="packed parts wg 64", wg_size=64)
+    # the unfused baseline runs them as separate kernels
+    with Plan(ops, "per_op") as p:
+        assert p.info()["n_kernels"] >= 2 * len([s for s in shapes])
+
+
+def test_packed_parts_share_an_input_and_mix_ops():
+    """Two parts may read the same parameter (no computed value is shared), and need not apply the same ops."""
+    g = graphs.Graph()
+    x = g.parameter("x", "f32", (33, 100))
+    s = g.parameter("s", "f32", (100,))
+    t = g.parameter("t", "f32", (5, 100))
+    g.output(g.multiply(g.tanh(x), g.col_broadcast(s, x)), "a")          # [33, 100]
+    g.output(g.add(g.exp(g.negate(g.multiply(s, s))), g.constant(1.0)), "b")   # [100]
+    g.output(g.maximum(t, g.col_broadcast(s, t)), "c")                   # [5, 100]
+    ins = inputs.normal_tensors([(33, 100), (100,), (5, 100)])
+    announce("packed parts sharing an input")
+    with Plan(g.ops) as p:
+        assert "packed in 3 independent parts" in p.describe()
+    check_against_oracle(g.ops, ins, what="packed parts sharing an input")

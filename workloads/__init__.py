@@ -68,7 +68,9 @@ def _ln_stats_inputs(rows, cols, dtype="f32"):
 # packing pattern of the backward phase, Section 5.1), row groups that no hand-written kernel
 # matches, the stand-in for the paper's motivating example (Section 3.1) at the sizes it
 # quotes, and the backward tail of a Transformer block (two row reductions, three column sums and
-# two full outputs packed over the same rows).  Not benchmark configs, so not in CONFIGS.
+# two full outputs packed over the same rows), and the momentum update of a Transformer layer's eight
+# parameter tensors as one group of independent parts of different shapes.  Not benchmark configs,
+# so not in CONFIGS.
 EXTRA_GROUPS = [
     Config(6, "adam_update_packed", graphs.adam_update, inputs.adam_update,
            dict(shape=(16384, 1024)), dict(shape=(129, 512)), "f32"),
@@ -84,5 +86,8 @@ EXTRA_GROUPS = [
            dict(batch=16384, m=94, n=94, k=1), dict(batch=7, m=94, n=94, k=1), "f32"),
     Config(12, "encoder_tail_bwd", graphs.encoder_tail_bwd, inputs.encoder_tail_bwd,
            dict(rows=16384, cols=1024), dict(rows=203, cols=1024), "f32"),
+    Config(13, "multi_tensor_momentum", graphs.multi_tensor_momentum, inputs.multi_tensor_momentum,
+           dict(shapes=[(1024, 1024), (1024,), (1024, 1024), (1024,), (4096, 1024), (4096,), (1024,), (1024,)]),
+           dict(shapes=[(33, 100), (100,), (7,), (64, 64)]), "f32"),
 ]
 BY_NAME = {c.name: c for c in CONFIGS + EXTRA_GROUPS}

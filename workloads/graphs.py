@@ -325,6 +325,25 @@ def adam_update(shape, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, dtype="f32"):
     return g.ops
 
 
+def multi_tensor_momentum(shapes, lr=1e-2, mu=0.9, dtypes=None):
+    """The same update on several tensors of different shapes, as ONE group of independent parts
+    (kernel packing of the backward phase's many small ops, Section 5.1): per tensor
+    m' = mu*m + g, p' = p - lr*m'; parameters (p_k, g_k, m_k) and outputs (p'_k, m'_k) per tensor.
+    `dtypes` gives each tensor's storage dtype (default all f32; the arithmetic is f32)."""
+    g = Graph()
+    dtypes = dtypes or ["f32"] * len(shapes)
+    for k, (shape, dt) in enumerate(zip(shapes, dtypes)):
+        p = g.parameter(f"p{k}", dt, shape)
+        grad = g.parameter(f"g{k}", dt, shape)
+        m = g.parameter(f"m{k}", dt, shape)
+        pf, gf, mf = (p, grad, m) if dt == "f32" else tuple(g.convert(t, "f32") for t in (p, grad, m))
+        m2 = g.add(g.multiply(mf, g.constant(mu)), gf)
+        p2 = g.subtract(pf, g.multiply(m2, g.constant(lr)))
+        g.output(p2 if dt == "f32" else g.convert(p2, dt), f"p{k}")
+        g.output(m2 if dt == "f32" else g.convert(m2, dt), f"m{k}")
+    return g.ops
+
+
 def scale_shift_rows_cols(shape, dtype="f32"):
     """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
     broadcasts along either side folded into one elementwise group."""

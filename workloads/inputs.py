@@ -142,3 +142,13 @@ def encoder_tail_bwd(rows, cols):
     mean = r64.mean(axis=-1) if rows else np.zeros(0)
     rstd = 1.0 / np.sqrt(r64.var(axis=-1) + 1e-5) if rows else np.zeros(0)
     return [round_to(t, "f32") for t in (dy, x, bias)] + [r] + [round_to(t, "f32") for t in (gamma, mean, rstd)]
+
+
+def multi_tensor_momentum(shapes, dtypes=None, seed_offset=41):
+    """Per tensor: p ~ N(0,1), g ~ N(0,0.1), m ~ N(0,0.05), in parameter order."""
+    r = _rng(seed_offset)
+    dtypes = dtypes or ["f32"] * len(shapes)
+    out = []
+    for shape, dt in zip(shapes, dtypes):
+        out += [round_to(r.normal(0.0, 1.0, shape), dt), round_to(r.normal(0.0, 0.1, shape), dt), round_to(r.normal(0.0, 0.05, shape), dt)]
+    return out
