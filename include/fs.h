@@ -122,7 +122,9 @@ typedef enum {
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
   FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as
                                 a kernel generated for the group (or interpreted, see
-                                FS_MODE_STITCHED_PREBUILT) */
+                                FS_MODE_STITCHED_PREBUILT).  The ops share one shape, or fall into
+                                up to 16 parts that share no computed value, each of one shape
+                                (generated form only): one kernel, a run of workgroups per part */
 } fs_schedule;
 
 /* Build a plan from a fusion group.

@@ -8,7 +8,7 @@
 //              fused kernel does not move, M from a measured bandwidth-vs-bytes table; negative
 //              if the kernel generator / recogniser cannot take the pattern
 //   selection  maximise the summed score over pairwise disjoint patterns (the ILP of Section
-//              4.1, solved exactly by branch and bound over at most 64 patterns); if the chosen
+//              4.1, solved by branch and bound over at most 256 patterns per conflict component); if the chosen
 //              patterns make the contracted graph cyclic, the patterns on the cycle are forbidden
 //              as a set and the problem is solved again
 //
