@@ -259,15 +259,39 @@ struct Planner {
     flush();
   }
 
-  // Algorithm 2: grow a seed by one producer or consumer at a time, every intermediate set a pattern
-  int visited = 0;
+  // Model-based score of a set of ops: negative if it is not convex or no stitched plan can be
+  // built for it (asked of fs_plan_create itself, which stops before compilation).  Remembered per set.
+  std::map<std::vector<int>, std::pair<double, int64_t>> evaluated;
+  double evaluate(const std::vector<int>& ops, int64_t* saved = nullptr) {
+    auto it = evaluated.find(ops);
+    if (it == evaluated.end()) {
+      std::pair<double, int64_t> r{-1.0, 0};
+      if (fusion_is_convex(g, ops)) {
+        FusionGroup gr;
+        extract(all, g, f, ops, &gr);
+        if (generable(gr)) {
+          r.second = fusion_saved_bytes(g, ops);
+          r.first = fusion_model_us(cfg, r.second) + (double)(ops.size() - 1) * cfg.launch_us;
+        }
+      }
+      it = evaluated.emplace(ops, r).first;
+    }
+    if (saved) *saved = it->second.second;
+    return it->second.first;
+  }
+
+  // Algorithm 2: a seed grows by one producer or consumer at a time as long as the grown set is
+  // still a valid pattern (convex, a stitched plan exists); every set on the way is a pattern.
+  // Depth first, so the maximal patterns around a seed come early; every seed has its share of
+  // the visit budget.
+  int visited = 0, seed_limit = 0;
   std::set<std::vector<int>> explored;
   bool fusible(const Node& x) const {
     return is_binary(x.kind) || is_unary(x.kind) || x.kind == FS_CONVERT || x.kind == FS_CAUSAL_MASK ||
            is_reduce_kind(x.kind) || small_dot(x);
   }
   void explore(const std::vector<int>& seed) {
-    if (visited >= cfg.explore_budget || (int)seed.size() >= cfg.max_pattern_ops) return;
+    if (visited >= seed_limit || (int)seed.size() >= cfg.max_pattern_ops) return;
     std::set<int> in(seed.begin(), seed.end()), cand;
     for (int o : seed) {
       for (int p : f.producers[o]) if (!in.count(p) && fusion_owns_kernel(g, p) && fusible(g[p])) cand.insert(p);
@@ -279,7 +303,8 @@ struct Planner {
       std::sort(next.begin(), next.end());
       if (!explored.insert(next).second) continue;
       if (!fusion_is_convex(g, next)) continue;          // would introduce a cyclic dependence
-      if (++visited > cfg.explore_budget) return;
+      if (++visited > seed_limit) return;
+      if (evaluate(next) < 0.0) continue;                // no kernel for it: nothing grows from here
       add(next, 2);
       explore(next);
     }
@@ -292,21 +317,18 @@ struct Planner {
     substitution([&](const Node& x) { return x.kind == FS_DOT || (is_reduce_kind(x.kind) && !row_reduce(x)); });
     substitution([&](const Node& x) { return x.kind == FS_DOT || is_reduce_kind(x.kind); });
     // exploratory seeds: fusible ops with large results and few operands (all ops here have at most two)
-    for (int o : owned)
-      if (fusible(g[o]) && value_bytes(g[o]) >= cfg.seed_bytes) explore(std::vector<int>{o});
+    std::vector<int> seeds;
+    for (int o : owned) if (fusible(g[o]) && value_bytes(g[o]) >= cfg.seed_bytes) seeds.push_back(o);
+    for (size_t k = 0; k < seeds.size() && visited < cfg.explore_budget; ++k) {
+      const int share = std::max(24, (cfg.explore_budget - visited) / (int)(seeds.size() - k));
+      seed_limit = std::min(cfg.explore_budget, visited + share);
+      explore(std::vector<int>{seeds[k]});
+    }
     for (const std::vector<int>& p : cfg.extra_patterns) add(p, 3);
   }
 
   void score() {
-    for (FusionPattern& p : patterns) {
-      p.score = -1.0;
-      if (!fusion_is_convex(g, p.ops)) continue;
-      FusionGroup gr;
-      extract(all, g, f, p.ops, &gr);
-      if (!generable(gr)) continue;
-      p.saved_bytes = fusion_saved_bytes(g, p.ops);
-      p.score = fusion_model_us(cfg, p.saved_bytes) + (double)(p.ops.size() - 1) * cfg.launch_us;
-    }
+    for (FusionPattern& p : patterns) p.score = evaluate(p.ops, &p.saved_bytes);
   }
 };
 

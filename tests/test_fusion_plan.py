@@ -112,7 +112,8 @@ def _check_plan(ops, fp, brute_force=True):
     is_dot = lambda op: op.kind == "dot"
     is_red = lambda op: op.kind in ("reduce_sum", "reduce_max")
     not_row = lambda op: is_red(op) and op.axis != len(ops[op.operands[0]].shape) - 1
-    have = {tuple(p["ops"]) for p in fp.patterns if p["origin"] == 0}
+    # (a segment that was first met as a connected part of a larger one keeps that origin)
+    have = {tuple(p["ops"]) for p in fp.patterns if p["origin"] in (0, 1)}
     for part in (is_dot, lambda op: is_dot(op) or not_row(op), lambda op: is_dot(op) or is_red(op)):
         for seg in of.substitution_segments(ops, part):
             if len(seg) <= 40:
@@ -210,6 +211,22 @@ def test_random_elementwise_graphs():
             g.output(vals[-1])
         fp = FusionPlan(g.ops, launch_us=PHI, bandwidth=TABLE, explore_budget=40)
         _check_plan(g.ops, fp)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_programs_are_cut_into_valid_groups(seed):
+    """Graphs that need several dependent groups (reductions over either dim as intermediates):
+    scores against the oracle, disjointness, order, acyclicity; and the exploratory search must
+    have found more than the substitution segments alone."""
+    rng = random.Random(100 + seed)
+    ops, _ = graphs.random_program(rng, 600, 1024, n_ops=rng.randint(10, 40))
+    fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
+    _check_plan(ops, fp)
+    assert all(p["score_us"] >= 0 for p in fp.patterns if p["origin"] == 2)      # the search only keeps valid patterns
+    without = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE, explore_budget=-1)
+    assert fp.total_score_us >= without.total_score_us - 1e-9
+    owned = sum(1 for op in ops if of.owns_kernel(op))
+    assert len(fp.groups) <= max(2, (2 * owned) // 3)                            # it does fuse
 
 
 def test_planner_rejects_bad_input():

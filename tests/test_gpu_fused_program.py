@@ -99,3 +99,23 @@ def test_single_group_graphs_through_the_planner(name):
     got, _, _ = _run(ops, ins)
     for a, b in zip(got, want):
         assert_close(a, b, TOLERANCE["f32"], name)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_programs_through_the_planner(seed):
+    """Random graphs over full, per-row and per-column values with reductions over either dim as
+    intermediates: the planner has to cut them into several dependent groups (a column-reduced value
+    ends its group; its readers start new ones), every group runs as its stitched plan, and the
+    program's outputs must match the oracle's evaluation of the whole graph."""
+    import random
+    rng = random.Random(100 + seed)
+    rows, cols = [(600, 1024), (257, 96), (64, 4096), (1000, 30)][seed % 4]
+    ops, pshapes = graphs.random_program(rng, rows, cols, n_ops=rng.randint(10, 40))
+    ins = inputs.normal_tensors(pshapes, seed_offset=400 + seed)
+    announce(f"random program seed {seed} {rows}x{cols}: {len(ops)} ops")
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins, seed_bytes=1)      # every fusible op may seed the exploratory search
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], f"random program {seed}")
+    with Plan(ops, "per_op") as p:
+        assert n_kernels <= p.info()["n_kernels"]

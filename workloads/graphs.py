@@ -733,3 +733,63 @@ def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
         g.output(c)
     pshapes = [shape, shape] + ([rowshape] if rowshape else []) + [(ncol,)]
     return g.ops, pshapes
+
+
+def random_program(rng, rows, cols, n_ops=30):
+    """A random graph larger than one fusion group, over full [rows, cols], per-row [rows] and
+    per-column [cols] values: elementwise ops on each class, reductions over the last dim and over
+    the rows as INTERMEDIATES (their results are broadcast back into later full ops), so that a
+    fusion plan has to cut it into several dependent groups.  Values stay tame (tanh before exp and
+    before every reduction, sums divided by their length).  `rng` is a random.Random.
+    Returns (ops, parameter shapes)."""
+    g = Graph()
+    x = g.parameter("x", "f32", (rows, cols))
+    y = g.parameter("y", "f32", (rows, cols))
+    rv = g.parameter("rv", "f32", (rows,))
+    cv = g.parameter("cv", "f32", (cols,))
+    full, rws, cls = [x, y], [rv], [cv]
+    for _ in range(n_ops):
+        kind = rng.choice(["bin", "bin", "un", "rsum", "rmax", "csum", "rowop", "colop", "bcast_row", "bcast_col", "const"])
+        if kind == "bin":
+            full.append(getattr(g, rng.choice(["add", "subtract", "multiply", "maximum"]))(rng.choice(full), rng.choice(full)))
+        elif kind == "un":
+            a = rng.choice(full)
+            full.append(rng.choice([lambda: g.tanh(a), lambda: g.exp(g.tanh(a)), lambda: g.rsqrt(g.add(g.multiply(a, a), g.constant(1.0)))])())
+        elif kind == "rsum":
+            rws.append(g.divide(g.reduce_sum(g.tanh(rng.choice(full)), -1), g.constant(cols)))
+        elif kind == "rmax":
+            rws.append(g.reduce_max(g.tanh(rng.choice(full)), -1))
+        elif kind == "csum":
+            cls.append(g.divide(g.reduce_sum(g.tanh(rng.choice(full)), 0), g.constant(rows)))
+        elif kind == "rowop":
+            rws.append(getattr(g, rng.choice(["add", "multiply", "maximum"]))(g.tanh(rng.choice(rws)), rng.choice(rws)))
+        elif kind == "colop":
+            cls.append(getattr(g, rng.choice(["add", "multiply", "maximum"]))(g.tanh(rng.choice(cls)), rng.choice(cls)))
+        elif kind == "bcast_row":
+            full.append(getattr(g, rng.choice(["add", "multiply", "subtract"]))(rng.choice(full), g.row_broadcast(rng.choice(rws), x)))
+        elif kind == "bcast_col":
+            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.col_broadcast(rng.choice(cls), x)))
+        else:
+            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.constant(rng.choice([0.5, -1.25, 2.0]))))
+    out = full[-1] if len(full) > 2 else g.add(x, y)
+    g.output(out, "full")
+    computed = lambda lst: [v for v in lst if g.ops[v].kind != "parameter"]
+    seen = {out}
+    for lst, name in ((rws, "row"), (cls, "col")):
+        c = [v for v in computed(lst) if v not in seen]
+        if c:
+            g.output(c[-1], name)
+            seen.add(c[-1])
+    # only what reaches an output stays (parameters all stay: they are the launch's inputs)
+    ops = g.ops
+    live = [op.kind in ("output", "parameter") for op in ops]
+    for i in range(len(ops) - 1, -1, -1):
+        if live[i]:
+            for o in ops[i].operands:
+                live[o] = True
+    renumber, kept = {}, []
+    for i, op in enumerate(ops):
+        if live[i]:
+            renumber[i] = len(kept)
+            kept.append(Op(op.kind, op.dtype, op.shape, tuple(renumber[o] for o in op.operands), op.axis, op.attr, op.name))
+    return kept, [(rows, cols), (rows, cols), (rows,), (cols,)]
