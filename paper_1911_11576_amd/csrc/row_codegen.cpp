@@ -62,6 +62,7 @@ struct Analysis {
   int64_t S[FS_MAX_RANK] = {1, 1, 1, 1};
   int64_t rows = 1, cols = 1;
   std::vector<int> cls;
+  std::vector<char> colv;        // a value of shape [C] computed in the group: one per column, the same for every row
   std::vector<RNode> nodes;
   std::vector<RView> views;
   int n_reduce = 0;
@@ -94,6 +95,11 @@ struct Analysis {
     if (x.rank != rank - 1) return false;
     for (int d = 0; d < rank - 1; ++d) if (x.shape[d] != S[d]) return false;
     return true;
+  }
+
+  // one value per column: [C] under a full shape of rank 2 or more (and not also the row shape)
+  bool shape_is_column(const Node& x) const {
+    return rank >= 2 && x.rank == 1 && x.shape[0] == S[rank - 1] && !shape_is_row(x);
   }
 
   // Leaf (parameter seen through broadcasts and widening converts, or constant) -> strides
@@ -132,16 +138,24 @@ struct Analysis {
     return (int)views.size() - 1;
   }
 
-  bool operand(int n, int consumer_cls, Opnd* o) {
+  // `as_column`: the consumer is a per-column value (shape [C]) kept as a full value whose rows are
+  // all alike; its parameter operands have that shape too and are read with row stride 0.
+  bool operand(int n, int consumer_cls, Opnd* o, bool as_column = false) {
     const int c = canon(n);
     if (is_compute(c)) {
-      if (cls[c] != consumer_cls) return fail("generated row schedule: operand of the wrong shape class");
+      if (cls[c] != consumer_cls || (as_column && !colv[c])) return fail("generated row schedule: operand of the wrong shape class");
       o->kind = OP_NODE; o->index = c;
       return true;
     }
     // a per-row value broadcast along the last dim into a full op
-    if (g[c].kind == FS_BROADCAST && consumer_cls == CLS_FULL) {
+    if (g[c].kind == FS_BROADCAST && consumer_cls == CLS_FULL && !as_column) {
       const int src = canon(g[c].operand[0]);
+      if (is_compute(src) && colv[src]) {
+        // a per-column value computed in the group, broadcast over the rows: it already is a full value here
+        if (!shape_is_full(g[c]) || g[c].axis != rank - 1) return fail("generated row schedule: a per-column value broadcast along another dim");
+        o->kind = OP_NODE; o->index = src;
+        return true;
+      }
       if (is_compute(src)) {
         if (cls[src] != CLS_ROW || !shape_is_full(g[c]) || (g[src].rank > 0 && g[c].axis != 0))  // leading dims line up
           return fail("generated row schedule: only per-row values may be broadcast back");
@@ -156,6 +170,15 @@ struct Analysis {
     if (!leaf_strides(c, &base, st, &is_const, &cv)) return false;
     if (is_const) { o->kind = OP_CONST; o->cval = cv; return true; }
     const Node& shp = g[c];
+    if (as_column) {
+      if (!shape_is_column(shp)) return fail("generated row schedule: operand shape differs from its consumer's");
+      const int64_t last = st[0];
+      for (int d = 0; d < FS_MAX_RANK; ++d) st[d] = 0;
+      st[rank - 1] = last;
+      o->kind = OP_VIEW;
+      o->index = view_index(base, st, CLS_FULL);
+      return true;
+    }
     if (consumer_cls == CLS_FULL ? !shape_is_full(shp) : !shape_is_row(shp))
       return fail("generated row schedule: operand shape differs from its consumer's");
     o->kind = OP_VIEW;
@@ -244,6 +267,7 @@ struct Analysis {
     rows = 1;
     for (int d = 0; d + 1 < rank; ++d) rows *= S[d];
     cls.assign(n, CLS_NONE);
+    colv.assign(n, 0);
     std::vector<int> out_ord(n, -1), out_dtype(n, 0);
     for (int o : g.outputs) {
       const int s = canon(g[o].operand[0]);
@@ -349,12 +373,17 @@ struct Analysis {
         if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
         ++n_reduce;
       } else {
-        r.cls = shape_is_full(x) ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
+        // arithmetic on per-column values (a scale vector prepared from parameters, say) is done as
+        // full arithmetic whose rows are all alike: a few redundant ops per row, no kernel of its own
+        const bool column = !shape_is_full(x) && !shape_is_row(x) && shape_is_column(x);
+        r.cls = shape_is_full(x) || column ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
         if (r.cls == CLS_NONE) return fail("generated row schedule: an op whose shape is neither the group's nor its row shape");
+        if (column && out_ord[i] >= 0) return fail("generated row schedule: a per-column value computed in the group is a group output");
         cls[i] = r.cls;
+        colv[i] = column;
         r.op = k == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : k;
         r.nop = is_binary(k) ? 2 : 1;
-        for (int j = 0; j < r.nop; ++j) if (!operand(x.operand[j], r.cls, &r.o[j])) return false;
+        for (int j = 0; j < r.nop; ++j) if (!operand(x.operand[j], r.cls, &r.o[j], column)) return false;
         if (r.nop == 2 && r.o[0].kind == OP_CONST && r.o[1].kind == OP_CONST) return fail("generated row schedule: op of two constants");
       }
       r.out_ord = out_ord[i];

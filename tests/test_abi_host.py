@@ -236,10 +236,17 @@ def test_elementwise_limits_are_reported():
     g.output(g.exp(x))
     e = _expect(binding.FS_ERR_INVALID, g.ops, wg_size=512)
     assert "wg_size" in str(e)
-    g = Graph()                               # a broadcast of a computed value is not elementwise
+    g = Graph()                               # a broadcast of a computed value is not elementwise ...
     x = g.parameter("x", "f32", (8, 64))
     v = g.parameter("v", "f32", (64,))
     g.output(g.add(x, g.col_broadcast(g.exp(v), x)))
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops, mode="prebuilt")
+    with Plan(g.ops) as p:                    # ... the row generator takes it: the per-column op is done per row
+        assert p.info()["schedule"] == "row" and p.info()["n_kernels"] == 1
+    g = Graph()                               # a computed value broadcast along another dim is nobody's
+    x = g.parameter("x", "f32", (8, 64, 4))
+    v = g.parameter("v", "f32", (64,))
+    g.output(g.add(x, g.broadcast(g.exp(v), (8, 64, 4), 1)))
     _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
 
 

@@ -438,6 +438,21 @@ def rmsnorm(shape, dtype="f32", eps=1e-6):
     return g.ops
 
 
+def rmsnorm_one_plus_weight(shape, dtype="bf16", eps=1e-6):
+    """y = x * rsqrt(mean(x^2) + eps) * (1 + w): the scale vector is computed in the group from the
+    per-column parameter (a [C]-shaped op whose result is broadcast over the rows)."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    w = g.parameter("w", dtype, (shape[-1],))
+    xf, wf = _f32_in(g, dtype, x, w)
+    ms = g.divide(g.reduce_sum(g.multiply(xf, xf), -1), g.constant(shape[-1]))
+    inv = g.rsqrt(g.add(ms, g.constant(eps)))
+    scale = g.add(wf, g.constant(1.0))
+    y = g.multiply(g.multiply(xf, g.row_broadcast(inv, xf)), g.col_broadcast(scale, xf))
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
+    return g.ops
+
+
 def l2_normalize_scaled(shape, dtype="f32"):
     """y = x * s / sqrt(sum(x^2)) with one scale s per row; also returns the norms."""
     g = Graph()
@@ -690,8 +705,9 @@ def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
     full = [conv(x), conv(y)]
     rows = [conv(rv)] if rv is not None else []
     cvf = conv(cv)
+    colvals = [cvf]                # per-column values: the parameter and what is computed from it
     for _ in range(n_ops):
-        kind = rng.choice(["bin", "bin", "un", "reduce", "rowop", "bcast_row", "bcast_col", "const"])
+        kind = rng.choice(["bin", "bin", "un", "reduce", "rowop", "bcast_row", "bcast_col", "const", "colop"])
         if kind == "bin":
             a, b = rng.choice(full), rng.choice(full)
             full.append(getattr(g, rng.choice(["add", "subtract", "multiply", "maximum"]))(a, b))
@@ -716,9 +732,13 @@ def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
         elif kind == "bcast_row" and rows:
             full.append(getattr(g, rng.choice(["add", "multiply", "subtract"]))(rng.choice(full), g.row_broadcast(rng.choice(rows), full[0])))
         elif kind == "bcast_col":
-            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.col_broadcast(cvf, full[0])))
+            full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.col_broadcast(rng.choice(colvals), full[0])))
         elif kind == "const":
             full.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(full), g.constant(rng.choice([0.5, -1.25, 2.0]))))
+        elif kind == "colop" and len(shape) >= 2 and tuple(shape[:-1]) != (ncol,):
+            a = rng.choice(colvals)
+            colvals.append(rng.choice([lambda: g.add(g.tanh(a), g.constant(1.0)), lambda: g.multiply(a, rng.choice(colvals)),
+                                       lambda: g.maximum(g.negate(a), cvf)])())
     out = full[-1]
     if out in (full[0], full[1]):
         out = g.add(full[0], full[1])
