@@ -148,7 +148,12 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
  *   outputs[n_out]  host array of DEVICE pointers, one per FS_OUTPUT in list order
  * Tensors are dense row-major in their op's dtype, 16-byte aligned, and borrowed until
  * the work enqueued by this call has finished.  Inputs are never written; outputs must
- * not overlap inputs or each other.  A plan that owns a workspace (fs_plan_info) must
+ * not overlap inputs or each other, with one exception, the update in place: an output may be
+ * given the very pointer of a parameter of its own shape and dtype where the plan runs a
+ * generated elementwise kernel or a generated register row kernel (fs_plan_describe says so)
+ * and reads that parameter only in the group's own layout (not through a broadcast); such
+ * kernels read every element in the thread, or the row's lanes, that later writes it.  Any
+ * other identical pointer is refused with FS_ERR_INVALID; partial overlaps are not detected.  A plan that owns a workspace (fs_plan_info) must
  * not have two launches in flight at once; the workspace is allocated on the first
  * launch on the then-current device and the plan stays bound to that device.
  * Errors: FS_ERR_INVALID (NULL or misaligned pointer, wrong counts), FS_ERR_HIP,

@@ -347,6 +347,25 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
   for (int i = 0; i < n_out; ++i) {
     if (g[g.outputs[i]].numel() == 0) continue;
     if (!outputs[i] || (reinterpret_cast<uintptr_t>(outputs[i]) & 15)) return set_error(FS_ERR_INVALID, "output pointer is NULL or not 16-byte aligned");
+    // An output in the very buffer of a parameter (an update in place): fine where the kernel reads
+    // every element of that parameter once, in the thread (or the row's lanes) that writes the same
+    // element, before it writes -- the generated elementwise kernels and the generated register
+    // row kernels, for parameters of the output's own shape and dtype that are read in no other way.
+    for (int k = 0; k < n_in; ++k) {
+      if (inputs[k] != outputs[i] || g[g.params[k]].numel() == 0) continue;
+      const fs::Node& pn = g[g.params[k]];
+      const fs::Node& on = g[g.outputs[i]];
+      bool ok = p->mode == FS_MODE_STITCHED && pn.dtype == on.dtype && pn.same_shape(on);
+      const std::vector<int>* vp = nullptr;
+      const std::vector<char>* vf = nullptr;
+      if (ok && p->schedule == FS_SCHED_ELEMENTWISE && p->ew.generated) { vp = &p->ew.view_param; vf = &p->ew.view_full; }
+      else if (ok && p->row_form == 3 && !p->row_gen.streamed && p->row_gen.rows_read_before_written &&
+               (p->schedule == FS_SCHED_ROW || p->schedule == FS_SCHED_ROW_COL)) { vp = &p->row_gen.view_param; vf = &p->row_gen.view_dense; }
+      else ok = false;
+      for (size_t q = 0; ok && q < vp->size(); ++q) if ((*vp)[q] == pn.ordinal && !(*vf)[q]) ok = false;
+      if (!ok) return set_error(FS_ERR_INVALID, "an output shares its buffer with an input that this plan may still read after writing it "
+                                                "(in-place updates: generated elementwise and register row kernels, same shape and dtype, parameter read only as the group's own layout)");
+    }
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   std::string err;

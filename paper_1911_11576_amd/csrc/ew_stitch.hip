@@ -676,7 +676,7 @@ static bool ew_plan_packed(const Graph& g, const LaunchOpts& opt, EwLaunch* out,
     if (cc.ir.n_outputs > kEwMaxOuts) { *err = "elementwise schedule: more than 8 outputs in one part"; return false; }
     irs.push_back(&cc.ir);
     l.n_ops += (int)cc.ir.nodes.size();
-    for (int k = 0; k < cc.c.n_views; ++k) l.view_param.push_back(cc.c.view_param[k]);
+    for (int k = 0; k < cc.c.n_views; ++k) { l.view_param.push_back(cc.c.view_param[k]); l.view_full.push_back(cc.ir.views[k].full ? 1 : 0); }
     n_views += cc.c.n_views;
     l.n += cc.ir.n;
   }
@@ -727,6 +727,7 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
   }
   l.n_ops = (int)cc.ir.nodes.size();
   l.view_param.assign(cc.c.view_param, cc.c.view_param + cc.c.n_views);
+  for (const EwIrView& v : cc.ir.views) l.view_full.push_back(v.full ? 1 : 0);
 
   // First choice: generate the kernel (the paper's way).  The interpreter below is the form
   // that needs no compiler at run time; it also takes over if generation fails.

@@ -49,6 +49,7 @@ struct Graph;
 struct EwLaunch {
   int wg = 256, grid = 1, n_ops = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view
+  std::vector<char> view_full;        // generated form: the view has the group's own dense layout (read once, by the thread that writes the same elements)
   // generated form
   bool generated = false;
   int width = 4;                      // elements per thread

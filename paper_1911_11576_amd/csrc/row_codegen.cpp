@@ -1441,7 +1441,13 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   l.rows = A.rows; l.cols = A.cols;
   l.n_ops = (int)A.nodes.size();
   l.n_reduce = A.n_reduce;
-  for (const RView& v : A.views) l.view_param.push_back(v.param);
+  for (const RView& v : A.views) {
+    l.view_param.push_back(v.param);
+    bool dense = v.cls == CLS_FULL && v.offset == 0;
+    int64_t st = 1;
+    for (int d = A.rank - 1; d >= 0 && dense; --d) { if (A.S[d] != 1 && v.stride[d] != st) dense = false; st *= A.S[d]; }
+    l.view_dense.push_back(dense ? 1 : 0);
+  }
   gen.want_persistent = want_persistent;
   gen.wg = opt.wg_size && (opt.wg_size <= 256 || A.n_col > 0) ? opt.wg_size : 256;
   if (gen.wg & (gen.wg - 1)) gen.wg = gen.wg > 512 ? 512 : gen.wg > 256 ? 256 : 128;   // lanes per row divide the workgroup
@@ -1453,6 +1459,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     std::string cerr;
     if (!ew_compile_source(gen.e.s, &l.code_object, &cerr)) { *err = "generated row schedule: " + cerr; return false; }
     l.L = gen.L; l.K = gen.K; l.W = gen.W;
+    l.rows_read_before_written = true;
+    for (const RNode& n : A.nodes) if (n.op == ROP_DOT_OUTER || n.op == ROP_DOT_REDUCE) l.rows_read_before_written = false;
     l.lds_bytes = gen.L > 64 ? (int64_t)A.n_reduce * (gen.L / 64) * 4 : gen.stage_bytes;
     l.wg = l.L > 64 ? l.L : gen.wg;     // a team is one workgroup per row
     const int64_t rows_per_wg = l.L > 64 ? 1 : l.wg / l.L;

@@ -26,6 +26,8 @@ struct RowGenLaunch {
   int64_t workspace_bytes = 0;
   int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view
+  std::vector<char> view_dense;       // the view is the parameter as a dense tensor of the group's full shape
+  bool rows_read_before_written = false;   // register templates without dots: a row is read completely, by the lanes that write it, before any of it is written
   std::vector<char> code_object;
   std::string kernel_name;
   EwModule loaded;                    // run-time state: the module once it is on a device

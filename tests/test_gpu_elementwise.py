@@ -249,3 +249,47 @@ def test_packed_parts_share_an_input_and_mix_ops():
     with Plan(g.ops) as p:
         assert "packed in 3 independent parts" in p.describe()
     check_against_oracle(g.ops, ins, what="packed parts sharing an input")
+
+
+# ---------------------------------------------------------------- updates in place
+
+def test_update_in_place_where_the_kernel_reads_before_it_writes():
+    """Optimizer-style updates: outputs given the very buffers of the parameters they replace."""
+    from paper_1911_11576_amd import FsError, binding
+    from gpu_util import to_device
+    shapes = [(300, 96), (96,), (7, 5, 3)]
+    ops, ins = graphs.multi_tensor_momentum(shapes), inputs.multi_tensor_momentum(shapes)
+    want = interp.run(ops, ins)
+    announce("in-place multi-tensor momentum")
+    dev = to_device(ops, ins)                                   # p0 g0 m0 p1 g1 m1 ...
+    outs = [dev[3 * (k // 2) + (0 if k % 2 == 0 else 2)] for k in range(2 * len(shapes))]      # p_k' -> p_k, m_k' -> m_k
+    with Plan(ops) as p:
+        p.launch(dev, outs)
+        torch.cuda.synchronize()
+    for got, ref in zip(outs, want):
+        assert_close(got.double().cpu().numpy(), ref, 1e-5, "in-place momentum")
+    # a generated row kernel: LayerNorm written over its input
+    rows, cols = 203, 1024
+    ops, ins = graphs.layernorm_fwd(rows, cols), inputs.layernorm_fwd(rows, cols)
+    (want,) = interp.run(ops, ins)
+    dev = to_device(ops, ins)
+    with Plan(ops, "generated") as p:
+        p.launch(dev, [dev[0]])
+        torch.cuda.synchronize()
+    assert_close(dev[0].double().cpu().numpy(), want, 1e-5, "in-place LayerNorm")
+    # refused: the hand-written kernel, the per-op baseline, the streamed template, a parameter read through a broadcast
+    dev = to_device(ops, ins)
+    for kw in (dict(mode="prebuilt"), dict(mode="per_op"), dict(mode="generated", grid=3)):
+        with Plan(ops, **kw) as p:
+            with pytest.raises(FsError) as e:
+                p.launch(dev, [dev[0]])
+            assert e.value.status == binding.FS_ERR_INVALID and "in-place" in e.value.message
+    g = graphs.Graph()
+    x = g.parameter("x", "f32", (64, 64))
+    v = g.parameter("v", "f32", (64,))
+    g.output(g.add(g.tanh(v), g.constant(1.0)), "v2")             # [64], would overwrite what the other part still reads
+    g.output(g.multiply(x, g.col_broadcast(v, x)), "y")
+    dev = to_device(g.ops, inputs.normal_tensors([(64, 64), (64,)]))
+    with Plan(g.ops) as p:
+        with pytest.raises(FsError):
+            p.launch(dev, [dev[1], torch.empty_like(dev[0])])
