@@ -413,10 +413,51 @@ class FusedProgram:
             plan.launch(gin, gout, stream)
         return [values[self.ops[i].operands[0]] for i in self.output_ops]
 
+    def bind(self, inputs):
+        """Fix the program's buffers: the given input tensors, and one freshly allocated tensor per value
+        that crosses a group boundary.  -> the output tensors; run_bound() then launches every group on
+        those buffers without allocating, which is what a HIP graph capture needs."""
+        torch = self._torch
+        dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+        values = {i: t for i, t in zip(self.param_ops, inputs)}
+        device = inputs[0].device if inputs else "cuda:0"
+        self._bound = []
+        for g, plan in zip(self.fusion.groups, self.plans):
+            gin = [values[i] for i in g["input_of"]]
+            gout = []
+            for i in g["output_of"]:
+                op = self.ops[i]
+                values[i] = torch.empty(op.shape, dtype=dt[op.dtype], device=device)
+                gout.append(values[i])
+            self._bound.append((plan, BoundArgs(gin, gout)))
+        self._bound_outputs = [values[self.ops[i].operands[0]] for i in self.output_ops]
+        return self._bound_outputs
+
+    def run_bound(self, stream=None):
+        if stream is None:
+            stream = self._torch.cuda.current_stream().cuda_stream
+        for plan, args in self._bound:
+            plan.launch_bound(args, stream)
+        return self._bound_outputs
+
+    def capture(self, inputs):
+        """bind(inputs), one ordinary run (kernels loaded, workspaces allocated), then the same launches
+        recorded into a HIP graph.  -> (graph, outputs): graph.replay() recomputes the outputs from whatever
+        the input tensors hold then."""
+        torch = self._torch
+        outs = self.bind(inputs)
+        self.run_bound()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            self.run_bound()
+        return graph, outs
+
     def close(self):
         for p in self.plans:
             p.close()
         self.plans = []
+        self._bound = []
 
     def __enter__(self):
         return self

@@ -119,3 +119,39 @@ def test_random_programs_through_the_planner(seed):
         assert_close(a, b, TOLERANCE["f32"], f"random program {seed}")
     with Plan(ops, "per_op") as p:
         assert n_kernels <= p.info()["n_kernels"]
+
+
+def test_fused_program_as_a_captured_graph():
+    """The groups of a planned graph recorded into one HIP graph: replayed with new input values and
+    eager work in between, every replay against the oracle; and timed against launching group by group."""
+    import random
+    import time
+    rng = random.Random(105)
+    ops, pshapes = graphs.random_program(rng, 600, 1024, n_ops=rng.randint(10, 40))
+    ins = inputs.normal_tensors(pshapes, seed_offset=405)
+    announce(f"fused program as a graph: {len(ops)} ops")
+    dev_in = to_device(ops, ins)
+    with FusedProgram(ops, seed_bytes=1) as prog:
+        graph, outs = prog.capture(dev_in)
+        assert len(prog.plans) >= 3
+        for rep, scale in enumerate([1.0, -0.5, 2.0]):
+            cur = [inputs.round_to(a * scale, "f32") if k == 0 else a for k, a in enumerate(ins)]
+            dev_in[0].copy_(to_device(ops, cur)[0])
+            for t in outs:
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, ref in zip(outs, interp.run(ops, cur)):
+                assert_close(got.double().cpu().numpy(), ref, TOLERANCE["f32"], f"fused program graph replay {rep}")
+        def timed(fn, n=200):
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / n * 1e6
+        eager_us, graph_us = timed(prog.run_bound), timed(graph.replay)
+        announce(f"  {len(prog.plans)} groups, {prog.n_kernels} kernels: {eager_us:.1f} us launched one by one, {graph_us:.1f} us as a graph")

@@ -488,3 +488,39 @@ def test_launch_on_a_side_stream():
         s.synchronize()
     (want,) = interp.run(ops, ins)
     assert_close(dev_out[0].double().cpu().numpy(), want, 1e-5, "side stream")
+
+
+# ---------------------------------------------------------------- launches recorded into a HIP graph
+
+@pytest.mark.parametrize("name", ["scaled_masked_softmax", "layernorm_bwd", "causal_attention", "multi_tensor_momentum"])
+def test_launches_replay_from_a_captured_graph(name):
+    """After one ordinary launch (which loads the kernels and allocates the plan's workspace) a launch is
+    nothing but kernel launches on the caller's stream, so it can be recorded into a HIP graph.
+    The graph is replayed three times, with eager work and new input values between the replays,
+    and every replay is compared with the oracle."""
+    announce(f"graph capture {name}")
+    cfg = BY_NAME[name]
+    ops, ins = cfg.build("small")
+    tol = TOLERANCE[cfg.dtype]
+    dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)
+    with Plan(ops) as plan:
+        plan.launch(dev_in, dev_out)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            plan.launch(dev_in, dev_out)                      # torch's current stream is the capturing one here
+        for rep in range(3):
+            # new values in the same buffers: the first tensor is scaled, eagerly, between replays
+            scale = [1.0, 0.5, -1.5][rep]
+            cur = [a * scale if k == 0 else a for k, a in enumerate(ins)]
+            cur[0] = inputs.round_to(cur[0], ops[0].dtype)
+            dev_in[0].copy_(to_device(ops, cur)[0])
+            for t in dev_out:
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = interp.run(ops, cur)
+            for got, ref in zip(dev_out, want):
+                assert_close(got.double().cpu().numpy(), ref, tol, f"graph replay {rep} of {name}")
