@@ -473,7 +473,7 @@ std::string op_text(int op, const std::string& a, const std::string& b, bool fas
     case FS_NEGATE: return "-" + a;
     case FS_EXP: return "expf(" + a + ")";
     case FS_LOG: return "logf(" + a + ")";
-    case FS_TANH: return (fast ? "tanh_fast(" : "tanhf(") + a + ")";
+    case FS_TANH: return (fast ? "tanh_fast(" : "tanh_f32(") + a + ")";
     case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";

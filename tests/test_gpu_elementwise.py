@@ -293,3 +293,22 @@ def test_update_in_place_where_the_kernel_reads_before_it_writes():
     with Plan(g.ops) as p:
         with pytest.raises(FsError):
             p.launch(dev, [dev[1], torch.empty_like(dev[0])])
+
+
+def test_tanh_of_fp32_groups_is_accurate_relative_to_its_value():
+    """The generated kernels' tanh for fp32 groups (a short series near zero, the exponential form
+    elsewhere): scaled by 1e4 the comparison bar 1e-5 + 1e-5*|ref| asks for about 1e-5 relative accuracy of
+    tanh itself, from 1e-7 to saturation, both signs."""
+    x = np.concatenate([np.logspace(-7, 1.5, 4093), -np.logspace(-7, 1.5, 4093), [0.0, -0.0, 0.3, -0.3, 0.29999998, 88.0, -1e6, 1e30]])
+    x = inputs.round_to(x, "f32").reshape(2, -1)
+    for build in ("elementwise", "row"):
+        g = graphs.Graph()
+        p = g.parameter("x", "f32", x.shape)
+        t = g.multiply(g.tanh(p), g.constant(1e4))
+        g.output(t, "t")
+        if build == "row":
+            g.output(g.reduce_max(t, -1), "m")
+        announce(f"tanh accuracy, {build} group")
+        with Plan(g.ops) as plan:
+            assert "generated kernel" in plan.describe()
+        check_against_oracle(g.ops, [x], what=f"tanh accuracy ({build})")
