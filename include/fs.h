@@ -200,6 +200,20 @@ fs_status fs_tune_cache_clear(void);
 fs_status fs_tune_cache_save(const char* path);
 fs_status fs_tune_cache_load(const char* path);
 
+/* Generated kernels are compiled once per process and source text.  With a cache directory they are
+ * also compiled once per machine: fs_plan_create looks for the code object of a generated source in
+ * that directory before it runs the compiler, and leaves it there afterwards (one file per kernel,
+ * named after a hash of source, compile options and compiler version; written under a temporary
+ * name and renamed, so concurrent processes are safe; a damaged or foreign file is ignored and
+ * replaced).  The directory comes from the environment variable FS_KERNEL_CACHE_DIR unless
+ * fs_kernel_cache_dir sets it (NULL or "" turns the disk cache off).  The directory must exist.
+ *   fs_kernel_cache_stats        any out-pointer may be NULL: kernels compiled, found in this
+ *                                process's memory, found on disk, since the library was loaded
+ *   fs_kernel_cache_drop_memory  forget the per-process copies (the files stay) */
+fs_status fs_kernel_cache_dir(const char* dir);
+fs_status fs_kernel_cache_stats(int64_t* compiled, int64_t* from_memory, int64_t* from_disk);
+fs_status fs_kernel_cache_drop_memory(void);
+
 /* Release the plan and its workspace.  NULL is a no-op.  The caller makes sure no
  * launch of the plan is still running. */
 fs_status fs_destroy(fs_plan* plan);

@@ -82,6 +82,12 @@ def lib():
         L.fs_plan_tune.restype = i32
         L.fs_stream_copy.argtypes = [vp, vp, i64, vp]
         L.fs_stream_copy.restype = i32
+        L.fs_kernel_cache_dir.argtypes = [C.c_char_p]
+        L.fs_kernel_cache_dir.restype = i32
+        L.fs_kernel_cache_stats.argtypes = [C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+        L.fs_kernel_cache_stats.restype = i32
+        L.fs_kernel_cache_drop_memory.argtypes = []
+        L.fs_kernel_cache_drop_memory.restype = i32
         L.fs_group_key.argtypes = [C.POINTER(fs_op_desc), i32, C.POINTER(C.c_uint64)]
         L.fs_group_key.restype = i32
         L.fs_tune_cache_size.argtypes = []
@@ -210,6 +216,22 @@ def fs_shared_plan(operands, req_bytes, is_output=None):
     total = C.c_int64(0)
     _check(lib().fs_shared_plan(ops, req, outs, n, off, shr, C.byref(total)))
     return list(off[:n]), list(shr[:n]), total.value
+
+
+def fs_kernel_cache_dir(path):
+    """Directory for compiled kernels shared between processes (None turns it off)."""
+    _check(lib().fs_kernel_cache_dir(None if path is None else str(path).encode()))
+
+
+def fs_kernel_cache_stats():
+    """-> dict(compiled, from_memory, from_disk): where generated kernels came from so far."""
+    c, m, d = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib().fs_kernel_cache_stats(C.byref(c), C.byref(m), C.byref(d)))
+    return {"compiled": c.value, "from_memory": m.value, "from_disk": d.value}
+
+
+def fs_kernel_cache_drop_memory():
+    _check(lib().fs_kernel_cache_drop_memory())
 
 
 def fs_group_key(ops):

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/fs.h"
+#include "ew_ir.h"
 #include "graph.h"
 #include "launchers.h"
 #include "match.h"
@@ -101,6 +102,21 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
     if (hit && plan_create_impl(ops, n_ops, &e.opt, out) == FS_OK) return FS_OK;
   }
   return plan_create_impl(ops, n_ops, opt, out);
+}
+
+fs_status fs_kernel_cache_dir(const char* dir) {
+  fs::codegen_cache_dir(dir);
+  return FS_OK;
+}
+
+fs_status fs_kernel_cache_stats(int64_t* compiled, int64_t* from_memory, int64_t* from_disk) {
+  fs::codegen_cache_stats(compiled, from_memory, from_disk);
+  return FS_OK;
+}
+
+fs_status fs_kernel_cache_drop_memory(void) {
+  fs::codegen_cache_drop_memory();
+  return FS_OK;
 }
 
 fs_status fs_group_key(const fs_op_desc* ops, int32_t n_ops, uint64_t* key) {

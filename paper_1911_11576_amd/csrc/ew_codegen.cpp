@@ -11,6 +11,7 @@
 
 #include <hip/hip_runtime.h>
 #include <hip/hiprtc.h>
+#include <unistd.h>
 
 #include <cstdarg>
 #include <cstdio>
@@ -317,23 +318,119 @@ namespace {
 std::mutex g_cache_mutex;
 std::map<std::string, std::shared_ptr<std::vector<char>>> g_cache;
 thread_local bool g_dry_run = false;
+// Code objects on disk, so that a later process does not compile again what this one compiled:
+// one file per generated source, named after a hash of the source and the compile options.
+std::string g_disk_dir;
+bool g_disk_dir_set = false;
+int64_t g_stat_compiled = 0, g_stat_memory = 0, g_stat_disk = 0;
+const char* const kCompileOptions[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+
+uint64_t fnv(const std::string& text, uint64_t h) {
+  for (unsigned char c : text) { h ^= c; h *= 1099511628211ull; }
+  return h;
+}
+
+std::string disk_dir_locked() {
+  if (!g_disk_dir_set) {
+    if (const char* env = getenv("FS_KERNEL_CACHE_DIR")) g_disk_dir = env;
+    g_disk_dir_set = true;
+  }
+  return g_disk_dir;
+}
+
+// what the file must belong to: the source, the options, the compiler's version
+std::string cache_identity(const std::string& source) {
+  int major = 0, minor = 0;
+  (void)hiprtcVersion(&major, &minor);
+  std::string id = "fs-code-object 1;hiprtc " + std::to_string(major) + "." + std::to_string(minor) + ";";
+  for (const char* o : kCompileOptions) { id += o; id += ' '; }
+  return id + "\n" + source;
+}
+
+std::string cache_path(const std::string& dir, const std::string& identity) {
+  char name[48];
+  snprintf(name, sizeof name, "/fs_%016llx.co", (unsigned long long)fnv(identity, 1469598103934665603ull));
+  return dir + name;
+}
+
+struct DiskHeader { char magic[8]; uint64_t check; uint64_t identity_bytes; uint64_t code_bytes; };
+
+bool disk_load(const std::string& path, const std::string& identity, std::vector<char>* code) {
+  FILE* f = fopen(path.c_str(), "rb");
+  if (!f) return false;
+  DiskHeader h{};
+  bool ok = fread(&h, sizeof h, 1, f) == 1 && memcmp(h.magic, "FSCODE1", 8) == 0 && h.identity_bytes == identity.size() &&
+            h.check == fnv(identity, 0x9e3779b97f4a7c15ull) && h.code_bytes > 0 && h.code_bytes < (64u << 20);
+  if (ok) {
+    code->resize(h.code_bytes);
+    ok = fread(code->data(), 1, h.code_bytes, f) == h.code_bytes && fgetc(f) == EOF;
+  }
+  fclose(f);
+  if (!ok) code->clear();
+  return ok;
+}
+
+void disk_store(const std::string& path, const std::string& identity, const std::vector<char>& code) {
+  char tmp[32];
+  snprintf(tmp, sizeof tmp, ".tmp.%ld", (long)getpid());
+  const std::string part = path + tmp;
+  FILE* f = fopen(part.c_str(), "wb");
+  if (!f) return;                               // an unwritable directory costs the next process a compile, nothing else
+  DiskHeader h{};
+  memcpy(h.magic, "FSCODE1", 8);
+  h.check = fnv(identity, 0x9e3779b97f4a7c15ull);
+  h.identity_bytes = identity.size();
+  h.code_bytes = code.size();
+  const bool ok = fwrite(&h, sizeof h, 1, f) == 1 && fwrite(code.data(), 1, code.size(), f) == code.size();
+  if (fclose(f) != 0 || !ok || rename(part.c_str(), path.c_str()) != 0) (void)remove(part.c_str());
+}
 }  // namespace
 
 void codegen_set_dry_run(bool on) { g_dry_run = on; }
 
+void codegen_cache_dir(const char* dir) {
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  g_disk_dir = dir ? dir : "";
+  g_disk_dir_set = true;
+}
+
+void codegen_cache_drop_memory() {
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  g_cache.clear();
+}
+
+void codegen_cache_stats(int64_t* compiled, int64_t* from_memory, int64_t* from_disk) {
+  std::lock_guard<std::mutex> lock(g_cache_mutex);
+  if (compiled) *compiled = g_stat_compiled;
+  if (from_memory) *from_memory = g_stat_memory;
+  if (from_disk) *from_disk = g_stat_disk;
+}
+
 bool ew_compile_source(const std::string& source, std::vector<char>* code_object, std::string* err) {
   if (g_dry_run) { code_object->clear(); return true; }     // planning only: the source exists, that is enough
+  std::string dir;
   {
     std::lock_guard<std::mutex> lock(g_cache_mutex);
     auto it = g_cache.find(source);
-    if (it != g_cache.end()) { *code_object = *it->second; return true; }
+    if (it != g_cache.end()) { *code_object = *it->second; ++g_stat_memory; return true; }
+    dir = disk_dir_locked();
+  }
+  std::string identity, path;
+  if (!dir.empty()) {
+    identity = cache_identity(source);
+    path = cache_path(dir, identity);
+    if (disk_load(path, identity, code_object)) {
+      std::lock_guard<std::mutex> lock(g_cache_mutex);
+      g_cache[source] = std::make_shared<std::vector<char>>(*code_object);
+      ++g_stat_disk;
+      return true;
+    }
   }
   hiprtcProgram prog = nullptr;
   hiprtcResult r = hiprtcCreateProgram(&prog, source.c_str(), "fs_ew.hip", 0, nullptr, nullptr);
   if (r != HIPRTC_SUCCESS) { *err = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r); return false; }
   // same code generation rules as the library's own kernels: gfx950 only, packed fp32 math off
-  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-  r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+  r = hiprtcCompileProgram(prog, (int)(sizeof kCompileOptions / sizeof kCompileOptions[0]), const_cast<const char**>(kCompileOptions));
   if (r != HIPRTC_SUCCESS) {
     size_t n = 0;
     std::string log;
@@ -353,8 +450,10 @@ bool ew_compile_source(const std::string& source, std::vector<char>* code_object
   }
   (void)hiprtcDestroyProgram(&prog);
   if (r != HIPRTC_SUCCESS) { *err = std::string("hiprtcGetCode: ") + hiprtcGetErrorString(r); return false; }
+  if (!path.empty()) disk_store(path, identity, *code_object);
   std::lock_guard<std::mutex> lock(g_cache_mutex);
   g_cache[source] = std::make_shared<std::vector<char>>(*code_object);
+  ++g_stat_compiled;
   return true;
 }
 

@@ -60,6 +60,12 @@ bool ew_compile_source(const std::string& source, std::vector<char>* code_object
 // While on (per thread), ew_compile_source succeeds without compiling: plans made then can be
 // inspected but not launched.  Used by the fusion planner to ask "can this group be generated".
 void codegen_set_dry_run(bool on);
+// Code objects on disk (directory from FS_KERNEL_CACHE_DIR unless set here; NULL or "" turns it off),
+// the per-process cache emptied (the files stay), and how often a kernel was compiled, found in
+// memory, found on disk.
+void codegen_cache_dir(const char* dir);
+void codegen_cache_drop_memory();
+void codegen_cache_stats(int64_t* compiled, int64_t* from_memory, int64_t* from_disk);
 
 // A loaded kernel (module handle and function), bound to the device current at load time.
 struct EwModule {

@@ -418,3 +418,52 @@ def test_tuning_cache_on_the_host(tmp_path):
         fs_tune_cache_save(tmp_path / "no_such_dir" / "x.txt")
     assert fs_tune_cache_size() == 1
     fs_tune_cache_clear()
+
+
+def test_compiled_kernels_are_kept_on_disk_between_processes(tmp_path):
+    """The kernel cache directory: a generated kernel is compiled once, found in memory after that,
+    and found on disk by a process (here: after dropping the in-memory copies) that has not compiled it."""
+    import time
+    from paper_1911_11576_amd import fs_kernel_cache_dir, fs_kernel_cache_drop_memory, fs_kernel_cache_stats
+    ops = graphs.log_softmax((41, 1234))                       # a shape nothing else in the suite uses
+    try:
+        fs_kernel_cache_dir(tmp_path)
+        fs_kernel_cache_drop_memory()
+        s0 = fs_kernel_cache_stats()
+        t0 = time.perf_counter()
+        with Plan(ops) as p:
+            first = p.describe()
+        t_compile = time.perf_counter() - t0
+        s1 = fs_kernel_cache_stats()
+        assert s1["compiled"] == s0["compiled"] + 1 and s1["from_disk"] == s0["from_disk"]
+        files = sorted(tmp_path.glob("fs_*.co"))
+        assert len(files) == 1 and files[0].stat().st_size > 1000 and not list(tmp_path.glob("*.tmp.*"))
+        with Plan(ops) as p:                                    # same process: memory
+            assert p.describe() == first
+        s2 = fs_kernel_cache_stats()
+        assert s2["from_memory"] == s1["from_memory"] + 1 and s2["compiled"] == s1["compiled"]
+        fs_kernel_cache_drop_memory()                           # as a new process would start
+        t0 = time.perf_counter()
+        with Plan(ops) as p:
+            assert p.describe() == first                        # same code object: same size in the description
+        t_disk = time.perf_counter() - t0
+        s3 = fs_kernel_cache_stats()
+        assert s3["from_disk"] == s2["from_disk"] + 1 and s3["compiled"] == s2["compiled"]
+        assert t_disk < t_compile / 3, (t_disk, t_compile)
+        # a damaged file is ignored and replaced
+        files[0].write_bytes(files[0].read_bytes()[:200])
+        fs_kernel_cache_drop_memory()
+        with Plan(ops) as p:
+            assert p.describe() == first
+        s4 = fs_kernel_cache_stats()
+        assert s4["compiled"] == s3["compiled"] + 1 and files[0].stat().st_size > 1000
+        # without a directory nothing is read or written
+        fs_kernel_cache_dir(None)
+        fs_kernel_cache_drop_memory()
+        for f in tmp_path.glob("fs_*.co"):
+            f.unlink()
+        with Plan(ops) as p:
+            pass
+        assert not list(tmp_path.glob("fs_*.co")) and fs_kernel_cache_stats()["compiled"] == s4["compiled"] + 1
+    finally:
+        fs_kernel_cache_dir(None)
