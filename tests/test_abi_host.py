@@ -467,3 +467,28 @@ def test_compiled_kernels_are_kept_on_disk_between_processes(tmp_path):
         assert not list(tmp_path.glob("fs_*.co")) and fs_kernel_cache_stats()["compiled"] == s4["compiled"] + 1
     finally:
         fs_kernel_cache_dir(None)
+
+
+def test_plans_are_created_concurrently_from_several_threads():
+    """Plan creation is thread-safe: run-time compilation, the kernel and tuning caches, the per-thread
+    error message."""
+    import threading
+    problems = []
+
+    def work(k):
+        try:
+            for j in range(2):
+                with Plan(graphs.log_softmax((50 + k, 96 + 8 * j))) as p:
+                    assert "generated kernel" in p.describe() and p.info()["algorithmic_bytes"] == 2 * (50 + k) * (96 + 8 * j) * 4
+                with pytest.raises(FsError) as e:                   # each thread sees its own message
+                    Plan(graphs.log_softmax((50 + k, 96)), wg_size=100 + k)
+                assert "wg_size" in e.value.message
+        except Exception as exc:            # collected, not raised in the thread
+            problems.append((k, repr(exc)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not problems, problems
