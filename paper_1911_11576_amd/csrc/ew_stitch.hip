@@ -653,8 +653,14 @@ static bool ew_plan_packed(const Graph& g, const LaunchOpts& opt, EwLaunch* out,
       if (probe.is_compute(a)) part[find(i)] = find(a);
     }
   }
+  // parts that reach no output compute nothing anyone sees: left out
+  std::vector<char> reaches_output(n, 0);
+  for (int o : g.outputs) {
+    const int src = probe.canon(g[o].operand[0]);
+    if (part[src] >= 0) reaches_output[find(src)] = 1;
+  }
   std::vector<int> roots;
-  for (int i = 0; i < n; ++i) if (part[i] >= 0 && find(i) == i) roots.push_back(i);
+  for (int i = 0; i < n; ++i) if (part[i] >= 0 && find(i) == i && reaches_output[i]) roots.push_back(i);
   if (roots.size() < 2) { *err = "elementwise schedule: ops of different shapes in one group"; return false; }
   if (roots.size() > 16) { *err = "elementwise schedule: more than 16 independent parts in one group"; return false; }
   if (g.outputs.size() > 16) { *err = "elementwise schedule: more than 16 outputs"; return false; }
@@ -711,7 +717,8 @@ bool ew_stitch_plan(const Graph& g, const LaunchOpts& opt, EwLaunch* out, int* s
       std::string perr;
       int pst = FS_ERR_UNSUPPORTED;
       if (ew_plan_packed(g, opt, out, &pst, &perr)) { *status = FS_OK; return true; }
-      if (pst == FS_ERR_INVALID) { *status = pst; *err = perr; }
+      if (pst == FS_ERR_INVALID) *status = pst;
+      if (perr != cc.err) *err = cc.err + " (as independent parts: " + perr + ")";
     }
     return false;
   }

@@ -93,3 +93,18 @@ def test_random_groups_wide_pool(seed):
     except FsError as e:
         # the one documented limit this pool reaches
         assert e.status == binding.FS_ERR_UNSUPPORTED and "column reductions over rows longer" in e.message
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_packed_elementwise_parts(seed):
+    """Independent elementwise computations of different shapes and dtypes in one op list: one kernel,
+    each part on its own run of workgroups."""
+    import numpy as np
+    rng = random.Random(5000 + seed)
+    ops, pshapes, pdtypes = graphs.random_elementwise_parts(rng)
+    r = np.random.default_rng(seed)
+    ins = [inputs.round_to(r.normal(0.0, 1.0, s), dt) for s, dt in zip(pshapes, pdtypes)]
+    announce(f"random packed parts seed {seed}: {len(ops)} ops, shapes {pshapes[::3]}")
+    with Plan(ops) as p:
+        assert p.info()["schedule"] == "elementwise" and p.info()["n_kernels"] == 1
+    check_against_oracle(ops, ins, what=f"random packed parts {seed}")

@@ -813,3 +813,43 @@ def random_program(rng, rows, cols, n_ops=30):
             renumber[i] = len(kept)
             kept.append(Op(op.kind, op.dtype, op.shape, tuple(renumber[o] for o in op.operands), op.axis, op.attr, op.name))
     return kept, [(rows, cols), (rows, cols), (rows,), (cols,)]
+
+
+def random_elementwise_parts(rng, n_parts=None):
+    """Several independent all-elementwise computations of different shapes and dtypes in one op
+    list (the kernel packing case): per part two full operands, a per-column operand broadcast in,
+    a random chain of ops, one or two outputs.  Returns (ops, parameter shapes, parameter dtypes)."""
+    g = Graph()
+    shapes_pool = [(37, 128), (5,), (3, 7, 64), (300, 8), (33, 100), (1,), (64, 64), (2, 3, 5, 32), (129, 16), (4096,)]
+    n_parts = n_parts or rng.randint(2, 6)
+    pshapes, pdtypes, n_out = [], [], 0
+    for k in range(n_parts):
+        shape = rng.choice(shapes_pool)
+        dt = rng.choice(["f32", "f32", "bf16", "f16"])
+        a = g.parameter(f"a{k}", dt, shape)
+        b = g.parameter(f"b{k}", dt, shape)
+        c = g.parameter(f"c{k}", dt, shape[-1:])
+        pshapes += [shape, shape, shape[-1:]]
+        pdtypes += [dt, dt, dt]
+        conv = (lambda t: t) if dt == "f32" else (lambda t: g.convert(t, "f32"))
+        vals = [conv(a), conv(b)]
+        cb = g.broadcast(conv(c), shape, len(shape) - 1) if len(shape) > 1 else conv(c)
+        for _ in range(rng.randint(2, 8)):
+            kind = rng.choice(["bin", "bin", "un", "col", "const"])
+            if kind == "bin":
+                vals.append(getattr(g, rng.choice(["add", "subtract", "multiply", "maximum"]))(rng.choice(vals), rng.choice(vals)))
+            elif kind == "un":
+                v = rng.choice(vals)
+                vals.append(rng.choice([lambda: g.tanh(v), lambda: g.exp(g.tanh(v)), lambda: g.negate(v),
+                                        lambda: g.rsqrt(g.add(g.multiply(v, v), g.constant(1.0)))])())
+            elif kind == "col":
+                vals.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(vals), cb))
+            else:
+                vals.append(getattr(g, rng.choice(["add", "multiply"]))(rng.choice(vals), g.constant(rng.choice([0.5, -1.25, 2.0]))))
+        outs = [vals[-1]] if len(vals) < 4 or n_out >= 14 or rng.random() < 0.5 else [vals[-1], vals[-3]]
+        for o in dict.fromkeys(outs):
+            if o in (vals[0], vals[1]):
+                o = g.add(vals[0], vals[1])
+            g.output(o if dt == "f32" else g.convert(o, dt))
+            n_out += 1
+    return g.ops, pshapes, pdtypes
