@@ -54,6 +54,7 @@ typedef enum {
  *  FS_DOT         batched matrix product a[B,M,K] . b[B,K,N]; axis==1: b is stored
  *                 [B,N,K] and the contraction runs over the last dim of both
  *  FS_CAUSAL_MASK x[..., i, j] is kept where j <= i and replaced by `attr` elsewhere
+ *  FS_ERF / FS_LOGISTIC   unary like FS_TANH: erf(x); 1 / (1 + exp(-x))
  *  FS_OUTPUT      marks operand 0 as a group output; the i-th output op is outputs[i]
  */
 typedef enum {
@@ -63,7 +64,8 @@ typedef enum {
   FS_CONVERT = 13, FS_BROADCAST = 14,
   FS_REDUCE_SUM = 15, FS_REDUCE_MAX = 16,
   FS_DOT = 17, FS_CAUSAL_MASK = 18, FS_OUTPUT = 19,
-  FS_NUM_OPKINDS = 20
+  FS_ERF = 20, FS_LOGISTIC = 21,   /* unary, like FS_TANH: the error function; 1 / (1 + exp(-x)) */
+  FS_NUM_OPKINDS = 22
 } fs_opkind;
 
 /* One op.  Plain data, caller-owned, copied by fs_plan_create.  `operand` holds

@@ -27,6 +27,8 @@ every group against the matching PyTorch CPU library routine.
 """
 from __future__ import annotations
 
+import math
+
 import numpy as np
 
 
@@ -73,7 +75,13 @@ _BINARY = {
 _UNARY = {
     "negate": np.negative, "exp": np.exp, "log": np.log, "tanh": np.tanh,
     "sqrt": np.sqrt, "rsqrt": lambda a: 1.0 / np.sqrt(a),
+    "erf": lambda a: _erf(a), "logistic": lambda a: 1.0 / (1.0 + np.exp(-a)),
 }
+
+
+def _erf(a):
+    """erf(x) = (2/sqrt(pi)) * integral from 0 to x of exp(-t^2) dt, element by element from the C library."""
+    return np.vectorize(math.erf, otypes=[np.float64])(np.asarray(a, dtype=np.float64))
 
 
 def run(ops, inputs, storage_rounding=False, keep=False):

@@ -23,7 +23,7 @@ DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 OPKINDS = {name: i for i, name in enumerate((
     "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum", "negate",
     "exp", "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast", "reduce_sum", "reduce_max",
-    "dot", "causal_mask", "output"))}
+    "dot", "causal_mask", "output", "erf", "logistic"))}
 
 
 class fs_op_desc(C.Structure):

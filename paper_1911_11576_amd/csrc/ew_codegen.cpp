@@ -73,6 +73,10 @@ static __device__ __forceinline__ float tanh_f32(float x) {
   const float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
   return ax < 0.3f ? p : __builtin_copysignf(t, x);
 }
+// 1 / (1 + e^-x): exp2 overflow (x very negative) gives rcp(inf) = 0
+static __device__ __forceinline__ float logistic(float x) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f));
+}
 // mul*h / (1 + exp2(h*(a0 + a1*h*h))), the tanh-form GELU; exp2 overflow gives rcp(inf) = 0
 static __device__ __forceinline__ float gelu_tanh(float h, float mul, float a0, float a1) {
   const float e = __builtin_amdgcn_exp2f(h * (a0 + a1 * (h * h)));
@@ -110,6 +114,8 @@ std::string op_text(const EwIrNode& n, bool fast) {
     case FS_TANH: return (fast ? "tanh_fast(" : "tanh_f32(") + a + ")";
     case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
+    case FS_ERF: return "erff(" + a + ")";
+    case FS_LOGISTIC: return "logistic(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
     case EW_OP_GELU_TANH: {

@@ -118,6 +118,8 @@ __device__ __forceinline__ void ew_alu_self(int op, ew_vec<N>& acc) {
     case FS_TANH: EW_FOR_ALL(tanhf(p)) break;
     case FS_RSQRT: EW_FOR_ALL(1.f / sqrtf(p)) break;
     case FS_SQRT: EW_FOR_ALL(sqrtf(p)) break;
+    case FS_ERF: EW_FOR_ALL(erff(p)) break;
+    case FS_LOGISTIC: EW_FOR_ALL(1.f / (1.f + expf(-p))) break;
     case EW_ROUND_F16: EW_FOR_ALL(f16_to_f32(f32_to_f16(p))) break;
     case EW_ROUND_BF16: EW_FOR_ALL(bf16_to_f32(f32_to_bf16(p))) break;
     default: break;              // maximum(x, x) = x

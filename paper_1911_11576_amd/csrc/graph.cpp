@@ -10,7 +10,7 @@ const char* kind_name(int k) {
   static const char* names[FS_NUM_OPKINDS] = {
       "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum", "negate", "exp",
       "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast", "reduce_sum", "reduce_max", "dot",
-      "causal_mask", "output"};
+      "causal_mask", "output", "erf", "logistic"};
   return (k >= 0 && k < FS_NUM_OPKINDS) ? names[k] : "?";
 }
 
@@ -84,7 +84,7 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
         if (!cb && !(b->same_shape(n) && b->dtype == n.dtype)) return fail("operand 1 shape/dtype differs from result");
         break;
       }
-      case FS_NEGATE: case FS_EXP: case FS_LOG: case FS_TANH: case FS_RSQRT: case FS_SQRT:
+      case FS_NEGATE: case FS_EXP: case FS_LOG: case FS_TANH: case FS_RSQRT: case FS_SQRT: case FS_ERF: case FS_LOGISTIC:
         if (!(a->same_shape(n) && a->dtype == n.dtype)) return fail("operand shape/dtype differs from result");
         break;
       case FS_CONVERT:

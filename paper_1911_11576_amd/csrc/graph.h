@@ -39,7 +39,7 @@ struct Graph {
 bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* err);
 
 inline bool is_binary(int k) { return k >= FS_ADD && k <= FS_MAXIMUM; }
-inline bool is_unary(int k) { return k >= FS_NEGATE && k <= FS_SQRT; }
+inline bool is_unary(int k) { return (k >= FS_NEGATE && k <= FS_SQRT) || k == FS_ERF || k == FS_LOGISTIC; }
 // how many entries of Node::operand an op of this kind reads
 inline int operand_count(int k) { return k == FS_PARAMETER || k == FS_CONSTANT ? 0 : (is_binary(k) || k == FS_DOT) ? 2 : 1; }
 const char* kind_name(int k);

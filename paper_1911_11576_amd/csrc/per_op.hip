@@ -60,6 +60,8 @@ __device__ __forceinline__ float ew_apply(int kind, float x, float y) {
     case FS_TANH: return tanhf(x);
     case FS_RSQRT: return 1.f / sqrtf(x);
     case FS_SQRT: return sqrtf(x);
+    case FS_ERF: return erff(x);
+    case FS_LOGISTIC: return 1.f / (1.f + expf(-x));
     default: return x;   // convert, copy
   }
 }

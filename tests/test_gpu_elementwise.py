@@ -312,3 +312,27 @@ def test_tanh_of_fp32_groups_is_accurate_relative_to_its_value():
         with Plan(g.ops) as plan:
             assert "generated kernel" in plan.describe()
         check_against_oracle(g.ops, [x], what=f"tanh accuracy ({build})")
+
+
+# ---------------------------------------------------------------- erf and logistic
+
+@pytest.mark.parametrize("mode", MODES + ["per_op"])
+@pytest.mark.parametrize("dtype,shape", [("bf16", (203, 1024)), ("f32", (33, 100)), ("f16", (5, 7, 9))])
+def test_swiglu(dtype, shape, mode):
+    ops = graphs.swiglu(shape, dtype)
+    ins = inputs.normal_tensors([shape, shape], dtype, scale=3.0, seed_offset=61)
+    announce(f"swiglu {dtype} {shape} {mode}")
+    check_against_oracle(ops, ins, mode, what=f"swiglu {dtype} {shape}")
+
+
+@pytest.mark.parametrize("mode", MODES + ["per_op"])
+def test_erf_and_logistic_over_their_whole_range(mode):
+    x = np.concatenate([np.linspace(-6.0, 6.0, 2041), [-100.0, -20.0, 20.0, 100.0, 0.0, -0.0, 1e-8]]).reshape(1, -1)
+    x = inputs.round_to(np.repeat(x, 2, axis=0), "f32")
+    g = graphs.Graph()
+    p = g.parameter("x", "f32", x.shape)
+    g.output(g.erf(p), "erf")
+    g.output(g.logistic(p), "logistic")
+    g.output(g.multiply(g.multiply(p, g.constant(0.5)), g.add(g.erf(g.multiply(p, g.constant(0.7071067811865476))), g.constant(1.0))), "gelu")
+    announce(f"erf and logistic {mode}")
+    check_against_oracle(g.ops, [x], mode, what="erf / logistic / exact gelu")

@@ -180,3 +180,44 @@ def test_shape_mismatch_is_an_error():
     g.output(g.parameter("a", "f32", (2, 3)))
     with pytest.raises(ValueError):
         interp.run(g.ops, [np.zeros((3, 2))])
+
+
+def test_erf_against_its_integral_its_series_and_another_library():
+    """erf(x) = 2/sqrt(pi) * integral_0^x exp(-t^2) dt: Simpson's rule with 20 000 panels, the Maclaurin series
+    sum (-1)^n x^(2n+1) / (n! (2n+1)), scipy's routine, oddness and the limits."""
+    from scipy import special
+    x = np.array([[-3.0, -1.0, -0.5, 0.0], [0.25, 0.5, 1.0, 2.5]])
+
+    def build(g):
+        g.output(g.erf(g.parameter("a", "f32", x.shape)))
+    (out,) = _run1(build, x)
+    for xi, got in zip(x.ravel(), out.ravel()):
+        t = np.linspace(0.0, xi, 20001)
+        f = np.exp(-t * t)
+        h = (xi - 0.0) / 20000
+        simpson = h / 3.0 * (f[0] + f[-1] + 4.0 * f[1:-1:2].sum() + 2.0 * f[2:-1:2].sum()) * 2.0 / math.sqrt(math.pi)
+        series = 2.0 / math.sqrt(math.pi) * sum((-1) ** n * xi ** (2 * n + 1) / (math.factorial(n) * (2 * n + 1)) for n in range(80))
+        assert got == pytest.approx(simpson, abs=1e-12)
+        assert got == pytest.approx(series, abs=1e-10)
+        assert got == pytest.approx(float(special.erf(xi)), abs=1e-15)
+    assert out[0, 3] == 0.0 and np.allclose(out[0, :3], -np.array([out_v for out_v in (1 - 2.209049699858544e-05, 0.8427007929497149, 0.5204998778130465)]), atol=1e-15)
+
+    def far(g):
+        g.output(g.erf(g.parameter("a", "f32", (1, 2))))
+    (lim,) = _run1(far, np.array([[30.0, -30.0]]))
+    assert lim.tolist() == [[1.0, -1.0]]
+
+
+def test_logistic_identities():
+    """1/(1+exp(-x)): value 1/2 at 0, s(x) + s(-x) = 1, s(x) = (1 + tanh(x/2))/2, limits 0 and 1."""
+    x = np.array([[-40.0, -2.0, -0.5, 0.0], [0.5, 1.0, 3.0, 40.0]])
+
+    def build(g):
+        g.output(g.logistic(g.parameter("a", "f32", x.shape)))
+    (s,) = _run1(build, x)
+    (sm,) = _run1(build, -x)
+    assert s[0, 3] == 0.5
+    assert np.allclose(s + sm, 1.0, atol=1e-15)
+    assert np.allclose(s, 0.5 * (1.0 + np.tanh(x / 2.0)), atol=1e-15)
+    assert s[0, 0] == pytest.approx(math.exp(-40.0), rel=1e-12) and s[1, 3] == pytest.approx(1.0, abs=1e-15)
+    assert s[1, 1] == pytest.approx(0.7310585786300049, abs=1e-15)        # 1/(1+1/e)

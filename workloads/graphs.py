@@ -32,7 +32,7 @@ Op = namedtuple("Op", "kind dtype shape operands axis attr name")
 KINDS = (
     "parameter", "constant", "add", "subtract", "multiply", "divide", "maximum",
     "negate", "exp", "log", "tanh", "rsqrt", "sqrt", "convert", "broadcast",
-    "reduce_sum", "reduce_max", "dot", "causal_mask", "output",
+    "reduce_sum", "reduce_max", "dot", "causal_mask", "output", "erf", "logistic",
 )
 DTYPES = ("f32", "f16", "bf16")
 
@@ -85,6 +85,8 @@ class Graph:
     def tanh(self, a): return self._unary("tanh", a)
     def rsqrt(self, a): return self._unary("rsqrt", a)
     def sqrt(self, a): return self._unary("sqrt", a)
+    def erf(self, a): return self._unary("erf", a)
+    def logistic(self, a): return self._unary("logistic", a)
 
     def convert(self, a, dtype):
         return self._new("convert", dtype, self.shape(a), (a,))
@@ -322,6 +324,35 @@ def adam_update(shape, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, dtype="f32"):
     g.output(p2, "p")
     g.output(m2, "m")
     g.output(v2, "v")
+    return g.ops
+
+
+def swiglu(shape, dtype="bf16"):
+    """y = silu(a) * b = a * logistic(a) * b: the gated activation of LLaMA-style MLPs, an
+    all-elementwise group with two full operands."""
+    g = Graph()
+    a = g.parameter("a", dtype, shape)
+    b = g.parameter("b", dtype, shape)
+    af, bf = (a, b) if dtype == "f32" else (g.convert(a, "f32"), g.convert(b, "f32"))
+    y = g.multiply(g.multiply(af, g.logistic(af)), bf)
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
+    return g.ops
+
+
+def bias_gelu_erf_residual_layernorm(rows, cols, dtype="bf16", eps=1e-5):
+    """Config 4 with the exact GELU, 0.5 h (1 + erf(h / sqrt 2)), in place of the tanh form."""
+    g = Graph()
+    x = g.parameter("x", dtype, (rows, cols))
+    bias = g.parameter("bias", dtype, (cols,))
+    res = g.parameter("residual", dtype, (rows, cols))
+    gamma = g.parameter("gamma", dtype, (cols,))
+    beta = g.parameter("beta", dtype, (cols,))
+    if dtype != "f32":
+        x, bias, res, gamma, beta = (g.convert(t, "f32") for t in (x, bias, res, gamma, beta))
+    h = g.add(x, g.col_broadcast(bias, x))
+    gelu = g.multiply(g.multiply(h, g.constant(0.5)), g.add(g.erf(g.multiply(h, g.constant(0.7071067811865476))), g.constant(1.0)))
+    y = _layernorm_tail(g, g.add(gelu, res), gamma, beta, eps)
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
     return g.ops
 
 
