@@ -73,6 +73,15 @@ static __device__ __forceinline__ float tanh_f32(float x) {
   const float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
   return ax < 0.3f ? p : __builtin_copysignf(t, x);
 }
+// erf for groups stored in 16 bits: 1 - (a1 t + ... + a5 t^5) e^(-x^2) with t = 1 / (1 + p |x|), the sign put
+// back (the classical five-term rational form, absolute error 1.5e-7): one reciprocal, one exp2
+static __device__ __forceinline__ float erf_fast(float x) {
+  const float ax = __builtin_fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * ax);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float e = __builtin_amdgcn_exp2f(ax * ax * -1.4426950408889634f);
+  return __builtin_copysignf(1.0f - poly * e, x);
+}
 // 1 / (1 + e^-x): exp2 overflow (x very negative) gives rcp(inf) = 0
 static __device__ __forceinline__ float logistic(float x) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(x * -1.4426950408889634f));
@@ -114,7 +123,7 @@ std::string op_text(const EwIrNode& n, bool fast) {
     case FS_TANH: return (fast ? "tanh_fast(" : "tanh_f32(") + a + ")";
     case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
-    case FS_ERF: return "erff(" + a + ")";
+    case FS_ERF: return (fast ? "erf_fast(" : "erff(") + a + ")";
     case FS_LOGISTIC: return "logistic(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";

@@ -476,7 +476,7 @@ std::string op_text(int op, const std::string& a, const std::string& b, bool fas
     case FS_TANH: return (fast ? "tanh_fast(" : "tanh_f32(") + a + ")";
     case FS_RSQRT: return "rsqrtf(" + a + ")";
     case FS_SQRT: return "sqrtf(" + a + ")";
-    case FS_ERF: return "erff(" + a + ")";
+    case FS_ERF: return (fast ? "erf_fast(" : "erff(") + a + ")";
     case FS_LOGISTIC: return "logistic(" + a + ")";
     case EW_OP_ROUND_F16: return "round_f16(" + a + ")";
     case EW_OP_ROUND_BF16: return "round_bf16(" + a + ")";
