@@ -435,6 +435,28 @@ class FusedProgram:
             plan.launch(gin, gout, stream)
         return [values[self.ops[i].operands[0]] for i in self.output_ops]
 
+    def tune(self, inputs, trials=10):
+        """Time every group's launch templates on the program's own data (fs_plan_tune, group by group in
+        execution order) and keep the winners.  -> the program's outputs, as run() would return them."""
+        torch = self._torch
+        dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+        values = {i: t for i, t in zip(self.param_ops, inputs)}
+        for k, g in enumerate(self.fusion.groups):
+            gin = [values[i] for i in g["input_of"]]
+            gout = []
+            for i in g["output_of"]:
+                op = self.ops[i]
+                values[i] = torch.empty(op.shape, dtype=dt[op.dtype], device=gin[0].device if gin else "cuda:0")
+                gout.append(values[i])
+            if self.plans[k].info()["schedule"] == "per_op":
+                self.plans[k].launch(gin, gout)
+                continue
+            tuned = Plan.tune(g["ops"], gin, gout, trials=trials)      # leaves the group's outputs written
+            self.plans[k].close()
+            self.plans[k] = tuned
+        self.n_kernels = sum(p.info()["n_kernels"] for p in self.plans)
+        return [values[self.ops[i].operands[0]] for i in self.output_ops]
+
     def bind(self, inputs):
         """Fix the program's buffers: the given input tensors, and one freshly allocated tensor per value
         that crosses a group boundary.  -> the output tensors; run_bound() then launches every group on

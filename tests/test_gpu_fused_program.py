@@ -155,3 +155,21 @@ def test_fused_program_as_a_captured_graph():
             return (time.perf_counter() - t0) / n * 1e6
         eager_us, graph_us = timed(prog.run_bound), timed(graph.replay)
         announce(f"  {len(prog.plans)} groups, {prog.n_kernels} kernels: {eager_us:.1f} us launched one by one, {graph_us:.1f} us as a graph")
+
+
+def test_fused_program_tuned_group_by_group():
+    announce("fused program, tuned")
+    rows, cols, batch, seq = 300, 1024, 6, 128
+    ops, ins = graphs.encoder_tail(rows, cols, batch, seq), _encoder_inputs(rows, cols, batch, seq)
+    want = interp.run(ops, ins)
+    dev_in = to_device(ops, ins)
+    with FusedProgram(ops) as prog:
+        outs = prog.tune(dev_in, trials=3)
+        torch.cuda.synchronize()
+        for a, b in zip(outs, want):
+            assert_close(a.double().cpu().numpy(), b, TOLERANCE["f32"], "tuned program, outputs of the tuning run")
+        assert all(p.tuned is not None for p in prog.plans)
+        again = prog.run(dev_in)
+        torch.cuda.synchronize()
+        for a, b in zip(again, want):
+            assert_close(a.double().cpu().numpy(), b, TOLERANCE["f32"], "tuned program, ordinary run")
