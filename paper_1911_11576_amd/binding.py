@@ -435,6 +435,35 @@ class FusedProgram:
             plan.launch(gin, gout, stream)
         return [values[self.ops[i].operands[0]] for i in self.output_ops]
 
+    @classmethod
+    def best_of(cls, ops, inputs, option_sets=None, trials=20):
+        """The execution-based side of Section 4.3 at the level of whole plans: build the program under
+        each set of planning options, time it on the given inputs (HIP events, `trials` runs after two
+        warm-ups), keep the fastest.  -> (program, microseconds per run, the winning options)."""
+        import torch
+        if option_sets is None:
+            option_sets = [dict(), dict(explore_budget=-1), dict(seed_bytes=1), dict(launch_us=10.0), dict(launch_us=0.5)]
+        best = None
+        for kw in option_sets:
+            prog = cls(ops, **kw)
+            prog.bind(inputs)
+            for _ in range(2):
+                prog.run_bound()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(trials):
+                prog.run_bound()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / trials
+            if best is None or us < best[1]:
+                if best is not None:
+                    best[0].close()
+                best = (prog, us, dict(kw))
+            else:
+                prog.close()
+        return best
+
     def tune(self, inputs, trials=10):
         """Time every group's launch templates on the program's own data (fs_plan_tune, group by group in
         execution order) and keep the winners.  -> the program's outputs, as run() would return them."""

@@ -173,3 +173,22 @@ def test_fused_program_tuned_group_by_group():
         torch.cuda.synchronize()
         for a, b in zip(again, want):
             assert_close(a.double().cpu().numpy(), b, TOLERANCE["f32"], "tuned program, ordinary run")
+
+
+def test_plans_compared_by_execution():
+    """Whole plans under different planning options, timed on the device; the fastest is kept and is still right."""
+    import random
+    announce("plans compared by execution")
+    rng = random.Random(111)
+    ops, pshapes = graphs.random_program(rng, 600, 1024, n_ops=36)
+    ins = inputs.normal_tensors(pshapes, seed_offset=411)
+    dev_in = to_device(ops, ins)
+    prog, us, kw = FusedProgram.best_of(ops, dev_in, trials=5)
+    try:
+        assert us > 0 and isinstance(kw, dict)
+        outs = prog.run_bound()
+        torch.cuda.synchronize()
+        for a, b in zip(outs, interp.run(ops, ins)):
+            assert_close(a.double().cpu().numpy(), b, TOLERANCE["f32"], "best plan by execution")
+    finally:
+        prog.close()
