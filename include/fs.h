@@ -11,6 +11,11 @@
  * memory.  No function throws or aborts, and none but fs_plan_tune synchronises the
  * device; every failure is a status code plus a message readable through
  * fs_last_error().
+ *
+ * Threads: every function may be called from several threads at once, and the last
+ * error is kept per thread.  One plan belongs to one thread at a time: its first
+ * launch loads the kernel and allocates the workspace into the plan, so launches of
+ * the same plan from two threads need the caller's own lock (different plans need none).
  */
 #ifndef FS_H_
 #define FS_H_
@@ -135,11 +140,12 @@ typedef enum {
  *   out         host, receives the plan on FS_OK, NULL otherwise
  * Pure host work: validates shapes and dtypes, recognises the group as one of the
  * stitched schedules (Algorithm 3 reduced to a recogniser over hand-written kernels),
- * checks the LDS budget and fixes the launch geometry.  An all-elementwise group that
- * matches none of them gets a kernel generated for it and compiled for gfx950 with the
- * HIP run-time compiler (a few hundred milliseconds the first time a given group is
- * seen in a process, cached afterwards).  Touches no GPU, so it also works on a
- * machine without one.
+ * checks the LDS budget and fixes the launch geometry.  A group that matches none of
+ * them -- all-elementwise, or elementwise ops mixed with reductions over the last dim and
+ * sums over the leading dims -- gets a kernel generated for it and compiled for gfx950
+ * with the HIP run-time compiler (a few hundred milliseconds the first time a given
+ * group is seen, cached afterwards per process and, with fs_kernel_cache_dir, per
+ * machine).  Touches no GPU, so it also works on a machine without one.
  * Errors: FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_NOMEM. */
 fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
                          const fs_plan_options* opt, fs_plan** out);

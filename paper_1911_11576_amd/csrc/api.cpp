@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <set>
@@ -105,7 +106,11 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops, const fs_plan_opt
 }
 
 fs_status fs_kernel_cache_dir(const char* dir) {
-  fs::codegen_cache_dir(dir);
+  try {
+    fs::codegen_cache_dir(dir);
+  } catch (...) {
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  }
   return FS_OK;
 }
 
@@ -155,6 +160,8 @@ fs_status fs_tune_cache_load(const char* path) {
   if (!path) return set_error(FS_ERR_INVALID, "fs_tune_cache_load: path is NULL");
   FILE* f = fopen(path, "r");
   if (!f) return set_error(FS_ERR_INVALID, std::string("fs_tune_cache_load: cannot read ") + path);
+  const std::unique_ptr<FILE, int (*)(FILE*)> closer(f, fclose);
+  try {
   std::map<uint64_t, TuneEntry> read;
   char line[256];
   bool ok = fgets(line, sizeof line, f) && strncmp(line, "fs-tune-cache 1", 15) == 0;
@@ -173,7 +180,6 @@ fs_status fs_tune_cache_load(const char* path) {
     }
     read[(uint64_t)key] = e;
   }
-  fclose(f);
   if (!ok) {
     char buf[96];
     snprintf(buf, sizeof buf, ": malformed line %d", lineno);
@@ -181,6 +187,9 @@ fs_status fs_tune_cache_load(const char* path) {
   }
   std::lock_guard<std::mutex> lock(g_tune_mu);
   for (const auto& kv : read) g_tune[kv.first] = kv.second;
+  } catch (...) {
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  }
   return FS_OK;
 }
 
@@ -429,6 +438,7 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
   if (!out) return set_error(FS_ERR_INVALID, "out is NULL");
   *out = nullptr;
   if (trials < 1 || trials > 1000) return set_error(FS_ERR_INVALID, "trials out of range [1,1000]");
+  try {
   // the default template first: it decides the schedule, and it is the fallback
   struct Tuning { Tuning() { g_tuning = true; } ~Tuning() { g_tuning = false; } } tuning_scope;
   fs_plan* base = nullptr;
@@ -528,6 +538,11 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
     std::lock_guard<std::mutex> lock(g_tune_mu);
     g_tune[group_key(ops, n_ops)] = TuneEntry{best_opt, best_t};
   }
+  } catch (const std::bad_alloc&) {
+    return set_error(FS_ERR_NOMEM, "out of host memory");
+  } catch (...) {
+    return set_error(FS_ERR_INVALID, "internal error while tuning");
+  }
   return FS_OK;
 }
 
@@ -614,13 +629,15 @@ fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion
         cfg.bandwidth.push_back({opt->bw_bytes[k], opt->bw_gbs[k]});
       }
     }
-    fs_fusion* f = new fs_fusion;
+    std::unique_ptr<fs_fusion> f(new fs_fusion);
     std::string err;
     const std::vector<fs_op_desc> list(ops, ops + n_ops);
-    if (!fs::fusion_plan(list, cfg, &f->result, &err)) { delete f; return set_error(FS_ERR_INVALID, err); }
-    *out = f;
+    if (!fs::fusion_plan(list, cfg, &f->result, &err)) return set_error(FS_ERR_INVALID, err);
+    *out = f.release();
   } catch (const std::bad_alloc&) {
     return set_error(FS_ERR_NOMEM, "out of host memory");
+  } catch (...) {
+    return set_error(FS_ERR_INVALID, "internal error while planning the fusion");
   }
   return FS_OK;
 }
