@@ -209,9 +209,15 @@ def cpu_baseline(cfg):
         t_total += time.perf_counter() - t0
         reps += 1
     sec = t_total / reps
+    cpu = None
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), None)
+    except OSError:
+        pass
     return {"value": algorithmic_bytes(ops) / sec / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"{rows} of 131072 rows of the same workload, {reps} repetitions, mean",
-            "ms_per_sample": sec * 1e3}
+            "ms_per_sample": sec * 1e3, "cpu_model": cpu}
 
 
 def main():
@@ -257,6 +263,15 @@ def main():
                      "frac": algo / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(head.name),
                      "kernel_us": ev_ms * 1e3, "frac_of_copy_kernel": res["stitched_frac_of_copy"]},
     }
+    props = torch.cuda.get_device_properties(0)       # device facts as read at run time, not assumed
+    out["device"] = {"name": props.name, "arch": getattr(props, "gcnArchName", None),
+                     "compute_units": props.multi_processor_count,
+                     "hbm_gib": round(props.total_memory / 2 ** 30, 1),
+                     "lds_bytes_per_workgroup": getattr(props, "shared_memory_per_block", None),
+                     "l2_bytes": getattr(props, "L2_cache_size", None),
+                     "clock_khz": getattr(props, "clock_rate", None),
+                     "memory_clock_khz": getattr(props, "memory_clock_rate", None),
+                     "memory_bus_bits": getattr(props, "memory_bus_width", None)}
     if not args.no_groups:
         groups = {head.name: res}
         for cfg in CONFIGS:
