@@ -42,7 +42,14 @@ __global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restr
   double s = 0.0;
   if (c < cols) {
     const double* p = partial + ((int64_t)r * groups) * cols + c;
-    for (int g = slice; g < groups; g += 64) s += p[(int64_t)g * cols];
+    // four partial rows requested at a time (the loads are independent, the additions keep their order)
+    int g = slice;
+    for (; g + 192 < groups; g += 256) {
+      const double v0 = p[(int64_t)g * cols], v1 = p[(int64_t)(g + 64) * cols];
+      const double v2 = p[(int64_t)(g + 128) * cols], v3 = p[(int64_t)(g + 192) * cols];
+      s += v0; s += v1; s += v2; s += v3;
+    }
+    for (; g < groups; g += 64) s += p[(int64_t)g * cols];
   }
   part[slice][j] = s;
   __syncthreads();
