@@ -56,12 +56,23 @@ template <class Op> __device__ __forceinline__ float rows_allreduce(float v) {
   return Op::apply(as_f32(r[0]), as_f32(r[1]));
 }
 
+// the value of the lane whose index differs in bit log2(CH): the lane that holds the other key of a
+// pair when CH lanes share one key (CH = 16-byte chunks per row of V)
+template <int CH> __device__ __forceinline__ uint32_t pair_exchange(uint32_t x) {
+  if constexpr (CH == 8) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, false);   // row_ror:8
+  } else {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x & 63) ^ CH) << 2), (int)x);
+  }
+}
+
 // NT: 16-row tiles along the sequence (workgroup = NT wavefronts); D: head dim
 template <typename T, int NT, int D>
 __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) {
   constexpr int KS = D / 32;                 // k-steps of the first dot
   constexpr int NTP = NT < 2 ? 2 : NT;       // key tiles padded to whole 32-key steps
   constexpr int SP = NTP * 16 + 8;           // padded row length of Vt (halves)
+  constexpr int SWM = (2 * NTP < 8 ? 2 * NTP : 8) - 1;   // granules of a row that the swizzle permutes
   extern __shared__ uint16_t smem[];
   uint16_t* vt = smem;                       // [D][SP]   V transposed, keys in k-slot order
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -161,18 +172,29 @@ __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) 
       }
   }
   // ---- V transposed into LDS (all wavefronts), zero-filling keys >= seq; key 32kk+16h+4g+i of
-  // a 32-key step sits at slot 8g+4h+i ---------------------------------------------------
+  // a 32-key step sits at slot 8g+4h+i.  Two things keep the stores off each other's banks: the
+  // lanes of keys 2n and 2n+1 first trade half of their eight values, so that each stores whole
+  // 32-bit words (both keys of one row) instead of 16-bit halves, and the 16-byte granule of a
+  // slot is xor-ed with the row's group of eight (row / 8), which spreads the eight row groups a
+  // store instruction touches over all banks.  (Stored piecewise the kernel spent as many cycles
+  // in bank conflicts as in everything else the LDS did, by the counters.) ---------------------
+  uint32_t* vt32 = reinterpret_cast<uint32_t*>(smem);
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int ci = threadIdx.x + i * 64 * NT;
-    const int key = ci / CH, d0 = (ci % CH) * 8;
-    const int slot = (key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3);
+    const int key = ci / CH, dg = ci % CH, d0 = dg * 8;
+    const int slot = ((key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3)) ^ ((dg & SWM) << 3);
     const u32x4 t = key < seq ? vreg[i] : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      vt[(d0 + 2 * j) * SP + slot] = (uint16_t)(t[j] & 0xFFFFu);
-      vt[(d0 + 2 * j + 1) * SP + slot] = (uint16_t)(t[j] >> 16);
-    }
+    const bool odd = (key & 1) != 0;
+    // the even key's lane ends up with rows d0 .. d0+3 of both keys, the odd key's with d0+4 .. d0+7
+    const uint32_t rx = pair_exchange<CH>(odd ? t[0] : t[2]), ry = pair_exchange<CH>(odd ? t[1] : t[3]);
+    const uint32_t ex = odd ? rx : t[0], ey = odd ? ry : t[1];     // the even key's two value pairs
+    const uint32_t ox = odd ? t[2] : rx, oy = odd ? t[3] : ry;     // the odd key's
+    uint32_t* w0 = vt32 + (((d0 + (odd ? 4 : 0)) * SP + (slot & ~1)) >> 1);
+    w0[0 * (SP / 2)] = (ex & 0xFFFFu) | (ox << 16);
+    w0[1 * (SP / 2)] = (ex >> 16) | (ox & 0xFFFF0000u);
+    w0[2 * (SP / 2)] = (ey & 0xFFFFu) | (oy << 16);
+    w0[3 * (SP / 2)] = (ey >> 16) | (oy & 0xFFFF0000u);
   }
   __syncthreads();   // Vt complete
 
@@ -187,7 +209,8 @@ __global__ __launch_bounds__(64 * NT) void attn_stitch_kernel(const AttnArgs a) 
       if (kk < ksteps) {
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-          const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + c) * SP + kk * 32 + 8 * g);
+          const int sw = (2 * dt + (c >> 3)) & SWM;          // the row's granule swizzle, as stored
+          const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + c) * SP + 8 * ((kk * 4 + g) ^ sw));
           o[dt] = Mfma<T>::run(vf, pb[kk], o[dt]);
         }
       }
