@@ -484,6 +484,39 @@ std::string op_text(int op, const std::string& a, const std::string& b, bool fas
   }
 }
 
+// Elements per 16-byte (or narrower) access of the full values, shared by the register and the
+// streamed templates: 8 when every full tensor is 16-bit, else 4, narrower when the row length or
+// an operand's strides and offset do not divide; 0 when an operand is strided along the last dim.
+// *fast: some tensor of the group is 16-bit (the short forms of tanh and erf are accurate enough).
+int chunk_elements(const Analysis& A, bool* fast) {
+  bool any32 = false, any16 = false;
+  for (const RView& v : A.views) {
+    if (v.dtype != FS_F32) any16 = true;
+    if (v.cls == CLS_FULL && v.stride[A.rank - 1] == 1 && v.dtype == FS_F32) any32 = true;
+  }
+  for (const RNode& n : A.nodes) if (n.out_ord >= 0) {
+    if (n.out_dtype != FS_F32) any16 = true;
+    if (n.cls == CLS_FULL && n.out_dtype == FS_F32) any32 = true;
+  }
+  *fast = any16;
+  auto fits = [&](int w) {
+    if (A.cols % w) return false;
+    for (const RView& v : A.views) {
+      if (v.cls != CLS_FULL) continue;
+      const int64_t ls = v.stride[A.rank - 1];
+      if (ls != 0 && ls != 1) return false;
+      if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
+      if (ls == 1 && v.offset % w) return false;
+    }
+    return true;
+  };
+  if (!any32 && fits(8)) return 8;
+  if (fits(4)) return 4;
+  if (fits(2)) return 2;
+  if (fits(1)) return 1;
+  return 0;
+}
+
 struct Gen {
   const Analysis& A;
   int L = 64, K = 1, W = 4;
@@ -549,32 +582,8 @@ struct Gen {
   int64_t stage_bytes = 0;
 
   bool geometry(std::string* err) {
-    bool any32 = false, any16 = false;
-    for (const RView& v : A.views) {
-      if (v.dtype != FS_F32) any16 = true;
-      if (v.cls == CLS_FULL && v.stride[A.rank - 1] == 1 && v.dtype == FS_F32) any32 = true;
-    }
-    for (const RNode& n : A.nodes) if (n.out_ord >= 0) {
-      if (n.out_dtype != FS_F32) any16 = true;
-      if (n.cls == CLS_FULL && n.out_dtype == FS_F32) any32 = true;
-    }
-    fast = any16;
-    auto fits = [&](int w) {
-      if (A.cols % w) return false;
-      for (const RView& v : A.views) {
-        if (v.cls != CLS_FULL) continue;
-        const int64_t ls = v.stride[A.rank - 1];
-        if (ls != 0 && ls != 1) return false;
-        if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
-        if (ls == 1 && v.offset % w) return false;
-      }
-      return true;
-    };
-    if (!any32 && fits(8)) W = 8;
-    else if (fits(4)) W = 4;
-    else if (fits(2)) W = 2;
-    else if (fits(1)) W = 1;
-    else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
+    W = chunk_elements(A, &fast);
+    if (W == 0) { *err = "generated row schedule: an operand strided along the last dim"; return false; }
     const int64_t nvec = A.cols / W;
     auto pow2_at_least = [](int64_t v) { int p = 1; while (p < v && p < 64) p *= 2; return p; };
     if (lanes_per_row > 0) {
@@ -1140,32 +1149,8 @@ struct Stream {
   }
 
   bool geometry(int want_wg, std::string* err) {
-    bool any32 = false, any16 = false;
-    for (const RView& v : A.views) {
-      if (v.dtype != FS_F32) any16 = true;
-      if (v.cls == CLS_FULL && v.stride[A.rank - 1] == 1 && v.dtype == FS_F32) any32 = true;
-    }
-    for (const RNode& n : A.nodes) if (n.out_ord >= 0) {
-      if (n.out_dtype != FS_F32) any16 = true;
-      if (n.cls == CLS_FULL && n.out_dtype == FS_F32) any32 = true;
-    }
-    fast = any16;
-    auto fits = [&](int w) {
-      if (A.cols % w) return false;
-      for (const RView& v : A.views) {
-        if (v.cls != CLS_FULL) continue;
-        const int64_t ls = v.stride[A.rank - 1];
-        if (ls != 0 && ls != 1) return false;
-        if (ls == 1) for (int d = 0; d + 1 < A.rank; ++d) if (v.stride[d] % w) return false;
-        if (ls == 1 && v.offset % w) return false;
-      }
-      return true;
-    };
-    if (!any32 && fits(8)) W = 8;
-    else if (fits(4)) W = 4;
-    else if (fits(2)) W = 2;
-    else if (fits(1)) W = 1;
-    else { *err = "generated row schedule: an operand strided along the last dim"; return false; }
+    W = chunk_elements(A, &fast);
+    if (W == 0) { *err = "generated row schedule: an operand strided along the last dim"; return false; }
     const int64_t nvec = A.cols / W;
     wg = want_wg ? want_wg : nvec <= 2048 ? 256 : nvec <= 8192 ? 512 : 1024;
     return true;
