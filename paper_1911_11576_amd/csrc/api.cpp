@@ -229,6 +229,17 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
       p->description = fs::per_op_describe(p->per_op);
     } else {
       p->moved_bytes = algo;
+      // the plan's fields once p->row_gen holds a generated row kernel
+      auto adopt_generated_row_kernel = [&]() {
+        p->match.kind = fs::MATCH_NONE;
+        p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
+        p->row_form = 3;
+        p->lds_bytes = p->row_gen.lds_bytes;
+        p->workspace_bytes = p->row_gen.workspace_bytes;
+        p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
+        p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
+        p->description = fs::row_gen_describe(p->row_gen);
+      };
       const bool recognised = fs::recognise(p->graph, &p->match);
       if (!recognised || want_generated) {
         // Not one of the hand-written reduce / dot patterns (or the caller prefers generated
@@ -245,14 +256,7 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
           p->lds_bytes = p->ew.lds_bytes;
           p->description = fs::ew_stitch_describe(p->ew);
         } else if (lo.codegen && fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &err2)) {
-          p->match.kind = fs::MATCH_NONE;
-          p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
-          p->row_form = 3;
-          p->lds_bytes = p->row_gen.lds_bytes;
-          p->workspace_bytes = p->row_gen.workspace_bytes;
-          p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
-          p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
-          p->description = fs::row_gen_describe(p->row_gen);
+          adopt_generated_row_kernel();
         } else if (!recognised) {
           if (lo.codegen && (has_reduce || st2 == FS_ERR_INVALID)) { st = st2; err = err2; }
           else if (lo.codegen && st == FS_ERR_UNSUPPORTED && !err2.empty()) err += "; " + err2;
@@ -270,14 +274,7 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
         if (!lo.codegen) return false;
         int st2 = FS_OK;
         if (!fs::row_gen_plan(p->graph, lo, &p->row_gen, &st2, &gen_err)) return false;
-        p->match.kind = fs::MATCH_NONE;
-        p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
-        p->row_form = 3;
-        p->lds_bytes = p->row_gen.lds_bytes;
-        p->workspace_bytes = p->row_gen.workspace_bytes;
-        p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
-        p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
-        p->description = fs::row_gen_describe(p->row_gen);
+        adopt_generated_row_kernel();
         return true;
       };
       switch (p->match.kind) {
