@@ -93,8 +93,6 @@ struct Rec {
   }
 };
 
-bool fail(Match* m, const std::string& why) { m->kind = MATCH_NONE; m->why = why; return false; }
-
 int64_t leading_rows(const Node& n) {
   int64_t r = 1;
   for (int d = 0; d + 1 < n.rank; ++d) r *= n.shape[d];
