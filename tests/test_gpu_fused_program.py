@@ -3,7 +3,6 @@ group becomes a stitched plan, the groups run in order on the GPU, and the progr
 are compared with the oracle's evaluation of the whole graph."""
 import sys
 
-import numpy as np
 import pytest
 import torch
 

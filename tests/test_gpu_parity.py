@@ -14,7 +14,7 @@ from paper_1911_11576_amd import FsError, Plan
 from paper_1911_11576_amd import binding
 from workloads import BY_NAME, CONFIGS, TOLERANCE, graphs, inputs
 
-from gpu_util import (alloc_outputs, assert_close, check_against_oracle, group_dtype, run_gpu,
+from gpu_util import (alloc_outputs, assert_close, check_against_oracle, run_gpu,
                       to_device)
 
 pytestmark = pytest.mark.gpu
