@@ -47,7 +47,10 @@ typedef enum {
 /* Op vocabulary: XLA-style tensor ops, the semantics the paper adopts (Section 3.1).
  * Tensors are dense, row-major, rank <= FS_MAX_RANK.
  *
- *  FS_PARAMETER   group input; the i-th parameter of the list is inputs[i] of fs_launch
+ *  FS_PARAMETER   group input; the i-th parameter of the list is inputs[i] of fs_launch.
+ *                 Rank 0 is a scalar held in device memory (one element, e.g. a value that an
+ *                 earlier group reduced over everything); it enters ops of a larger shape
+ *                 through FS_BROADCAST
  *  FS_CONSTANT    rank-0 scalar of value `attr`; allowed directly as an operand of a
  *                 binary op (implicit scalar broadcast)
  *  FS_ADD .. FS_MAXIMUM   elementwise binary; operands have the result's shape and dtype

@@ -409,7 +409,7 @@ struct EwCompiler {
       if (!g[pv.base].same_shape(shape)) return fail("elementwise schedule: parameter shape differs from the group's");
     } else {
       P.need_idx = 1;
-      const int64_t last = pv.stride[shape.rank - 1];
+      const int64_t last = shape.rank > 0 ? pv.stride[shape.rank - 1] : 0;
       if (last != 0 && last != 1) vec = false;
       for (int d = 0; d + 1 < shape.rank; ++d) if (last == 1 && pv.stride[d] % 4 != 0) vec = false;
     }
@@ -441,16 +441,16 @@ struct EwCompiler {
       }
     }
     if (S < 0 || order.empty()) return fail("elementwise schedule: the group computes nothing");
-    if (g[S].rank < 1) return fail("elementwise schedule: rank-0 group");
     if (active.empty() && (int)g.outputs.size() > kEwMaxOuts) return fail("elementwise schedule: more than 8 outputs");
     EwProgram& P = c.prog;
-    P.rank = g[S].rank;
+    // a group of scalars (rank 0: arithmetic on fully reduced values) runs as a group of shape [1]
+    P.rank = g[S].rank < 1 ? 1 : g[S].rank;
     P.n = g[S].numel();
     for (int d = 0; d < FS_MAX_RANK; ++d) {
       const int src = d - (FS_MAX_RANK - g[S].rank);
       P.shape[d] = src >= 0 ? g[S].shape[src] : 1;
     }
-    vec = g[S].shape[g[S].rank - 1] % 4 == 0;
+    vec = g[S].rank >= 1 && g[S].shape[g[S].rank - 1] % 4 == 0;
 
     last_use.assign(n, -1);
     slot_of.assign(n, -1);
@@ -472,7 +472,7 @@ struct EwCompiler {
       out_dtype[src] = g[o].dtype;
     }
 
-    ir.rank = g[S].rank;
+    ir.rank = P.rank;
     ir.n = P.n;
     ir.n_outputs = n_my_outputs;
     if (n_my_outputs == 0) return fail("elementwise schedule: ops that reach no output");

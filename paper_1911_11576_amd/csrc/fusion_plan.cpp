@@ -192,7 +192,6 @@ namespace {
 
 bool generable(const FusionGroup& gr) {
   if (gr.list.empty() || gr.output_of.empty()) return false;
-  for (const fs_op_desc& d : gr.list) if (d.kind == FS_PARAMETER && d.rank < 1) return false;
   fs_plan* p = nullptr;
   codegen_set_dry_run(true);
   const fs_status st = fs_plan_create(gr.list.data(), (int32_t)gr.list.size(), nullptr, &p);
@@ -249,6 +248,25 @@ struct Planner {
         std::map<int, std::vector<int>> parts;
         for (int o : seg) parts[find(o)].push_back(o);
         if (parts.size() > 1) for (auto& kv : parts) add(kv.second, 1);
+        // and the connected parts of its ops of one shape: the scalar arithmetic behind full
+        // reductions, the elementwise ops of one tensor among several -- candidates where the
+        // segment as a whole mixes shapes that no single kernel iterates over
+        for (int o : seg) comp[o] = o;
+        for (int o : seg) for (int p : f.producers[o]) if (inseg.count(p) && g[o].same_shape(g[p])) comp[find(o)] = find(p);
+        std::map<int, std::vector<int>> same;
+        for (int o : seg) same[find(o)].push_back(o);
+        if (same.size() > 1) {
+          for (auto& kv : same) add(kv.second, 1);
+          // what is left of the segment without one such part: ops that only met through it (the
+          // tensors that a shared scalar factor scales are independent parts of one kernel once the
+          // factor is computed elsewhere)
+          if (same.size() <= 64) for (auto& kv : same) {
+            if (kv.second.size() < 2) continue;
+            std::vector<int> rest;
+            for (int o : seg) if (find(o) != kv.first) rest.push_back(o);
+            add(rest, 1);
+          }
+        }
       }
       seg.clear();
     };
@@ -417,13 +435,21 @@ bool fusion_plan(const std::vector<fs_op_desc>& ops, const FusionConfig& cfg, Fu
     for (auto& kv : by_comp) {
       std::vector<int> ids = kv.second;
       if ((int)ids.size() > cap) {
-        // More candidates than the solver takes: first the two heaviest patterns that contain each
-        // op (so that no op loses its best cover to a crowd of variants elsewhere), then the
-        // heaviest of the rest.
+        // More candidates than the solver takes: first the patterns of substitution fusion (few, and
+        // the search's variants of a large pattern must not crowd out a small disjoint one), then the
+        // two heaviest patterns that contain each op (so that no op loses its best cover to a crowd
+        // of variants elsewhere), then the heaviest of the rest.
         std::map<int, int> covers;
         std::vector<char> keep(ids.size(), 0);
         int kept = 0;
         for (size_t q = 0; q < ids.size() && kept < cap; ++q) {
+          if (pl.patterns[cand[ids[q]]].origin == 2) continue;
+          keep[q] = 1;
+          ++kept;
+          for (int o : sets[ids[q]]) ++covers[o];
+        }
+        for (size_t q = 0; q < ids.size() && kept < cap; ++q) {
+          if (keep[q]) continue;
           bool wanted = false;
           for (int o : sets[ids[q]]) if (covers[o] < 2) wanted = true;
           if (!wanted) continue;

@@ -70,7 +70,6 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
     const Node* b = nop > 1 ? &g->nodes[n.operand[1]] : nullptr;
     switch (d.kind) {
       case FS_PARAMETER:
-        if (n.rank < 1) return fail("parameter must have rank >= 1");
         n.ordinal = (int)g->params.size();
         g->params.push_back(i);
         break;

@@ -188,6 +188,30 @@ def test_invalid_op_lists():
     assert lib.fs_destroy(None) == binding.FS_OK
 
 
+def test_scalar_parameters_and_scalar_groups():
+    """A rank-0 parameter is one element in device memory: arithmetic among scalars is an
+    elementwise group of one element, and a scalar enters a larger shape through a broadcast."""
+    g = graphs.Graph()
+    a, b = g.parameter("a", "f32", ()), g.parameter("b", "f32", ())
+    g.output(g.sqrt(g.add(a, g.multiply(b, g.constant(2.0)))))
+    with Plan(g.ops) as p:
+        info = p.info()
+        assert info["schedule"] == "elementwise" and info["algorithmic_bytes"] == 12
+    g = graphs.Graph()
+    f, x = g.parameter("f", "f32", ()), g.parameter("x", "bf16", (33, 100))
+    y = g.multiply(g.convert(x, "f32"), g.broadcast(f, (33, 100), 0))
+    g.output(g.convert(y, "bf16"))
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "elementwise"
+    with Plan(g.ops, "per_op") as p:
+        assert p.info()["n_kernels"] >= 1
+    # a scalar is not implicitly broadcast: only constants are
+    g = graphs.Graph()
+    f, x = g.parameter("f", "f32", ()), g.parameter("x", "f32", (8, 16))
+    bad = g.ops + [Op("multiply", "f32", (8, 16), (1, 0), -1, 0.0, ""), Op("output", "f32", (8, 16), (2,), -1, 0.0, "")]
+    _expect(binding.FS_ERR_INVALID, bad)
+
+
 def test_launch_without_plan_is_an_error_not_a_crash():
     lib = binding.lib()
     assert lib.fs_launch(None, None, 0, None, 0, None) == binding.FS_ERR_INVALID

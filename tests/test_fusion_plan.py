@@ -192,6 +192,25 @@ def test_cycle_repair_with_a_supplied_pattern():
     assert without.solver_rounds == 1
 
 
+def test_scalars_between_groups_clip_by_global_norm():
+    """A value reduced over everything feeds ops on the full tensors: no single kernel covers the
+    graph.  The planner must fuse each tensor's square with its first reduction, the scalar
+    arithmetic behind the reductions into one kernel, and the final scalings of all tensors into one
+    kernel of independent parts -- and every group, scalar parameters included, must plan."""
+    shapes = [(300, 1024), (1024,), (64, 3, 50)]
+    ops = graphs.clip_by_global_norm(shapes, 5.0)
+    fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
+    _check_plan(ops, fp, brute_force=False)
+    kinds = lambda g: sorted(ops[o].kind for o in g["members"])
+    assert ["add", "divide", "divide", "maximum", "sqrt"] in [kinds(g) for g in fp.groups]
+    assert ["multiply"] * len(shapes) in [kinds(g) for g in fp.groups]          # the scalings, packed
+    assert any(kinds(g) == ["multiply", "reduce_sum"] for g in fp.groups)
+    assert len(fp.groups) <= 10 < sum(1 for op in ops if of.owns_kernel(op))
+    for g in fp.groups:
+        with Plan(g["ops"]) as p:
+            assert p.info()["schedule"] != "per_op"
+
+
 def test_random_elementwise_graphs():
     rng = random.Random(7)
     for trial in range(6):

@@ -191,3 +191,20 @@ def test_plans_compared_by_execution():
             assert_close(a.double().cpu().numpy(), b, TOLERANCE["f32"], "best plan by execution")
     finally:
         prog.close()
+
+
+@pytest.mark.parametrize("max_norm", [5.0, 1e6])
+def test_clip_by_global_norm_passes_scalars_between_groups(max_norm):
+    """Three tensors of different shapes, their global norm, every tensor scaled by the clipping
+    factor: reductions down to scalars, scalar arithmetic as a group of its own, the factor broadcast
+    back into one kernel of independent parts.  With max_norm far above the norm the factor is 1."""
+    announce(f"fused program clip by global norm {max_norm}")
+    shapes = [(300, 1024), (1024,), (64, 3, 50)]
+    ops = graphs.clip_by_global_norm(shapes, max_norm)
+    ins = inputs.normal_tensors(shapes, "f32", seed_offset=33)
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins)
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], "clip by global norm")
+    with Plan(ops, "per_op") as p:
+        assert n_kernels < p.info()["n_kernels"]

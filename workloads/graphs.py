@@ -375,6 +375,27 @@ def multi_tensor_momentum(shapes, lr=1e-2, mu=0.9, dtypes=None):
     return g.ops
 
 
+def clip_by_global_norm(shapes, max_norm=1.0):
+    """Gradient clipping over several tensors: n = sqrt(sum_k sum(g_k^2)), every g_k scaled by
+    1 / max(1, n / max_norm).  Each tensor's sum of squares is spelled as a chain of reductions down
+    to a scalar, the scalars are added, and the factor is broadcast back: a graph that no single
+    group covers (a value reduced over everything feeds ops on the full tensors), so the planner
+    has to cut it.  Parameters g_k, outputs the clipped g_k, in order."""
+    g = Graph()
+    params = [g.parameter(f"g{k}", "f32", shape) for k, shape in enumerate(shapes)]
+    total = None
+    for x in params:
+        s = g.multiply(x, x)
+        while len(g.shape(s)) > 0:
+            s = g.reduce_sum(s, len(g.shape(s)) - 1)
+        total = s if total is None else g.add(total, s)
+    norm = g.sqrt(total)
+    factor = g.divide(g.constant(1.0), g.maximum(g.divide(norm, g.constant(max_norm)), g.constant(1.0)))
+    for k, x in enumerate(params):
+        g.output(g.multiply(x, g.broadcast(factor, g.shape(x), 0)), f"g{k}")
+    return g.ops
+
+
 def scale_shift_rows_cols(shape, dtype="f32"):
     """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
     broadcasts along either side folded into one elementwise group."""
