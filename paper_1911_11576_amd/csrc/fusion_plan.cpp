@@ -252,11 +252,22 @@ struct Planner {
         // reductions, the elementwise ops of one tensor among several -- candidates where the
         // segment as a whole mixes shapes that no single kernel iterates over
         for (int o : seg) comp[o] = o;
-        for (int o : seg) for (int p : f.producers[o]) if (inseg.count(p) && g[o].same_shape(g[p])) comp[find(o)] = find(p);
+        auto plain = [&](int v) { return !is_reduce_kind(g[v].kind) && g[v].kind != FS_DOT; };
+        for (int o : seg) for (int p : f.producers[o])
+          if (inseg.count(p) && plain(o) && plain(p) && g[o].same_shape(g[p])) comp[find(o)] = find(p);
         std::map<int, std::vector<int>> same;
         for (int o : seg) same[find(o)].push_back(o);
         if (same.size() > 1) {
           for (auto& kv : same) add(kv.second, 1);
+          // such a part together with the row reductions that read it (elementwise -> reduce, the
+          // input fusion of a reduction)
+          for (auto& kv : same) {
+            std::vector<int> ext = kv.second;
+            for (int o : seg)
+              if (row_reduce(g[o]) && find(o) != kv.first)
+                for (int p : f.producers[o]) if (inseg.count(p) && find(p) == kv.first) { ext.push_back(o); break; }
+            if (ext.size() > kv.second.size()) add(ext, 1);
+          }
           // what is left of the segment without one such part: ops that only met through it (the
           // tensors that a shared scalar factor scales are independent parts of one kernel once the
           // factor is computed elsewhere)

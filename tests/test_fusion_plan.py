@@ -176,20 +176,24 @@ def test_whole_groups_are_found_where_one_kernel_can_run_them():
     assert len(big["members"]) >= 20 and len(big["output_of"]) == 2       # the LayerNorm branch with both its outputs
 
 
-def test_cycle_repair_with_a_supplied_pattern():
+def test_cycle_repair_between_two_chains_that_feed_each_other():
     """Two chains that feed each other: each is a valid pattern, together they are cyclic.  The
     solver's first answer takes both; the repair forbids the pair and the second answer is the
-    best acyclic selection."""
+    best acyclic selection.  The per-column chain is a connected same-shape part of the graph's one
+    segment, so the planner meets the cycle on its own; supplying the chain changes nothing."""
     ops = graphs.crossing_branches(4096, 1024)
     kinds = [op.kind for op in ops]
     b_chain = [kinds.index("tanh"), kinds.index("tanh") + 2, len(ops) - 3]      # b1, n, b2
     assert [ops[i].shape for i in b_chain] == [(1024,)] * 3
     fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE, extra_patterns=[b_chain])
     assert fp.solver_rounds == 2
-    assert any(p["origin"] == 3 and p["ops"] == sorted(b_chain) and p["score_us"] > 0 for p in fp.patterns)
+    assert any(p["origin"] in (1, 3) and p["ops"] == sorted(b_chain) and p["score_us"] > 0 for p in fp.patterns)
     _check_plan(ops, fp)                      # acyclic, and the brute-force optimum over the same candidates
-    without = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
-    assert without.solver_rounds == 1
+    own = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
+    assert own.solver_rounds == 2 and own.total_score_us == pytest.approx(fp.total_score_us)
+    _check_plan(ops, own)
+    # without that candidate nothing is cyclic: substitution segments of a graph cut only at its reductions
+    assert FusionPlan(graphs.log_softmax((4096, 1024)), launch_us=PHI, bandwidth=TABLE).solver_rounds == 1
 
 
 def test_scalars_between_groups_clip_by_global_norm():
@@ -202,10 +206,10 @@ def test_scalars_between_groups_clip_by_global_norm():
     fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
     _check_plan(ops, fp, brute_force=False)
     kinds = lambda g: sorted(ops[o].kind for o in g["members"])
-    assert ["add", "divide", "divide", "maximum", "sqrt"] in [kinds(g) for g in fp.groups]
+    assert ["add", "add", "divide", "divide", "maximum", "sqrt"] in [kinds(g) for g in fp.groups]
     assert ["multiply"] * len(shapes) in [kinds(g) for g in fp.groups]          # the scalings, packed
-    assert any(kinds(g) == ["multiply", "reduce_sum"] for g in fp.groups)
-    assert len(fp.groups) <= 10 < sum(1 for op in ops if of.owns_kernel(op))
+    assert sum(kinds(g) == ["multiply", "reduce_sum"] for g in fp.groups) == len(shapes)
+    assert len(fp.groups) == 8 < sum(1 for op in ops if of.owns_kernel(op))
     for g in fp.groups:
         with Plan(g["ops"]) as p:
             assert p.info()["schedule"] != "per_op"
