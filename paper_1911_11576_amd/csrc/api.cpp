@@ -219,6 +219,16 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
       want_generated = opt->mode == FS_MODE_STITCHED_GENERATED;
       lo.wg_size = opt->wg_size; lo.rows_per_wave = opt->rows_per_wave; lo.grid = opt->grid;
     }
+    if (p->mode != FS_MODE_PER_OP) {
+      // chained reductions over the trailing dims become one reduction over a merged dim (same memory)
+      std::vector<fs_op_desc> merged;
+      for (int step = 0; step < FS_MAX_RANK && fs::collapse_trailing_reductions(p->graph, &merged); ++step) {
+        fs::Graph g2;
+        std::string err2;
+        if (!fs::build_graph(merged.data(), (int32_t)merged.size(), &g2, &err2)) break;
+        p->graph = g2;
+      }
+    }
     const int64_t algo = p->graph.algorithmic_bytes();
     if (p->mode == FS_MODE_PER_OP) {
       if (!fs::per_op_plan(p->graph, &p->per_op, &err)) { delete p; return set_error(FS_ERR_UNSUPPORTED, err); }

@@ -267,6 +267,16 @@ struct Planner {
               if (row_reduce(g[o]) && find(o) != kv.first)
                 for (int p : f.producers[o]) if (inseg.count(p) && find(p) == kv.first) { ext.push_back(o); break; }
             if (ext.size() > kv.second.size()) add(ext, 1);
+            // and with the reductions that continue those over the next dim (chains over the
+            // trailing dims, which a plan merges into one reduction)
+            for (bool grown = ext.size() > kv.second.size(); grown;) {
+              grown = false;
+              const std::set<int> have(ext.begin(), ext.end());
+              for (int o : seg)
+                if (row_reduce(g[o]) && !have.count(o))
+                  for (int p : f.producers[o]) if (have.count(p) && is_reduce_kind(g[p].kind) && g[p].kind == g[o].kind) { ext.push_back(o); grown = true; break; }
+              if (grown) add(ext, 1);          // one more link of every chain
+            }
           }
           // what is left of the segment without one such part: ops that only met through it (the
           // tensors that a shared scalar factor scales are independent parts of one kernel once the

@@ -141,4 +141,61 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
   return true;
 }
 
+// A reduction over the last dim whose only reader reduces the result over ITS last dim, by the same
+// operator, is one reduction over the two trailing dims taken as one: tensors are dense, so [.., B, C]
+// read as [.., B*C] is the same memory.  The rewritten list has one reduction less and its full
+// values one dim less; every kernel schedule sees a plain reduction over the last dim.  Applies
+// only where nothing else distinguishes the two trailing dims: every op of full rank has the full
+// shape, every op one dim shorter is such an inner reduction, and what is broadcast into the full
+// shape covers leading dims only.  At least one leading dim is kept (a reduction of everything to
+// a scalar stays a chain: one row would leave the whole tensor to one workgroup).
+bool collapse_trailing_reductions(const Graph& g, std::vector<fs_op_desc>* out) {
+  const int n = g.size();
+  std::vector<int> readers(n, 0), reader_of(n, -1);
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < operand_count(g[i].kind); ++j) { ++readers[g[i].operand[j]]; reader_of[g[i].operand[j]] = i; }
+  auto is_reduce = [](int k) { return k == FS_REDUCE_SUM || k == FS_REDUCE_MAX; };
+  auto inner_of = [&](int i) {      // i is the inner reduction of a collapsible pair
+    const Node& r1 = g[i];
+    if (!is_reduce(r1.kind) || readers[i] != 1) return false;
+    const Node& x = g[r1.operand[0]];
+    const Node& r2 = g[reader_of[i]];
+    return x.rank >= 3 && r1.axis == x.rank - 1 && r2.kind == r1.kind && r2.axis == r1.rank - 1;
+  };
+  int first = -1;
+  for (int i = 0; i < n && first < 0; ++i) if (inner_of(i)) first = i;
+  if (first < 0) return false;
+  const Node& full = g[g[first].operand[0]];
+  const int r = full.rank;
+  for (int i = 0; i < n; ++i) {
+    const Node& x = g[i];
+    if (x.kind == FS_DOT || x.kind == FS_CAUSAL_MASK) return false;
+    if (x.rank > r) return false;
+    if (x.rank == r && !x.same_shape(full)) return false;
+    if (x.rank == r - 1 && !(inner_of(i) && g[x.operand[0]].same_shape(full))) return false;
+    if (x.kind == FS_BROADCAST && x.rank == r && x.axis + g[x.operand[0]].rank > r - 2) return false;
+    if (x.kind == FS_BROADCAST && x.rank == r - 1) return false;
+  }
+  std::vector<int> remap(n, -1);
+  out->clear();
+  for (int i = 0; i < n; ++i) {
+    const Node& x = g[i];
+    if (x.rank == r - 1 && is_reduce(x.kind)) { remap[i] = remap[x.operand[0]]; continue; }   // the inner reduction: its reader reads the full value
+    fs_op_desc d{};
+    d.kind = x.kind; d.dtype = x.dtype; d.rank = x.rank; d.axis = x.axis; d.attr = x.attr;
+    for (int k = 0; k < x.rank; ++k) d.shape[k] = x.shape[k];
+    if (x.rank == r) {
+      d.rank = r - 1;
+      d.shape[r - 2] = full.shape[r - 2] * full.shape[r - 1];
+      d.shape[r - 1] = 0;
+    }
+    const int nop = operand_count(x.kind);
+    for (int k = 0; k < 3; ++k) d.operand[k] = k < nop ? remap[x.operand[k]] : -1;
+    if (is_reduce(x.kind) && g[x.operand[0]].rank == r - 1) d.axis = r - 2;     // the outer reduction, now over the merged dim
+    remap[i] = (int)out->size();
+    out->push_back(d);
+  }
+  return true;
+}
+
 }  // namespace fs

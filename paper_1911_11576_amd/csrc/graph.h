@@ -38,6 +38,10 @@ struct Graph {
 // Copies and checks the list.  On failure returns false and sets *err.
 bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* err);
 
+// One step of merging chained reductions over the two trailing dims into a reduction over one merged
+// dim; true (and the rewritten op list) if the group allows it.  See graph.cpp.
+bool collapse_trailing_reductions(const Graph& g, std::vector<fs_op_desc>* out);
+
 inline bool is_binary(int k) { return k >= FS_ADD && k <= FS_MAXIMUM; }
 inline bool is_unary(int k) { return (k >= FS_NEGATE && k <= FS_SQRT) || k == FS_ERF || k == FS_LOGISTIC; }
 // how many entries of Node::operand an op of this kind reads

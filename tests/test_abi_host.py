@@ -8,7 +8,7 @@ import re
 import pytest
 
 from paper_1911_11576_amd import FsError, Plan, binding
-from workloads import BY_NAME, CONFIGS, graphs
+from workloads import BY_NAME, CONFIGS, algorithmic_bytes, graphs
 from workloads.graphs import Graph, Op
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -210,6 +210,32 @@ def test_scalar_parameters_and_scalar_groups():
     f, x = g.parameter("f", "f32", ()), g.parameter("x", "f32", (8, 16))
     bad = g.ops + [Op("multiply", "f32", (8, 16), (1, 0), -1, 0.0, ""), Op("output", "f32", (8, 16), (2,), -1, 0.0, "")]
     _expect(binding.FS_ERR_INVALID, bad)
+
+
+def test_chained_reductions_over_trailing_dims_are_one_reduction():
+    """[.., B, C] reduced over C and then over B is a reduction over the B*C elements that lie
+    together in memory: one row kernel, not a kernel per link -- as long as nothing in the group
+    tells the two dims apart and a leading dim is left."""
+    for ops in (graphs.norm_over_trailing_dims((32, 8, 96)), graphs.norm_over_trailing_dims((6, 4, 5, 32), 3, "bf16"),
+                graphs.max_abs_over_trailing_dims((64, 3, 50), 2), graphs.max_abs_over_trailing_dims((6, 4, 5, 32), 3, "f16")):
+        with Plan(ops) as p:
+            info = p.info()
+            assert info["schedule"] == "row" and info["n_kernels"] == 1
+            assert info["algorithmic_bytes"] == algorithmic_bytes(ops)
+    # not when the reduction would leave no row (everything down to a scalar) ...
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.max_abs_over_trailing_dims((64, 50), 2))
+    # ... or when an operand tells the trailing dims apart
+    g = graphs.Graph()
+    x, w = g.parameter("x", "f32", (32, 8, 96)), g.parameter("w", "f32", (96,))
+    g.output(g.reduce_sum(g.reduce_sum(g.multiply(x, g.broadcast(w, (32, 8, 96), 2)), 2), 1))
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    # ... or when the inner result is wanted too
+    g = graphs.Graph()
+    x = g.parameter("x", "f32", (32, 8, 96))
+    inner = g.reduce_sum(x, 2)
+    g.output(inner)
+    g.output(g.reduce_sum(inner, 1))
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
 
 
 def test_launch_without_plan_is_an_error_not_a_crash():

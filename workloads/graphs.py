@@ -396,6 +396,43 @@ def clip_by_global_norm(shapes, max_norm=1.0):
     return g.ops
 
 
+def norm_over_trailing_dims(shape, n_trailing=2, dtype="f32", eps=1e-5):
+    """Normalisation of x over its last `n_trailing` dims jointly (a group or instance norm's
+    statistics), every reduction spelled as a chain of reductions over one dim each:
+    c = x - mean, y = c * rsqrt(mean(c^2) + eps); outputs (y, mean).  Parameter x."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    xf = x if dtype == "f32" else g.convert(x, "f32")
+    count = 1
+    for d in shape[len(shape) - n_trailing:]:
+        count *= d
+
+    def chain(v, reduce):
+        for _ in range(n_trailing):
+            v = reduce(v, len(g.shape(v)) - 1)
+        return v
+    mean = g.multiply(chain(xf, g.reduce_sum), g.constant(1.0 / count))
+    c = g.subtract(xf, g.broadcast(mean, shape, 0))
+    var = g.multiply(chain(g.multiply(c, c), g.reduce_sum), g.constant(1.0 / count))
+    rstd = g.rsqrt(g.add(var, g.constant(eps)))
+    y = g.multiply(c, g.broadcast(rstd, shape, 0))
+    g.output(y if dtype == "f32" else g.convert(y, dtype), "y")
+    g.output(mean, "mean")
+    return g.ops
+
+
+def max_abs_over_trailing_dims(shape, n_trailing, dtype="f32"):
+    """max(x, -x) reduced over the last `n_trailing` dims by a chain of reduce_max ops."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    v = x if dtype == "f32" else g.convert(x, "f32")
+    v = g.maximum(v, g.negate(v))
+    for _ in range(n_trailing):
+        v = g.reduce_max(v, len(g.shape(v)) - 1)
+    g.output(v, "amax")
+    return g.ops
+
+
 def scale_shift_rows_cols(shape, dtype="f32"):
     """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
     broadcasts along either side folded into one elementwise group."""
