@@ -128,7 +128,10 @@ typedef enum {
                             hand-written kernels for the recognised patterns (LayerNorm,
                             softmax, ...), a generated kernel for any other mix of
                             elementwise ops and reductions over the last dim */
-  FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials */
+  FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials: sums over
+                            all rows ([R, C] -> [C], on higher ranks spelled as a chain of sums over
+                            the leading dim), or over each run of the innermost row dims
+                            ([B, S, H] -> [B, H]: sequence pooling) */
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
   FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as
                                 a kernel generated for the group (or interpreted, see

@@ -247,7 +247,7 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
         p->lds_bytes = p->row_gen.lds_bytes;
         p->workspace_bytes = p->row_gen.workspace_bytes;
         p->moved_bytes = algo + 2 * p->row_gen.workspace_bytes;
-        p->n_kernels = p->row_gen.n_col > 0 ? 2 : 1;
+        p->n_kernels = p->row_gen.n_kernels;
         p->description = fs::row_gen_describe(p->row_gen);
       };
       const bool recognised = fs::recognise(p->graph, &p->match);

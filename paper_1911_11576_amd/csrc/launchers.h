@@ -72,8 +72,9 @@ int ew_stitch_launch(EwLaunch&, const void* const* in, void* const* out, int n_o
 void ew_stitch_release(EwLaunch&);
 
 int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, std::string* err);
-// out[r][c] = sum over g of partial[r][g][c] (doubles), stored in dtype[r]; r < n_red <= 8
+// out[r][s][c] = sum over g of partial[r][s * groups + g][c] (doubles), stored in dtype[r]; r < n_red <= 8;
+// s < n_seg runs of rows (1: sums over all rows)
 int col_combine_launch(const void* partial, int groups, int64_t cols, int n_red, void* const* out, const int* dtype,
-                       void* stream, std::string* err);
+                       void* stream, std::string* err, int64_t n_seg = 1);
 
 }  // namespace fs

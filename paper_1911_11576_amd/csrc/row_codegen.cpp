@@ -67,6 +67,8 @@ struct Analysis {
   std::vector<RView> views;
   int n_reduce = 0;
   int n_col = 0;                 // column reductions (over the rows), results are outputs only
+  int64_t seg_rows = 0;          // 0: the column reductions run over all rows; else over each run of this many
+                                 // consecutive rows (the innermost row dims: [B, S, H] summed over S -> [B, H])
   bool has_causal = false;       // a causal_mask op: the row's index in the second-to-last dim is needed
 
   explicit Analysis(const Graph& gr) : g(gr) {}
@@ -300,6 +302,40 @@ struct Analysis {
         col_base[i] = cur;
         for (int m : mids) col_mid[m] = 1;
       }
+    }
+    // A sum over the innermost row dims only ([B, S, H] summed over S, or [B, N, S, H] over S and then
+    // over N, each link over the dim before the last): column sums per run of consecutive rows.
+    if (rank >= 3) {
+      std::vector<int> n_users(n, 0);
+      for (int i = 0; i < n; ++i) for (int j = 0; j < operand_count(g[i].kind); ++j) ++n_users[g[i].operand[j]];
+      for (int i = 0; i < n; ++i) {
+        const Node& x = g[i];
+        if (x.kind != FS_REDUCE_SUM || col_base[i] >= 0 || col_mid[i] || out_ord[i] < 0) continue;
+        int cur = i, levels = 0;
+        std::vector<int> mids;
+        while (g[cur].kind == FS_REDUCE_SUM && g[g[cur].operand[0]].rank >= 3 && g[cur].axis == g[g[cur].operand[0]].rank - 2 &&
+               (cur == i || (n_users[cur] == 1 && out_ord[cur] < 0))) {
+          if (cur != i) mids.push_back(cur);
+          cur = g[cur].operand[0];
+          ++levels;
+        }
+        cur = canon(cur);
+        if (levels < 1 || levels > rank - 2 || g[cur].rank != rank || !shape_is_full(g[cur])) continue;
+        // the result keeps the outer row dims and the columns
+        bool fits = x.rank == rank - levels && x.shape[x.rank - 1] == S[rank - 1];
+        for (int d = 0; d + 1 < x.rank && fits; ++d) fits = x.shape[d] == S[d];
+        if (!fits) continue;
+        int64_t seg = 1;
+        for (int d = rank - 1 - levels; d < rank - 1; ++d) seg *= S[d];
+        if (seg == 0) continue;          // empty runs: left to the per-op form
+        if (seg_rows != 0 && seg_rows != seg) return fail("generated row schedule: column sums over runs of rows of different lengths");
+        seg_rows = seg;
+        col_base[i] = cur;
+        for (int m : mids) col_mid[m] = 1;
+      }
+      if (seg_rows != 0)
+        for (int i = 0; i < n; ++i) if (col_base[i] >= 0 && g[i].rank == 1 && rank >= 2)
+          return fail("generated row schedule: sums over all rows and sums over runs of rows in one group");
     }
     // the tanh-form GELU is computed as one op
     std::vector<int> idiom_of(n, -1);
@@ -578,6 +614,7 @@ struct Gen {
   int wg = 256;               // workgroup size the kernel is generated for
   bool persistent = false;    // a fixed grid loops over the rows (groups with column reductions, or on request)
   bool want_persistent = false;
+  int seg_groups = 0;         // column sums per run of rows: workgroups that share one run (1: results are stored directly)
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
@@ -682,11 +719,26 @@ struct Gen {
         e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = 0.0;", n.id);
       }
       e.line("  constexpr int RPW = %d;                      // rows a workgroup handles at a time", wg / L);
-      e.line("  for (long long row0 = (long long)blockIdx.x * RPW; row0 < %lldll; row0 += (long long)gridDim.x * RPW) {", (long long)A.rows);
+      if (A.seg_rows > 0) {
+        // column sums per run of SEG consecutive rows: G consecutive workgroups share one run
+        e.line("  constexpr long long SEG = %lldll; constexpr int G = %d;", (long long)A.seg_rows, seg_groups);
+        e.line("  const long long seg = blockIdx.x / G, seg_lo = seg * SEG, seg_hi = seg_lo + SEG;");
+        e.line("  const long long first_row = seg_lo + (long long)(blockIdx.x %% G) * RPW, row_step = (long long)G * RPW;");
+        e.line("  for (long long row0 = first_row; row0 < seg_hi; row0 += row_step) {");
+      } else {
+        e.line("  const long long first_row = (long long)blockIdx.x * RPW, row_step = (long long)gridDim.x * RPW;");
+        e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += row_step) {", (long long)A.rows);
+      }
       e.line("  long long row = row0 + threadIdx.x / L;");
     }
-    e.line("  const bool row_ok = row < %lldll;", (long long)A.rows);
-    e.line("  if (!row_ok) row = %lldll;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", (long long)A.rows - 1);
+    char row_hi[32], row_last[40], row_any[32];     // end of the rows of this workgroup's loop, its last row, a row that is surely valid
+    if (persistent && A.seg_rows > 0) {
+      snprintf(row_hi, sizeof row_hi, "seg_hi"); snprintf(row_last, sizeof row_last, "(seg_hi - 1)"); snprintf(row_any, sizeof row_any, "seg_lo");
+    } else {
+      snprintf(row_hi, sizeof row_hi, "%lldll", (long long)A.rows); snprintf(row_last, sizeof row_last, "%lldll", (long long)A.rows - 1); snprintf(row_any, sizeof row_any, "0");
+    }
+    e.line("  const bool row_ok = row < %s;", row_hi);
+    e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);
     std::vector<std::string> roff(A.views.size());
@@ -748,11 +800,10 @@ struct Gen {
         // the prologue goes before the row loop: find the loop header emitted above
         const std::string header = "  for (long long row0 = ";
         const size_t at = e.s.rfind(header);
-        snprintf(buf, sizeof buf, "  long long rowp = (long long)blockIdx.x * %d + threadIdx.x / L;\n  if (rowp >= %lldll) rowp = %lldll;\n",
-                 wg / L, (long long)A.rows, (long long)A.rows - 1);
+        snprintf(buf, sizeof buf, "  long long rowp = first_row + threadIdx.x / L;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
         e.s.insert(at, std::string(buf) + pro);
-        e.line("  long long rown = row0 + (long long)gridDim.x * %d + threadIdx.x / L;", wg / L);
-        e.line("  if (rown >= %lldll) rown = 0;          // past the end: any valid row (row 0 is cached by then)", (long long)A.rows);
+        e.line("  long long rown = row0 + row_step + threadIdx.x / L;");
+        e.line("  if (rown >= %s) rown = %s;          // past the end: any valid row (one that is cached by then)", row_hi, row_any);
         e.s += nxt;
         e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
         advance = adv;
@@ -951,14 +1002,26 @@ struct Gen {
       if (T > 1 && A.n_reduce > 0) e.line("  __syncthreads();                             // the exchange slots are written again in the next row");
       e.line("  }");
     }
+    // a run of rows that one workgroup sums alone: its sums are the results, stored as they are
+    const bool direct = A.seg_rows > 0 && seg_groups == 1;
+    auto direct_store = [&](const RNode& n, const char* index, const char* value) {
+      char buf[256];
+      if (n.out_dtype == FS_F32) snprintf(buf, sizeof buf, "static_cast<float*>(a.out[%d])[seg * %lldll + %s] = (float)%s;", n.out_ord, (long long)A.cols, index, value);
+      else snprintf(buf, sizeof buf, "static_cast<unsigned short*>(a.out[%d])[seg * %lldll + %s] = (unsigned short)%s((float)%s);", n.out_ord, (long long)A.cols, index,
+                    n.out_dtype == FS_F16 ? "to_f16" : "to_bf16", value);
+      return std::string(buf);
+    };
     if (persistent && A.n_col > 0 && T > 1) {
       // one row per workgroup at a time: no two lanes of the workgroup hold the same column
-      e.line("  double* ws = static_cast<double*>(a.ws);");
+      if (!direct) e.line("  double* ws = static_cast<double*>(a.ws);");
       int ci = 0;
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        char val[32];
+        snprintf(val, sizeof val, "ca%d[k][j]", n.id);
         e.line("  UNROLL for (int k = 0; k < K; ++k) {");
         e.line("    if (!ok[k]) continue;");
-        e.line("    UNROLL for (int j = 0; j < W; ++j) ws[((long long)%d * gridDim.x + blockIdx.x) * %lldll + col[k] + j] = ca%d[k][j];", ci, (long long)A.cols, n.id);
+        if (direct) e.line("    UNROLL for (int j = 0; j < W; ++j) %s", direct_store(n, "col[k] + j", val).c_str());
+        else e.line("    UNROLL for (int j = 0; j < W; ++j) ws[((long long)%d * gridDim.x + blockIdx.x) * %lldll + col[k] + j] = ca%d[k][j];", ci, (long long)A.cols, n.id);
         e.line("  }");
         ++ci;
       }
@@ -985,10 +1048,19 @@ struct Gen {
       e.line("    }");
       e.line("    __syncthreads();");
       e.line("  }");
-      e.line("  double* ws = static_cast<double*>(a.ws);");
-      e.line("  for (int r = 0; r < %d; ++r)", A.n_col);
-      e.line("    for (int i = threadIdx.x; i < %lld; i += blockDim.x) ws[((long long)r * gridDim.x + blockIdx.x) * %lldll + i] = colacc[r][i];",
-             (long long)A.cols, (long long)A.cols);
+      if (direct) {
+        int r = 0;
+        for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+          char val[32];
+          snprintf(val, sizeof val, "colacc[%d][i]", r++);
+          e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) %s", (long long)A.cols, direct_store(n, "i", val).c_str());
+        }
+      } else {
+        e.line("  double* ws = static_cast<double*>(a.ws);");
+        e.line("  for (int r = 0; r < %d; ++r)", A.n_col);
+        e.line("    for (int i = threadIdx.x; i < %lld; i += blockDim.x) ws[((long long)r * gridDim.x + blockIdx.x) * %lldll + i] = colacc[r][i];",
+               (long long)A.cols, (long long)A.cols);
+      }
     }
     e.line("}");
     uint64_t h = 1469598103934665603ull;
@@ -1441,6 +1513,20 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   std::string gerr;
   if (!want_stream && gen.geometry(&gerr)) {
     // the row lives in registers
+    int64_t n_seg = 0;
+    if (A.seg_rows > 0) {
+      // column sums per run of rows: a run belongs to one workgroup where there are runs enough to fill
+      // the chip; fewer, longer runs are shared by as many workgroups as leave each at least four rounds of rows
+      n_seg = A.rows / A.seg_rows;
+      const int64_t per_round = gen.L > 64 ? 1 : gen.wg / gen.L;
+      int64_t share = n_seg >= 512 ? 1 : (512 + n_seg - 1) / n_seg;
+      const int64_t most = A.seg_rows / (4 * per_round);
+      if (share > most) share = most;
+      if (share < 1) share = 1;
+      if (share > 4096) share = 4096;
+      gen.seg_groups = (int)share;
+      if (n_seg * share > 0x7fffffffLL) { *err = "generated row schedule: too many runs of rows for one grid"; return false; }
+    }
     gen.emit(&l.kernel_name);
     dump_source(gen.e.s);
     std::string cerr;
@@ -1459,6 +1545,10 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       int64_t want = opt.grid > 0 ? opt.grid : l.L > 64 ? 256 * (2048 / l.L) / 2 : 256;
       if (l.L > 64 && opt.grid <= 0 && want > (A.rows + 15) / 16) want = (A.rows + 15) / 16;
       if (want < grid) grid = want;
+      if (n_seg > 0) grid = n_seg * gen.seg_groups;      // the runs of rows fix the grid
+      l.segmented = A.seg_rows > 0;
+      l.seg_count = n_seg;
+      l.seg_groups = gen.seg_groups;
       l.persistent = true;
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
         l.col_out[l.n_col] = n.out_ord;
@@ -1466,7 +1556,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
         ++l.n_col;
       }
       if (A.n_col > 0 && l.L <= 64) l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
-      l.workspace_bytes = (int64_t)A.n_col * grid * A.cols * 8;
+      l.workspace_bytes = (n_seg > 0 && gen.seg_groups == 1) ? 0 : (int64_t)A.n_col * grid * A.cols * 8;
+      l.n_kernels = A.n_col > 0 && l.workspace_bytes > 0 ? 2 : 1;
     }
     if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
     l.grid = (int)(grid < 1 ? 1 : grid);
@@ -1522,7 +1613,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
 }
 
 std::string row_gen_describe(const RowGenLaunch& l) {
-  char buf[400];
+  char buf[560];
   if (l.streamed) {
     snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d] streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
              l.n_reduce, l.n_ops - l.n_reduce, l.W, l.passes, l.row_buffers, l.buffers_shared,
@@ -1537,8 +1628,15 @@ std::string row_gen_describe(const RowGenLaunch& l) {
     return buf;
   }
   if (l.n_col > 0) {
-    snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,%s-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %d partial rows, then a combine kernel); cta_num=%d, cta_size=%d, lds=%lld",
-             l.n_reduce, l.L > 64 ? "CTA-S" : "WARP", l.n_col, l.n_ops - l.n_reduce - l.n_col, l.L > 64 ? "CTA" : "WARP", l.K * l.W, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.grid, l.wg,
+    char how[160];
+    if (l.segmented && l.n_kernels == 1)
+      snprintf(how, sizeof how, "column sums per run of %lld rows, one workgroup per run", (long long)(l.seg_count ? l.rows / l.seg_count : 0));
+    else if (l.segmented)
+      snprintf(how, sizeof how, "column sums per run of %lld rows, %d partial rows per run, then a combine kernel", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_groups);
+    else
+      snprintf(how, sizeof how, "%d partial rows, then a combine kernel", l.grid);
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,%s-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %s); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.L > 64 ? "CTA-S" : "WARP", l.n_col, l.n_ops - l.n_reduce - l.n_col, l.L > 64 ? "CTA" : "WARP", l.K * l.W, l.kernel_name.c_str(), l.code_object.size(), how, l.grid, l.wg,
              (long long)l.lds_bytes);
     return buf;
   }
@@ -1552,7 +1650,7 @@ int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int
                    std::string* err) {
   if (l.rows == 0 || l.cols == 0) {
     // no rows: the column sums are zero (the combine kernel over zero partial rows writes them)
-    if (l.n_col > 0 && l.cols > 0) {
+    if (l.n_col > 0 && l.cols > 0 && !l.segmented) {      // (no rows and sums per run of rows: no run, nothing to write)
       void* col_out[8];
       for (int r = 0; r < l.n_col; ++r) col_out[r] = out[l.col_out[r]];
       return col_combine_launch(nullptr, 0, l.cols, l.n_col, col_out, l.col_dtype, stream, err);
@@ -1564,9 +1662,10 @@ int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int
   for (int k = 0; k < n_out && k < 8; ++k) args.out[k] = out[k];
   args.ws = workspace;
   const int rc = ew_module_launch(&l.loaded, l.code_object, l.kernel_name, &args, sizeof args, l.grid, l.wg, stream, err);
-  if (rc != 0 || l.n_col == 0) return rc;
+  if (rc != 0 || l.n_col == 0 || l.n_kernels == 1) return rc;
   void* col_out[8];
   for (int r = 0; r < l.n_col; ++r) col_out[r] = out[l.col_out[r]];
+  if (l.seg_count > 0) return col_combine_launch(workspace, l.seg_groups, l.cols, l.n_col, col_out, l.col_dtype, stream, err, l.seg_count);
   return col_combine_launch(workspace, l.grid, l.cols, l.n_col, col_out, l.col_dtype, stream, err);
 }
 

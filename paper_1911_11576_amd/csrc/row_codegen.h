@@ -23,6 +23,12 @@ struct RowGenLaunch {
   // then a second kernel adds them
   int n_col = 0;
   int col_out[8] = {0}, col_dtype[8] = {0};   // output ordinal and dtype of each
+  // column sums per run of consecutive rows ([B, S, H] summed over S): number of runs (0: sums over all
+  // rows) and workgroups per run; with one workgroup per run the kernel stores the results itself
+  bool segmented = false;
+  int64_t seg_count = 0;
+  int seg_groups = 0;
+  int n_kernels = 1;
   int64_t workspace_bytes = 0;
   int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view

@@ -33,15 +33,17 @@ struct ColCombineArgs {
   int dtype[8];
 };
 
-__global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restrict__ partial, int groups, int64_t cols,
-                                                           const ColCombineArgs args) {
-  // a block owns 16 columns; its 1024 threads are 64 slices of the partial rows
+__global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restrict__ partial, int groups, int64_t total_groups,
+                                                           int64_t cols, const ColCombineArgs args) {
+  // a block owns 16 columns of one run of rows; its 1024 threads are 64 slices of that run's partial rows
   __shared__ double part[64][17];
+  const int64_t col_blocks = (cols + 15) / 16;
+  const int64_t seg = blockIdx.x / col_blocks;
   const int r = blockIdx.y, j = threadIdx.x & 15, slice = threadIdx.x >> 4;
-  const int64_t c = (int64_t)blockIdx.x * 16 + j;
+  const int64_t c = (blockIdx.x % col_blocks) * 16 + j;
   double s = 0.0;
   if (c < cols) {
-    const double* p = partial + ((int64_t)r * groups) * cols + c;
+    const double* p = partial + ((int64_t)r * total_groups + seg * groups) * cols + c;
     // four partial rows requested at a time (the loads are independent, the additions keep their order)
     int g = slice;
     for (; g + 192 < groups; g += 256) {
@@ -59,19 +61,24 @@ __global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restr
     for (int k = 1; k < 64; ++k) t += part[k][j];
     void* o = args.out[r];
     const float f = (float)t;
-    if (args.dtype[r] == DT_F32) static_cast<float*>(o)[c] = f;
-    else static_cast<uint16_t*>(o)[c] = (uint16_t)(args.dtype[r] == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f));
+    const int64_t at = seg * cols + c;
+    if (args.dtype[r] == DT_F32) static_cast<float*>(o)[at] = f;
+    else static_cast<uint16_t*>(o)[at] = (uint16_t)(args.dtype[r] == DT_F16 ? f32_to_f16(f) : f32_to_bf16(f));
   }
 }
 
+// partial: [n_red][n_seg * groups][cols] doubles -- for every reduction and every run of rows, `groups`
+// partial rows, added in a fixed order into out[r][n_seg][cols].  n_seg = 1: sums over all rows.
 int col_combine_launch(const void* partial, int groups, int64_t cols, int n_red, void* const* out, const int* dtype,
-                       void* stream, std::string* err) {
-  if (n_red <= 0 || cols <= 0) return 0;
+                       void* stream, std::string* err, int64_t n_seg) {
+  if (n_red <= 0 || cols <= 0 || n_seg <= 0) return 0;
+  const int64_t blocks = n_seg * ((cols + 15) / 16);
+  if (blocks > 0x7fffffffLL) { *err = "col_combine launch: too many runs of rows for one grid"; return -1; }
   ColCombineArgs a{};
   for (int r = 0; r < n_red && r < 8; ++r) { a.out[r] = out[r]; a.dtype[r] = dtype[r]; }
-  const dim3 grid((unsigned)((cols + 15) / 16), (unsigned)n_red);
+  const dim3 grid((unsigned)blocks, (unsigned)n_red);
   hipLaunchKernelGGL(col_combine_kernel, grid, dim3(1024), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const double*>(partial), groups, cols, a);
+                     static_cast<const double*>(partial), groups, n_seg * (int64_t)groups, cols, a);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) { *err = std::string("col_combine launch: ") + hipGetErrorString(e); return -1; }
   return 0;

@@ -433,6 +433,27 @@ def max_abs_over_trailing_dims(shape, n_trailing, dtype="f32"):
     return g.ops
 
 
+def sequence_pool(shape, levels=1, dtype="f32", with_row_work=False):
+    """Sum pooling over the innermost row dims: x[.., S, H] -> tanh -> sum over S -> [.., H] (with
+    levels=2, over the two dims before the last, each a reduction of its own).  With row work the
+    pooled value is tanh(x - rowmax(x)), which is a second, full-size output.  Parameter x; outputs
+    (full value if any, pooled); the pooled output is f32."""
+    g = Graph()
+    x = g.parameter("x", dtype, shape)
+    v = x if dtype == "f32" else g.convert(x, "f32")
+    if with_row_work:
+        m = g.reduce_max(v, len(shape) - 1)
+        v = g.tanh(g.subtract(v, g.broadcast(m, shape, 0)))
+        g.output(v if dtype == "f32" else g.convert(v, dtype), "y")
+    else:
+        v = g.tanh(v)
+    s = v
+    for _ in range(levels):
+        s = g.reduce_sum(s, len(g.shape(s)) - 2)
+    g.output(s, "pooled_sum")
+    return g.ops
+
+
 def scale_shift_rows_cols(shape, dtype="f32"):
     """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
     broadcasts along either side folded into one elementwise group."""
