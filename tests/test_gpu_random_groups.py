@@ -64,6 +64,24 @@ def test_random_groups_with_column_sums(seed):
     check_against_oracle(ops, ins, what=f"random column group {seed} grid 3", grid=3, wg_size=128)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_groups_with_column_sums_per_run_of_rows(seed):
+    """Random row groups whose extra outputs are sums over the innermost row dims ([B, S, H] over S;
+    [B, N, S, H] over S, or over S and N): runs of 1 to 600 rows, one or several workgroups per run,
+    rows of one wavefront and of a team."""
+    rng = random.Random(4242 + seed)
+    shape = [(37, 5, 128), (300, 7, 8), (3, 600, 100), (2, 3, 5, 32), (65, 2, 30), (5, 9, 2048), (1, 64, 64), (4, 1, 96),
+             (6, 20, 4096), (2, 4, 50, 100), (700, 3, 64), (2, 2, 2, 2)][seed]
+    dtype = ["f32", "bf16", "f16"][seed % 3]
+    ops, pshapes = graphs.random_row_group(rng, shape, dtype, n_ops=rng.randint(4, 12), column_sums="runs")
+    ins = inputs.normal_tensors(pshapes, dtype, seed_offset=400 + seed)
+    announce(f"random group with column sums per run seed {seed} shape {shape} {dtype}: {len(ops)} ops")
+    with Plan(ops) as p:
+        assert p.info()["schedule"] == "row_col" and "per run of" in p.describe()
+    check_against_oracle(ops, ins, what=f"random run-sum group {seed}")
+    check_against_oracle(ops, ins, what=f"random run-sum group {seed} wg 128", wg_size=128)
+
+
 @pytest.mark.parametrize("shape,dtype", [((300, 96), "f32"), ((7, 5, 33), "f32"), ((64, 2048), "bf16"), ((1000, 4), "f16")])
 def test_per_row_arithmetic_without_a_reduction(shape, dtype):
     ops = graphs.gated_rows(shape, dtype)

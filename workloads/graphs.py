@@ -856,7 +856,16 @@ def random_row_group(rng, shape, dtype="f32", n_ops=12, column_sums=False):
     computed_rows = [r for r in rows if g.ops[r].kind not in ("parameter", "convert")]
     if computed_rows:
         g.output(computed_rows[-1])
-    if column_sums and len(shape) >= 2:
+    if column_sums == "runs" and len(shape) >= 3:
+        # sums over the innermost row dims only, each link over the dim before the last:
+        # [B, N, S, H] -> [B, N, H] (-> [B, H]); two values summed the same way
+        levels = rng.randint(1, len(shape) - 2)
+        for _ in range(rng.randint(1, 2)):
+            c = g.tanh(rng.choice(full))
+            for _ in range(levels):
+                c = g.reduce_sum(c, len(g.shape(c)) - 2)
+            g.output(c)
+    elif column_sums and len(shape) >= 2:
         c = g.tanh(rng.choice(full))
         for _ in range(len(shape) - 1):          # one sum per leading dim: [B, S, H] -> [S, H] -> [H]
             c = g.reduce_sum(c, 0)
