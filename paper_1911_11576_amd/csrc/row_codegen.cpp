@@ -615,6 +615,7 @@ struct Gen {
   bool persistent = false;    // a fixed grid loops over the rows (groups with column reductions, or on request)
   bool want_persistent = false;
   int seg_groups = 0;         // column sums per run of rows: workgroups that share one run (1: results are stored directly)
+  bool seg_per_wave = false;  // ... or every wavefront has a run of its own (many short runs): no LDS, no barrier
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
@@ -719,17 +720,30 @@ struct Gen {
         e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = 0.0;", n.id);
       }
       e.line("  constexpr int RPW = %d;                      // rows a workgroup handles at a time", wg / L);
-      if (A.seg_rows > 0) {
+      if (A.seg_rows > 0 && seg_per_wave) {
+        // column sums per run of SEG consecutive rows, a run per wavefront (a wavefront past the last
+        // run redoes the last one and stores nothing)
+        e.line("  constexpr long long SEG = %lldll;", (long long)A.seg_rows);
+        e.line("  long long seg = (long long)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);");
+        e.line("  const bool seg_ok = seg < %lldll;", (long long)(A.rows / A.seg_rows));
+        e.line("  if (!seg_ok) seg = %lldll;", (long long)(A.rows / A.seg_rows) - 1);
+        e.line("  const long long seg_lo = seg * SEG, seg_hi = seg_lo + SEG;");
+        e.line("  const int rl = (threadIdx.x & 63) / L;          // the lane's row among those its wavefront covers at a time");
+        e.line("  const long long first_row = seg_lo, row_step = 64 / L;");
+        e.line("  for (long long row0 = first_row; row0 < seg_hi; row0 += row_step) {");
+      } else if (A.seg_rows > 0) {
         // column sums per run of SEG consecutive rows: G consecutive workgroups share one run
         e.line("  constexpr long long SEG = %lldll; constexpr int G = %d;", (long long)A.seg_rows, seg_groups);
         e.line("  const long long seg = blockIdx.x / G, seg_lo = seg * SEG, seg_hi = seg_lo + SEG;");
+        e.line("  const int rl = threadIdx.x / L;");
         e.line("  const long long first_row = seg_lo + (long long)(blockIdx.x %% G) * RPW, row_step = (long long)G * RPW;");
         e.line("  for (long long row0 = first_row; row0 < seg_hi; row0 += row_step) {");
       } else {
+        e.line("  const int rl = threadIdx.x / L;");
         e.line("  const long long first_row = (long long)blockIdx.x * RPW, row_step = (long long)gridDim.x * RPW;");
         e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += row_step) {", (long long)A.rows);
       }
-      e.line("  long long row = row0 + threadIdx.x / L;");
+      e.line("  long long row = row0 + rl;");
     }
     char row_hi[32], row_last[40], row_any[32];     // end of the rows of this workgroup's loop, its last row, a row that is surely valid
     if (persistent && A.seg_rows > 0) {
@@ -737,7 +751,7 @@ struct Gen {
     } else {
       snprintf(row_hi, sizeof row_hi, "%lldll", (long long)A.rows); snprintf(row_last, sizeof row_last, "%lldll", (long long)A.rows - 1); snprintf(row_any, sizeof row_any, "0");
     }
-    e.line("  const bool row_ok = row < %s;", row_hi);
+    e.line("  const bool row_ok = row < %s%s;", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
     e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);
@@ -800,9 +814,9 @@ struct Gen {
         // the prologue goes before the row loop: find the loop header emitted above
         const std::string header = "  for (long long row0 = ";
         const size_t at = e.s.rfind(header);
-        snprintf(buf, sizeof buf, "  long long rowp = first_row + threadIdx.x / L;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
+        snprintf(buf, sizeof buf, "  long long rowp = first_row + rl;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
         e.s.insert(at, std::string(buf) + pro);
-        e.line("  long long rown = row0 + row_step + threadIdx.x / L;");
+        e.line("  long long rown = row0 + row_step + rl;");
         e.line("  if (rown >= %s) rown = %s;          // past the end: any valid row (one that is cached by then)", row_hi, row_any);
         e.s += nxt;
         e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
@@ -1003,7 +1017,7 @@ struct Gen {
       e.line("  }");
     }
     // a run of rows that one workgroup sums alone: its sums are the results, stored as they are
-    const bool direct = A.seg_rows > 0 && seg_groups == 1;
+    const bool direct = A.seg_rows > 0 && (seg_groups == 1 || seg_per_wave);
     auto direct_store = [&](const RNode& n, const char* index, const char* value) {
       char buf[256];
       if (n.out_dtype == FS_F32) snprintf(buf, sizeof buf, "static_cast<float*>(a.out[%d])[seg * %lldll + %s] = (float)%s;", n.out_ord, (long long)A.cols, index, value);
@@ -1025,6 +1039,23 @@ struct Gen {
         e.line("  }");
         ++ci;
       }
+    } else if (persistent && A.n_col > 0 && seg_per_wave) {
+      // the wavefront's row groups hold the same columns: an xor butterfly adds them (fixed order), the
+      // first row group stores
+      if (L < 64) {
+        for (const RNode& n : A.nodes) if (n.cls == CLS_COL)
+          e.line("  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id);
+      }
+      e.line("  if (seg_ok && (int)(threadIdx.x & 63) < L) {");
+      for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+        char val[32];
+        snprintf(val, sizeof val, "ca%d[k][j]", n.id);
+        e.line("    UNROLL for (int k = 0; k < K; ++k) {");
+        e.line("      if (!ok[k]) continue;");
+        e.line("      UNROLL for (int j = 0; j < W; ++j) %s", direct_store(n, "col[k] + j", val).c_str());
+        e.line("    }");
+      }
+      e.line("  }");
     } else if (persistent && A.n_col > 0) {
       e.line("  __shared__ double colacc[%d][%lld];", A.n_col, (long long)A.cols);
       e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
@@ -1526,6 +1557,15 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       if (share > 4096) share = 4096;
       gen.seg_groups = (int)share;
       if (n_seg * share > 0x7fffffffLL) { *err = "generated row schedule: too many runs of rows for one grid"; return false; }
+      // Many short runs in a group that only reads full-size tensors: a run per wavefront, where a run
+      // fills a workgroup's rounds of rows badly (below 90%) or a row takes a whole wavefront anyway --
+      // nothing goes through LDS then.  Measured on [16384, 50, 128] fp32: 72 against 96 us; with a
+      // full-size output packed in, the workgroup form is the faster one (139 against 158 us).
+      bool full_out = false;
+      for (const RNode& n : A.nodes) if (n.out_ord >= 0 && n.cls == CLS_FULL) full_out = true;
+      const int64_t rounds = (A.seg_rows + per_round - 1) / per_round;
+      const bool fills_badly = A.seg_rows * 10 < rounds * per_round * 9;
+      gen.seg_per_wave = share == 1 && gen.L <= 64 && n_seg >= 2048 && A.seg_rows <= 512 && !full_out && (fills_badly || gen.L == 64);
     }
     gen.emit(&l.kernel_name);
     dump_source(gen.e.s);
@@ -1545,7 +1585,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       int64_t want = opt.grid > 0 ? opt.grid : l.L > 64 ? 256 * (2048 / l.L) / 2 : 256;
       if (l.L > 64 && opt.grid <= 0 && want > (A.rows + 15) / 16) want = (A.rows + 15) / 16;
       if (want < grid) grid = want;
-      if (n_seg > 0) grid = n_seg * gen.seg_groups;      // the runs of rows fix the grid
+      if (n_seg > 0) grid = gen.seg_per_wave ? (n_seg + l.wg / 64 - 1) / (l.wg / 64) : n_seg * gen.seg_groups;      // the runs of rows fix the grid
       l.segmented = A.seg_rows > 0;
       l.seg_count = n_seg;
       l.seg_groups = gen.seg_groups;
@@ -1555,7 +1595,8 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
         l.col_dtype[l.n_col] = n.out_dtype;
         ++l.n_col;
       }
-      if (A.n_col > 0 && l.L <= 64) l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
+      if (A.n_col > 0 && l.L <= 64 && !gen.seg_per_wave) l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
+      l.seg_per_wave = gen.seg_per_wave;
       l.workspace_bytes = (n_seg > 0 && gen.seg_groups == 1) ? 0 : (int64_t)A.n_col * grid * A.cols * 8;
       l.n_kernels = A.n_col > 0 && l.workspace_bytes > 0 ? 2 : 1;
     }
@@ -1630,7 +1671,7 @@ std::string row_gen_describe(const RowGenLaunch& l) {
   if (l.n_col > 0) {
     char how[160];
     if (l.segmented && l.n_kernels == 1)
-      snprintf(how, sizeof how, "column sums per run of %lld rows, one workgroup per run", (long long)(l.seg_count ? l.rows / l.seg_count : 0));
+      snprintf(how, sizeof how, "column sums per run of %lld rows, one %s per run", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_per_wave ? "wavefront" : "workgroup");
     else if (l.segmented)
       snprintf(how, sizeof how, "column sums per run of %lld rows, %d partial rows per run, then a combine kernel", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_groups);
     else

@@ -25,7 +25,7 @@ struct RowGenLaunch {
   int col_out[8] = {0}, col_dtype[8] = {0};   // output ordinal and dtype of each
   // column sums per run of consecutive rows ([B, S, H] summed over S): number of runs (0: sums over all
   // rows) and workgroups per run; with one workgroup per run the kernel stores the results itself
-  bool segmented = false;
+  bool segmented = false, seg_per_wave = false;
   int64_t seg_count = 0;
   int seg_groups = 0;
   int n_kernels = 1;
