@@ -128,7 +128,7 @@ typedef enum {
                             hand-written kernels for the recognised patterns (LayerNorm,
                             softmax, ...), a generated kernel for any other mix of
                             elementwise ops and reductions over the last dim */
-  FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials: sums over
+  FS_SCHED_ROW_COL = 2,  /* row schedule packed with column reductions via LDS partials: sums or maxima over
                             all rows ([R, C] -> [C], on higher ranks spelled as a chain of sums over
                             the leading dim), or over each run of the innermost row dims
                             ([B, S, H] -> [B, H]: sequence pooling) */

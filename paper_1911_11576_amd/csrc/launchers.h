@@ -75,6 +75,6 @@ int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, 
 // out[r][s][c] = sum over g of partial[r][s * groups + g][c] (doubles), stored in dtype[r]; r < n_red <= 8;
 // s < n_seg runs of rows (1: sums over all rows)
 int col_combine_launch(const void* partial, int groups, int64_t cols, int n_red, void* const* out, const int* dtype,
-                       void* stream, std::string* err, int64_t n_seg = 1);
+                       void* stream, std::string* err, int64_t n_seg = 1, const int* is_max = nullptr);   // is_max[r]: a maximum, not a sum
 
 }  // namespace fs

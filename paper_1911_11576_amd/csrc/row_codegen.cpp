@@ -289,10 +289,10 @@ struct Analysis {
       for (int i = 0; i < n; ++i) for (int j = 0; j < operand_count(g[i].kind); ++j) ++n_users[g[i].operand[j]];
       for (int i = 0; i < n; ++i) {
         const Node& x = g[i];
-        if (x.kind != FS_REDUCE_SUM || x.axis != 0 || x.rank != 1 || rank < 2 || x.shape[0] != S[rank - 1]) continue;
+        if (!is_reduce(x.kind) || x.axis != 0 || x.rank != 1 || rank < 2 || x.shape[0] != S[rank - 1]) continue;
         int cur = x.operand[0], levels = 1;
         std::vector<int> mids;
-        while (g[cur].kind == FS_REDUCE_SUM && g[cur].axis == 0 && n_users[cur] == 1 && out_ord[cur] < 0) {
+        while (g[cur].kind == x.kind && g[cur].axis == 0 && n_users[cur] == 1 && out_ord[cur] < 0) {
           mids.push_back(cur);
           cur = g[cur].operand[0];
           ++levels;
@@ -310,10 +310,10 @@ struct Analysis {
       for (int i = 0; i < n; ++i) for (int j = 0; j < operand_count(g[i].kind); ++j) ++n_users[g[i].operand[j]];
       for (int i = 0; i < n; ++i) {
         const Node& x = g[i];
-        if (x.kind != FS_REDUCE_SUM || col_base[i] >= 0 || col_mid[i] || out_ord[i] < 0) continue;
+        if (!is_reduce(x.kind) || col_base[i] >= 0 || col_mid[i] || out_ord[i] < 0) continue;
         int cur = i, levels = 0;
         std::vector<int> mids;
-        while (g[cur].kind == FS_REDUCE_SUM && g[g[cur].operand[0]].rank >= 3 && g[cur].axis == g[g[cur].operand[0]].rank - 2 &&
+        while (g[cur].kind == x.kind && g[g[cur].operand[0]].rank >= 3 && g[cur].axis == g[g[cur].operand[0]].rank - 2 &&
                (cur == i || (n_users[cur] == 1 && out_ord[cur] < 0))) {
           if (cur != i) mids.push_back(cur);
           cur = g[cur].operand[0];
@@ -396,7 +396,6 @@ struct Analysis {
       r.id = i;
       if (col_base[i] >= 0) {
         // a reduction over the rows: packed with the row work over the same register-resident rows
-        if (k != FS_REDUCE_SUM) return fail("generated row schedule: only sums are reduced over the rows");
         if (out_ord[i] < 0) return fail("generated row schedule: a column-reduced value must be a group output");
         r.cls = CLS_COL; r.op = k; r.nop = 1;
         cls[i] = CLS_COL;
@@ -717,7 +716,7 @@ struct Gen {
       // and leave as one partial row per workgroup (a second, tiny kernel adds the partial rows).
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
         e.line("  double ca%d[K][W];", n.id);
-        e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = 0.0;", n.id);
+        e.line("  UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = %s;", n.id, n.op == FS_REDUCE_MAX ? "-__builtin_inf()" : "0.0");
       }
       e.line("  constexpr int RPW = %d;                      // rows a workgroup handles at a time", wg / L);
       if (A.seg_rows > 0 && seg_per_wave) {
@@ -907,7 +906,10 @@ struct Gen {
       };
       if (n.cls == CLS_COL) {
         const std::string x = opnd(n.o[0], CLS_FULL);
-        e.line("  if (row_ok) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += (double)%s;", n.id, x.c_str());
+        if (n.op == FS_REDUCE_MAX)
+          e.line("  if (row_ok) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = fmax(ca%d[k][j], (double)%s);", n.id, n.id, x.c_str());
+        else
+          e.line("  if (row_ok) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += (double)%s;", n.id, x.c_str());
         continue;
       }
       if (reduce) {
@@ -1044,7 +1046,9 @@ struct Gen {
       // first row group stores
       if (L < 64) {
         for (const RNode& n : A.nodes) if (n.cls == CLS_COL)
-          e.line("  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id);
+          e.line(n.op == FS_REDUCE_MAX
+                     ? "  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = fmax(ca%d[k][j], shfl_xor_f64(ca%d[k][j], m));"
+                     : "  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id, n.id);
       }
       e.line("  if (seg_ok && (int)(threadIdx.x & 63) < L) {");
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
@@ -1058,13 +1062,24 @@ struct Gen {
       e.line("  }");
     } else if (persistent && A.n_col > 0) {
       e.line("  __shared__ double colacc[%d][%lld];", A.n_col, (long long)A.cols);
-      e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
+      {
+        unsigned max_mask = 0;      // a maximum starts from -inf (one loop: each element is initialised by one thread)
+        int r = 0;
+        for (const RNode& n : A.nodes) if (n.cls == CLS_COL) { if (n.op == FS_REDUCE_MAX) max_mask |= 1u << r; ++r; }
+        if (max_mask == 0)
+          e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = 0.0;", (long long)A.n_col * A.cols);
+        else
+          e.line("  for (int i = threadIdx.x; i < %lld; i += blockDim.x) (&colacc[0][0])[i] = ((0x%xu >> (i / %lld)) & 1u) ? -__builtin_inf() : 0.0;",
+                 (long long)A.n_col * A.cols, max_mask, (long long)A.cols);
+      }
       e.line("  __syncthreads();");
       // fixed summation order (results are bit-reproducible): first the row groups of a wavefront
       // (lanes that hold the same columns) by an xor butterfly, then the wavefronts one after the other
       if (L < 64) {
         for (const RNode& n : A.nodes) if (n.cls == CLS_COL)
-          e.line("  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id);
+          e.line(n.op == FS_REDUCE_MAX
+                     ? "  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] = fmax(ca%d[k][j], shfl_xor_f64(ca%d[k][j], m));"
+                     : "  for (int m = L; m < 64; m <<= 1) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += shfl_xor_f64(ca%d[k][j], m);", n.id, n.id, n.id);
       }
       e.line("  for (int w = 0; w < (int)blockDim.x / 64; ++w) {");
       e.line("    if ((int)(threadIdx.x >> 6) == w && (int)(threadIdx.x & 63) < L) {");
@@ -1072,7 +1087,8 @@ struct Gen {
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
         e.line("      UNROLL for (int k = 0; k < K; ++k) {");
         e.line("        if (!ok[k]) continue;");
-        e.line("        UNROLL for (int j = 0; j < W; ++j) colacc[%d][col[k] + j] += ca%d[k][j];", ci, n.id);
+        if (n.op == FS_REDUCE_MAX) e.line("        UNROLL for (int j = 0; j < W; ++j) colacc[%d][col[k] + j] = fmax(colacc[%d][col[k] + j], ca%d[k][j]);", ci, ci, n.id);
+        else e.line("        UNROLL for (int j = 0; j < W; ++j) colacc[%d][col[k] + j] += ca%d[k][j];", ci, n.id);
         e.line("      }");
         ++ci;
       }
@@ -1593,6 +1609,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
         l.col_out[l.n_col] = n.out_ord;
         l.col_dtype[l.n_col] = n.out_dtype;
+        l.col_is_max[l.n_col] = n.op == FS_REDUCE_MAX ? 1 : 0;
         ++l.n_col;
       }
       if (A.n_col > 0 && l.L <= 64 && !gen.seg_per_wave) l.lds_bytes = (int64_t)A.n_col * A.cols * 8;
@@ -1671,9 +1688,9 @@ std::string row_gen_describe(const RowGenLaunch& l) {
   if (l.n_col > 0) {
     char how[160];
     if (l.segmented && l.n_kernels == 1)
-      snprintf(how, sizeof how, "column sums per run of %lld rows, one %s per run", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_per_wave ? "wavefront" : "workgroup");
+      snprintf(how, sizeof how, "column reductions per run of %lld rows, one %s per run", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_per_wave ? "wavefront" : "workgroup");
     else if (l.segmented)
-      snprintf(how, sizeof how, "column sums per run of %lld rows, %d partial rows per run, then a combine kernel", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_groups);
+      snprintf(how, sizeof how, "column reductions per run of %lld rows, %d partial rows per run, then a combine kernel", (long long)(l.seg_count ? l.rows / l.seg_count : 0), l.seg_groups);
     else
       snprintf(how, sizeof how, "%d partial rows, then a combine kernel", l.grid);
     snprintf(buf, sizeof buf, "reduce x%d[GRID,%s] + column reduce x%d[GRID-S,CTA] + elementwise x%d[GRID,%s-THREAD_%d] packed (generated kernel %s, %zu bytes of code; %s); cta_num=%d, cta_size=%d, lds=%lld",
@@ -1706,8 +1723,8 @@ int row_gen_launch(RowGenLaunch& l, const void* const* in, void* const* out, int
   if (rc != 0 || l.n_col == 0 || l.n_kernels == 1) return rc;
   void* col_out[8];
   for (int r = 0; r < l.n_col; ++r) col_out[r] = out[l.col_out[r]];
-  if (l.seg_count > 0) return col_combine_launch(workspace, l.seg_groups, l.cols, l.n_col, col_out, l.col_dtype, stream, err, l.seg_count);
-  return col_combine_launch(workspace, l.grid, l.cols, l.n_col, col_out, l.col_dtype, stream, err);
+  if (l.seg_count > 0) return col_combine_launch(workspace, l.seg_groups, l.cols, l.n_col, col_out, l.col_dtype, stream, err, l.seg_count, l.col_is_max);
+  return col_combine_launch(workspace, l.grid, l.cols, l.n_col, col_out, l.col_dtype, stream, err, 1, l.col_is_max);
 }
 
 void row_gen_release(RowGenLaunch& l) { ew_module_release(&l.loaded); }

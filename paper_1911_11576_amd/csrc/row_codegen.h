@@ -22,7 +22,7 @@ struct RowGenLaunch {
   // column reductions: one double-precision partial row per workgroup in the plan's workspace,
   // then a second kernel adds them
   int n_col = 0;
-  int col_out[8] = {0}, col_dtype[8] = {0};   // output ordinal and dtype of each
+  int col_out[8] = {0}, col_dtype[8] = {0}, col_is_max[8] = {0};   // output ordinal, dtype and operator of each
   // column sums per run of consecutive rows ([B, S, H] summed over S): number of runs (0: sums over all
   // rows) and workgroups per run; with one workgroup per run the kernel stores the results itself
   bool segmented = false, seg_per_wave = false;

@@ -31,6 +31,7 @@ int stream_copy_launch(void* dst, const void* src, int64_t bytes, void* stream, 
 struct ColCombineArgs {
   void* out[8];
   int dtype[8];
+  int is_max[8];     // the reduction is a maximum, not a sum
 };
 
 __global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restrict__ partial, int groups, int64_t total_groups,
@@ -41,24 +42,33 @@ __global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restr
   const int64_t seg = blockIdx.x / col_blocks;
   const int r = blockIdx.y, j = threadIdx.x & 15, slice = threadIdx.x >> 4;
   const int64_t c = (blockIdx.x % col_blocks) * 16 + j;
-  double s = 0.0;
+  const bool is_max = args.is_max[r] != 0;
+  double s = is_max ? -__builtin_inf() : 0.0;
   if (c < cols) {
     const double* p = partial + ((int64_t)r * total_groups + seg * groups) * cols + c;
-    // four partial rows requested at a time (the loads are independent, the additions keep their order)
-    int g = slice;
-    for (; g + 192 < groups; g += 256) {
-      const double v0 = p[(int64_t)g * cols], v1 = p[(int64_t)(g + 64) * cols];
-      const double v2 = p[(int64_t)(g + 128) * cols], v3 = p[(int64_t)(g + 192) * cols];
-      s += v0; s += v1; s += v2; s += v3;
+    if (is_max) {
+      for (int g = slice; g < groups; g += 64) s = fmax(s, p[(int64_t)g * cols]);
+    } else {
+      // four partial rows requested at a time (the loads are independent, the additions keep their order)
+      int g = slice;
+      for (; g + 192 < groups; g += 256) {
+        const double v0 = p[(int64_t)g * cols], v1 = p[(int64_t)(g + 64) * cols];
+        const double v2 = p[(int64_t)(g + 128) * cols], v3 = p[(int64_t)(g + 192) * cols];
+        s += v0; s += v1; s += v2; s += v3;
+      }
+      for (; g < groups; g += 64) s += p[(int64_t)g * cols];
     }
-    for (; g < groups; g += 64) s += p[(int64_t)g * cols];
   }
   part[slice][j] = s;
   __syncthreads();
   if (slice == 0 && c < cols) {
     double t = part[0][j];
+    if (is_max) {
+      for (int k = 1; k < 64; ++k) t = fmax(t, part[k][j]);
+    } else {
 #pragma unroll 8
-    for (int k = 1; k < 64; ++k) t += part[k][j];
+      for (int k = 1; k < 64; ++k) t += part[k][j];
+    }
     void* o = args.out[r];
     const float f = (float)t;
     const int64_t at = seg * cols + c;
@@ -70,12 +80,12 @@ __global__ __launch_bounds__(1024) void col_combine_kernel(const double* __restr
 // partial: [n_red][n_seg * groups][cols] doubles -- for every reduction and every run of rows, `groups`
 // partial rows, added in a fixed order into out[r][n_seg][cols].  n_seg = 1: sums over all rows.
 int col_combine_launch(const void* partial, int groups, int64_t cols, int n_red, void* const* out, const int* dtype,
-                       void* stream, std::string* err, int64_t n_seg) {
+                       void* stream, std::string* err, int64_t n_seg, const int* is_max) {
   if (n_red <= 0 || cols <= 0 || n_seg <= 0) return 0;
   const int64_t blocks = n_seg * ((cols + 15) / 16);
   if (blocks > 0x7fffffffLL) { *err = "col_combine launch: too many runs of rows for one grid"; return -1; }
   ColCombineArgs a{};
-  for (int r = 0; r < n_red && r < 8; ++r) { a.out[r] = out[r]; a.dtype[r] = dtype[r]; }
+  for (int r = 0; r < n_red && r < 8; ++r) { a.out[r] = out[r]; a.dtype[r] = dtype[r]; a.is_max[r] = is_max ? is_max[r] : 0; }
   const dim3 grid((unsigned)blocks, (unsigned)n_red);
   hipLaunchKernelGGL(col_combine_kernel, grid, dim3(1024), 0, static_cast<hipStream_t>(stream),
                      static_cast<const double*>(partial), groups, n_seg * (int64_t)groups, cols, a);

@@ -421,11 +421,11 @@ def test_tuned_options_are_reused_by_later_plans(tmp_path):
 def test_plan_tune_rejects_unsupported_groups_and_bad_arguments():
     announce("tune errors")
     g = graphs.Graph()
-    x = g.parameter("x", "f32", (4, 8, 64))
-    g.output(g.reduce_sum(g.exp(x), 1))       # a reduction over a middle dim has no stitched schedule
-    t = torch.zeros(4, 8, 64, device="cuda:0")
+    x = g.parameter("x", "f32", (4, 8, 6, 64))
+    g.output(g.reduce_sum(g.exp(x), 1))       # a reduction over an outer dim that keeps the dims between: no stitched schedule
+    t = torch.zeros(4, 8, 6, 64, device="cuda:0")
     with pytest.raises(FsError) as e:
-        Plan.tune(g.ops, [t], [torch.empty(4, 64, device="cuda:0")])
+        Plan.tune(g.ops, [t], [torch.empty(4, 6, 64, device="cuda:0")])
     assert e.value.status == binding.FS_ERR_UNSUPPORTED
     ops, ins = graphs.layernorm_fwd(4, 768), inputs.layernorm_fwd(4, 768)
     dev_in, dev_out = to_device(ops, ins), alloc_outputs(ops)

@@ -60,6 +60,10 @@ def _rmsnorm_inputs(shape, dtype="f32"):
     return inputs.normal_tensors([shape, shape[-1:]], dtype)
 
 
+def _sequence_pool_inputs(shape, levels=1, dtype="f32", with_row_work=False):
+    return inputs.normal_tensors([shape], dtype, seed_offset=14)
+
+
 def _ln_stats_inputs(rows, cols, dtype="f32"):
     return inputs.layernorm_fwd(rows, cols, dtype)
 
@@ -69,8 +73,8 @@ def _ln_stats_inputs(rows, cols, dtype="f32"):
 # matches, the stand-in for the paper's motivating example (Section 3.1) at the sizes it
 # quotes, and the backward tail of a Transformer block (two row reductions, three column sums and
 # two full outputs packed over the same rows), and the momentum update of a Transformer layer's eight
-# parameter tensors as one group of independent parts of different shapes.  Not benchmark configs,
-# so not in CONFIGS.
+# parameter tensors as one group of independent parts of different shapes, and sequence pooling
+# ([B, S, H] summed over S: column sums per run of rows).  Not benchmark configs, so not in CONFIGS.
 EXTRA_GROUPS = [
     Config(6, "adam_update_packed", graphs.adam_update, inputs.adam_update,
            dict(shape=(16384, 1024)), dict(shape=(129, 512)), "f32"),
@@ -89,5 +93,7 @@ EXTRA_GROUPS = [
     Config(13, "multi_tensor_momentum", graphs.multi_tensor_momentum, inputs.multi_tensor_momentum,
            dict(shapes=[(1024, 1024), (1024,), (1024, 1024), (1024,), (4096, 1024), (4096,), (1024,), (1024,)]),
            dict(shapes=[(33, 100), (100,), (7,), (64, 64)]), "f32"),
+    Config(14, "sequence_pool", graphs.sequence_pool, _sequence_pool_inputs,
+           dict(shape=(16384, 50, 128)), dict(shape=(37, 50, 128)), "f32"),
 ]
 BY_NAME = {c.name: c for c in CONFIGS + EXTRA_GROUPS}

@@ -433,11 +433,11 @@ def max_abs_over_trailing_dims(shape, n_trailing, dtype="f32"):
     return g.ops
 
 
-def sequence_pool(shape, levels=1, dtype="f32", with_row_work=False):
+def sequence_pool(shape, levels=1, dtype="f32", with_row_work=False, pool="sum"):
     """Sum pooling over the innermost row dims: x[.., S, H] -> tanh -> sum over S -> [.., H] (with
     levels=2, over the two dims before the last, each a reduction of its own).  With row work the
-    pooled value is tanh(x - rowmax(x)), which is a second, full-size output.  Parameter x; outputs
-    (full value if any, pooled); the pooled output is f32."""
+    pooled value is tanh(x - rowmax(x)), which is a second, full-size output.  `pool`: "sum", "max" or
+    "both" (two pooled outputs).  Parameter x; outputs (full value if any, pooled...); pooled outputs are f32."""
     g = Graph()
     x = g.parameter("x", dtype, shape)
     v = x if dtype == "f32" else g.convert(x, "f32")
@@ -447,10 +447,11 @@ def sequence_pool(shape, levels=1, dtype="f32", with_row_work=False):
         g.output(v if dtype == "f32" else g.convert(v, dtype), "y")
     else:
         v = g.tanh(v)
-    s = v
-    for _ in range(levels):
-        s = g.reduce_sum(s, len(g.shape(s)) - 2)
-    g.output(s, "pooled_sum")
+    for kind in (("sum", "max") if pool == "both" else (pool,)):
+        s = v
+        for _ in range(levels):
+            s = (g.reduce_sum if kind == "sum" else g.reduce_max)(s, len(g.shape(s)) - 2)
+        g.output(s, "pooled_" + kind)
     return g.ops
 
 
