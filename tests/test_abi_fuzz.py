@@ -13,7 +13,10 @@ from workloads import graphs
 def _bases():
     return [graphs.layernorm_fwd(8, 64), graphs.scaled_masked_softmax((2, 2, 8, 16), 0.125, "key_padding"),
             graphs.layernorm_bwd(8, 64), graphs.causal_attention(2, 16, 32), graphs.adam_update((8, 16)),
-            graphs.multi_interest_pattern(2, 6, 6, 1), graphs.bias_gelu_bwd(8, 32), graphs.multi_tensor_momentum([(4, 8), (5,)])]
+            graphs.multi_interest_pattern(2, 6, 6, 1), graphs.bias_gelu_bwd(8, 32), graphs.multi_tensor_momentum([(4, 8), (5,)]),
+            graphs.sequence_pool((3, 5, 16), 1, "f32", True, "both"), graphs.sequence_pool((2, 3, 4, 8), 2, "bf16"),
+            graphs.norm_over_trailing_dims((4, 3, 8)), graphs.max_abs_over_trailing_dims((2, 3, 4, 8), 3, "f16"),
+            graphs.clip_by_global_norm([(4, 8), (5,)], 1.0)]
 
 
 def _mutate(rng, arr):
