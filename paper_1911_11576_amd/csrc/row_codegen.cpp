@@ -12,6 +12,12 @@
 // L = 128..1024: the block-composed template, one workgroup per row, wavefronts combine
 // through one float each in LDS and a barrier); a lane keeps its K chunks of W consecutive
 // elements of every live full value in registers from the row's one read to its one write.
+//
+// Packed with the row work (kernel packing, Section 5.1): reductions over the rows -- sums and maxima
+// of a full value over all rows, or over each run of consecutive rows ([B, S, H] -> [B, H]) -- kept as
+// running values per lane and column while a fixed grid of workgroups loops over the rows; small batched
+// dots whose operands are a row's registers.  Rows too long for registers are streamed in passes by one
+// workgroup, with LDS row buffers laid out by the shared-memory optimisation (Section 5.3, Algorithm 4).
 #include "row_codegen.h"
 #include "shared_plan.h"
 #include "launchers.h"

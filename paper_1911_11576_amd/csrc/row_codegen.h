@@ -1,6 +1,7 @@
 // Generated form of the row schedule (warp composition, paper Section 5.1, emitted as code,
 // Section 5.3): any group of elementwise ops and reductions over the last dim, in any
-// order and depth, whose row fits the registers of up to 64 lanes.  See row_codegen.cpp.
+// order and depth, with column reductions and small dots packed in; rows in the registers of
+// 1 to 1024 lanes, or streamed through LDS.  See row_codegen.cpp.
 #pragma once
 #include <stdint.h>
 #include <string>
