@@ -380,9 +380,10 @@ class FusionPlan:
                                         members=list(gmem[:n_mem.value]), score_us=score.value))
             for k in range(npat.value):
                 n_ops, origin, saved, score, chosen = C.c_int32(), C.c_int32(), C.c_int64(), C.c_double(), C.c_int32()
-                buf = (C.c_int32 * 64)()
-                _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), buf, 64, C.byref(origin), C.byref(saved), C.byref(score), C.byref(chosen)))
-                self.patterns.append(dict(ops=list(buf[:min(64, n_ops.value)]), n_ops=n_ops.value, origin=origin.value,
+                _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), None, 0, None, None, None, None))      # its size first
+                buf = (C.c_int32 * max(1, n_ops.value))()
+                _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), buf, n_ops.value, C.byref(origin), C.byref(saved), C.byref(score), C.byref(chosen)))
+                self.patterns.append(dict(ops=list(buf[:n_ops.value]), n_ops=n_ops.value, origin=origin.value,
                                           saved_bytes=saved.value, score_us=score.value, chosen=bool(chosen.value)))
         finally:
             lib().fs_fusion_destroy(h)

@@ -238,6 +238,12 @@ struct Planner {
     auto flush = [&]() {
       if (seg.size() >= 2) {
         add(seg, 0);
+        // a segment beyond the size a pattern may have: its consecutive stretches of that size, and of
+        // half that size (any stretch of a topological order is convex)
+        if ((int)seg.size() > cfg.max_pattern_ops)
+          for (int len : {cfg.max_pattern_ops, cfg.max_pattern_ops / 2})
+            for (size_t at = 0; len >= 2 && at < seg.size(); at += (size_t)len)
+              add(std::vector<int>(seg.begin() + at, seg.begin() + std::min(seg.size(), at + (size_t)len)), 0);
         // its connected parts as patterns of their own (what the generator takes when the
         // whole segment mixes shapes)
         std::map<int, int> comp;

@@ -13,7 +13,7 @@ struct FusionConfig {
   double launch_us = 2.5;                 // phi: average launch latency of one kernel
   int max_patterns = 256;                 // patterns per conflict component handed to the solver (the best by score)
   int explore_budget = 400;               // patterns the exploratory search may visit
-  int max_pattern_ops = 40;
+  int max_pattern_ops = 128;
   int64_t seed_bytes = 1 << 20;           // exploratory seeds: ops whose result is at least this large
   std::vector<std::pair<int64_t, double>> bandwidth;   // M(V) model: (bytes, GB/s), increasing bytes
   std::vector<std::vector<int>> extra_patterns;        // caller-supplied candidates

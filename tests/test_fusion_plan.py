@@ -216,6 +216,26 @@ def test_scalars_between_groups_clip_by_global_norm():
             assert p.info()["schedule"] != "per_op"
 
 
+def test_segments_longer_than_a_pattern_are_cut_into_stretches():
+    """A stack of row-local layers with no partition op between them: up to the pattern size the whole
+    stack is one group (one row kernel, rows stay in registers across the layers); beyond it the segment's
+    consecutive stretches of that size are the candidates, and the plan is a few large groups -- not
+    the pieces between reductions."""
+    ops = graphs.encoder_tail_stack(3, 4096, 1024)
+    fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
+    assert len(fp.groups) == 1
+    _check_plan(ops, fp, brute_force=False)
+    ops = graphs.encoder_tail_stack(12, 4096, 1024)
+    owned = sum(1 for op in ops if of.owns_kernel(op))
+    assert owned > 2 * 128
+    fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE)
+    _check_plan(ops, fp, brute_force=False)
+    assert len(fp.groups) <= 4 and max(len(g["members"]) for g in fp.groups) == 128
+    for g in fp.groups:
+        with Plan(g["ops"]) as p:
+            assert p.info()["schedule"] == "row" and p.info()["n_kernels"] == 1
+
+
 def test_random_elementwise_graphs():
     rng = random.Random(7)
     for trial in range(6):

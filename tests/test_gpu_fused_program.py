@@ -208,3 +208,18 @@ def test_clip_by_global_norm_passes_scalars_between_groups(max_norm):
         assert_close(a, b, TOLERANCE["f32"], "clip by global norm")
     with Plan(ops, "per_op") as p:
         assert n_kernels < p.info()["n_kernels"]
+
+
+@pytest.mark.parametrize("n_layers", [3, 8])
+def test_stack_of_row_local_layers(n_layers):
+    """Layers with no partition op between them: the planner makes one group of three layers (one row
+    kernel with six reductions) and cuts eight layers into stretches of at most 128 ops."""
+    announce(f"fused program stack of {n_layers} layers")
+    rows, cols = 150, 512
+    ops = graphs.encoder_tail_stack(n_layers, rows, cols)
+    ins = inputs.normal_tensors([(rows, cols)] + [(cols,)] * (3 * n_layers), "f32", seed_offset=60, scale=0.7)
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins)
+    assert n_groups == (1 if n_layers == 3 else 2) and n_kernels == n_groups
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE["f32"], f"stack of {n_layers} layers")

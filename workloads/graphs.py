@@ -455,6 +455,23 @@ def sequence_pool(shape, levels=1, dtype="f32", with_row_work=False, pool="sum")
     return g.ops
 
 
+def encoder_tail_stack(n_layers, rows, cols, eps=1e-5):
+    """`n_layers` times bias + GELU(tanh) + residual + LayerNorm, each layer reading the one before:
+    every op is local to a row, so any stretch of the list is a valid row group -- a planner test for
+    segments longer than a pattern may be.  Parameters: x[rows, cols], then (bias, gamma, beta)[cols]
+    per layer; one output."""
+    g = Graph()
+    cur = g.parameter("x", "f32", (rows, cols))
+    for k in range(n_layers):
+        b, ga, be = (g.parameter(f"{n}{k}", "f32", (cols,)) for n in ("bias", "gamma", "beta"))
+        h = g.add(cur, g.col_broadcast(b, cur))
+        inner = g.multiply(g.add(h, g.multiply(g.multiply(g.multiply(h, h), h), g.constant(0.044715))), g.constant(0.7978845608028654))
+        gelu = g.multiply(g.multiply(h, g.constant(0.5)), g.add(g.tanh(inner), g.constant(1.0)))
+        cur = _layernorm_tail(g, g.add(gelu, cur), ga, be, eps)
+    g.output(cur, "y")
+    return g.ops
+
+
 def scale_shift_rows_cols(shape, dtype="f32"):
     """y = (x - rowv) * colv / (1 + exp(-x)) with a per-row and a per-column operand:
     broadcasts along either side folded into one elementwise group."""
