@@ -17,7 +17,7 @@
 // of a full value over all rows, or over each run of consecutive rows ([B, S, H] -> [B, H]) -- kept as
 // running values per lane and column while a fixed grid of workgroups loops over the rows; small batched
 // dots whose operands are a row's registers.  Rows too long for registers are streamed in passes by one
-// workgroup, with LDS row buffers laid out by the shared-memory optimisation (Section 5.3, Algorithm 4).
+// workgroup, with LDS row buffers laid out by the shared-memory optimisation (Section 5.4, Algorithm 4).
 #include "row_codegen.h"
 #include "shared_plan.h"
 #include "launchers.h"
