@@ -194,6 +194,56 @@ def bench_group(cfg, steps, warmup, with_per_op=True, build_kw=None):
     return res, ev_ms, wall_ms
 
 
+def bench_programs(steps=40, warmup=5):
+    """Whole graphs through the fusion planner (Section 4) and the stitched groups it makes, against the
+    same graph one kernel per op: a stack of five row-local layers (bias + GELU + residual + LayerNorm,
+    no partition op between them) and the clipping of four gradient tensors by their global norm.  Device tensors are drawn by torch (seeded); results are checked elsewhere (tests)."""
+    import torch
+    from paper_1911_11576_amd import FusedProgram, Plan
+    from workloads import graphs
+    gen = torch.Generator(device="cuda:0").manual_seed(1911)
+    rnd = lambda *shape: torch.randn(*shape, device="cuda:0", generator=gen)
+    rows, cols, layers = 16384, 1024, 5
+    shapes = [(4096, 1024), (1024,), (1024, 4096), (4096,)]
+    cases = {
+        "encoder_tail_stack_5_layers": (graphs.encoder_tail_stack(layers, rows, cols),
+                                        [rnd(rows, cols)] + [0.5 * rnd(cols) for _ in range(3 * layers)]),
+        "clip_by_global_norm_4_tensors": (graphs.clip_by_global_norm(shapes, 1.0), [rnd(*sh) for sh in shapes]),
+    }
+
+    def timed(fn):
+        t_end = time.perf_counter() + SPIN_UP_S
+        while time.perf_counter() < t_end:
+            fn()
+            torch.cuda.synchronize()
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e3
+
+    out = {}
+    for name, (ops, ins) in cases.items():
+        with FusedProgram(ops) as prog:
+            prog.bind(ins)
+            fused_us = timed(prog.run_bound)
+            res = {"ops": len(ops), "groups": len(prog.fusion.groups), "kernels": prog.n_kernels, "fused_us": fused_us,
+                   "group_sizes": [len(g["members"]) for g in prog.fusion.groups]}
+        with Plan(ops, "per_op") as plan:
+            outs = [torch.empty(op.shape, dtype=_torch_dt()[op.dtype], device="cuda:0") for op in ops if op.kind == "output"]
+            per_op_us = timed(lambda: plan.launch(ins, outs))
+            res.update(per_op_kernels=plan.info()["n_kernels"], per_op_us=per_op_us, speedup_vs_per_op=per_op_us / fused_us)
+        out[name] = res
+        del ins
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(cfg):
     """The oracle as it stands on the host cores, on a bounded row sample of the headline
     workload (numpy runs its elementwise loops on one thread)."""
@@ -287,6 +337,10 @@ def main():
             groups[cfg.name] = bench_group(cfg, max(20, args.steps // (25 if heavy else 4)), max(3, args.warmup // (10 if heavy else 2)))[0]
         out["groups"] = groups
         out["bandwidth_model"] = bandwidth_model()
+        try:
+            out["programs"] = bench_programs()
+        except Exception as e:      # an extra beside the groups: report, do not fail the bench
+            out["programs"] = {"error": str(e)}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(head)
     print(json.dumps(out))
