@@ -152,6 +152,9 @@ typedef enum {
  * with the HIP run-time compiler (a few hundred milliseconds the first time a given
  * group is seen, cached afterwards per process and, with fs_kernel_cache_dir, per
  * machine).  Touches no GPU, so it also works on a machine without one.
+ * Limits of a group: 1..4096 ops, at most 64 parameters and 16 outputs (8 for a group with
+ * reductions or dots), tensors below 2^40 elements; beyond them FS_ERR_INVALID or
+ * FS_ERR_UNSUPPORTED with a message that names the limit.
  * Errors: FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_NOMEM. */
 fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
                          const fs_plan_options* opt, fs_plan** out);
