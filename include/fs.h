@@ -132,7 +132,9 @@ typedef enum {
                             all rows ([R, C] -> [C], on higher ranks spelled as a chain of sums over
                             the leading dim), or over each run of the innermost row dims
                             ([B, S, H] -> [B, H]: sequence pooling) */
-  FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA, P in LDS */
+  FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA; the probabilities stay in
+                                registers (accumulators of the first dot = operands of the second), V goes
+                                through LDS */
   FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as
                                 a kernel generated for the group (or interpreted, see
                                 FS_MODE_STITCHED_PREBUILT).  The ops share one shape, or fall into
@@ -159,8 +161,9 @@ typedef enum {
 fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
                          const fs_plan_options* opt, fs_plan** out);
 
-/* Enqueue the group on `hip_stream` (a hipStream_t passed as void*, NULL = the
- * default stream) and return without waiting.
+/* Run the plan's kernel (Section 5.5: the generated kernel is handed to the run time, which launches it):
+ * enqueue the group on `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and return
+ * without waiting.
  *   inputs[n_in]    host array of DEVICE pointers, one per FS_PARAMETER in list order
  *   outputs[n_out]  host array of DEVICE pointers, one per FS_OUTPUT in list order
  * Tensors are dense row-major in their op's dtype, 16-byte aligned, and borrowed until
@@ -231,11 +234,13 @@ fs_status fs_kernel_cache_dir(const char* dir);
 fs_status fs_kernel_cache_stats(int64_t* compiled, int64_t* from_memory, int64_t* from_disk);
 fs_status fs_kernel_cache_drop_memory(void);
 
-/* Release the plan and its workspace.  NULL is a no-op.  The caller makes sure no
+/* Release what fs_plan_create built (Section 5.5 ends with the kernel handed over; the plan is this
+ * library's handle on it): the plan, its loaded kernel and its workspace.  NULL is a no-op.  The caller makes sure no
  * launch of the plan is still running. */
 fs_status fs_destroy(fs_plan* plan);
 
-/* Message of the last failing call on this thread.  Library-owned, valid until the
+/* Why the last failing call failed -- for fs_plan_create this is the reason a group gets the paper's
+ * "negative score" (Section 4.3).  Message of the last failing call on this thread.  Library-owned, valid until the
  * next failing call on the same thread.  Never NULL. */
 const char* fs_last_error(void);
 

@@ -20,40 +20,20 @@
 #include "row_codegen.h"
 #include "shared_plan.h"
 #include "fusion_plan.h"
-
-struct fs_plan {
-  fs::Graph graph;
-  int mode = FS_MODE_STITCHED;
-  int schedule = FS_SCHED_PER_OP;
-  fs::Match match;
-  fs::RowLaunch row;
-  fs::RowTeamLaunch row_team;
-  fs::RowBlockLaunch row_block;
-  fs::RowGenLaunch row_gen;
-  int row_form = 0;   // 0 one wavefront per row group, 1 wavefront team, 2 row cached in LDS, 3 generated kernel
-  fs::LnBwdLaunch lnbwd;
-  fs::AttnLaunch attn;
-  fs::EwLaunch ew;
-  fs::PerOpPlan per_op;
-  int n_kernels = 1;
-  int64_t lds_bytes = 0, workspace_bytes = 0, moved_bytes = 0;
-  void* workspace = nullptr;
-  int device = -1;
-  std::string description;
-};
+#include "plan.h"
 
 struct fs_fusion {
   fs::FusionResult result;
 };
 
+namespace fs {
+fs_status set_error(fs_status st, const std::string& msg);
+}
+using fs::set_error;
+
 namespace {
 
 thread_local std::string g_error = "";
-
-fs_status set_error(fs_status st, const std::string& msg) {
-  g_error = msg;
-  return st;
-}
 
 // ---- tuning cache: winning options of fs_plan_tune per group key
 struct TuneEntry { fs_plan_options opt; double us; };
@@ -81,6 +61,11 @@ uint64_t group_key(const fs_op_desc* ops, int32_t n_ops) {
 fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_options* opt, fs_plan** out);
 
 }  // namespace
+
+fs_status fs::set_error(fs_status st, const std::string& msg) {
+  g_error = msg;
+  return st;
+}
 
 extern "C" {
 
@@ -334,6 +319,7 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
           p->schedule = FS_SCHED_ROW_COL;
           p->lds_bytes = p->lnbwd.lds_bytes;
           p->workspace_bytes = p->lnbwd.workspace_bytes;
+          p->n_kernels = p->lnbwd.n_kernels;
           p->moved_bytes = algo + 2 * (p->lnbwd.workspace_bytes);
           p->description = fs::lnbwd_stitch_describe(p->match.lnbwd, p->lnbwd);
           break;
@@ -365,8 +351,10 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
 
 extern "C" {
 
-fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* const* outputs, int32_t n_out,
-                    void* hip_stream) {
+}  // extern "C"
+
+// Arguments of a launch checked against the plan (counts, NULL and alignment, identical pointers).
+fs_status fs::check_launch_args(fs_plan* p, const void* const* inputs, int32_t n_in, void* const* outputs, int32_t n_out) {
   if (!p) return set_error(FS_ERR_INVALID, "plan is NULL");
   const fs::Graph& g = p->graph;
   if (n_in != (int32_t)g.params.size()) return set_error(FS_ERR_INVALID, "n_in differs from the number of parameters");
@@ -379,6 +367,8 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
   for (int i = 0; i < n_out; ++i) {
     if (g[g.outputs[i]].numel() == 0) continue;
     if (!outputs[i] || (reinterpret_cast<uintptr_t>(outputs[i]) & 15)) return set_error(FS_ERR_INVALID, "output pointer is NULL or not 16-byte aligned");
+    for (int k = 0; k < i; ++k)
+      if (outputs[k] == outputs[i] && g[g.outputs[k]].numel() != 0) return set_error(FS_ERR_INVALID, "two outputs share one buffer");
     // An output in the very buffer of a parameter (an update in place): fine where the kernel reads
     // every element of that parameter once, in the thread (or the row's lanes) that writes the same
     // element, before it writes -- the generated elementwise kernels and the generated register
@@ -399,44 +389,57 @@ fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* c
                                                 "(in-place updates: generated elementwise and register row kernels, same shape and dtype, parameter read only as the group's own layout)");
     }
   }
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  return FS_OK;
+}
+
+// The plan's kernels enqueued with `workspace` as their scratch memory (the plan's own, or the static array).
+fs_status fs::enqueue_plan(fs_plan* p, const void* const* inputs, void* const* outputs, int32_t n_out, void* workspace,
+                              void* hip_stream) {
   std::string err;
   try {
-    if (p->workspace_bytes > 0) {
-      int dev = -1;
-      if (hipGetDevice(&dev) != hipSuccess) return set_error(FS_ERR_HIP, "hipGetDevice failed");
-      if (!p->workspace) {
-        hipError_t e = hipMalloc(&p->workspace, (size_t)p->workspace_bytes);
-        if (e != hipSuccess) { p->workspace = nullptr; return set_error(FS_ERR_NOMEM, std::string("workspace hipMalloc: ") + hipGetErrorString(e)); }
-        p->device = dev;
-        // tickets start at zero; every launch leaves them at zero again
-        e = hipMemsetAsync(p->workspace, 0, (size_t)(p->workspace_bytes < 65536 ? p->workspace_bytes : 65536), stream);
-        if (e != hipSuccess) return set_error(FS_ERR_HIP, std::string("workspace memset: ") + hipGetErrorString(e));
-      } else if (dev != p->device) {
-        return set_error(FS_ERR_INVALID, "plan is bound to the device of its first launch");
-      }
-    }
     int rc = 0;
     switch (p->schedule) {
       case FS_SCHED_ROW:
-        rc = p->row_form == 3   ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, p->workspace, hip_stream, &err)
+        rc = p->row_form == 3   ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, workspace, hip_stream, &err)
              : p->row_form == 2 ? fs::row_block_launch(p->match.row, p->row_block, inputs, outputs, hip_stream, &err)
              : p->row_form == 1 ? fs::row_team_launch(p->match.row, p->row_team, inputs, outputs, hip_stream, &err)
                                 : fs::row_stitch_launch(p->match.row, p->row, inputs, outputs, hip_stream, &err);
         break;
       case FS_SCHED_ROW_COL:
-        rc = p->row_form == 3 ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, p->workspace, hip_stream, &err)
-                              : fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, p->workspace, hip_stream, &err);
+        rc = p->row_form == 3 ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, workspace, hip_stream, &err)
+                              : fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, workspace, hip_stream, &err);
         break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
       case FS_SCHED_ELEMENTWISE: rc = fs::ew_stitch_launch(p->ew, inputs, outputs, n_out, hip_stream, &err); break;
-      default: rc = fs::per_op_launch(g, p->per_op, inputs, outputs, p->workspace, hip_stream, &err); break;
+      default: rc = fs::per_op_launch(p->graph, p->per_op, inputs, outputs, workspace, hip_stream, &err); break;
     }
     if (rc != 0) return set_error(FS_ERR_HIP, err);
   } catch (...) {
     return set_error(FS_ERR_HIP, "internal error while launching");
   }
   return FS_OK;
+}
+
+extern "C" {
+
+fs_status fs_launch(fs_plan* p, const void* const* inputs, int32_t n_in, void* const* outputs, int32_t n_out,
+                    void* hip_stream) {
+  const fs_status st = fs::check_launch_args(p, inputs, n_in, outputs, n_out);
+  if (st != FS_OK) return st;
+  if (p->workspace_bytes > 0) {
+    // Nothing in the workspace needs an initial value: every kernel that reads it reads only what an
+    // earlier kernel of the same launch wrote there.
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return set_error(FS_ERR_HIP, "hipGetDevice failed");
+    if (!p->workspace) {
+      const hipError_t e = hipMalloc(&p->workspace, (size_t)p->workspace_bytes);
+      if (e != hipSuccess) { p->workspace = nullptr; return set_error(FS_ERR_NOMEM, std::string("workspace hipMalloc: ") + hipGetErrorString(e)); }
+      p->device = dev;
+    } else if (dev != p->device) {
+      return set_error(FS_ERR_INVALID, "plan is bound to the device of its first launch");
+    }
+  }
+  return fs::enqueue_plan(p, inputs, outputs, n_out, p->workspace, hip_stream);
 }
 
 fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* inputs, int32_t n_in,

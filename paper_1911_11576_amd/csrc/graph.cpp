@@ -51,11 +51,20 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
     if (d.reserved != 0) return fail("reserved field must be 0");
     Node n;
     n.kind = d.kind; n.dtype = d.dtype; n.rank = d.rank; n.axis = d.axis; n.attr = d.attr;
+    // every extent and the running product stay below 2^40, so the product cannot wrap; an extent of 0
+    // makes the tensor empty whatever the other extents are
+    bool empty = false;
+    for (int k = 0; k < d.rank; ++k) empty = empty || d.shape[k] == 0;
+    int64_t running = 1;
     for (int k = 0; k < d.rank; ++k) {
       if (d.shape[k] < 0) return fail("negative extent");
+      if (d.shape[k] >= ((int64_t)1 << 40)) return fail("tensor too large");
+      if (!empty) {
+        running *= d.shape[k];
+        if (running >= ((int64_t)1 << 40)) return fail("tensor too large");
+      }
       n.shape[k] = d.shape[k];
     }
-    if (n.numel() >= ((int64_t)1 << 40)) return fail("tensor too large");
     const int nop = operand_count(d.kind);
     for (int k = 0; k < 3; ++k) {
       if (k < nop) {

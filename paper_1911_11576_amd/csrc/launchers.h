@@ -30,7 +30,7 @@ int row_block_launch(const RowSpec&, const RowBlockLaunch&, const void* const* i
                      void* stream, std::string* err);
 
 // LayerNorm backward: row path for dx packed with the column path for dgamma/dbeta.
-struct LnBwdLaunch { int K = 1, wg = 512, grid = 1, group = 1; int64_t lds_bytes = 0, workspace_bytes = 0; };
+struct LnBwdLaunch { int K = 1, wg = 256, grid = 1, n_kernels = 1; int64_t lds_bytes = 0, workspace_bytes = 0; };
 bool lnbwd_stitch_plan(const LnBwdSpec&, const LaunchOpts&, LnBwdLaunch*, std::string* err);
 std::string lnbwd_stitch_describe(const LnBwdSpec&, const LnBwdLaunch&);
 int lnbwd_stitch_launch(const LnBwdSpec&, const LnBwdLaunch&, const void* const* in, void* const* out,

@@ -1,31 +1,27 @@
 // Schedules 1+2 packed (kernel packing + warp composition + block composition, paper
-// Section 5.1): LayerNorm backward as one kernel.  The row path (dx: two row reductions,
+// Section 5.1): LayerNorm backward, hand-written.  The row path (dx: two row reductions,
 // broadcast back through registers) and the column path (dgamma, dbeta: reductions over
-// all rows) have no data dependence on each other but share their inputs, so they are
-// packed over the same register-resident rows: dy and x are read from HBM exactly once.
+// all rows, which Section 4.2 lists among the ops with parallelisation needs of their own)
+// have no data dependence on each other but share their inputs, so they are packed over the
+// same register-resident rows: dy and x are read from HBM exactly once.
 //
-// Row path: one wavefront per row, lane l owns 16-byte vectors l, l+64, ...; wave64
-// all-reduce for sum(g) and sum(g*xhat).  A wavefront's next row is loaded while the
-// current one is processed (register double buffering).
-// Column path: every lane accumulates its own columns over all rows its wavefront
-// visits, in fp64 (32768-term fp32 sums would not meet a 1e-5 absolute bar), in a
-// wavefront-private LDS array (ds_add_f64; 32 accumulators per lane would otherwise take
-// 64 VGPRs).  The wavefronts of a workgroup then combine their arrays by a binary tree in
-// LDS (the `S` hand-off of block composition), each workgroup writes one partial row to
-// a plan-owned HBM workspace, and the partials are summed in a fixed order by the
-// workgroups that arrive last (two-level ticket tree).  No floating-point atomics on
-// shared data: the result is bit-reproducible.  No workgroup ever waits for another one.
+// Row path: a fixed grid of workgroups walks the rows together (row = step * grid * waves +
+// workgroup * waves + wave), one wavefront per row, lane l owns 16-byte vectors l, l+64, ...;
+// wave64 all-reduce for sum(g) and sum(g*xhat).  A wavefront requests its rows two steps
+// ahead (three register buffers): with one wavefront per SIMD the time of a step is otherwise
+// the latency of its loads.
+// Column path: every lane keeps double-precision running sums for its own columns over all
+// rows its wavefront visits (32768-term fp32 sums would not meet a 1e-5 absolute bar).  At
+// the end each wavefront writes its sums to an LDS array of its own (the `S` hand-off of
+// block composition), the workgroup adds the arrays in wavefront order and writes ONE partial
+// row to a plan-owned workspace; a second, small kernel adds the partial rows in a fixed
+// order.  No atomics, no tickets, no waiting between workgroups: the hand-off between the two
+// kernels is the stream order, and the result is bit-reproducible.
 //
-// Accumulator slot layout (LDS and workspace): slot (k*4+j)*64 + lane holds column
-// (k*64+lane)*4 + j, so that the 64 lanes of one LDS instruction touch 64 consecutive
-// doubles (no bank conflicts).  Only the final store maps slots back to columns.
-//
-// Cross-workgroup hand-off without a device-wide fence: a release fence at agent scope
-// writes back the whole L2 of the XCD, which in a kernel that is streaming hundreds of
-// megabytes of dx through that L2 costs far more than the reduction itself.  Instead the
-// partials are written and read with agent-scope atomic stores/loads (coherent across
-// the XCDs' L2s by themselves), every thread waits for its own stores to complete, the
-// workgroup barriers, and only then one thread takes the ticket.
+// Slot layout (LDS and workspace): slot q*64 + lane with q = r*4K + k*4 + j holds column
+// (k*64+lane)*4 + j of reduction r (0 dbeta, 1 dgamma), so that the 64 lanes of one LDS
+// instruction touch 64 consecutive doubles (no bank conflicts).  Only the final store of the
+// combine kernel maps slots back to columns.
 #include <mutex>
 #include <set>
 
@@ -42,77 +38,20 @@ struct LnBwdArgs {
   const float* dy; const float* x; const float* gamma; const float* mean; const float* rstd;
   float* dx; float* dgamma; float* dbeta;
   int64_t rows; int cols; int nvec; float inv_n;
-  double* part0;      // [grid][2*K*256]   one partial (slot layout) per workgroup
-  double* part1;      // [n_groups][2*K*256]
-  unsigned* tickets;  // [1 + n_groups], zero between launches
-  int group;          // workgroups per first-level group
-  int n_groups;
+  double* part;       // [grid][2*K*256]   one partial row (slot layout) per workgroup
 };
-
-// Register budget of the kernel: asking for 4 wavefronts per SIMD caps it at 128 VGPRs.
-#ifndef FS_LNBWD_MIN_WAVES
-#define FS_LNBWD_MIN_WAVES 0
-#endif
-#if FS_LNBWD_MIN_WAVES > 0
-#define FS_LNBWD_OCCUPANCY __attribute__((amdgpu_waves_per_eu(FS_LNBWD_MIN_WAVES, 8)))
-#else
-#define FS_LNBWD_OCCUPANCY
-#endif
-
-__device__ __forceinline__ void coherent_store(double* p, double v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double coherent_load(const double* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// all of this thread's earlier stores have completed at their coherence scope
-__device__ __forceinline__ void wait_for_own_stores() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0);
-}
-
-// Sum `count` consecutive partial rows of n2 doubles, in ascending row order.  A thread
-// owns four columns at a time and issues the loads of up to 16 partials of all four before
-// it uses any of them (64 independent loads in flight), so a finishing workgroup of 512
-// threads pays about one memory latency for 16 partials of 2048 columns instead of one
-// per load.
-template <class Sink>
-__device__ __forceinline__ void sum_partials(const double* __restrict__ src, int count, int n2, Sink sink) {
-  constexpr int Q = 4, D = 16;
-  const int nt = blockDim.x;
-  for (int c0 = threadIdx.x; c0 < n2; c0 += Q * nt) {
-    double acc[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) acc[q] = 0.0;
-    for (int b0 = 0; b0 < count; b0 += D) {
-      double v[Q][D];
-#pragma unroll
-      for (int q = 0; q < Q; ++q)
-#pragma unroll
-        for (int j = 0; j < D; ++j) {
-          const int c = c0 + q * nt, b = b0 + j;
-          v[q][j] = (c < n2 && b < count) ? coherent_load(src + (int64_t)b * n2 + c) : 0.0;
-        }
-#pragma unroll
-      for (int q = 0; q < Q; ++q)
-#pragma unroll
-        for (int j = 0; j < D; ++j) acc[q] += v[q][j];
-    }
-#pragma unroll
-    for (int q = 0; q < Q; ++q)
-      if (c0 + q * nt < n2) sink(c0 + q * nt, acc[q]);
-  }
-}
 
 // COL: 0 no column outputs, 1 dbeta only (x is not needed), 2 dgamma and dbeta
 // EXACT: cols == K*256, no per-vector masking
-template <int K, bool WANT_DX, int COL, bool EXACT>
-__global__ __launch_bounds__(512) FS_LNBWD_OCCUPANCY
-void lnbwd_stitch_kernel(const LnBwdArgs a) {
-  extern __shared__ double lds[];   // [waves][2][K*256] accumulator slots
-  __shared__ unsigned s_ticket;
+// PF: row steps requested ahead of the one being worked on
+// MAXWG: largest workgroup the instance is launched with (256: one wavefront per SIMD may use the
+// whole register file; 512: two share it)
+template <int K, bool WANT_DX, int COL, bool EXACT, int PF, int MAXWG>
+__global__ __launch_bounds__(MAXWG)
+void lnbwd_rows_kernel(const LnBwdArgs a) {
+  extern __shared__ double lds[];   // [waves][2*K*256] slots
   constexpr bool WANT_COL = COL != 0, NEED_X = WANT_DX || COL == 2;
-  constexpr int SLOTS = K * 256;    // per quantity
+  constexpr int SLOTS = K * 256;    // per reduction
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
   bool vld[K];
   int voff[K];
@@ -123,79 +62,77 @@ void lnbwd_stitch_kernel(const LnBwdArgs a) {
     voff[k] = (vld[k] ? vi : 0) * 4;
   }
   float gam[K][4];
-  double* acc = lds + (int64_t)wave * 2 * SLOTS + lane;   // + (k*4+j)*64 (+ SLOTS for dbeta)
+  double dg[K][4], db[K][4];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     if constexpr (WANT_DX) Vec<float>::load(a.gamma + voff[k], gam[k]);
-    if constexpr (WANT_COL) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { acc[(k * 4 + j) * 64] = 0.0; acc[SLOTS + (k * 4 + j) * 64] = 0.0; }
-    }
+    for (int j = 0; j < 4; ++j) { dg[k][j] = 0.0; db[k][j] = 0.0; }
   }
 
-  // All workgroups advance through the rows together (row = step*grid*waves + wg*waves +
-  // wave), so at any moment the chip streams one compact window of dy, x and dx, as a
-  // one-shot grid would; giving each workgroup its own contiguous block of rows instead
-  // measured about 8% slower.
+  // All workgroups advance through the rows together, so at any moment the chip streams one
+  // compact window of dy, x and dx, as a one-shot grid would.
   const int64_t row_end = a.rows;
   const int64_t row_step = (int64_t)gridDim.x * waves;
   int64_t row = (int64_t)blockIdx.x * waves + wave;
-  u32x4 dyn[K], xn[K];
-  float mun = 0.f, rsn = 0.f;
-  if (row < row_end) {
+  u32x4 rdy[PF][K], rx[PF][K];
+  float rmu[PF], rrs[PF];
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    // past the end: row 0, which is in cache by then (no extra HBM traffic); its values are never used
+    const int64_t r = row + p * row_step < row_end ? row + p * row_step : 0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      dyn[k] = stream_load16(a.dy + row * a.cols + voff[k]);
-      if constexpr (NEED_X) xn[k] = stream_load16(a.x + row * a.cols + voff[k]);
+      rdy[p][k] = stream_load16(a.dy + r * a.cols + voff[k]);
+      if constexpr (NEED_X) rx[p][k] = stream_load16(a.x + r * a.cols + voff[k]);
     }
-    if constexpr (NEED_X) { mun = a.mean[row]; rsn = a.rstd[row]; }
+    if constexpr (NEED_X) { rmu[p] = a.mean[r]; rrs[p] = a.rstd[r]; }
   }
   for (; row < row_end; row += row_step) {
     float dy[K][4], xv[K][4];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      Vec<float>::unpack(dyn[k], dy[k]);
-      if constexpr (NEED_X) Vec<float>::unpack(xn[k], xv[k]);
+      Vec<float>::unpack(rdy[0][k], dy[k]);
+      if constexpr (NEED_X) Vec<float>::unpack(rx[0][k], xv[k]);
     }
-    const float mu = mun, rs = rsn;
-    // prefetch the next row: issued unconditionally and pinned ahead of the arithmetic (the
-    // last iteration reads row 0, which every wavefront does at that point: an L2 hit, no
-    // extra HBM traffic)
-    const int64_t nrow = row + row_step < row_end ? row + row_step : 0;
+    const float mu = NEED_X ? rmu[0] : 0.f, rs = NEED_X ? rrs[0] : 0.f;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      dyn[k] = stream_load16(a.dy + nrow * a.cols + voff[k]);
-      if constexpr (NEED_X) xn[k] = stream_load16(a.x + nrow * a.cols + voff[k]);
-    }
-    if constexpr (NEED_X) { mun = a.mean[nrow]; rsn = a.rstd[nrow]; }
-    __builtin_amdgcn_sched_barrier(0);
-
-    if constexpr (WANT_COL) {
-      const double mu64 = (double)mu, rs64 = (double)rs;
-#pragma unroll
-      for (int k = 0; k < K; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const double d = vld[k] ? (double)dy[k][j] : 0.0;
-          __hip_atomic_fetch_add(acc + SLOTS + (k * 4 + j) * 64, d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-          if constexpr (COL == 2)
-            __hip_atomic_fetch_add(acc + (k * 4 + j) * 64, d * (((double)xv[k][j] - mu64) * rs64), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_WAVEFRONT);
-        }
-    }
-    if constexpr (WANT_DX) {
-      float s1 = 0.f, s2 = 0.f;
-      float g[K][4];
+    for (int p = 0; p + 1 < PF; ++p) {
 #pragma unroll
       for (int k = 0; k < K; ++k) {
+        rdy[p][k] = rdy[p + 1][k];
+        if constexpr (NEED_X) rx[p][k] = rx[p + 1][k];
+      }
+      if constexpr (NEED_X) { rmu[p] = rmu[p + 1]; rrs[p] = rrs[p + 1]; }
+    }
+    // request the row PF steps ahead, pinned ahead of the arithmetic
+    const int64_t nrow = row + PF * row_step < row_end ? row + PF * row_step : 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          xv[k][j] = (xv[k][j] - mu) * rs;              // xhat
-          g[k][j] = dy[k][j] * gam[k][j];
-          s1 += vld[k] ? g[k][j] : 0.f;
-          s2 += vld[k] ? g[k][j] * xv[k][j] : 0.f;
+    for (int k = 0; k < K; ++k) {
+      rdy[PF - 1][k] = stream_load16(a.dy + nrow * a.cols + voff[k]);
+      if constexpr (NEED_X) rx[PF - 1][k] = stream_load16(a.x + nrow * a.cols + voff[k]);
+    }
+    if constexpr (NEED_X) { rmu[PF - 1] = a.mean[nrow]; rrs[PF - 1] = a.rstd[nrow]; }
+    __builtin_amdgcn_sched_barrier(0);
+
+    float s1 = 0.f, s2 = 0.f;
+    float g[K][4];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float d = vld[k] ? dy[k][j] : 0.f;
+        if constexpr (NEED_X) xv[k][j] = (xv[k][j] - mu) * rs;      // xhat
+        if constexpr (WANT_COL) db[k][j] += (double)d;
+        if constexpr (COL == 2) dg[k][j] += (double)(d * xv[k][j]);
+        if constexpr (WANT_DX) {
+          g[k][j] = d * gam[k][j];
+          s1 += g[k][j];
+          s2 += g[k][j] * xv[k][j];
         }
       }
+    }
+    if constexpr (WANT_DX) {
       const float c1 = group_allreduce<SumOp, 64>(s1) * a.inv_n;
       const float c2 = group_allreduce<SumOp, 64>(s2) * a.inv_n;
 #pragma unroll
@@ -209,58 +146,67 @@ void lnbwd_stitch_kernel(const LnBwdArgs a) {
   }
 
   if constexpr (WANT_COL) {
-    // ---- block composition: binary tree over the wavefronts' LDS arrays, in place -----------
+    // ---- block composition: every wavefront's sums into its own LDS array, then the arrays
+    // added in wavefront order by all threads, two slots each, straight into the partial row
     constexpr int n2 = 2 * SLOTS;
-    int P = 1;
-    while (P < waves) P <<= 1;
-    int wcur = waves;
-    for (int s = P >> 1; s >= 1; s >>= 1) {
-      __syncthreads();
-      if (wave < s && wave + s < wcur) {
-        const double* other = acc + (int64_t)s * n2;
+    double* mine = lds + (int64_t)wave * n2 + lane;
 #pragma unroll
-        for (int q = 0; q < 2 * K * 4; ++q) acc[q * 64] += other[q * 64];
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        mine[(k * 4 + j) * 64] = db[k][j];
+        mine[SLOTS + (k * 4 + j) * 64] = dg[k][j];
       }
-      wcur = min(wcur, s);
+    __syncthreads();
+    typedef double f64x2 __attribute__((ext_vector_type(2)));
+    double* out = a.part + (int64_t)blockIdx.x * n2;
+    for (int s = threadIdx.x * 2; s < n2; s += blockDim.x * 2) {
+      f64x2 t = *reinterpret_cast<const f64x2*>(lds + s);
+      for (int w = 1; w < waves; ++w) t += *reinterpret_cast<const f64x2*>(lds + (int64_t)w * n2 + s);
+      *reinterpret_cast<f64x2*>(out + s) = t;
     }
-    __syncthreads();
-    double* mine = a.part0 + (int64_t)blockIdx.x * n2;
-    for (int c = threadIdx.x; c < n2; c += blockDim.x) coherent_store(mine + c, lds[c]);
+  }
+}
 
-    // ---- first-level ticket: the last workgroup of a group sums the group's partials --
-    const int grp = blockIdx.x / a.group;
-    const int first = grp * a.group;
-    const int pop = min(a.group, (int)gridDim.x - first);
-    wait_for_own_stores();
-    __syncthreads();
-    if (threadIdx.x == 0) s_ticket = atomicAdd(&a.tickets[1 + grp], 1u);
-    __syncthreads();
-    if (s_ticket != (unsigned)(pop - 1)) return;
-    if (threadIdx.x == 0) __hip_atomic_store(&a.tickets[1 + grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    double* gsum = a.part1 + (int64_t)grp * n2;
-    sum_partials(a.part0 + (int64_t)first * n2, pop, n2, [&](int c, double v) { coherent_store(gsum + c, v); });
-    // ---- second-level ticket: the last group sums the group sums and writes the outputs
-    wait_for_own_stores();
-    __syncthreads();
-    if (threadIdx.x == 0) s_ticket = atomicAdd(&a.tickets[0], 1u);
-    __syncthreads();
-    if (s_ticket != (unsigned)(a.n_groups - 1)) return;
-    if (threadIdx.x == 0) __hip_atomic_store(&a.tickets[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sum_partials(a.part1, a.n_groups, n2, [&](int c, double v) {
-      // slot -> column
-      const int r = c % SLOTS, kj = r >> 6, vi = (kj >> 2) * 64 + (r & 63);
-      const int col = vi * 4 + (kj & 3);
-      if (vi < a.nvec) {
-        if (c < SLOTS) { if (a.dgamma) a.dgamma[col] = (float)v; }
-        else if (a.dbeta) a.dbeta[col] = (float)v;
-      }
-    });
+// Second kernel of the plan: out[col(slot)] = sum over the workgroups' partial rows, in a fixed order
+// (32 interleaved slices of partial rows, then the slices in order).  A block owns 8 consecutive slots.
+__global__ __launch_bounds__(256)
+void lnbwd_combine_kernel(const double* __restrict__ part, int groups, int K, int nvec, float* dgamma, float* dbeta) {
+  __shared__ double stage[32][9];
+  const int n2 = 2 * K * 256;
+  const int j = threadIdx.x & 7, slice = threadIdx.x >> 3;
+  const int s = blockIdx.x * 8 + j;
+  const double* p = part + s;
+  double acc = 0.0;
+  int g = slice;
+  // eight partial rows requested at a time (the loads are independent, the additions keep their order)
+  for (; g + 7 * 32 < groups; g += 8 * 32) {
+    double v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = p[(int64_t)(g + i * 32) * n2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += v[i];
+  }
+  for (; g < groups; g += 32) acc += p[(int64_t)g * n2];
+  stage[slice][j] = acc;
+  __syncthreads();
+  if (slice == 0) {
+    double t = stage[0][j];
+#pragma unroll
+    for (int k = 1; k < 32; ++k) t += stage[k][j];
+    // slot -> column
+    const int slots = K * 256;
+    const int r = s >= slots ? 1 : 0, q = (s - r * slots) >> 6, vi = (q >> 2) * 64 + (s & 63);
+    const int col = vi * 4 + (q & 3);
+    float* o = r ? dgamma : dbeta;
+    if (vi < nvec && o) o[col] = (float)t;
   }
 }
 
 namespace {
 
 constexpr int kKs[] = {1, 2, 3, 4};
+constexpr int kPrefetch = 2;
 
 // more than 64 KB of dynamic LDS has to be enabled once per kernel
 template <typename Kern>
@@ -280,60 +226,56 @@ hipError_t launch_with_lds(Kern kern, const LnBwdArgs& a, int grid, int wg, size
   return hipGetLastError();
 }
 
-template <int K, bool EXACT>
-hipError_t launch_KE(const LnBwdArgs& a, bool want_dx, bool want_col, int grid, int wg, size_t lds,
-                     hipStream_t s) {
+template <int K, bool EXACT, int MAXWG>
+hipError_t launch_KEW(const LnBwdArgs& a, bool want_dx, bool want_col, int grid, int wg, size_t lds,
+                      hipStream_t s) {
   const bool need_x_cols = a.dgamma != nullptr;
   if (want_dx && want_col)   // with dx the row is loaded anyway: always the full column path
-    return launch_with_lds(lnbwd_stitch_kernel<K, true, 2, EXACT>, a, grid, wg, lds, s);
-  if (want_dx) return launch_with_lds(lnbwd_stitch_kernel<K, true, 0, EXACT>, a, grid, wg, 0, s);
-  if (need_x_cols) return launch_with_lds(lnbwd_stitch_kernel<K, false, 2, EXACT>, a, grid, wg, lds, s);
-  return launch_with_lds(lnbwd_stitch_kernel<K, false, 1, EXACT>, a, grid, wg, lds, s);
+    return launch_with_lds(lnbwd_rows_kernel<K, true, 2, EXACT, kPrefetch, MAXWG>, a, grid, wg, lds, s);
+  if (want_dx) return launch_with_lds(lnbwd_rows_kernel<K, true, 0, EXACT, kPrefetch, MAXWG>, a, grid, wg, 0, s);
+  if (need_x_cols) return launch_with_lds(lnbwd_rows_kernel<K, false, 2, EXACT, kPrefetch, MAXWG>, a, grid, wg, lds, s);
+  return launch_with_lds(lnbwd_rows_kernel<K, false, 1, EXACT, kPrefetch, MAXWG>, a, grid, wg, lds, s);
 }
 
 template <int K>
 hipError_t launch_K(const LnBwdArgs& a, bool want_dx, bool want_col, int grid, int wg, size_t lds,
                     hipStream_t s) {
-  if (a.nvec == K * 64) return launch_KE<K, true>(a, want_dx, want_col, grid, wg, lds, s);
-  return launch_KE<K, false>(a, want_dx, want_col, grid, wg, lds, s);
+  const bool exact = a.nvec == K * 64;
+  if (wg <= 256) return exact ? launch_KEW<K, true, 256>(a, want_dx, want_col, grid, wg, lds, s)
+                              : launch_KEW<K, false, 256>(a, want_dx, want_col, grid, wg, lds, s);
+  return exact ? launch_KEW<K, true, 512>(a, want_dx, want_col, grid, wg, lds, s)
+               : launch_KEW<K, false, 512>(a, want_dx, want_col, grid, wg, lds, s);
 }
-
-int64_t align256(int64_t v) { return (v + 255) / 256 * 256; }
 
 }  // namespace
 
 bool lnbwd_stitch_plan(const LnBwdSpec& sp, const LaunchOpts& opt, LnBwdLaunch* out, std::string* err) {
   if (sp.cols % 4 != 0) { *err = "LayerNorm-backward schedule: cols must be a multiple of 4"; return false; }
-  // a lane holds its columns' fp64 accumulators: 4 vectors of 4 columns is what fits
+  // a lane holds its columns' fp64 running sums: 4 vectors of 4 columns is what fits
   if (sp.cols > 1024) { *err = "LayerNorm-backward schedule: cols > 1024 exceed one wavefront's register tile"; return false; }
   LnBwdLaunch l;
   const int need = (int)((sp.cols / 4 + 63) / 64);
   l.K = 4;
   for (int k : kKs) if (k >= need) { l.K = k; break; }
-  // 8 wavefronts per workgroup and one workgroup per CU: two wavefronts per SIMD is what
-  // the kernel's register budget allows (fp64 column accumulators plus a double-buffered
-  // row), and fewer, larger workgroups mean fewer partials
-  l.wg = opt.wg_size ? opt.wg_size : 512;
+  // 4 wavefronts per workgroup and one workgroup per CU: one wavefront per SIMD has the whole
+  // register file for its running sums and three row buffers; more wavefronts measured slower
+  l.wg = opt.wg_size ? opt.wg_size : 256;
   if (l.wg < 64 || l.wg > 512 || l.wg % 64) { *err = "LayerNorm-backward schedule: wg_size must be a multiple of 64 in [64,512]"; return false; }
   const int waves = l.wg / 64;
   int64_t grid = opt.grid > 0 ? opt.grid : 256;
   const int64_t max_useful = (sp.rows + waves - 1) / waves;
   if (grid > max_useful) grid = max_useful;
   if (grid < 1) grid = 1;
-  if (grid > 65536) grid = 65536;
+  if (grid > 4096) grid = 4096;
   l.grid = (int)grid;
-  // two-level tree with groups of about sqrt(grid) workgroups
-  int group = 1;
-  while (group * group < l.grid) ++group;
-  l.group = group;
   const bool want_col = sp.out_dgamma >= 0 || sp.out_dbeta >= 0;
-  const int n_groups = (l.grid + l.group - 1) / l.group;
+  l.n_kernels = want_col ? 2 : 1;
   l.lds_bytes = want_col ? (int64_t)waves * 2 * l.K * 256 * 8 : 0;
   if (l.lds_bytes > kLdsMax) {
-    *err = "LayerNorm-backward schedule: wg_size needs more LDS for the column accumulators than a CU has";
+    *err = "LayerNorm-backward schedule: wg_size needs more LDS for the column sums than a CU has";
     return false;
   }
-  l.workspace_bytes = want_col ? align256(4 * (1 + n_groups)) + (int64_t)16 * l.K * 256 * ((int64_t)l.grid + n_groups) : 0;
+  l.workspace_bytes = want_col ? (int64_t)16 * l.K * 256 * (int64_t)l.grid : 0;
   *out = l;
   return true;
 }
@@ -342,9 +284,9 @@ std::string lnbwd_stitch_describe(const LnBwdSpec& sp, const LnBwdLaunch& l) {
   char buf[512];
   snprintf(buf, sizeof buf,
            "reduce_s1[GRID-WARP,WARP]; reduce_s2[GRID-WARP,WARP]; dx[GRID-WARP,WARP-THREAD_%d]; "
-           "reduce_dgamma[GRID-CTA-THREAD,WARP-THREAD_%d]S; reduce_dbeta[GRID-CTA-THREAD,WARP-THREAD_%d]S; "
-           "cta_num=%d, cta_size=%d",
-           l.K * 4, l.K * 4, l.K * 4, l.grid, l.wg);
+           "reduce_dgamma[GRID-CTA-THREAD,WARP-THREAD_%d]S; reduce_dbeta[GRID-CTA-THREAD,WARP-THREAD_%d]S "
+           "(hand-written kernel; %d partial rows, then a combine kernel); cta_num=%d, cta_size=%d",
+           l.K * 4, l.K * 4, l.K * 4, l.grid, l.grid, l.wg);
   (void)sp;
   return buf;
 }
@@ -352,14 +294,6 @@ std::string lnbwd_stitch_describe(const LnBwdSpec& sp, const LnBwdLaunch& l) {
 int lnbwd_stitch_launch(const LnBwdSpec& sp, const LnBwdLaunch& l, const void* const* in, void* const* out,
                         void* workspace, void* stream, std::string* err) {
   if (sp.cols == 0) return 0;
-  if (sp.rows == 0) {
-    // sums over zero rows are zero: the combine kernel over zero partial rows writes them
-    void* col_out[2];
-    int dtype[2] = {DT_F32, DT_F32}, n = 0;
-    if (sp.out_dgamma >= 0) col_out[n++] = out[sp.out_dgamma];
-    if (sp.out_dbeta >= 0) col_out[n++] = out[sp.out_dbeta];
-    return col_combine_launch(nullptr, 0, sp.cols, n, col_out, dtype, stream, err);
-  }
   const bool want_dx = sp.out_dx >= 0;
   const bool want_col = sp.out_dgamma >= 0 || sp.out_dbeta >= 0;
   LnBwdArgs a{};
@@ -373,24 +307,28 @@ int lnbwd_stitch_launch(const LnBwdSpec& sp, const LnBwdLaunch& l, const void* c
   a.dbeta = sp.out_dbeta >= 0 ? static_cast<float*>(out[sp.out_dbeta]) : nullptr;
   a.rows = sp.rows; a.cols = (int)sp.cols; a.nvec = (int)(sp.cols / 4);
   a.inv_n = (float)(1.0 / (double)sp.cols);
-  a.group = l.group;
-  a.n_groups = (l.grid + l.group - 1) / l.group;
-  if (want_col) {
-    char* ws = static_cast<char*>(workspace);
-    a.tickets = reinterpret_cast<unsigned*>(ws);
-    a.part0 = reinterpret_cast<double*>(ws + align256(4 * (1 + a.n_groups)));
-    a.part1 = a.part0 + (int64_t)l.grid * 2 * l.K * 256;
-  }
+  a.part = static_cast<double*>(workspace);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e;
-  const size_t lds = (size_t)l.lds_bytes;
-  switch (l.K) {
-    case 1: e = launch_K<1>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
-    case 2: e = launch_K<2>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
-    case 3: e = launch_K<3>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
-    default: e = launch_K<4>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
+  int groups = 0;
+  if (sp.rows > 0) {
+    if (want_col && !workspace) { *err = "lnbwd_stitch launch: no workspace"; return -1; }
+    hipError_t e;
+    const size_t lds = (size_t)l.lds_bytes;
+    switch (l.K) {
+      case 1: e = launch_K<1>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
+      case 2: e = launch_K<2>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
+      case 3: e = launch_K<3>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
+      default: e = launch_K<4>(a, want_dx, want_col, l.grid, l.wg, lds, s); break;
+    }
+    if (e != hipSuccess) { *err = std::string("lnbwd_stitch launch: ") + hipGetErrorString(e); return -1; }
+    groups = l.grid;
   }
-  if (e != hipSuccess) { *err = std::string("lnbwd_stitch launch: ") + hipGetErrorString(e); return -1; }
+  if (want_col) {
+    // sums over zero rows are zero: the combine kernel over zero partial rows writes them
+    hipLaunchKernelGGL(lnbwd_combine_kernel, dim3(2 * l.K * 256 / 8), dim3(256), 0, s, a.part, groups, l.K, a.nvec, a.dgamma, a.dbeta);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { *err = std::string("lnbwd_combine launch: ") + hipGetErrorString(e); return -1; }
+  }
   return 0;
 }
 

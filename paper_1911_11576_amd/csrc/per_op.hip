@@ -442,6 +442,11 @@ std::string per_op_describe(const PerOpPlan& plan) {
   return buf;
 }
 
+__global__ __launch_bounds__(256) void zero_bytes_kernel(unsigned char* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 int per_op_launch(const Graph& g, const PerOpPlan& plan, const void* const* in, void* const* out, void* workspace,
                   void* stream, std::string* err) {
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -466,7 +471,12 @@ int per_op_launch(const Graph& g, const PerOpPlan& plan, const void* const* in, 
       const void* src = addr(st.a.base);
       void* dst = const_cast<void*>(addr(st.node));
       double* scratch = reinterpret_cast<double*>(ws + plan.scratch_offset);
-      if (st.red == 0) { e = hipMemsetAsync(dst, 0, (size_t)(x.numel() * (x.dtype == FS_F32 ? 4 : 2)), s); }
+      if (st.red == 0) {
+        // nothing to reduce: zeros, written by a kernel (a memset node recorded into a captured graph is avoided)
+        const int64_t nbytes = x.numel() * (x.dtype == FS_F32 ? 4 : 2);
+        hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)((nbytes + 255) / 256)), dim3(256), 0, s, static_cast<unsigned char*>(dst), nbytes);
+        e = hipGetLastError();
+      }
       else {
         const int chunks = col_chunks(st);
         switch (x.dtype) {

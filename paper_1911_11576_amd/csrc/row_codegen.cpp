@@ -624,6 +624,18 @@ struct Gen {
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
+  // Row steps requested ahead in the persistent form.  With one wavefront per SIMD a step otherwise lasts
+  // as long as the latency of its loads; two steps ahead where the row buffers (three per streamed
+  // operand) and the double-precision running sums still fit the wavefront's registers.
+  int force_prefetch = 0;     // 1 or 2: the caller's choice
+  int prefetch_depth(int n_prefetched) const {
+    if (force_prefetch == 1 || force_prefetch == 2) return force_prefetch;
+    if (A.seg_rows > 0 || L > 64) return 1;
+    const int per_value = K * W;      // 32-bit registers one full fp32 value takes per lane
+    const int regs = 3 * n_prefetched * per_value + 2 * A.n_col * per_value + 3 * per_value;
+    return regs <= 224 ? 2 : 1;
+  }
+
   bool geometry(std::string* err) {
     W = chunk_elements(A, &fast);
     if (W == 0) { *err = "generated row schedule: an operand strided along the last dim"; return false; }
@@ -798,21 +810,32 @@ struct Gen {
       }
     }
     if (persistent) {
+      // `depth` row steps are requested ahead of the one being worked on: raw<q> holds the current
+      // step, raw<q>b the one after it (depth 2), nraw<q> the newest request
       std::string pro, nxt, adv;
       char buf[512];
+      int n_pref = 0;
+      for (size_t q = 0; q < A.views.size(); ++q) n_pref += prefetched[q] ? 1 : 0;
+      const int depth = prefetch_depth(n_pref);
       for (size_t q = 0; q < A.views.size(); ++q) if (prefetched[q]) {
         const RView& v = A.views[q];
         const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
         const char* rt = raw_type(v);
         bool dummy = false;
-        const std::string offp = row_offset(v, &dummy, "rowp"), offn = row_offset(v, &dummy, "rown");
+        const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
         snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
                  rt, q, q, rt, ty, q, offp.c_str());
         pro += buf;
+        if (depth == 2) {
+          snprintf(buf, sizeof buf, "  %s raw%zub[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zub[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   rt, q, q, rt, ty, q, offp2.c_str());
+          pro += buf;
+        }
         snprintf(buf, sizeof buf, "  %s nraw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) nraw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
                  rt, q, q, rt, ty, q, offn.c_str());
         nxt += buf;
-        snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = nraw%zu[k];\n", q, q);
+        if (depth == 2) snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) { raw%zu[k] = raw%zub[k]; raw%zub[k] = nraw%zu[k]; }\n", q, q, q, q);
+        else snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = nraw%zu[k];\n", q, q);
         adv += buf;
       }
       if (!pro.empty()) {
@@ -820,8 +843,13 @@ struct Gen {
         const std::string header = "  for (long long row0 = ";
         const size_t at = e.s.rfind(header);
         snprintf(buf, sizeof buf, "  long long rowp = first_row + rl;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
-        e.s.insert(at, std::string(buf) + pro);
-        e.line("  long long rown = row0 + row_step + rl;");
+        std::string head = buf;
+        if (depth == 2) {
+          snprintf(buf, sizeof buf, "  long long rowp2 = first_row + row_step + rl;\n  if (rowp2 >= %s) rowp2 = %s;\n", row_hi, row_last);
+          head += buf;
+        }
+        e.s.insert(at, head + pro);
+        e.line("  long long rown = row0 + %d * row_step + rl;", depth);
         e.line("  if (rown >= %s) rown = %s;          // past the end: any valid row (one that is cached by then)", row_hi, row_any);
         e.s += nxt;
         e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
@@ -1561,6 +1589,7 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     l.view_dense.push_back(dense ? 1 : 0);
   }
   gen.want_persistent = want_persistent;
+  if (const char* pf = getenv("FS_ROW_PREFETCH")) gen.force_prefetch = atoi(pf);   // measurement aid: 1 or 2 row steps requested ahead
   gen.wg = opt.wg_size && (opt.wg_size <= 256 || A.n_col > 0) ? opt.wg_size : 256;
   if (gen.wg & (gen.wg - 1)) gen.wg = gen.wg > 512 ? 512 : gen.wg > 256 ? 256 : 128;   // lanes per row divide the workgroup
   std::string gerr;
