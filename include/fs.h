@@ -181,6 +181,25 @@ fs_status fs_plan_create(const fs_op_desc* ops, int32_t n_ops,
 fs_status fs_launch(fs_plan* plan, const void* const* inputs, int32_t n_in,
                     void* const* outputs, int32_t n_out, void* hip_stream);
 
+/* fs_launch for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * fs_launch, but a plan that needs scratch memory (fs_plan_info: workspace_bytes > 0 -- the partial rows
+ * of column reductions, the intermediates of a per-op plan) gets it from an array of
+ * FS_STATIC_SCRATCH_BYTES that is part of the library's device code, one copy per GPU, held from the
+ * moment the library is loaded on that GPU until the process ends, instead of from a hipMalloc on the
+ * plan's first launch.  The call allocates nothing and frees nothing, on the host side of HIP or the device.
+ *   - FS_ERR_UNSUPPORTED if the plan needs more than FS_STATIC_SCRATCH_BYTES of scratch memory.
+ *   - FS_ERR_INVALID if the plan runs a generated kernel that has not been loaded onto the device yet
+ *     (loading allocates): launch the plan once with fs_launch before, or build it with
+ *     FS_MODE_STITCHED_PREBUILT, whose kernels are part of the library.
+ *   - Every call on one GPU uses that GPU's one array, whatever the plan or the stream: two calls whose
+ *     work overlaps in time on one GPU race on it.  Calls on one stream, or ordered by events, are safe.
+ *     Nothing in the array has to start at zero and nothing is kept there between calls.
+ *   - Other errors and all argument rules as for fs_launch. */
+#define FS_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+fs_status fs_launch_static(fs_plan* plan, const void* const* inputs, int32_t n_in,
+                           void* const* outputs, int32_t n_out, void* hip_stream);
+
 /* Kernel tuning (Algorithm 3's outer loop, Section 5.3: generate templates, evaluate each
  * kernel, keep the best; "optimize once, reuse").  Builds the stitched plan of the group
  * under every launch template the group's schedule offers (workgroup size, row groups in

@@ -68,6 +68,8 @@ def lib():
         L.fs_plan_create.restype = i32
         L.fs_launch.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), i32, vp]
         L.fs_launch.restype = i32
+        L.fs_launch_static.argtypes = [vp, C.POINTER(vp), i32, C.POINTER(vp), i32, vp]
+        L.fs_launch_static.restype = i32
         L.fs_destroy.argtypes = [vp]
         L.fs_destroy.restype = i32
         L.fs_last_error.argtypes = []
@@ -169,6 +171,14 @@ def fs_launch(plan, inputs, outputs, stream=None):
         import torch
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().fs_launch(plan, _pointers(inputs), len(inputs), _pointers(outputs), len(outputs), stream))
+
+
+def fs_launch_static(plan, inputs, outputs, stream=None):
+    """fs_launch without any allocation: the plan's scratch memory is the library's static device array."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().fs_launch_static(plan, _pointers(inputs), len(inputs), _pointers(outputs), len(outputs), stream))
 
 
 def fs_plan_tune(ops, inputs, outputs, stream=None, trials=20):
@@ -297,6 +307,9 @@ class Plan:
 
     def launch(self, inputs, outputs, stream=None):
         fs_launch(self._h, inputs, outputs, stream)
+
+    def launch_static(self, inputs, outputs, stream=None):
+        fs_launch_static(self._h, inputs, outputs, stream)
 
     def launch_bound(self, bound, stream):
         """Launch with pre-marshalled arguments (see BoundArgs) on an explicit stream handle."""
