@@ -17,7 +17,7 @@ OBJ = os.environ.get("FS_OBJ_DIR", os.path.join(HERE, "_build"))
 LIB = os.environ.get("FS_LIB_OUT", os.path.join(HERE, "libfusionstitch.so"))
 
 SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f32.hip", "row_stitch_f16.hip", "row_stitch_bf16.hip", "row_team.hip", "row_block.hip", "lnbwd_stitch.hip",
-           "attn_stitch.hip", "per_op.hip", "ew_stitch.hip", "ew_codegen.cpp", "row_codegen.cpp", "shared_plan.cpp", "fusion_plan.cpp", "util.hip", "launch_static.hip"]
+           "attn_stitch.hip", "attn_stitch_f16.hip", "attn_stitch_bf16.hip", "per_op.hip", "ew_stitch.hip", "ew_codegen.cpp", "row_codegen.cpp", "shared_plan.cpp", "fusion_plan.cpp", "util.hip", "launch_static.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -305,13 +305,14 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
           }
           break;
         case fs::MATCH_LNBWD:
-          // The generated kernel (row work and column sums packed, one partial row per workgroup,
-          // then the combine kernel) measured faster than the hand-written single kernel, whose
-          // in-kernel ticket tree costs a serial tail: 71 against 81 us on config 5.  It is the
-          // default where kernels may be generated; the hand-written one serves the prebuilt mode.
-          if (lo.codegen && fall_back_to_generated()) break;
+          // The hand-written kernel (rows requested two steps ahead, per-wavefront LDS arrays) measured
+          // faster than the generated one on config 5 (69.0 against 71.2 us): it is the default where it
+          // takes the shape (fp32, up to 1024 columns); the generated kernel serves the other shapes and
+          // FS_MODE_STITCHED_GENERATED.
+          if (want_generated && fall_back_to_generated()) break;
           if (!fs::lnbwd_stitch_plan(p->match.lnbwd, lo, &p->lnbwd, &err)) {
             const bool bad_opt = err.find("wg_size") != std::string::npos;
+            if (!bad_opt && fall_back_to_generated()) break;
             if (!bad_opt && !gen_err.empty()) err += "; " + gen_err;
             delete p;
             return set_error(bad_opt ? FS_ERR_INVALID : FS_ERR_UNSUPPORTED, err);
@@ -481,11 +482,13 @@ fs_status fs_plan_tune(const fs_op_desc* ops, int32_t n_ops, const void* const* 
     for (int wg : {128, 256, 512, 1024}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});
     cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});
   } else if (base->schedule == FS_SCHED_ROW_COL) {
-    // generated (two kernels) against hand-written (one kernel, where it matches the group)
-    for (int wg : {128, 256, 512})
+    // the hand-written kernel (where it matches the group) and the generated one, each under a few
+    // workgroup sizes and grids
+    for (int wg : {128, 192, 256, 512})
       for (int grid : {256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, grid});
-    for (int wg : {256, 384, 512})
-      for (int grid : {128, 256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED_PREBUILT, wg, 0, grid});
+    cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, 0, 0, 0});
+    for (int wg : {128, 256, 512})
+      for (int grid : {256, 512}) cands.push_back(fs_plan_options{FS_MODE_STITCHED_GENERATED, wg, 0, grid});
   } else if (base->schedule == FS_SCHED_ELEMENTWISE) {
     // the generated kernel under two workgroup sizes, and the interpreted form
     for (int wg : {128, 256}) cands.push_back(fs_plan_options{FS_MODE_STITCHED, wg, 0, 0});

@@ -37,7 +37,7 @@ int lnbwd_stitch_launch(const LnBwdSpec&, const LnBwdLaunch&, const void* const*
                         void* workspace, void* stream, std::string* err);
 
 // Batched dot -> softmax -> batched dot on MFMA.
-struct AttnLaunch { int wg = 256, grid = 1, tiles = 4; int64_t lds_bytes = 0; };
+struct AttnLaunch { int wg = 256, grid = 1, nq = 4, nk = 4; int64_t lds_bytes = 0; };   // nq, nk: 16-row tiles of queries (= wavefronts) and of keys
 bool attn_stitch_plan(const AttnSpec&, const LaunchOpts&, AttnLaunch*, int* status, std::string* err);
 std::string attn_stitch_describe(const AttnSpec&, const AttnLaunch&);
 int attn_stitch_launch(const AttnSpec&, const AttnLaunch&, const void* const* in, void* const* out,

@@ -441,49 +441,136 @@ bool try_layernorm_bwd(const Rec& r, Match* m) {
   return true;
 }
 
-// ---- batched dot -> softmax -> batched dot ----------------------------------------------------
+// ---- batched dot -> softmax -> batched dot, with the elementwise ops around them ---------------
+// softmax over the last axis with the nodes a second output may refer to: z, max(z), sum(exp(z - max))
+struct SoftmaxParts { int z = -1, zmax = -1, den = -1; };
+bool match_softmax_parts(const Rec& r, int p, SoftmaxParts* out) {
+  const Graph& g = r.g;
+  if (g[p].kind != FS_DIVIDE) return false;
+  const int e = g[p].operand[0];
+  const int den = r.row_bcast(g[p].operand[1]);
+  if (den < 0 || r.last_axis_reduce(den, FS_REDUCE_SUM) != e) return false;
+  if (g[e].kind != FS_EXP) return false;
+  int z = -1, zmax = -1;
+  if (!r.minus_row_bcast(g[e].operand[0], &z, &zmax)) return false;
+  if (r.last_axis_reduce(zmax, FS_REDUCE_MAX) != z) return false;
+  out->z = z; out->zmax = zmax; out->den = den;
+  return true;
+}
+
 bool try_attention(const Rec& r, Match* m) {
   const Graph& g = r.g;
-  if (g.outputs.size() != 1) return false;
-  const Node& out = g[g.outputs[0]];
-  if (out.rank != 3) return false;
-  const int o = r.strip_convert(out.operand[0]);
-  if (g[o].kind != FS_DOT || g[o].axis != 0) return false;
+  if (g.outputs.empty() || g.outputs.size() > 2) return false;
+  AttnSpec sp;
+  int o_out = -1, lse_out = -1;
+  for (int oi : g.outputs) {
+    if (g[oi].rank == 3 && o_out < 0) o_out = oi;
+    else if (g[oi].rank == 2 && lse_out < 0) lse_out = oi;
+    else return false;
+  }
+  if (o_out < 0) return false;
+  const Node& out = g[o_out];
+  // ---- epilogue: out = convert(dot * gate + res), gate and residual optional, parameters of o's shape and dtype
+  int top = r.strip_convert(out.operand[0]);
+  std::vector<Term> ot; double oc = 0;
+  r.sum_terms(top, +1, ot, oc);
+  if (oc != 0 || ot.empty() || ot.size() > 2) return false;
+  int core = -1, res = -1;
+  if (ot.size() == 1) {
+    if (ot[0].sign < 0) return false;
+    core = ot[0].node;
+  } else {
+    for (int k = 0; k < 2 && res < 0; ++k) {
+      const int pr = r.in_param(ot[k].node);
+      if (pr >= 0 && ot[k].sign > 0 && ot[1 - k].sign > 0) { res = pr; core = ot[1 - k].node; }
+    }
+    if (res < 0) return false;
+  }
+  std::vector<int> of; double ofc = 1;
+  r.prod_factors(core, of, ofc);
+  if (ofc != 1.0 || of.empty() || of.size() > 2) return false;
+  int o = -1, gate = -1;
+  for (int n : of) {
+    if (g[n].kind == FS_DOT && o < 0) o = n;
+    else if (r.in_param(n) >= 0 && gate < 0) gate = r.in_param(n);
+    else return false;
+  }
+  if (o < 0 || g[o].axis != 0) return false;
   const int v = g[o].operand[1];
   if (g[v].kind != FS_PARAMETER) return false;
   const int p = r.strip_convert(g[o].operand[0]);
-  int z = match_softmax_tail(r, p);
-  if (z < 0) return false;
-  AttnSpec sp;
-  // z = causal_mask(scale * dot) or scale * causal_mask(dot, -inf) or without a mask
+  SoftmaxParts sm;
+  if (!match_softmax_parts(r, p, &sm)) return false;
+  // ---- second output: max(z) + log(sum(exp(z - max(z)))), one value per score row
+  if (lse_out >= 0) {
+    std::vector<Term> lt; double lc = 0;
+    r.sum_terms(g[lse_out].operand[0], +1, lt, lc);
+    if (lc != 0 || lt.size() != 2 || lt[0].sign < 0 || lt[1].sign < 0) return false;
+    bool ok = false;
+    for (int k = 0; k < 2; ++k)
+      if (lt[k].node == sm.zmax && g[lt[1 - k].node].kind == FS_LOG && g[lt[1 - k].node].operand[0] == sm.den) ok = true;
+    if (!ok) return false;
+    if (g[lse_out].dtype != FS_F32) { m->why = "attention schedule: the log-sum-exp output must be f32"; return false; }
+  }
+  // ---- z: the first dot under, from the outside in, any of: a positive constant factor, one additive
+  // fp32 mask or bias (a parameter, possibly broadcast over the batch or the query rows), a causal mask.
+  // What sits outside the causal mask is applied to the fill value too, which only -inf survives unchanged.
   double scale = 1.0;
-  auto peel_scale = [&](int n) {
+  int mask = -1;           // the parameter
+  int64_t mask_sb = 0, mask_sq = 0;
+  bool outside = false;    // something was peeled that the causal fill would pass through
+  int n = sm.z;
+  const Node& zs = g[sm.z];
+  if (zs.rank != 3) return false;
+  const int64_t SQ = zs.shape[1], SK = zs.shape[2];
+  for (int guard = 0; guard < 8 && g[n].kind != FS_DOT; ++guard) {
+    const Node& x = g[n];
+    if (x.kind == FS_CAUSAL_MASK) {
+      if (sp.causal) return false;
+      sp.causal = true;
+      sp.fill = (float)x.attr;
+      if (outside && !(sp.fill == -INFINITY && scale > 0)) {
+        m->why = "attention schedule: a scale or mask applied after the causal mask needs fill=-inf and scale>0";
+        return false;
+      }
+      n = x.operand[0];
+      continue;
+    }
+    if (x.kind == FS_ADD) {
+      if (mask >= 0 || scale != 1.0) return false;      // one mask, and not inside the scale
+      int found = -1;
+      for (int k = 0; k < 2 && found < 0; ++k) {
+        const int t = x.operand[k];
+        int src = -1;
+        int64_t sb = 0, sq = 0;
+        if (g[t].kind == FS_PARAMETER && g[t].rank == 3) { src = t; sb = SQ * SK; sq = SK; }
+        else if (g[t].kind == FS_BROADCAST && g[g[t].operand[0]].kind == FS_PARAMETER) {
+          const Node& pm = g[g[t].operand[0]];
+          const int ax = g[t].axis;
+          // operand dim d sits at result dim ax + d; extent-1 dims are expanded
+          int64_t ext[3] = {1, 1, 1};
+          bool fits = ax >= 0 && ax + pm.rank <= 3;
+          for (int d = 0; fits && d < pm.rank; ++d) ext[ax + d] = pm.shape[d];
+          if (fits && ext[2] == SK && (ext[1] == SQ || ext[1] == 1) && (ext[0] == zs.shape[0] || ext[0] == 1)) {
+            src = g[t].operand[0];
+            sq = ext[1] == 1 ? 0 : SK;
+            sb = ext[0] == 1 ? 0 : ext[1] * SK;
+          }
+        }
+        if (src >= 0 && g[src].dtype == FS_F32) { found = k; mask = src; mask_sb = sb; mask_sq = sq; }
+      }
+      if (found < 0) return false;
+      outside = true;
+      n = x.operand[1 - found];
+      continue;
+    }
+    // a constant factor
     std::vector<int> f; double c = 1;
     r.prod_factors(n, f, c);
-    if (f.size() != 1) return -1;
+    if (f.size() != 1 || f[0] == n) return false;
     scale *= c;
-    return f[0];
-  };
-  int n = z;
-  bool scaled_outside = false;
-  if (g[n].kind != FS_CAUSAL_MASK && g[n].kind != FS_DOT) {
-    n = peel_scale(n);
-    scaled_outside = true;
-    if (n < 0) return false;
-  }
-  if (g[n].kind == FS_CAUSAL_MASK) {
-    sp.causal = true;
-    sp.fill = (float)g[n].attr;
-    n = g[n].operand[0];
-    if (scaled_outside && !(sp.fill == -INFINITY && scale > 0)) {
-      m->why = "attention schedule: a scale applied after the mask needs fill=-inf and scale>0";
-      return false;
-    }
-    if (g[n].kind != FS_DOT) {
-      if (scaled_outside) return false;
-      n = peel_scale(n);
-      if (n < 0) return false;
-    }
+    outside = true;
+    n = f[0];
   }
   if (g[n].kind != FS_DOT || g[n].axis != 1) return false;
   const int q = g[n].operand[0], k = g[n].operand[1];
@@ -492,15 +579,28 @@ bool try_attention(const Rec& r, Match* m) {
   if (dt == FS_F32) { m->why = "attention schedule: fp32 operands have no MFMA path here (use f16 or bf16)"; return false; }
   if (g[k].dtype != dt || g[v].dtype != dt || out.dtype != dt) { m->why = "attention schedule: q, k, v and o must share one 16-bit dtype"; return false; }
   if (g[g[o].operand[0]].dtype != dt) return false;
-  if (g[n].dtype != FS_F32) { m->why = "attention schedule: scores must accumulate in f32"; return false; }
-  sp.batch = g[q].shape[0]; sp.seq = g[q].shape[1]; sp.dim = g[q].shape[2];
-  if (g[k].shape[1] != sp.seq || g[v].shape[1] != sp.seq || g[v].shape[2] != sp.dim) {
-    m->why = "attention schedule: needs equal query/key lengths and equal q/v head dims";
+  if (g[n].dtype != FS_F32 || g[o].dtype != FS_F32) { m->why = "attention schedule: both dots must accumulate in f32"; return false; }
+  sp.batch = g[q].shape[0]; sp.sq = g[q].shape[1]; sp.dim = g[q].shape[2]; sp.sk = g[k].shape[1];
+  if (g[v].shape[1] != sp.sk || g[v].shape[2] != sp.dim) {
+    m->why = "attention schedule: needs equal key/value lengths and equal q/v head dims";
     return false;
+  }
+  for (int e : {gate, res}) {
+    if (e < 0) continue;
+    if (g[e].dtype != dt || g[e].rank != 3 || !g[e].same_shape(out)) {
+      m->why = "attention schedule: gate and residual must have the output's shape and dtype";
+      return false;
+    }
   }
   sp.dtype = dt;
   sp.scale = (float)scale;
   sp.in_q = g[q].ordinal; sp.in_k = g[k].ordinal; sp.in_v = g[v].ordinal;
+  sp.in_mask = mask >= 0 ? g[mask].ordinal : -1;
+  sp.mask_sb = mask_sb; sp.mask_sq = mask_sq;
+  sp.in_gate = gate >= 0 ? g[gate].ordinal : -1;
+  sp.in_res = res >= 0 ? g[res].ordinal : -1;
+  sp.out_o = out.ordinal;
+  sp.out_lse = lse_out >= 0 ? g[lse_out].ordinal : -1;
   m->kind = MATCH_ATTN;
   m->attn = sp;
   return true;

@@ -624,16 +624,15 @@ struct Gen {
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
-  // Row steps requested ahead in the persistent form.  With one wavefront per SIMD a step otherwise lasts
-  // as long as the latency of its loads; two steps ahead where the row buffers (three per streamed
-  // operand) and the double-precision running sums still fit the wavefront's registers.
+  // Row steps requested ahead in the persistent form: one.  Two (three row buffers per streamed
+  // operand) is what the hand-written LayerNorm-backward kernel uses, where it is worth 5%; in the
+  // generated kernels it measured 1% to 3% slower (config 5's group and the backward tail of a
+  // Transformer block), so it is only there to be measured (FS_ROW_PREFETCH=2).
   int force_prefetch = 0;     // 1 or 2: the caller's choice
   int prefetch_depth(int n_prefetched) const {
-    if (force_prefetch == 1 || force_prefetch == 2) return force_prefetch;
-    if (A.seg_rows > 0 || L > 64) return 1;
-    const int per_value = K * W;      // 32-bit registers one full fp32 value takes per lane
-    const int regs = 3 * n_prefetched * per_value + 2 * A.n_col * per_value + 3 * per_value;
-    return regs <= 224 ? 2 : 1;
+    (void)n_prefetched;
+    if (force_prefetch == 2 && A.seg_rows == 0 && L <= 64) return 2;
+    return 1;
   }
 
   bool geometry(std::string* err) {
@@ -800,13 +799,16 @@ struct Gen {
       return W == 8 ? "u32x4" : W == 4 ? "u32x2" : nullptr;
     };
     std::vector<char> prefetched(A.views.size(), 0);
+    std::vector<char> scalar_prefetched(A.views.size(), 0);    // per-row scalars (one value per row) requested ahead like the rows
     if (persistent) {
       for (size_t q = 0; q < A.views.size(); ++q) {
         const RView& v = A.views[q];
-        bool dense = true, needs_coords = false;
+        bool dense = true, needs_coords = false, varies = false;
         for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] == 0) dense = false;
+        for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] != 0) varies = true;
         (void)row_offset(v, &needs_coords);
         prefetched[q] = !splat[q] && dense && !needs_coords && raw_type(v) != nullptr;
+        scalar_prefetched[q] = splat[q] && varies && !needs_coords;
       }
     }
     if (persistent) {
@@ -817,6 +819,26 @@ struct Gen {
       int n_pref = 0;
       for (size_t q = 0; q < A.views.size(); ++q) n_pref += prefetched[q] ? 1 : 0;
       const int depth = prefetch_depth(n_pref);
+      // A per-row scalar loaded where it is used would make every iteration wait for all requests issued
+      // before it, the rows requested ahead included (loads complete in order): it is requested with them.
+      for (size_t q = 0; q < A.views.size(); ++q) if (scalar_prefetched[q]) {
+        const RView& v = A.views[q];
+        const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+        const char* cv = v.dtype == FS_F32 ? "" : v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
+        bool dummy = false;
+        const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
+        snprintf(buf, sizeof buf, "  float sraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp.c_str());
+        pro += buf;
+        if (depth == 2) {
+          snprintf(buf, sizeof buf, "  float sraw%zub = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp2.c_str());
+          pro += buf;
+        }
+        snprintf(buf, sizeof buf, "  const float nsraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offn.c_str());
+        nxt += buf;
+        if (depth == 2) snprintf(buf, sizeof buf, "  sraw%zu = sraw%zub; sraw%zub = nsraw%zu;\n", q, q, q, q);
+        else snprintf(buf, sizeof buf, "  sraw%zu = nsraw%zu;\n", q, q);
+        adv += buf;
+      }
       for (size_t q = 0; q < A.views.size(); ++q) if (prefetched[q]) {
         const RView& v = A.views[q];
         const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
@@ -874,6 +896,11 @@ struct Gen {
           e.s.insert(e.s.rfind("  for (long long row0 = "), text);
         }
       } hoist{e, invariant, text_from};
+      if (splat[q] && scalar_prefetched[q] && !advance.empty()) {
+        hoist.on = false;
+        e.line("  const float s%zu = sraw%zu;", q, q);
+        continue;
+      }
       if (splat[q]) {
         e.line("  float s%zu;", q);
         e.line("  { const %s* p = static_cast<const %s*>(a.in[%zu]) + (%s); s%zu = %s; }", ty, ty, q, roff[q].c_str(), q, one);

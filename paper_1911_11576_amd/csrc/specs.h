@@ -49,14 +49,19 @@ struct LnBwdSpec {
   int out_dx = -1, out_dgamma = -1, out_dbeta = -1;   // output ordinals, -1 = not produced
 };
 
-// ---- schedule 3: batched dot -> scale -> (causal mask) -> row softmax -> batched dot ----
+// ---- schedule 3: batched dot -> scale -> (+ mask) -> (causal mask) -> row softmax -> batched dot
+// -> (x gate) -> (+ residual); optional second output: the log-sum-exp of every score row ----------
 struct AttnSpec {
-  int64_t batch = 0, seq = 0, dim = 0;
-  int dtype = DT_F16;          // storage dtype of q, k, v and o
+  int64_t batch = 0, sq = 0, sk = 0, dim = 0;   // query length, key length, head dim
+  int dtype = DT_F16;          // storage dtype of q, k, v, gate, residual and o
   int in_q = -1, in_k = -1, in_v = -1;
   float scale = 1.f;
   bool causal = false;
   float fill = 0.f;            // value of masked scores (-inf allowed)
+  int in_mask = -1;            // fp32 parameter added to the scaled scores, -1 = none; element (b, i, j) at
+  int64_t mask_sb = 0, mask_sq = 0;   //   b * mask_sb + i * mask_sq + j  (0 strides: broadcast over batch / over query rows)
+  int in_gate = -1, in_res = -1;      // [batch, sq, dim] parameters of the epilogue O * gate + res, -1 = absent
+  int out_o = 0, out_lse = -1;        // output ordinals; lse [batch, sq] fp32
 };
 
 }  // namespace fs

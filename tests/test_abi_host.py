@@ -42,7 +42,7 @@ def test_configs_are_recognised(cfg):
     with Plan(ops) as p:
         info = p.info()
         assert info["schedule"] == want
-        # one stitched kernel; config 5's plan is the generated kernel plus its combine kernel
+        # one stitched kernel; config 5's plan is the row kernel plus its combine kernel
         assert info["n_kernels"] == (2 if cfg.name == "layernorm_bwd" else 1)
         assert "cta_num=" in p.describe() and "cta_size=" in p.describe()
     with Plan(ops, "prebuilt") as p:          # the hand-written kernels: one launch each, config 5's row kernel plus its combine kernel
@@ -63,7 +63,7 @@ def test_plan_info_sizes():
         assert info["lds_bytes"] == 4 * 2 * 1024 * 8
         assert info["workspace_bytes"] == 256 * 2 * 1024 * 8
         assert info["moved_bytes"] == info["algorithmic_bytes"] + 2 * info["workspace_bytes"]
-    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full)) as p:
+    with Plan(BY_NAME["layernorm_bwd"].graph_fn(**BY_NAME["layernorm_bwd"].full), "generated") as p:
         info = p.info()
         # generated: (dgamma, dbeta) x 1024 fp64 sums in LDS, 256 partial rows of them in the workspace
         assert info["lds_bytes"] == 2 * 1024 * 8 and info["workspace_bytes"] == 256 * 2 * 1024 * 8
@@ -553,3 +553,40 @@ def test_plans_are_created_concurrently_from_several_threads():
     for t in threads:
         t.join()
     assert not problems, problems
+
+
+# ---------------------------------------------------------------- schedule 3 with prologue and epilogue
+
+def test_attention_block_forms_are_recognised():
+    cases = [dict(), dict(causal=True), dict(mask="key"), dict(mask="full", causal=True), dict(mask="shared"),
+             dict(mask="key", causal=True, mask_outside_causal=True), dict(gate=True), dict(residual=True),
+             dict(gate=True, residual=True, lse=True), dict(lse=True, mask="key", causal=True)]
+    for kw in cases:
+        for sq, sk in ((64, 64), (40, 72), (100, 24)):
+            with Plan(graphs.attention_block(3, sq, sk, 64, "f16", **kw)) as p:
+                info, text = p.info(), p.describe()
+                assert info["schedule"] == "bdot_softmax" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0, (kw, sq, sk)
+                assert ("add_mask" in text) == ("mask" in kw) and ("logsumexp" in text) == bool(kw.get("lse"))
+                assert ("multiply_gate" in text) == bool(kw.get("gate")) and ("add_residual" in text) == bool(kw.get("residual"))
+                # one wavefront per 16 query rows; V^T of the (padded) key tiles in LDS
+                nq = 1 if sq <= 16 else 2 if sq <= 32 else 4 if sq <= 64 else 8
+                nk = 2 if sk <= 32 else 4 if sk <= 64 else 8
+                assert f"cta_size={64 * nq}" in text and info["lds_bytes"] == 2 * 64 * (nk * 16 + 8)
+
+
+def test_attention_block_forms_that_are_refused():
+    # a finite causal fill under a mask that is added afterwards: the fill value would be shifted
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 32, 32, 64, causal=True, fill=-1e4, mask="key", mask_outside_causal=True))
+    # lengths beyond the fine-grained schedule
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 32, 200, 64))
+    _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 200, 32, 64))
+    # a mask inside the scale: scale * (dot + mask)
+    g = Graph()
+    q = g.parameter("q", "f16", (2, 32, 64)); k = g.parameter("k", "f16", (2, 32, 64)); v = g.parameter("v", "f16", (2, 32, 64))
+    m = g.parameter("m", "f32", (2, 32, 32))
+    z = g.multiply(g.add(g.dot(q, k, transpose_b=True, dtype="f32"), m), g.constant(0.125))
+    zmax = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
+    p = g.convert(g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), e)), "f16")
+    g.output(g.convert(g.dot(p, v, dtype="f32"), "f16"))
+    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)

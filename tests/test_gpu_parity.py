@@ -216,9 +216,9 @@ def test_row_schedule_launch_options_do_not_change_results(opts):
 
 # ---------------------------------------------------------------- LayerNorm backward
 
-# both forms of the group: the generated kernel + combine kernel (default) and the hand-written
-# single kernel (mode "prebuilt")
-LNBWD_MODES = ["stitched", "prebuilt"]
+# both forms of the group: the hand-written row kernel + combine kernel (default) and the generated
+# row kernel + combine kernel (mode "generated")
+LNBWD_MODES = ["stitched", "generated"]
 
 
 @pytest.mark.parametrize("mode", LNBWD_MODES)
@@ -299,6 +299,44 @@ def test_attention_mask_variants(causal, fill):
     B, S, d = 3, 40, 64
     ops = _attention_variant(B, S, d, causal, fill)
     check_against_oracle(ops, inputs.causal_attention(B, S, d), what=f"attn causal={causal} fill={fill}")
+
+
+# ---- schedule 3 with the elementwise ops around the two dots (Section 3.1's pattern shape): additive
+# masks, an epilogue on O, a second output, unequal query and key lengths
+
+ATTN_BLOCK_CASES = [
+    # (batch, sq, sk, dim, dtype, kwargs)
+    (3, 40, 72, 64, "f16", dict()),                                            # more keys than queries
+    (2, 100, 24, 32, "bf16", dict()),                                          # more queries than keys
+    (2, 16, 128, 128, "f16", dict(causal=True)),                               # one query tile, eight key tiles
+    (3, 64, 64, 64, "f16", dict(mask="key")),                                  # key padding, vector mask loads
+    (3, 50, 37, 64, "bf16", dict(mask="key")),                                 # ... ragged: scalar mask loads
+    (2, 48, 64, 32, "f16", dict(mask="full")),
+    (2, 33, 45, 64, "f16", dict(mask="full", causal=True)),
+    (4, 64, 64, 64, "bf16", dict(mask="shared")),                              # one bias for the whole batch
+    (2, 40, 40, 64, "f16", dict(mask="key", causal=True, mask_outside_causal=True)),
+    (3, 64, 64, 64, "f16", dict(gate=True)),
+    (3, 40, 72, 64, "bf16", dict(residual=True)),
+    (2, 70, 50, 128, "f16", dict(gate=True, residual=True)),
+    (3, 64, 64, 64, "f16", dict(lse=True, causal=True)),
+    (2, 35, 90, 32, "bf16", dict(lse=True, mask="key")),
+    (5, 64, 64, 64, "f16", dict(causal=True, mask="key", gate=True, residual=True, lse=True)),   # everything at once
+    (2, 128, 128, 128, "bf16", dict(causal=True, mask="full", gate=True, residual=True, lse=True)),   # maximum sizes
+    (1, 1, 1, 32, "f16", dict(lse=True, gate=True)),                           # a single score
+]
+
+
+@pytest.mark.parametrize("case", ATTN_BLOCK_CASES, ids=lambda c: f"{c[0]}x{c[1]}x{c[2]}x{c[3]}-{c[4]}-" + "+".join(sorted(c[5])))
+def test_attention_with_prologue_and_epilogue(case):
+    B, sq, sk, d, dtype, kw = case
+    announce(f"attention block {case}")
+    ops = graphs.attention_block(B, sq, sk, d, dtype, **kw)
+    ins = inputs.attention_block(B, sq, sk, d, dtype, **kw)
+    with Plan(ops) as plan:
+        assert plan.info()["schedule"] == "bdot_softmax" and plan.info()["n_kernels"] == 1
+    got, want = check_against_oracle(ops, ins, what=f"attention block {case}")
+    if kw.get("lse"):
+        assert got[1].shape == (B, sq)
 
 
 # ---------------------------------------------------------------- full-size configs, bench launch shape

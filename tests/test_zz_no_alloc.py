@@ -28,7 +28,7 @@ def _both(ops, ins, mode):
     return f(ref), f(got)
 
 
-@pytest.mark.parametrize("mode", ["prebuilt", "stitched"])
+@pytest.mark.parametrize("mode", ["stitched", "generated"])
 def test_static_launch_matches_fs_launch_twice_second_smaller(mode):
     cfg = BY_NAME["layernorm_bwd"]
     for rows in (1500, 203):                               # the second call is the smaller one

@@ -224,6 +224,47 @@ def causal_attention(batch, seq, dim, dtype="f16", scale=None):
     return g.ops
 
 
+def attention_block(batch, sq, sk, dim, dtype="f16", scale=None, causal=False, fill=float("-inf"), mask=None,
+                    gate=False, residual=False, lse=False, mask_outside_causal=False):
+    """Schedule 3 with the elementwise ops the motivating pattern has around its two dots
+    (Section 3.1): O = (softmax_rows(causal(Q K^T * scale + mask)) V) * gate + residual, optionally with a
+    second output, the log-sum-exp of every score row.  mask: None, "key" ([batch, 1, sk], key padding),
+    "full" ([batch, sq, sk]) or "shared" ([sq, sk], one bias for every batch element), fp32."""
+    if scale is None:
+        scale = dim ** -0.5
+    g = Graph()
+    q = g.parameter("q", dtype, (batch, sq, dim))
+    k = g.parameter("k", dtype, (batch, sk, dim))
+    v = g.parameter("v", dtype, (batch, sk, dim))
+    z = g.multiply(g.dot(q, k, transpose_b=True, dtype="f32"), g.constant(scale))
+    m = None
+    if mask == "key":
+        m = g.broadcast(g.parameter("mask", "f32", (batch, 1, sk)), (batch, sq, sk), 0)
+    elif mask == "full":
+        m = g.parameter("mask", "f32", (batch, sq, sk))
+    elif mask == "shared":
+        m = g.broadcast(g.parameter("mask", "f32", (sq, sk)), (batch, sq, sk), 1)
+    if m is not None and not mask_outside_causal:
+        z = g.add(z, m)
+    if causal:
+        z = g.causal_mask(z, fill)
+    if m is not None and mask_outside_causal:
+        z = g.add(m, z)
+    zmax = g.reduce_max(z, -1)
+    e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
+    denom = g.reduce_sum(e, -1)
+    p = g.convert(g.divide(e, g.row_broadcast(denom, e)), dtype)
+    o = g.dot(p, v, transpose_b=False, dtype="f32")
+    if gate:
+        o = g.multiply(o, g.convert(g.parameter("gate", dtype, (batch, sq, dim)), "f32"))
+    if residual:
+        o = g.add(o, g.convert(g.parameter("residual", dtype, (batch, sq, dim)), "f32"))
+    g.output(g.convert(o, dtype), "o")
+    if lse:
+        g.output(g.add(g.log(denom), zmax), "lse")
+    return g.ops
+
+
 GELU_K0 = 0.7978845608028654   # sqrt(2/pi)
 GELU_K1 = 0.044715
 

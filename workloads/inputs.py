@@ -68,6 +68,25 @@ def causal_attention(batch=512, seq=64, dim=64, dtype="f16", seed_offset=3):
     return [round_to(r.normal(0.0, 1.0, (batch, seq, dim)), dtype) for _ in range(3)]
 
 
+def attention_block(batch, sq, sk, dim, dtype="f16", mask=None, gate=False, residual=False, seed_offset=15, **_):
+    """Inputs of graphs.attention_block in parameter order: q, k, v ~ N(0,1); an additive mask of 0 / -1e4
+    (padding with probability 0.1) for "key" and "full", a bias ~ N(0,1) for "shared"; gate ~ U(0,1),
+    residual ~ N(0,1)."""
+    r = _rng(seed_offset)
+    out = [round_to(r.normal(0.0, 1.0, (batch, n, dim)), dtype) for n in (sq, sk, sk)]
+    if mask == "key":
+        out.append(round_to(np.where(r.random((batch, 1, sk)) < 0.1, -1e4, 0.0), "f32"))
+    elif mask == "full":
+        out.append(round_to(np.where(r.random((batch, sq, sk)) < 0.1, -1e4, 0.0), "f32"))
+    elif mask == "shared":
+        out.append(round_to(r.normal(0.0, 1.0, (sq, sk)), "f32"))
+    if gate:
+        out.append(round_to(r.random((batch, sq, dim)), dtype))
+    if residual:
+        out.append(round_to(r.normal(0.0, 1.0, (batch, sq, dim)), dtype))
+    return out
+
+
 def bias_gelu_residual_layernorm(rows=16384, cols=1024, dtype="bf16", seed_offset=4):
     r = _rng(seed_offset)
     x = r.normal(0.0, 1.0, (rows, cols))
