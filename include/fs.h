@@ -135,11 +135,16 @@ typedef enum {
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA; the probabilities stay in
                                 registers (accumulators of the first dot = operands of the second), V goes
                                 through LDS */
-  FS_SCHED_ELEMENTWISE = 4   /* any all-elementwise group: thread composition + packing, as
+  FS_SCHED_ELEMENTWISE = 4,  /* any all-elementwise group: thread composition + packing, as
                                 a kernel generated for the group (or interpreted, see
                                 FS_MODE_STITCHED_PREBUILT).  The ops share one shape, or fall into
                                 up to 16 parts that share no computed value, each of one shape
                                 (generated form only): one kernel, a run of workgroups per part */
+  FS_SCHED_BLOCK_DOT = 5     /* generated block composition around batched dots on MFMA (Sections 5.1, 5.3):
+                                a[B,M,K] . b[B,N,K]^T (16-bit, K 16..128, tile up to 128 x 128) -> any
+                                elementwise ops and row reductions on the tile -> optionally a second dot
+                                with v[B,N,D], its operand handed over through LDS; what the hand-written
+                                FS_SCHED_BDOT_SOFTMAX kernel does not match */
 } fs_schedule;
 
 /* Build a plan from a fusion group.

@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("FS_LIB_PATH") or os.path.join(os.path.dirname(os.path
 FS_OK, FS_ERR_INVALID, FS_ERR_UNSUPPORTED, FS_ERR_LDS, FS_ERR_HIP, FS_ERR_NOMEM = range(6)
 STATUS_NAMES = ["FS_OK", "FS_ERR_INVALID", "FS_ERR_UNSUPPORTED", "FS_ERR_LDS", "FS_ERR_HIP", "FS_ERR_NOMEM"]
 FS_MODE_STITCHED, FS_MODE_PER_OP, FS_MODE_STITCHED_PREBUILT, FS_MODE_STITCHED_GENERATED = 0, 1, 2, 3
-SCHEDULE_NAMES = ["per_op", "row", "row_col", "bdot_softmax", "elementwise"]
+SCHEDULE_NAMES = ["per_op", "row", "row_col", "bdot_softmax", "elementwise", "block_dot"]
 
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 OPKINDS = {name: i for i, name in enumerate((

@@ -227,7 +227,7 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
       // the plan's fields once p->row_gen holds a generated row kernel
       auto adopt_generated_row_kernel = [&]() {
         p->match.kind = fs::MATCH_NONE;
-        p->schedule = p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
+        p->schedule = p->row_gen.mma ? FS_SCHED_BLOCK_DOT : p->row_gen.n_col > 0 ? FS_SCHED_ROW_COL : FS_SCHED_ROW;
         p->row_form = 3;
         p->lds_bytes = p->row_gen.lds_bytes;
         p->workspace_bytes = p->row_gen.workspace_bytes;
@@ -410,6 +410,7 @@ fs_status fs::enqueue_plan(fs_plan* p, const void* const* inputs, void* const* o
         rc = p->row_form == 3 ? fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, workspace, hip_stream, &err)
                               : fs::lnbwd_stitch_launch(p->match.lnbwd, p->lnbwd, inputs, outputs, workspace, hip_stream, &err);
         break;
+      case FS_SCHED_BLOCK_DOT: rc = fs::row_gen_launch(p->row_gen, inputs, outputs, n_out, workspace, hip_stream, &err); break;
       case FS_SCHED_BDOT_SOFTMAX: rc = fs::attn_stitch_launch(p->match.attn, p->attn, inputs, outputs, hip_stream, &err); break;
       case FS_SCHED_ELEMENTWISE: rc = fs::ew_stitch_launch(p->ew, inputs, outputs, n_out, hip_stream, &err); break;
       default: rc = fs::per_op_launch(p->graph, p->per_op, inputs, outputs, workspace, hip_stream, &err); break;

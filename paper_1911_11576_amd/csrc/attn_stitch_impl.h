@@ -81,8 +81,10 @@ template <int CH> __device__ __forceinline__ uint32_t pair_exchange(uint32_t x) 
   }
 }
 
-// NQ: 16-row tiles of queries (workgroup = NQ wavefronts); NK: 16-key tiles; D: head dim
-template <typename T, int NQ, int NK, int D>
+// NQ: 16-row tiles of queries (workgroup = NQ wavefronts); NK: 16-key tiles; D: head dim;
+// X: the group has a mask, an epilogue operand or a second output (without any of them those paths
+// are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 4%)
+template <typename T, int NQ, int NK, int D, bool X>
 __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) {
   constexpr int KS = D / 32;                 // k-steps of the first dot
   constexpr int NKP = NK < 2 ? 2 : NK;       // key tiles padded to whole 32-key steps
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       const int key = min(ci / CH, sk - 1), d0 = (ci % CH) * 8;
       vreg[i] = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * D + d0);
     }
-    if (a.mask) {
+    if (X && a.mask) {
       const float* mrow = a.mask + (int64_t)b * a.mask_sb + (int64_t)qrow * a.mask_sq;
 #pragma unroll
       for (int kt = 0; kt < NK; ++kt) {
@@ -151,12 +153,12 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
         }
       }
     }
-    if (a.gate) {
+    if (X && a.gate) {
       const uint16_t* p = static_cast<const uint16_t*>(a.gate) + ((int64_t)b * sq + qrow) * D + 4 * g;
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) gt[dt] = *reinterpret_cast<const u32x2*>(p + dt * 16);
     }
-    if (a.res) {
+    if (X && a.res) {
       const uint16_t* p = static_cast<const uint16_t*>(a.res) + ((int64_t)b * sq + qrow) * D + 4 * g;
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) rs[dt] = *reinterpret_cast<const u32x2*>(p + dt * 16);
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       for (int i = 0; i < 4; ++i) {
         const int key = kt * 16 + 4 * g + i;
         float z = acc[kt][i] * a.scale;
-        if (a.mask) z += mk[kt][i];
+        if (X && a.mask) z += mk[kt][i];
         if (a.causal && key > qi) z = a.fill;
         if (key >= sk || kt >= tiles) z = -INFINITY;
         acc[kt][i] = z;
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       }
     sum = rows_allreduce<SumOp>(sum);
     const float inv = 1.f / sum;
-    if (a.lse && g == 0 && qi < sq) a.lse[(int64_t)b * sq + qi] = mx + logf(sum);
+    if (X && a.lse && g == 0 && qi < sq) a.lse[(int64_t)b * sq + qi] = mx + logf(sum);
     // P rounded to the dot's dtype, packed in k-slot order: slots 4h+i of step kk <- tile 2kk+h
 #pragma unroll
     for (int kk = 0; kk < NKP / 2; ++kk)
@@ -264,14 +266,14 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       }
     }
     // ---- epilogue on the accumulators: the lane holds O[q0+c][16dt+4g+i], i < 4 -----------------
-    if (a.gate) {
+    if (X && a.gate) {
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
         o[dt][0] *= Mfma<T>::lo(gt[dt][0]); o[dt][1] *= Mfma<T>::hi(gt[dt][0]);
         o[dt][2] *= Mfma<T>::lo(gt[dt][1]); o[dt][3] *= Mfma<T>::hi(gt[dt][1]);
       }
     }
-    if (a.res) {
+    if (X && a.res) {
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) {
         o[dt][0] += Mfma<T>::lo(rs[dt][0]); o[dt][1] += Mfma<T>::hi(rs[dt][0]);
@@ -302,8 +304,9 @@ inline int64_t attn_lds_bytes(int NK, int D) {
 
 template <typename T, int NQ, int NK, int D>
 hipError_t attn_launch_one(const AttnArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D>), dim3(a.batch), dim3(64 * NQ),
-                     (size_t)attn_lds_bytes(NK, D), s, a);
+  const bool extras = a.mask || a.gate || a.res || a.lse;
+  if (extras) hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, true>), dim3(a.batch), dim3(64 * NQ), (size_t)attn_lds_bytes(NK, D), s, a);
+  else hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, false>), dim3(a.batch), dim3(64 * NQ), (size_t)attn_lds_bytes(NK, D), s, a);
   return hipGetLastError();
 }
 

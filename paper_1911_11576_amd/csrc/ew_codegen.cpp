@@ -368,17 +368,31 @@ std::string cache_path(const std::string& dir, const std::string& identity) {
   return dir + name;
 }
 
-struct DiskHeader { char magic[8]; uint64_t check; uint64_t identity_bytes; uint64_t code_bytes; };
+// File layout: header, the identity text (source, options, compiler version), the code object.  A file is
+// used only if the header is well formed, the identity text is the expected one byte for byte, and the code
+// bytes match their checksum; anything else (a truncated or damaged file, a file written by another version,
+// a hash collision on the name) is ignored and replaced by a fresh compile.
+struct DiskHeader { char magic[8]; uint64_t identity_check; uint64_t identity_bytes; uint64_t code_bytes; uint64_t code_check; };
+
+uint64_t fnv_bytes(const std::vector<char>& v, uint64_t h) {
+  for (char c : v) { h ^= (unsigned char)c; h *= 1099511628211ull; }
+  return h;
+}
 
 bool disk_load(const std::string& path, const std::string& identity, std::vector<char>* code) {
   FILE* f = fopen(path.c_str(), "rb");
   if (!f) return false;
   DiskHeader h{};
-  bool ok = fread(&h, sizeof h, 1, f) == 1 && memcmp(h.magic, "FSCODE1", 8) == 0 && h.identity_bytes == identity.size() &&
-            h.check == fnv(identity, 0x9e3779b97f4a7c15ull) && h.code_bytes > 0 && h.code_bytes < (64u << 20);
+  bool ok = fread(&h, sizeof h, 1, f) == 1 && memcmp(h.magic, "FSCODE2", 8) == 0 && h.identity_bytes == identity.size() &&
+            h.identity_check == fnv(identity, 0x9e3779b97f4a7c15ull) && h.code_bytes > 0 && h.code_bytes < (64u << 20);
+  if (ok) {
+    std::string stored(h.identity_bytes, '\0');
+    ok = fread(&stored[0], 1, stored.size(), f) == stored.size() && stored == identity;
+  }
   if (ok) {
     code->resize(h.code_bytes);
-    ok = fread(code->data(), 1, h.code_bytes, f) == h.code_bytes && fgetc(f) == EOF;
+    ok = fread(code->data(), 1, h.code_bytes, f) == h.code_bytes && fgetc(f) == EOF &&
+         fnv_bytes(*code, 0x9e3779b97f4a7c15ull) == h.code_check;
   }
   fclose(f);
   if (!ok) code->clear();
@@ -392,11 +406,13 @@ void disk_store(const std::string& path, const std::string& identity, const std:
   FILE* f = fopen(part.c_str(), "wb");
   if (!f) return;                               // an unwritable directory costs the next process a compile, nothing else
   DiskHeader h{};
-  memcpy(h.magic, "FSCODE1", 8);
-  h.check = fnv(identity, 0x9e3779b97f4a7c15ull);
+  memcpy(h.magic, "FSCODE2", 8);
+  h.identity_check = fnv(identity, 0x9e3779b97f4a7c15ull);
   h.identity_bytes = identity.size();
   h.code_bytes = code.size();
-  const bool ok = fwrite(&h, sizeof h, 1, f) == 1 && fwrite(code.data(), 1, code.size(), f) == code.size();
+  h.code_check = fnv_bytes(code, 0x9e3779b97f4a7c15ull);
+  const bool ok = fwrite(&h, sizeof h, 1, f) == 1 && fwrite(identity.data(), 1, identity.size(), f) == identity.size() &&
+                  fwrite(code.data(), 1, code.size(), f) == code.size();
   if (fclose(f) != 0 || !ok || rename(part.c_str(), path.c_str()) != 0) (void)remove(part.c_str());
 }
 }  // namespace

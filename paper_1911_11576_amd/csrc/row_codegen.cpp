@@ -39,14 +39,16 @@ const char* ew_preamble();   // ew_codegen.cpp: typedefs, Args, dtype conversion
 
 namespace {
 
-enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2, CLS_COL = 3 };   // COL: one value per column (reduced over the rows)
+enum Cls : int { CLS_NONE = 0, CLS_FULL = 1, CLS_ROW = 2, CLS_COL = 3, CLS_DOT_OUT = 4 };   // COL: one value per column (reduced over the rows); DOT_OUT: [B, M, D] result of a consuming dot on the matrix unit
 enum OpndKind : int { OP_NODE = 0, OP_ROWB = 1, OP_VIEW = 2, OP_CONST = 3 };
 
 struct Opnd { int kind = OP_NODE; int index = -1; float cval = 0.f; };
 // beside the fs_opkind / EwExtraOp values: a batched dot with a tiny contraction that produces
 // the full tile (sum over k of a per-row scalar times a per-column vector), and a batched dot
 // that contracts the full last dim into one value per row
-enum RowExtraOp : int { ROP_DOT_OUTER = 200, ROP_DOT_REDUCE = 201 };
+// ... and the two dots of the block-composed template on the matrix unit: a producing dot
+// a[B,M,K] . b[B,N,K]^T -> the group's full tile, and a consuming dot p[B,M,N] . v[B,N,D] -> [B,M,D]
+enum RowExtraOp : int { ROP_DOT_OUTER = 200, ROP_DOT_REDUCE = 201, ROP_DOT_MMA_IN = 202, ROP_DOT_MMA_OUT = 203 };
 
 struct RNode {
   int id = -1, op = 0, cls = CLS_NONE, nop = 1;
@@ -76,6 +78,11 @@ struct Analysis {
   int64_t seg_rows = 0;          // 0: the column reductions run over all rows; else over each run of this many
                                  // consecutive rows (the innermost row dims: [B, S, H] summed over S -> [B, H])
   bool has_causal = false;       // a causal_mask op: the row's index in the second-to-last dim is needed
+  // block composition around dots on the matrix unit (16-bit operands, contraction 16..128)
+  int mma_in = -1, mma_out = -1;         // node ids of the producing and the consuming dot, -1 = none
+  int mma_dtype = FS_F16;                // dtype of the dots' operands
+  int64_t mma_k = 0, mma_d = 0;          // contraction length of the producing dot, result width of the consuming one
+  int mma_va = -1, mma_vb = -1, mma_vv = -1;   // views (pointer only) of a, b and v
 
   explicit Analysis(const Graph& gr) : g(gr) {}
   bool fail(const std::string& m) { err = m; return false; }
@@ -221,6 +228,41 @@ struct Analysis {
     if (!dense_param(ib, &pb)) return fail("generated row schedule: second dot operand must be a group input");
     if (a.rank != 3 || b.rank != 3 || b.shape[0] != S[0] || (bt ? b.shape[2] : b.shape[1]) != Kc)
       return fail("generated row schedule: dot operand shapes do not fit the group");
+    const int64_t none[FS_MAX_RANK] = {0, 0, 0, 0};
+    if (is_compute(ia) && cls[ia] == CLS_FULL && x.shape[2] != 1) {
+      // consuming dot on the matrix unit: p[B,M,N] . v[B,N,D] -> [B,M,D], p a 16-bit full value of the group
+      if (mma_out >= 0) return fail("generated row schedule: more than one consuming dot");
+      if (bt) return fail("generated row schedule: the second operand of a consuming dot must be stored [B, N, D]");
+      if (Kc != S[2] || x.shape[0] != S[0] || x.shape[1] != S[1]) return fail("generated row schedule: consuming dot shape differs from the group's");
+      if (a.dtype == FS_F32 || b.dtype != a.dtype) return fail("generated row schedule: a consuming dot needs 16-bit operands of one dtype");
+      if (Nout != 32 && Nout != 64 && Nout != 128) return fail("generated row schedule: consuming dot result width must be 32, 64 or 128");
+      if (x.dtype != FS_F32) return fail("generated row schedule: dots accumulate in f32");
+      if (mma_in >= 0 && mma_dtype != a.dtype) return fail("generated row schedule: the two dots use different operand dtypes");
+      r->op = ROP_DOT_MMA_OUT; r->cls = CLS_DOT_OUT; r->nop = 1;
+      cls[i] = CLS_DOT_OUT;
+      if (!operand(x.operand[0], CLS_FULL, &r->o[0])) return false;
+      mma_out = i; mma_dtype = a.dtype; mma_d = Nout;
+      mma_vv = view_index(pb, none, CLS_NONE);
+      return true;
+    }
+    if (shape_is_full(x) && !(is_compute(ia) && cls[ia] == CLS_FULL) && Kc >= 16) {
+      // producing dot on the matrix unit: a[B,M,K] . b[B,N,K]^T -> the full tile
+      int pa = -1;
+      if (!dense_param(ia, &pa)) return fail("generated row schedule: first operand of a producing dot must be a group input");
+      if (mma_in >= 0) return fail("generated row schedule: more than one producing dot with a real contraction");
+      if (a.dtype == FS_F32 || b.dtype != a.dtype) return fail("generated row schedule: a dot with contraction >= 16 needs 16-bit operands of one dtype (the matrix unit)");
+      if (!bt) return fail("generated row schedule: the second operand of a producing dot must be stored [B, N, K] (contraction along the last dim)");
+      if (Kc % 8 != 0 || Kc > 128) return fail("generated row schedule: producing dot contraction must be a multiple of 8 up to 128");
+      if (a.shape[0] != S[0] || a.shape[1] != S[1] || Nout != S[2]) return fail("generated row schedule: dot shape differs from the group's");
+      if (x.dtype != FS_F32) return fail("generated row schedule: dots accumulate in f32");
+      if (mma_out >= 0 && mma_dtype != a.dtype) return fail("generated row schedule: the two dots use different operand dtypes");
+      r->op = ROP_DOT_MMA_IN; r->cls = CLS_FULL; r->nop = 0;
+      cls[i] = CLS_FULL;
+      mma_in = i; mma_dtype = a.dtype; mma_k = Kc;
+      mma_va = view_index(pa, none, CLS_NONE);
+      mma_vb = view_index(pb, none, CLS_NONE);
+      return true;
+    }
     if (shape_is_full(x) && !(is_compute(ia) && cls[ia] == CLS_FULL)) {
       // outer form
       int pa = -1;
@@ -258,7 +300,14 @@ struct Analysis {
     int first = -1;
     for (int i = 0; i < n && first < 0; ++i) if (is_reduce(g[i].kind)) first = i;
     int shape_of = first >= 0 ? g[first].operand[0] : -1;
-    if (first < 0) {
+    // a dot of two group inputs with a real contraction fixes the shape: its result is the tile the
+    // block-composed template is built around
+    for (int i = 0; i < n; ++i) {
+      if (g[i].kind != FS_DOT || g[i].rank != 3) continue;
+      const int ia = canon(g[i].operand[0]), ib = canon(g[i].operand[1]);
+      if (g[ia].kind == FS_PARAMETER && g[ib].kind == FS_PARAMETER && g[ia].rank == 3 && g[ia].shape[2] >= 16) { shape_of = i; break; }
+    }
+    if (shape_of < 0) {
       for (int i = 0; i < n; ++i) {
         const int k = g[i].kind;
         if (!(is_binary(k) || is_unary(k) || k == FS_CONVERT || k == FS_CAUSAL_MASK)) continue;
@@ -277,8 +326,17 @@ struct Analysis {
     cls.assign(n, CLS_NONE);
     colv.assign(n, 0);
     std::vector<int> out_ord(n, -1), out_dtype(n, 0);
+    std::vector<char> store_rounding(n, 0);    // a convert whose only job is the rounding of a consuming dot's result at its store
     for (int o : g.outputs) {
-      const int s = canon(g[o].operand[0]);
+      int s = canon(g[o].operand[0]);
+      if (g[s].kind == FS_CONVERT && g[canon(g[s].operand[0])].kind == FS_DOT && g[s].rank == 3 && rank == 3) {
+        const int d = canon(g[s].operand[0]);
+        const int da = canon(g[d].operand[0]);
+        int users = 0;
+        for (int i = 0; i < n; ++i) for (int j = 0; j < operand_count(g[i].kind); ++j) if (g[i].operand[j] == s) ++users;
+        // (the dot is a consuming one if its first operand is computed in the group and is not a widening alias of an input)
+        if (users == 1 && g[da].kind != FS_PARAMETER && g[d].shape[2] != 1) { store_rounding[s] = 1; s = d; }
+      }
       if (!is_compute(s)) return fail("generated row schedule: an output that is a plain copy of an input");
       if (out_ord[s] >= 0) return fail("generated row schedule: one value feeds two outputs");
       out_ord[s] = g[o].ordinal;
@@ -358,7 +416,7 @@ struct Analysis {
       const Node& x = g[i];
       const int k = x.kind;
       if (k == FS_PARAMETER || k == FS_CONSTANT || k == FS_BROADCAST || k == FS_OUTPUT) continue;
-      if (inside_idiom[i] || col_mid[i]) continue;
+      if (inside_idiom[i] || col_mid[i] || store_rounding[i]) continue;
       if (idiom_of[i] >= 0) {
         const GeluIdiom& id = idioms[idiom_of[i]];
         RNode r;
@@ -378,6 +436,7 @@ struct Analysis {
         if (!dot_node(i, &r)) return false;
         r.out_ord = out_ord[i];
         r.out_dtype = out_dtype[i];
+        if (r.op == ROP_DOT_MMA_OUT && r.out_ord < 0) return fail("generated row schedule: the result of a consuming dot must be a group output (no ops after it)");
         nodes.push_back(r);
         continue;
       }
@@ -432,6 +491,14 @@ struct Analysis {
       nodes.push_back(r);
     }
     if (views.size() > 24) return fail("generated row schedule: more than 24 distinct operand views");
+    if (mma_out >= 0 && mma_in < 0) return fail("generated row schedule: a consuming dot without a producing one (the block-composed template is built around the first dot's tile)");
+    if (mma_in >= 0) {
+      if (n_col > 0) return fail("generated row schedule: column reductions beside dots on the matrix unit");
+      if (S[1] > 128 || S[2] > 128) return fail("generated row schedule: dots on the matrix unit are fine-grained (tile up to 128 x 128)");
+      if (S[1] == 0 || S[2] == 0) return fail("generated row schedule: empty tile of a matrix-unit dot");
+      if (S[2] % 4 != 0) return fail("generated row schedule: the tile of a matrix-unit dot must be a multiple of 4 wide");
+      for (const RNode& r : nodes) if (r.op == ROP_DOT_OUTER || r.op == ROP_DOT_REDUCE) return fail("generated row schedule: register dots beside dots on the matrix unit");
+    }
     // a rounding read by nothing but the store of the same dtype is left to the store
     std::vector<char> read(n, 0);
     for (const RNode& r : nodes)
@@ -492,6 +559,39 @@ template <class Op, int L> static __device__ __forceinline__ float lanes_allredu
     v = Op::apply(bits_f32(lo), bits_f32(hi));
   }
   return v;
+}
+)SRC";
+
+// what the block-composed template around matrix-unit dots adds: the MFMA wrappers (fp32 accumulate),
+// the all-reduce over the four lanes that share an accumulator row, the lane-pair exchange of the
+// transposing LDS stores
+const char* kMmaPreamble = R"SRC(
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+static __device__ __forceinline__ f32x4 mma_f16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+static __device__ __forceinline__ f32x4 mma_bf16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+// the value of lanes c, c+16, c+32, c+48 combined, in all four
+template <class Op> static __device__ __forceinline__ float rows_allreduce(float v) {
+  unsigned u = f32_bits(v);
+  auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  unsigned lo = r[0], hi = r[1];
+  v = Op::apply(bits_f32(lo), bits_f32(hi));
+  u = f32_bits(v);
+  r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = r[0]; hi = r[1];
+  return Op::apply(bits_f32(lo), bits_f32(hi));
+}
+// the value of the lane whose index differs in bit log2(CH)
+template <int CH> static __device__ __forceinline__ unsigned pair_exchange(unsigned x) {
+  if constexpr (CH == 8) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, false);   // row_ror:8
+  } else {
+    return (unsigned)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x & 63) ^ CH) << 2), (int)x);
+  }
 }
 )SRC";
 
@@ -635,7 +735,58 @@ struct Gen {
     return 1;
   }
 
+  // ---- block composition around dots on the matrix unit (Section 5.1; DotGen of Section 5.3): one
+  // workgroup per batch element, one wavefront per 16 rows of the tile.  The producing dot is computed
+  // transposed (tile kt = b_kt . a^T), so lane (c, g) = (l % 16, l / 16) holds elements 16kt + 4g .. +3
+  // of row c: in the terms of the register templates a row is spread over L = 4 lanes (g) with K = key
+  // tiles chunks of W = 4 -- every elementwise op, reduction, load and store of those templates applies
+  // unchanged, only the lanes of a row are 16 apart instead of adjacent.  The consuming dot takes the
+  // lanes' values as its B fragments (keys inside a 32-step in the order the accumulators imply) and its
+  // second operand transposed through LDS, in a buffer placed by the shared-memory planner.
+  bool mma = false;
+  int NQ = 1;                 // wavefronts = 16-row tiles of the tile's rows
+  int64_t mma_lds_bytes = 0, mma_vt_offset = 0;
+  static int pow2_tiles(int64_t len) {
+    const int need = (int)((len + 15) / 16);
+    return need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
+  }
+  bool geometry_mma(std::string* err) {
+    mma = true;
+    const int w = chunk_elements(A, &fast);
+    if (w < 4) { *err = "generated row schedule: an operand of a matrix-unit group is not readable in 16-byte pieces of 4 elements"; return false; }
+    fast = true;
+    W = 4; L = 4;
+    NQ = pow2_tiles(A.S[1]);
+    K = pow2_tiles(A.S[2]);
+    exact = (int64_t)K * 16 == A.cols;
+    wg = 64 * NQ;
+    if (A.mma_out >= 0) {
+      // the LDS hand-off of the consuming dot (its second operand, transposed), placed by Algorithm 4
+      const int NKP = K < 2 ? 2 : K, SP = NKP * 16 + 8;
+      const int n = (int)A.nodes.size();
+      SharedPlanInput in;
+      in.operands.resize(n);
+      in.req_bytes.assign(n, 0);
+      in.is_output.assign(n, 0);
+      std::vector<int> idx_of(A.g.size(), -1);
+      for (int i = 0; i < n; ++i) idx_of[A.nodes[i].id] = i;
+      int at = -1;
+      for (int i = 0; i < n; ++i) {
+        const RNode& x = A.nodes[i];
+        for (int j = 0; j < x.nop; ++j)
+          if (x.o[j].kind == OP_NODE || x.o[j].kind == OP_ROWB) in.operands[i].push_back(idx_of[x.o[j].index]);
+        if (x.out_ord >= 0) in.is_output[i] = 1;
+        if (x.op == ROP_DOT_MMA_OUT) { in.req_bytes[i] = 2 * A.mma_d * SP; at = i; }
+      }
+      const SharedPlanResult r = shared_plan(in);
+      mma_vt_offset = r.offset[at];
+      mma_lds_bytes = r.total_bytes;
+    }
+    return true;
+  }
+
   bool geometry(std::string* err) {
+    if (A.mma_in >= 0) return geometry_mma(err);
     W = chunk_elements(A, &fast);
     if (W == 0) { *err = "generated row schedule: an operand strided along the last dim"; return false; }
     const int64_t nvec = A.cols / W;
@@ -697,15 +848,135 @@ struct Gen {
     return true;
   }
 
+  // The consuming dot's second operand v[B, N, D]: every thread's 16-byte chunks are requested at the top
+  // of the kernel, long before the LDS transpose needs them.
+  void emit_mma_v_loads() {
+    const int D2 = (int)A.mma_d, NKP = K < 2 ? 2 : K, CH = D2 / 8, VTOT = NKP * 16 * CH, NV = (VTOT + wg - 1) / wg;
+    e.line("  constexpr int D2 = %d, NKP = %d, CH = %d, VTOT = %d, NV = %d, SP = %d, SWM = %d;", D2, NKP, CH, VTOT, NV, NKP * 16 + 8,
+           (2 * NKP < 8 ? 2 * NKP : 8) - 1);
+    e.line("  u32x4 vreg[NV];");
+    e.line("  {");
+    e.line("    const unsigned short* vb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * D2;", A.mma_vv);
+    e.line("    UNROLL for (int i = 0; i < NV; ++i) {");
+    e.line("      int ci = (int)threadIdx.x + i * %d; if (ci > VTOT - 1) ci = VTOT - 1;", wg);
+    e.line("      int key = ci / CH; if (key > N - 1) key = N - 1;");
+    e.line("      vreg[i] = *reinterpret_cast<const u32x4*>(vb + (long long)key * D2 + (ci %% CH) * 8);");
+    e.line("    }");
+    e.line("  }");
+  }
+
+  // The producing dot, transposed: tile k = b_k(16 x KC) . a^T, so the lane holds t[k][j] = row `row`,
+  // column 16k + 4*lane + j.  Operand fragments come straight from global memory in MFMA layout (8
+  // consecutive contraction indices of one row: one 16-byte load); steps beyond KC are zero on both sides.
+  void emit_mma_in(const RNode& n) {
+    const int KC = (int)A.mma_k, KS = (KC + 31) / 32;
+    const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
+    e.line("  float t%d[K][W];", n.id);
+    e.line("  {");
+    e.line("    constexpr int KC = %d, KS = %d;", KC, KS);
+    e.line("    const unsigned short* pa = static_cast<const unsigned short*>(a.in[%d]) + row * KC;", A.mma_va);
+    e.line("    const unsigned short* pb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * KC;", A.mma_vb);
+    e.line("    u32x4 qf[KS], kf[K][KS];");
+    e.line("    UNROLL for (int ks = 0; ks < KS; ++ks) {");
+    e.line("      const int k0 = ks * 32 + 8 * lane;");
+    e.line("      qf[ks] = k0 < KC ? *reinterpret_cast<const u32x4*>(pa + k0) : u32x4{0u, 0u, 0u, 0u};");
+    e.line("    }");
+    e.line("    UNROLL for (int k = 0; k < K; ++k) {");
+    e.line("      int nrow = 16 * k + lane16; if (nrow > N - 1) nrow = N - 1;");
+    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) {");
+    e.line("        const int k0 = ks * 32 + 8 * lane;");
+    e.line("        kf[k][ks] = k0 < KC ? *reinterpret_cast<const u32x4*>(pb + (long long)nrow * KC + k0) : u32x4{0u, 0u, 0u, 0u};");
+    e.line("      }");
+    e.line("    }");
+    e.line("    UNROLL for (int k = 0; k < K; ++k) {");
+    e.line("      f32x4 acc = {0.f, 0.f, 0.f, 0.f};");
+    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) acc = %s(kf[k][ks], qf[ks], acc);", mm);
+    e.line("      UNROLL for (int j = 0; j < W; ++j) t%d[k][j] = acc[j];", n.id);
+    e.line("    }");
+    e.line("  }");
+  }
+
+  // The consuming dot, transposed: O^T(D2 x 16) = V^T(D2 x keys) . P^T.  P is the operand's registers packed
+  // to the dot dtype (keys beyond N are zero), V^T comes from LDS, where it was stored transposed with the
+  // keys of a 32-step in the order the accumulators of the producing dot imply.
+  void emit_mma_out(const RNode& n) {
+    const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
+    const char* pk = A.mma_dtype == FS_F16 ? "pack_to_f16" : "pack_to_bf16";
+    const int src = n.o[0].index;
+    e.line("  {");
+    e.line("    u32x4 pb2[NKP / 2];");
+    e.line("    UNROLL for (int kk = 0; kk < NKP / 2; ++kk) UNROLL for (int h = 0; h < 2; ++h) {");
+    e.line("      const int kt = 2 * kk + h;");
+    e.line("      float p[4] = {0.f, 0.f, 0.f, 0.f};");
+    e.line("      if (kt < K) { UNROLL for (int i = 0; i < 4; ++i) p[i] = ok[kt < K ? kt : 0] ? t%d[kt < K ? kt : 0][i] : 0.f; }", src);
+    e.line("      pb2[kk][2 * h] = %s(p[0], p[1]);", pk);
+    e.line("      pb2[kk][2 * h + 1] = %s(p[2], p[3]);", pk);
+    e.line("    }");
+    e.line("    __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
+    e.line("    unsigned short* vt = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [D2][SP]", (long long)mma_vt_offset);
+    e.line("    unsigned* vt32 = reinterpret_cast<unsigned*>(vt);");
+    e.line("    UNROLL for (int i = 0; i < NV; ++i) {");
+    e.line("      const int cu = (int)threadIdx.x + i * %d;", wg);
+    e.line("      const int ci = cu < VTOT - 1 ? cu : VTOT - 1;");
+    e.line("      const int key = ci / CH, dg = ci %% CH, d0 = dg * 8;");
+    e.line("      const int slot = ((key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3)) ^ ((dg & SWM) << 3);");
+    e.line("      const u32x4 tv = key < N ? vreg[i] : u32x4{0u, 0u, 0u, 0u};");
+    e.line("      const bool odd = (key & 1) != 0;");
+    e.line("      const unsigned rx = pair_exchange<CH>(odd ? tv[0] : tv[2]), ry = pair_exchange<CH>(odd ? tv[1] : tv[3]);");
+    e.line("      const unsigned ex = odd ? rx : tv[0], ey = odd ? ry : tv[1];");
+    e.line("      const unsigned ox = odd ? tv[2] : rx, oy = odd ? tv[3] : ry;");
+    e.line("      if (cu < VTOT) {");
+    e.line("        unsigned* w0 = vt32 + (((d0 + (odd ? 4 : 0)) * SP + (slot & ~1)) >> 1);");
+    e.line("        w0[0 * (SP / 2)] = (ex & 0xFFFFu) | (ox << 16);");
+    e.line("        w0[1 * (SP / 2)] = (ex >> 16) | (ox & 0xFFFF0000u);");
+    e.line("        w0[2 * (SP / 2)] = (ey & 0xFFFFu) | (oy << 16);");
+    e.line("        w0[3 * (SP / 2)] = (ey >> 16) | (oy & 0xFFFF0000u);");
+    e.line("      }");
+    e.line("    }");
+    e.line("    __syncthreads();");
+    e.line("    f32x4 o[D2 / 16];");
+    e.line("    UNROLL for (int dt = 0; dt < D2 / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};");
+    e.line("    UNROLL for (int kk = 0; kk < NKP / 2; ++kk) UNROLL for (int dt = 0; dt < D2 / 16; ++dt) {");
+    e.line("      const int sw = (2 * dt + (lane16 >> 3)) & SWM;");
+    e.line("      const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + lane16) * SP + 8 * ((kk * 4 + lane) ^ sw));");
+    e.line("      o[dt] = %s(vf, pb2[kk], o[dt]);", mm);
+    e.line("    }");
+    if (n.out_dtype == FS_F32) {
+      e.line("    float* orow = static_cast<float*>(a.out[%d]) + row * D2 + 4 * lane;", n.out_ord);
+      e.line("    if (row_ok) { UNROLL for (int dt = 0; dt < D2 / 16; ++dt) __builtin_nontemporal_store(o[dt], reinterpret_cast<f32x4*>(orow + 16 * dt)); }");
+    } else {
+      const char* po = n.out_dtype == FS_F16 ? "pack_to_f16" : "pack_to_bf16";
+      // 8 bytes per tile and lane; lanes g and g^1 trade one tile of a pair so that each stores 16 bytes
+      e.line("    unsigned short* orow = static_cast<unsigned short*>(a.out[%d]) + row * D2 + 16 * (lane & 1) + 8 * (lane >> 1);", n.out_ord);
+      e.line("    UNROLL for (int dp = 0; dp < D2 / 32; ++dp) {");
+      e.line("      const unsigned a0 = %s(o[2 * dp][0], o[2 * dp][1]), a1 = %s(o[2 * dp][2], o[2 * dp][3]);", po, po);
+      e.line("      const unsigned b0 = %s(o[2 * dp + 1][0], o[2 * dp + 1][1]), b1 = %s(o[2 * dp + 1][2], o[2 * dp + 1][3]);", po, po);
+      e.line("      const auto r0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);");
+      e.line("      const auto r1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);");
+      e.line("      const unsigned x0 = r0[0], x1 = r1[0], x2 = r0[1], x3 = r1[1];");
+      e.line("      if (row_ok) *reinterpret_cast<u32x4*>(orow + dp * 32) = u32x4{x0, x1, x2, x3};");
+      e.line("    }");
+    }
+    e.line("  }");
+  }
+
   void emit(std::string* kernel_name) {
     const int rank = A.rank, nrow = rank - 1;
     std::string advance;        // persistent form: hand the prefetched vectors to the next iteration
     e.s = ew_preamble();
     e.s += kReducePreamble;
+    if (mma) e.s += kMmaPreamble;
     const int T = L > 64 ? L / 64 : 1;      // wavefronts per row
-    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", L > 256 ? L : wg > 256 ? wg : 256);
+    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", mma ? wg : L > 256 ? L : wg > 256 ? wg : 256);
     e.line("  constexpr int L = %d, K = %d, W = %d;", L, K, W);
-    if (T > 1) {
+    if (mma) {
+      e.line("  constexpr int M = %lld, N = %lld;             // the tile of one batch element", (long long)A.S[1], (long long)A.S[2]);
+      e.line("  const int lane = (threadIdx.x & 63) >> 4;      // the lane's place among the four that share a row (accumulator layout)");
+      e.line("  const int lane16 = threadIdx.x & 15;           // the row inside the wavefront's 16");
+      e.line("  const int mrow = 16 * (int)(threadIdx.x >> 6) + lane16;");
+      e.line("  const bool row_ok = mrow < M;");
+      e.line("  long long row = (long long)blockIdx.x * M + (row_ok ? mrow : M - 1);   // idle lanes redo the last row and store nothing");
+    } else if (T > 1) {
       // one workgroup of T wavefronts per row; every reduction has its own exchange slots, so one
       // barrier per reduction is enough
       e.line("  constexpr int T = %d;", T);
@@ -767,8 +1038,11 @@ struct Gen {
     } else {
       snprintf(row_hi, sizeof row_hi, "%lldll", (long long)A.rows); snprintf(row_last, sizeof row_last, "%lldll", (long long)A.rows - 1); snprintf(row_any, sizeof row_any, "0");
     }
-    e.line("  const bool row_ok = row < %s%s;", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
-    e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
+    if (!mma) {
+      e.line("  const bool row_ok = row < %s%s;", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
+      e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
+    }
+    if (mma && A.mma_out >= 0) emit_mma_v_loads();
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);
     std::vector<std::string> roff(A.views.size());
@@ -882,6 +1156,7 @@ struct Gen {
       const RView& v = A.views[q];
       const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
       const char* one = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
+      if (v.cls == CLS_NONE) continue;     // an operand of a matrix-unit dot: read by the dot's own code
       // persistent form: an operand that does not depend on the row (a per-column vector, a
       // scalar) is loaded once, before the row loop
       bool invariant = persistent;
@@ -961,6 +1236,8 @@ struct Gen {
           e.line("  r%d = exch[%d][0];", id, red_index);
           e.line("  UNROLL for (int w = 1; w < T; ++w) r%d = %s::apply(r%d, exch[%d][w]);", id, op, id, red_index);
           ++red_index;
+        } else if (mma) {
+          e.line("  r%d = rows_allreduce<%s>(r%d);", id, op, id);
         } else if (L > 1) {
           e.line("  r%d = lanes_allreduce<%s, L>(r%d);", id, op, id);
         }
@@ -992,6 +1269,11 @@ struct Gen {
         e.line("    UNROLL for (int j = 0; j < W; ++j) r%d = fmaf(%s, v%d[k][j], r%d);", n.id, x.c_str(), n.dot_full[0], n.id);
         e.line("  }");
         combine(n.id, true);
+      } else if (n.op == ROP_DOT_MMA_IN) {
+        emit_mma_in(n);
+      } else if (n.op == ROP_DOT_MMA_OUT) {
+        emit_mma_out(n);
+        continue;                          // stores its result itself
       } else if (n.op == ROP_DOT_OUTER) {
         // the full tile from a tiny contraction: sum over k of (row scalar) * (column vector)
         e.line("  float t%d[K][W];", n.id);
@@ -1679,6 +1961,21 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
       l.workspace_bytes = (n_seg > 0 && gen.seg_groups == 1) ? 0 : (int64_t)A.n_col * grid * A.cols * 8;
       l.n_kernels = A.n_col > 0 && l.workspace_bytes > 0 ? 2 : 1;
     }
+    if (gen.mma) {
+      // one workgroup per batch element, one wavefront per 16 rows of the tile
+      l.mma = true;
+      l.mma_dots = A.mma_out >= 0 ? 2 : 1;
+      l.mma_k = (int)A.mma_k; l.mma_d = (int)A.mma_d;
+      l.wg = gen.wg;
+      l.lds_bytes = gen.mma_lds_bytes;
+      l.rows_read_before_written = false;
+      grid = A.S[0];
+      if (opt.wg_size && opt.wg_size != l.wg) {
+        *status = FS_ERR_INVALID;
+        *err = "generated row schedule: wg_size of a matrix-unit group is fixed at 64 per 16 rows of the tile";
+        return false;
+      }
+    }
     if (grid > 0x7fffffffLL) { *err = "generated row schedule: too many rows for one grid"; return false; }
     l.grid = (int)(grid < 1 ? 1 : grid);
     *out = l;
@@ -1733,12 +2030,19 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
 }
 
 std::string row_gen_describe(const RowGenLaunch& l) {
-  char buf[560];
+  char buf[720];
   if (l.streamed) {
     snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d] streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
              l.n_reduce, l.n_ops - l.n_reduce, l.W, l.passes, l.row_buffers, l.buffers_shared,
              l.passes > 1 && !l.inputs_cached ? ", inputs re-read per pass" : "",
              l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
+    return buf;
+  }
+  if (l.mma) {
+    char tail[160] = "";
+    if (l.mma_dots == 2) snprintf(tail, sizeof tail, " + dot_2[GRID,WARP_16,CTA]S (contraction over the tile's %lld columns, %d wide, on MFMA)", (long long)l.cols, l.mma_d);
+    snprintf(buf, sizeof buf, "dot_1[GRID,WARP_16,CTA] (contraction %d on MFMA) + reduce x%d[GRID,WARP_16,WARP] + elementwise x%d[GRID,WARP_16,WARP-THREAD_%d]%s block-composed (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
+             l.mma_k, l.n_reduce, l.n_ops - l.n_reduce - l.mma_dots, l.K * l.W, tail, l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
     return buf;
   }
   if (l.persistent && l.n_col == 0) {

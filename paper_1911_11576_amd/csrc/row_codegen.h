@@ -30,6 +30,9 @@ struct RowGenLaunch {
   int64_t seg_count = 0;
   int seg_groups = 0;
   int n_kernels = 1;
+  // block composition around dots on the matrix unit: one workgroup per batch element
+  bool mma = false;
+  int mma_dots = 0, mma_k = 0, mma_d = 0;   // dots on MFMA (1 or 2), contraction of the first, result width of the second
   int64_t workspace_bytes = 0;
   int64_t rows = 0, cols = 0, lds_bytes = 0;
   std::vector<int> view_param;        // parameter ordinal behind each operand view

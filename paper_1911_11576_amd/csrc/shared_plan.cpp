@@ -1,14 +1,7 @@
-// Shared-memory planning (paper Section 5.4, Algorithm 4).
-//
-// Ops are visited in execution order.  An op that needs no shared space passes on the
-// allocation information of its operands (which spaces its inputs still live in).  An op
-// that needs space looks at the spaces reaching it through its operands: a space whose owner
-// is dominated by the op (every path from the group's root to the owner runs through the
-// op: once the op has produced its result nothing else will read the owner's value) can be
-// taken over; the first such space is shared, the others are reclaimed for later ops.  If
-// none can be taken over, a reclaimed space that is large enough is reused, else fresh
-// space is allocated.  The goal, as in the paper, is to bound the worst-case footprint, not
-// to find the minimum.
+// Shared-memory planning (paper Section 5.4, Algorithm 4): an arena of LDS blocks, a dominance tree
+// of the group's data-flow graph, and one walk over the ops in execution order that decides for every
+// request whether it takes over the block of a value it dominates, reuses a freed block or grows the
+// arena.  The goal, as in the paper, is to bound the worst-case footprint, not to find the minimum.
 #include "shared_plan.h"
 
 #include <algorithm>
@@ -65,54 +58,72 @@ bool dominates(const std::vector<int>& idom, int a, int b) {
   return false;
 }
 
+namespace {
+
+// The LDS arena: blocks carved out of one growing range.  A block has an owner (the op whose value
+// lives in it) or is free; a free block keeps its place and size and is handed to the next request it
+// is large enough for.
+struct Arena {
+  struct Block { int64_t offset, bytes; int owner; };   // owner -1: free
+  std::vector<Block> blocks;
+  int64_t top = 0;
+  int grow(int64_t bytes, int owner) {
+    blocks.push_back(Block{top, bytes, owner});
+    top += bytes;
+    return (int)blocks.size() - 1;
+  }
+  // the smallest free block that holds `bytes`, or -1
+  int best_free(int64_t bytes) const {
+    int best = -1;
+    for (size_t k = 0; k < blocks.size(); ++k)
+      if (blocks[k].owner < 0 && blocks[k].bytes >= bytes && (best < 0 || blocks[k].bytes < blocks[best].bytes)) best = (int)k;
+    return best;
+  }
+};
+
+}  // namespace
+
+// Every value carries the set of arena blocks it still depends on: its own block, if it has one, and the
+// blocks of the values it was computed from, as long as those values may be read again.  A value that
+// needs space may take the block of a value it dominates (Section 5.4: once the dominating op has
+// produced its result, nothing reads the dominated value any more); the other blocks of dominated
+// values in its set become free.
 SharedPlanResult shared_plan(const SharedPlanInput& in) {
   const int n = (int)in.operands.size();
   SharedPlanResult r;
   r.offset.assign(n, -1);
   r.shares_with.assign(n, -1);
   const std::vector<int> idom = dataflow_idom(in);
-  struct Block { int64_t offset, bytes; };
-  std::vector<Block> block_of(n, Block{-1, 0});     // the space an op currently owns
-  std::vector<Block> reclaimed;                      // spaces free for later ops
-  std::vector<std::set<int>> info(n);                // per op: owners of the spaces its value still depends on
+  Arena arena;
+  std::vector<std::vector<int>> depends(n);          // per op: arena blocks in use below it, ordered by owner
+  auto by_owner = [&](int a, int b) { return arena.blocks[a].owner < arena.blocks[b].owner; };
   for (int i = 0; i < n; ++i) {
-    std::set<int> prev;                              // CollectAllocInfo over the operands
-    for (int o : in.operands[i]) prev.insert(info[o].begin(), info[o].end());
-    if (in.req_bytes[i] <= 0) { info[i] = prev; continue; }   // PropagateAllocInfo
+    std::vector<int>& mine = depends[i];
+    for (int o : in.operands[i]) mine.insert(mine.end(), depends[o].begin(), depends[o].end());
+    // blocks that changed hands since an operand recorded them no longer hold that operand's input
+    mine.erase(std::remove_if(mine.begin(), mine.end(), [&](int k) { return arena.blocks[k].owner < 0 || arena.blocks[k].owner >= i; }), mine.end());
+    std::sort(mine.begin(), mine.end(), by_owner);
+    mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
     const int64_t need = in.req_bytes[i];
-    bool shared = false;
-    std::set<int> still;
-    for (int p : prev) {
-      if (block_of[p].offset < 0) continue;          // already handed on
-      if (dominates(idom, i, p)) {
-        if (!shared && block_of[p].bytes >= need) {  // Share
-          block_of[i] = block_of[p];
-          r.shares_with[i] = p;
-          shared = true;
-        } else {                                     // Reclaim
-          reclaimed.push_back(block_of[p]);
-        }
-        block_of[p] = Block{-1, 0};
-      } else {
-        still.insert(p);
-      }
+    if (need <= 0) continue;
+    int taken = -1;
+    std::vector<int> kept;
+    for (int k : mine) {
+      Arena::Block& b = arena.blocks[k];
+      if (!dominates(idom, i, b.owner)) { kept.push_back(k); continue; }
+      if (taken < 0 && b.bytes >= need) { taken = k; r.shares_with[i] = b.owner; b.owner = i; }
+      else b.owner = -1;
     }
-    if (!shared) {                                   // Alloc: a reclaimed space that fits, else fresh space
-      int best = -1;
-      for (size_t k = 0; k < reclaimed.size(); ++k)
-        if (reclaimed[k].bytes >= need && (best < 0 || reclaimed[k].bytes < reclaimed[best].bytes)) best = (int)k;
-      if (best >= 0) {
-        block_of[i] = reclaimed[best];
-        reclaimed.erase(reclaimed.begin() + best);
-      } else {
-        block_of[i] = Block{r.total_bytes, need};
-        r.total_bytes += need;
-      }
+    if (taken < 0) {
+      taken = arena.best_free(need);
+      if (taken >= 0) arena.blocks[taken].owner = i;
+      else taken = arena.grow(need, i);
     }
-    r.offset[i] = block_of[i].offset;
-    still.insert(i);
-    info[i] = still;
+    r.offset[i] = arena.blocks[taken].offset;
+    kept.push_back(taken);
+    mine = kept;
   }
+  r.total_bytes = arena.top;
   return r;
 }
 

@@ -87,3 +87,25 @@ def test_mutated_op_lists_never_crash_the_fusion_planner():
         else:
             assert not out.value and binding.fs_last_error()
     assert ok > 5
+
+
+def test_extents_whose_product_wraps_are_refused():
+    """Two (or more) extents that are each below 2^40 but whose product is not, up to products that wrap a
+    64-bit integer to 0 or to something small: FS_ERR_INVALID, never an "empty" or a small tensor."""
+    for shape in ([2**32, 2**32, 1, 1], [2**32, 2**32, 2**32, 2**32], [2**33, 2**31 + 1, 2, 1], [2**21, 2**21, 2**21, 2],
+                  [2**39, 4, 1, 1], [3, 2**39, 1, 1]):
+        for kind in ("parameter", "add"):
+            ops = graphs.adam_update((8, 16))
+            arr = marshal_ops(ops)
+            target = next(i for i, op in enumerate(ops) if op.kind == kind)
+            arr[target].rank = 4
+            for k in range(4):
+                arr[target].shape[k] = shape[k]
+            out = C.c_void_p()
+            st = lib().fs_plan_create(arr, len(arr), None, C.byref(out))
+            assert st == binding.FS_ERR_INVALID and not out.value, (shape, kind, st)
+            assert "too large" in binding.fs_last_error() or "shape" in binding.fs_last_error()
+    # a zero extent still makes a legal, empty tensor whatever the other extents are
+    ops = graphs.layernorm_fwd(0, 64)
+    with binding.Plan(ops) as p:
+        assert p.info()["algorithmic_bytes"] == 2 * 64 * 4

@@ -518,6 +518,21 @@ def test_compiled_kernels_are_kept_on_disk_between_processes(tmp_path):
             assert p.describe() == first
         s4 = fs_kernel_cache_stats()
         assert s4["compiled"] == s3["compiled"] + 1 and files[0].stat().st_size > 1000
+        # ... and so is a file of the right length with one byte flipped in the middle of the code, or in the
+        # identity text that says which source, options and compiler the code belongs to
+        good = files[0].read_bytes()
+        for at in (len(good) // 2 + 1000, 100):
+            bad = bytearray(good)
+            bad[min(at, len(bad) - 1)] ^= 0x40
+            files[0].write_bytes(bytes(bad))
+            fs_kernel_cache_drop_memory()
+            before = fs_kernel_cache_stats()
+            with Plan(ops) as p:
+                assert p.describe() == first
+            after = fs_kernel_cache_stats()
+            assert after["compiled"] == before["compiled"] + 1 and after["from_disk"] == before["from_disk"], at
+            assert files[0].read_bytes() == good                # replaced by the fresh compile
+        s4 = fs_kernel_cache_stats()
         # without a directory nothing is read or written
         fs_kernel_cache_dir(None)
         fs_kernel_cache_drop_memory()
@@ -574,13 +589,15 @@ def test_attention_block_forms_are_recognised():
                 assert f"cta_size={64 * nq}" in text and info["lds_bytes"] == 2 * 64 * (nk * 16 + 8)
 
 
-def test_attention_block_forms_that_are_refused():
-    # a finite causal fill under a mask that is added afterwards: the fill value would be shifted
-    _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 32, 32, 64, causal=True, fill=-1e4, mask="key", mask_outside_causal=True))
-    # lengths beyond the fine-grained schedule
+def test_attention_block_forms_beyond_the_hand_written_kernel():
+    # lengths beyond the fine-grained schedules: refused by both the hand-written kernel and the generator
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 32, 200, 64))
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.attention_block(2, 200, 32, 64))
-    # a mask inside the scale: scale * (dot + mask)
+    # a finite causal fill under a mask that is added afterwards (the fill value is shifted by the mask): not the
+    # hand-written kernel's form -- the generated block-composed kernel takes it
+    with Plan(graphs.attention_block(2, 32, 32, 64, causal=True, fill=-1e4, mask="key", mask_outside_causal=True)) as p:
+        assert p.info()["schedule"] == "block_dot"
+    # a mask inside the scale, scale * (dot + mask): likewise
     g = Graph()
     q = g.parameter("q", "f16", (2, 32, 64)); k = g.parameter("k", "f16", (2, 32, 64)); v = g.parameter("v", "f16", (2, 32, 64))
     m = g.parameter("m", "f32", (2, 32, 32))
@@ -589,4 +606,35 @@ def test_attention_block_forms_that_are_refused():
     e = g.exp(g.subtract(z, g.row_broadcast(zmax, z)))
     p = g.convert(g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), e)), "f16")
     g.output(g.convert(g.dot(p, v, dtype="f32"), "f16"))
-    _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "block_dot"
+
+
+# ---------------------------------------------------------------- generated block composition around MFMA dots
+
+def _dot_group(dtype="f16", kc=64, transpose_b=True, after=False, d=64):
+    g = Graph()
+    B, M, N = 2, 32, 48
+    q = g.parameter("q", dtype, (B, M, kc))
+    k = g.parameter("k", dtype, (B, N, kc) if transpose_b else (B, kc, N))
+    v = g.parameter("v", dtype, (B, N, d))
+    p = g.logistic(g.dot(q, k, transpose_b=transpose_b, dtype="f32"))
+    o = g.dot(g.convert(p, dtype) if dtype != "f32" else p, v, dtype="f32")
+    if after:
+        o = g.multiply(o, g.constant(2.0))
+    g.output(o)
+    return g.ops
+
+
+def test_block_dot_groups_are_generated_or_refused_with_a_reason():
+    with Plan(_dot_group()) as p:
+        info = p.info()
+        assert info["schedule"] == "block_dot" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+        # V^T of the padded key tiles (64 keys + 8 halves of padding) x 64 rows, placed by the shared-memory planner
+        assert info["lds_bytes"] == 2 * 64 * (4 * 16 + 8)
+        assert "dot_1" in p.describe() and "dot_2" in p.describe() and "MFMA" in p.describe()
+    assert "matrix unit" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group("f32"))            # fp32 dots have no MFMA path
+    assert "[B, N, K]" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(transpose_b=False))   # contraction must be contiguous
+    assert "no ops after" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(after=True))
+    assert "32, 64 or 128" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(d=48))
+    assert "multiple of 8" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(kc=20))
