@@ -306,7 +306,9 @@ fs_status fs_shared_plan(const int32_t* operands, const int64_t* req_bytes, cons
  * which ops to fuse: fusion patterns are generated by substitution fusion (Algorithm 1, with
  * its growing set of partition ops) and exploratory fusion (Algorithm 2), scored by the
  * model-based score f(P) = M(V) + (N-1)*phi (negative when no stitched kernel can be built
- * for the pattern), and a set of pairwise disjoint patterns of maximal total score is
+ * for the pattern) or, for the patterns the caller has run, by the time they were measured to
+ * save (the hybrid policy of Section 4.3: fs_fusion_pattern_group hands out any candidate as an
+ * op list to build, time against its per-op plan and report back in extra_scores), and a set of pairwise disjoint patterns of maximal total score is
  * selected exactly (the ILP of Section 4.1), with the paper's iterative repair when the
  * selection would make the graph cyclic.  Pure host work.  The result is a list of groups in
  * an order that respects data flow; each group comes back as an op list of its own, ready
@@ -326,6 +328,10 @@ typedef struct {
   int32_t n_extra;         /* caller-supplied patterns, scored and offered to the solver like the */
   const int32_t* extra_sizes; /* generated ones: n_extra sizes, then the op indices of all of them  */
   const int32_t* extra_ops;   /* back to back (kernel-owning ops of the list, any order)            */
+  const double* extra_scores; /* NULL, or n_extra entries: the execution-based score of that pattern  */
+                              /* (Section 4.3): the microseconds the caller measured it to save over  */
+                              /* one kernel per op, used instead of the model's f(P) -- also for a    */
+                              /* generated pattern with the same ops; NaN: the model's score          */
 } fs_fusion_options;
 
 /* Errors: FS_ERR_INVALID (malformed list or options), FS_ERR_NOMEM. */
@@ -346,9 +352,18 @@ fs_status fs_fusion_group(const fs_fusion* fusion, int32_t g, fs_op_desc* ops, i
 /* Candidate pattern k (0 <= k < n_patterns): number of ops, the ops themselves (up to cap),
  * how it was found (0 substitution, 1 connected part of a substitution segment, 2 exploratory,
  * 3 supplied by the caller),
- * V in bytes, f(P) in microseconds (negative: not generable), whether the plan uses it. */
+ * V in bytes, f(P) in microseconds (negative: not generable, or measured to be slower fused),
+ * whether the plan uses it. */
 fs_status fs_fusion_pattern(const fs_fusion* fusion, int32_t k, int32_t* n_ops, int32_t* ops, int32_t cap,
                             int32_t* origin, int64_t* saved_bytes, double* score_us, int32_t* chosen);
+
+/* Candidate pattern k as a stand-alone op list, as fs_fusion_group gives a chosen group: sizes
+ * first (all 0 for a pattern no stitched plan exists for; measured = 1 if its score is the
+ * caller's), then the list and the original ops its parameters / outputs stand for. */
+fs_status fs_fusion_pattern_group_size(const fs_fusion* fusion, int32_t k, int32_t* n_ops, int32_t* n_inputs,
+                                       int32_t* n_outputs, int32_t* measured);
+fs_status fs_fusion_pattern_group(const fs_fusion* fusion, int32_t k, fs_op_desc* ops, int32_t* input_of,
+                                  int32_t* output_of);
 
 /* Measurement aid: plain streaming copy of `bytes` (multiple of 16) from src to dst,
  * both DEVICE pointers, 16-byte aligned, on `hip_stream`.  Gives the achievable HBM

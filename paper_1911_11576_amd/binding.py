@@ -41,7 +41,7 @@ class fs_fusion_options(C.Structure):
     _fields_ = [("launch_us", C.c_double), ("max_patterns", C.c_int32), ("explore_budget", C.c_int32),
                 ("seed_bytes", C.c_int64), ("bw_bytes", C.POINTER(C.c_int64)), ("bw_gbs", C.POINTER(C.c_double)),
                 ("n_bw", C.c_int32), ("n_extra", C.c_int32), ("extra_sizes", C.POINTER(C.c_int32)),
-                ("extra_ops", C.POINTER(C.c_int32))]
+                ("extra_ops", C.POINTER(C.c_int32)), ("extra_scores", C.POINTER(C.c_double))]
 
 
 class FsError(RuntimeError):
@@ -117,6 +117,10 @@ def lib():
         L.fs_fusion_pattern.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(i64),
                                         C.POINTER(C.c_double), C.POINTER(i32)]
         L.fs_fusion_pattern.restype = i32
+        L.fs_fusion_pattern_group_size.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+        L.fs_fusion_pattern_group_size.restype = i32
+        L.fs_fusion_pattern_group.argtypes = [vp, i32, C.POINTER(fs_op_desc), C.POINTER(i32), C.POINTER(i32)]
+        L.fs_fusion_pattern_group.restype = i32
         _lib = L
     return _lib
 
@@ -353,10 +357,14 @@ class FusionPlan:
     .groups     list of dicts in execution order: ops (marshalled fs_op_desc array, ready for
                 fs_plan_create), input_of / output_of (indices into the original list), members
                 (the original ops it fuses), score_us
-    .patterns   every scored candidate: ops, origin, saved_bytes, score_us, chosen
+    .patterns   every scored candidate: ops, origin, saved_bytes, score_us, chosen, measured, and (where a
+                stitched plan exists for it) group_ops / input_of / output_of like a group's
+
+    extra_scores: per extra pattern the microseconds it was measured to save (None or NaN: the model's score).
     """
 
-    def __init__(self, ops, launch_us=0.0, max_patterns=0, explore_budget=0, seed_bytes=0, bandwidth=None, extra_patterns=None):
+    def __init__(self, ops, launch_us=0.0, max_patterns=0, explore_budget=0, seed_bytes=0, bandwidth=None, extra_patterns=None,
+                 extra_scores=None):
         arr = ops if isinstance(ops, C.Array) else marshal_ops(ops)
         opt = fs_fusion_options()
         opt.launch_us, opt.max_patterns, opt.explore_budget, opt.seed_bytes = launch_us, max_patterns, explore_budget, seed_bytes
@@ -373,6 +381,12 @@ class FusionPlan:
             eo = (C.c_int32 * len(flat))(*flat)
             opt.n_extra, opt.extra_sizes, opt.extra_ops = len(extra_patterns), sizes, eo
             keep2 = (sizes, eo)
+            if extra_scores is not None:
+                if len(extra_scores) != len(extra_patterns):
+                    raise ValueError("extra_scores: one entry per extra pattern")
+                es = (C.c_double * len(extra_scores))(*[float("nan") if v is None else float(v) for v in extra_scores])
+                opt.extra_scores = es
+                keep2 = (sizes, eo, es)
         h = C.c_void_p()
         _check(lib().fs_fusion_create(arr, len(arr), C.byref(opt), C.byref(h)))
         del keep, keep2
@@ -396,8 +410,17 @@ class FusionPlan:
                 _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), None, 0, None, None, None, None))      # its size first
                 buf = (C.c_int32 * max(1, n_ops.value))()
                 _check(lib().fs_fusion_pattern(h, k, C.byref(n_ops), buf, n_ops.value, C.byref(origin), C.byref(saved), C.byref(score), C.byref(chosen)))
-                self.patterns.append(dict(ops=list(buf[:n_ops.value]), n_ops=n_ops.value, origin=origin.value,
-                                          saved_bytes=saved.value, score_us=score.value, chosen=bool(chosen.value)))
+                pat = dict(ops=list(buf[:n_ops.value]), n_ops=n_ops.value, origin=origin.value,
+                           saved_bytes=saved.value, score_us=score.value, chosen=bool(chosen.value))
+                l_ops, l_in, l_out, measured = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+                _check(lib().fs_fusion_pattern_group_size(h, k, C.byref(l_ops), C.byref(l_in), C.byref(l_out), C.byref(measured)))
+                pat["measured"] = bool(measured.value)
+                if l_ops.value:
+                    gops = (fs_op_desc * l_ops.value)()
+                    gin, gout = (C.c_int32 * max(1, l_in.value))(), (C.c_int32 * max(1, l_out.value))()
+                    _check(lib().fs_fusion_pattern_group(h, k, gops, gin, gout))
+                    pat.update(group_ops=gops, input_of=list(gin[:l_in.value]), output_of=list(gout[:l_out.value]))
+                self.patterns.append(pat)
         finally:
             lib().fs_fusion_destroy(h)
 
@@ -416,11 +439,11 @@ class FusedProgram:
     intermediates between groups in device tensors.  Inputs: one tensor per parameter op of the
     original list, in order; outputs: one per output op."""
 
-    def __init__(self, ops, **fusion_options):
+    def __init__(self, ops, fusion=None, **fusion_options):
         import torch
         self._torch = torch
         self.ops = list(ops)
-        self.fusion = FusionPlan(self.ops, **fusion_options)
+        self.fusion = fusion if fusion is not None else FusionPlan(self.ops, **fusion_options)
         self.param_ops = [i for i, op in enumerate(self.ops) if op.kind == "parameter"]
         self.output_ops = [i for i, op in enumerate(self.ops) if op.kind == "output"]
         self.plans = []
@@ -477,6 +500,46 @@ class FusedProgram:
             else:
                 prog.close()
         return best
+
+    @classmethod
+    def measured(cls, ops, top=12, trials=20, device="cuda:0", **fusion_options):
+        """The hybrid scoring policy of Section 4.3.  Plan with the model's scores; build the plan's
+        patterns and the `top` best other candidates, time each stitched and as one kernel per op on
+        buffers of the right shapes, and plan again with the measured savings in place of the model's
+        for those patterns.  -> (program, list of (pattern ops, model score, measured score))."""
+        import torch
+        ops = list(ops)
+        dt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+        first = FusionPlan(ops, **fusion_options)
+        ranked = sorted((p for p in first.patterns if p["score_us"] >= 0 and "group_ops" in p),
+                        key=lambda p: (not p["chosen"], -p["score_us"]))
+        n_chosen = sum(1 for p in ranked if p["chosen"])
+        picked = ranked[:n_chosen + top]
+
+        def timed(plan, gin, gout):
+            for _ in range(2):
+                plan.launch(gin, gout)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(trials):
+                plan.launch(gin, gout)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / trials
+
+        report = []
+        for p in picked:
+            shapes = [(ops[i].shape, ops[i].dtype) for i in p["input_of"]]
+            gin = [torch.randn(sh, dtype=torch.float32, device=device).to(dt[d]) for sh, d in shapes]
+            gout = [torch.empty(ops[i].shape, dtype=dt[ops[i].dtype], device=device) for i in p["output_of"]]
+            with Plan(p["group_ops"]) as fused, Plan(p["group_ops"], "per_op") as apart:
+                saved = timed(apart, gin, gout) - timed(fused, gin, gout)
+            report.append((p["ops"], p["score_us"], saved))
+        kw = dict(fusion_options)
+        extra = list(kw.pop("extra_patterns", None) or [])
+        scores = list(kw.pop("extra_scores", None) or [None] * len(extra))
+        second = FusionPlan(ops, extra_patterns=extra + [r[0] for r in report], extra_scores=scores + [r[2] for r in report], **kw)
+        return cls(ops, fusion=second), report
 
     def tune(self, inputs, trials=10):
         """Time every group's launch templates on the program's own data (fs_plan_tune, group by group in

@@ -213,6 +213,12 @@ fs_status plan_create_impl(const fs_op_desc* ops, int32_t n_ops, const fs_plan_o
         if (!fs::build_graph(merged.data(), (int32_t)merged.size(), &g2, &err2)) break;
         p->graph = g2;
       }
+      // reductions over the leading dim that keep the inner dims: the inner dims become one (same memory)
+      if (fs::collapse_kept_dims_of_leading_reductions(p->graph, &merged)) {
+        fs::Graph g2;
+        std::string err2;
+        if (fs::build_graph(merged.data(), (int32_t)merged.size(), &g2, &err2)) p->graph = g2;
+      }
     }
     const int64_t algo = p->graph.algorithmic_bytes();
     if (p->mode == FS_MODE_PER_OP) {
@@ -630,6 +636,7 @@ fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion
         next += opt->extra_sizes[k];
         for (int o : pat) if (o < 0 || o >= n_ops) return set_error(FS_ERR_INVALID, "extra patterns: op index out of range");
         cfg.extra_patterns.push_back(pat);
+        if (opt->extra_scores) cfg.extra_scores.push_back(opt->extra_scores[k]);
       }
       if (opt->max_patterns < 0 || opt->max_patterns > 256) return set_error(FS_ERR_INVALID, "max_patterns out of range [0,256]");
       if (opt->n_bw < 0 || (opt->n_bw > 0 && (!opt->bw_bytes || !opt->bw_gbs))) return set_error(FS_ERR_INVALID, "bandwidth model: NULL table");
@@ -706,6 +713,28 @@ fs_status fs_fusion_pattern(const fs_fusion* f, int32_t k, int32_t* n_ops, int32
   if (saved_bytes) *saved_bytes = p.saved_bytes;
   if (score) *score = p.score;
   if (chosen) *chosen = p.chosen ? 1 : 0;
+  return FS_OK;
+}
+
+fs_status fs_fusion_pattern_group_size(const fs_fusion* f, int32_t k, int32_t* n_ops, int32_t* n_in, int32_t* n_out,
+                                       int32_t* measured) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (k < 0 || k >= (int32_t)f->result.patterns.size()) return set_error(FS_ERR_INVALID, "pattern index out of range");
+  const fs::FusionPattern& p = f->result.patterns[k];
+  if (n_ops) *n_ops = (int32_t)p.list.size();
+  if (n_in) *n_in = (int32_t)p.input_of.size();
+  if (n_out) *n_out = (int32_t)p.output_of.size();
+  if (measured) *measured = p.measured ? 1 : 0;
+  return FS_OK;
+}
+
+fs_status fs_fusion_pattern_group(const fs_fusion* f, int32_t k, fs_op_desc* ops, int32_t* input_of, int32_t* output_of) {
+  if (!f) return set_error(FS_ERR_INVALID, "fusion is NULL");
+  if (k < 0 || k >= (int32_t)f->result.patterns.size()) return set_error(FS_ERR_INVALID, "pattern index out of range");
+  const fs::FusionPattern& p = f->result.patterns[k];
+  if (ops) for (size_t j = 0; j < p.list.size(); ++j) ops[j] = p.list[j];
+  if (input_of) for (size_t j = 0; j < p.input_of.size(); ++j) input_of[j] = p.input_of[j];
+  if (output_of) for (size_t j = 0; j < p.output_of.size(); ++j) output_of[j] = p.output_of[j];
   return FS_OK;
 }
 

@@ -83,7 +83,7 @@ template <int CH> __device__ __forceinline__ uint32_t pair_exchange(uint32_t x) 
 
 // NQ: 16-row tiles of queries (workgroup = NQ wavefronts); NK: 16-key tiles; D: head dim;
 // X: the group has a mask, an epilogue operand or a second output (without any of them those paths
-// are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 4%)
+// are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 0.15 us of 6)
 template <typename T, int NQ, int NK, int D, bool X>
 __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) {
   constexpr int KS = D / 32;                 // k-steps of the first dot

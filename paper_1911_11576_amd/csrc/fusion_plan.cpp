@@ -307,6 +307,7 @@ struct Planner {
   // Model-based score of a set of ops: negative if it is not convex or no stitched plan can be
   // built for it (asked of fs_plan_create itself, which stops before compilation).  Remembered per set.
   std::map<std::vector<int>, std::pair<double, int64_t>> evaluated;
+  std::map<std::vector<int>, FusionGroup> lists;       // the stand-alone op lists of the generable sets
   double evaluate(const std::vector<int>& ops, int64_t* saved = nullptr) {
     auto it = evaluated.find(ops);
     if (it == evaluated.end()) {
@@ -317,6 +318,7 @@ struct Planner {
         if (generable(gr)) {
           r.second = fusion_saved_bytes(g, ops);
           r.first = fusion_model_us(cfg, r.second) + (double)(ops.size() - 1) * cfg.launch_us;
+          lists.emplace(ops, std::move(gr));
         }
       }
       it = evaluated.emplace(ops, r).first;
@@ -372,8 +374,24 @@ struct Planner {
     for (const std::vector<int>& p : cfg.extra_patterns) add(p, 3);
   }
 
+  // The hybrid policy of Section 4.3: the model's score for every pattern; where the caller ran a
+  // pattern and reports the time it saves, that figure stands instead (also when it says the
+  // fused kernel loses: a negative score keeps the pattern out of the selection).
   void score() {
-    for (FusionPattern& p : patterns) p.score = evaluate(p.ops, &p.saved_bytes);
+    std::map<std::vector<int>, double> reported;
+    for (size_t k = 0; k < cfg.extra_patterns.size() && k < cfg.extra_scores.size(); ++k) {
+      if (std::isnan(cfg.extra_scores[k])) continue;
+      std::vector<int> key = cfg.extra_patterns[k];
+      std::sort(key.begin(), key.end());
+      reported[key] = cfg.extra_scores[k];
+    }
+    for (FusionPattern& p : patterns) {
+      p.score = evaluate(p.ops, &p.saved_bytes);
+      auto li = lists.find(p.ops);
+      if (li != lists.end()) { p.list = li->second.list; p.input_of = li->second.input_of; p.output_of = li->second.output_of; }
+      auto it = reported.find(p.ops);
+      if (p.score >= 0.0 && it != reported.end()) { p.score = it->second; p.measured = true; }
+    }
   }
 };
 

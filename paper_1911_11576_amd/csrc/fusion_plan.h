@@ -17,14 +17,20 @@ struct FusionConfig {
   int64_t seed_bytes = 1 << 20;           // exploratory seeds: ops whose result is at least this large
   std::vector<std::pair<int64_t, double>> bandwidth;   // M(V) model: (bytes, GB/s), increasing bytes
   std::vector<std::vector<int>> extra_patterns;        // caller-supplied candidates
+  std::vector<double> extra_scores;                    // per supplied candidate: its measured f(P) in microseconds,
+                                                       // NaN (or no entry): the model's score
 };
 
 struct FusionPattern {
   std::vector<int> ops;                   // owned ops (op indices of the graph), increasing
   int origin = 0;                         // 0 substitution, 1 a connected part of a substitution segment, 2 exploratory, 3 caller
   int64_t saved_bytes = 0;                // V
-  double score = -1.0;                    // f(P) in microseconds, negative: cannot be generated
+  double score = -1.0;                    // f(P) in microseconds; negative: cannot be generated, or measured to lose
+  bool measured = false;                  // the score is the caller's measurement, not the model's
   bool chosen = false;
+  // the pattern as a stand-alone op list (filled for patterns a stitched plan exists for)
+  std::vector<fs_op_desc> list;
+  std::vector<int> input_of, output_of;
 };
 
 struct FusionGroup {

@@ -207,4 +207,52 @@ bool collapse_trailing_reductions(const Graph& g, std::vector<fs_op_desc>* out) 
   return true;
 }
 
+// A reduction over the leading dim that keeps all the others ([B, S, H] -> [S, H]) is a column reduction
+// of the same memory read as [B, S*H] -> [S*H]: tensors are dense, so the kept dims merge into one.  The
+// rewritten list has rank-2 full values and rank-1 kept values; the schedules then see sums (or maxima)
+// over the rows of a matrix.  Applies where nothing tells the kept dims apart: every op has the full
+// shape, the kept shape or rank 0, every reduction runs over the leading dim of a full value, and what is
+// broadcast into the full shape is a kept-shape value or a scalar.
+bool collapse_kept_dims_of_leading_reductions(const Graph& g, std::vector<fs_op_desc>* out) {
+  const int n = g.size();
+  auto is_reduce = [](int k) { return k == FS_REDUCE_SUM || k == FS_REDUCE_MAX; };
+  int first = -1;
+  for (int i = 0; i < n && first < 0; ++i)
+    if (is_reduce(g[i].kind) && g[i].axis == 0 && g[g[i].operand[0]].rank >= 3) first = i;
+  if (first < 0) return false;
+  const Node& full = g[g[first].operand[0]];
+  const int r = full.rank;
+  auto is_kept = [&](const Node& x) {
+    if (x.rank != r - 1) return false;
+    for (int d = 0; d < r - 1; ++d) if (x.shape[d] != full.shape[d + 1]) return false;
+    return true;
+  };
+  for (int i = 0; i < n; ++i) {
+    const Node& x = g[i];
+    if (x.kind == FS_DOT || x.kind == FS_CAUSAL_MASK) return false;
+    if (!(x.rank == 0 || (x.rank == r && x.same_shape(full)) || is_kept(x))) return false;
+    if (is_reduce(x.kind) && !(x.axis == 0 && g[x.operand[0]].rank == r)) return false;
+    if (x.kind == FS_BROADCAST) {
+      const Node& a = g[x.operand[0]];
+      if (a.rank == 0) continue;
+      if (!(x.rank == r && is_kept(a) && x.axis == 1)) return false;
+    }
+  }
+  int64_t merged = 1;
+  for (int d = 1; d < r; ++d) merged *= full.shape[d];
+  out->clear();
+  for (int i = 0; i < n; ++i) {
+    const Node& x = g[i];
+    fs_op_desc d{};
+    d.kind = x.kind; d.dtype = x.dtype; d.rank = x.rank; d.axis = x.axis; d.attr = x.attr;
+    if (x.rank == r) { d.rank = 2; d.shape[0] = full.shape[0]; d.shape[1] = merged; }
+    else if (x.rank == r - 1) { d.rank = 1; d.shape[0] = merged; }
+    if (x.kind == FS_BROADCAST) d.axis = g[x.operand[0]].rank == 0 ? 0 : 1;
+    const int nop = operand_count(x.kind);
+    for (int k = 0; k < 3; ++k) d.operand[k] = k < nop ? x.operand[k] : -1;
+    out->push_back(d);
+  }
+  return true;
+}
+
 }  // namespace fs

@@ -41,6 +41,9 @@ bool build_graph(const fs_op_desc* ops, int32_t n_ops, Graph* g, std::string* er
 // One step of merging chained reductions over the two trailing dims into a reduction over one merged
 // dim; true (and the rewritten op list) if the group allows it.  See graph.cpp.
 bool collapse_trailing_reductions(const Graph& g, std::vector<fs_op_desc>* out);
+// Reductions over the leading dim that keep all other dims ([B, S, H] -> [S, H]): the kept dims merged
+// into one, so that the group is a matrix [B, S*H] with reductions over its rows.  See graph.cpp.
+bool collapse_kept_dims_of_leading_reductions(const Graph& g, std::vector<fs_op_desc>* out);
 
 inline bool is_binary(int k) { return k >= FS_ADD && k <= FS_MAXIMUM; }
 inline bool is_unary(int k) { return (k >= FS_NEGATE && k <= FS_SQRT) || k == FS_ERF || k == FS_LOGISTIC; }

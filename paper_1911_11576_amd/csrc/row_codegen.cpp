@@ -1495,7 +1495,9 @@ struct Stream {
 
   explicit Stream(const Analysis& a) : A(a) {}
 
-  static bool is_red(const RNode& n) { return n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX || n.op == ROP_DOT_REDUCE; }
+  static bool is_col(const RNode& n) { return n.cls == CLS_COL; }     // a reduction over the rows: running values per thread and column
+  static bool is_red(const RNode& n) { return !is_col(n) && (n.op == FS_REDUCE_SUM || n.op == FS_REDUCE_MAX || n.op == ROP_DOT_REDUCE); }
+  int n_iter() const { return (int)((A.cols / W + wg - 1) / wg); }   // chunks of a row per thread
 
   void schedule() {
     const int n = (int)A.nodes.size();
@@ -1510,6 +1512,7 @@ struct Stream {
       for (int j = 0; j < x.nop; ++j)
         if (x.o[j].kind == OP_NODE || x.o[j].kind == OP_ROWB) r = std::max(r, ready[idx_of[x.o[j].index]]);
       if (is_red(x)) { phase[i] = r; ready[i] = r + 1; last = std::max(last, r); }
+      else if (is_col(x)) { phase[i] = r; ready[i] = r; last = std::max(last, r); }    // accumulated in the pass that has its operand
       else {
         ready[i] = r;
         if (x.cls == CLS_FULL && x.out_ord >= 0) last = std::max(last, r);
@@ -1526,7 +1529,7 @@ struct Stream {
     targets->assign(n_loops, {});
     for (int i = 0; i < n; ++i) {
       const RNode& x = A.nodes[i];
-      if (is_red(x)) (*targets)[phase[i]].push_back(i);
+      if (is_red(x) || is_col(x)) (*targets)[phase[i]].push_back(i);
       else if (x.cls == CLS_FULL && x.out_ord >= 0) (*targets)[ready[i]].push_back(i);
     }
     first_use.assign(A.views.size(), -1);
@@ -1547,7 +1550,7 @@ struct Stream {
         if (!seen[k]) { seen[k] = 1; stack.push_back(k); }
       };
       for (int t : (*targets)[p]) {
-        if (is_red(A.nodes[t])) {
+        if (is_red(A.nodes[t]) || is_col(A.nodes[t])) {
           use_full(A.nodes[t].o[0]);
           for (int v : A.nodes[t].dot_full) use_view(v);
         } else if (!seen[t]) { seen[t] = 1; stack.push_back(t); }
@@ -1575,7 +1578,7 @@ struct Stream {
     const int n = (int)A.nodes.size(), nv = (int)A.views.size();
     std::vector<int> order(n);
     for (int i = 0; i < n; ++i) order[i] = i;
-    auto time_of = [&](int i) { return is_red(A.nodes[i]) ? phase[i] : ready[i]; };
+    auto time_of = [&](int i) { return is_red(A.nodes[i]) || is_col(A.nodes[i]) ? phase[i] : ready[i]; };
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return time_of(a) < time_of(b); });
     std::vector<int> pos(n);
     for (int k = 0; k < n; ++k) pos[order[k]] = nv + k;
@@ -1702,6 +1705,17 @@ struct Stream {
     e.line("  constexpr int W = %d, NVEC = %lld, WG = %d, T = %d;", W, (long long)(A.cols / W), wg, T);
     if (lds_floats > 0) e.line("  __shared__ float rowbuf[%lld];", (long long)lds_floats);
     if (n_red > 0) e.line("  __shared__ float exch[%d][T];", n_red);
+    const bool cols_red = A.n_col > 0;
+    if (cols_red) {
+      // Reductions over the rows: a thread works on the same chunks of every row (chunk threadIdx.x + it * WG),
+      // so it keeps a double-precision running value per element of its chunks across the row loop, in
+      // registers; the loops over a row are unrolled so that the chunk number is a constant.
+      e.line("  constexpr int NIT = %d;", n_iter());
+      for (const RNode& x : A.nodes) if (is_col(x)) {
+        e.line("  double ca%d[NIT][W];", x.id);
+        e.line("  UNROLL for (int it = 0; it < NIT; ++it) UNROLL for (int j = 0; j < W; ++j) ca%d[it][j] = %s;", x.id, x.op == FS_REDUCE_MAX ? "-__builtin_inf()" : "0.0");
+      }
+    }
     e.line("  for (long long row = blockIdx.x; row < %lldll; row += gridDim.x) {", (long long)A.rows);
     if (coords) {
       e.line("    unsigned long long rr = (unsigned long long)row;");
@@ -1732,9 +1746,16 @@ struct Stream {
     for (int p = 0; p < n_loops; ++p) {
       for (int t : targets[p]) if (is_red(A.nodes[t]))
         e.line("    float r%d = %s;", A.nodes[t].id, A.nodes[t].op == FS_REDUCE_MAX ? "-__builtin_inff()" : "0.0f");
-      e.line("    for (int c = threadIdx.x; c < NVEC; c += WG) {      // pass %d", p);
-      e.line("      const int col = c * W;");
-      e.line("      {");
+      if (cols_red) {
+        e.line("    UNROLL for (int it = 0; it < NIT; ++it) {      // pass %d", p);
+        e.line("      const int c = (int)threadIdx.x + it * WG;");
+        e.line("      const int col = c * W;");
+        e.line("      if (c < NVEC) {");
+      } else {
+        e.line("    for (int c = threadIdx.x; c < NVEC; c += WG) {      // pass %d", p);
+        e.line("      const int col = c * W;");
+        e.line("      {");
+      }
       std::vector<char> have_node(n, 0), have_view(nv, 0);
       std::function<void(int)> need_view = [&](int q) {
         if (splat[q] || have_view[q]) return;
@@ -1780,11 +1801,18 @@ struct Stream {
       // take over the buffer of the value it was computed from
       for (int t : targets[p]) {
         const RNode& x = A.nodes[t];
-        if (is_red(x)) {
+        if (is_red(x) || is_col(x)) {
           if (x.o[0].kind == OP_VIEW) need_view(x.o[0].index);
           else if (x.o[0].kind == OP_NODE) need_node(idx_of[x.o[0].index]);
           for (int v : x.dot_full) need_view(v);
         } else need_node(t);
+      }
+      for (int t : targets[p]) {
+        const RNode& x = A.nodes[t];
+        if (!is_col(x)) continue;
+        const std::string v = opnd(x.o[0], CLS_FULL);
+        if (x.op == FS_REDUCE_MAX) e.line("        UNROLL for (int j = 0; j < W; ++j) ca%d[it][j] = fmax(ca%d[it][j], (double)%s);", x.id, x.id, v.c_str());
+        else e.line("        UNROLL for (int j = 0; j < W; ++j) ca%d[it][j] += (double)%s;", x.id, v.c_str());
       }
       if (cached) for (int q = 0; q < nv; ++q) if (cut_view[q] && first_use[q] == p) need_view(q);
       for (int t : targets[p]) {
@@ -1803,7 +1831,7 @@ struct Stream {
       }
       for (int t : targets[p]) {
         const RNode& x = A.nodes[t];
-        if (!is_red(x) && x.out_ord >= 0) store_global(x);
+        if (!is_red(x) && !is_col(x) && x.out_ord >= 0) store_global(x);
       }
       e.line("      }");
       e.line("    }");
@@ -1834,6 +1862,19 @@ struct Stream {
     }
     if (n_red > 0 && T > 1) e.line("    __syncthreads();      // the exchange slots are reused by the next row");
     e.line("  }");
+    if (cols_red) {
+      // every thread's columns are its own in the workgroup: one partial row per workgroup and reduction,
+      // straight from the registers (a second kernel adds the partial rows)
+      e.line("  double* ws = static_cast<double*>(a.ws);");
+      int ci = 0;
+      for (const RNode& x : A.nodes) if (is_col(x)) {
+        e.line("  UNROLL for (int it = 0; it < NIT; ++it) {");
+        e.line("    const int c = (int)threadIdx.x + it * WG;");
+        e.line("    if (c < NVEC) { UNROLL for (int j = 0; j < W; ++j) ws[((long long)%d * gridDim.x + blockIdx.x) * %lldll + c * W + j] = ca%d[it][j]; }", ci, (long long)A.cols, x.id);
+        e.line("  }");
+        ++ci;
+      }
+    }
     e.line("}");
     uint64_t h = 1469598103934665603ull;
     for (unsigned char c : e.s) { h ^= c; h *= 1099511628211ull; }
@@ -1982,12 +2023,32 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
     *status = FS_OK;
     return true;
   }
-  if (!want_stream && (opt.rows_per_wave || gerr.find("row longer") == std::string::npos)) { *err = gerr; return false; }
-  if (A.n_col > 0) { *err = "generated row schedule: column reductions over rows longer than the register templates hold"; return false; }
+  const bool too_long = gerr.find("row longer") != std::string::npos || gerr.find("running sums to stay in registers") != std::string::npos;
+  if (!want_stream && (opt.rows_per_wave || !too_long)) { *err = gerr; return false; }
+  if (A.mma_in >= 0) { *err = gerr.empty() ? "generated row schedule: dots on the matrix unit have no streamed form" : gerr; return false; }
+  if (A.n_col > 0 && A.seg_rows > 0) { *err = "generated row schedule: column reductions per run of rows over rows longer than the register templates hold"; return false; }
 
   // the row is streamed in passes by one workgroup
   Stream st(A);
-  if (!st.geometry(opt.wg_size, err)) return false;
+  if (A.n_col > 0) {
+    // Running values of the column reductions: two registers each, beside about 48 for the rest of the kernel.  A
+    // workgroup of 1024 threads has 128 registers per thread, one of 512 has 256, one of 256 has 512: the largest
+    // workgroup whose threads can hold their share (rounded up to whole passes) is taken.
+    const int sizes[3] = {1024, 512, 256};
+    bool fits = false;
+    for (int k = 0; k < 3 && !fits; ++k) {
+      if (opt.wg_size && k > 0) break;
+      if (!st.geometry(opt.wg_size ? opt.wg_size : sizes[k], err)) return false;
+      const int64_t per_thread = (int64_t)st.n_iter() * st.W * A.n_col;
+      fits = per_thread <= (st.wg > 512 ? 40 : st.wg > 256 ? 104 : 232);
+    }
+    if (!fits) {
+      *err = "generated row schedule: column reductions over rows too long for their running values to stay in registers";
+      return false;
+    }
+  } else if (!st.geometry(opt.wg_size, err)) {
+    return false;
+  }
   st.schedule();
   std::vector<std::vector<int>> targets;
   const int64_t kLdsLimit = 160 * 1024 - 512;
@@ -2023,6 +2084,21 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
   int64_t grid = A.rows;
   if (opt.grid > 0 && opt.grid < grid) grid = opt.grid;
   if (grid > (1 << 22)) grid = 1 << 22;
+  if (A.n_col > 0) {
+    // a fixed grid walks the rows: workgroups that fill 2048 threads per CU, one partial row each
+    const int64_t want = opt.grid > 0 ? opt.grid : 256 * (2048 / st.wg);
+    if (grid > want) grid = want;
+    for (const RNode& n : A.nodes) if (n.cls == CLS_COL) {
+      l.col_out[l.n_col] = n.out_ord;
+      l.col_dtype[l.n_col] = n.out_dtype;
+      l.col_is_max[l.n_col] = n.op == FS_REDUCE_MAX ? 1 : 0;
+      ++l.n_col;
+    }
+    l.persistent = true;
+    if (grid < 1) grid = 1;
+    l.workspace_bytes = (int64_t)A.n_col * grid * A.cols * 8;
+    l.n_kernels = 2;
+  }
   l.grid = (int)(grid < 1 ? 1 : grid);
   *out = l;
   *status = FS_OK;
@@ -2032,8 +2108,10 @@ bool row_gen_plan(const Graph& g, const LaunchOpts& opt, RowGenLaunch* out, int*
 std::string row_gen_describe(const RowGenLaunch& l) {
   char buf[720];
   if (l.streamed) {
-    snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d] streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
-             l.n_reduce, l.n_ops - l.n_reduce, l.W, l.passes, l.row_buffers, l.buffers_shared,
+    char cols[96] = "";
+    if (l.n_col > 0) snprintf(cols, sizeof cols, " + column reduce x%d[GRID-THREAD,CTA] (%d partial rows, then a combine kernel)", l.n_col, l.grid);
+    snprintf(buf, sizeof buf, "reduce x%d[GRID,CTA-S] + elementwise x%d[GRID,CTA-THREAD_%d]%s streamed in %d passes, %d row buffers in LDS (%d taken over from dominated values)%s (generated kernel %s, %zu bytes of code); cta_num=%d, cta_size=%d, lds=%lld",
+             l.n_reduce, l.n_ops - l.n_reduce - l.n_col, l.W, cols, l.passes, l.row_buffers, l.buffers_shared,
              l.passes > 1 && !l.inputs_cached ? ", inputs re-read per pass" : "",
              l.kernel_name.c_str(), l.code_object.size(), l.grid, l.wg, (long long)l.lds_bytes);
     return buf;

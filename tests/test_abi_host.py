@@ -135,8 +135,18 @@ def test_unsupported_groups_return_unsupported_not_crash():
     with Plan(graphs.layernorm_bwd(64, 8192)) as p:
         assert p.info()["schedule"] == "row_col" and "CTA-S" in p.describe() and "cta_size=1024" in p.describe()
         assert p.info()["workspace_bytes"] == 2 * 4 * 8192 * 8          # 16 rows per workgroup: 4 partial rows
-    msg = _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 16384))
-    assert "column reductions" in msg
+    # beyond the register templates the streamed template keeps the column sums as running values per thread
+    with Plan(graphs.layernorm_bwd(8, 16384)) as p:
+        assert p.info()["schedule"] == "row_col" and "streamed" in p.describe() and "column reduce x2" in p.describe()
+        assert p.info()["n_kernels"] == 2 and p.info()["workspace_bytes"] == 2 * 8 * 16384 * 8     # one partial row per workgroup (8 rows: 8 workgroups)
+    msg = _expect(binding.FS_ERR_UNSUPPORTED, graphs.layernorm_bwd(8, 32768))
+    assert "column reductions" in msg and "registers" in msg
+    # a reduction over the leading dim that keeps the inner dims is a column reduction of the same memory read as a matrix
+    g = Graph()
+    x = g.parameter("x", "f32", (4, 8, 64))
+    g.output(g.reduce_sum(g.exp(x), 0))
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "row_col" and p.info()["n_kernels"] == 2
     # fp32 attention has no MFMA path
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 64, 64, "f32"))
     _expect(binding.FS_ERR_UNSUPPORTED, graphs.causal_attention(2, 256, 64))

@@ -273,6 +273,50 @@ def test_random_programs_are_cut_into_valid_groups(seed):
     assert len(fp.groups) <= max(2, (2 * owned) // 3)                            # it does fuse
 
 
+def test_measured_scores_replace_the_models_and_the_selection_follows():
+    """Section 4.3's hybrid policy: a pattern the caller has run carries the time it was measured to save; the
+    selection is the brute-force optimum over the candidates with those figures in place of the model's."""
+    ops = graphs.encoder_tail(4096, 1024, 64, 128)
+    base = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE, explore_budget=-1)
+    usable = [p for p in base.patterns if p["score_us"] >= 0]
+    assert len(usable) >= 3 and all("group_ops" in p and not p["measured"] for p in usable)
+    for p in usable:      # a candidate's op list plans on its own, and stands for the same ops
+        assert len(p["output_of"]) >= 1 and set(p["output_of"]) <= set(p["ops"])
+    with Plan(usable[0]["group_ops"]) as plan:
+        assert plan.info()["schedule"] != "per_op"
+    assert all("group_ops" not in p for p in base.patterns if p["score_us"] < 0)
+    chosen = [p for p in base.patterns if p["chosen"]]
+    loser = max(chosen, key=lambda p: p["score_us"])
+    others = [p for p in usable if not p["chosen"]]
+    winner = others[0]
+    # the best chosen pattern was measured to lose, one the model passed over to win big; one entry says nothing
+    quiet = next(p for p in usable if p is not loser and p is not winner)
+    extra = [loser["ops"], list(reversed(winner["ops"])), quiet["ops"]]
+    fp = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE, explore_budget=-1, extra_patterns=extra, extra_scores=[-4.0, 1e4, None])
+    by_ops = {tuple(p["ops"]): p for p in fp.patterns}
+    assert len(fp.patterns) == len(base.patterns)                      # the same candidates, not new ones
+    lo, wi, silent = by_ops[tuple(loser["ops"])], by_ops[tuple(winner["ops"])], by_ops[tuple(quiet["ops"])]
+    assert lo["measured"] and lo["score_us"] == -4.0 and not lo["chosen"]
+    assert wi["measured"] and wi["score_us"] == 1e4 and wi["chosen"]
+    assert not silent["measured"] and silent["score_us"] == pytest.approx(quiet["score_us"])
+    for p in fp.patterns:
+        if not p["measured"] and p["score_us"] >= 0:
+            assert p["score_us"] == pytest.approx(of.score(ops, p["ops"], TABLE, PHI), rel=1e-9)
+    cands = [p for p in fp.patterns if p["score_us"] >= 0]
+    assert fp.total_score_us == pytest.approx(sum(p["score_us"] for p in cands if p["chosen"]))
+    if len(cands) <= 16:
+        best, _ = of.best_selection(ops, [p["ops"] for p in cands], [p["score_us"] for p in cands])
+        assert fp.total_score_us == pytest.approx(best)
+    # a measurement for a pattern no kernel can be built for changes nothing
+    bad = next((p for p in base.patterns if p["score_us"] < 0), None)
+    if bad is not None:
+        fp2 = FusionPlan(ops, launch_us=PHI, bandwidth=TABLE, explore_budget=-1, extra_patterns=[bad["ops"]], extra_scores=[50.0])
+        again = {tuple(p["ops"]): p for p in fp2.patterns}[tuple(bad["ops"])]
+        assert again["score_us"] < 0 and not again["measured"] and not again["chosen"]
+    with pytest.raises(ValueError):
+        FusionPlan(ops, extra_patterns=[loser["ops"]], extra_scores=[1.0, 2.0])
+
+
 def test_planner_rejects_bad_input():
     ops = graphs.log_softmax((64, 64))
     with pytest.raises(FsError) as e:

@@ -265,6 +265,21 @@ def attention_block(batch, sq, sk, dim, dtype="f16", scale=None, causal=False, f
     return g.ops
 
 
+def sigmoid_attention(batch, sq, sk, kc, dim, dtype="bf16"):
+    """A dot -> elementwise -> dot group that is no softmax attention: weights logistic(q k^T / sqrt(kc)), not
+    normalised, returned as a second (fp32) output beside o = weights v.  The hand-written attention recogniser
+    refuses it; the generated block-composed kernel runs both dots on the matrix unit."""
+    g = Graph()
+    q = g.parameter("q", dtype, (batch, sq, kc))
+    k = g.parameter("k", dtype, (batch, sk, kc))
+    v = g.parameter("v", dtype, (batch, sk, dim))
+    w = g.logistic(g.multiply(g.dot(q, k, transpose_b=True, dtype="f32"), g.constant(kc ** -0.5)))
+    o = g.dot(g.convert(w, dtype), v, transpose_b=False, dtype="f32")
+    g.output(g.convert(o, dtype), "o")
+    g.output(w, "weights")
+    return g.ops
+
+
 GELU_K0 = 0.7978845608028654   # sqrt(2/pi)
 GELU_K1 = 0.044715
 

@@ -87,6 +87,14 @@ def attention_block(batch, sq, sk, dim, dtype="f16", mask=None, gate=False, resi
     return out
 
 
+def sigmoid_attention(batch, sq, sk, kc, dim, dtype="bf16", seed_offset=16):
+    """q, k ~ N(0,1); v ~ N(0, 0.25): the weights are not normalised and are rounded to 16 bits before the second
+    dot, so v is drawn small enough for that rounding to stay well inside the 2e-2 bar on outputs near zero."""
+    r = _rng(seed_offset)
+    return [round_to(r.normal(0.0, 1.0, (batch, sq, kc)), dtype), round_to(r.normal(0.0, 1.0, (batch, sk, kc)), dtype),
+            round_to(r.normal(0.0, 0.25, (batch, sk, dim)), dtype)]
+
+
 def bias_gelu_residual_layernorm(rows=16384, cols=1024, dtype="bf16", seed_offset=4):
     r = _rng(seed_offset)
     x = r.normal(0.0, 1.0, (rows, cols))
