@@ -248,6 +248,13 @@ def bench_programs(steps=40, warmup=5):
             fused_us = timed(prog.run_bound)
             res = {"ops": len(ops), "groups": len(prog.fusion.groups), "kernels": prog.n_kernels, "fused_us": fused_us,
                    "group_sizes": [len(g["members"]) for g in prog.fusion.groups]}
+        # the same graph planned again with execution-based scores for the plan's patterns and the best other candidates
+        prog, report = FusedProgram.measured(ops, top=8, trials=10)
+        with prog:
+            prog.bind(ins)
+            res.update(measured_plan_us=timed(prog.run_bound), measured_plan_groups=len(prog.fusion.groups),
+                       measured_plan_kernels=prog.n_kernels, measured_patterns=len(report),
+                       measured_vs_model_us=[[len(o), round(m, 2), round(v, 2)] for o, m, v in report[:6]])
         with Plan(ops, "per_op") as plan:
             outs = [torch.empty(op.shape, dtype=_torch_dt()[op.dtype], device="cuda:0") for op in ops if op.kind == "output"]
             per_op_us = timed(lambda: plan.launch(ins, outs))

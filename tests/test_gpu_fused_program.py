@@ -120,6 +120,42 @@ def test_random_programs_through_the_planner(seed):
         assert n_kernels <= p.info()["n_kernels"]
 
 
+@pytest.mark.parametrize("name", ["encoder_tail", "clip", "random"])
+def test_planning_with_measured_scores(name):
+    """Section 4.3's hybrid policy end to end: the plan's patterns and the best other candidates are built and
+    timed against one kernel per op, the plan is made again with those measurements, and the program that comes
+    out computes what the oracle computes.  The measured patterns carry their measurement, and the selection is
+    the best one over the scores it was given."""
+    import random
+    announce(f"measured planning {name}")
+    if name == "encoder_tail":
+        rows, cols, batch, seq = 300, 1024, 6, 128
+        ops, ins = graphs.encoder_tail(rows, cols, batch, seq), _encoder_inputs(rows, cols, batch, seq)
+    elif name == "clip":
+        shapes = [(300, 256), (1000,), (64, 64), (5, 7, 11)]
+        ops, ins = graphs.clip_by_global_norm(shapes), inputs.normal_tensors(shapes, seed_offset=77)
+    else:
+        rng = random.Random(111)
+        ops, pshapes = graphs.random_program(rng, 600, 1024, n_ops=30)
+        ins = inputs.normal_tensors(pshapes, seed_offset=411)
+    want = interp.run(ops, ins)
+    prog, report = FusedProgram.measured(ops, top=6, trials=5)
+    with prog:
+        assert report and all(len(r) == 3 for r in report)
+        by_ops = {tuple(p["ops"]): p for p in prog.fusion.patterns}
+        for pat_ops, model_us, saved_us in report:
+            p = by_ops[tuple(pat_ops)]
+            assert p["measured"] and p["score_us"] == pytest.approx(saved_us)
+            assert model_us >= 0
+        chosen = [p for p in prog.fusion.patterns if p["chosen"]]
+        assert all(p["score_us"] >= 0 for p in chosen)
+        assert prog.fusion.total_score_us == pytest.approx(sum(p["score_us"] for p in chosen))
+        outs = prog.run(to_device(ops, ins))
+        torch.cuda.synchronize()
+        for a, b in zip(outs, want):
+            assert_close(a.to(torch.float64).cpu().numpy(), b, TOLERANCE["f32"], f"measured planning {name}")
+
+
 def test_fused_program_as_a_captured_graph():
     """The groups of a planned graph recorded into one HIP graph: replayed with new input values and
     eager work in between, every replay against the oracle; and timed against launching group by group."""
