@@ -22,6 +22,7 @@ SOURCES = ["api.cpp", "graph.cpp", "match.cpp", "row_stitch.hip", "row_stitch_f3
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form",      # MFMA results in ordinary registers: no copies to and from the accumulation file
          "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]
 
 

@@ -14,16 +14,21 @@
 // second dot's B-operand layout: O^T = V^T . P^T contracts over keys, and the order of the keys
 // inside a 32-key step is free as long as both operands use the same one, so k-slot 8g+4h+i of
 // step kk is key 32kk+16h+4g+i - the scores of tiles 2kk and 2kk+1 that lane g holds.  P never
-// leaves the registers.  V is the only operand that goes through LDS (the `S` attribute):
-// transposed on the way in, keys stored in that slot order, read back as 16-byte A fragments.
+// leaves the registers.  V goes through LDS as stored (row-major, 16-byte stores) and comes back
+// transposed: the transposing LDS read of gfx950 (ds_read_b64_tr_b16) hands lane c of a 16-lane
+// group column c of a 4 x 16 tile whose four rows the group's lanes address in fours, which is the
+// A fragment of four consecutive keys at head-dim 16dt + c; two reads make the eight k-slots.
 // O^T leaves the accumulators as four consecutive head-dim values per lane and tile (where the
 // epilogue operands are read, 8 bytes each); one row swap between lane pairs makes that eight, so
 // the final store is 16 bytes per lane.
 //
-// Operand fragments of Q and K are read from global memory directly in MFMA layout (8
-// consecutive k-values of row c starting at 8g: one 16-byte load).  With a causal mask of -inf,
-// key tiles right of the diagonal contribute exactly zero and are skipped.  Query and key
-// lengths are independent (each up to 128).
+// Operand fragments of Q are read from global memory directly in MFMA layout (8 consecutive
+// k-values of row c starting at 8g: one 16-byte load).  K is read the same way, every 16-key tile
+// by ONE wavefront, and handed to the others through LDS (row-major, rows padded by 16 bytes so
+// that eight lanes' 16-byte accesses fall on different banks): every wavefront loading every tile
+// it needs keeps the texture path busy with the same lines up to four times over, which costs 0.4 us
+// of 5 on 512 x 64 x 64 x 64.  With a causal mask of -inf, key tiles right of the diagonal contribute
+// exactly zero and are skipped.  Query and key lengths are independent (each up to 128).
 #pragma once
 #include "dev_common.h"
 #include "launchers.h"
@@ -71,52 +76,56 @@ template <class Op> __device__ __forceinline__ float rows_allreduce(float v) {
   return Op::apply(as_f32(r[0]), as_f32(r[1]));
 }
 
-// the value of the lane whose index differs in bit log2(CH): the lane that holds the other key of a
-// pair when CH lanes share one key (CH = 16-byte chunks per row of V)
-template <int CH> __device__ __forceinline__ uint32_t pair_exchange(uint32_t x) {
-  if constexpr (CH == 8) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, false);   // row_ror:8
-  } else {
-    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x & 63) ^ CH) << 2), (int)x);
-  }
-}
-
 // NQ: 16-row tiles of queries (workgroup = NQ wavefronts); NK: 16-key tiles; D: head dim;
 // X: the group has a mask, an epilogue operand or a second output (without any of them those paths
-// are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 0.15 us of 6)
-template <typename T, int NQ, int NK, int D, bool X>
+// are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 0.15 us of 6);
+// E: the lengths are exactly 16 NQ queries and 16 NK keys (NK >= 2), so no row is clamped and no key
+// or query is tested against a length.
+// With two wavefronts per SIMD and a memory phase of one round trip, the kernel's time follows its
+// instruction count: everything that is the same for a whole wavefront (its first query row, the
+// number of key tiles it needs, whether a tile touches the causal diagonal or the end of the keys)
+// is kept in scalar registers and decided by scalar branches, and only tiles that a mask can touch
+// pay for the comparisons.
+template <typename T, int NQ, int NK, int D, bool X, bool E>
 __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) {
   constexpr int KS = D / 32;                 // k-steps of the first dot
   constexpr int NKP = NK < 2 ? 2 : NK;       // key tiles padded to whole 32-key steps
-  constexpr int SP = NKP * 16 + 8;           // padded row length of Vt (halves)
-  constexpr int SWM = (2 * NKP < 8 ? 2 * NKP : 8) - 1;   // granules of a row that the swizzle permutes
+  constexpr int VP = D + (D == 64 ? 8 : 16); // padded row length of V in LDS (halves): the four rows of a
+                                             // transposing read fall on different banks
+  constexpr int KP = D + 8;                  // padded row length of K in LDS (halves)
+  constexpr int KT = (NK + NQ - 1) / NQ;     // key tiles a wavefront loads for the workgroup
   extern __shared__ uint16_t smem[];
-  uint16_t* vt = smem;                       // [D][SP]   V transposed, keys in k-slot order
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint16_t* ksh = smem;                      // [NK * 16][KP]  K as stored
+  uint16_t* vsh = smem + NK * 16 * KP;       // [NKP * 16][VP]  V as stored, keys beyond the last zero
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));    // the same in the whole wavefront
   const int c = lane & 15, g = lane >> 4;
   const int b = blockIdx.x;
-  const int sq = a.sq, sk = a.sk;
+  const int sq = E ? 16 * NQ : a.sq, sk = E ? 16 * NK : a.sk;
   const uint16_t* qb = static_cast<const uint16_t*>(a.q) + (int64_t)b * sq * D;
   const uint16_t* kb = static_cast<const uint16_t*>(a.k) + (int64_t)b * sk * D;
   const uint16_t* vb = static_cast<const uint16_t*>(a.v) + (int64_t)b * sk * D;
   uint16_t* ob = static_cast<uint16_t*>(a.o) + (int64_t)b * sq * D;
   const int q0 = 16 * w;
-  const bool active = q0 < sq;
+  const bool active = E || q0 < sq;
   const int qi = q0 + c;                     // the lane's query row
-  const int qrow = min(qi, sq - 1);
+  const int qrow = E ? qi : min(qi, sq - 1);
   // key tiles this wavefront needs: all that hold a valid key, cut at the diagonal when
   // masked scores are exactly -inf
   int tiles = (sk + 15) / 16;
+  int wg_tiles = tiles;                      // ... and the workgroup as a whole
+  if (a.skip_masked_tiles && NQ < wg_tiles) wg_tiles = NQ;
   if (a.skip_masked_tiles && w + 1 < tiles) tiles = w + 1;
 
-  // ---- every global load of the wavefront is issued before the first use: Q, all K tiles, its
-  // share of V (for the LDS transpose), the mask values of its scores and the epilogue operands.
+  // ---- every global load of the wavefront is issued before the first use: Q, its share of K and
+  // of V (for LDS), the mask values of its scores and the epilogue operands.
   // Loads behind run-time conditions would each wait out a full memory latency in turn; rows
   // beyond the lengths are clamped to the last row and masked later.
   constexpr int CH = D / 8;                  // 16-byte chunks per row
   constexpr int VTOT = NKP * 16 * CH;        // chunks of the (padded) V tile
   constexpr int NV = (VTOT + 64 * NQ - 1) / (64 * NQ);
-  u32x4 qf[KS], kf[NK][KS], vreg[NV];
+  constexpr bool VFULL = VTOT % (64 * NQ) == 0;   // every lane has a chunk in every round
+  u32x4 qf[KS], kf[KT][KS], vreg[NV];
   f32x4 mk[NK];
   u32x2 gt[D / 16], rs[D / 16];
   {
@@ -124,17 +133,18 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
     for (int ks = 0; ks < KS; ++ks)
       qf[ks] = *reinterpret_cast<const u32x4*>(qb + (int64_t)qrow * D + ks * 32 + 8 * g);
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt) {
-      const int krow = min(kt * 16 + c, sk - 1);
+    for (int j = 0; j < KT; ++j) {
+      const int kt = w + j * NQ;               // the same for the whole wavefront
+      const int krow = E ? kt * 16 + c : min(kt * 16 + c, sk - 1);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        if (kt < tiles) kf[kt][ks] = *reinterpret_cast<const u32x4*>(kb + (int64_t)krow * D + ks * 32 + 8 * g);   // same for the whole wavefront
+        if (kt < wg_tiles) kf[j][ks] = *reinterpret_cast<const u32x4*>(kb + (int64_t)krow * D + ks * 32 + 8 * g);
       }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int ci = min((int)threadIdx.x + i * 64 * NQ, VTOT - 1);
-      const int key = min(ci / CH, sk - 1), d0 = (ci % CH) * 8;
+      const int ci = VFULL ? (int)threadIdx.x + i * 64 * NQ : min((int)threadIdx.x + i * 64 * NQ, VTOT - 1);
+      const int key = E ? ci / CH : min(ci / CH, sk - 1), d0 = (ci % CH) * 8;
       vreg[i] = *reinterpret_cast<const u32x4*>(vb + (int64_t)key * D + d0);
     }
     if (X && a.mask) {
@@ -164,46 +174,126 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       for (int dt = 0; dt < D / 16; ++dt) rs[dt] = *reinterpret_cast<const u32x2*>(p + dt * 16);
     }
   }
+  // the loads stay here: left alone, the compiler moves some down to their use, behind the wait for
+  // others - a second memory round trip.  (The empty statement claims to read and write memory.)
+  asm volatile("" ::: "memory");
 
+  // ---- K into LDS as loaded ------------------------------------------------------------------
+#pragma unroll
+  for (int j = 0; j < KT; ++j) {
+    const int kt = w + j * NQ;
+    if (kt < wg_tiles) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<u32x4*>(ksh + (kt * 16 + c) * KP + ks * 32 + 8 * g) = kf[j][ks];
+    }
+  }
+  // ---- V into LDS as loaded (all wavefronts), zero-filling keys >= sk ---------------------------
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int cu = (int)threadIdx.x + i * 64 * NQ;       // chunks beyond the tile exist only where the workgroup has
+    const int ci = VFULL ? cu : min(cu, VTOT - 1);       // more lanes than the tile has chunks
+    const int key = ci / CH, d0 = (ci % CH) * 8;
+    const u32x4 t = (E || key < sk) ? vreg[i] : u32x4{0u, 0u, 0u, 0u};
+    if (VFULL || cu < VTOT) *reinterpret_cast<u32x4*>(vsh + key * VP + d0) = t;
+  }
+  __syncthreads();   // K and V complete
+
+  // the A fragment of the second dot for 32-key step kk and head-dim tile dt: keys 32kk+16h+4g+i at
+  // k-slot 4h+i, head-dim 16dt+c.  Lane c addresses row (c / 4) and columns 4 (c % 4) .. +3 of the tile.
+  const uint16_t* vlane = vsh + (4 * g + (c >> 2)) * VP + 4 * (c & 3);
+  auto vfrag = [&](int kk, int dt) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const uint16_t* p = vlane + 32 * kk * VP + 16 * dt;
+    const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p)));
+    const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 16 * VP)));
+    return u32x4{lo[0], lo[1], hi[0], hi[1]};
+  };
   u32x4 pb[NKP / 2];                         // P^T, the second dot's B fragments
   if (active) {
     // ---- first dot, transposed: tile kt = K_kt(16 x D) . Q^T -----------------------------
+    // (the LDS reads of up to eight fragments first, then their matrix instructions: one latency per
+    // batch, not one per tile)
     f32x4 acc[NK];
+    constexpr int CT = KS >= 8 ? 1 : 8 / KS;     // key tiles per batch
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt) {
-      acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (kt < tiles) {
+    for (int k0 = 0; k0 < NK; k0 += CT) {
+      u32x4 kfr[CT][KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) acc[kt] = Mfma<T>::run(kf[kt][ks], qf[ks], acc[kt]);
+      for (int j = 0; j < CT; ++j) {
+        const int kt = k0 + j;
+        if (kt < NK && kt < tiles) {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            kfr[j][ks] = *reinterpret_cast<const u32x4*>(ksh + (kt * 16 + c) * KP + ks * 32 + 8 * g);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < CT; ++j) {
+        const int kt = k0 + j;
+        if (kt < NK) {
+          acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (kt < tiles) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc[kt] = Mfma<T>::run(kfr[j][ks], qf[ks], acc[kt]);
+          }
+        }
       }
     }
-    // ---- scale, mask, softmax of query row q0+c: the lane holds S[q0+c][16kt+4g+i] ---------
+    // the first 32-key step of V^T for the second dot: its LDS latency passes under the softmax
+    // (where registers allow)
+    constexpr bool PRE = D <= 64;
+    u32x4 vpre[PRE ? D / 16 : 1];
+    if constexpr (PRE) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) vpre[dt] = vfrag(0, dt);
+    }
+    // ---- scale, mask, softmax of query row q0+c: the lane holds S[q0+c][16kt+4g+i].  The scores
+    // are kept in units of log 2 (scale, mask and fill times log2 e), so that the exponential is the
+    // hardware's base-2 one without a multiplication per score. ------------------------------------
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    const float sc2 = a.scale * kLog2e;
+    const float fill2 = a.fill == -INFINITY ? -INFINITY : fmaxf(a.fill * kLog2e, -3.0e38f);
     float mx = -INFINITY;
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt)
+    for (int kt = 0; kt < NK; ++kt) {
+      if (kt < tiles) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = kt * 16 + 4 * g + i;
-        float z = acc[kt][i] * a.scale;
-        if (X && a.mask) z += mk[kt][i];
-        if (a.causal && key > qi) z = a.fill;
-        if (key >= sk || kt >= tiles) z = -INFINITY;
-        acc[kt][i] = z;
-        mx = fmaxf(mx, z);
+        for (int i = 0; i < 4; ++i) {
+          float z = acc[kt][i] * sc2;
+          if (X && a.mask) z = fmaf(mk[kt][i], kLog2e, z);
+          acc[kt][i] = z;
+        }
+        if (a.causal && 16 * kt + 15 > q0) {             // the tile holds keys right of some row's diagonal
+#pragma unroll
+          for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i > qi) acc[kt][i] = fill2;
+        }
+        if (!E && 16 * kt + 15 >= sk) {                  // the tile runs past the last key
+#pragma unroll
+          for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i >= sk) acc[kt][i] = -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, acc[kt][i]);
       }
+    }
     mx = rows_allreduce<MaxOp>(mx);
     float sum = 0.f;
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt)
+    for (int kt = 0; kt < NK; ++kt) {
+      if (kt < tiles) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float e = __expf(acc[kt][i] - mx);
-        acc[kt][i] = e;
-        sum += e;
+        for (int i = 0; i < 4; ++i) {
+          const float e = __builtin_amdgcn_exp2f(acc[kt][i] - mx);
+          acc[kt][i] = e;
+          sum += e;
+        }
+      } else {
+        acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
+    }
     sum = rows_allreduce<SumOp>(sum);
-    const float inv = 1.f / sum;
-    if (X && a.lse && g == 0 && qi < sq) a.lse[(int64_t)b * sq + qi] = mx + logf(sum);
+    const float inv = __builtin_amdgcn_rcpf(sum);
+    if (X && a.lse && g == 0 && qi < sq) a.lse[(int64_t)b * sq + qi] = (mx + __builtin_amdgcn_logf(sum)) * kLn2;
     // P rounded to the dot's dtype, packed in k-slot order: slots 4h+i of step kk <- tile 2kk+h
 #pragma unroll
     for (int kk = 0; kk < NKP / 2; ++kk)
@@ -218,51 +308,20 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
         pb[kk][2 * h] = Mfma<T>::pack(p[0], p[1]);
         pb[kk][2 * h + 1] = Mfma<T>::pack(p[2], p[3]);
       }
-  }
-  // ---- V transposed into LDS (all wavefronts), zero-filling keys >= sk; key 32kk+16h+4g+i of
-  // a 32-key step sits at slot 8g+4h+i.  Two things keep the stores off each other's banks: the
-  // lanes of keys 2n and 2n+1 first trade half of their eight values, so that each stores whole
-  // 32-bit words (both keys of one row) instead of 16-bit halves, and the 16-byte granule of a
-  // slot is xor-ed with the row's group of eight (row / 8), which spreads the eight row groups a
-  // store instruction touches over all banks. ------------------------------------------------
-  uint32_t* vt32 = reinterpret_cast<uint32_t*>(smem);
-#pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int cu = (int)threadIdx.x + i * 64 * NQ;       // chunks beyond the tile exist only where the workgroup has more
-    const int ci = min(cu, VTOT - 1);                    // lanes than the tile has chunks: they take part in the exchange, not in the store
-    const int key = ci / CH, dg = ci % CH, d0 = dg * 8;
-    const int slot = ((key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3)) ^ ((dg & SWM) << 3);
-    const u32x4 t = key < sk ? vreg[i] : u32x4{0u, 0u, 0u, 0u};
-    const bool odd = (key & 1) != 0;
-    // the even key's lane ends up with rows d0 .. d0+3 of both keys, the odd key's with d0+4 .. d0+7
-    const uint32_t rx = pair_exchange<CH>(odd ? t[0] : t[2]), ry = pair_exchange<CH>(odd ? t[1] : t[3]);
-    const uint32_t ex = odd ? rx : t[0], ey = odd ? ry : t[1];     // the even key's two value pairs
-    const uint32_t ox = odd ? t[2] : rx, oy = odd ? t[3] : ry;     // the odd key's
-    if (cu < VTOT) {
-      uint32_t* w0 = vt32 + (((d0 + (odd ? 4 : 0)) * SP + (slot & ~1)) >> 1);
-      w0[0 * (SP / 2)] = (ex & 0xFFFFu) | (ox << 16);
-      w0[1 * (SP / 2)] = (ex >> 16) | (ox & 0xFFFF0000u);
-      w0[2 * (SP / 2)] = (ey & 0xFFFFu) | (oy << 16);
-      w0[3 * (SP / 2)] = (ey >> 16) | (oy & 0xFFFF0000u);
-    }
-  }
-  __syncthreads();   // Vt complete
 
-  if (active) {
     // ---- second dot, transposed: O^T(D x 16) = V^T(D x keys) . P^T ---------------------------
     f32x4 o[D / 16];
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < D / 16; ++dt) {
+      if constexpr (PRE) o[dt] = Mfma<T>::run(vpre[dt], pb[0], f32x4{0.f, 0.f, 0.f, 0.f});
+      else o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     const int ksteps = (tiles + 1) / 2;
 #pragma unroll
-    for (int kk = 0; kk < NKP / 2; ++kk) {
+    for (int kk = PRE ? 1 : 0; kk < NKP / 2; ++kk) {
       if (kk < ksteps) {
 #pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-          const int sw = (2 * dt + (c >> 3)) & SWM;          // the row's granule swizzle, as stored
-          const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + c) * SP + 8 * ((kk * 4 + g) ^ sw));
-          o[dt] = Mfma<T>::run(vf, pb[kk], o[dt]);
-        }
+        for (int dt = 0; dt < D / 16; ++dt) o[dt] = Mfma<T>::run(vfrag(kk, dt), pb[kk], o[dt]);
       }
     }
     // ---- epilogue on the accumulators: the lane holds O[q0+c][16dt+4g+i], i < 4 -----------------
@@ -291,22 +350,44 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       // odd rows of the first operand trade places with even rows of the second
       const auto r0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
       const auto r1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
-      if (qi < sq) *reinterpret_cast<u32x4*>(orow + dp * 32) = u32x4{r0[0], r1[0], r0[1], r1[1]};
+      if (E || qi < sq) *reinterpret_cast<u32x4*>(orow + dp * 32) = u32x4{r0[0], r1[0], r0[1], r1[1]};
     }
   }
 }
 
 inline int64_t attn_lds_bytes(int NK, int D) {
   const int NKP = NK < 2 ? 2 : NK;
-  const int SP = NKP * 16 + 8;
-  return 2 * (int64_t)D * SP;
+  const int VP = D + (D == 64 ? 8 : 16);
+  return 2 * ((int64_t)NKP * 16 * VP + (int64_t)NK * 16 * (D + 8));
 }
 
 template <typename T, int NQ, int NK, int D>
 hipError_t attn_launch_one(const AttnArgs& a, hipStream_t s) {
   const bool extras = a.mask || a.gate || a.res || a.lse;
-  if (extras) hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, true>), dim3(a.batch), dim3(64 * NQ), (size_t)attn_lds_bytes(NK, D), s, a);
-  else hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, false>), dim3(a.batch), dim3(64 * NQ), (size_t)attn_lds_bytes(NK, D), s, a);
+  const bool exact = NK >= 2 && a.sq == 16 * NQ && a.sk == 16 * NK;
+  const dim3 grid(a.batch), wg(64 * NQ);
+  const size_t lds = (size_t)attn_lds_bytes(NK, D);
+  if (lds > 64 * 1024) {     // more dynamic LDS than a kernel may use unasked
+    const void* f = extras ? reinterpret_cast<const void*>(attn_stitch_kernel<T, NQ, NK, D, true, false>)
+                           : reinterpret_cast<const void*>(attn_stitch_kernel<T, NQ, NK, D, false, false>);
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    if constexpr (NK >= 2) {
+      const void* fe = extras ? reinterpret_cast<const void*>(attn_stitch_kernel<T, NQ, NK, D, true, true>)
+                              : reinterpret_cast<const void*>(attn_stitch_kernel<T, NQ, NK, D, false, true>);
+      const hipError_t e2 = hipFuncSetAttribute(fe, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e2 != hipSuccess) return e2;
+    }
+  }
+  if constexpr (NK >= 2) {
+    if (exact) {
+      if (extras) hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, true, true>), grid, wg, lds, s, a);
+      else hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, false, true>), grid, wg, lds, s, a);
+      return hipGetLastError();
+    }
+  }
+  if (extras) hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, true, false>), grid, wg, lds, s, a);
+  else hipLaunchKernelGGL((attn_stitch_kernel<T, NQ, NK, D, false, false>), grid, wg, lds, s, a);
   return hipGetLastError();
 }
 
