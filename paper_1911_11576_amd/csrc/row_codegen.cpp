@@ -563,8 +563,7 @@ template <class Op, int L> static __device__ __forceinline__ float lanes_allredu
 )SRC";
 
 // what the block-composed template around matrix-unit dots adds: the MFMA wrappers (fp32 accumulate),
-// the all-reduce over the four lanes that share an accumulator row, the lane-pair exchange of the
-// transposing LDS stores
+// the all-reduce over the four lanes that share an accumulator row, the transposing LDS read
 const char* kMmaPreamble = R"SRC(
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -585,13 +584,14 @@ template <class Op> static __device__ __forceinline__ float rows_allreduce(float
   lo = r[0]; hi = r[1];
   return Op::apply(bits_f32(lo), bits_f32(hi));
 }
-// the value of the lane whose index differs in bit log2(CH)
-template <int CH> static __device__ __forceinline__ unsigned pair_exchange(unsigned x) {
-  if constexpr (CH == 8) {
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, false);   // row_ror:8
-  } else {
-    return (unsigned)__builtin_amdgcn_ds_bpermute((int)(((threadIdx.x & 63) ^ CH) << 2), (int)x);
-  }
+// eight 16-bit values read through the transposing LDS read of gfx950, twice four: lane c of a 16-lane group
+// receives column c of the 4 x 16 tile whose rows the group's lanes address in fours
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+static __device__ __forceinline__ u32x4 lds_read_transposed(const unsigned short* p, int second) {
+  const u32x2 lo = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p)));
+  const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + second)));
+  return u32x4{lo[0], lo[1], hi[0], hi[1]};
 }
 )SRC";
 
@@ -745,7 +745,8 @@ struct Gen {
   // second operand transposed through LDS, in a buffer placed by the shared-memory planner.
   bool mma = false;
   int NQ = 1;                 // wavefronts = 16-row tiles of the tile's rows
-  int64_t mma_lds_bytes = 0, mma_vt_offset = 0;
+  int64_t mma_lds_bytes = 0, mma_vt_offset = 0, mma_k_offset = 0;
+  int mma_vp = 0, mma_kp = 0;              // padded row lengths (16-bit elements) of the two operands in LDS
   static int pow2_tiles(int64_t len) {
     const int need = (int)((len + 15) / 16);
     return need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
@@ -762,7 +763,8 @@ struct Gen {
     wg = 64 * NQ;
     if (A.mma_out >= 0) {
       // the LDS hand-off of the consuming dot (its second operand, transposed), placed by Algorithm 4
-      const int NKP = K < 2 ? 2 : K, SP = NKP * 16 + 8;
+      const int NKP = K < 2 ? 2 : K;
+      mma_vp = padded_row((int)A.mma_d, 8);
       const int n = (int)A.nodes.size();
       SharedPlanInput in;
       in.operands.resize(n);
@@ -776,13 +778,33 @@ struct Gen {
         for (int j = 0; j < x.nop; ++j)
           if (x.o[j].kind == OP_NODE || x.o[j].kind == OP_ROWB) in.operands[i].push_back(idx_of[x.o[j].index]);
         if (x.out_ord >= 0) in.is_output[i] = 1;
-        if (x.op == ROP_DOT_MMA_OUT) { in.req_bytes[i] = 2 * A.mma_d * SP; at = i; }
+        if (x.op == ROP_DOT_MMA_OUT) { in.req_bytes[i] = 2 * (int64_t)NKP * 16 * mma_vp; at = i; }
       }
       const SharedPlanResult r = shared_plan(in);
       mma_vt_offset = r.offset[at];
       mma_lds_bytes = r.total_bytes;
     }
+    // the producing dot's second operand, shared by the workgroup's wavefronts: rows of whole 32-steps plus 8
+    mma_kp = ((int)((A.mma_k + 31) / 32)) * 32 + 8;
+    mma_k_offset = (mma_lds_bytes + 15) / 16 * 16;
+    mma_lds_bytes = mma_k_offset + 2 * (int64_t)K * 16 * mma_kp;
     return true;
+  }
+  // Row length in 16-bit elements of an LDS tile that is read four rows at a time, `piece` bytes per lane and four
+  // lanes per row (the transposing read): the shortest padding that is a multiple of 16 bytes and puts the four
+  // rows of one access on different banks (64 banks of 4 bytes).
+  static int padded_row(int width, int piece) {
+    for (int pad = 8; pad <= 64; pad += 8) {
+      const int banks = (width + pad) / 2, span = 4 * piece / 4;
+      bool clash = false;
+      for (int a = 0; a < 4 && !clash; ++a)
+        for (int b = a + 1; b < 4 && !clash; ++b) {
+          const int d = (((b - a) * banks) % 64 + 64) % 64;
+          if (d < span || 64 - d < span) clash = true;
+        }
+      if (!clash) return width + pad;
+    }
+    return width + 8;
   }
 
   bool geometry(std::string* err) {
@@ -852,8 +874,7 @@ struct Gen {
   // of the kernel, long before the LDS transpose needs them.
   void emit_mma_v_loads() {
     const int D2 = (int)A.mma_d, NKP = K < 2 ? 2 : K, CH = D2 / 8, VTOT = NKP * 16 * CH, NV = (VTOT + wg - 1) / wg;
-    e.line("  constexpr int D2 = %d, NKP = %d, CH = %d, VTOT = %d, NV = %d, SP = %d, SWM = %d;", D2, NKP, CH, VTOT, NV, NKP * 16 + 8,
-           (2 * NKP < 8 ? 2 * NKP : 8) - 1);
+    e.line("  constexpr int D2 = %d, NKP = %d, CH = %d, VTOT = %d, NV = %d, VP = %d;", D2, NKP, CH, VTOT, NV, mma_vp);
     e.line("  u32x4 vreg[NV];");
     e.line("  {");
     e.line("    const unsigned short* vb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * D2;", A.mma_vv);
@@ -866,39 +887,64 @@ struct Gen {
   }
 
   // The producing dot, transposed: tile k = b_k(16 x KC) . a^T, so the lane holds t[k][j] = row `row`,
-  // column 16k + 4*lane + j.  Operand fragments come straight from global memory in MFMA layout (8
-  // consecutive contraction indices of one row: one 16-byte load); steps beyond KC are zero on both sides.
+  // column 16k + 4*lane + j.  Fragments of a come straight from global memory in MFMA layout (8 consecutive
+  // contraction indices of one row: one 16-byte load).  Every 16-row tile of b is loaded that way by ONE
+  // wavefront and handed to the others through LDS; steps beyond KC are zero on both sides.  The consuming
+  // dot's second operand goes to LDS as stored behind the same barrier.
   void emit_mma_in(const RNode& n) {
-    const int KC = (int)A.mma_k, KS = (KC + 31) / 32;
+    const int KC = (int)A.mma_k, KS = (KC + 31) / 32, KT = (K + NQ - 1) / NQ;
     const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
     e.line("  float t%d[K][W];", n.id);
     e.line("  {");
-    e.line("    constexpr int KC = %d, KS = %d;", KC, KS);
+    e.line("    constexpr int KC = %d, KS = %d, KT = %d, KP = %d;", KC, KS, KT, mma_kp);
+    e.line("    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));");
     e.line("    const unsigned short* pa = static_cast<const unsigned short*>(a.in[%d]) + row * KC;", A.mma_va);
     e.line("    const unsigned short* pb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * KC;", A.mma_vb);
-    e.line("    u32x4 qf[KS], kf[K][KS];");
+    e.line("    unsigned short* ksh = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [K * 16][KP]", (long long)mma_k_offset);
+    e.line("    u32x4 qf[KS], kf[KT][KS];");
     e.line("    UNROLL for (int ks = 0; ks < KS; ++ks) {");
     e.line("      const int k0 = ks * 32 + 8 * lane;");
     e.line("      qf[ks] = k0 < KC ? *reinterpret_cast<const u32x4*>(pa + k0) : u32x4{0u, 0u, 0u, 0u};");
     e.line("    }");
-    e.line("    UNROLL for (int k = 0; k < K; ++k) {");
-    e.line("      int nrow = 16 * k + lane16; if (nrow > N - 1) nrow = N - 1;");
+    e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
+    e.line("      const int kt = wv + j * %d;", NQ);
+    e.line("      int nrow = 16 * kt + lane16; if (nrow > N - 1) nrow = N - 1;");
     e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) {");
     e.line("        const int k0 = ks * 32 + 8 * lane;");
-    e.line("        kf[k][ks] = k0 < KC ? *reinterpret_cast<const u32x4*>(pb + (long long)nrow * KC + k0) : u32x4{0u, 0u, 0u, 0u};");
+    e.line("        kf[j][ks] = u32x4{0u, 0u, 0u, 0u};");
+    e.line("        if (kt < K && k0 < KC) kf[j][ks] = *reinterpret_cast<const u32x4*>(pb + (long long)nrow * KC + k0);");
     e.line("      }");
     e.line("    }");
+    e.line("    asm volatile(\"\" ::: \"memory\");     // every request above is issued before the first wait below");
+    e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
+    e.line("      const int kt = wv + j * %d;", NQ);
+    e.line("      if (kt < K) { UNROLL for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<u32x4*>(ksh + (16 * kt + lane16) * KP + ks * 32 + 8 * lane) = kf[j][ks]; }");
+    e.line("    }");
+    if (A.mma_out >= 0) {
+      e.line("    unsigned short* vsh = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [NKP * 16][VP], rows beyond N zero", (long long)mma_vt_offset);
+      e.line("    UNROLL for (int i = 0; i < NV; ++i) {");
+      e.line("      const int cu = (int)threadIdx.x + i * %d;", wg);
+      e.line("      const int ci = cu < VTOT - 1 ? cu : VTOT - 1;");
+      e.line("      const int key = ci / CH;");
+      e.line("      const u32x4 tv = key < N ? vreg[i] : u32x4{0u, 0u, 0u, 0u};");
+      e.line("      if (cu < VTOT) *reinterpret_cast<u32x4*>(vsh + key * VP + (ci %% CH) * 8) = tv;");
+      e.line("    }");
+    }
+    e.line("    __syncthreads();");
     e.line("    UNROLL for (int k = 0; k < K; ++k) {");
+    e.line("      u32x4 kr[KS];");
+    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) kr[ks] = *reinterpret_cast<const u32x4*>(ksh + (16 * k + lane16) * KP + ks * 32 + 8 * lane);");
     e.line("      f32x4 acc = {0.f, 0.f, 0.f, 0.f};");
-    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) acc = %s(kf[k][ks], qf[ks], acc);", mm);
+    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) acc = %s(kr[ks], qf[ks], acc);", mm);
     e.line("      UNROLL for (int j = 0; j < W; ++j) t%d[k][j] = acc[j];", n.id);
     e.line("    }");
     e.line("  }");
   }
 
   // The consuming dot, transposed: O^T(D2 x 16) = V^T(D2 x keys) . P^T.  P is the operand's registers packed
-  // to the dot dtype (keys beyond N are zero), V^T comes from LDS, where it was stored transposed with the
-  // keys of a 32-step in the order the accumulators of the producing dot imply.
+  // to the dot dtype (keys beyond N are zero); V sits in LDS as stored and is read transposed, the keys of a
+  // 32-step in the order the accumulators of the producing dot imply (k-slot 4h+i of lane group g: key
+  // 32kk + 16h + 4g + i).
   void emit_mma_out(const RNode& n) {
     const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
     const char* pk = A.mma_dtype == FS_F16 ? "pack_to_f16" : "pack_to_bf16";
@@ -912,33 +958,11 @@ struct Gen {
     e.line("      pb2[kk][2 * h] = %s(p[0], p[1]);", pk);
     e.line("      pb2[kk][2 * h + 1] = %s(p[2], p[3]);", pk);
     e.line("    }");
-    e.line("    __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
-    e.line("    unsigned short* vt = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [D2][SP]", (long long)mma_vt_offset);
-    e.line("    unsigned* vt32 = reinterpret_cast<unsigned*>(vt);");
-    e.line("    UNROLL for (int i = 0; i < NV; ++i) {");
-    e.line("      const int cu = (int)threadIdx.x + i * %d;", wg);
-    e.line("      const int ci = cu < VTOT - 1 ? cu : VTOT - 1;");
-    e.line("      const int key = ci / CH, dg = ci %% CH, d0 = dg * 8;");
-    e.line("      const int slot = ((key & ~31) | ((key & 12) << 1) | ((key & 16) >> 2) | (key & 3)) ^ ((dg & SWM) << 3);");
-    e.line("      const u32x4 tv = key < N ? vreg[i] : u32x4{0u, 0u, 0u, 0u};");
-    e.line("      const bool odd = (key & 1) != 0;");
-    e.line("      const unsigned rx = pair_exchange<CH>(odd ? tv[0] : tv[2]), ry = pair_exchange<CH>(odd ? tv[1] : tv[3]);");
-    e.line("      const unsigned ex = odd ? rx : tv[0], ey = odd ? ry : tv[1];");
-    e.line("      const unsigned ox = odd ? tv[2] : rx, oy = odd ? tv[3] : ry;");
-    e.line("      if (cu < VTOT) {");
-    e.line("        unsigned* w0 = vt32 + (((d0 + (odd ? 4 : 0)) * SP + (slot & ~1)) >> 1);");
-    e.line("        w0[0 * (SP / 2)] = (ex & 0xFFFFu) | (ox << 16);");
-    e.line("        w0[1 * (SP / 2)] = (ex >> 16) | (ox & 0xFFFF0000u);");
-    e.line("        w0[2 * (SP / 2)] = (ey & 0xFFFFu) | (oy << 16);");
-    e.line("        w0[3 * (SP / 2)] = (ey >> 16) | (oy & 0xFFFF0000u);");
-    e.line("      }");
-    e.line("    }");
-    e.line("    __syncthreads();");
+    e.line("    const unsigned short* vlane = reinterpret_cast<const unsigned short*>(lds_pool + %lld) + (4 * lane + (lane16 >> 2)) * VP + 4 * (lane16 & 3);", (long long)mma_vt_offset);
     e.line("    f32x4 o[D2 / 16];");
     e.line("    UNROLL for (int dt = 0; dt < D2 / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};");
     e.line("    UNROLL for (int kk = 0; kk < NKP / 2; ++kk) UNROLL for (int dt = 0; dt < D2 / 16; ++dt) {");
-    e.line("      const int sw = (2 * dt + (lane16 >> 3)) & SWM;");
-    e.line("      const u32x4 vf = *reinterpret_cast<const u32x4*>(vt + (dt * 16 + lane16) * SP + 8 * ((kk * 4 + lane) ^ sw));");
+    e.line("      const u32x4 vf = lds_read_transposed(vlane + 32 * kk * VP + 16 * dt, 16 * VP);");
     e.line("      o[dt] = %s(vf, pb2[kk], o[dt]);", mm);
     e.line("    }");
     if (n.out_dtype == FS_F32) {
@@ -1042,6 +1066,7 @@ struct Gen {
       e.line("  const bool row_ok = row < %s%s;", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
       e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     }
+    if (mma) e.line("  __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
     if (mma && A.mma_out >= 0) emit_mma_v_loads();
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);

@@ -641,8 +641,9 @@ def test_block_dot_groups_are_generated_or_refused_with_a_reason():
     with Plan(_dot_group()) as p:
         info = p.info()
         assert info["schedule"] == "block_dot" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
-        # V^T of the padded key tiles (64 keys + 8 halves of padding) x 64 rows, placed by the shared-memory planner
-        assert info["lds_bytes"] == 2 * 64 * (4 * 16 + 8)
+        # V (64 keys of 64 + 8 halves), placed by the shared-memory planner, and behind it the first dot's second
+        # operand (64 rows of 64 + 8 halves), which one wavefront per 16 rows loads for all
+        assert info["lds_bytes"] == 2 * 64 * (64 + 8) + 2 * 64 * (64 + 8)
         assert "dot_1" in p.describe() and "dot_2" in p.describe() and "MFMA" in p.describe()
     assert "matrix unit" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group("f32"))            # fp32 dots have no MFMA path
     assert "[B, N, K]" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(transpose_b=False))   # contraction must be contiguous
