@@ -724,10 +724,10 @@ struct Gen {
   bool stage = false;         // full outputs leave through an LDS staging tile (see emit)
   int64_t stage_bytes = 0;
 
-  // Row steps requested ahead in the persistent form: one.  Two (three row buffers per streamed
-  // operand) is what the hand-written LayerNorm-backward kernel uses, where it is worth 5%; in the
-  // generated kernels it measured 1% to 3% slower (config 5's group and the backward tail of a
-  // Transformer block), so it is only there to be measured (FS_ROW_PREFETCH=2).
+  // Row steps requested ahead in the persistent form: one, or two (FS_ROW_PREFETCH=2): two row buffers per
+  // streamed operand, the row loop unrolled twice so that each keeps its registers, and a buffer requested
+  // again - for two steps ahead - as soon as its row has been taken out of it.  (Shifting the buffers down at
+  // the end of an iteration instead makes the iteration wait for the request it has just issued.)
   int force_prefetch = 0;     // 1 or 2: the caller's choice
   int prefetch_depth(int n_prefetched) const {
     (void)n_prefetched;
@@ -998,6 +998,7 @@ struct Gen {
   void emit(std::string* kernel_name) {
     const int rank = A.rank, nrow = rank - 1;
     std::string advance;        // persistent form: hand the prefetched vectors to the next iteration
+    bool two_phase = false;     // persistent form with two row steps requested ahead
     e.s = ew_preamble();
     e.s += kReducePreamble;
     if (mma) e.s += kMmaPreamble;
@@ -1063,9 +1064,17 @@ struct Gen {
       } else {
         e.line("  const int rl = threadIdx.x / L;");
         e.line("  const long long first_row = (long long)blockIdx.x * RPW, row_step = (long long)gridDim.x * RPW;");
-        e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += row_step) {", (long long)A.rows);
+        if (prefetch_depth(0) == 2) {
+          // two row steps per trip, unrolled, so that each of the two row buffers keeps its registers
+          e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += 2 * row_step) {", (long long)A.rows);
+          e.line("  UNROLL for (int ph = 0; ph < 2; ++ph) {");
+          two_phase = true;
+        } else {
+          e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += row_step) {", (long long)A.rows);
+        }
       }
-      e.line("  long long row = row0 + rl;");
+      if (two_phase) e.line("  long long row = row0 + ph * row_step + rl;");
+      else e.line("  long long row = row0 + rl;");
     }
     char row_hi[32], row_last[40], row_any[32];     // end of the rows of this workgroup's loop, its last row, a row that is surely valid
     if (persistent && A.seg_rows > 0) {
@@ -1137,17 +1146,21 @@ struct Gen {
         const char* cv = v.dtype == FS_F32 ? "" : v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
         bool dummy = false;
         const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
-        snprintf(buf, sizeof buf, "  float sraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp.c_str());
-        pro += buf;
         if (depth == 2) {
-          snprintf(buf, sizeof buf, "  float sraw%zub = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp2.c_str());
+          // two buffers, each re-requested (for two steps ahead) right after its value was taken
+          snprintf(buf, sizeof buf, "  float sraw%zux[2];\n  sraw%zux[0] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n  sraw%zux[1] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n",
+                   q, q, cv, ty, q, offp.c_str(), q, cv, ty, q, offp2.c_str());
           pro += buf;
+          snprintf(buf, sizeof buf, "  const float sraw%zu = sraw%zux[ph];\n  sraw%zux[ph] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, q, q, cv, ty, q, offn.c_str());
+          nxt += buf;
+        } else {
+          snprintf(buf, sizeof buf, "  float sraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp.c_str());
+          pro += buf;
+          snprintf(buf, sizeof buf, "  const float nsraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offn.c_str());
+          nxt += buf;
+          snprintf(buf, sizeof buf, "  sraw%zu = nsraw%zu;\n", q, q);
+          adv += buf;
         }
-        snprintf(buf, sizeof buf, "  const float nsraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offn.c_str());
-        nxt += buf;
-        if (depth == 2) snprintf(buf, sizeof buf, "  sraw%zu = sraw%zub; sraw%zub = nsraw%zu;\n", q, q, q, q);
-        else snprintf(buf, sizeof buf, "  sraw%zu = nsraw%zu;\n", q, q);
-        adv += buf;
       }
       for (size_t q = 0; q < A.views.size(); ++q) if (prefetched[q]) {
         const RView& v = A.views[q];
@@ -1155,20 +1168,26 @@ struct Gen {
         const char* rt = raw_type(v);
         bool dummy = false;
         const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
-        snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
-                 rt, q, q, rt, ty, q, offp.c_str());
-        pro += buf;
         if (depth == 2) {
-          snprintf(buf, sizeof buf, "  %s raw%zub[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zub[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
-                   rt, q, q, rt, ty, q, offp2.c_str());
+          snprintf(buf, sizeof buf, "  %s raw%zux[2][K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zux[0][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   rt, q, q, rt, ty, q, offp.c_str());
           pro += buf;
+          snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zux[1][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   q, rt, ty, q, offp2.c_str());
+          pro += buf;
+          snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) { raw%zu[k] = raw%zux[ph][k]; raw%zux[ph][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k])); }\n",
+                   rt, q, q, q, q, rt, ty, q, offn.c_str());
+          nxt += buf;
+        } else {
+          snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   rt, q, q, rt, ty, q, offp.c_str());
+          pro += buf;
+          snprintf(buf, sizeof buf, "  %s nraw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) nraw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   rt, q, q, rt, ty, q, offn.c_str());
+          nxt += buf;
+          snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = nraw%zu[k];\n", q, q);
+          adv += buf;
         }
-        snprintf(buf, sizeof buf, "  %s nraw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) nraw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
-                 rt, q, q, rt, ty, q, offn.c_str());
-        nxt += buf;
-        if (depth == 2) snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) { raw%zu[k] = raw%zub[k]; raw%zub[k] = nraw%zu[k]; }\n", q, q, q, q);
-        else snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = nraw%zu[k];\n", q, q);
-        adv += buf;
       }
       if (!pro.empty()) {
         // the prologue goes before the row loop: find the loop header emitted above
@@ -1181,11 +1200,12 @@ struct Gen {
           head += buf;
         }
         e.s.insert(at, head + pro);
-        e.line("  long long rown = row0 + %d * row_step + rl;", depth);
+        if (two_phase) e.line("  long long rown = row0 + (ph + 2) * row_step + rl;");
+        else e.line("  long long rown = row0 + row_step + rl;");
         e.line("  if (rown >= %s) rown = %s;          // past the end: any valid row (one that is cached by then)", row_hi, row_any);
         e.s += nxt;
         e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
-        advance = adv;
+        advance = adv.empty() ? std::string(" ") : adv;      // (non-empty: the operands are served from the buffers)
       }
     }
     for (size_t q = 0; q < A.views.size(); ++q) {
@@ -1396,6 +1416,7 @@ struct Gen {
       e.s += advance;
       if (T > 1 && A.n_reduce > 0) e.line("  __syncthreads();                             // the exchange slots are written again in the next row");
       e.line("  }");
+      if (two_phase) e.line("  }");
     }
     // a run of rows that one workgroup sums alone: its sums are the results, stored as they are
     const bool direct = A.seg_rows > 0 && (seg_groups == 1 || seg_per_wave);
