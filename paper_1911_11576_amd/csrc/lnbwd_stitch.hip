@@ -70,80 +70,92 @@ void lnbwd_rows_kernel(const LnBwdArgs a) {
     for (int j = 0; j < 4; ++j) { dg[k][j] = 0.0; db[k][j] = 0.0; }
   }
 
+  // gamma has arrived before the first row is requested: a load still pending at the top of the row loop
+  // would put a wait into the loop that, trip after trip, also waits for the rows requested ahead
+  __builtin_amdgcn_s_waitcnt(0);
+
   // All workgroups advance through the rows together, so at any moment the chip streams one
   // compact window of dy, x and dx, as a one-shot grid would.
   const int64_t row_end = a.rows;
   const int64_t row_step = (int64_t)gridDim.x * waves;
   int64_t row = (int64_t)blockIdx.x * waves + wave;
-  u32x4 rdy[PF][K], rx[PF][K];
-  float rmu[PF], rrs[PF];
-#pragma unroll
-  for (int p = 0; p < PF; ++p) {
+  // PF + 1 row buffers that take turns: the loop is unrolled PF + 1 times, step p works on buffer p and
+  // first requests the row PF steps ahead into the buffer the step before it has finished with.  No buffer is
+  // ever copied (a copy of a buffer that was requested only one step ago would wait for it, which is what
+  // shifting the buffers down costs), and every request has PF whole steps to arrive.
+  constexpr int NB = PF + 1;
+  u32x4 rdy[NB][K], rx[NB][K];
+  float rmu[NB], rrs[NB];
+  auto request = [&](int b, int64_t want) {
     // past the end: row 0, which is in cache by then (no extra HBM traffic); its values are never used
-    const int64_t r = row + p * row_step < row_end ? row + p * row_step : 0;
+    const int64_t r = want < row_end ? want : 0;
+    // (loads complete in the order they are issued: the row's mean and rstd, needed first, go first)
+    if constexpr (NEED_X) { rmu[b] = a.mean[r]; rrs[b] = a.rstd[r]; }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      rdy[p][k] = stream_load16(a.dy + r * a.cols + voff[k]);
-      if constexpr (NEED_X) rx[p][k] = stream_load16(a.x + r * a.cols + voff[k]);
+      rdy[b][k] = stream_load16(a.dy + r * a.cols + voff[k]);
+      if constexpr (NEED_X) rx[b][k] = stream_load16(a.x + r * a.cols + voff[k]);
     }
-    if constexpr (NEED_X) { rmu[p] = a.mean[r]; rrs[p] = a.rstd[r]; }
-  }
-  for (; row < row_end; row += row_step) {
+  };
+#pragma unroll
+  for (int p = 0; p < PF; ++p) request(p, row + p * row_step);
+  // one step: request the row PF steps ahead, then the arithmetic of row r out of buffer p
+  auto step = [&](const int p, const int64_t r) {
+    request((p + PF) % NB, r + PF * row_step);
+    __builtin_amdgcn_sched_barrier(0);                    // the requests stay ahead of the arithmetic
     float dy[K][4], xv[K][4];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      Vec<float>::unpack(rdy[0][k], dy[k]);
-      if constexpr (NEED_X) Vec<float>::unpack(rx[0][k], xv[k]);
+      Vec<float>::unpack(rdy[p][k], dy[k]);
+      if constexpr (NEED_X) Vec<float>::unpack(rx[p][k], xv[k]);
     }
-    const float mu = NEED_X ? rmu[0] : 0.f, rs = NEED_X ? rrs[0] : 0.f;
-#pragma unroll
-    for (int p = 0; p + 1 < PF; ++p) {
-#pragma unroll
-      for (int k = 0; k < K; ++k) {
-        rdy[p][k] = rdy[p + 1][k];
-        if constexpr (NEED_X) rx[p][k] = rx[p + 1][k];
-      }
-      if constexpr (NEED_X) { rmu[p] = rmu[p + 1]; rrs[p] = rrs[p + 1]; }
-    }
-    // request the row PF steps ahead, pinned ahead of the arithmetic
-    const int64_t nrow = row + PF * row_step < row_end ? row + PF * row_step : 0;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-      rdy[PF - 1][k] = stream_load16(a.dy + nrow * a.cols + voff[k]);
-      if constexpr (NEED_X) rx[PF - 1][k] = stream_load16(a.x + nrow * a.cols + voff[k]);
-    }
-    if constexpr (NEED_X) { rmu[PF - 1] = a.mean[nrow]; rrs[PF - 1] = a.rstd[nrow]; }
-    __builtin_amdgcn_sched_barrier(0);
-
+    const float rs = NEED_X ? rrs[p] : 0.f, nmurs = NEED_X ? -rmu[p] * rs : 0.f;
     float s1 = 0.f, s2 = 0.f;
-    float g[K][4];
+    constexpr bool KEEP_G = K * (PF + 1) < 12;
+    float g[KEEP_G ? K : 1][4];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float d = vld[k] ? dy[k][j] : 0.f;
-        if constexpr (NEED_X) xv[k][j] = (xv[k][j] - mu) * rs;      // xhat
+        if constexpr (NEED_X) xv[k][j] = fmaf(xv[k][j], rs, nmurs);      // xhat = (x - mu) * rs
         if constexpr (WANT_COL) db[k][j] += (double)d;
         if constexpr (COL == 2) dg[k][j] += (double)(d * xv[k][j]);
         if constexpr (WANT_DX) {
-          g[k][j] = d * gam[k][j];
-          s1 += g[k][j];
-          s2 += g[k][j] * xv[k][j];
+          const float gj = d * gam[k][j];
+          if constexpr (KEEP_G) g[k][j] = gj;
+          s1 += gj;
+          s2 = fmaf(gj, xv[k][j], s2);
         }
       }
     }
     if constexpr (WANT_DX) {
-      const float c1 = group_allreduce<SumOp, 64>(s1) * a.inv_n;
-      const float c2 = group_allreduce<SumOp, 64>(s2) * a.inv_n;
+      // dx = (g - c1 - xhat c2) rs, as two fused multiply-adds per element
+      const float nc1 = -(group_allreduce<SumOp, 64>(s1) * a.inv_n) * rs;
+      const float nc2 = -(group_allreduce<SumOp, 64>(s2) * a.inv_n) * rs;
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         float o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = ((g[k][j] - c1) - xv[k][j] * c2) * rs;
-        if (vld[k]) stream_store16(a.dx + row * a.cols + voff[k], pack16<float>(o));
+        for (int j = 0; j < 4; ++j) {
+          // (with four vectors per lane dy * gamma is multiplied out again rather than kept: sixteen registers
+          // fewer is what keeps three row buffers, the fp64 sums and gamma inside the 256 vector registers)
+          const float gj = KEEP_G ? g[k][j] : (vld[k] ? dy[k][j] : 0.f) * gam[k][j];
+          o[j] = fmaf(xv[k][j], nc2, fmaf(gj, rs, nc1));
+        }
+        if (vld[k]) stream_store16(a.dx + r * a.cols + voff[k], pack16<float>(o));
       }
     }
+  };
+  // whole trips of PF + 1 steps without a branch inside (one path through the loop: the waits on the
+  // requests count exactly), then the last, partial trip
+  for (; row + PF * row_step < row_end; row += NB * row_step) {
+#pragma unroll
+    for (int p = 0; p < NB; ++p) step(p, row + p * row_step);
   }
+#pragma unroll
+  for (int p = 0; p < NB; ++p)
+    if (row + p * row_step < row_end) step(p, row + p * row_step);
 
   if constexpr (WANT_COL) {
     // ---- block composition: every wavefront's sums into its own LDS array, then the arrays

@@ -539,6 +539,8 @@ static __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
 template <int CTRL> static __device__ __forceinline__ float dpp_move(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
 }
+struct std_true { static constexpr bool value = true; };      // compile-time switches handed to generic lambdas
+struct std_false { static constexpr bool value = false; };
 struct SumOp { static __device__ __forceinline__ float apply(float a, float b) { return a + b; } };
 struct MaxOp { static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); } };
 template <class Op, int L> static __device__ __forceinline__ float lanes_allreduce(float v) {
@@ -998,7 +1000,11 @@ struct Gen {
   void emit(std::string* kernel_name) {
     const int rank = A.rank, nrow = rank - 1;
     std::string advance;        // persistent form: hand the prefetched vectors to the next iteration
-    bool two_phase = false;     // persistent form with two row steps requested ahead
+    bool rotating = false;      // persistent form whose row buffers take turns (row loop unrolled over them)
+    int rot_buffers = 2;        // ... how many
+    std::string pro_req;        // ... the requests of the rows the loop starts with
+    std::string deferred_head;  // ... and the text that goes between what is loaded once and the loop
+    std::string loop_anchor = "  for (long long row0 = ";   // the text the row loop starts with: what is loaded once goes before it
     e.s = ew_preamble();
     e.s += kReducePreamble;
     if (mma) e.s += kMmaPreamble;
@@ -1064,17 +1070,19 @@ struct Gen {
       } else {
         e.line("  const int rl = threadIdx.x / L;");
         e.line("  const long long first_row = (long long)blockIdx.x * RPW, row_step = (long long)gridDim.x * RPW;");
-        if (prefetch_depth(0) == 2) {
-          // two row steps per trip, unrolled, so that each of the two row buffers keeps its registers
-          e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += 2 * row_step) {", (long long)A.rows);
-          e.line("  UNROLL for (int ph = 0; ph < 2; ++ph) {");
-          two_phase = true;
+        if (L <= 64) {
+          // One step of the row loop as a function of the row buffer it works on (ph) and of whether every row
+          // of the step exists (ALL): the loop below is unrolled over the buffers, which take turns without
+          // ever being copied, and has a branch-free main part.
+          rotating = true;
+          loop_anchor = "  auto step = [&](auto all_c, const int ph, const long long row0) __attribute__((always_inline)) {";
+          e.line("%s", loop_anchor.c_str());
+          e.line("  constexpr bool ALL = decltype(all_c)::value;");
         } else {
           e.line("  for (long long row0 = first_row; row0 < %lldll; row0 += row_step) {", (long long)A.rows);
         }
       }
-      if (two_phase) e.line("  long long row = row0 + ph * row_step + rl;");
-      else e.line("  long long row = row0 + rl;");
+      e.line("  long long row = row0 + rl;");
     }
     char row_hi[32], row_last[40], row_any[32];     // end of the rows of this workgroup's loop, its last row, a row that is surely valid
     if (persistent && A.seg_rows > 0) {
@@ -1083,7 +1091,7 @@ struct Gen {
       snprintf(row_hi, sizeof row_hi, "%lldll", (long long)A.rows); snprintf(row_last, sizeof row_last, "%lldll", (long long)A.rows - 1); snprintf(row_any, sizeof row_any, "0");
     }
     if (!mma) {
-      e.line("  const bool row_ok = row < %s%s;", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
+      e.line("  const bool row_ok = %srow < %s%s;", rotating ? "ALL || " : "", row_hi, persistent && A.seg_rows > 0 && seg_per_wave ? " && seg_ok" : "");
       e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     }
     if (mma) e.line("  __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
@@ -1131,27 +1139,33 @@ struct Gen {
       }
     }
     if (persistent) {
-      // `depth` row steps are requested ahead of the one being worked on: raw<q> holds the current
-      // step, raw<q>b the one after it (depth 2), nraw<q> the newest request
+      // Rows are requested ahead of the one being worked on.  Rotating form: `depth` steps ahead into
+      // depth + 1 buffers raw<q>x[..] that take turns - step ph works on buffer ph and first requests the row
+      // `depth` steps ahead into the buffer the step before it has finished with; no buffer is ever copied (a
+      // copy of a buffer requested one step ago would wait for it).  Otherwise: one step ahead into nraw<q>,
+      // handed to raw<q> at the end of the iteration.
       std::string pro, nxt, adv;
-      char buf[512];
+      char buf[640];
       int n_pref = 0;
       for (size_t q = 0; q < A.views.size(); ++q) n_pref += prefetched[q] ? 1 : 0;
-      const int depth = prefetch_depth(n_pref);
+      const int depth = rotating ? prefetch_depth(n_pref) : 1;
+      const int nb = depth + 1;
+      rot_buffers = nb;
       // A per-row scalar loaded where it is used would make every iteration wait for all requests issued
-      // before it, the rows requested ahead included (loads complete in order): it is requested with them.
+      // before it, the rows requested ahead included (loads complete in order): it is requested with them,
+      // and first, because it is needed first.
       for (size_t q = 0; q < A.views.size(); ++q) if (scalar_prefetched[q]) {
         const RView& v = A.views[q];
         const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
         const char* cv = v.dtype == FS_F32 ? "" : v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
         bool dummy = false;
-        const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
-        if (depth == 2) {
-          // two buffers, each re-requested (for two steps ahead) right after its value was taken
-          snprintf(buf, sizeof buf, "  float sraw%zux[2];\n  sraw%zux[0] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n  sraw%zux[1] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n",
-                   q, q, cv, ty, q, offp.c_str(), q, cv, ty, q, offp2.c_str());
+        const std::string offp = row_offset(v, &dummy, "rowp"), offn = row_offset(v, &dummy, "rown");
+        if (rotating) {
+          snprintf(buf, sizeof buf, "  float sraw%zux[%d];\n", q, nb);
           pro += buf;
-          snprintf(buf, sizeof buf, "  const float sraw%zu = sraw%zux[ph];\n  sraw%zux[ph] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, q, q, cv, ty, q, offn.c_str());
+          snprintf(buf, sizeof buf, "    sraw%zux[pp] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp.c_str());
+          pro_req += buf;
+          snprintf(buf, sizeof buf, "  sraw%zux[(ph + %d) %% %d] = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, depth, nb, cv, ty, q, offn.c_str());
           nxt += buf;
         } else {
           snprintf(buf, sizeof buf, "  float sraw%zu = %s((static_cast<const %s*>(a.in[%zu]) + (%s))[0]);\n", q, cv, ty, q, offp.c_str());
@@ -1167,16 +1181,15 @@ struct Gen {
         const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
         const char* rt = raw_type(v);
         bool dummy = false;
-        const std::string offp = row_offset(v, &dummy, "rowp"), offp2 = row_offset(v, &dummy, "rowp2"), offn = row_offset(v, &dummy, "rown");
-        if (depth == 2) {
-          snprintf(buf, sizeof buf, "  %s raw%zux[2][K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zux[0][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
-                   rt, q, q, rt, ty, q, offp.c_str());
+        const std::string offp = row_offset(v, &dummy, "rowp"), offn = row_offset(v, &dummy, "rown");
+        if (rotating) {
+          snprintf(buf, sizeof buf, "  %s raw%zux[%d][K];\n", rt, q, nb);
           pro += buf;
-          snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zux[1][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
-                   q, rt, ty, q, offp2.c_str());
-          pro += buf;
-          snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) { raw%zu[k] = raw%zux[ph][k]; raw%zux[ph][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k])); }\n",
-                   rt, q, q, q, q, rt, ty, q, offn.c_str());
+          snprintf(buf, sizeof buf, "    UNROLL for (int k = 0; k < K; ++k) raw%zux[pp][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   q, rt, ty, q, offp.c_str());
+          pro_req += buf;
+          snprintf(buf, sizeof buf, "  UNROLL for (int k = 0; k < K; ++k) raw%zux[(ph + %d) %% %d][k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
+                   q, depth, nb, rt, ty, q, offn.c_str());
           nxt += buf;
         } else {
           snprintf(buf, sizeof buf, "  %s raw%zu[K];\n  UNROLL for (int k = 0; k < K; ++k) raw%zu[k] = __builtin_nontemporal_load(reinterpret_cast<const %s*>(static_cast<const %s*>(a.in[%zu]) + (%s) + col[k]));\n",
@@ -1191,17 +1204,25 @@ struct Gen {
       }
       if (!pro.empty()) {
         // the prologue goes before the row loop: find the loop header emitted above
-        const std::string header = "  for (long long row0 = ";
-        const size_t at = e.s.rfind(header);
-        snprintf(buf, sizeof buf, "  long long rowp = first_row + rl;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
-        std::string head = buf;
-        if (depth == 2) {
-          snprintf(buf, sizeof buf, "  long long rowp2 = first_row + row_step + rl;\n  if (rowp2 >= %s) rowp2 = %s;\n", row_hi, row_last);
+        const size_t at = e.s.rfind(loop_anchor);
+        std::string head;
+        if (rotating) {
+          // what is loaded once has arrived before the first row is requested: a load still pending at the top
+          // of the row loop would put a wait into the loop that, trip after trip, also waits for the rows
+          // requested ahead
+          head = "  __builtin_amdgcn_s_waitcnt(0);\n" + pro;
+          snprintf(buf, sizeof buf, "  UNROLL for (int pp = 0; pp < %d; ++pp) {\n    long long rowp = first_row + pp * row_step + rl;\n    if (rowp >= %s) rowp = %s;\n", depth, row_hi, row_last);
           head += buf;
+          head += pro_req + "  }\n";
+          deferred_head = head;      // placed when the loop is closed: behind everything that is loaded once
+          (void)at;
+          e.line("  long long rown = row0 + %d * row_step + rl;", depth);
+        } else {
+          snprintf(buf, sizeof buf, "  long long rowp = first_row + rl;\n  if (rowp >= %s) rowp = %s;\n", row_hi, row_last);
+          head = buf;
+          e.s.insert(at, head + pro);
+          e.line("  long long rown = row0 + row_step + rl;");
         }
-        e.s.insert(at, head + pro);
-        if (two_phase) e.line("  long long rown = row0 + (ph + 2) * row_step + rl;");
-        else e.line("  long long rown = row0 + row_step + rl;");
         e.line("  if (rown >= %s) rown = %s;          // past the end: any valid row (one that is cached by then)", row_hi, row_any);
         e.s += nxt;
         e.line("  __builtin_amdgcn_sched_barrier(0);     // keep the requests above the work below");
@@ -1215,21 +1236,21 @@ struct Gen {
       if (v.cls == CLS_NONE) continue;     // an operand of a matrix-unit dot: read by the dot's own code
       // persistent form: an operand that does not depend on the row (a per-column vector, a
       // scalar) is loaded once, before the row loop
-      bool invariant = persistent;
+      bool invariant = persistent && !prefetched[q];      // (what is requested ahead is unpacked inside the loop, also when there is only one row)
       for (int d = 0; d < nrow; ++d) if (A.S[d] != 1 && v.stride[d] != 0) invariant = false;
       const size_t text_from = e.s.size();
       struct Hoist {
-        Emitter& e; bool on; size_t from;
+        Emitter& e; bool on; size_t from; const std::string& anchor;
         ~Hoist() {
           if (!on) return;
           const std::string text = e.s.substr(from);
           e.s.erase(from);
-          e.s.insert(e.s.rfind("  for (long long row0 = "), text);
+          e.s.insert(e.s.rfind(anchor), text);
         }
-      } hoist{e, invariant, text_from};
+      } hoist{e, invariant, text_from, loop_anchor};
       if (splat[q] && scalar_prefetched[q] && !advance.empty()) {
         hoist.on = false;
-        e.line("  const float s%zu = sraw%zu;", q, q);
+        e.line("  const float s%zu = sraw%zu%s;", q, q, rotating ? "x[ph]" : "");
         continue;
       }
       if (splat[q]) {
@@ -1241,9 +1262,10 @@ struct Gen {
         // unpack what was requested one iteration ago
         e.line("  float v%zu[K][W];", q);
         e.line("  UNROLL for (int k = 0; k < K; ++k) {");
-        if (v.dtype == FS_F32) e.line("    UNROLL for (int j = 0; j < 4; ++j) v%zu[k][j] = raw%zu[k][j];", q, q);
-        else e.line("    UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[k][2 * j] = %s(raw%zu[k][j]); v%zu[k][2 * j + 1] = %s(raw%zu[k][j]); }",
-                    q, v.dtype == FS_F16 ? "f16_lo" : "bf16_lo", q, q, v.dtype == FS_F16 ? "f16_hi" : "bf16_hi", q);
+        const char* ix = rotating ? "x[ph]" : "";
+        if (v.dtype == FS_F32) e.line("    UNROLL for (int j = 0; j < 4; ++j) v%zu[k][j] = raw%zu%s[k][j];", q, q, ix);
+        else e.line("    UNROLL for (int j = 0; j < W / 2; ++j) { v%zu[k][2 * j] = %s(raw%zu%s[k][j]); v%zu[k][2 * j + 1] = %s(raw%zu%s[k][j]); }",
+                    q, v.dtype == FS_F16 ? "f16_lo" : "bf16_lo", q, ix, q, v.dtype == FS_F16 ? "f16_hi" : "bf16_hi", q, ix);
         e.line("  }");
         continue;
       }
@@ -1412,11 +1434,22 @@ struct Gen {
       }
       e.line("  }");
     }
-    if (persistent) {
+    if (persistent && rotating) {
+      e.line("  };");
+      e.s.insert(e.s.rfind(loop_anchor), deferred_head);
+      // whole trips over the buffers without a branch inside (one path through the loop: the waits on the
+      // requests count exactly), then the last, partial trip
+      e.line("  long long trip0 = first_row;");
+      e.line("  for (; trip0 + %d * row_step + RPW <= %s; trip0 += %d * row_step) {", rot_buffers - 1, row_hi, rot_buffers);
+      e.line("    UNROLL for (int ph = 0; ph < %d; ++ph) step(std_true{}, ph, trip0 + ph * row_step);", rot_buffers);
+      e.line("  }");
+      e.line("  for (; trip0 < %s; trip0 += %d * row_step) {", row_hi, rot_buffers);
+      e.line("    UNROLL for (int ph = 0; ph < %d; ++ph) if (trip0 + ph * row_step < %s) step(std_false{}, ph, trip0 + ph * row_step);", rot_buffers, row_hi);
+      e.line("  }");
+    } else if (persistent) {
       e.s += advance;
       if (T > 1 && A.n_reduce > 0) e.line("  __syncthreads();                             // the exchange slots are written again in the next row");
       e.line("  }");
-      if (two_phase) e.line("  }");
     }
     // a run of rows that one workgroup sums alone: its sums are the results, stored as they are
     const bool direct = A.seg_rows > 0 && (seg_groups == 1 || seg_per_wave);
