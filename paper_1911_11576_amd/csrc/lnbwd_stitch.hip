@@ -70,9 +70,7 @@ void lnbwd_rows_kernel(const LnBwdArgs a) {
     for (int j = 0; j < 4; ++j) { dg[k][j] = 0.0; db[k][j] = 0.0; }
   }
 
-  // gamma has arrived before the first row is requested: a load still pending at the top of the row loop
-  // would put a wait into the loop that, trip after trip, also waits for the rows requested ahead
-  __builtin_amdgcn_s_waitcnt(0);
+  asm volatile("" ::: "memory");   // gamma is requested before the rows (the wait below the row requests counts on it)
 
   // All workgroups advance through the rows together, so at any moment the chip streams one
   // compact window of dy, x and dx, as a one-shot grid would.
@@ -99,6 +97,13 @@ void lnbwd_rows_kernel(const LnBwdArgs a) {
   };
 #pragma unroll
   for (int p = 0; p < PF; ++p) request(p, row + p * row_step);
+  // gamma has arrived before the row loop starts: a load still pending at its top would put a wait into the
+  // loop that, trip after trip, also waits for the rows requested ahead.  Loads complete in the order they
+  // were issued, gamma's first: the wait lets the row requests just issued stay in flight (vmcnt = their
+  // number; bits 3:0 and 15:14 of the operand, the other counters left alone).
+  constexpr int kRowLoads = PF * (K + (NEED_X ? K + 2 : 0));
+  static_assert(kRowLoads < 64, "the wait counter has six bits");
+  __builtin_amdgcn_s_waitcnt((kRowLoads & 15) | ((kRowLoads >> 4) << 14) | 0x0F70);
   // one step: request the row PF steps ahead, then the arithmetic of row r out of buffer p
   auto step = [&](const int p, const int64_t r) {
     request((p + PF) % NB, r + PF * row_step);
