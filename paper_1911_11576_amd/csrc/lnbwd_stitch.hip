@@ -186,31 +186,34 @@ void lnbwd_rows_kernel(const LnBwdArgs a) {
 }
 
 // Second kernel of the plan: out[col(slot)] = sum over the workgroups' partial rows, in a fixed order
-// (32 interleaved slices of partial rows, then the slices in order).  A block owns 8 consecutive slots.
-__global__ __launch_bounds__(256)
+// (256 / SL interleaved slices of partial rows, then the slices in order).  A block owns SL consecutive slots:
+// with 16 the 16 lanes of a slice read one whole 128-byte line of a partial row.
+template <int SL, int NT = 256>
+__global__ __launch_bounds__(NT)
 void lnbwd_combine_kernel(const double* __restrict__ part, int groups, int K, int nvec, float* dgamma, float* dbeta) {
-  __shared__ double stage[32][9];
+  constexpr int NS = NT / SL;           // slices
+  __shared__ double stage[NS][SL + 1];
   const int n2 = 2 * K * 256;
-  const int j = threadIdx.x & 7, slice = threadIdx.x >> 3;
-  const int s = blockIdx.x * 8 + j;
+  const int j = threadIdx.x % SL, slice = threadIdx.x / SL;
+  const int s = blockIdx.x * SL + j;
   const double* p = part + s;
   double acc = 0.0;
   int g = slice;
   // eight partial rows requested at a time (the loads are independent, the additions keep their order)
-  for (; g + 7 * 32 < groups; g += 8 * 32) {
+  for (; g + 7 * NS < groups; g += 8 * NS) {
     double v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = p[(int64_t)(g + i * 32) * n2];
+    for (int i = 0; i < 8; ++i) v[i] = p[(int64_t)(g + i * NS) * n2];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc += v[i];
   }
-  for (; g < groups; g += 32) acc += p[(int64_t)g * n2];
+  for (; g < groups; g += NS) acc += p[(int64_t)g * n2];
   stage[slice][j] = acc;
   __syncthreads();
   if (slice == 0) {
     double t = stage[0][j];
 #pragma unroll
-    for (int k = 1; k < 32; ++k) t += stage[k][j];
+    for (int k = 1; k < NS; ++k) t += stage[k][j];
     // slot -> column
     const int slots = K * 256;
     const int r = s >= slots ? 1 : 0, q = (s - r * slots) >> 6, vi = (q >> 2) * 64 + (s & 63);
@@ -219,6 +222,7 @@ void lnbwd_combine_kernel(const double* __restrict__ part, int groups, int K, in
     if (vi < nvec && o) o[col] = (float)t;
   }
 }
+constexpr int kCombineSlots = 16;
 
 namespace {
 
@@ -342,7 +346,7 @@ int lnbwd_stitch_launch(const LnBwdSpec& sp, const LnBwdLaunch& l, const void* c
   }
   if (want_col) {
     // sums over zero rows are zero: the combine kernel over zero partial rows writes them
-    hipLaunchKernelGGL(lnbwd_combine_kernel, dim3(2 * l.K * 256 / 8), dim3(256), 0, s, a.part, groups, l.K, a.nvec, a.dgamma, a.dbeta);
+    hipLaunchKernelGGL(lnbwd_combine_kernel<kCombineSlots>, dim3(2 * l.K * 256 / kCombineSlots), dim3(256), 0, s, a.part, groups, l.K, a.nvec, a.dgamma, a.dbeta);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { *err = std::string("lnbwd_combine launch: ") + hipGetErrorString(e); return -1; }
   }
