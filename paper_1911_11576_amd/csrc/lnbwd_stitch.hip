@@ -188,7 +188,7 @@ void lnbwd_rows_kernel(const LnBwdArgs a) {
 // Second kernel of the plan: out[col(slot)] = sum over the workgroups' partial rows, in a fixed order
 // (256 / SL interleaved slices of partial rows, then the slices in order).  A block owns SL consecutive slots:
 // with 16 the 16 lanes of a slice read one whole 128-byte line of a partial row.
-template <int SL, int NT = 256>
+template <int SL, int NT = 256, int NL = 8>
 __global__ __launch_bounds__(NT)
 void lnbwd_combine_kernel(const double* __restrict__ part, int groups, int K, int nvec, float* dgamma, float* dbeta) {
   constexpr int NS = NT / SL;           // slices
@@ -199,13 +199,13 @@ void lnbwd_combine_kernel(const double* __restrict__ part, int groups, int K, in
   const double* p = part + s;
   double acc = 0.0;
   int g = slice;
-  // eight partial rows requested at a time (the loads are independent, the additions keep their order)
-  for (; g + 7 * NS < groups; g += 8 * NS) {
-    double v[8];
+  // NL partial rows requested at a time (the loads are independent, the additions keep their order)
+  for (; g + (NL - 1) * NS < groups; g += NL * NS) {
+    double v[NL];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = p[(int64_t)(g + i * NS) * n2];
+    for (int i = 0; i < NL; ++i) v[i] = p[(int64_t)(g + i * NS) * n2];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc += v[i];
+    for (int i = 0; i < NL; ++i) acc += v[i];
   }
   for (; g < groups; g += NS) acc += p[(int64_t)g * n2];
   stage[slice][j] = acc;
