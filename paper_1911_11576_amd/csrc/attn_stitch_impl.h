@@ -76,6 +76,8 @@ template <class Op> __device__ __forceinline__ float rows_allreduce(float v) {
   return Op::apply(as_f32(r[0]), as_f32(r[1]));
 }
 
+template <int N> struct TileCount { static constexpr int value = N; };   // a compile-time count handed to a generic lambda
+
 // NQ: 16-row tiles of queries (workgroup = NQ wavefronts); NK: 16-key tiles; D: head dim;
 // X: the group has a mask, an epilogue operand or a second output (without any of them those paths
 // are compiled out: on the bare dot-softmax-dot group their run-time tests alone cost 0.15 us of 6);
@@ -209,34 +211,35 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
     const u32x2 hi = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 16 * VP)));
     return u32x4{lo[0], lo[1], hi[0], hi[1]};
   };
-  u32x4 pb[NKP / 2];                         // P^T, the second dot's B fragments
-  if (active) {
+  // ---- everything behind the barrier as a function of TL, the number of key tiles the wavefront needs (the
+  // same for the whole wavefront, so which instance runs is a scalar branch): straight-line code per count.
+  // With the count a run-time bound of unrolled loops the compiler merged the paths register by register -
+  // on 128 x 128 x 64, 497 of 1266 instructions were moves - and held 212 registers.
+  auto work = [&](auto tl_c) __attribute__((always_inline)) {
+    constexpr int TL = decltype(tl_c)::value;
+    constexpr int KST = (TL + 1) / 2;           // 32-key steps of the second dot
     // ---- first dot, transposed: tile kt = K_kt(16 x D) . Q^T -----------------------------
     // (the LDS reads of up to eight fragments first, then their matrix instructions: one latency per
     // batch, not one per tile)
-    f32x4 acc[NK];
+    f32x4 acc[TL];
     constexpr int CT = KS >= 8 ? 1 : 8 / KS;     // key tiles per batch
 #pragma unroll
-    for (int k0 = 0; k0 < NK; k0 += CT) {
+    for (int k0 = 0; k0 < TL; k0 += CT) {
       u32x4 kfr[CT][KS];
 #pragma unroll
       for (int j = 0; j < CT; ++j) {
-        const int kt = k0 + j;
-        if (kt < NK && kt < tiles) {
+        if (k0 + j < TL) {
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks)
-            kfr[j][ks] = *reinterpret_cast<const u32x4*>(ksh + (kt * 16 + c) * KP + ks * 32 + 8 * g);
+            kfr[j][ks] = *reinterpret_cast<const u32x4*>(ksh + ((k0 + j) * 16 + c) * KP + ks * 32 + 8 * g);
         }
       }
 #pragma unroll
       for (int j = 0; j < CT; ++j) {
-        const int kt = k0 + j;
-        if (kt < NK) {
-          acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-          if (kt < tiles) {
+        if (k0 + j < TL) {
+          acc[k0 + j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc[kt] = Mfma<T>::run(kfr[j][ks], qf[ks], acc[kt]);
-          }
+          for (int ks = 0; ks < KS; ++ks) acc[k0 + j] = Mfma<T>::run(kfr[j][ks], qf[ks], acc[k0 + j]);
         }
       }
     }
@@ -256,54 +259,48 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
     const float fill2 = a.fill == -INFINITY ? -INFINITY : fmaxf(a.fill * kLog2e, -3.0e38f);
     float mx = -INFINITY;
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt) {
-      if (kt < tiles) {
+    for (int kt = 0; kt < TL; ++kt) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float z = acc[kt][i] * sc2;
-          if (X && a.mask) z = fmaf(mk[kt][i], kLog2e, z);
-          acc[kt][i] = z;
-        }
-        if (a.causal && 16 * kt + 15 > q0) {             // the tile holds keys right of some row's diagonal
-#pragma unroll
-          for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i > qi) acc[kt][i] = fill2;
-        }
-        if (!E && 16 * kt + 15 >= sk) {                  // the tile runs past the last key
-#pragma unroll
-          for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i >= sk) acc[kt][i] = -INFINITY;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, acc[kt][i]);
+      for (int i = 0; i < 4; ++i) {
+        float z = acc[kt][i] * sc2;
+        if (X && a.mask) z = fmaf(mk[kt][i], kLog2e, z);
+        acc[kt][i] = z;
       }
+      if (a.causal && 16 * kt + 15 > q0) {             // the tile holds keys right of some row's diagonal
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i > qi) acc[kt][i] = fill2;
+      }
+      if (!E && 16 * kt + 15 >= sk) {                  // the tile runs past the last key
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (kt * 16 + 4 * g + i >= sk) acc[kt][i] = -INFINITY;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, acc[kt][i]);
     }
     mx = rows_allreduce<MaxOp>(mx);
     float sum = 0.f;
 #pragma unroll
-    for (int kt = 0; kt < NK; ++kt) {
-      if (kt < tiles) {
+    for (int kt = 0; kt < TL; ++kt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float e = __builtin_amdgcn_exp2f(acc[kt][i] - mx);
-          acc[kt][i] = e;
-          sum += e;
-        }
-      } else {
-        acc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < 4; ++i) {
+        const float e = __builtin_amdgcn_exp2f(acc[kt][i] - mx);
+        acc[kt][i] = e;
+        sum += e;
       }
-    }
     sum = rows_allreduce<SumOp>(sum);
     const float inv = __builtin_amdgcn_rcpf(sum);
     if (X && a.lse && g == 0 && qi < sq) a.lse[(int64_t)b * sq + qi] = (mx + __builtin_amdgcn_logf(sum)) * kLn2;
     // P rounded to the dot's dtype, packed in k-slot order: slots 4h+i of step kk <- tile 2kk+h
+    u32x4 pb[KST];                              // P^T, the second dot's B fragments
 #pragma unroll
-    for (int kk = 0; kk < NKP / 2; ++kk)
+    for (int kk = 0; kk < KST; ++kk)
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int kt = 2 * kk + h;
         float p[4] = {0.f, 0.f, 0.f, 0.f};
-        if (kt < NK) {
+        if (kt < TL) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) p[i] = acc[kt < NK ? kt : 0][i] * inv;
+          for (int i = 0; i < 4; ++i) p[i] = acc[kt < TL ? kt : 0][i] * inv;
         }
         pb[kk][2 * h] = Mfma<T>::pack(p[0], p[1]);
         pb[kk][2 * h + 1] = Mfma<T>::pack(p[2], p[3]);
@@ -316,13 +313,10 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       if constexpr (PRE) o[dt] = Mfma<T>::run(vpre[dt], pb[0], f32x4{0.f, 0.f, 0.f, 0.f});
       else o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const int ksteps = (tiles + 1) / 2;
 #pragma unroll
-    for (int kk = PRE ? 1 : 0; kk < NKP / 2; ++kk) {
-      if (kk < ksteps) {
+    for (int kk = PRE ? 1 : 0; kk < KST; ++kk) {
 #pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) o[dt] = Mfma<T>::run(vfrag(kk, dt), pb[kk], o[dt]);
-      }
+      for (int dt = 0; dt < D / 16; ++dt) o[dt] = Mfma<T>::run(vfrag(kk, dt), pb[kk], o[dt]);
     }
     // ---- epilogue on the accumulators: the lane holds O[q0+c][16dt+4g+i], i < 4 -----------------
     if (X && a.gate) {
@@ -351,6 +345,19 @@ __global__ __launch_bounds__(64 * NQ) void attn_stitch_kernel(const AttnArgs a) 
       const auto r0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
       const auto r1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
       if (E || qi < sq) *reinterpret_cast<u32x4*>(orow + dp * 32) = u32x4{r0[0], r1[0], r0[1], r1[1]};
+    }
+  };
+  if (active) {
+    switch (tiles) {
+      case 1: work(TileCount<1>{}); break;
+      case 2: if constexpr (NK >= 2) work(TileCount<2>{}); break;
+      case 3: if constexpr (NK >= 4) work(TileCount<3>{}); break;
+      case 4: if constexpr (NK >= 4) work(TileCount<4>{}); break;
+      case 5: if constexpr (NK >= 8) work(TileCount<5>{}); break;
+      case 6: if constexpr (NK >= 8) work(TileCount<6>{}); break;
+      case 7: if constexpr (NK >= 8) work(TileCount<7>{}); break;
+      case 8: if constexpr (NK >= 8) work(TileCount<8>{}); break;
+      default: break;
     }
   }
 }
