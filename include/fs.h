@@ -334,7 +334,8 @@ typedef struct {
                               /* generated pattern with the same ops; NaN: the model's score          */
 } fs_fusion_options;
 
-/* Errors: FS_ERR_INVALID (malformed list or options), FS_ERR_NOMEM. */
+/* Errors: FS_ERR_INVALID (malformed list or options, a measured score that is infinite or beyond 1e12),
+ * FS_ERR_NOMEM. */
 fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion_options* opt, fs_fusion** out);
 fs_status fs_fusion_destroy(fs_fusion* fusion);
 /* Any out-pointer may be NULL.  solver_rounds = 1 + number of cycle repairs. */

@@ -5,6 +5,7 @@
 #include <cstring>
 #include <map>
 #include <memory>
+#include <cmath>
 #include <mutex>
 #include <new>
 #include <set>
@@ -636,7 +637,11 @@ fs_status fs_fusion_create(const fs_op_desc* ops, int32_t n_ops, const fs_fusion
         next += opt->extra_sizes[k];
         for (int o : pat) if (o < 0 || o >= n_ops) return set_error(FS_ERR_INVALID, "extra patterns: op index out of range");
         cfg.extra_patterns.push_back(pat);
-        if (opt->extra_scores) cfg.extra_scores.push_back(opt->extra_scores[k]);
+        if (opt->extra_scores) {
+          const double sc = opt->extra_scores[k];
+          if (std::isinf(sc) || std::fabs(sc) > 1e12) return set_error(FS_ERR_INVALID, "extra patterns: a measured score must be a finite number of microseconds (or NaN for none)");
+          cfg.extra_scores.push_back(sc);
+        }
       }
       if (opt->max_patterns < 0 || opt->max_patterns > 256) return set_error(FS_ERR_INVALID, "max_patterns out of range [0,256]");
       if (opt->n_bw < 0 || (opt->n_bw > 0 && (!opt->bw_bytes || !opt->bw_gbs))) return set_error(FS_ERR_INVALID, "bandwidth model: NULL table");

@@ -77,12 +77,30 @@ def test_mutated_op_lists_never_crash_the_fusion_planner():
         opt.launch_us = rng.choice([0.0, 2.5, -1.0, float("nan")])
         opt.max_patterns = rng.choice([0, 0, 4, 256, 1000, -3])
         opt.explore_budget = rng.choice([0, -1, 5, 10**6])
+        # caller-supplied patterns (valid or not) with measured scores of every kind
+        keep = None
+        if rng.random() < 0.5:
+            n_extra = rng.randint(1, 3)
+            sizes = [rng.randint(1, 5) for _ in range(n_extra)]
+            flat = [rng.randint(-1, len(arr) + 1) for _ in range(sum(sizes))]
+            scores = [rng.choice([float("nan"), float("inf"), -float("inf"), -3.0, 0.0, 7.5, 1e300]) for _ in range(n_extra)]
+            keep = ((C.c_int32 * n_extra)(*sizes), (C.c_int32 * len(flat))(*flat), (C.c_double * n_extra)(*scores))
+            opt.n_extra, opt.extra_sizes, opt.extra_ops = n_extra, keep[0], keep[1]
+            if rng.random() < 0.7:
+                opt.extra_scores = keep[2]
         out = C.c_void_p()
         st = lib().fs_fusion_create(arr, len(arr), C.byref(opt), C.byref(out))
         if st == binding.FS_OK:
             ok += 1
-            n_groups = C.c_int32()
-            assert lib().fs_fusion_info(out, C.byref(n_groups), None, None, None) == binding.FS_OK and n_groups.value >= 1
+            n_groups, n_pat = C.c_int32(), C.c_int32()
+            assert lib().fs_fusion_info(out, C.byref(n_groups), C.byref(n_pat), None, None) == binding.FS_OK and n_groups.value >= 1
+            for k in range(-1, n_pat.value + 1):        # every candidate as an op list, and both ends past the range
+                a, b, c, m = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+                st2 = lib().fs_fusion_pattern_group_size(out, k, C.byref(a), C.byref(b), C.byref(c), C.byref(m))
+                assert (st2 == binding.FS_OK) == (0 <= k < n_pat.value)
+                if st2 == binding.FS_OK and a.value:
+                    gops = (binding.fs_op_desc * a.value)()
+                    assert lib().fs_fusion_pattern_group(out, k, gops, None, None) == binding.FS_OK
             assert lib().fs_fusion_destroy(out) == binding.FS_OK
         else:
             assert not out.value and binding.fs_last_error()

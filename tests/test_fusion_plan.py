@@ -315,6 +315,9 @@ def test_measured_scores_replace_the_models_and_the_selection_follows():
         assert again["score_us"] < 0 and not again["measured"] and not again["chosen"]
     with pytest.raises(ValueError):
         FusionPlan(ops, extra_patterns=[loser["ops"]], extra_scores=[1.0, 2.0])
+    for bad_score in (float("inf"), -float("inf"), 1e300):
+        with pytest.raises(FsError):
+            FusionPlan(ops, extra_patterns=[loser["ops"]], extra_scores=[bad_score])
 
 
 def test_planner_rejects_bad_input():
