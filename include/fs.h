@@ -133,8 +133,8 @@ typedef enum {
                             the leading dim), or over each run of the innermost row dims
                             ([B, S, H] -> [B, H]: sequence pooling) */
   FS_SCHED_BDOT_SOFTMAX = 3, /* batched dot -> softmax -> batched dot on MFMA; the probabilities stay in
-                                registers (accumulators of the first dot = operands of the second), V goes
-                                through LDS */
+                                registers (accumulators of the first dot = operands of the second), K and V
+                                go through LDS */
   FS_SCHED_ELEMENTWISE = 4,  /* any all-elementwise group: thread composition + packing, as
                                 a kernel generated for the group (or interpreted, see
                                 FS_MODE_STITCHED_PREBUILT).  The ops share one shape, or fall into

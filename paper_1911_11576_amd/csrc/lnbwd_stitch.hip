@@ -8,8 +8,8 @@
 // Row path: a fixed grid of workgroups walks the rows together (row = step * grid * waves +
 // workgroup * waves + wave), one wavefront per row, lane l owns 16-byte vectors l, l+64, ...;
 // wave64 all-reduce for sum(g) and sum(g*xhat).  A wavefront requests its rows two steps
-// ahead (three register buffers): with one wavefront per SIMD the time of a step is otherwise
-// the latency of its loads.
+// ahead into three register buffers that take turns (none is ever copied): with one wavefront
+// per SIMD the time of a step is otherwise the latency of its loads.
 // Column path: every lane keeps double-precision running sums for its own columns over all
 // rows its wavefront visits (32768-term fp32 sums would not meet a 1e-5 absolute bar).  At
 // the end each wavefront writes its sums to an LDS array of its own (the `S` hand-off of
