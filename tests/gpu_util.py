@@ -45,8 +45,9 @@ def group_dtype(ops):
     return "f32"
 
 
-def assert_close(got, want, tol, what=""):
-    """|got - want| <= tol + tol*|want| for every element; NaN anywhere fails."""
+def assert_close(got, want, tol, what="", slack=None):
+    """|got - want| <= tol + tol*|want| (+ slack, an array of further absolute room per element, when a caller
+    derives one) for every element; NaN anywhere fails."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
@@ -54,6 +55,8 @@ def assert_close(got, want, tol, what=""):
         return
     err = np.abs(got - want)
     bound = tol + tol * np.abs(want)
+    if slack is not None:
+        bound = bound + np.broadcast_to(np.asarray(slack, dtype=np.float64), want.shape)
     bad = ~(err <= bound)          # also true for NaN
     if bad.any():
         k = np.unravel_index(np.argmax(np.where(np.isnan(err), np.inf, err - bound)), err.shape)
