@@ -143,8 +143,10 @@ typedef enum {
   FS_SCHED_BLOCK_DOT = 5     /* generated block composition around batched dots on MFMA (Sections 5.1, 5.3):
                                 a[B,M,K] . b[B,N,K]^T (16-bit, K 16..128, tile up to 128 x 128) -> any
                                 elementwise ops and row reductions on the tile -> optionally a second dot
-                                with v[B,N,D], its operand handed over through LDS; what the hand-written
-                                FS_SCHED_BDOT_SOFTMAX kernel does not match */
+                                with v[B,N,D], its operand handed over through LDS -> optionally
+                                elementwise ops on the [B,M,D] result (operands: such values, per-row
+                                values of the tile, constants, inputs seen as [B,M,D]; no reduction);
+                                what the hand-written FS_SCHED_BDOT_SOFTMAX kernel does not match */
 } fs_schedule;
 
 /* Build a plan from a fusion group.

@@ -201,6 +201,50 @@ struct Analysis {
     return true;
   }
 
+  bool shape_is_dot_out(const Node& x) const {
+    return mma_out >= 0 && rank == 3 && x.rank == 3 && x.shape[0] == S[0] && x.shape[1] == S[1] && x.shape[2] == mma_d;
+  }
+  // does op i work on the result of the consuming dot (the epilogue around the second dot)?
+  bool reads_dot_out(int i) const {
+    for (int j = 0; j < operand_count(g[i].kind); ++j) {
+      const int c = canon(g[i].operand[j]);
+      if (is_compute(c) && cls[c] == CLS_DOT_OUT) return true;
+    }
+    return false;
+  }
+  // Operand of an elementwise op on the consuming dot's result [B, M, D]: another such value, a per-row value
+  // of the group broadcast along D, a constant, or an input seen as [B, M, D] (any strides over B and M;
+  // contiguous or repeated along D).
+  bool operand_dot_out(int n, Opnd* o) {
+    const int c = canon(n);
+    if (is_compute(c)) {
+      if (cls[c] != CLS_DOT_OUT) return fail("generated row schedule: operand of the wrong shape class");
+      o->kind = OP_NODE; o->index = c;
+      return true;
+    }
+    if (g[c].kind == FS_BROADCAST) {
+      const int src = canon(g[c].operand[0]);
+      if (is_compute(src)) {
+        if (cls[src] != CLS_ROW || !shape_is_dot_out(g[c]) || (g[src].rank > 0 && g[c].axis != 0))
+          return fail("generated row schedule: only per-row values may be broadcast into the ops after a consuming dot");
+        o->kind = OP_ROWB; o->index = src;
+        return true;
+      }
+    }
+    int base = -1;
+    int64_t st[FS_MAX_RANK] = {0, 0, 0, 0};
+    bool is_const = false;
+    float cv = 0.f;
+    if (!leaf_strides(c, &base, st, &is_const, &cv)) return false;
+    if (is_const) { o->kind = OP_CONST; o->cval = cv; return true; }
+    if (!shape_is_dot_out(g[c])) return fail("generated row schedule: operand shape differs from its consumer's");
+    if (st[2] != 0 && st[2] != 1) return fail("generated row schedule: an operand strided along the last dim");
+    if (st[2] == 1 && (st[0] % 4 || st[1] % 4)) return fail("generated row schedule: an operand of the ops after a consuming dot is not readable in pieces of 4 elements");
+    o->kind = OP_VIEW;
+    o->index = view_index(base, st, CLS_DOT_OUT);
+    return true;
+  }
+
   // A parameter behind widening converts, as a dense tensor: its node and dims.
   bool dense_param(int n, int* base) const {
     n = canon(n);
@@ -421,10 +465,12 @@ struct Analysis {
         const GeluIdiom& id = idioms[idiom_of[i]];
         RNode r;
         r.id = i; r.op = EW_OP_GELU_TANH; r.nop = 1;
-        r.cls = shape_is_full(x) ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
+        const int hc = canon(id.h);
+        const bool after_dot = is_compute(hc) && cls[hc] == CLS_DOT_OUT;
+        r.cls = after_dot ? CLS_DOT_OUT : shape_is_full(x) ? CLS_FULL : shape_is_row(x) ? CLS_ROW : CLS_NONE;
         if (r.cls == CLS_NONE) return fail("generated row schedule: an op whose shape is neither the group's nor its row shape");
         cls[i] = r.cls;
-        if (!operand(id.h, r.cls, &r.o[0])) return false;
+        if (after_dot ? !operand_dot_out(id.h, &r.o[0]) : !operand(id.h, r.cls, &r.o[0])) return false;
         gelu_constants(id, r.gelu);
         r.out_ord = out_ord[i];
         r.out_dtype = out_dtype[i];
@@ -436,7 +482,6 @@ struct Analysis {
         if (!dot_node(i, &r)) return false;
         r.out_ord = out_ord[i];
         r.out_dtype = out_dtype[i];
-        if (r.op == ROP_DOT_MMA_OUT && r.out_ord < 0) return fail("generated row schedule: the result of a consuming dot must be a group output (no ops after it)");
         nodes.push_back(r);
         continue;
       }
@@ -467,11 +512,20 @@ struct Analysis {
         if (!operand(col_base[i], CLS_FULL, &r.o[0])) return false;
         ++n_col;
       } else if (is_reduce(k)) {
+        if (reads_dot_out(i)) return fail("generated row schedule: a reduction over the result of a consuming dot");
         if (x.axis != rank - 1 || !shape_is_row(x)) return fail("generated row schedule: reduction not over the last dim of the group's shape");
         r.cls = CLS_ROW; r.op = k; r.nop = 1;
         cls[i] = CLS_ROW;
         if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
         ++n_reduce;
+      } else if (reads_dot_out(i)) {
+        // the epilogue around the consuming dot: elementwise on its [B, M, D] result, in the accumulators' layout
+        if (!shape_is_dot_out(x)) return fail("generated row schedule: an op on a consuming dot's result with another shape");
+        r.cls = CLS_DOT_OUT;
+        cls[i] = CLS_DOT_OUT;
+        r.op = k == FS_CONVERT ? (x.dtype == FS_F16 ? (int)EW_OP_ROUND_F16 : (int)EW_OP_ROUND_BF16) : k;
+        r.nop = is_binary(k) ? 2 : 1;
+        for (int j = 0; j < r.nop; ++j) if (!operand_dot_out(x.operand[j], &r.o[j])) return false;
       } else {
         // arithmetic on per-column values (a scale vector prepared from parameters, say) is done as
         // full arithmetic whose rows are all alike: a few redundant ops per row, no kernel of its own
@@ -503,6 +557,8 @@ struct Analysis {
     std::vector<char> read(n, 0);
     for (const RNode& r : nodes)
       for (int j = 0; j < r.nop; ++j) if (r.o[j].kind == OP_NODE || r.o[j].kind == OP_ROWB) read[r.o[j].index] = 1;
+    for (const RNode& r : nodes)
+      if (r.cls == CLS_DOT_OUT && r.out_ord < 0 && !read[r.id]) return fail("generated row schedule: a value computed after the consuming dot that nothing reads");
     for (RNode& r : nodes) {
       const bool rounds = (r.op == EW_OP_ROUND_F16 && r.out_dtype == FS_F16) || (r.op == EW_OP_ROUND_BF16 && r.out_dtype == FS_BF16);
       if (rounds && r.out_ord >= 0 && !read[r.id]) r.op = EW_OP_COPY;
@@ -672,6 +728,15 @@ struct Gen {
 
   std::string opnd(const Opnd& o, int consumer_cls) const {
     char buf[64];
+    if (consumer_cls == CLS_DOT_OUT) {
+      // values after the consuming dot: D2 / 16 tiles of four consecutive columns per lane
+      switch (o.kind) {
+        case OP_NODE: snprintf(buf, sizeof buf, "d%d[dt][i]", o.index); return buf;
+        case OP_ROWB: snprintf(buf, sizeof buf, "r%d", o.index); return buf;
+        case OP_VIEW: snprintf(buf, sizeof buf, A.views[o.index].stride[2] == 0 ? "ws%d" : "w%d[dt][i]", o.index); return buf;
+        default: return const_text(o.cval);
+      }
+    }
     switch (o.kind) {
       case OP_NODE: snprintf(buf, sizeof buf, consumer_cls == CLS_FULL ? "t%d[k][j]" : "r%d", o.index); return buf;
       case OP_ROWB: snprintf(buf, sizeof buf, "r%d", o.index); return buf;
@@ -682,7 +747,7 @@ struct Gen {
   std::string expr(const RNode& n) const {
     const std::string a = opnd(n.o[0], n.cls), b = n.nop == 2 ? opnd(n.o[1], n.cls) : std::string();
     // a full value divided by a per-row value: one reciprocal per row, then multiplies
-    if (n.op == FS_DIVIDE && n.cls == CLS_FULL && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
+    if (n.op == FS_DIVIDE && (n.cls == CLS_FULL || n.cls == CLS_DOT_OUT) && n.o[1].kind == OP_ROWB) return a + " * inv" + std::to_string(n.o[1].index);
     if (n.op == FS_CAUSAL_MASK) return "(col[k] + j <= irow) ? " + a + " : " + const_text(n.o[1].cval);
     if (n.op == EW_OP_GELU_TANH) return "gelu_tanh(" + a + ", " + const_text(n.gelu[0]) + ", " + const_text(n.gelu[1]) + ", " + const_text(n.gelu[2]) + ")";
     return op_text(n.op, a, b, fast);
@@ -962,6 +1027,7 @@ struct Gen {
     const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
     const char* pk = A.mma_dtype == FS_F16 ? "pack_to_f16" : "pack_to_bf16";
     const int src = n.o[0].index;
+    e.line("  f32x4 d%d[D2 / 16];", n.id);
     e.line("  {");
     e.line("    u32x4 pb2[NKP / 2];");
     e.line("    UNROLL for (int kk = 0; kk < NKP / 2; ++kk) UNROLL for (int h = 0; h < 2; ++h) {");
@@ -972,22 +1038,29 @@ struct Gen {
     e.line("      pb2[kk][2 * h + 1] = %s(p[2], p[3]);", pk);
     e.line("    }");
     e.line("    const unsigned short* vlane = reinterpret_cast<const unsigned short*>(lds_pool + %lld) + (4 * lane + (lane16 >> 2)) * VP + 4 * (lane16 & 3);", (long long)mma_vt_offset);
-    e.line("    f32x4 o[D2 / 16];");
-    e.line("    UNROLL for (int dt = 0; dt < D2 / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};");
+    e.line("    UNROLL for (int dt = 0; dt < D2 / 16; ++dt) d%d[dt] = f32x4{0.f, 0.f, 0.f, 0.f};", n.id);
     e.line("    UNROLL for (int kk = 0; kk < NKP / 2; ++kk) UNROLL for (int dt = 0; dt < D2 / 16; ++dt) {");
     e.line("      const u32x4 vf = lds_read_transposed(vlane + 32 * kk * VP + 16 * dt, 16 * VP);");
-    e.line("      o[dt] = %s(vf, pb2[kk], o[dt]);", mm);
+    e.line("      d%d[dt] = %s(vf, pb2[kk], d%d[dt]);", n.id, mm, n.id);
     e.line("    }");
+    e.line("  }");
+    if (n.out_ord >= 0) store_dot_out(n);
+  }
+
+  // A [B, M, D] value in the accumulators' layout (lane g of a row holds columns 16 dt + 4 g .. + 3 of every
+  // 16-column tile dt) to its output.
+  void store_dot_out(const RNode& n) {
+    e.line("  {");
     if (n.out_dtype == FS_F32) {
       e.line("    float* orow = static_cast<float*>(a.out[%d]) + row * D2 + 4 * lane;", n.out_ord);
-      e.line("    if (row_ok) { UNROLL for (int dt = 0; dt < D2 / 16; ++dt) __builtin_nontemporal_store(o[dt], reinterpret_cast<f32x4*>(orow + 16 * dt)); }");
+      e.line("    if (row_ok) { UNROLL for (int dt = 0; dt < D2 / 16; ++dt) __builtin_nontemporal_store(d%d[dt], reinterpret_cast<f32x4*>(orow + 16 * dt)); }", n.id);
     } else {
       const char* po = n.out_dtype == FS_F16 ? "pack_to_f16" : "pack_to_bf16";
       // 8 bytes per tile and lane; lanes g and g^1 trade one tile of a pair so that each stores 16 bytes
       e.line("    unsigned short* orow = static_cast<unsigned short*>(a.out[%d]) + row * D2 + 16 * (lane & 1) + 8 * (lane >> 1);", n.out_ord);
       e.line("    UNROLL for (int dp = 0; dp < D2 / 32; ++dp) {");
-      e.line("      const unsigned a0 = %s(o[2 * dp][0], o[2 * dp][1]), a1 = %s(o[2 * dp][2], o[2 * dp][3]);", po, po);
-      e.line("      const unsigned b0 = %s(o[2 * dp + 1][0], o[2 * dp + 1][1]), b1 = %s(o[2 * dp + 1][2], o[2 * dp + 1][3]);", po, po);
+      e.line("      const unsigned a0 = %s(d%d[2 * dp][0], d%d[2 * dp][1]), a1 = %s(d%d[2 * dp][2], d%d[2 * dp][3]);", po, n.id, n.id, po, n.id, n.id);
+      e.line("      const unsigned b0 = %s(d%d[2 * dp + 1][0], d%d[2 * dp + 1][1]), b1 = %s(d%d[2 * dp + 1][2], d%d[2 * dp + 1][3]);", po, n.id, n.id, po, n.id, n.id);
       e.line("      const auto r0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);");
       e.line("      const auto r1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);");
       e.line("      const unsigned x0 = r0[0], x1 = r1[0], x2 = r0[1], x3 = r1[1];");
@@ -995,6 +1068,34 @@ struct Gen {
       e.line("    }");
     }
     e.line("  }");
+  }
+
+  // Inputs read by the ops after the consuming dot, in the accumulators' layout: requested at the top of the
+  // kernel (they depend on nothing), used at the end.
+  void emit_dot_out_view_loads() {
+    for (size_t q = 0; q < A.views.size(); ++q) {
+      const RView& v = A.views[q];
+      if (v.cls != CLS_DOT_OUT) continue;
+      const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
+      e.line("  const %s* wp%zu = static_cast<const %s*>(a.in[%zu]) + (long long)blockIdx.x * %lldll + (long long)(row_ok ? mrow : M - 1) * %lldll;",
+             ty, q, ty, q, (long long)v.stride[0], (long long)v.stride[1]);
+      if (v.stride[2] == 0) {
+        e.line("  const float ws%zu = %s;", q, v.dtype == FS_F32 ? ("wp" + std::to_string(q) + "[0]").c_str()
+                                                 : ((v.dtype == FS_F16 ? "f16_lo(wp" : "bf16_lo(wp") + std::to_string(q) + "[0])").c_str());
+        continue;
+      }
+      e.line("  f32x4 w%zu[D2 / 16];", q);
+      if (v.dtype == FS_F32) {
+        e.line("  UNROLL for (int dt = 0; dt < D2 / 16; ++dt) w%zu[dt] = *reinterpret_cast<const f32x4*>(wp%zu + 16 * dt + 4 * lane);", q, q);
+      } else {
+        const char* lo = v.dtype == FS_F16 ? "f16_lo" : "bf16_lo";
+        const char* hi = v.dtype == FS_F16 ? "f16_hi" : "bf16_hi";
+        e.line("  UNROLL for (int dt = 0; dt < D2 / 16; ++dt) {");
+        e.line("    const u32x2 x = *reinterpret_cast<const u32x2*>(wp%zu + 16 * dt + 4 * lane);", q);
+        e.line("    w%zu[dt] = f32x4{%s(x[0]), %s(x[0]), %s(x[1]), %s(x[1])};", q, lo, hi, lo, hi);
+        e.line("  }");
+      }
+    }
   }
 
   void emit(std::string* kernel_name) {
@@ -1095,7 +1196,7 @@ struct Gen {
       e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     }
     if (mma) e.line("  __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
-    if (mma && A.mma_out >= 0) emit_mma_v_loads();
+    if (mma && A.mma_out >= 0) { emit_mma_v_loads(); emit_dot_out_view_loads(); }
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);
     std::vector<std::string> roff(A.views.size());
@@ -1234,6 +1335,7 @@ struct Gen {
       const char* ty = v.dtype == FS_F32 ? "float" : "unsigned short";
       const char* one = v.dtype == FS_F32 ? "p[0]" : v.dtype == FS_F16 ? "f16_lo(p[0])" : "bf16_lo(p[0])";
       if (v.cls == CLS_NONE) continue;     // an operand of a matrix-unit dot: read by the dot's own code
+      if (v.cls == CLS_DOT_OUT) continue;  // read in the accumulators' layout, at the top of the kernel
       // persistent form: an operand that does not depend on the row (a per-column vector, a
       // scalar) is loaded once, before the row loop
       bool invariant = persistent && !prefetched[q];      // (what is requested ahead is unpacked inside the loop, also when there is only one row)
@@ -1352,6 +1454,15 @@ struct Gen {
       } else if (n.op == ROP_DOT_MMA_OUT) {
         emit_mma_out(n);
         continue;                          // stores its result itself
+      } else if (n.cls == CLS_DOT_OUT) {
+        if (n.op == FS_DIVIDE && n.o[1].kind == OP_ROWB && !inv_done[n.o[1].index]) {
+          e.line("  const float inv%d = 1.0f / r%d;", n.o[1].index, n.o[1].index);
+          inv_done[n.o[1].index] = 1;
+        }
+        e.line("  f32x4 d%d[D2 / 16];", n.id);
+        e.line("  UNROLL for (int dt = 0; dt < D2 / 16; ++dt) UNROLL for (int i = 0; i < 4; ++i) d%d[dt][i] = %s;", n.id, expr(n).c_str());
+        if (n.out_ord >= 0) store_dot_out(n);
+        continue;
       } else if (n.op == ROP_DOT_OUTER) {
         // the full tile from a tiny contraction: sum over k of (row scalar) * (column vector)
         e.line("  float t%d[K][W];", n.id);

@@ -16,7 +16,21 @@ def _bases():
             graphs.multi_interest_pattern(2, 6, 6, 1), graphs.bias_gelu_bwd(8, 32), graphs.multi_tensor_momentum([(4, 8), (5,)]),
             graphs.sequence_pool((3, 5, 16), 1, "f32", True, "both"), graphs.sequence_pool((2, 3, 4, 8), 2, "bf16"),
             graphs.norm_over_trailing_dims((4, 3, 8)), graphs.max_abs_over_trailing_dims((2, 3, 4, 8), 3, "f16"),
-            graphs.clip_by_global_norm([(4, 8), (5,)], 1.0)]
+            graphs.clip_by_global_norm([(4, 8), (5,)], 1.0), _dots_with_an_epilogue()]
+
+
+def _dots_with_an_epilogue():
+    """dot -> exp -> row sum -> dot -> division by the row sum -> gate -> residual: the generated block-composed form
+    with ops after its second dot."""
+    g = graphs.Graph()
+    q = g.parameter("q", "f16", (2, 16, 32)); k = g.parameter("k", "f16", (2, 24, 32)); v = g.parameter("v", "f16", (2, 24, 32))
+    res = g.parameter("res", "f16", (2, 16, 32)); gate = g.parameter("gate", "f32", (32,))
+    e = g.exp(g.dot(q, k, transpose_b=True, dtype="f32"))
+    den = g.reduce_sum(e, -1)
+    o = g.dot(g.convert(e, "f16"), v, dtype="f32")
+    o = g.add(g.multiply(g.divide(o, g.row_broadcast(den, o)), g.col_broadcast(gate, o)), g.convert(res, "f32"))
+    g.output(g.convert(o, "f16"))
+    return g.ops
 
 
 def _mutate(rng, arr):

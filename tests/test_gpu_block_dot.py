@@ -108,3 +108,59 @@ def test_generated_and_hand_written_attention_agree():
     a, _ = check_against_oracle(ops, ins, "stitched", what="hand-written")
     b, _ = check_against_oracle(ops, ins, "generated", what="generated")
     assert np.abs(a[0] - b[0]).max() <= 2e-3
+
+
+def _epilogue_group(B, M, N, Kc, D, dtype, out_dtype):
+    """dot -> exp(s - max) -> dot on the un-normalised weights, then the epilogue on the [B, M, D] result:
+    division by the row sum (the deferred normalisation), a per-column gate, a residual, a per-row scale, tanh."""
+    g = graphs.Graph()
+    q, k, v = _qkv(g, B, M, N, Kc, D, dtype)
+    res = g.parameter("res", out_dtype, (B, M, D))
+    gate = g.parameter("gate", "f32", (D,))
+    rowscale = g.parameter("rowscale", "f32", (B, M))
+    s = g.multiply(g.dot(q, k, transpose_b=True, dtype="f32"), g.constant(Kc ** -0.5))
+    e = g.exp(g.subtract(s, g.row_broadcast(g.reduce_max(s, -1), s)))
+    den = g.reduce_sum(e, -1)
+    o = g.dot(g.convert(e, dtype), v, dtype="f32")
+    o = g.divide(o, g.row_broadcast(den, o))
+    o = g.multiply(o, g.col_broadcast(gate, o))
+    o = g.add(o, g.convert(res, "f32") if out_dtype != "f32" else res)
+    o = g.tanh(g.multiply(o, g.row_broadcast(rowscale, o)))
+    g.output(g.convert(o, out_dtype) if out_dtype != "f32" else o)
+    g.output(den)
+    return g.ops
+
+
+@pytest.mark.parametrize("B,M,N,Kc,D,dtype,out_dtype", [(4, 64, 64, 64, 64, "f16", "f16"), (3, 37, 52, 32, 32, "bf16", "bf16"),
+                                                        (2, 100, 36, 64, 128, "f16", "f32"), (5, 1, 8, 16, 32, "bf16", "bf16"),
+                                                        (2, 128, 128, 128, 64, "bf16", "f32")])
+def test_ops_after_the_consuming_dot(B, M, N, Kc, D, dtype, out_dtype):
+    announce(f"epilogue after the second dot {B}x{M}x{N} K={Kc} D={D} {dtype}->{out_dtype}")
+    ops = _epilogue_group(B, M, N, Kc, D, dtype, out_dtype)
+    with Plan(ops) as plan:
+        assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
+    ins = _inputs(B, M, N, Kc, D, dtype, extra=[((B, M, D), out_dtype), ((D,), "f32")])
+    r = np.random.Generator(np.random.PCG64(inputs.BASE_SEED + 23))
+    ins.append(inputs.round_to(r.uniform(0.5, 1.5, (B, M)), "f32"))
+    check_against_oracle(ops, ins, what="epilogue after the second dot")
+
+
+def test_dot_result_and_values_after_it_as_outputs():
+    # the second dot's result is itself an output (f32), a GELU of it a second one (16-bit), their sum with an
+    # f32 residual a third; the weights are sigmoids
+    B, M, N, Kc, D = 3, 48, 40, 32, 64
+    announce("three outputs after the second dot")
+    g = graphs.Graph()
+    q, k, v = _qkv(g, B, M, N, Kc, D, "f16")
+    res = g.parameter("res", "f32", (B, M, D))
+    p = g.logistic(g.multiply(g.dot(q, k, transpose_b=True, dtype="f32"), g.constant(Kc ** -0.5)))
+    o = g.dot(g.convert(p, "f16"), v, dtype="f32")
+    g.output(o)
+    o3 = g.multiply(g.multiply(o, o), o)
+    inner = g.multiply(g.add(o, g.multiply(o3, g.constant(graphs.GELU_K1))), g.constant(graphs.GELU_K0))
+    h = g.multiply(g.multiply(o, g.constant(0.5)), g.add(g.tanh(inner), g.constant(1.0)))      # the tanh-form GELU, spelled out
+    g.output(g.convert(h, "f16"))
+    g.output(g.add(h, res))
+    with Plan(g.ops) as plan:
+        assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
+    check_against_oracle(g.ops, _inputs(B, M, N, Kc, D, "f16", extra=[((B, M, D), "f32")], v_scale=0.25), what="outputs after the second dot")
