@@ -144,8 +144,8 @@ typedef enum {
                                 a[B,M,K] . b[B,N,K]^T (16-bit, K 16..128, tile up to 128 x 128) -> any
                                 elementwise ops and row reductions on the tile -> optionally a second dot
                                 with v[B,N,D], its operand handed over through LDS -> optionally
-                                elementwise ops on the [B,M,D] result (operands: such values, per-row
-                                values of the tile, constants, inputs seen as [B,M,D]; no reduction);
+                                elementwise ops and row reductions on the [B,M,D] result (operands: such
+                                values, per-row values, constants, inputs seen as [B,M,D]);
                                 what the hand-written FS_SCHED_BDOT_SOFTMAX kernel does not match */
 } fs_schedule;
 

@@ -56,6 +56,7 @@ struct RNode {
   std::vector<int> dot_row, dot_full;   // ROP_DOT_OUTER: view pairs per k; ROP_DOT_REDUCE: dot_full[0]
   float gelu[3] = {0.f, 0.f, 0.f};      // EW_OP_GELU_TANH: mul, a0, a1 of mul*h / (1 + exp2(h*(a0 + a1*h*h)))
   int out_ord = -1, out_dtype = FS_F32;
+  bool over_dot_out = false;            // a row reduction over the [B, M, D] result of a consuming dot
 };
 struct RView {
   int param = -1, dtype = FS_F32, cls = CLS_FULL;
@@ -512,11 +513,12 @@ struct Analysis {
         if (!operand(col_base[i], CLS_FULL, &r.o[0])) return false;
         ++n_col;
       } else if (is_reduce(k)) {
-        if (reads_dot_out(i)) return fail("generated row schedule: a reduction over the result of a consuming dot");
+        const bool after_dot = reads_dot_out(i);      // over the D columns of the consuming dot's result: one value per row all the same
         if (x.axis != rank - 1 || !shape_is_row(x)) return fail("generated row schedule: reduction not over the last dim of the group's shape");
         r.cls = CLS_ROW; r.op = k; r.nop = 1;
+        r.over_dot_out = after_dot;
         cls[i] = CLS_ROW;
-        if (!operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
+        if (after_dot ? !operand_dot_out(x.operand[0], &r.o[0]) : !operand(x.operand[0], CLS_FULL, &r.o[0])) return false;
         ++n_reduce;
       } else if (reads_dot_out(i)) {
         // the epilogue around the consuming dot: elementwise on its [B, M, D] result, in the accumulators' layout
@@ -1430,7 +1432,14 @@ struct Gen {
           e.line("  if (row_ok) UNROLL for (int k = 0; k < K; ++k) UNROLL for (int j = 0; j < W; ++j) ca%d[k][j] += (double)%s;", n.id, x.c_str());
         continue;
       }
-      if (reduce) {
+      if (reduce && n.over_dot_out) {
+        const bool sum = n.op == FS_REDUCE_SUM;
+        const std::string x = opnd(n.o[0], CLS_DOT_OUT);
+        e.line("  float r%d = %s;", n.id, sum ? "0.0f" : "-__builtin_inff()");
+        e.line("  UNROLL for (int dt = 0; dt < D2 / 16; ++dt) UNROLL for (int i = 0; i < 4; ++i) r%d = %s;", n.id,
+               sum ? ("r" + std::to_string(n.id) + " + " + x).c_str() : ("fmaxf(r" + std::to_string(n.id) + ", " + x + ")").c_str());
+        combine(n.id, sum);
+      } else if (reduce) {
         const bool sum = n.op == FS_REDUCE_SUM;
         const std::string x = opnd(n.o[0], CLS_FULL);
         e.line("  float r%d = %s;", n.id, sum ? "0.0f" : "-__builtin_inff()");

@@ -647,8 +647,8 @@ def test_block_dot_groups_are_generated_or_refused_with_a_reason():
         assert "dot_1" in p.describe() and "dot_2" in p.describe() and "MFMA" in p.describe()
     assert "matrix unit" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group("f32"))            # fp32 dots have no MFMA path
     assert "[B, N, K]" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(transpose_b=False))   # contraction must be contiguous
-    # elementwise ops after the consuming dot run on its accumulators (same kernel, same LDS); a reduction over
-    # its result does not
+    # elementwise ops after the consuming dot run on its accumulators (same kernel, same LDS), and so do
+    # reductions over its rows; a reduction over another dim of its result does not
     with Plan(_dot_group(after=True)) as p:
         info = p.info()
         assert info["schedule"] == "block_dot" and info["n_kernels"] == 1 and info["lds_bytes"] == 2 * 64 * (64 + 8) + 2 * 64 * (64 + 8)
@@ -656,7 +656,13 @@ def test_block_dot_groups_are_generated_or_refused_with_a_reason():
     q = g.parameter("q", "f16", (2, 32, 64)); k = g.parameter("k", "f16", (2, 48, 64)); v = g.parameter("v", "f16", (2, 48, 64))
     o = g.dot(g.convert(g.logistic(g.dot(q, k, transpose_b=True, dtype="f32")), "f16"), v, dtype="f32")
     g.output(g.reduce_sum(o, -1))
-    assert "reduction over the result of a consuming dot" in _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
+    with Plan(g.ops) as p:
+        assert p.info()["schedule"] == "block_dot" and p.info()["n_kernels"] == 1
+    g = Graph()
+    q = g.parameter("q", "f16", (2, 32, 64)); k = g.parameter("k", "f16", (2, 48, 64)); v = g.parameter("v", "f16", (2, 48, 64))
+    o = g.dot(g.convert(g.logistic(g.dot(q, k, transpose_b=True, dtype="f32")), "f16"), v, dtype="f32")
+    g.output(g.reduce_sum(o, 1))
+    assert "not over the last dim" in _expect(binding.FS_ERR_UNSUPPORTED, g.ops)
     # an operand of the ops after the dot with the wrong shape ([B, M, N] where [B, M, D] is needed)
     g = Graph()
     q = g.parameter("q", "f16", (2, 32, 64)); k = g.parameter("k", "f16", (2, 48, 64)); v = g.parameter("v", "f16", (2, 48, 32))

@@ -164,3 +164,32 @@ def test_dot_result_and_values_after_it_as_outputs():
     with Plan(g.ops) as plan:
         assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
     check_against_oracle(g.ops, _inputs(B, M, N, Kc, D, "f16", extra=[((B, M, D), "f32")], v_scale=0.25), what="outputs after the second dot")
+
+
+@pytest.mark.parametrize("B,M,N,D,dtype", [(4, 64, 64, 64, "f16"), (3, 37, 52, 32, "bf16"), (2, 128, 100, 128, "bf16")])
+def test_layernorm_after_the_second_dot(B, M, N, D, dtype):
+    # softmax attention, a residual added to its result, LayerNorm over the D columns with gamma and beta: the row
+    # reductions after the second dot run over the accumulators; the row means are a second output
+    announce(f"attention + residual + LayerNorm {B}x{M}x{N}x{D} {dtype}")
+    g = graphs.Graph()
+    q, k, v = _qkv(g, B, M, N, D, D, dtype)
+    res = g.parameter("res", dtype, (B, M, D))
+    gamma = g.parameter("gamma", "f32", (D,))
+    beta = g.parameter("beta", "f32", (D,))
+    s = g.multiply(g.dot(q, k, transpose_b=True, dtype="f32"), g.constant(D ** -0.5))
+    e = g.exp(g.subtract(s, g.row_broadcast(g.reduce_max(s, -1), s)))
+    p = g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), e))
+    h = g.add(g.dot(g.convert(p, dtype), v, dtype="f32"), g.convert(res, "f32"))
+    mean = g.divide(g.reduce_sum(h, -1), g.constant(float(D)))
+    c = g.subtract(h, g.row_broadcast(mean, h))
+    var = g.divide(g.reduce_sum(g.multiply(c, c), -1), g.constant(float(D)))
+    y = g.multiply(c, g.row_broadcast(g.rsqrt(g.add(var, g.constant(1e-5))), c))
+    y = g.add(g.multiply(y, g.col_broadcast(gamma, y)), g.col_broadcast(beta, y))
+    g.output(g.convert(y, dtype))
+    g.output(mean)
+    with Plan(g.ops) as plan:
+        assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
+    ins = _inputs(B, M, N, D, D, dtype, extra=[((B, M, D), dtype)])
+    r = np.random.Generator(np.random.PCG64(inputs.BASE_SEED + 24))
+    ins += [inputs.round_to(1.0 + r.normal(0, 0.02, (D,)), "f32"), inputs.round_to(r.normal(0, 0.02, (D,)), "f32")]
+    check_against_oracle(g.ops, ins, what="attention + residual + LayerNorm")
