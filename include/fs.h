@@ -141,7 +141,7 @@ typedef enum {
                                 up to 16 parts that share no computed value, each of one shape
                                 (generated form only): one kernel, a run of workgroups per part */
   FS_SCHED_BLOCK_DOT = 5     /* generated block composition around batched dots on MFMA (Sections 5.1, 5.3):
-                                a[B,M,K] . b[B,N,K]^T (16-bit, K 16..128, tile up to 128 x 128) -> any
+                                a[B,M,K] . b, b stored [B,N,K] or [B,K,N] (16-bit, K 16..128, tile up to 128 x 128) -> any
                                 elementwise ops and row reductions on the tile -> optionally a second dot
                                 with v[B,N,D], its operand handed over through LDS -> optionally
                                 elementwise ops and row reductions on the [B,M,D] result (operands: such

@@ -84,6 +84,7 @@ struct Analysis {
   int mma_dtype = FS_F16;                // dtype of the dots' operands
   int64_t mma_k = 0, mma_d = 0;          // contraction length of the producing dot, result width of the consuming one
   int mma_va = -1, mma_vb = -1, mma_vv = -1;   // views (pointer only) of a, b and v
+  bool mma_b_kn = false;                 // the producing dot's second operand is stored [B, K, N] (contraction along its rows)
 
   explicit Analysis(const Graph& gr) : g(gr) {}
   bool fail(const std::string& m) { err = m; return false; }
@@ -296,14 +297,13 @@ struct Analysis {
       if (!dense_param(ia, &pa)) return fail("generated row schedule: first operand of a producing dot must be a group input");
       if (mma_in >= 0) return fail("generated row schedule: more than one producing dot with a real contraction");
       if (a.dtype == FS_F32 || b.dtype != a.dtype) return fail("generated row schedule: a dot with contraction >= 16 needs 16-bit operands of one dtype (the matrix unit)");
-      if (!bt) return fail("generated row schedule: the second operand of a producing dot must be stored [B, N, K] (contraction along the last dim)");
       if (Kc % 8 != 0 || Kc > 128) return fail("generated row schedule: producing dot contraction must be a multiple of 8 up to 128");
       if (a.shape[0] != S[0] || a.shape[1] != S[1] || Nout != S[2]) return fail("generated row schedule: dot shape differs from the group's");
       if (x.dtype != FS_F32) return fail("generated row schedule: dots accumulate in f32");
       if (mma_out >= 0 && mma_dtype != a.dtype) return fail("generated row schedule: the two dots use different operand dtypes");
       r->op = ROP_DOT_MMA_IN; r->cls = CLS_FULL; r->nop = 0;
       cls[i] = CLS_FULL;
-      mma_in = i; mma_dtype = a.dtype; mma_k = Kc;
+      mma_in = i; mma_dtype = a.dtype; mma_k = Kc; mma_b_kn = !bt;
       mma_va = view_index(pa, none, CLS_NONE);
       mma_vb = view_index(pb, none, CLS_NONE);
       return true;
@@ -854,9 +854,15 @@ struct Gen {
       mma_lds_bytes = r.total_bytes;
     }
     // the producing dot's second operand, shared by the workgroup's wavefronts: rows of whole 32-steps plus 8
-    mma_kp = ((int)((A.mma_k + 31) / 32)) * 32 + 8;
     mma_k_offset = (mma_lds_bytes + 15) / 16 * 16;
-    mma_lds_bytes = mma_k_offset + 2 * (int64_t)K * 16 * mma_kp;
+    if (A.mma_b_kn) {
+      // stored [K, N]: in LDS as stored, whole 32-steps of rows (zero beyond K), read back transposed like v
+      mma_kp = padded_row(K * 16, 8);
+      mma_lds_bytes = mma_k_offset + 2 * (int64_t)((A.mma_k + 31) / 32) * 32 * mma_kp;
+    } else {
+      mma_kp = ((int)((A.mma_k + 31) / 32)) * 32 + 8;
+      mma_lds_bytes = mma_k_offset + 2 * (int64_t)K * 16 * mma_kp;
+    }
     return true;
   }
   // Row length in 16-bit elements of an LDS tile that is read four rows at a time, `piece` bytes per lane and four
@@ -966,6 +972,21 @@ struct Gen {
     e.line("  }");
   }
 
+  // The producing dot's second operand when it is stored [B, KC, N]: every thread's pieces of the batch element's
+  // slab are requested at the top of the kernel (8 elements where rows start on 16 bytes, else 4).
+  void emit_mma_b_loads() {
+    const int KC = (int)A.mma_k, VE = A.S[2] % 8 == 0 ? 8 : 4, CHB = (int)((A.S[2] + VE - 1) / VE), BTOT = KC * CHB, NB = (BTOT + wg - 1) / wg;
+    e.line("  constexpr int VE = %d, CHB = %d, BTOT = %d, NB = %d;", VE, CHB, BTOT, NB);
+    e.line("  %s breg[NB];", VE == 8 ? "u32x4" : "u32x2");
+    e.line("  {");
+    e.line("    const unsigned short* bb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * %lldll;", A.mma_vb, (long long)(A.mma_k * A.S[2]));
+    e.line("    UNROLL for (int i = 0; i < NB; ++i) {");
+    e.line("      int ci = (int)threadIdx.x + i * %d; if (ci > BTOT - 1) ci = BTOT - 1;", wg);
+    e.line("      breg[i] = *reinterpret_cast<const %s*>(bb + (long long)(ci / CHB) * N + (ci %% CHB) * VE);", VE == 8 ? "u32x4" : "u32x2");
+    e.line("    }");
+    e.line("  }");
+  }
+
   // The producing dot, transposed: tile k = b_k(16 x KC) . a^T, so the lane holds t[k][j] = row `row`,
   // column 16k + 4*lane + j.  Fragments of a come straight from global memory in MFMA layout (8 consecutive
   // contraction indices of one row: one 16-byte load).  Every 16-row tile of b is loaded that way by ONE
@@ -973,33 +994,49 @@ struct Gen {
   // dot's second operand goes to LDS as stored behind the same barrier.
   void emit_mma_in(const RNode& n) {
     const int KC = (int)A.mma_k, KS = (KC + 31) / 32, KT = (K + NQ - 1) / NQ;
+    const bool kn = A.mma_b_kn;
     const char* mm = A.mma_dtype == FS_F16 ? "mma_f16" : "mma_bf16";
     e.line("  float t%d[K][W];", n.id);
     e.line("  {");
     e.line("    constexpr int KC = %d, KS = %d, KT = %d, KP = %d;", KC, KS, KT, mma_kp);
     e.line("    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));");
     e.line("    const unsigned short* pa = static_cast<const unsigned short*>(a.in[%d]) + row * KC;", A.mma_va);
-    e.line("    const unsigned short* pb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * KC;", A.mma_vb);
-    e.line("    unsigned short* ksh = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [K * 16][KP]", (long long)mma_k_offset);
-    e.line("    u32x4 qf[KS], kf[KT][KS];");
+    if (!kn) e.line("    const unsigned short* pb = static_cast<const unsigned short*>(a.in[%d]) + (long long)blockIdx.x * N * KC;", A.mma_vb);
+    e.line("    unsigned short* ksh = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // %s", (long long)mma_k_offset,
+           kn ? "[KS * 32][KP]: as stored, rows = contraction index" : "[K * 16][KP]");
+    e.line("    u32x4 qf[KS];");
     e.line("    UNROLL for (int ks = 0; ks < KS; ++ks) {");
     e.line("      const int k0 = ks * 32 + 8 * lane;");
     e.line("      qf[ks] = k0 < KC ? *reinterpret_cast<const u32x4*>(pa + k0) : u32x4{0u, 0u, 0u, 0u};");
     e.line("    }");
-    e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
-    e.line("      const int kt = wv + j * %d;", NQ);
-    e.line("      int nrow = 16 * kt + lane16; if (nrow > N - 1) nrow = N - 1;");
-    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) {");
-    e.line("        const int k0 = ks * 32 + 8 * lane;");
-    e.line("        kf[j][ks] = u32x4{0u, 0u, 0u, 0u};");
-    e.line("        if (kt < K && k0 < KC) kf[j][ks] = *reinterpret_cast<const u32x4*>(pb + (long long)nrow * KC + k0);");
-    e.line("      }");
-    e.line("    }");
-    e.line("    asm volatile(\"\" ::: \"memory\");     // every request above is issued before the first wait below");
-    e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
-    e.line("      const int kt = wv + j * %d;", NQ);
-    e.line("      if (kt < K) { UNROLL for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<u32x4*>(ksh + (16 * kt + lane16) * KP + ks * 32 + 8 * lane) = kf[j][ks]; }");
-    e.line("    }");
+    if (!kn) {
+      e.line("    u32x4 kf[KT][KS];");
+      e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
+      e.line("      const int kt = wv + j * %d;", NQ);
+      e.line("      int nrow = 16 * kt + lane16; if (nrow > N - 1) nrow = N - 1;");
+      e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) {");
+      e.line("        const int k0 = ks * 32 + 8 * lane;");
+      e.line("        kf[j][ks] = u32x4{0u, 0u, 0u, 0u};");
+      e.line("        if (kt < K && k0 < KC) kf[j][ks] = *reinterpret_cast<const u32x4*>(pb + (long long)nrow * KC + k0);");
+      e.line("      }");
+      e.line("    }");
+      e.line("    asm volatile(\"\" ::: \"memory\");     // every request above is issued before the first wait below");
+      e.line("    UNROLL for (int j = 0; j < KT; ++j) {");
+      e.line("      const int kt = wv + j * %d;", NQ);
+      e.line("      if (kt < K) { UNROLL for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<u32x4*>(ksh + (16 * kt + lane16) * KP + ks * 32 + 8 * lane) = kf[j][ks]; }");
+      e.line("    }");
+    } else {
+      e.line("    (void)wv;");
+      e.line("    asm volatile(\"\" ::: \"memory\");     // every request above is issued before the first wait below");
+      // the slab as stored; what the matrix instructions read beyond it (columns N .. 16 K of every row, rows KC .. 32 KS) is zero
+      e.line("    UNROLL for (int i = 0; i < NB; ++i) {");
+      e.line("      const int ci = (int)threadIdx.x + i * %d;", wg);
+      e.line("      if (ci < BTOT) *reinterpret_cast<%s*>(ksh + (ci / CHB) * KP + (ci %% CHB) * VE) = breg[i];", A.S[2] % 8 == 0 ? "u32x4" : "u32x2");
+      e.line("    }");
+      e.line("    constexpr int PADC = (16 * K - N) / 4;         // 4-element pieces right of the slab, per row");
+      e.line("    for (int i = threadIdx.x; i < KC * PADC; i += %d) *reinterpret_cast<u32x2*>(ksh + (i / (PADC > 0 ? PADC : 1)) * KP + N + 4 * (i %% (PADC > 0 ? PADC : 1))) = u32x2{0u, 0u};", wg);
+      e.line("    for (int i = threadIdx.x; i < (32 * KS - KC) * 4 * K; i += %d) *reinterpret_cast<u32x2*>(ksh + (KC + i / (4 * K)) * KP + 4 * (i %% (4 * K))) = u32x2{0u, 0u};", wg);
+    }
     if (A.mma_out >= 0) {
       e.line("    unsigned short* vsh = reinterpret_cast<unsigned short*>(lds_pool + %lld);   // [NKP * 16][VP], rows beyond N zero", (long long)mma_vt_offset);
       e.line("    UNROLL for (int i = 0; i < NV; ++i) {");
@@ -1011,9 +1048,11 @@ struct Gen {
       e.line("    }");
     }
     e.line("    __syncthreads();");
+    if (kn) e.line("    const unsigned short* blane = ksh + (8 * lane + (lane16 >> 2)) * KP + 4 * (lane16 & 3);   // the transposing read: rows 8 lane .. + 7 of a 32-step");
     e.line("    UNROLL for (int k = 0; k < K; ++k) {");
     e.line("      u32x4 kr[KS];");
-    e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) kr[ks] = *reinterpret_cast<const u32x4*>(ksh + (16 * k + lane16) * KP + ks * 32 + 8 * lane);");
+    if (kn) e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) kr[ks] = lds_read_transposed(blane + 32 * ks * KP + 16 * k, 4 * KP);");
+    else e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) kr[ks] = *reinterpret_cast<const u32x4*>(ksh + (16 * k + lane16) * KP + ks * 32 + 8 * lane);");
     e.line("      f32x4 acc = {0.f, 0.f, 0.f, 0.f};");
     e.line("      UNROLL for (int ks = 0; ks < KS; ++ks) acc = %s(kr[ks], qf[ks], acc);", mm);
     e.line("      UNROLL for (int j = 0; j < W; ++j) t%d[k][j] = acc[j];", n.id);
@@ -1198,6 +1237,7 @@ struct Gen {
       e.line("  if (!row_ok) row = %s;   // idle lanes redo the last row and store nothing: cross-lane steps need every lane", row_last);
     }
     if (mma) e.line("  __shared__ __attribute__((aligned(16))) unsigned char lds_pool[%lld];", (long long)mma_lds_bytes);
+    if (mma && A.mma_b_kn) emit_mma_b_loads();
     if (mma && A.mma_out >= 0) { emit_mma_v_loads(); emit_dot_out_view_loads(); }
     // which views need the row's coordinates
     splat.assign(A.views.size(), 0);

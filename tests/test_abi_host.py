@@ -646,7 +646,10 @@ def test_block_dot_groups_are_generated_or_refused_with_a_reason():
         assert info["lds_bytes"] == 2 * 64 * (64 + 8) + 2 * 64 * (64 + 8)
         assert "dot_1" in p.describe() and "dot_2" in p.describe() and "MFMA" in p.describe()
     assert "matrix unit" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group("f32"))            # fp32 dots have no MFMA path
-    assert "[B, N, K]" in _expect(binding.FS_ERR_UNSUPPORTED, _dot_group(transpose_b=False))   # contraction must be contiguous
+    # the second operand stored [B, K, N] (contraction along its rows): kept in LDS as stored, whole 32-steps of rows
+    # (64) of whole 16-column tiles (48 -> 64 columns, + 8 halves of padding)
+    with Plan(_dot_group(transpose_b=False)) as p:
+        assert p.info()["schedule"] == "block_dot" and p.info()["lds_bytes"] == 2 * 64 * (64 + 8) + 2 * 64 * (64 + 8)
     # elementwise ops after the consuming dot run on its accumulators (same kernel, same LDS), and so do
     # reductions over its rows; a reduction over another dim of its result does not
     with Plan(_dot_group(after=True)) as p:

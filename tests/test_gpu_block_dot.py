@@ -193,3 +193,28 @@ def test_layernorm_after_the_second_dot(B, M, N, D, dtype):
     r = np.random.Generator(np.random.PCG64(inputs.BASE_SEED + 24))
     ins += [inputs.round_to(1.0 + r.normal(0, 0.02, (D,)), "f32"), inputs.round_to(r.normal(0, 0.02, (D,)), "f32")]
     check_against_oracle(g.ops, ins, what="attention + residual + LayerNorm")
+
+
+@pytest.mark.parametrize("B,M,N,Kc,D,dtype", [(4, 64, 64, 64, 64, "f16"), (3, 37, 52, 40, 32, "bf16"), (2, 100, 36, 72, 64, "f16"),
+                                              (3, 16, 128, 128, 128, "bf16"), (2, 1, 4, 16, 32, "f16"), (2, 50, 120, 24, 0, "f16")])
+def test_second_operand_stored_k_by_n(B, M, N, Kc, D, dtype):
+    # x[B,M,K] . w[B,K,N] (the contraction runs along w's rows, as a weight matrix is stored) -> scale -> softmax ->
+    # (. v, or the probabilities themselves when D == 0): w sits in LDS as stored and is read back transposed
+    announce(f"second operand [B,K,N] {B}x{M}x{N} K={Kc} D={D} {dtype}")
+    g = graphs.Graph()
+    x = g.parameter("x", dtype, (B, M, Kc))
+    w = g.parameter("w", dtype, (B, Kc, N))
+    s = g.multiply(g.dot(x, w, dtype="f32"), g.constant(Kc ** -0.5))
+    e = g.exp(g.subtract(s, g.row_broadcast(g.reduce_max(s, -1), s)))
+    p = g.divide(e, g.row_broadcast(g.reduce_sum(e, -1), e))
+    r = np.random.Generator(np.random.PCG64(inputs.BASE_SEED + 25))
+    ins = [inputs.round_to(r.normal(0, 1, (B, M, Kc)), dtype), inputs.round_to(r.normal(0, 1, (B, Kc, N)), dtype)]
+    if D:
+        v = g.parameter("v", dtype, (B, N, D))
+        g.output(g.convert(g.dot(g.convert(p, dtype), v, dtype="f32"), dtype))
+        ins.append(inputs.round_to(r.normal(0, 1, (B, N, D)), dtype))
+    else:
+        g.output(p)
+    with Plan(g.ops) as plan:
+        assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
+    check_against_oracle(g.ops, ins, what="second operand stored [B,K,N]")
