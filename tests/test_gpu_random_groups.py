@@ -126,3 +126,25 @@ def test_random_packed_elementwise_parts(seed):
     with Plan(ops) as p:
         assert p.info()["schedule"] == "elementwise" and p.info()["n_kernels"] == 1
     check_against_oracle(ops, ins, what=f"random packed parts {seed}")
+
+
+DOT_SHAPES = [(3, 64, 64, 64, 64), (2, 37, 52, 40, 32), (4, 16, 128, 32, 128), (2, 100, 36, 72, 64), (5, 1, 8, 16, 32),
+              (2, 128, 128, 128, 64), (3, 50, 20, 24, 32), (2, 33, 100, 64, 128)]
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_groups_around_two_dots(seed):
+    """dot -> random middle section -> dot -> random epilogue (elementwise ops and row reductions on the second
+    dot's result), the first dot's second operand stored either way, f16 and bf16: all through the generated
+    block-composed kernel (the hand-written attention kernel is not asked), one kernel each."""
+    import numpy as np
+    rng = random.Random(12000 + seed)
+    B, M, N, Kc, D = DOT_SHAPES[seed % len(DOT_SHAPES)]
+    dtype = ["f16", "bf16"][seed % 2]
+    ops, params = graphs.random_dot_group(rng, B, M, N, Kc, D, dtype)
+    r = np.random.Generator(np.random.PCG64(inputs.BASE_SEED + 400 + seed))
+    ins = [inputs.round_to(r.normal(0.0, 1.0, shape), dt) for shape, dt in params]
+    announce(f"random group around two dots, seed {seed} {B}x{M}x{N} K={Kc} D={D} {dtype}: {len(ops)} ops")
+    with Plan(ops, "generated") as plan:
+        assert plan.info()["schedule"] == "block_dot" and plan.info()["n_kernels"] == 1
+    check_against_oracle(ops, ins, "generated", what=f"random dot group {seed}")

@@ -1008,6 +1008,82 @@ def random_program(rng, rows, cols, n_ops=30):
     return kept, [(rows, cols), (rows, cols), (rows,), (cols,)]
 
 
+def random_dot_group(rng, B, M, N, Kc, D, dtype="f16"):
+    """A random group around two batched dots: x[B,M,K] . w (stored [B,N,K] or [B,K,N]) -> a random middle section
+    on the [B,M,N] tile that ends in bounded weights (softmax, scaled sigmoid or normalised relu^2) -> . v[B,N,D]
+    -> a random epilogue on the [B,M,D] result (residual, per-column gate, per-row values of either section, row
+    reductions over D, tanh).  Outputs: the last value, a per-row value, sometimes the second dot's own result.
+    `rng` is a random.Random.  Returns (ops, [(shape, dtype) per parameter])."""
+    g = Graph()
+    kn = rng.random() < 0.5
+    x = g.parameter("x", dtype, (B, M, Kc))
+    w = g.parameter("w", dtype, (B, Kc, N) if kn else (B, N, Kc))
+    v = g.parameter("v", dtype, (B, N, D))
+    bias = g.parameter("bias", "f32", (N,))
+    temp = g.parameter("temp", "f32", (B, M))
+    res = g.parameter("res", dtype, (B, M, D))
+    gate = g.parameter("gate", "f32", (D,))
+    params = [((B, M, Kc), dtype), ((B, Kc, N) if kn else (B, N, Kc), dtype), ((B, N, D), dtype), ((N,), "f32"), ((B, M), "f32"),
+              ((B, M, D), dtype), ((D,), "f32")]
+    s = g.multiply(g.dot(x, w, transpose_b=not kn, dtype="f32"), g.constant(Kc ** -0.5))
+    rows = [g.tanh(temp)]
+    for _ in range(rng.randint(0, 3)):
+        kind = rng.choice(["bias", "temp", "tanh", "const"])
+        if kind == "bias":
+            s = g.add(s, g.col_broadcast(bias, s))
+        elif kind == "temp":
+            s = g.multiply(s, g.row_broadcast(rows[0], s))
+        elif kind == "tanh":
+            s = g.multiply(g.tanh(s), g.constant(2.0))
+        else:
+            s = g.add(s, g.constant(rng.choice([0.5, -1.0])))
+    form = rng.choice(["softmax", "sigmoid", "relu2"])
+    if form == "softmax":
+        smax = g.reduce_max(s, -1)
+        e = g.exp(g.subtract(s, g.row_broadcast(smax, s)))
+        den = g.reduce_sum(e, -1)
+        rows += [smax, g.log(den)]
+        p = g.divide(e, g.row_broadcast(den, e))
+    elif form == "sigmoid":
+        p = g.multiply(g.logistic(s), g.constant(1.0 / N))
+        rows.append(g.reduce_sum(p, -1))
+    else:
+        r = g.maximum(s, g.constant(0.0))
+        r2 = g.add(g.multiply(r, r), g.constant(1e-2))
+        den = g.reduce_sum(r2, -1)
+        rows.append(g.divide(den, g.constant(float(N))))
+        p = g.divide(r2, g.row_broadcast(den, r2))
+    o = g.dot(g.convert(p, dtype), v, dtype="f32")
+    dot_result = o
+    resf = g.convert(res, "f32")
+    for _ in range(rng.randint(1, 6)):
+        kind = rng.choice(["res", "gate", "row", "tanh", "center", "const", "scale_by_max"])
+        if kind == "res":
+            o = g.add(o, resf)
+        elif kind == "gate":
+            o = g.multiply(o, g.col_broadcast(gate, o))
+        elif kind == "row":
+            o = getattr(g, rng.choice(["add", "multiply"]))(o, g.row_broadcast(g.tanh(rng.choice(rows)), o))
+        elif kind == "tanh":
+            o = g.tanh(o)
+        elif kind == "center":
+            mean = g.divide(g.reduce_sum(o, -1), g.constant(float(D)))
+            rows.append(mean)
+            o = g.subtract(o, g.row_broadcast(mean, o))
+        elif kind == "const":
+            o = getattr(g, rng.choice(["add", "multiply", "maximum"]))(o, g.constant(rng.choice([0.5, -0.75, 1.5])))
+        else:
+            mx = g.reduce_max(g.tanh(o), -1)
+            rows.append(mx)
+            o = g.multiply(o, g.row_broadcast(g.add(mx, g.constant(1.5)), o))
+    out_dtype = rng.choice([dtype, "f32"])
+    g.output(o if out_dtype == "f32" else g.convert(o, out_dtype))
+    g.output(rows[-1])
+    if rng.random() < 0.4 and o != dot_result:
+        g.output(dot_result)
+    return g.ops, params
+
+
 def random_elementwise_parts(rng, n_parts=None):
     """Several independent all-elementwise computations of different shapes and dtypes in one op
     list (the kernel packing case): per part two full operands, a per-column operand broadcast in,
