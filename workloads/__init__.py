@@ -75,8 +75,9 @@ def _ln_stats_inputs(rows, cols, dtype="f32"):
 # two full outputs packed over the same rows), and the momentum update of a Transformer layer's eight
 # parameter tensors as one group of independent parts of different shapes, and sequence pooling
 # ([B, S, H] summed over S: column sums per run of rows), and two groups around dots on the matrix unit: the
-# attention kernel with a key mask, gate, residual and log-sum-exp output, and a dot -> logistic -> dot group
-# that only the generated block-composed kernel takes.  Not benchmark configs, so not in CONFIGS.
+# attention kernel with a key mask, gate, residual and log-sum-exp output, a dot -> logistic -> dot group
+# that only the generated block-composed kernel takes, and attention with the normalisation, a residual and a
+# LayerNorm after the second dot (keys stored [B, D, Sk]).  Not benchmark configs, so not in CONFIGS.
 EXTRA_GROUPS = [
     Config(6, "adam_update_packed", graphs.adam_update, inputs.adam_update,
            dict(shape=(16384, 1024)), dict(shape=(129, 512)), "f32"),
@@ -102,5 +103,7 @@ EXTRA_GROUPS = [
            dict(batch=3, sq=40, sk=72, dim=64, dtype="f16", causal=True, mask="key", gate=True, residual=True, lse=True), "f16"),
     Config(16, "sigmoid_attention", graphs.sigmoid_attention, inputs.sigmoid_attention,
            dict(batch=512, sq=64, sk=64, kc=64, dim=64, dtype="bf16"), dict(batch=3, sq=40, sk=72, kc=64, dim=64, dtype="bf16"), "bf16"),
+    Config(17, "attention_residual_layernorm", graphs.attention_residual_layernorm, inputs.attention_residual_layernorm,
+           dict(batch=512, sq=64, sk=64, dim=64, dtype="f16"), dict(batch=3, sq=40, sk=72, dim=64, dtype="f16"), "f16"),
 ]
 BY_NAME = {c.name: c for c in CONFIGS + EXTRA_GROUPS}

@@ -280,6 +280,27 @@ def sigmoid_attention(batch, sq, sk, kc, dim, dtype="bf16"):
     return g.ops
 
 
+def attention_residual_layernorm(batch, sq, sk, dim, dtype="f16", eps=1e-5):
+    """Softmax attention whose weights are normalised after the second dot (o = (exp(s - max) v) / sum), a residual,
+    and LayerNorm over the head dim with gamma and beta: dot -> elementwise / reductions -> dot -> elementwise /
+    reductions, one group.  x is stored [B, Sq, D], the keys as a weight matrix is, [B, D, Sk]."""
+    g = Graph()
+    q = g.parameter("q", dtype, (batch, sq, dim))
+    kt = g.parameter("kt", dtype, (batch, dim, sk))
+    v = g.parameter("v", dtype, (batch, sk, dim))
+    res = g.parameter("res", dtype, (batch, sq, dim))
+    gamma = g.parameter("gamma", "f32", (dim,))
+    beta = g.parameter("beta", "f32", (dim,))
+    s = g.multiply(g.dot(q, kt, transpose_b=False, dtype="f32"), g.constant(dim ** -0.5))
+    e = g.exp(g.subtract(s, g.row_broadcast(g.reduce_max(s, -1), s)))
+    den = g.reduce_sum(e, -1)
+    o = g.dot(g.convert(e, dtype), v, transpose_b=False, dtype="f32")
+    h = g.add(g.divide(o, g.row_broadcast(den, o)), g.convert(res, "f32"))
+    y = _layernorm_tail(g, h, gamma, beta, eps)
+    g.output(g.convert(y, dtype), "y")
+    return g.ops
+
+
 GELU_K0 = 0.7978845608028654   # sqrt(2/pi)
 GELU_K1 = 0.044715
 

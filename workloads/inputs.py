@@ -95,6 +95,13 @@ def sigmoid_attention(batch, sq, sk, kc, dim, dtype="bf16", seed_offset=16):
             round_to(r.normal(0.0, 0.25, (batch, sk, dim)), dtype)]
 
 
+def attention_residual_layernorm(batch, sq, sk, dim, dtype="f16", seed_offset=17):
+    r = _rng(seed_offset)
+    return [round_to(r.normal(0.0, 1.0, (batch, sq, dim)), dtype), round_to(r.normal(0.0, 1.0, (batch, dim, sk)), dtype),
+            round_to(r.normal(0.0, 1.0, (batch, sk, dim)), dtype), round_to(r.normal(0.0, 1.0, (batch, sq, dim)), dtype),
+            round_to(1.0 + r.normal(0.0, 0.02, (dim,)), "f32"), round_to(r.normal(0.0, 0.02, (dim,)), "f32")]
+
+
 def bias_gelu_residual_layernorm(rows=16384, cols=1024, dtype="bf16", seed_offset=4):
     r = _rng(seed_offset)
     x = r.normal(0.0, 1.0, (rows, cols))
