@@ -219,6 +219,15 @@ struct Planner {
     const Node& a = g[x.operand[0]];
     return a.shape[a.rank - 1] <= 8 || x.shape[x.rank - 1] == 1;     // arithmetic on a row's registers, no matrix unit
   }
+  // a dot that a stitched kernel can hold: arithmetic on registers, or fine-grained enough for one workgroup's
+  // matrix-unit tile (Section 5.1 composes batched GEMMs of that size with the ops around them); larger dots are
+  // library calls and part the graph
+  bool fine_dot(const Node& x) const {
+    if (small_dot(x)) return true;
+    if (x.kind != FS_DOT || x.rank != 3) return false;
+    const Node& a = g[x.operand[0]];
+    return a.rank == 3 && x.shape[1] <= 128 && x.shape[2] <= 128 && a.shape[2] <= 128;
+  }
   bool row_reduce(const Node& x) const { return is_reduce_kind(x.kind) && x.axis == g[x.operand[0]].rank - 1; }
 
   void add(std::vector<int> ops, int origin) {
@@ -335,7 +344,7 @@ struct Planner {
   std::set<std::vector<int>> explored;
   bool fusible(const Node& x) const {
     return is_binary(x.kind) || is_unary(x.kind) || x.kind == FS_CONVERT || x.kind == FS_CAUSAL_MASK ||
-           is_reduce_kind(x.kind) || small_dot(x);
+           is_reduce_kind(x.kind) || fine_dot(x);
   }
   void explore(const std::vector<int>& seed) {
     if (visited >= seed_limit || (int)seed.size() >= cfg.max_pattern_ops) return;
@@ -359,7 +368,7 @@ struct Planner {
 
   void generate() {
     // the multi-step heuristic: partition ops grow from large dots to every reduction
-    substitution([&](const Node& x) { return x.kind == FS_DOT && !small_dot(x); });
+    substitution([&](const Node& x) { return x.kind == FS_DOT && !fine_dot(x); });
     substitution([&](const Node& x) { return x.kind == FS_DOT; });
     substitution([&](const Node& x) { return x.kind == FS_DOT || (is_reduce_kind(x.kind) && !row_reduce(x)); });
     substitution([&](const Node& x) { return x.kind == FS_DOT || is_reduce_kind(x.kind); });

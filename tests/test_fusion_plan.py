@@ -176,6 +176,25 @@ def test_whole_groups_are_found_where_one_kernel_can_run_them():
     assert len(big["members"]) >= 20 and len(big["output_of"]) == 2       # the LayerNorm branch with both its outputs
 
 
+def test_fine_grained_dots_do_not_part_the_graph():
+    # a dot whose tile one workgroup's matrix-unit schedule holds (Section 5.1: batched GEMMs of fine granularity are
+    # composed with the ops around them) is fusible; a larger one is a library call and parts the graph
+    for ops, sched in ((graphs.causal_attention(512, 64, 64), "bdot_softmax"), (graphs.sigmoid_attention(512, 64, 64, 64, 64), "block_dot"),
+                       (graphs.attention_residual_layernorm(512, 64, 64, 64), "block_dot")):
+        fp = FusionPlan(ops)
+        owned = [i for i, op in enumerate(ops) if of.owns_kernel(op)]
+        whole = [p for p in fp.patterns if p["ops"] == owned]
+        assert len(whole) == 1 and whole[0]["score_us"] > 0 and whole[0]["origin"] == 0      # found by the first substitution step
+        with Plan(whole[0]["group_ops"]) as p:
+            assert p.info()["schedule"] == sched and p.info()["n_kernels"] == 1
+        # (the model may still prefer two groups: two small savings score a little higher than one large one)
+        assert len(fp.groups) <= 2 and all(len(g["members"]) > 1 for g in fp.groups)
+    fp = FusionPlan(graphs.attention_block(4, 64, 256, 64))          # 256 keys: beyond the fine-grained tile
+    dots = [i for i, op in enumerate(graphs.attention_block(4, 64, 256, 64)) if op.kind == "dot"]
+    for d in dots:
+        assert any(g["members"] == [d] for g in fp.groups)
+
+
 def test_cycle_repair_between_two_chains_that_feed_each_other():
     """Two chains that feed each other: each is a valid pattern, together they are cyclic.  The
     solver's first answer takes both; the repair forbids the pair and the second answer is the

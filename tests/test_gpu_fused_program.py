@@ -259,3 +259,27 @@ def test_stack_of_row_local_layers(n_layers):
     assert n_groups == (1 if n_layers == 3 else 2) and n_kernels == n_groups
     for a, b in zip(got, want):
         assert_close(a, b, TOLERANCE["f32"], f"stack of {n_layers} layers")
+
+
+@pytest.mark.parametrize("name", ["causal_attention", "attention_residual_layernorm", "sigmoid_attention"])
+def test_fine_grained_dots_are_fused_with_the_ops_around_them(name):
+    """Section 5.1 composes batched GEMMs of fine granularity with the memory-intensive ops around them: the planner
+    does not part the graph at such dots.  With the model's scores the whole graph is one group or two (the
+    bandwidth table makes two small savings look a little better than one large one); with measured scores
+    (Section 4.3's hybrid policy) it is one group and one kernel on the matrix unit."""
+    from workloads import BY_NAME
+    cfg = BY_NAME[name]
+    announce(f"fused program around fine-grained dots: {name}")
+    ops, ins = cfg.graph_fn(**cfg.full), cfg.input_fn(**cfg.full)
+    want = interp.run(ops, ins)
+    got, n_kernels, n_groups = _run(ops, ins)
+    assert n_groups <= 2 and n_kernels <= 2
+    for a, b in zip(got, want):
+        assert_close(a, b, TOLERANCE[cfg.dtype], name)
+    prog, report = FusedProgram.measured(ops)
+    with prog:
+        assert len(prog.fusion.groups) == 1 and prog.n_kernels == 1, [(len(r[0]), r[1], r[2]) for r in report]
+        outs = prog.run(to_device(ops, ins))
+        torch.cuda.synchronize()
+        for a, b in zip(outs, want):
+            assert_close(a.to(torch.float64).cpu().numpy(), b, TOLERANCE[cfg.dtype], name + " (measured plan)")
