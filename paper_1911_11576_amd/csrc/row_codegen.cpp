@@ -672,7 +672,7 @@ std::string op_text(int op, const std::string& a, const std::string& b, bool fas
     case FS_DIVIDE: return a + " / " + b;
     case FS_MAXIMUM: return "fmaxf(" + a + ", " + b + ")";
     case FS_NEGATE: return "-" + a;
-    case FS_EXP: return "expf(" + a + ")";
+    case FS_EXP: return (fast ? "exp_fast(" : "expf(") + a + ")";
     case FS_LOG: return "logf(" + a + ")";
     case FS_TANH: return (fast ? "tanh_fast(" : "tanh_f32(") + a + ")";
     case FS_RSQRT: return "rsqrtf(" + a + ")";
