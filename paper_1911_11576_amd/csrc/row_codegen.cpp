@@ -565,6 +565,19 @@ struct Analysis {
       const bool rounds = (r.op == EW_OP_ROUND_F16 && r.out_dtype == FS_F16) || (r.op == EW_OP_ROUND_BF16 && r.out_dtype == FS_BF16);
       if (rounds && r.out_ord >= 0 && !read[r.id]) r.op = EW_OP_COPY;
     }
+    // ... and one read by nothing but the consuming dot is left to the packing of the dot's operand
+    if (mma_out >= 0) {
+      std::vector<int> readers(n, 0), by_dot(n, 0);
+      for (const RNode& r : nodes)
+        for (int j = 0; j < r.nop; ++j) if (r.o[j].kind == OP_NODE || r.o[j].kind == OP_ROWB) {
+          ++readers[r.o[j].index];
+          if (r.op == ROP_DOT_MMA_OUT) ++by_dot[r.o[j].index];
+        }
+      for (RNode& r : nodes) {
+        const bool rounds = (r.op == EW_OP_ROUND_F16 && mma_dtype == FS_F16) || (r.op == EW_OP_ROUND_BF16 && mma_dtype == FS_BF16);
+        if (rounds && r.cls == CLS_FULL && r.out_ord < 0 && readers[r.id] > 0 && readers[r.id] == by_dot[r.id]) r.op = EW_OP_COPY;
+      }
+    }
     return true;
   }
 };
