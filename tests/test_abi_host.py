@@ -25,6 +25,25 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
+def test_a_caller_written_in_c(tmp_path):
+    """include/fs.h is plain C (c99, pedantic, no warnings) and the library is usable from it: tests/abi_from_c.c
+    describes a softmax group, plans it, reads the plan back and checks an error path."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    libdir = os.path.dirname(binding.lib()._name)
+    exe = str(tmp_path / "abi_from_c")
+    build = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"), "-o", exe,
+                            os.path.join(ROOT, "tests", "abi_from_c.c"), "-L", libdir, "-lfusionstitch", "-Wl,-rpath," + libdir],
+                           capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "schedule=1 kernels=1" in run.stdout and "refused:" in run.stdout
+
+
 def test_struct_layout_matches_the_header():
     # int32 x4, int64 x4, int32 x3, int32, double
     assert ctypes.sizeof(binding.fs_op_desc) == 16 + 32 + 12 + 4 + 8
