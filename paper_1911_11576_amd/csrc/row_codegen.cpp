@@ -1164,7 +1164,10 @@ struct Gen {
     e.s += kReducePreamble;
     if (mma) e.s += kMmaPreamble;
     const int T = L > 64 ? L / 64 : 1;      // wavefronts per row
-    e.line("extern \"C\" __global__ __launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", mma ? wg : L > 256 ? L : wg > 256 ? wg : 256);
+    // (matrix-unit kernels: two wavefronts per SIMD asked for, so that the register budget is the 256 ordinary
+    // registers and the compiler keeps the accumulators there instead of copying through the accumulation file)
+    e.line("extern \"C\" __global__ %s__launch_bounds__(%d) void FS_ROW_NAME(const Args a) {", mma ? "__attribute__((amdgpu_waves_per_eu(2))) " : "",
+           mma ? wg : L > 256 ? L : wg > 256 ? wg : 256);
     e.line("  constexpr int L = %d, K = %d, W = %d;", L, K, W);
     if (mma) {
       e.line("  constexpr int M = %lld, N = %lld;             // the tile of one batch element", (long long)A.S[1], (long long)A.S[2]);
